@@ -1,0 +1,340 @@
+/*
+ * CPU oracle for the micrograph hot path of HopGNN (arxiv 2409.00657).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, single-threaded
+ * definition that the GPU library is checked against.  It shares no code,
+ * header, table or helper with the HIP sources; nothing in the product path
+ * may call it.  Everything here runs on host arrays.
+ *
+ * The paper defines the steps only at the level of "sample a k-hop
+ * computation graph per root vertex (a micrograph), merge the vertex sets of
+ * the micrographs a worker will train and drop duplicates (pre-gathering),
+ * collect the feature vector of every vertex, then aggregate neighbour
+ * features and apply a neural transform per layer" (paper sections 2, 4 and
+ * 5.2).  It names no hash, no ordering and no layer formula; the concrete
+ * readings taken here are:
+ *
+ *   - sampling is with replacement, child = row[hash64(key,root,v,h,j) mod deg]
+ *     where the hash is a three-round chain of the SplitMix64 output finaliser;
+ *   - a micrograph is a fixed-shape tree of slots stored level-major;
+ *   - the pre-gather set is the ascending, duplicate-free list of valid IDs;
+ *   - the layer is GraphSAGE-mean:  act(x_self W_self + mean(nbrs) W_neigh + b).
+ *
+ * All floating point is done in double; the caller decides how a result is
+ * rounded for storage (orc_round_store does one round-to-nearest-even step).
+ *
+ * Pin status: every function below is pinned by tests that do not call back
+ * into it (published SplitMix64 outputs, closed-form graphs, brute-force
+ * enumeration, algebraic special cases, the paper's worked pre-gather example).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2, ORC_F64 = 3 };
+
+/* ------------------------------------------------------------------ hash -- */
+
+/* SplitMix64 output finaliser (Steele, Lea, Flood, OOPSLA 2014). */
+uint64_t orc_mix(uint64_t z)
+{
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+#define ORC_GOLDEN 0x9E3779B97F4A7C15ULL
+
+/* hash64(key, root, v, h, j): absorb the key, then (root,v), then (h,j);
+ * each absorption is "xor the word in, add the golden-ratio increment, mix". */
+uint64_t orc_hash64(uint64_t key, uint32_t root, uint32_t v, uint32_t h, uint32_t j)
+{
+    uint64_t w0 = ((uint64_t)root << 32) | (uint64_t)v;
+    uint64_t w1 = ((uint64_t)h << 32) | (uint64_t)j;
+    uint64_t x = orc_mix(key + ORC_GOLDEN);
+    x = orc_mix((x ^ w0) + ORC_GOLDEN);
+    x = orc_mix((x ^ w1) + ORC_GOLDEN);
+    return x;
+}
+
+/* -------------------------------------------------------------- sampling -- */
+
+/* T_seed = sum_{h=0..L} P_h with P_0 = 1, P_h = f_1 ... f_h.  -1 on bad input. */
+int64_t orc_slots_per_seed(const int32_t *fanouts, int32_t n_layers)
+{
+    if (!fanouts || n_layers < 1) return -1;
+    int64_t p = 1, t = 1;
+    for (int32_t h = 0; h < n_layers; ++h) {
+        if (fanouts[h] < 1) return -1;
+        p *= fanouts[h];
+        t += p;
+    }
+    return t;
+}
+
+static int64_t off_at(const void *offsets, int off64, int64_t v)
+{
+    return off64 ? ((const int64_t *)offsets)[v] : (int64_t)((const int32_t *)offsets)[v];
+}
+
+/*
+ * Micrograph sampling (paper section 2 "sampling", section 4 "micrograph
+ * definition": one k-hop computation graph per root vertex of the batch).
+ *
+ * ids is level-major.  Level h (0..L) holds B*P_h slots starting at
+ * S_{h-1} = B * sum_{i<h} P_i; inside a level the slot of micrograph m and
+ * path p is m*P_h + p.  The children of the slot with level-local index q
+ * at level h-1 are the f_h slots q*f_h .. q*f_h+f_h-1 of level h.
+ * A slot holding v<0 or a vertex of degree 0 has only invalid (-1) children.
+ *
+ * indptr (optional) has one entry per non-leaf slot plus one: the position,
+ * counted from the first level-1 slot, where that slot's children start.
+ */
+int orc_sample(const void *offsets, int offsets_i64, const int32_t *indices,
+               int64_t n_vertices, const int32_t *seeds, int32_t n_seeds,
+               const int32_t *fanouts, int32_t n_layers, uint64_t key,
+               int32_t *ids, int32_t *indptr)
+{
+    if (orc_slots_per_seed(fanouts, n_layers) < 0 || n_seeds < 0) return 1;
+    const int64_t B = n_seeds;
+    for (int64_t m = 0; m < B; ++m) {
+        if (seeds[m] < 0 || seeds[m] >= n_vertices) return 3;
+        ids[m] = seeds[m];
+    }
+    int64_t prev_base = 0;      /* S_{h-2}: first slot of level h-1 */
+    int64_t prev_P = 1;         /* P_{h-1} */
+    int64_t cur_base = B;       /* S_{h-1}: first slot of level h   */
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        const int64_t f = fanouts[h - 1];
+        for (int64_t q = 0; q < B * prev_P; ++q) {
+            const int64_t m = q / prev_P;
+            const int32_t v = ids[prev_base + q];
+            const int64_t child0 = cur_base + q * f;
+            if (indptr) indptr[prev_base + q] = (int32_t)(child0 - B);
+            int64_t o0 = 0, deg = 0;
+            if (v >= 0) {
+                o0 = off_at(offsets, offsets_i64, v);
+                deg = off_at(offsets, offsets_i64, (int64_t)v + 1) - o0;
+            }
+            for (int64_t j = 0; j < f; ++j) {
+                if (v < 0 || deg <= 0) {
+                    ids[child0 + j] = -1;
+                } else {
+                    uint64_t x = orc_hash64(key, (uint32_t)seeds[m], (uint32_t)v,
+                                            (uint32_t)h, (uint32_t)j);
+                    ids[child0 + j] = indices[o0 + (int64_t)(x % (uint64_t)deg)];
+                }
+            }
+        }
+        prev_base = cur_base;
+        cur_base += B * prev_P * f;
+        prev_P *= f;
+    }
+    /* prev_base is now S_{L-1} (first leaf slot), cur_base is T */
+    if (indptr) indptr[prev_base] = (int32_t)(cur_base - B);
+    return 0;
+}
+
+/* ------------------------------------------------------------ pre-gather -- */
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Pre-gathering (paper section 5.2: fetch the features needed by all the
+ * micrographs of one iteration in a single batch, each vertex once; the
+ * implementation section says duplicates are detected and removed from the
+ * stored list of micrographs).
+ *
+ * uniq  = ascending duplicate-free list of the non-negative entries of ids
+ * remap = for every slot the position of its id in uniq, -1 for invalid slots
+ * returns U = |uniq|, or -1 on allocation failure.
+ */
+int64_t orc_pregather(const int32_t *ids, int64_t n_ids, int32_t *uniq, int32_t *remap)
+{
+    int32_t *tmp = (int32_t *)malloc((size_t)(n_ids > 0 ? n_ids : 1) * sizeof(int32_t));
+    if (!tmp) return -1;
+    int64_t n = 0;
+    for (int64_t i = 0; i < n_ids; ++i)
+        if (ids[i] >= 0) tmp[n++] = ids[i];
+    qsort(tmp, (size_t)n, sizeof(int32_t), cmp_i32);
+    int64_t U = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if (i == 0 || tmp[i] != tmp[i - 1]) uniq[U++] = tmp[i];
+    free(tmp);
+    for (int64_t i = 0; i < n_ids; ++i) {
+        if (ids[i] < 0) { remap[i] = -1; continue; }
+        int64_t lo = 0, hi = U - 1;
+        while (lo < hi) {
+            int64_t mid = lo + (hi - lo) / 2;
+            if (uniq[mid] < ids[i]) lo = mid + 1; else hi = mid;
+        }
+        remap[i] = (int32_t)lo;
+    }
+    return U;
+}
+
+/* ---------------------------------------------------------------- gather -- */
+
+/* Gathering (paper section 2): Xu[i,:] = X[uniq[i],:], a copy of row bytes.
+ * ld_bytes is the distance between rows of X; Xu is packed. */
+int orc_gather(const void *X, int64_t n_rows, int64_t row_bytes, int64_t ld_bytes,
+               const int32_t *uniq, int64_t n_uniq, void *Xu)
+{
+    for (int64_t i = 0; i < n_uniq; ++i) {
+        if (uniq[i] < 0 || uniq[i] >= n_rows) return 3;
+        memcpy((char *)Xu + i * row_bytes, (const char *)X + (int64_t)uniq[i] * ld_bytes,
+               (size_t)row_bytes);
+    }
+    return 0;
+}
+
+/* -------------------------------------------------- storage conversions -- */
+
+static double half_to_double(uint16_t hbits)
+{
+    int sign = hbits >> 15, e = (hbits >> 10) & 31, m = hbits & 1023;
+    double v;
+    if (e == 0) v = ldexp((double)m, -24);
+    else if (e == 31) v = m ? NAN : INFINITY;
+    else v = ldexp((double)(m + 1024), e - 25);
+    return sign ? -v : v;
+}
+
+static double bf16_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static double load_elem(const void *p, int dtype, int64_t i)
+{
+    switch (dtype) {
+    case ORC_F32: return (double)((const float *)p)[i];
+    case ORC_BF16: return bf16_to_double(((const uint16_t *)p)[i]);
+    case ORC_F16: return half_to_double(((const uint16_t *)p)[i]);
+    default: return ((const double *)p)[i];
+    }
+}
+
+/* One round-to-nearest-even step from double to a binary format with
+ * `sig` significand bits (hidden bit included), smallest quantum 2^qmin and
+ * largest finite value maxv; the result is returned as a double that is
+ * exactly representable in the target format (or +-inf on overflow). */
+static double round_to_format(double x, int sig, int qmin, double maxv)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(x, &e);              /* |x| = m * 2^e, m in [0.5, 1) */
+    int q = e - sig;                 /* quantum of a normal number    */
+    if (q < qmin) q = qmin;
+    double r = ldexp(rint(ldexp(x, -q)), q);   /* rint: ties to even */
+    if (fabs(r) > maxv) r = x > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/* Round n doubles once to `dtype` and store them (fp32 / bf16 / fp16 / fp64). */
+void orc_round_store(const double *src, int64_t n, int dtype, void *dst)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double x = src[i];
+        if (dtype == ORC_F64) {
+            ((double *)dst)[i] = x;
+        } else if (dtype == ORC_F32) {
+            ((float *)dst)[i] = (float)x;      /* IEEE default rounding: nearest even */
+        } else if (dtype == ORC_BF16) {
+            /* 8 significand bits, float exponent range: min quantum 2^-133 */
+            double r = round_to_format(x, 8, -133, ldexp(255.0, 120));
+            float f = (float)r;                /* exact */
+            uint32_t u;
+            memcpy(&u, &f, 4);
+            ((uint16_t *)dst)[i] = (uint16_t)(u >> 16);
+        } else {
+            /* fp16: 11 significand bits, min quantum 2^-24, max 65504 */
+            double r = round_to_format(x, 11, -24, 65504.0);
+            uint16_t s = (uint16_t)(signbit(r) ? 0x8000 : 0), out;
+            double a = fabs(r);
+            if (isnan(r)) out = 0x7E00;
+            else if (isinf(r)) out = (uint16_t)(s | 0x7C00);
+            else if (a == 0.0) out = s;
+            else if (a < ldexp(1.0, -14)) out = (uint16_t)(s | (uint16_t)ldexp(a, 24));
+            else {
+                int e;
+                double m = frexp(a, &e);       /* a = m 2^e, m in [0.5,1) */
+                out = (uint16_t)(s | ((e + 14) << 10) | ((uint16_t)ldexp(m, 11) - 1024));
+            }
+            ((uint16_t *)dst)[i] = out;
+        }
+    }
+}
+
+/* Convert n stored elements of `dtype` to double (exact). */
+void orc_load_f64(const void *src, int64_t n, int dtype, double *dst)
+{
+    for (int64_t i = 0; i < n; ++i) dst[i] = load_elem(src, dtype, i);
+}
+
+/* -------------------------------------------------------- GraphSAGE-mean -- */
+
+/*
+ * One layer: for destination row r
+ *   c   = number of e in [indptr[r], indptr[r+1]) with idx[e] >= 0
+ *   m   = (sum of Hsrc[idx[e], :] over those e, in order) / c, or 0 if c == 0
+ *   out = x_self W_self + m W_neigh + b,  x_self = Hsrc[self_idx[r]] (identity
+ *         if self_idx is NULL; a negative self index gives a zero row)
+ *   out = max(out, 0) if relu
+ * (paper section 2 "computation": aggregate the neighbouring features, then a
+ * neural-network transform; mean aggregator of GraphSAGE).
+ *
+ * Hsrc and the weights are stored in `dtype`; everything is converted to
+ * double first; out is double [n_dst x d_out], unrounded.
+ */
+int orc_sage_fwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in,
+                 const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                 int64_t n_dst, const void *W_self, const void *W_neigh,
+                 const void *bias, int32_t d_out, int32_t relu, double *out)
+{
+    double *xs = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *mn = (double *)malloc(sizeof(double) * (size_t)d_in);
+    if (!xs || !mn) { free(xs); free(mn); return 2; }
+    int rc = 0;
+    for (int64_t r = 0; r < n_dst && !rc; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        if (s >= n_src) { rc = 3; break; }
+        for (int32_t k = 0; k < d_in; ++k)
+            xs[k] = s < 0 ? 0.0 : load_elem(Hsrc, dtype, s * d_in + k);
+        for (int32_t k = 0; k < d_in; ++k) mn[k] = 0.0;
+        int64_t c = 0;
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            int64_t u = idx[e];
+            if (u < 0) continue;
+            if (u >= n_src) { rc = 3; break; }
+            for (int32_t k = 0; k < d_in; ++k) mn[k] += load_elem(Hsrc, dtype, u * d_in + k);
+            ++c;
+        }
+        if (rc) break;
+        if (c > 0)
+            for (int32_t k = 0; k < d_in; ++k) mn[k] /= (double)c;
+        for (int32_t n = 0; n < d_out; ++n) {
+            double acc = bias ? load_elem(bias, dtype, n) : 0.0;
+            for (int32_t k = 0; k < d_in; ++k)
+                acc += xs[k] * load_elem(W_self, dtype, (int64_t)k * d_out + n);
+            for (int32_t k = 0; k < d_in; ++k)
+                acc += mn[k] * load_elem(W_neigh, dtype, (int64_t)k * d_out + n);
+            if (relu && acc < 0.0) acc = 0.0;
+            out[r * d_out + n] = acc;
+        }
+    }
+    free(xs);
+    free(mn);
+    return rc;
+}

@@ -1,0 +1,10 @@
+"""MI355X-native micrograph hot path of HopGNN (arxiv 2409.00657).
+
+``binding`` is the thin ctypes layer over the C-ABI library built from
+``csrc/`` (hand-written HIP for gfx950); ``synth`` produces seeded inputs.
+"""
+from . import synth  # noqa: F401
+from .binding import (  # noqa: F401
+    DTYPE_OF, hopgnn_gather, hopgnn_pregather, hopgnn_pregather_ws_bytes, hopgnn_sage_fwd,
+    hopgnn_sage_fwd_ws_bytes, hopgnn_sample, hopgnn_slots_per_seed, library_path, load_library,
+)
