@@ -1,0 +1,173 @@
+/*
+ * hopgnn.h - C ABI of the MI355X (gfx950) micrograph hot path of HopGNN
+ * (arxiv 2409.00657): one worker's share of a micrograph-based training step
+ * on one GPU.
+ *
+ *   hopgnn_sample     k-hop neighbour sampling, one micrograph per root vertex
+ *   hopgnn_pregather  merged, duplicate-free vertex-ID set of a batch (or a
+ *                     group of batches) of micrographs + slot -> position table
+ *   hopgnn_gather     copy of the feature rows of that set into a dense buffer
+ *   hopgnn_sage_fwd   one GraphSAGE-mean layer: CSR segmented mean of neighbour
+ *                     rows, then the W_self / W_neigh projection
+ *
+ * Conventions for every call
+ *   - Pointers marked DEVICE are HIP device pointers owned by the caller; the
+ *     library never allocates, frees or keeps them.  Pointers marked HOST are
+ *     ordinary host memory read during the call.
+ *   - `stream` is a hipStream_t passed as void*; all device work is enqueued on
+ *     it and no call synchronises.  The library holds no global state.
+ *   - Argument errors that the host can see are reported before any launch.
+ *     Vertex IDs inside device arrays are the caller's contract: they must lie
+ *     in [0, n_vertices) (or be negative = "invalid slot" where allowed).
+ *   - Results are pure functions of the inputs and bit-stable from run to run
+ *     (no result depends on the order in which atomics land).
+ */
+#ifndef HOPGNN_H
+#define HOPGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HOPGNN_OK = 0,
+    HOPGNN_EINVAL = 1,    /* NULL / negative / inconsistent argument            */
+    HOPGNN_ENOMEM_WS = 2, /* workspace smaller than the *_ws_bytes query         */
+    HOPGNN_ERANGE = 3,    /* a size exceeds what the 32-bit slot arrays can hold */
+    HOPGNN_EHIP = 4       /* a HIP launch failed                                 */
+} hopgnn_status;
+
+typedef enum { HOPGNN_F32 = 0, HOPGNN_BF16 = 1, HOPGNN_F16 = 2 } hopgnn_dtype;
+
+/* How hopgnn_pregather builds the set. Both give identical results. */
+typedef enum {
+    HOPGNN_PG_AUTO = 0,   /* pick by n_ids and n_vertices                               */
+    HOPGNN_PG_BITMAP = 1, /* presence bitmap over the vertex range + popcount ranks     */
+    HOPGNN_PG_RADIX = 2   /* LSD radix sort of (id, slot) pairs, head flags, scan       */
+} hopgnn_pg_algo;
+
+/* Read-only graph topology in CSR form (replicated per worker in the paper,
+ * section 2, because it is small next to the features). Row v lists the
+ * vertices that v samples from and aggregates over. */
+typedef struct {
+    int64_t n_vertices;
+    int64_t n_edges;
+    const void *offsets;    /* DEVICE [n_vertices+1], int32 or int64 (see offsets_i64) */
+    int32_t offsets_i64;    /* 0: int32 offsets, 1: int64 offsets                      */
+    const int32_t *indices; /* DEVICE [n_edges]                                        */
+} hopgnn_csr;
+
+const char *hopgnn_status_str(hopgnn_status s);
+
+/*
+ * Slots per micrograph, T_seed = sum_{h=0..L} P_h, P_0 = 1, P_h = f_1*...*f_h
+ * (fanouts[0] applies at the root).  Returns -1 if n_layers < 1 or n_layers > 8
+ * or any fanout < 1.  HOST only.
+ */
+int64_t hopgnn_slots_per_seed(const int32_t *fanouts /*HOST*/, int32_t n_layers);
+
+/*
+ * Sampling (paper section 2 "sampling"; section 4 "micrograph definition": a
+ * k-hop computation graph per root vertex of the mini-batch).
+ *
+ * For each of the n_seeds roots a fixed-shape tree of slots is filled, with
+ * replacement:  child j (0-based) at hop h (1-based) of a slot holding vertex v
+ * in the micrograph of root r is
+ *     indices[offsets[v] + hash64(key, r, v, h, j) mod deg(v)]
+ * (exact unsigned 64-bit remainder), or -1 if v < 0 or deg(v) = 0.  hash64 is a
+ * three-step chain of the SplitMix64 finaliser absorbing key, (r,v), (h,j).
+ *
+ * ids    DEVICE out [n_seeds*T_seed] level-major: level h holds n_seeds*P_h
+ *        slots starting at n_seeds*sum_{i<h} P_i; in a level the slot of seed m,
+ *        path p is m*P_h + p; children of level-local slot q are q*f_h .. +f_h-1.
+ * indptr DEVICE out [S+1], S = number of non-leaf slots, or NULL: children of
+ *        slot r are ids[n_seeds + indptr[r] .. n_seeds + indptr[r+1]).
+ * slot_idx DEVICE out [S - n_seeds] or NULL: for e below S - n_seeds (the
+ *        children that are themselves non-leaf slots), n_seeds + e if
+ *        ids[n_seeds + e] >= 0, else -1.  (indptr, slot_idx) is the CSR of the
+ *        computation graph in slot numbering: the neighbour list a layer after
+ *        the first aggregates over, whose input row of a slot is the slot number.
+ * seeds  DEVICE [n_seeds], each in [0, n_vertices).
+ * Errors: EINVAL (NULL, n_seeds < 0, bad fanouts), ERANGE (n_seeds*T_seed >= 2^31).
+ * n_seeds == 0 is a no-op returning OK.
+ */
+hopgnn_status hopgnn_sample(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds,
+                            int32_t n_seeds, const int32_t *fanouts /*HOST*/, int32_t n_layers,
+                            uint64_t key, int32_t *ids, int32_t *indptr, int32_t *slot_idx,
+                            void *stream);
+
+/*
+ * Pre-gathering (paper section 5.2: merge the fetches of all micrographs a
+ * worker trains in one iteration into one, each vertex once; implementation
+ * section: duplicates are removed from the stored list of micrographs).
+ *
+ * ids        DEVICE [n_ids]; concatenation of one or more batches' slot arrays;
+ *            negative entries are invalid slots and are skipped.
+ * uniq       DEVICE out, capacity min(n_ids, n_vertices): valid IDs, strictly ascending.
+ * n_uniq_dev DEVICE out, one int64: U = number of entries written to uniq.
+ * remap      DEVICE out [n_ids]: position of ids[i] in uniq, -1 for invalid slots.
+ * ws         DEVICE scratch of at least hopgnn_pregather_ws_bytes(...) bytes,
+ *            256-byte aligned; contents on entry are irrelevant.
+ * Errors: EINVAL, ENOMEM_WS, ERANGE (n_ids >= 2^31 or n_vertices > 2^31).
+ */
+size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo);
+
+hopgnn_status hopgnn_pregather(const int32_t *ids, int64_t n_ids, int64_t n_vertices,
+                               int32_t algo, int32_t *uniq, int64_t *n_uniq_dev, int32_t *remap,
+                               void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Gathering (paper section 2 "gathering": collect the feature vector of every
+ * vertex of the sampled structure; section 3.1 names it the bottleneck).
+ *
+ *     Xu[i, :] = X[uniq[i], :]   for i < U, byte for byte.
+ *
+ * X          DEVICE [n_rows x dim] row-major, rows ld_elems elements apart.
+ * uniq       DEVICE [U] row numbers in [0, n_rows).
+ * n_uniq     if n_uniq_dev is NULL: U itself.  Otherwise the capacity of uniq/Xu
+ *            (an upper bound of U used to size the launch) and U is read on the
+ *            device from *n_uniq_dev, so no host synchronisation is needed.
+ * Xu         DEVICE out [U x dim], packed.
+ * Rows move as 128-bit words when base addresses, dim*size and ld*size are all
+ * multiples of 16 bytes, else as 32-bit words, else as bytes.
+ */
+hopgnn_status hopgnn_gather(const void *X, hopgnn_dtype dt, int64_t n_rows, int32_t dim,
+                            int64_t ld_elems, const int32_t *uniq, int64_t n_uniq,
+                            const int64_t *n_uniq_dev, void *Xu, void *stream);
+
+/*
+ * GraphSAGE-mean layer forward (paper section 2 "computation": per layer an
+ * aggregation over each vertex's neighbours, then a neural-network transform;
+ * the aggregator is the mean of Hamilton et al.'s GraphSAGE):
+ *
+ *   c_r    = #{ e in [indptr[r], indptr[r+1]) : idx[e] >= 0 }
+ *   m_r    = (1/c_r) * sum over those e of Hsrc[idx[e], :]      (0 if c_r = 0)
+ *   out[r] = act( x_r W_self + m_r W_neigh + bias ),  x_r = Hsrc[self_idx[r], :]
+ *
+ * Hsrc     DEVICE [n_src x d_in], packed rows, dtype dt.
+ * self_idx DEVICE [n_dst] or NULL (= identity: x_r = Hsrc[r]); a negative entry
+ *          gives a zero self row.
+ * indptr   DEVICE [n_dst+1], idx DEVICE [indptr[n_dst]]; negative idx = skip.
+ * W_self, W_neigh DEVICE [d_in x d_out] row-major, dtype dt; bias DEVICE [d_out] or NULL.
+ * relu     0: identity activation, else max(., 0).
+ * out      DEVICE [n_dst x d_out], dtype dt (sums are fp32, rounded once on store;
+ *          for 2-byte types the mean is rounded to dt before the projection).
+ * ws       DEVICE scratch of at least hopgnn_sage_fwd_ws_bytes(...) bytes, 256-byte aligned.
+ * The sum over a segment runs in entry order, so results are run-to-run stable.
+ * Errors: EINVAL, ENOMEM_WS, ERANGE (n_dst or n_src >= 2^31).
+ */
+size_t hopgnn_sage_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out);
+
+hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                              const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                              int64_t n_dst, const void *W_self, const void *W_neigh,
+                              const void *bias, int32_t d_out, int32_t relu, void *out, void *ws,
+                              size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HOPGNN_H */

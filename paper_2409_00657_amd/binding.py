@@ -1,0 +1,160 @@
+"""Thin ctypes binding over libhopgnn.so: argument marshalling only.
+
+Every function has the name and meaning of the C entry point in
+``include/hopgnn.h``; tensors are torch CUDA(HIP) tensors whose storage the
+caller owns, and work is enqueued on torch's current stream.  There is no CPU
+path: if the library has not been built the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "libhopgnn.so")
+_lib: Optional[ctypes.CDLL] = None
+
+F32, BF16, F16 = 0, 1, 2
+DTYPE_OF = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
+PG_AUTO, PG_BITMAP, PG_RADIX = 0, 1, 2
+
+EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
+           "hopgnn_pregather_ws_bytes", "hopgnn_pregather", "hopgnn_gather",
+           "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd"]
+
+
+class HopgnnError(RuntimeError):
+    pass
+
+
+class _Csr(ctypes.Structure):
+    _fields_ = [("n_vertices", ctypes.c_int64), ("n_edges", ctypes.c_int64),
+                ("offsets", ctypes.c_void_p), ("offsets_i64", ctypes.c_int32),
+                ("indices", ctypes.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; never falls back to anything else."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise HopgnnError("libhopgnn.so is not built: run `python -m paper_2409_00657_amd.build` "
+                          "(there is no CPU fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    L.hopgnn_status_str.restype = c.c_char_p
+    L.hopgnn_status_str.argtypes = [c.c_int]
+    L.hopgnn_slots_per_seed.restype = c.c_int64
+    L.hopgnn_slots_per_seed.argtypes = [c.POINTER(c.c_int32), c.c_int32]
+    L.hopgnn_sample.restype = c.c_int
+    L.hopgnn_sample.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.POINTER(c.c_int32),
+                                c.c_int32, c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p,
+                                c.c_void_p]
+    L.hopgnn_pregather_ws_bytes.restype = c.c_size_t
+    L.hopgnn_pregather_ws_bytes.argtypes = [c.c_int64, c.c_int64, c.c_int32]
+    L.hopgnn_pregather.restype = c.c_int
+    L.hopgnn_pregather.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int32, c.c_void_p,
+                                   c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_gather.restype = c.c_int
+    L.hopgnn_gather.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64, c.c_void_p,
+                                c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p]
+    L.hopgnn_sage_fwd_ws_bytes.restype = c.c_size_t
+    L.hopgnn_sage_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32]
+    L.hopgnn_sage_fwd.restype = c.c_int
+    L.hopgnn_sage_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p,
+                                  c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
+                                  c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
+                                  c.c_size_t, c.c_void_p]
+    _lib = L
+    return L
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        msg = load_library().hopgnn_status_str(rc).decode()
+        raise HopgnnError("%s: %s (status %d)" % (what, msg, rc))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise HopgnnError("expected a device tensor")
+    if not t.is_contiguous():
+        raise HopgnnError("expected a contiguous tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _fan(fanouts: Sequence[int]):
+    return (ctypes.c_int32 * len(fanouts))(*[int(f) for f in fanouts])
+
+
+def hopgnn_slots_per_seed(fanouts: Sequence[int]) -> int:
+    return int(load_library().hopgnn_slots_per_seed(_fan(fanouts), len(fanouts)))
+
+
+def hopgnn_sample(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor,
+                  fanouts: Sequence[int], key: int, ids: torch.Tensor,
+                  indptr: Optional[torch.Tensor] = None,
+                  slot_idx: Optional[torch.Tensor] = None) -> None:
+    g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
+             1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+    if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
+        raise HopgnnError("offsets must be int32/int64 and indices int32")
+    _ptr(offsets), _ptr(indices)
+    rc = load_library().hopgnn_sample(ctypes.byref(g), _ptr(seeds), seeds.numel(), _fan(fanouts),
+                                      len(fanouts), ctypes.c_uint64(key & 0xFFFFFFFFFFFFFFFF),
+                                      _ptr(ids), _ptr(indptr), _ptr(slot_idx), _stream())
+    _check(rc, "hopgnn_sample")
+
+
+def hopgnn_pregather_ws_bytes(n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> int:
+    return int(load_library().hopgnn_pregather_ws_bytes(n_ids, n_vertices, algo))
+
+
+def hopgnn_pregather(ids: torch.Tensor, n_vertices: int, uniq: torch.Tensor,
+                     n_uniq_dev: torch.Tensor, remap: torch.Tensor, ws: torch.Tensor,
+                     algo: int = PG_AUTO) -> None:
+    rc = load_library().hopgnn_pregather(_ptr(ids), ids.numel(), n_vertices, algo, _ptr(uniq),
+                                         _ptr(n_uniq_dev), _ptr(remap), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_pregather")
+
+
+def hopgnn_gather(X: torch.Tensor, uniq: torch.Tensor, n_uniq: int,
+                  n_uniq_dev: Optional[torch.Tensor], Xu: torch.Tensor) -> None:
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise HopgnnError("X must be 2-D with unit column stride")
+    rc = load_library().hopgnn_gather(ctypes.c_void_p(X.data_ptr()), DTYPE_OF[X.dtype], X.shape[0],
+                                      X.shape[1], X.stride(0), _ptr(uniq), n_uniq,
+                                      _ptr(n_uniq_dev), _ptr(Xu), _stream())
+    _check(rc, "hopgnn_gather")
+
+
+def hopgnn_sage_fwd_ws_bytes(dtype: torch.dtype, n_dst: int, d_in: int, d_out: int) -> int:
+    return int(load_library().hopgnn_sage_fwd_ws_bytes(DTYPE_OF[dtype], n_dst, d_in, d_out))
+
+
+def hopgnn_sage_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor],
+                    indptr: torch.Tensor, idx: torch.Tensor, n_dst: int, W_self: torch.Tensor,
+                    W_neigh: torch.Tensor, bias: Optional[torch.Tensor], relu: bool,
+                    out: torch.Tensor, ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_fwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in,
+                                        _ptr(self_idx), _ptr(indptr), _ptr(idx), n_dst,
+                                        _ptr(W_self), _ptr(W_neigh), _ptr(bias), d_out,
+                                        1 if relu else 0, _ptr(out), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_sage_fwd")

@@ -1,0 +1,149 @@
+// hopgnn_sample: counter-hash k-hop sampling, one micrograph per root vertex
+// (paper section 2 "sampling", section 4 "micrograph definition").
+//
+// One workgroup owns one micrograph and walks its levels in order; a level is
+// written to HBM (coalesced inside the micrograph's slice of the level-major
+// array) and read back by the same workgroup after a barrier, so all hops of
+// all micrographs run in a single launch.  Work per slot is two dependent
+// random reads (row bounds, then one neighbour) - latency bound, hidden by
+// keeping every micrograph's workgroup resident at once.
+#include "common.hpp"
+
+namespace hopgnn {
+
+struct SampleShape {
+    int32_t n_layers;
+    int32_t f[kMaxLayers + 1];      // f[h], h = 1..L
+    int32_t P[kMaxLayers + 1];      // P[h] = slots per micrograph at level h
+    int32_t base[kMaxLayers + 2];   // base[h] = first slot of level h; base[L+1] = T
+};
+
+__device__ __forceinline__ uint64_t finalise64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Exact unsigned 64-bit remainder (a multiply-high range reduction would pick
+// different neighbours and is not an acceptable substitute).
+__device__ __forceinline__ uint64_t mod_u64(uint64_t x, uint64_t d) {
+    return x % d;
+}
+
+template <typename OffT>
+__global__ void __launch_bounds__(256)
+sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
+                   const int32_t* __restrict__ seeds, int32_t n_seeds, SampleShape sh,
+                   uint64_t keyed, int32_t* ids, int32_t* indptr, int32_t* slot_idx) {
+    const int32_t m = blockIdx.x;
+    const int32_t root = seeds[m];
+    const int32_t B = n_seeds;
+    if (threadIdx.x == 0) {
+        ids[m] = root;
+        if (indptr != nullptr && m == 0) indptr[sh.base[sh.n_layers]] = sh.base[sh.n_layers + 1] - B;
+    }
+    for (int32_t h = 1; h <= sh.n_layers; ++h) {
+        const uint32_t f = sh.f[h];
+        const int32_t P = sh.P[h];
+        const int32_t* parents = ids + sh.base[h - 1] + (int64_t)m * sh.P[h - 1];
+        int32_t* children = ids + sh.base[h] + (int64_t)m * P;
+        for (uint32_t c = threadIdx.x; c < (uint32_t)P; c += blockDim.x) {
+            const uint32_t q = c / f;
+            const uint32_t j = c - q * f;
+            const int32_t v = (h == 1) ? root : parents[q];
+            int32_t child = -1;
+            if (v >= 0) {
+                const int64_t o0 = (int64_t)offsets[v];
+                const int64_t deg = (int64_t)offsets[(int64_t)v + 1] - o0;
+                if (deg > 0) {
+                    uint64_t x = finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v)) +
+                                            0x9E3779B97F4A7C15ull);
+                    x = finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
+                    child = indices[o0 + (int64_t)mod_u64(x, (uint64_t)deg)];
+                }
+            }
+            children[c] = child;
+            if (slot_idx != nullptr && h < sh.n_layers) {   // non-leaf child: its own row in later layers
+                const int32_t slot = sh.base[h] + m * P + (int32_t)c;
+                slot_idx[slot - B] = child >= 0 ? slot : -1;
+            }
+            if (indptr != nullptr && j == 0)
+                indptr[sh.base[h - 1] + m * sh.P[h - 1] + (int32_t)q] =
+                    sh.base[h] + (m * sh.P[h - 1] + (int32_t)q) * (int32_t)f - B;
+        }
+        __syncthreads();   // this level is visible to the whole workgroup before the next hop
+    }
+}
+
+static uint64_t host_finalise64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace hopgnn
+
+using namespace hopgnn;
+
+extern "C" int64_t hopgnn_slots_per_seed(const int32_t* fanouts, int32_t n_layers) {
+    if (fanouts == nullptr || n_layers < 1 || n_layers > kMaxLayers) return -1;
+    int64_t p = 1, t = 1;
+    for (int32_t h = 0; h < n_layers; ++h) {
+        if (fanouts[h] < 1) return -1;
+        p *= fanouts[h];
+        if (p > (int64_t)1 << 31) return -1;
+        t += p;
+    }
+    return t;
+}
+
+extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                       const int32_t* fanouts, int32_t n_layers, uint64_t key,
+                                       int32_t* ids, int32_t* indptr, int32_t* slot_idx,
+                                       void* stream) {
+    if (g == nullptr || fanouts == nullptr || n_seeds < 0) return HOPGNN_EINVAL;
+    const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
+    if (t_seed < 0) return HOPGNN_EINVAL;
+    if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (g->offsets == nullptr || seeds == nullptr || ids == nullptr) return HOPGNN_EINVAL;
+    if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
+    if ((int64_t)n_seeds * t_seed >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+
+    SampleShape sh{};
+    sh.n_layers = n_layers;
+    sh.P[0] = 1;
+    sh.base[0] = 0;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        sh.f[h] = fanouts[h - 1];
+        sh.P[h] = sh.P[h - 1] * sh.f[h];
+        sh.base[h] = sh.base[h - 1] + n_seeds * sh.P[h - 1];
+    }
+    sh.base[n_layers + 1] = sh.base[n_layers] + n_seeds * sh.P[n_layers];
+
+    int threads = 64;
+    while (threads < 256 && threads < sh.P[n_layers]) threads *= 2;
+    const uint64_t keyed = host_finalise64(key + 0x9E3779B97F4A7C15ull);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (g->offsets_i64)
+        hipLaunchKernelGGL(sample_micrographs<int64_t>, dim3(n_seeds), dim3(threads), 0, s,
+                           static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh,
+                           keyed, ids, indptr, slot_idx);
+    else
+        hipLaunchKernelGGL(sample_micrographs<int32_t>, dim3(n_seeds), dim3(threads), 0, s,
+                           static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh,
+                           keyed, ids, indptr, slot_idx);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+extern "C" const char* hopgnn_status_str(hopgnn_status s) {
+    switch (s) {
+        case HOPGNN_OK: return "ok";
+        case HOPGNN_EINVAL: return "invalid argument";
+        case HOPGNN_ENOMEM_WS: return "workspace too small";
+        case HOPGNN_ERANGE: return "size out of range";
+        case HOPGNN_EHIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,171 @@
+"""GPU parity on whole batches: the five workload shapes, sample -> pregather ->
+gather -> layers, against the oracle.  Configs 1-2 are checked in full; the
+large ones on the sampled rows the oracle can afford."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _layer_rows(n_dst, budget):
+    """Row ranges of a layer to check: all of it, or its head and tail."""
+    if n_dst <= budget:
+        return [(0, n_dst)]
+    h = budget // 2
+    return [(0, h), (n_dst - h, n_dst)]
+
+
+def _check_batch(orc, hp, cfg, graph_np, X, weights, seeds_list, keys, row_budget=4000,
+                 full_forward=False):
+    """Run a group on the GPU and compare everything with the oracle."""
+    from paper_2409_00657_amd.pipeline import BatchShape
+    off_np, idx_np = graph_np
+    sh = hp.shape
+    B, T, L = sh.n_seeds, sh.n_slots, sh.n_layers
+    G = hp.group
+    dt = X.dtype
+    odt = ORC_DT[dt]
+    outs = [torch.empty_like(hp.H[L - 1]) for _ in range(G)]
+    layer_out = []           # per batch, per layer copies for the isolated-layer checks
+
+    # GPU: run step by step so that intermediate layers can be kept
+    for b in range(G):
+        hp.sample(b, seeds_list[b], keys[b])
+    hp.pregather()
+    hp.gather()
+    for b in range(G):
+        hp.layers(b)
+        layer_out.append([h.clone() for h in hp.H])
+    torch.cuda.synchronize()
+
+    # oracle: sampling, pre-gather, gather
+    ref_ids, ref_indptr = [], None
+    for b in range(G):
+        i, ip = orc.sample(off_np, idx_np, seeds_list[b].cpu().numpy(), sh.fanouts, keys[b])
+        ref_ids.append(i)
+        ref_indptr = ip
+    all_ids = np.concatenate(ref_ids)
+    np.testing.assert_array_equal(hp.ids.cpu().numpy(), all_ids)
+    np.testing.assert_array_equal(hp.indptr.cpu().numpy(), ref_indptr)
+    ref_uniq, ref_remap = orc.pregather(all_ids)
+    U = int(hp.n_uniq.item())
+    assert U == len(ref_uniq)
+    np.testing.assert_array_equal(hp.uniq[:U].cpu().numpy(), ref_uniq)
+    np.testing.assert_array_equal(hp.remap.cpu().numpy(), ref_remap)
+    # gathered rows: byte for byte against the source rows the oracle copies
+    Xu_ref = orc.gather(to_bits(X[torch.from_numpy(ref_uniq).long().to(X.device)]),
+                        np.arange(U, dtype=np.int32)) if X.shape[0] > 4_000_000 else \
+        orc.gather(to_bits(X), ref_uniq)
+    assert to_bits(hp.Xu[:U]).tobytes() == Xu_ref.tobytes()
+
+    wb = weights_bits(weights)
+    stats = {"U": U, "T_valid": int((all_ids >= 0).sum())}
+    for b in range(G if full_forward else min(G, 2)):
+        ids_b, remap_b = ref_ids[b], ref_remap[b * T:(b + 1) * T]
+        prev_gpu = None
+        for k in range(1, L + 1):
+            n_dst = sh.n_dst(k)
+            Ws, Wn, bias = wb[k - 1]
+            got_all = layer_out[b][k - 1]
+            for lo, hi in _layer_rows(n_dst, row_budget if not full_forward else n_dst):
+                ip = ref_indptr[lo:hi + 1].astype(np.int64)
+                e0, e1 = int(ip[0]), int(ip[-1])
+                ipl = (ip - e0).astype(np.int32)
+                if k == 1:
+                    src = Xu_ref
+                    self_idx = remap_b[lo:hi]
+                    idx = remap_b[B + e0:B + e1]
+                else:
+                    # isolated layer: the oracle reads the GPU's own stored previous output
+                    src = to_bits(prev_gpu)
+                    self_idx = np.arange(lo, hi, dtype=np.int32)
+                    e = np.arange(e0, e1, dtype=np.int32)
+                    idx = np.where(ids_b[B + e0:B + e1] >= 0, B + e, -1).astype(np.int32)
+                ref = orc.sage_fwd(src, odt, self_idx, ipl, idx, Ws, Wn, bias, relu=(k < L))
+                err = rel_err(to_f64(got_all[lo:hi]), ref)
+                assert err <= TOL[dt], (cfg.name, b, k, lo, hi, err)
+            prev_gpu = got_all
+    return stats, layer_out, ref_ids, ref_remap, Xu_ref
+
+
+def _setup(cfg_id, group=1, device=DEV):
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    cfg = synth.CONFIGS[cfg_id]
+    g = cfg.make_graph(device=device)
+    X = cfg.make_features(device=device)
+    W = cfg.make_weights(device=device)
+    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group)
+    return cfg, g, X, W, hp
+
+
+def _seeds(cfg, it, group):
+    from paper_2409_00657_amd import synth
+    return [synth.seeds(cfg.n_vertices, cfg.batch, it * group + b, device=DEV) for b in range(group)], \
+        [it * group + b for b in range(group)]
+
+
+def test_config1_full_chain_vs_oracle(orc):
+    cfg, g, X, W, hp = _setup(1)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    for it in range(2):
+        seeds, keys = _seeds(cfg, it, 1)
+        stats, layer_out, ref_ids, ref_remap, Xu_ref = _check_batch(
+            orc, hp, cfg, graph_np, X, W, seeds, keys, full_forward=True)
+        # end to end (the oracle chains its own rounded activations)
+        outs = orc.forward(Xu_ref, 0, ref_ids[0], hp.indptr.cpu().numpy(), ref_remap, cfg.batch,
+                           cfg.fanouts, weights_bits(W))
+        for k in range(len(cfg.fanouts)):
+            assert rel_err(to_f64(layer_out[0][k]), outs[k][0]) <= 1e-5
+        # draws are with replacement and equal vertices at one level share their subtree, so
+        # a micrograph holds about 1 + a + a^2 distinct vertices of its 31 slots, with
+        # a = E_d[d (1 - (1 - 1/d)^5)] ~ 4.2 for d uniform in [8,16]: U/T ~ 23/31 = 0.74
+        a = np.mean([d * (1 - (1 - 1 / d) ** 5) for d in range(8, 17)])
+        expect = (1 + a + a * a) / 31
+        assert abs(stats["U"] / stats["T_valid"] - expect) < 0.05
+
+
+def test_config2_full_chain_vs_oracle(orc):
+    cfg, g, X, W, hp = _setup(2)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    seeds, keys = _seeds(cfg, 0, 1)
+    stats, layer_out, ref_ids, ref_remap, Xu_ref = _check_batch(
+        orc, hp, cfg, graph_np, X, W, seeds, keys, full_forward=True)
+    outs = orc.forward(Xu_ref, 0, ref_ids[0], hp.indptr.cpu().numpy(), ref_remap, cfg.batch,
+                       cfg.fanouts, weights_bits(W))
+    for k in range(len(cfg.fanouts)):
+        assert rel_err(to_f64(layer_out[0][k]), outs[k][0]) <= 1e-5
+    # same inputs again: bit-identical outputs (deterministic path)
+    again = hp.run_batch(seeds[0], keys[0]).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(again, layer_out[0][-1])
+
+
+def test_config3_sampled_rows_vs_oracle(orc):
+    cfg, g, X, W, hp = _setup(3)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    seeds, keys = _seeds(cfg, 3, 1)
+    _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, row_budget=3000)
+
+
+@pytest.mark.timeout(600)
+def test_config4_bf16_full_size_sampled_rows_vs_oracle(orc):
+    cfg, g, X, W, hp = _setup(4)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    seeds, keys = _seeds(cfg, 1, 1)
+    _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, row_budget=2000)
+
+
+@pytest.mark.timeout(900)
+def test_config5_fp16_grouped_pregather_vs_oracle(orc):
+    # the full-size table (100M x 128 fp16 = 25.6 GB) and graph (1.2e9 edges) live on the GPU;
+    # a group of 8 batches shares one pre-gather
+    cfg, g, X, W, hp = _setup(5, group=8)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    seeds, keys = _seeds(cfg, 0, 8)
+    stats, *_ = _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, row_budget=1500)
+    assert stats["U"] <= stats["T_valid"]

@@ -1,0 +1,228 @@
+"""GPU parity: every step through the C ABI against the CPU oracle, element by
+element, on seeded inputs spanning several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2409_00657_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _csr(rows, dtype=torch.int32):
+    off = np.zeros(len(rows) + 1, np.int64)
+    off[1:] = np.cumsum([len(r) for r in rows])
+    idx = np.array([x for r in rows for x in r], np.int32)
+    if len(idx) == 0:
+        idx = np.zeros(0, np.int32)
+    return torch.from_numpy(off).to(dtype), torch.from_numpy(idx)
+
+
+def _gpu_sample(hb, off, idx, seeds, fan, key, with_slot_idx=True):
+    B = len(seeds)
+    lv = [B]
+    for f in fan:
+        lv.append(lv[-1] * f)
+    T, S = sum(lv), sum(lv[:-1])
+    ids = torch.full((T,), -7, dtype=torch.int32, device=DEV)
+    indptr = torch.full((S + 1,), -7, dtype=torch.int32, device=DEV)
+    slot_idx = torch.full((max(S - B, 1),), -7, dtype=torch.int32, device=DEV)
+    hb.hopgnn_sample(off.to(DEV), idx.to(DEV), torch.as_tensor(seeds, dtype=torch.int32).to(DEV), fan,
+                     key, ids, indptr, slot_idx if (with_slot_idx and len(fan) > 1) else None)
+    torch.cuda.synchronize()
+    return ids.cpu().numpy(), indptr.cpu().numpy(), slot_idx.cpu().numpy()[:S - B], (B, T, S)
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_sample_bit_exact(hb, orc, case):
+    rng = np.random.default_rng(100 + case)
+    N = [3, 50, 1000, 5000, 257, 20000][case]
+    maxdeg = [3, 6, 40, 9, 300, 17][case]
+    rows = [rng.integers(0, N, size=int(rng.integers(0, maxdeg))).tolist() for _ in range(N)]
+    fan = [[2], [3, 2], [5, 5], [4, 3, 2], [10, 10], [7, 1, 6]][case]
+    B = [1, 7, 64, 130, 33, 300][case]
+    seeds = rng.integers(0, N, size=B).astype(np.int32)
+    key = int(rng.integers(0, 2 ** 63))
+    for dt in (torch.int32, torch.int64):
+        off, idx = _csr(rows, dt)
+        ids, indptr, slot_idx, (B_, T, S) = _gpu_sample(hb, off, idx, seeds, fan, key)
+        ref_ids, ref_indptr = orc.sample(off.numpy(), idx.numpy(), seeds, fan, key)
+        np.testing.assert_array_equal(ids, ref_ids)
+        np.testing.assert_array_equal(indptr, ref_indptr)
+        if len(fan) > 1:
+            e = np.arange(S - B, dtype=np.int32)
+            np.testing.assert_array_equal(slot_idx, np.where(ref_ids[B:S] >= 0, B + e, -1))
+
+
+def test_sample_edge_cases(hb, orc):
+    # zero seeds: no-op; all-isolated graph: every child invalid
+    off, idx = _csr([[], [], []])
+    ids, indptr, _, _ = _gpu_sample(hb, off, idx, np.array([2, 0], np.int32), [3, 2], 5)
+    ref_ids, ref_indptr = orc.sample(off.numpy(), idx.numpy(), np.array([2, 0], np.int32), [3, 2], 5)
+    np.testing.assert_array_equal(ids, ref_ids)
+    np.testing.assert_array_equal(indptr, ref_indptr)
+    assert (ids[2:] == -1).all()
+    empty = torch.zeros(0, dtype=torch.int32, device=DEV)
+    hb.hopgnn_sample(off.to(DEV), idx.to(DEV), empty, [3, 2], 0, empty, None, None)
+    with pytest.raises(hb.HopgnnError):
+        hb.hopgnn_sample(off.to(DEV), idx.to(DEV), empty, [3, 0], 0, empty, None, None)
+    # a vertex of huge degree and degree 1 (remainder by 1 and by a large number)
+    rows = [[1] * 1 , list(range(2, 70002)) ] + [[0]] * 70000
+    off, idx = _csr(rows, torch.int64)
+    seeds = np.array([1, 0, 1], np.int32)
+    ids, _, _, _ = _gpu_sample(hb, off, idx, seeds, [64, 2], 99)
+    ref_ids, _ = orc.sample(off.numpy(), idx.numpy(), seeds, [64, 2], 99)
+    np.testing.assert_array_equal(ids, ref_ids)
+
+
+def _gpu_pregather(hb, ids_np, n_vertices, algo=0):
+    ids = torch.from_numpy(ids_np).to(DEV)
+    n = len(ids_np)
+    uniq = torch.full((max(min(n, n_vertices), 1),), -7, dtype=torch.int32, device=DEV)
+    remap = torch.full((max(n, 1),), -7, dtype=torch.int32, device=DEV)
+    n_uniq = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+    ws = torch.empty(hb.hopgnn_pregather_ws_bytes(n, n_vertices, algo), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xAB)      # the call may not rely on workspace contents
+    hb.hopgnn_pregather(ids, n_vertices, uniq, n_uniq, remap, ws, algo)
+    torch.cuda.synchronize()
+    U = int(n_uniq.item())
+    return uniq.cpu().numpy()[:U], remap.cpu().numpy()[:n], U
+
+
+@pytest.mark.parametrize("algo", [0, 1, 2])
+@pytest.mark.parametrize("case", range(8))
+def test_pregather_bit_exact(hb, orc, case, algo):
+    rng = np.random.default_rng(200 + case)
+    n, N = [(0, 10), (1, 1), (5, 33), (1984, 20000), (113664, 1 << 20), (300001, 70000),
+            (4096, (1 << 31) - 1), (200000, 100)][case]
+    ids = rng.integers(0, N, size=n).astype(np.int32)
+    if n > 3:
+        ids[rng.random(n) < 0.25] = -1
+        ids[-1] = N - 1          # the last vertex, in the bitmap's ragged last word
+        ids[0] = 0
+    if case == 2:
+        ids[:] = -1              # nothing valid
+    uniq, remap, U = _gpu_pregather(hb, ids, N, algo)
+    ref_uniq, ref_remap = orc.pregather(ids)
+    assert U == len(ref_uniq)
+    np.testing.assert_array_equal(uniq, ref_uniq)
+    np.testing.assert_array_equal(remap, ref_remap)
+
+
+def test_pregather_hub_heavy_and_repeatable(hb, orc):
+    # power-law-like multiset: a few IDs repeated tens of thousands of times
+    rng = np.random.default_rng(7)
+    N = 1 << 22
+    ids = np.minimum((N * rng.random(500000) ** 6).astype(np.int64), N - 1).astype(np.int32)
+    ref_uniq, ref_remap = orc.pregather(ids)
+    for _ in range(2):
+        uniq, remap, U = _gpu_pregather(hb, ids, N)
+        np.testing.assert_array_equal(uniq, ref_uniq)
+        np.testing.assert_array_equal(remap, ref_remap)
+
+
+@pytest.mark.parametrize("dtype,dim,ld", [(torch.float32, 32, 32), (torch.float32, 128, 128),
+                                          (torch.float32, 100, 100), (torch.bfloat16, 256, 256),
+                                          (torch.float16, 128, 128), (torch.float32, 7, 7),
+                                          (torch.float16, 5, 5), (torch.float16, 6, 6),
+                                          (torch.float32, 64, 80), (torch.bfloat16, 24, 40)])
+def test_gather_byte_exact(hb, orc, dtype, dim, ld):
+    rng = np.random.default_rng(dim)
+    n_rows = 5003
+    big = torch.from_numpy(rng.standard_normal((n_rows, ld)).astype(np.float32)).to(dtype).to(DEV)
+    X = big[:, :dim]
+    uniq_np = np.unique(rng.integers(0, n_rows, size=3001)).astype(np.int32)
+    uniq_np[-1] = n_rows - 1
+    uniq = torch.from_numpy(uniq_np).to(DEV)
+    U = len(uniq_np)
+    ref = orc.gather(to_bits(big)[:, :dim], uniq_np)
+    # host-count mode
+    Xu = torch.zeros((U, dim), dtype=dtype, device=DEV)
+    hb.hopgnn_gather(X, uniq, U, None, Xu)
+    torch.cuda.synchronize()
+    assert to_bits(Xu).tobytes() == ref.tobytes()
+    # device-count mode: capacity larger than U, rows past U untouched
+    cap = U + 100
+    Xu2 = torch.full((cap, dim), 3.0, dtype=dtype, device=DEV)
+    uniq_cap = torch.cat([uniq, torch.zeros(100, dtype=torch.int32, device=DEV)])
+    n_dev = torch.tensor([U], dtype=torch.int64, device=DEV)
+    hb.hopgnn_gather(X, uniq_cap, cap, n_dev, Xu2)
+    torch.cuda.synchronize()
+    assert to_bits(Xu2[:U]).tobytes() == ref.tobytes()
+    assert (Xu2[U:] == 3.0).all()
+
+
+def _rand_csr(rng, n_dst, n_src, max_len, p_invalid=0.15):
+    lens = rng.integers(0, max_len + 1, size=n_dst)
+    indptr = np.zeros(n_dst + 1, np.int32)
+    indptr[1:] = np.cumsum(lens)
+    idx = rng.integers(0, n_src, size=int(indptr[-1])).astype(np.int32)
+    idx[rng.random(len(idx)) < p_invalid] = -1
+    return indptr, idx
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("shape", [(700, 333, 32, 32, 6), (3000, 1111, 128, 128, 12),
+                                   (5000, 777, 100, 256, 16), (900, 300, 256, 256, 30),
+                                   (400, 129, 20, 12, 5), (300, 65, 7, 5, 4),
+                                   (2000, 40000, 64, 128, 3)])
+def test_sage_fwd_within_tolerance(hb, orc, dtype, shape):
+    n_src, n_dst, d_in, d_out, max_len = shape
+    rng = np.random.default_rng(n_src + d_in)
+    mk = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32))
+    H = mk(n_src, d_in).to(dtype)
+    Ws = (mk(d_in, d_out) / np.sqrt(d_in)).to(dtype)
+    Wn = (mk(d_in, d_out) / np.sqrt(d_in)).to(dtype)
+    b = (mk(d_out) * 0.1).to(dtype)
+    indptr, idx = _rand_csr(rng, n_dst, n_src, max_len)
+    self_idx = rng.integers(0, n_src, size=n_dst).astype(np.int32)
+    self_idx[rng.random(n_dst) < 0.05] = -1
+    for relu, use_bias, use_self in [(True, True, True), (False, False, False)]:
+        if not use_self and n_dst > n_src:
+            continue
+        ws = torch.empty(hb.hopgnn_sage_fwd_ws_bytes(dtype, n_dst, d_in, d_out), dtype=torch.uint8, device=DEV)
+        out = torch.full((n_dst, d_out), 9.0, dtype=dtype, device=DEV)
+        hb.hopgnn_sage_fwd(H.to(DEV), n_src, torch.from_numpy(self_idx).to(DEV) if use_self else None,
+                           torch.from_numpy(indptr).to(DEV), torch.from_numpy(idx).to(DEV), n_dst,
+                           Ws.to(DEV), Wn.to(DEV), b.to(DEV) if use_bias else None, relu, out, ws)
+        torch.cuda.synchronize()
+        ref = orc.sage_fwd(to_bits(H), ORC_DT[dtype], self_idx if use_self else None, indptr, idx,
+                           to_bits(Ws), to_bits(Wn), to_bits(b) if use_bias else None, relu)
+        err = rel_err(to_f64(out), ref)
+        assert err <= TOL[dtype], (err, shape, relu)
+        # run-to-run bit stability
+        out2 = torch.empty_like(out)
+        hb.hopgnn_sage_fwd(H.to(DEV), n_src, torch.from_numpy(self_idx).to(DEV) if use_self else None,
+                           torch.from_numpy(indptr).to(DEV), torch.from_numpy(idx).to(DEV), n_dst,
+                           Ws.to(DEV), Wn.to(DEV), b.to(DEV) if use_bias else None, relu, out2, ws)
+        torch.cuda.synchronize()
+        assert to_bits(out).tobytes() == to_bits(out2).tobytes()
+
+
+def test_sage_fwd_special_cases_exact(hb):
+    # one neighbour -> mean is that row; identity weights -> output is the row (exact in fp32)
+    rng = np.random.default_rng(1)
+    d = 64
+    H = torch.from_numpy(rng.standard_normal((50, d)).astype(np.float32)).to(DEV)
+    I = torch.eye(d, device=DEV)
+    Z = torch.zeros((d, d), device=DEV)
+    n_dst = 40
+    indptr = torch.arange(n_dst + 1, dtype=torch.int32, device=DEV)
+    idx = torch.from_numpy(rng.integers(0, 50, size=n_dst).astype(np.int32)).to(DEV)
+    ws = torch.empty(hb.hopgnn_sage_fwd_ws_bytes(torch.float32, n_dst, d, d), dtype=torch.uint8, device=DEV)
+    out = torch.empty((n_dst, d), device=DEV)
+    hb.hopgnn_sage_fwd(H, 50, None, indptr, idx, n_dst, Z, I, None, False, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, H[idx.long()])
+    hb.hopgnn_sage_fwd(H, 50, None, indptr, idx, n_dst, I, Z, None, False, out, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, H[:n_dst])
