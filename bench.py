@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the micrograph hot path on one MI355X.
+
+A *step* is one whole batch: hopgnn_sample -> hopgnn_pregather -> hopgnn_gather ->
+L x hopgnn_sage_fwd for B fresh seeds, all on one stream, inputs resident in HBM,
+no host synchronisation inside the timed region.  The default workload is the
+R-MAT 2^20-vertex shape (128 fp32 features, 1024 seeds, fanout [10,10], hidden 128).
+
+Prints ONE JSON line: batches/s, the gather kernel's effective HBM GB/s against the
+8 TB/s peak (timed with events inside the timed region), a per-stage breakdown, and
+the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+DTYPE_NAME = {"torch.float32": "f32", "torch.bfloat16": "bf16", "torch.float16": "f16"}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload shape 1..5")
+    ap.add_argument("--group", type=int, default=0, help="batches per pre-gather (0: the shape's default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, g, X, W, group, budget_s):
+    """Time the CPU oracle as it stands (single thread) on whole batches of the same workload."""
+    import numpy as np
+
+    import oracle
+    from paper_2409_00657_amd import synth
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import ORC_DT, to_bits, weights_bits
+
+    off = g.offsets.cpu().numpy()
+    idx = g.indices.cpu().numpy()
+    big = X.shape[0] > 4_000_000
+    Xh = None if big else to_bits(X)
+    wb = weights_bits(W)
+    odt = ORC_DT[X.dtype]
+    done, t_total, it = 0, 0.0, 0
+    while True:
+        seeds = [synth.seeds(cfg.n_vertices, cfg.batch, 10_000 + it * group + b).numpy() for b in range(group)]
+        rows = None
+        if big:   # the oracle cannot hold the table: hand it the rows it will ask for (untimed)
+            ids0 = np.concatenate([oracle.sample(off, idx, s, cfg.fanouts, key=it * group + b)[0]
+                                   for b, s in enumerate(seeds)])
+            u0, _ = oracle.pregather(ids0)
+            import torch
+            rows = to_bits(X[torch.from_numpy(u0).long().to(X.device)])
+        t0 = time.perf_counter()
+        ids, indptr = [], None
+        for b, s in enumerate(seeds):
+            i, indptr = oracle.sample(off, idx, s, cfg.fanouts, key=it * group + b)
+            ids.append(i)
+        allids = np.concatenate(ids)
+        uniq, remap = oracle.pregather(allids)
+        Xu = oracle.gather(rows, np.arange(len(uniq), dtype=np.int32)) if big else oracle.gather(Xh, uniq)
+        T = len(ids[0])
+        for b in range(group):
+            oracle.forward(Xu, odt, ids[b], indptr, remap[b * T:(b + 1) * T], cfg.batch, cfg.fanouts, wb)
+        t_total += time.perf_counter() - t0
+        done += group
+        it += 1
+        if t_total >= budget_s or it >= 64:
+            break
+    return {"value": done / t_total, "unit": "batches/s", "cores": 1, "kind": "oracle",
+            "sample": "%d whole batches of %s (sample+pregather+gather+%d layers, fp64 C oracle, 1 thread)"
+                      % (done, cfg.name, len(cfg.fanouts)),
+            "seconds": round(t_total, 2)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build is the single-GPU hot path (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2409_00657_amd import binding as hb
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+
+    hb.load_library()                      # fail loudly if the HIP library is not built
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    group = args.group or cfg.groups[0]
+    g = cfg.make_graph(device=dev)
+    X = cfg.make_features(device=dev)
+    W = cfg.make_weights(device=dev)
+    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group)
+    sh = hp.shape
+    n_total = args.warmup + args.steps
+    seeds = [[synth.seeds(cfg.n_vertices, cfg.batch, i * group + b, device=dev) for b in range(group)]
+             for i in range(n_total)]
+    keys = [[i * group + b for b in range(group)] for i in range(n_total)]
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        for b in range(group):
+            hp.sample(b, seeds[i][b], keys[i][b])
+        hp.pregather()
+        if ev is not None:
+            ev[0].record()
+        hp.gather()
+        if ev is not None:
+            ev[1].record()
+        for b in range(group):
+            hp.layers(b)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    gather_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                 for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, gather_ev[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    gather_ms = [a.elapsed_time(b) for a, b in gather_ev]
+
+    # untimed, instrumented replay of the same steps: U per step and a per-stage breakdown
+    stage = {"sample": 0.0, "pregather": 0.0, "gather": 0.0}
+    for k in range(1, sh.n_layers + 1):
+        stage["sage_l%d" % k] = 0.0
+    U_sum, valid_sum, gbytes = 0, 0, 0.0
+    E = lambda: torch.cuda.Event(enable_timing=True)
+    n_replay = min(args.steps, 50)
+    for i in range(n_replay):
+        j = args.warmup + i
+        e = [E() for _ in range(4)]
+        e[0].record()
+        for b in range(group):
+            hp.sample(b, seeds[j][b], keys[j][b])
+        e[1].record()
+        hp.pregather()
+        e[2].record()
+        hp.gather()
+        e[3].record()
+        torch.cuda.synchronize()
+        stage["sample"] += e[0].elapsed_time(e[1])
+        stage["pregather"] += e[1].elapsed_time(e[2])
+        stage["gather"] += e[2].elapsed_time(e[3])
+        U_sum += int(hp.n_uniq.item())
+        valid_sum += int((hp.ids >= 0).sum().item())
+        # layers, one event pair per layer, summed over the group's batches
+        T, B, L = sh.n_slots, sh.n_seeds, sh.n_layers
+        for b in range(group):
+            remap = hp.remap[b * T:(b + 1) * T]
+            src, n_src = hp.Xu, hp.cap
+            for k in range(1, L + 1):
+                n_dst, nnz = sh.n_dst(k), sh.nnz(k)
+                Ws, Wn, bias = W[k - 1]
+                self_idx, idx = (remap[:n_dst], remap[B:B + nnz]) if k == 1 else (None, hp.slot_idx[b][:nnz])
+                a, c = E(), E()
+                a.record()
+                hb.hopgnn_sage_fwd(src, n_src, self_idx, hp.indptr[:n_dst + 1], idx, n_dst, Ws, Wn, bias,
+                                   k < L, hp.H[k - 1], hp.sage_ws)
+                c.record()
+                torch.cuda.synchronize()
+                stage["sage_l%d" % k] += a.elapsed_time(c)
+                src, n_src = hp.H[k - 1], n_dst
+    stage = {k: v / n_replay for k, v in stage.items()}
+    U_avg = U_sum / n_replay
+    row_bytes = X.shape[1] * X.element_size()
+    # algorithmic bytes of one gather launch: every unique row read once and written once,
+    # plus its 4-byte index
+    gather_bytes = U_avg * (2 * row_bytes + 4)
+    gather_ms_avg = sum(gather_ms) / len(gather_ms)
+    gather_gbps = gather_bytes / (gather_ms_avg * 1e-3) / 1e9
+
+    out = {
+        "metric": "micrograph batches/s",
+        "value": args.steps * group / elapsed,
+        "unit": "batches/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": DTYPE_NAME[str(X.dtype)], "data": "synthetic",
+        "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges,
+                   "feature_dim": cfg.d, "batch": cfg.batch, "fanouts": cfg.fanouts,
+                   "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots},
+        "gather_GBps": gather_gbps,
+        "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
+        "unique_rows_per_step": U_avg,
+        "unique_over_valid_slots": U_sum / max(valid_sum, 1),
+        "valid_slot_fraction": valid_sum / (n_replay * group * sh.n_slots),
+        "stage_ms": {k: round(v, 5) for k, v in stage.items()},
+        "roofline": {"kernel": "gather_rows", "bound": "hbm", "achieved": gather_gbps,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
+                     "traffic": None, "algorithmic_bytes_per_launch": gather_bytes,
+                     "avg_launch_ms": gather_ms_avg},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, g, X, W, group, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
