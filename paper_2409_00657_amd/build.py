@@ -56,6 +56,12 @@ def build_library(verbose: bool = False) -> str:
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
     os.replace(tmp, LIB)
+    # torch-free timing driver of the C ABI (used under rocprofv3)
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "include"),
+                        os.path.join(CSRC, "cbench.cpp"), "-o", os.path.join(PKG, "cbench"),
+                        "-L", PKG, "-lhopgnn", "-Wl,-rpath,$ORIGIN"], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("cbench build failed:\n" + r.stderr)
     return LIB
 
 

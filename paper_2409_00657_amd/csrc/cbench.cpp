@@ -1,0 +1,166 @@
+// cbench: a torch-free driver of the C ABI for timing one entry point under rocprofv3.
+//
+//   cbench sage   <n_src> <n_dst> <d_in> <d_out> <f32|bf16|f16> <fanout> <iters>
+//   cbench gather <n_rows> <n_uniq> <dim> <f32|bf16|f16> <iters>
+//   cbench pregather <n_ids> <n_vertices> <iters>
+//
+// Inputs are pseudo-random with the right shapes; results are not checked here (the
+// parity tests do that).  Prints the mean time per call measured with HIP events.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "hopgnn.h"
+
+#define CK(x)                                                                      \
+    do {                                                                           \
+        hipError_t e_ = (x);                                                       \
+        if (e_ != hipSuccess) {                                                    \
+            fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_));                \
+            exit(1);                                                               \
+        }                                                                          \
+    } while (0)
+
+static uint64_t rng_state = 0x1234567;
+static uint64_t rnd() {
+    rng_state ^= rng_state << 13;
+    rng_state ^= rng_state >> 7;
+    rng_state ^= rng_state << 17;
+    return rng_state;
+}
+
+static hopgnn_dtype parse_dt(const char* s) {
+    if (!strcmp(s, "f32")) return HOPGNN_F32;
+    if (!strcmp(s, "bf16")) return HOPGNN_BF16;
+    return HOPGNN_F16;
+}
+
+template <typename T>
+static T* upload(const std::vector<T>& h) {
+    T* d;
+    CK(hipMalloc(&d, h.size() * sizeof(T) + 256));
+    CK(hipMemcpy(d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice));
+    return d;
+}
+
+// small finite values of the given type
+static std::vector<uint8_t> random_table(size_t n, hopgnn_dtype dt) {
+    const size_t es = dt == HOPGNN_F32 ? 4 : 2;
+    std::vector<uint8_t> h(n * es);
+    for (size_t i = 0; i < n; ++i) {
+        const float f = (float)((int64_t)(rnd() % 2001) - 1000) * 1e-3f;
+        if (dt == HOPGNN_F32) {
+            memcpy(&h[i * 4], &f, 4);
+        } else if (dt == HOPGNN_BF16) {
+            uint32_t u;
+            memcpy(&u, &f, 4);
+            const uint16_t b = (uint16_t)(u >> 16);
+            memcpy(&h[i * 2], &b, 2);
+        } else {
+            const _Float16 hf = (_Float16)f;
+            memcpy(&h[i * 2], &hf, 2);
+        }
+    }
+    return h;
+}
+
+template <typename F>
+static void time_it(const char* what, int iters, F&& f) {
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    for (int i = 0; i < 3; ++i) f();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0, 0));
+    for (int i = 0; i < iters; ++i) f();
+    CK(hipEventRecord(e1, 0));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    printf("%s: %.2f us per call (%d calls)\n", what, ms * 1e3f / iters, iters);
+}
+
+int main(int argc, char** argv) {
+    if (argc < 2) return 1;
+    const std::string mode = argv[1];
+    if (mode == "sage" && argc >= 9) {
+        const int64_t n_src = atoll(argv[2]), n_dst = atoll(argv[3]);
+        const int d_in = atoi(argv[4]), d_out = atoi(argv[5]);
+        const hopgnn_dtype dt = parse_dt(argv[6]);
+        const int fan = atoi(argv[7]), iters = atoi(argv[8]);
+        const size_t es = dt == HOPGNN_F32 ? 4 : 2;
+        auto H = upload(random_table((size_t)n_src * d_in, dt));
+        auto Ws = upload(random_table((size_t)d_in * d_out, dt));
+        auto Wn = upload(random_table((size_t)d_in * d_out, dt));
+        std::vector<int32_t> indptr(n_dst + 1), idx((size_t)n_dst * fan), self(n_dst);
+        for (int64_t r = 0; r <= n_dst; ++r) indptr[r] = (int32_t)(r * fan);
+        for (auto& x : idx) x = (int32_t)(rnd() % n_src);
+        for (auto& x : self) x = (int32_t)(rnd() % n_src);
+        auto d_indptr = upload(indptr);
+        auto d_idx = upload(idx);
+        auto d_self = upload(self);
+        void *out, *ws;
+        const size_t wsb = hopgnn_sage_fwd_ws_bytes(dt, n_dst, d_in, d_out);
+        CK(hipMalloc(&out, (size_t)n_dst * d_out * es));
+        CK(hipMalloc(&ws, wsb));
+        time_it("hopgnn_sage_fwd", iters, [&] {
+            hopgnn_status st = hopgnn_sage_fwd(H, dt, n_src, d_in, d_self, d_indptr, d_idx, n_dst, Ws, Wn, nullptr,
+                                               d_out, 1, out, ws, wsb, nullptr);
+            if (st != HOPGNN_OK) { fprintf(stderr, "sage_fwd: %s\n", hopgnn_status_str(st)); exit(1); }
+        });
+        const double flop = 2.0 * n_dst * 2.0 * d_in * d_out;
+        printf("projection flop per call: %.3f GFLOP; aggregate bytes per call: %.1f MB\n", flop / 1e9,
+               (double)(n_dst * (fan + 1)) * d_in * es / 1e6);
+    } else if (mode == "gather" && argc >= 7) {
+        const int64_t n_rows = atoll(argv[2]), n_uniq = atoll(argv[3]);
+        const int dim = atoi(argv[4]);
+        const hopgnn_dtype dt = parse_dt(argv[5]);
+        const int iters = atoi(argv[6]);
+        const size_t es = dt == HOPGNN_F32 ? 4 : 2;
+        void *X, *Xu;
+        CK(hipMalloc(&X, (size_t)n_rows * dim * es));
+        CK(hipMemset(X, 1, (size_t)n_rows * dim * es));
+        CK(hipMalloc(&Xu, (size_t)n_uniq * dim * es));
+        std::vector<int32_t> uniq(n_uniq);   // ascending sample of the rows
+        for (int64_t i = 0; i < n_uniq; ++i) {
+            const int64_t lo = i * n_rows / n_uniq, hi = (i + 1) * n_rows / n_uniq;
+            uniq[i] = (int32_t)(lo + (int64_t)(rnd() % (uint64_t)(hi > lo ? hi - lo : 1)));
+        }
+        auto d_uniq = upload(uniq);
+        time_it("hopgnn_gather", iters, [&] {
+            hopgnn_status st = hopgnn_gather(X, dt, n_rows, dim, dim, d_uniq, n_uniq, nullptr, Xu, nullptr);
+            if (st != HOPGNN_OK) { fprintf(stderr, "gather: %s\n", hopgnn_status_str(st)); exit(1); }
+        });
+        printf("algorithmic bytes per call: %.1f MB\n", (double)n_uniq * (2.0 * dim * es + 4) / 1e6);
+    } else if (mode == "pregather" && argc >= 5) {
+        const int64_t n_ids = atoll(argv[2]), n_vertices = atoll(argv[3]);
+        const int iters = atoi(argv[4]);
+        std::vector<int32_t> ids(n_ids);
+        for (auto& x : ids) {   // skewed towards low IDs like a power-law graph
+            const double u = (double)(rnd() >> 11) / 9007199254740992.0;
+            x = (int32_t)((double)n_vertices * u * u * u);
+        }
+        auto d_ids = upload(ids);
+        int32_t *uniq, *remap;
+        int64_t* n_uniq;
+        void* ws;
+        const size_t wsb = hopgnn_pregather_ws_bytes(n_ids, n_vertices, 0);
+        CK(hipMalloc(&uniq, (size_t)n_ids * 4));
+        CK(hipMalloc(&remap, (size_t)n_ids * 4));
+        CK(hipMalloc(&n_uniq, 8));
+        CK(hipMalloc(&ws, wsb));
+        time_it("hopgnn_pregather", iters, [&] {
+            hopgnn_status st = hopgnn_pregather(d_ids, n_ids, n_vertices, 0, uniq, n_uniq, remap, ws, wsb, nullptr);
+            if (st != HOPGNN_OK) { fprintf(stderr, "pregather: %s\n", hopgnn_status_str(st)); exit(1); }
+        });
+    } else {
+        fprintf(stderr, "see the header of cbench.cpp for usage\n");
+        return 1;
+    }
+    return 0;
+}

@@ -71,7 +71,9 @@ template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
-              uint4* __restrict__ Mean) {
+              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words) {
+    if (blockIdx.x == 0)   // the projection reads absent rows and the K padding from this row
+        for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
@@ -111,7 +113,9 @@ template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
                const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
-               typename Tr::store_t* __restrict__ Mean) {
+               typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words) {
+    if (blockIdx.x == 0)
+        for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
@@ -133,31 +137,51 @@ sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __r
 
 // -------------------------------------------------------------- projection --
 //
+// out = act( [x_self | mean] (M x 2*d_in) * [W_self ; W_neigh] (2*d_in x d_out) + b )
+//
 // 256 threads = 4 waves in a 2 x 2 arrangement; each wave owns a (BM/2) x (BN/2)
-// piece of the output as 32 x 32 MFMA tiles.  The K loop runs over two phases:
-// phase 0 multiplies the self rows by W_self, phase 1 the means by W_neigh; each
-// phase is zero-padded to a whole number of BK tiles.
+// piece of the output as 32 x 32 MFMA tiles.  K runs over the concatenation of the
+// self half (read from Hsrc through self_idx) and the mean half; the last K tile is
+// zero padded.  Tiles are staged global -> registers -> LDS with two register sets
+// and two LDS stages, so the loads of tiles t+2 and t+3 are in flight while tile t is
+// multiplied; the per-tile barrier waits for LDS traffic only.
 //
 // Accumulator layout of a 32x32 MFMA tile: register i of lane l holds
 //   row = 8*(i/4) + 4*(l/32) + i%4,  col = l%32.
 
 constexpr int kProjThreads = 256;
+constexpr int kXcds = 8;
 
-template <typename Tr, int BM, int BN>
-__device__ __forceinline__ void project_epilogue(floatx16 (&acc)[BM / 64][BN / 64], int64_t row0,
-                                                 int32_t col0, int wm, int wn, int lane, int64_t n_dst,
-                                                 int32_t d_out, const typename Tr::store_t* bias,
-                                                 int relu, typename Tr::store_t* out) {
+// Workgroup barrier that waits for this wave's LDS operations only.  __syncthreads()
+// would also wait for every outstanding global load and drain the prefetch queue.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Keep all N
+// tiles of one M tile on one XCD so the left operand is fetched into one L2 only.
+__device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t n_tiles, uint32_t& mt, uint32_t& nt) {
+    const uint32_t xcd = bid % kXcds, j = bid / kXcds;
+    nt = j % n_tiles;
+    mt = (j / n_tiles) * kXcds + xcd;
+}
+
+// Writes one wave's TM x TN block of 32x32 tiles whose top-left element is (row0, col0).
+template <typename Tr, int TM, int TN>
+__device__ __forceinline__ void project_epilogue(floatx16 (&acc)[TM][TN], int64_t row0, int32_t col0,
+                                                 int lane, int64_t n_dst, int32_t d_out,
+                                                 const typename Tr::store_t* bias, int relu,
+                                                 typename Tr::store_t* out) {
 #pragma unroll
-    for (int tn = 0; tn < BN / 64; ++tn) {
-        const int32_t col = col0 + wn * (BN / 2) + tn * 32 + (lane & 31);
+    for (int tn = 0; tn < TN; ++tn) {
+        const int32_t col = col0 + tn * 32 + (lane & 31);
         if (col >= d_out) continue;
         const float b = bias != nullptr ? Tr::to_f(bias[col]) : 0.f;
 #pragma unroll
-        for (int tm = 0; tm < BM / 64; ++tm) {
+        for (int tm = 0; tm < TM; ++tm) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int64_t row = row0 + wm * (BM / 2) + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                const int64_t row = row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
                 if (row < n_dst) {
                     float x = acc[tm][tn][i] + b;
                     if (relu) x = fmaxf(x, 0.f);
@@ -168,26 +192,80 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[BM / 64][BN / 6
     }
 }
 
-// fp32: v_mfma_f32_32x32x2_f32.  LDS holds A transposed (k-major) so that the 32
-// lanes of a half-wave read 32 consecutive floats.
+// 2-byte outputs: a lane of an MFMA tile holds single elements of 16 different rows, so
+// storing them directly issues 2-byte writes (64-byte pieces of two rows per instruction).
+// Instead each wave passes one 32-row band of its tiles through a private piece of LDS
+// ([32][32*TN + 8] elements) and writes it out as 128-bit words, whole rows at a time.
+// Requires d_out % 8 == 0.  `band` points at this wave's LDS piece; waves do not share it,
+// so only this wave's own LDS traffic has to be waited for.
+template <typename Tr, int TM, int TN>
+__device__ __forceinline__ void project_epilogue_staged(floatx16 (&acc)[TM][TN], int64_t row0, int32_t col0,
+                                                        int lane, int64_t n_dst, int32_t d_out,
+                                                        const typename Tr::store_t* bias, int relu,
+                                                        typename Tr::store_t* out,
+                                                        typename Tr::store_t* band) {
+    using T = typename Tr::store_t;
+    constexpr int W = 32 * TN, LDW = W + 8;          // band width in elements, padded row
+    constexpr int WORDS = W / 8;                     // 16-byte words per band row
+    float b[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int32_t col = col0 + tn * 32 + (lane & 31);
+        b[tn] = (bias != nullptr && col < d_out) ? Tr::to_f(bias[col]) : 0.f;
+    }
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float x = acc[tm][tn][i] + b[tn];
+                if (relu) x = fmaxf(x, 0.f);
+                band[(8 * (i / 4) + 4 * (lane >> 5) + (i & 3)) * LDW + tn * 32 + (lane & 31)] = Tr::from_f(x);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < 32 * WORDS / 64; ++j) {
+            const int w = j * 64 + lane;
+            const int r = w / WORDS, c = (w % WORDS) * 8;
+            const int64_t row = row0 + tm * 32 + r;
+            const uint4 v = *reinterpret_cast<const uint4*>(&band[r * LDW + c]);
+            if (row < n_dst && col0 + c < d_out)
+                *reinterpret_cast<uint4*>(&out[row * d_out + col0 + c]) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // band is rewritten by the next tm
+    }
+    (void)sizeof(T);
+}
+
+// fp32: v_mfma_f32_32x32x2_f32 (lane l feeds A[row l%32][k = l/32] and B[k = l/32][col l%32]).
+// LDS: A row-major [BM][BK+4] read as 128-bit words - lane group g = l/32 takes the four
+// k values 4g..4g+3 of an 8-wide K block and the four MFMAs of the block pair A's i-th
+// value with B row 4g+i, which only permutes the order in which k is summed.
+// B is [BK][BN+4], read as 32 consecutive floats per half wave.
 template <int BM, int BN, bool VEC>
 __global__ void __launch_bounds__(kProjThreads)
 sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                  const float* __restrict__ Mean, const float* __restrict__ Wself,
                  const float* __restrict__ Wneigh, const float* __restrict__ bias, int64_t n_dst,
-                 int32_t d_in, int32_t d_out, int relu, float* __restrict__ out) {
-    constexpr int BK = 16;
+                 int32_t d_in, int32_t d_out, int relu, uint32_t n_tiles_n, const float* __restrict__ Zero,
+                 float* __restrict__ out) {
+    constexpr int BK = 16, LDA = BK + 4, LDB = BN + 4;
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_ITEMS = BM * BK / 4 / kProjThreads;   // float4 items per thread
     constexpr int B_ITEMS = BK * BN / 4 / kProjThreads;
     static_assert(A_ITEMS >= 1 && B_ITEMS >= 1, "tile too small for 256 threads");
-    __shared__ float As[BK][BM + 4];
-    __shared__ __attribute__((aligned(16))) float Bs[BK][BN + 4];
+    __shared__ __attribute__((aligned(16))) float As[2][BM][LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
 
+    uint32_t mt, nt;
+    tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
+    const int64_t row0 = (int64_t)mt * BM;
+    if (row0 >= n_dst) return;
+    const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t row0 = (int64_t)blockIdx.x * BM;
-    const int32_t col0 = blockIdx.y * BN;
+    const int K = 2 * d_in;
 
     // rows this thread stages, fixed for the whole K loop
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
@@ -212,32 +290,40 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.f;
 
-    const int tiles_per_phase = (d_in + BK - 1) / BK;
-    const int n_tiles = 2 * tiles_per_phase;
+    struct Regs {
+        float4 a[A_ITEMS], b[B_ITEMS];
+    };
+    const int n_tiles = (K + BK - 1) / BK;
 
-    float4 ra[A_ITEMS], rb[B_ITEMS];
-    auto load_tile = [&](int t) {
-        const int phase = t >= tiles_per_phase;
-        const int k0 = (t - phase * tiles_per_phase) * BK;
-        const float* Asrc = phase ? Mean : Hsrc;
-        const float* W = phase ? Wneigh : Wself;
+    // Branch-free addressing for the vector path: rows that do not exist and the K padding
+    // are read from `Zero`, a row of zeros at least one padded K long, so the loop has no
+    // control flow and nothing consumes a loaded value before it is stored to LDS.
+    const float* p_self[A_ITEMS];
+    const float* p_mean[A_ITEMS];
+#pragma unroll
+    for (int it = 0; it < A_ITEMS; ++it) {
+        p_self[it] = a_self[it] >= 0 ? Hsrc + a_self[it] : Zero;
+        p_mean[it] = a_mean[it] >= 0 ? Mean + a_mean[it] - d_in : Zero;   // indexed by the concatenated k
+    }
+    auto a_elem = [&](int it, int k) -> float {   // one element of the concatenated row
+        if (k < d_in) return a_self[it] >= 0 ? Hsrc[a_self[it] + k] : 0.f;
+        if (k < K) return a_mean[it] >= 0 ? Mean[a_mean[it] + (k - d_in)] : 0.f;
+        return 0.f;
+    };
+    auto load_tile = [&](Regs& r, int t) {
+        const int k0 = t * BK;
 #pragma unroll
         for (int it = 0; it < A_ITEMS; ++it) {
             const int i = it * kProjThreads + tid;
             const int k = k0 + (i % (BK / 4)) * 4;
-            const int64_t base = phase ? a_mean[it] : a_self[it];
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (base >= 0) {
-                if (VEC && k + 3 < d_in) {
-                    v = *reinterpret_cast<const float4*>(Asrc + base + k);
-                } else {
-                    if (k + 0 < d_in) v.x = Asrc[base + k + 0];
-                    if (k + 1 < d_in) v.y = Asrc[base + k + 1];
-                    if (k + 2 < d_in) v.z = Asrc[base + k + 2];
-                    if (k + 3 < d_in) v.w = Asrc[base + k + 3];
-                }
+            float4 v;
+            if (VEC) {   // d_in % 4 == 0: a float4 never straddles the self/mean boundary
+                const float* p = (k < d_in ? p_self[it] : p_mean[it]) + k;
+                v = *reinterpret_cast<const float4*>(k < K ? p : Zero);
+            } else {
+                v = make_float4(a_elem(it, k), a_elem(it, k + 1), a_elem(it, k + 2), a_elem(it, k + 3));
             }
-            ra[it] = v;
+            r.a[it] = v;
         }
 #pragma unroll
         for (int it = 0; it < B_ITEMS; ++it) {
@@ -245,60 +331,82 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
             const int k = k0 + i / (BN / 4);
             const int n = col0 + (i % (BN / 4)) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k < d_in) {
-                const float* p = W + (int64_t)k * d_out + n;
-                if (VEC && n + 3 < d_out) {
-                    v = *reinterpret_cast<const float4*>(p);
-                } else {
-                    if (n + 0 < d_out) v.x = p[0];
-                    if (n + 1 < d_out) v.y = p[1];
-                    if (n + 2 < d_out) v.z = p[2];
-                    if (n + 3 < d_out) v.w = p[3];
-                }
+            if (VEC) {   // d_out % 4 == 0
+                const float* p = (k < d_in ? Wself + (int64_t)k * d_out : Wneigh + (int64_t)(k - d_in) * d_out) + n;
+                v = *reinterpret_cast<const float4*>((k < K && n < d_out) ? p : Zero);
+            } else if (k < K) {
+                const float* p = (k < d_in ? Wself + (int64_t)k * d_out : Wneigh + (int64_t)(k - d_in) * d_out) + n;
+                if (n + 0 < d_out) v.x = p[0];
+                if (n + 1 < d_out) v.y = p[1];
+                if (n + 2 < d_out) v.z = p[2];
+                if (n + 3 < d_out) v.w = p[3];
             }
-            rb[it] = v;
+            r.b[it] = v;
         }
     };
-
-    load_tile(0);
-    for (int t = 0; t < n_tiles; ++t) {
-        __syncthreads();
+    auto store_tile = [&](const Regs& r, int st) {
 #pragma unroll
         for (int it = 0; it < A_ITEMS; ++it) {
             const int i = it * kProjThreads + tid;
-            const int r = i / (BK / 4), kq = (i % (BK / 4)) * 4;
-            As[kq + 0][r] = ra[it].x;
-            As[kq + 1][r] = ra[it].y;
-            As[kq + 2][r] = ra[it].z;
-            As[kq + 3][r] = ra[it].w;
+            *reinterpret_cast<float4*>(&As[st][i / (BK / 4)][(i % (BK / 4)) * 4]) = r.a[it];
         }
 #pragma unroll
         for (int it = 0; it < B_ITEMS; ++it) {
             const int i = it * kProjThreads + tid;
-            *reinterpret_cast<float4*>(&Bs[i / (BN / 4)][(i % (BN / 4)) * 4]) = rb[it];
+            *reinterpret_cast<float4*>(&Bs[st][i / (BN / 4)][(i % (BN / 4)) * 4]) = r.b[it];
         }
-        __syncthreads();
-        if (t + 1 < n_tiles) load_tile(t + 1);
+    };
+    auto compute = [&](int st) {
+        const int g = lane >> 5, l32 = lane & 31;
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 2) {
-            float a[TM], b[TN];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) a[tm] = As[kk + (lane >> 5)][wm * (BM / 2) + tm * 32 + (lane & 31)];
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) b[tn] = Bs[kk + (lane >> 5)][wn * (BN / 2) + tn * 32 + (lane & 31)];
+        for (int kk = 0; kk < BK; kk += 8) {
+            float4 a[TM];
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
+                a[tm] = *reinterpret_cast<const float4*>(&As[st][wm * (BM / 2) + tm * 32 + l32][kk + 4 * g]);
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tm], b[tn], acc[tm][tn], 0, 0, 0);
+            for (int i = 0; i < 4; ++i) {
+                float b[TN];
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn) b[tn] = Bs[st][kk + 4 * g + i][wn * (BN / 2) + tn * 32 + l32];
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    const float av = i == 0 ? a[tm].x : i == 1 ? a[tm].y : i == 2 ? a[tm].z : a[tm].w;
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[tn], acc[tm][tn], 0, 0, 0);
+                }
+            }
         }
+    };
+
+    // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
+    // an even number of tiles.  Iteration t: r holds tile t+1 -> LDS stage (t+1)&1; r is
+    // refilled with tile t+3; tile t is multiplied from stage t&1.
+    Regs r0, r1;
+    load_tile(r0, 0);
+    store_tile(r0, 0);
+    load_tile(r1, 1);
+    load_tile(r0, 2);
+    lds_barrier();
+    for (int t = 0; t < n_tiles; t += 2) {
+        store_tile(r1, 1);
+        load_tile(r1, t + 3);
+        compute(0);
+        lds_barrier();
+        store_tile(r0, 0);
+        load_tile(r0, t + 4);
+        compute(1);
+        lds_barrier();
     }
-    project_epilogue<TrF32, BM, BN>(acc, row0, col0, wm, wn, lane, n_dst, d_out, bias, relu, out);
+    project_epilogue<TrF32, TM, TN>(acc, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane, n_dst, d_out, bias, relu, out);
 }
 
-// bf16 / fp16: v_mfma_f32_32x32x16_{bf16,f16}.  Lane l feeds 8 consecutive k of
-// row (or column) l%32, k-group l/32.  LDS: A row-major [BM][BK+8], B n-major
-// [BN][BK+8] (W is transposed while it is staged), both read as 128-bit words.
+// bf16 / fp16: v_mfma_f32_32x32x16_{bf16,f16}.  Lane l feeds 8 consecutive k of row (or
+// column) l%32, k-group l/32, so both operands sit in LDS with k contiguous and are read
+// as 128-bit words: A [BM][BK+8], B [BN][BK+8] (row stride 80 bytes: conflict free).
+// B comes from Wt, the transposed weights [NP][KP] (k contiguous, zero padded to whole
+// tiles) that sage_transpose_w writes into the workspace.
 template <typename Tr>
 __device__ __forceinline__ floatx16 mfma16(const uint4& a, const uint4& b, floatx16 c);
 template <>
@@ -312,30 +420,61 @@ __device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b
                                                   *reinterpret_cast<const halfx8*>(&b), c, 0, 0, 0);
 }
 
-template <typename Tr, int BM, int BN, bool VEC>
-__global__ void __launch_bounds__(kProjThreads)
-sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
-                const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wself,
-                const uint16_t* __restrict__ Wneigh, const typename Tr::store_t* __restrict__ bias,
-                int64_t n_dst, int32_t d_in, int32_t d_out, int relu,
-                typename Tr::store_t* __restrict__ out) {
-    constexpr int BK = 32, LD = BK + 8;
-    constexpr int TM = BM / 64, TN = BN / 64;
-    constexpr int A_ITEMS = BM * BK / 8 / kProjThreads;   // 16-byte items per thread
-    constexpr int B_ITEMS = BK * BN / 8 / kProjThreads;
-    static_assert(A_ITEMS >= 1 && B_ITEMS >= 1, "tile too small for 256 threads");
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM][LD];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN][LD];
+constexpr int kKPad16 = 64;   // Wt rows are zero padded to a multiple of this many k
 
+// Wt[n][k] = (k < d_in ? W_self[k][n] : W_neigh[k - d_in][n]), zero outside [0,2*d_in) x [0,d_out).
+// 32 x 32 tiles through LDS so both the reads and the writes are coalesced.
+__global__ void __launch_bounds__(256)
+sage_transpose_w(const uint16_t* __restrict__ Wself, const uint16_t* __restrict__ Wneigh, int32_t d_in,
+                 int32_t d_out, int32_t KP, int32_t NP, uint16_t* __restrict__ Wt) {
+    __shared__ uint16_t tile[32][33];
+    const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int j = ty; j < 32; j += 8) {
+        const int k = k0 + j, n = n0 + tx;
+        uint16_t v = 0;
+        if (k < 2 * d_in && n < d_out)
+            v = k < d_in ? Wself[(int64_t)k * d_out + n] : Wneigh[(int64_t)(k - d_in) * d_out + n];
+        tile[j][tx] = v;
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        const int n = n0 + j, k = k0 + tx;
+        if (n < NP && k < KP) Wt[(int64_t)n * KP + k] = tile[tx][j];
+    }
+}
+
+template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
+__global__ void __launch_bounds__(64 * WM * WN)
+sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
+                const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
+                const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_in,
+                int32_t d_out, int relu, uint32_t n_tiles_n, const uint16_t* __restrict__ Zero,
+                typename Tr::store_t* __restrict__ out) {
+    constexpr int LD = BK + 8;
+    static_assert(kKPad16 % BK == 0, "Wt padding must cover whole K tiles");
+    constexpr int NT = 64 * WM * WN;                      // threads: WM x WN waves
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
+    constexpr int A_ITEMS = BM * BK / 8 / NT;             // 16-byte items per thread
+    constexpr int B_ITEMS = BN * BK / 8 / NT;
+    static_assert(A_ITEMS >= 1 && B_ITEMS >= 1, "tile too small for the workgroup");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds16[];
+    uint16_t (*As)[BM][LD] = reinterpret_cast<uint16_t (*)[BM][LD]>(lds16);
+    uint16_t (*Bs)[BN][LD] = reinterpret_cast<uint16_t (*)[BN][LD]>(lds16 + 2 * BM * LD);
+
+    uint32_t mt, nt;
+    tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
+    const int64_t row0 = (int64_t)mt * BM;
+    if (row0 >= n_dst) return;
+    const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int64_t row0 = (int64_t)blockIdx.x * BM;
-    const int32_t col0 = blockIdx.y * BN;
+    const int wm = wave / WN, wn = wave % WN;
+    const int K = 2 * d_in;
 
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
 #pragma unroll
     for (int it = 0; it < A_ITEMS; ++it) {
-        const int i = it * kProjThreads + tid;
+        const int i = it * NT + tid;
         const int64_t r = row0 + i / (BK / 8);
         a_self[it] = -1;
         a_mean[it] = -1;
@@ -354,92 +493,111 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.f;
 
-    const int tiles_per_phase = (d_in + BK - 1) / BK;
-    const int n_tiles = 2 * tiles_per_phase;
-
+    struct Regs {
+        uint4 a[A_ITEMS], b[B_ITEMS];
+    };
     union U16x8 {
         uint4 v;
         uint16_t e[8];
     };
-    U16x8 ra[A_ITEMS], rb[B_ITEMS];
-    auto load_tile = [&](int t) {
-        const int phase = t >= tiles_per_phase;
-        const int k0 = (t - phase * tiles_per_phase) * BK;
-        const uint16_t* Asrc = phase ? Mean : Hsrc;
-        const uint16_t* W = phase ? Wneigh : Wself;
+    const int n_tiles = (K + BK - 1) / BK;
+
+    const uint16_t* p_self[A_ITEMS];
+    const uint16_t* p_mean[A_ITEMS];
+#pragma unroll
+    for (int it = 0; it < A_ITEMS; ++it) {
+        p_self[it] = a_self[it] >= 0 ? Hsrc + a_self[it] : Zero;
+        p_mean[it] = a_mean[it] >= 0 ? Mean + a_mean[it] - d_in : Zero;   // indexed by the concatenated k
+    }
+    auto a_elem = [&](int it, int k) -> uint16_t {
+        if (k < d_in) return a_self[it] >= 0 ? Hsrc[a_self[it] + k] : (uint16_t)0;
+        if (k < K) return a_mean[it] >= 0 ? Mean[a_mean[it] + (k - d_in)] : (uint16_t)0;
+        return 0;
+    };
+    auto load_tile = [&](Regs& r, int t) {
+        const int k0 = t * BK;
 #pragma unroll
         for (int it = 0; it < A_ITEMS; ++it) {
-            const int i = it * kProjThreads + tid;
+            const int i = it * NT + tid;
             const int k = k0 + (i % (BK / 8)) * 8;
-            const int64_t base = phase ? a_mean[it] : a_self[it];
             U16x8 v;
-            v.v = make_uint4(0u, 0u, 0u, 0u);
-            if (base >= 0) {
-                if (VEC && k + 7 < d_in) {
-                    v.v = *reinterpret_cast<const uint4*>(Asrc + base + k);
-                } else {
+            if (VEC) {   // d_in % 8 == 0: a 16-byte word never straddles the self/mean boundary
+                const uint16_t* p = (k < d_in ? p_self[it] : p_mean[it]) + k;
+                v.v = *reinterpret_cast<const uint4*>(k < K ? p : Zero);
+            } else {
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (k + j < d_in) v.e[j] = Asrc[base + k + j];
-                }
+                for (int j = 0; j < 8; ++j) v.e[j] = a_elem(it, k + j);
             }
-            ra[it] = v;
+            r.a[it] = v.v;
         }
-        // B: lanes run along k so the transposed LDS stores of a wave are contiguous
+        // Wt is padded to whole tiles; tiles past the end re-read the last one (A is zero there)
+        const int kb = k0 < KP ? k0 : KP - BK;
 #pragma unroll
         for (int it = 0; it < B_ITEMS; ++it) {
-            const int i = it * kProjThreads + tid;
-            const int k = k0 + (i % BK);
-            const int n = col0 + (i / BK) * 8;
-            U16x8 v;
-            v.v = make_uint4(0u, 0u, 0u, 0u);
-            if (k < d_in) {
-                const uint16_t* p = W + (int64_t)k * d_out + n;
-                if (VEC && n + 7 < d_out) {
-                    v.v = *reinterpret_cast<const uint4*>(p);
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (n + j < d_out) v.e[j] = p[j];
-                }
-            }
-            rb[it] = v;
+            const int i = it * NT + tid;
+            r.b[it] = *reinterpret_cast<const uint4*>(Wt + (int64_t)(col0 + i / (BK / 8)) * KP + kb + (i % (BK / 8)) * 8);
         }
     };
-
-    load_tile(0);
-    for (int t = 0; t < n_tiles; ++t) {
-        __syncthreads();
+    auto store_tile = [&](const Regs& r, int st) {
 #pragma unroll
         for (int it = 0; it < A_ITEMS; ++it) {
-            const int i = it * kProjThreads + tid;
-            *reinterpret_cast<uint4*>(&As[i / (BK / 8)][(i % (BK / 8)) * 8]) = ra[it].v;
+            const int i = it * NT + tid;
+            *reinterpret_cast<uint4*>(&As[st][i / (BK / 8)][(i % (BK / 8)) * 8]) = r.a[it];
         }
 #pragma unroll
         for (int it = 0; it < B_ITEMS; ++it) {
-            const int i = it * kProjThreads + tid;
-            const int k = i % BK, n = (i / BK) * 8;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) Bs[n + j][k] = rb[it].e[j];
+            const int i = it * NT + tid;
+            *reinterpret_cast<uint4*>(&Bs[st][i / (BK / 8)][(i % (BK / 8)) * 8]) = r.b[it];
         }
-        __syncthreads();
-        if (t + 1 < n_tiles) load_tile(t + 1);
+    };
+    auto compute = [&](int st) {
+        const int g = lane >> 5, l32 = lane & 31;
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 16) {
             uint4 a[TM], b[TN];
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
-                a[tm] = *reinterpret_cast<const uint4*>(&As[wm * (BM / 2) + tm * 32 + (lane & 31)][kk + (lane >> 5) * 8]);
+                a[tm] = *reinterpret_cast<const uint4*>(&As[st][wm * (BM / WM) + tm * 32 + l32][kk + g * 8]);
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn)
-                b[tn] = *reinterpret_cast<const uint4*>(&Bs[wn * (BN / 2) + tn * 32 + (lane & 31)][kk + (lane >> 5) * 8]);
+                b[tn] = *reinterpret_cast<const uint4*>(&Bs[st][wn * (BN / WN) + tn * 32 + l32][kk + g * 8]);
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma16<Tr>(a[tm], b[tn], acc[tm][tn]);
         }
+    };
+
+    // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
+    // an even number of tiles.  Iteration t: r holds tile t+1 -> LDS stage (t+1)&1; r is
+    // refilled with tile t+3; tile t is multiplied from stage t&1.
+    Regs r0, r1;
+    load_tile(r0, 0);
+    store_tile(r0, 0);
+    load_tile(r1, 1);
+    load_tile(r0, 2);
+    lds_barrier();
+    for (int t = 0; t < n_tiles; t += 2) {
+        store_tile(r1, 1);
+        load_tile(r1, t + 3);
+        compute(0);
+        lds_barrier();
+        store_tile(r0, 0);
+        load_tile(r0, t + 4);
+        compute(1);
+        lds_barrier();
     }
-    project_epilogue<Tr, BM, BN>(acc, row0, col0, wm, wn, lane, n_dst, d_out, bias, relu, out);
+    if (VEC && (d_out & 7) == 0) {
+        // every wave is past its last LDS read of the tiles: reuse that LDS, one band per wave
+        constexpr int BAND = 32 * (32 * TN + 8);
+        static_assert((size_t)WM * WN * BAND <= (size_t)2 * (BM + BN) * LD, "epilogue bands exceed the tile LDS");
+        typename Tr::store_t* band = reinterpret_cast<typename Tr::store_t*>(lds16) + wave * BAND;
+        project_epilogue_staged<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out,
+                                            bias, relu, out, band);
+    } else {
+        project_epilogue<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out, bias,
+                                     relu, out);
+    }
 }
 
 // ------------------------------------------------------------------ launch --
@@ -452,7 +610,8 @@ static int mean_group(int units) {   // lanes per destination row: power of two,
 
 template <typename Tr>
 static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const int32_t* idx,
-                                 int64_t n_dst, int32_t d_in, void* mean, hipStream_t s) {
+                                 int64_t n_dst, int32_t d_in, void* mean, void* zero_row,
+                                 size_t zero_bytes, hipStream_t s) {
     using T = typename Tr::store_t;
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
@@ -461,52 +620,89 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
     if (vec)
         hipLaunchKernelGGL(sage_mean_vec<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
-                           static_cast<uint4*>(mean));
+                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4));
     else
         hipLaunchKernelGGL(sage_mean_elem<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
-                           static_cast<T*>(mean));
+                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4));
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
 
+static uint32_t project_grid(int64_t n_dst, int BM, uint32_t n_tiles_n) {
+    const int64_t m_tiles = ceil_div(n_dst, BM);
+    return (uint32_t)(ceil_div(m_tiles, kXcds) * kXcds * n_tiles_n);
+}
+
 template <int BM, int BN>
-static void launch_project_f32(bool vec, dim3 grid, hipStream_t s, const void* Hsrc,
-                               const int32_t* self_idx, const void* mean, const void* Ws,
-                               const void* Wn, const void* bias, int64_t n_dst, int32_t d_in,
-                               int32_t d_out, int relu, void* out) {
+static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                                        const void* mean, const void* Ws, const void* Wn, const void* bias,
+                                        int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
+                                        void* out) {
+    const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
+    const dim3 grid(project_grid(n_dst, BM, ntn));
     auto a = static_cast<const float*>(Hsrc);
     auto m = static_cast<const float*>(mean);
     auto ws = static_cast<const float*>(Ws);
     auto wn = static_cast<const float*>(Wn);
     auto b = static_cast<const float*>(bias);
     auto o = static_cast<float*>(out);
+    auto z = static_cast<const float*>(zero);
     if (vec)
         hipLaunchKernelGGL((sage_project_f32<BM, BN, true>), grid, dim3(kProjThreads), 0, s, a, self_idx,
-                           m, ws, wn, b, n_dst, d_in, d_out, relu, o);
+                           m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
     else
         hipLaunchKernelGGL((sage_project_f32<BM, BN, false>), grid, dim3(kProjThreads), 0, s, a, self_idx,
-                           m, ws, wn, b, n_dst, d_in, d_out, relu, o);
+                           m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }
 
-template <typename Tr, int BM, int BN>
-static void launch_project_16(bool vec, dim3 grid, hipStream_t s, const void* Hsrc,
-                              const int32_t* self_idx, const void* mean, const void* Ws,
-                              const void* Wn, const void* bias, int64_t n_dst, int32_t d_in,
-                              int32_t d_out, int relu, void* out) {
+template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
+static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                                         const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
+                                         int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
+                                         void* out) {
     using T = typename Tr::store_t;
-    auto a = static_cast<const uint16_t*>(Hsrc);
-    auto m = static_cast<const uint16_t*>(mean);
-    auto ws = static_cast<const uint16_t*>(Ws);
-    auto wn = static_cast<const uint16_t*>(Wn);
-    auto b = static_cast<const T*>(bias);
-    auto o = static_cast<T*>(out);
-    if (vec)
-        hipLaunchKernelGGL((sage_project_16<Tr, BM, BN, true>), grid, dim3(kProjThreads), 0, s, a,
-                           self_idx, m, ws, wn, b, n_dst, d_in, d_out, relu, o);
-    else
-        hipLaunchKernelGGL((sage_project_16<Tr, BM, BN, false>), grid, dim3(kProjThreads), 0, s, a,
-                           self_idx, m, ws, wn, b, n_dst, d_in, d_out, relu, o);
+    constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(uint16_t);
+    auto kern = sage_project_16<Tr, BM, BN, BK, WM, WN, VEC>;
+    if (lds > 64 * 1024) {   // above the default limit the size has to be opted into
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return HOPGNN_EHIP;
+    }
+    const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
+    hipLaunchKernelGGL(kern, dim3(project_grid(n_dst, BM, ntn)), dim3(64 * WM * WN), lds, s,
+                       static_cast<const uint16_t*>(Hsrc), self_idx, static_cast<const uint16_t*>(mean), Wt,
+                       KP, static_cast<const T*>(bias), n_dst, d_in, d_out, relu, ntn,
+                       static_cast<const uint16_t*>(zero), static_cast<T*>(out));
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+template <typename Tr, int BM, int BN, int BK, int WM, int WN>
+static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                                       const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
+                                       int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
+                                       void* out) {
+    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, d_out, relu, zero, out)
+               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, d_out, relu, zero, out);
+}
+
+// Workspace: [ mean : n_dst x d_in ][ Wt : NP x KP, 2-byte types only ][ zero row ]
+struct SageWs {
+    size_t mean_bytes, wt_bytes, zero_bytes, total;
+    int32_t KP, NP;
+};
+static SageWs sage_ws_layout(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out) {
+    SageWs L{};
+    L.mean_bytes = align_up((size_t)n_dst * (size_t)d_in * dtype_size(dt), 256);
+    L.KP = (int32_t)(ceil_div(2 * (int64_t)d_in, kKPad16) * kKPad16);
+    L.NP = (int32_t)(ceil_div(d_out, 256) * 256);
+    L.wt_bytes = dt == HOPGNN_F32 ? 0 : align_up((size_t)L.KP * (size_t)L.NP * 2, 256);
+    L.zero_bytes = align_up(((size_t)2 * d_in + 64) * dtype_size(dt), 256);
+    L.total = L.mean_bytes + L.wt_bytes + L.zero_bytes;
+    return L;
 }
 
 }  // namespace hopgnn
@@ -514,9 +710,8 @@ static void launch_project_16(bool vec, dim3 grid, hipStream_t s, const void* Hs
 using namespace hopgnn;
 
 extern "C" size_t hopgnn_sage_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out) {
-    (void)d_out;
-    if (n_dst < 0 || d_in < 1) return 0;
-    return align_up((size_t)n_dst * (size_t)d_in * dtype_size(dt), 256) + 256;
+    if (n_dst < 0 || d_in < 1 || d_out < 1) return 0;
+    return sage_ws_layout(dt, n_dst, d_in, d_out).total;
 }
 
 extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
@@ -532,34 +727,44 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
         return HOPGNN_EINVAL;
     if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
-    if (ws_bytes < hopgnn_sage_fwd_ws_bytes(dt, n_dst, d_in, d_out)) return HOPGNN_ENOMEM_WS;
+    const SageWs L = sage_ws_layout(dt, n_dst, d_in, d_out);
+    if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    void* mean = ws;
+    uint16_t* Wt = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + L.mean_bytes);
+    void* zero = static_cast<char*>(ws) + L.mean_bytes + L.wt_bytes;
 
     hopgnn_status st;
-    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, ws, s);
-    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, ws, s);
-    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, ws, s);
+    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
+    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
+    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
     if (st != HOPGNN_OK) return st;
 
     const int per16 = dt == HOPGNN_F32 ? 4 : 8;
-    const bool vec = d_in % per16 == 0 && d_out % per16 == 0 && aligned(Hsrc, 16) &&
-                     aligned(W_self, 16) && aligned(W_neigh, 16);
-    // large tiles once there is enough work to fill 256 CUs twice over
-    const bool big = d_out > 64 && ceil_div(n_dst, 128) * ceil_div(d_out, 128) >= 512;
-    const int BM = big ? 128 : 64, BN = big ? 128 : 64;
-    if (ceil_div(d_out, BN) > 65535) return HOPGNN_ERANGE;
-    dim3 grid((unsigned)ceil_div(n_dst, BM), (unsigned)ceil_div(d_out, BN));
+    const int64_t work = ceil_div(n_dst, 128) * ceil_div(d_out, 128);   // 128 x 128 output tiles
     if (dt == HOPGNN_F32) {
-        if (big) launch_project_f32<128, 128>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
-        else launch_project_f32<64, 64>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
-    } else if (dt == HOPGNN_BF16) {
-        if (big) launch_project_16<TrBF16, 128, 128>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
-        else launch_project_16<TrBF16, 64, 64>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
-    } else {
-        if (big) launch_project_16<TrF16, 128, 128>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
-        else launch_project_16<TrF16, 64, 64>(vec, grid, s, Hsrc, self_idx, ws, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, out);
+        const bool vec = d_in % per16 == 0 && d_out % per16 == 0 && aligned(Hsrc, 16) &&
+                         aligned(W_self, 16) && aligned(W_neigh, 16);
+        // large tiles once there is enough work to fill 256 CUs twice over
+        if (d_out > 64 && work >= 512)
+            return launch_project_f32<128, 128>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
+        return launch_project_f32<64, 64>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
     }
+    hipLaunchKernelGGL(sage_transpose_w, dim3(L.KP / 32, L.NP / 32), dim3(256), 0, s,
+                       static_cast<const uint16_t*>(W_self), static_cast<const uint16_t*>(W_neigh), d_in, d_out,
+                       L.KP, L.NP, Wt);
     HOPGNN_LAUNCH_CHECK();
-    return HOPGNN_OK;
+    const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16);
+    const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
+    const bool big = d_out > 64 && work >= 512;
+    if (dt == HOPGNN_BF16) {
+        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+        if (big) return launch_project_16<TrBF16, 128, 128, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+        return launch_project_16<TrBF16, 64, 64, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    }
+    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    if (big) return launch_project_16<TrF16, 128, 128, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    return launch_project_16<TrF16, 64, 64, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
 }
