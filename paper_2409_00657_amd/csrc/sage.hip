@@ -62,13 +62,14 @@ union Pack16 {
 // ------------------------------------------------------------ segmented mean --
 
 constexpr int kMeanThreads = 256;
-constexpr int kMeanUnroll = 8;
+constexpr int kMeanUnroll = 4;
 
 // Vector path: d_in * sizeof(elem) is a multiple of 16.  `group` lanes (a power of
 // two <= 64) share one destination row; lane g of the group owns 16-byte word
-// g, g+group, ... of the row.  Eight neighbour rows are fetched per step with no
-// control flow between the loads (an absent entry reads row 0 and is masked out of the
-// sum), so all eight are in flight together; the sum still runs in entry order.
+// g, g+group, ... of the row.  Four neighbour rows are fetched per step; absent
+// entries (negative index) are skipped by predication, which measured faster than
+// reading a stand-in row and masking it out (whole dead micrographs are common on
+// graphs with isolated vertices).  The sum runs in entry order.
 template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
@@ -90,19 +91,17 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
             int32_t u[kMeanUnroll];
             Pack16<Tr> v[kMeanUnroll];
 #pragma unroll
-            for (int k = 0; k < kMeanUnroll; ++k) {
-                const int32_t x = idx[min(e + k, end - 1)];
-                u[k] = (e + k < end) ? x : -1;
-            }
+            for (int k = 0; k < kMeanUnroll; ++k) u[k] = (e + k < end) ? idx[e + k] : -1;
 #pragma unroll
-            for (int k = 0; k < kMeanUnroll; ++k) v[k].v = Hsrc[(int64_t)max(u[k], 0) * words_per_row + c];
+            for (int k = 0; k < kMeanUnroll; ++k)
+                if (u[k] >= 0) v[k].v = Hsrc[(int64_t)u[k] * words_per_row + c];
 #pragma unroll
-            for (int k = 0; k < kMeanUnroll; ++k) {
-                const bool on = u[k] >= 0;
+            for (int k = 0; k < kMeanUnroll; ++k)
+                if (u[k] >= 0) {
 #pragma unroll
-                for (int i = 0; i < Tr::kPer16; ++i) acc[i] += on ? Tr::to_f(v[k].e[i]) : 0.f;
-                cnt += on ? 1 : 0;
-            }
+                    for (int i = 0; i < Tr::kPer16; ++i) acc[i] += Tr::to_f(v[k].e[i]);
+                    ++cnt;
+                }
         }
         Pack16<Tr> o;
         const float fc = (float)cnt;
