@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# HBM bytes of the gather kernel per algorithmic byte, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by a plain copy kernel (profiles/gather_traffic_pmc.txt)
+GATHER_TRAFFIC_OVER_ALGORITHMIC = 1.012
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 DTYPE_NAME = {"torch.float32": "f32", "torch.bfloat16": "bf16", "torch.float16": "f16"}
 
 
@@ -125,18 +129,21 @@ def main():
             ev[1].record()
         for b in range(group):
             hp.layers(b)
+        if ev is not None:      # an empty pair: what two event markers cost with nothing between
+            ev[2].record()
+            ev[3].record()
 
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    gather_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                 for _ in range(args.steps)]
+    gather_ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(4)) for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, gather_ev[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    gather_ms = [a.elapsed_time(b) for a, b in gather_ev]
+    gather_ms = [e[0].elapsed_time(e[1]) for e in gather_ev]
+    empty_ms = [e[2].elapsed_time(e[3]) for e in gather_ev]
 
     # untimed, instrumented replay of the same steps: U per step and a per-stage breakdown
     stage = {"sample": 0.0, "pregather": 0.0, "gather": 0.0}
@@ -185,8 +192,30 @@ def main():
     # algorithmic bytes of one gather launch: every unique row read once and written once,
     # plus its 4-byte index
     gather_bytes = U_avg * (2 * row_bytes + 4)
-    gather_ms_avg = sum(gather_ms) / len(gather_ms)
+    # a marker pair with nothing between reads ~5 us; the kernel's own duration is the pair
+    # around it minus that (rocprofv3's per-kernel average is the cross-check, see profiles/)
+    gather_ms_raw = sum(gather_ms) / len(gather_ms)
+    empty_ms_avg = sum(empty_ms) / len(empty_ms)
+    gather_ms_avg = max(gather_ms_raw - empty_ms_avg, 1e-6)
     gather_gbps = gather_bytes / (gather_ms_avg * 1e-3) / 1e9
+    # per-stage algorithmic work (whole entry points, from the instrumented replay)
+    es = X.element_size()
+    valid_avg = valid_sum / n_replay
+    stage_work = {"gather": {"bound": "hbm", "bytes": gather_bytes}}
+    stage_work["pregather"] = {"bound": "hbm", "bytes": group * sh.n_slots * 8 + 4 * U_avg}
+    din = X.shape[1]
+    for k in range(1, sh.n_layers + 1):
+        n_dst, nnz = sh.n_dst(k), sh.nnz(k)
+        stage_work["sage_l%d" % k] = {
+            "bound": "hbm+mfma",
+            "bytes": group * ((nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es),
+            "flops": group * 2.0 * n_dst * 2 * din * cfg.hidden}
+        din = cfg.hidden
+    for name, w in stage_work.items():
+        t = stage[name] * 1e-3
+        w["GBps"] = round(w["bytes"] / t / 1e9, 1)
+        if "flops" in w:
+            w["TFLOPs"] = round(w["flops"] / t / 1e12, 2)
 
     out = {
         "metric": "micrograph batches/s",
@@ -205,10 +234,13 @@ def main():
         "unique_over_valid_slots": U_sum / max(valid_sum, 1),
         "valid_slot_fraction": valid_sum / (n_replay * group * sh.n_slots),
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
+        "stage_work": stage_work,
         "roofline": {"kernel": "gather_rows", "bound": "hbm", "achieved": gather_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
-                     "traffic": None, "algorithmic_bytes_per_launch": gather_bytes,
-                     "avg_launch_ms": gather_ms_avg},
+                     "traffic": gather_bytes * GATHER_TRAFFIC_OVER_ALGORITHMIC,
+                     "algorithmic_bytes_per_launch": gather_bytes,
+                     "avg_launch_ms": gather_ms_avg, "event_pair_ms": gather_ms_raw,
+                     "empty_event_pair_ms": empty_ms_avg},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, g, X, W, group, args.cpu_seconds)

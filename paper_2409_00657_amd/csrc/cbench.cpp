@@ -1,8 +1,12 @@
 // cbench: a torch-free driver of the C ABI for timing one entry point under rocprofv3.
 //
 //   cbench sage   <n_src> <n_dst> <d_in> <d_out> <f32|bf16|f16> <fanout> <iters>
-//   cbench gather <n_rows> <n_uniq> <dim> <f32|bf16|f16> <iters>
+//   cbench gather <n_rows> <n_uniq> <dim> <f32|bf16|f16> <iters> [capacity]
+//          with a capacity, U is passed on the device and the launch is sized for the
+//          capacity, as in a batch where the pre-gather count never visits the host
 //   cbench pregather <n_ids> <n_vertices> <iters>
+//   cbench copy <bytes> <iters>      plain 128-bit copy kernel of known size, to calibrate
+//                                    the profiler's FETCH_SIZE / WRITE_SIZE counters
 //
 // Inputs are pseudo-random with the right shapes; results are not checked here (the
 // parity tests do that).  Prints the mean time per call measured with HIP events.
@@ -25,6 +29,11 @@
             exit(1);                                                               \
         }                                                                          \
     } while (0)
+
+__global__ void __launch_bounds__(256) plain_copy(const uint4* __restrict__ a, uint4* __restrict__ b, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) b[i] = a[i];
+}
 
 static uint64_t rng_state = 0x1234567;
 static uint64_t rnd() {
@@ -131,9 +140,18 @@ int main(int argc, char** argv) {
             const int64_t lo = i * n_rows / n_uniq, hi = (i + 1) * n_rows / n_uniq;
             uniq[i] = (int32_t)(lo + (int64_t)(rnd() % (uint64_t)(hi > lo ? hi - lo : 1)));
         }
+        const int64_t cap = argc >= 8 ? atoll(argv[7]) : 0;
+        if (cap > 0) uniq.resize(cap, 0);
         auto d_uniq = upload(uniq);
+        int64_t* d_count = nullptr;
+        if (cap > 0) {
+            CK(hipFree(Xu));
+            CK(hipMalloc(&Xu, (size_t)cap * dim * es));
+            CK(hipMalloc(&d_count, 8));
+            CK(hipMemcpy(d_count, &n_uniq, 8, hipMemcpyHostToDevice));
+        }
         time_it("hopgnn_gather", iters, [&] {
-            hopgnn_status st = hopgnn_gather(X, dt, n_rows, dim, dim, d_uniq, n_uniq, nullptr, Xu, nullptr);
+            hopgnn_status st = hopgnn_gather(X, dt, n_rows, dim, dim, d_uniq, cap > 0 ? cap : n_uniq, d_count, Xu, nullptr);
             if (st != HOPGNN_OK) { fprintf(stderr, "gather: %s\n", hopgnn_status_str(st)); exit(1); }
         });
         printf("algorithmic bytes per call: %.1f MB\n", (double)n_uniq * (2.0 * dim * es + 4) / 1e6);
@@ -158,6 +176,19 @@ int main(int argc, char** argv) {
             hopgnn_status st = hopgnn_pregather(d_ids, n_ids, n_vertices, 0, uniq, n_uniq, remap, ws, wsb, nullptr);
             if (st != HOPGNN_OK) { fprintf(stderr, "pregather: %s\n", hopgnn_status_str(st)); exit(1); }
         });
+    } else if (mode == "copy" && argc >= 4) {
+        const int64_t bytes = atoll(argv[2]) / 16 * 16;
+        const int iters = atoi(argv[3]);
+        void *a, *b;
+        CK(hipMalloc(&a, bytes));
+        CK(hipMalloc(&b, bytes));
+        CK(hipMemset(a, 1, bytes));
+        const int64_t n = bytes / 16;
+        time_it("plain_copy", iters, [&] {
+            hipLaunchKernelGGL(plain_copy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, 0,
+                               static_cast<const uint4*>(a), static_cast<uint4*>(b), n);
+        });
+        printf("bytes read = bytes written = %lld\n", (long long)bytes);
     } else {
         fprintf(stderr, "see the header of cbench.cpp for usage\n");
         return 1;
