@@ -44,7 +44,7 @@ typedef enum { HOPGNN_F32 = 0, HOPGNN_BF16 = 1, HOPGNN_F16 = 2 } hopgnn_dtype;
 
 /* How hopgnn_pregather builds the set. Both give identical results. */
 typedef enum {
-    HOPGNN_PG_AUTO = 0,   /* pick by n_ids and n_vertices                               */
+    HOPGNN_PG_AUTO = 0,   /* bitmap unless n_vertices > 256 * max(n_ids, 2^18)          */
     HOPGNN_PG_BITMAP = 1, /* presence bitmap over the vertex range + popcount ranks     */
     HOPGNN_PG_RADIX = 2   /* LSD radix sort of (id, slot) pairs, head flags, scan       */
 } hopgnn_pg_algo;

@@ -4,7 +4,7 @@
 //   cbench gather <n_rows> <n_uniq> <dim> <f32|bf16|f16> <iters> [capacity]
 //          with a capacity, U is passed on the device and the launch is sized for the
 //          capacity, as in a batch where the pre-gather count never visits the host
-//   cbench pregather <n_ids> <n_vertices> <iters>
+//   cbench pregather <n_ids> <n_vertices> <iters> [algo: 0 auto, 1 bitmap, 2 radix]
 //   cbench copy <bytes> <iters>      plain 128-bit copy kernel of known size, to calibrate
 //                                    the profiler's FETCH_SIZE / WRITE_SIZE counters
 //
@@ -158,6 +158,7 @@ int main(int argc, char** argv) {
     } else if (mode == "pregather" && argc >= 5) {
         const int64_t n_ids = atoll(argv[2]), n_vertices = atoll(argv[3]);
         const int iters = atoi(argv[4]);
+        const int algo = argc >= 6 ? atoi(argv[5]) : 0;
         std::vector<int32_t> ids(n_ids);
         for (auto& x : ids) {   // skewed towards low IDs like a power-law graph
             const double u = (double)(rnd() >> 11) / 9007199254740992.0;
@@ -167,13 +168,13 @@ int main(int argc, char** argv) {
         int32_t *uniq, *remap;
         int64_t* n_uniq;
         void* ws;
-        const size_t wsb = hopgnn_pregather_ws_bytes(n_ids, n_vertices, 0);
+        const size_t wsb = hopgnn_pregather_ws_bytes(n_ids, n_vertices, algo);
         CK(hipMalloc(&uniq, (size_t)n_ids * 4));
         CK(hipMalloc(&remap, (size_t)n_ids * 4));
         CK(hipMalloc(&n_uniq, 8));
         CK(hipMalloc(&ws, wsb));
         time_it("hopgnn_pregather", iters, [&] {
-            hopgnn_status st = hopgnn_pregather(d_ids, n_ids, n_vertices, 0, uniq, n_uniq, remap, ws, wsb, nullptr);
+            hopgnn_status st = hopgnn_pregather(d_ids, n_ids, n_vertices, algo, uniq, n_uniq, remap, ws, wsb, nullptr);
             if (st != HOPGNN_OK) { fprintf(stderr, "pregather: %s\n", hopgnn_status_str(st)); exit(1); }
         });
     } else if (mode == "copy" && argc >= 4) {

@@ -122,28 +122,33 @@ bitmap_pack_count(const uint4* __restrict__ present16, uint4* __restrict__ bits4
     // A wave covers 8 KiB of presence bytes = 256 bitmap words.  Load k of lane l is the
     // 16-byte piece k*64+l of that range (fully coalesced) = one half of word k*32 + l/2;
     // lanes 2j and 2j+1 exchange halves and the even lane stores the word.
+    // A workgroup takes chunks blockIdx.x, blockIdx.x + gridDim.x, ... and draws ONE ticket at the
+    // end (one ticket per chunk serialised thousands of same-address atomics on large graphs).
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t wave_id = ((int64_t)blockIdx.x * kPgThreads + threadIdx.x) / kWave;
-    const uint4* src = present16 + wave_id * (kWave * 8);
-    uint32_t* dst = reinterpret_cast<uint32_t*>(bits4) + wave_id * (kWave * kWordsPerThread);
-    uint4 q[8];
+    for (uint32_t chunk = blockIdx.x; chunk < n_blocks; chunk += gridDim.x) {
+        const int64_t wave_id = ((int64_t)chunk * kPgThreads + threadIdx.x) / kWave;
+        const uint4* src = present16 + wave_id * (kWave * 8);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(bits4) + wave_id * (kWave * kWordsPerThread);
+        uint4 q[8];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) q[k] = src[k * kWave + lane];
-    uint32_t mine = 0;
+        for (int k = 0; k < 8; ++k) q[k] = src[k * kWave + lane];
+        uint32_t mine = 0;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const uint32_t half = pack16(q[k]);
-        mine += __popc(half);
-        const uint32_t other = __shfl_xor(half, 1, kWave);
-        if ((lane & 1) == 0) dst[k * 32 + (lane >> 1)] = half | (other << 16);
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t half = pack16(q[k]);
+            mine += __popc(half);
+            const uint32_t other = __shfl_xor(half, 1, kWave);
+            if ((lane & 1) == 0) dst[k * 32 + (lane >> 1)] = half | (other << 16);
+        }
+        uint32_t total;
+        (void)block_exclusive_scan(mine, lds4, total);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&block_sum[chunk], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    uint32_t total;
-    (void)block_exclusive_scan(mine, lds4, total);
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&block_sum[blockIdx.x], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __threadfence();
         const uint32_t done = atomicAdd(ticket, 1u);
-        is_last = (done == n_blocks - 1);
+        is_last = (done == gridDim.x - 1);
     }
     __syncthreads();
     if (!is_last) return;
@@ -224,7 +229,7 @@ static hopgnn_status pregather_bitmap(const int32_t* ids, int64_t n_ids, int64_t
                            ids, n_ids, L.present);
         HOPGNN_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(bitmap_pack_count, dim3((unsigned)L.n_blocks), dim3(kPgThreads), 0, s,
+    hipLaunchKernelGGL(bitmap_pack_count, dim3((unsigned)(L.n_blocks < 1024 ? L.n_blocks : 1024)), dim3(kPgThreads), 0, s,
                        reinterpret_cast<const uint4*>(L.present), reinterpret_cast<uint4*>(L.bits),
                        L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
     HOPGNN_LAUNCH_CHECK();
@@ -239,13 +244,340 @@ static hopgnn_status pregather_bitmap(const int32_t* ids, int64_t n_ids, int64_t
     return HOPGNN_OK;
 }
 
+// ------------------------------------------------------------------ radix path --
+//
+// LSD radix sort of (key, slot) pairs, 8 bits per pass, then head flags + prefix sum:
+//     key = id for valid slots, 2^bits for invalid ones (bits = width of n_vertices-1), so
+//           invalid slots sort behind every vertex and ceil((bits+1)/8) passes suffice;
+//     a pass = per-tile digit histogram -> exclusive scan over (digit, tile) -> stable
+//           scatter.  Ranking inside a tile is by wavefront ballots (the lanes holding the
+//           same digit are found with 8 ballots, one per digit bit), and the tile is first
+//           put in digit order in LDS so that runs of equal digits leave as coalesced writes;
+//     uniq = first key of every run of equal valid keys, remap[slot] = number of runs before it.
+// Identical output to the bitmap path (ascending uniq, same remap).  It moves 16 bytes per
+// slot per pass, so it only pays when n_vertices is huge next to the number of slots.
+
+constexpr int kRxThreads = 256;
+constexpr int kRxIpt = 8;                                  // items per thread
+constexpr int kRxTile = kRxThreads * kRxIpt;               // 2048 items per workgroup
+constexpr int kRxWaves = kRxThreads / kWave;
+
+struct RadixWs {
+    uint32_t *keys[2], *vals[2];   // ping-pong pair buffers [n]
+    uint32_t* flags;               // [n] head flags, then their exclusive prefix
+    uint32_t* hist;                // [256][n_tiles], scanned in place
+    uint32_t* sums;                // chunk sums of the scans
+    uint32_t* ticket;
+    size_t bytes;
+    int64_t n_tiles, scan_len_max;
+};
+
+static RadixWs radix_layout(void* ws, int64_t n_ids) {
+    RadixWs L{};
+    const int64_t n = n_ids > 0 ? n_ids : 1;
+    L.n_tiles = ceil_div(n, kRxTile);
+    const int64_t hist_len = 256 * L.n_tiles;
+    L.scan_len_max = hist_len > n ? hist_len : n;
+    char* p = static_cast<char*>(ws);
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        char* q = p + o;
+        o += align_up(bytes, 256);
+        return q;
+    };
+    for (int i = 0; i < 2; ++i) L.keys[i] = reinterpret_cast<uint32_t*>(take((size_t)n * 4));
+    for (int i = 0; i < 2; ++i) L.vals[i] = reinterpret_cast<uint32_t*>(take((size_t)n * 4));
+    L.flags = reinterpret_cast<uint32_t*>(take((size_t)n * 4));
+    L.hist = reinterpret_cast<uint32_t*>(take((size_t)hist_len * 4));
+    L.sums = reinterpret_cast<uint32_t*>(take((size_t)ceil_div(L.scan_len_max, kWordsPerBlock) * 4));
+    L.ticket = reinterpret_cast<uint32_t*>(take(256));
+    L.bytes = o;
+    return L;
+}
+
+__device__ __forceinline__ uint32_t radix_key(int32_t id, uint32_t invalid_key) {
+    return id >= 0 ? (uint32_t)id : invalid_key;
+}
+
+// Item order inside a tile: wave w, round j, lane l  <->  index base + w*512 + j*64 + l,
+// i.e. ascending index, which is what makes the ballot ranking stable.
+template <bool FIRST>
+__global__ void __launch_bounds__(kRxThreads)
+radix_histogram(const uint32_t* __restrict__ keys_in, int64_t n, int shift, uint32_t invalid_key,
+                uint32_t* __restrict__ hist, uint32_t n_tiles) {
+    __shared__ uint32_t counts[256];
+    counts[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kRxTile;
+#pragma unroll
+    for (int j = 0; j < kRxIpt; ++j) {
+        const int64_t i = base + j * kRxThreads + threadIdx.x;
+        if (i < n) {
+            const uint32_t key = FIRST ? radix_key((int32_t)keys_in[i], invalid_key) : keys_in[i];
+            atomicAdd(&counts[(key >> shift) & 255u], 1u);
+        }
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * n_tiles + blockIdx.x] = counts[threadIdx.x];
+}
+
+template <bool FIRST>
+__global__ void __launch_bounds__(kRxThreads)
+radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__ vals_in, int64_t n,
+              int shift, uint32_t invalid_key, const uint32_t* __restrict__ hist, uint32_t n_tiles,
+              uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+    __shared__ uint32_t wave_count[kRxWaves][256];   // per wave, per digit: count, then start inside the digit
+    __shared__ uint32_t digit_start[256];            // start of the digit's run in the tile
+    __shared__ uint32_t lds4[kRxWaves];
+    __shared__ uint32_t skey[kRxTile], sval[kRxTile];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int64_t base = (int64_t)blockIdx.x * kRxTile;
+    const int64_t left = n - base;
+    const uint32_t count = (uint32_t)(left < kRxTile ? left : kRxTile);
+#pragma unroll
+    for (int w = 0; w < kRxWaves; ++w) wave_count[w][tid] = 0;
+    __syncthreads();
+
+    uint32_t key[kRxIpt], val[kRxIpt], rank[kRxIpt];
+    const uint64_t below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < kRxIpt; ++j) {
+        const uint32_t local = wave * (kWave * kRxIpt) + j * kWave + lane;
+        const bool on = local < count;
+        key[j] = 0;
+        val[j] = 0;
+        if (on) {
+            const int64_t i = base + local;
+            key[j] = FIRST ? radix_key((int32_t)keys_in[i], invalid_key) : keys_in[i];
+            val[j] = FIRST ? (uint32_t)i : vals_in[i];
+        }
+        const uint32_t d = (key[j] >> shift) & 255u;
+        // lanes of this wave that are active and hold the same digit
+        uint64_t peers = __ballot(on);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t vote = __ballot(on && ((d >> b) & 1u));
+            peers &= ((d >> b) & 1u) ? vote : ~vote;
+        }
+        rank[j] = 0;
+        if (on) {
+            const int leader = __ffsll((long long)peers) - 1;
+            uint32_t prev = 0;
+            if (lane == leader) {
+                prev = wave_count[wave][d];
+                wave_count[wave][d] = prev + (uint32_t)__popcll(peers);
+            }
+            prev = __shfl(prev, leader, kWave);
+            rank[j] = prev + (uint32_t)__popcll(peers & below);
+        }
+        // the next round reads the counters this round's leaders wrote (same wave: LDS ops of a
+        // wave complete in order, no barrier needed)
+    }
+    __syncthreads();
+    {   // thread d: waves in order -> start of every wave inside digit d, and the digit's total
+        uint32_t off = 0;
+#pragma unroll
+        for (int w = 0; w < kRxWaves; ++w) {
+            const uint32_t t = wave_count[w][tid];
+            wave_count[w][tid] = off;
+            off += t;
+        }
+        uint32_t total;
+        digit_start[tid] = block_exclusive_scan(off, lds4, total);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kRxIpt; ++j) {
+        const uint32_t local = wave * (kWave * kRxIpt) + j * kWave + lane;
+        if (local < count) {
+            const uint32_t d = (key[j] >> shift) & 255u;
+            const uint32_t p = digit_start[d] + wave_count[wave][d] + rank[j];
+            skey[p] = key[j];
+            sval[p] = val[j];
+        }
+    }
+    __syncthreads();
+    for (uint32_t p = tid; p < count; p += kRxThreads) {
+        const uint32_t k = skey[p];
+        const uint32_t d = (k >> shift) & 255u;
+        const int64_t g = (int64_t)hist[(int64_t)d * n_tiles + blockIdx.x] + (p - digit_start[d]);
+        keys_out[g] = k;
+        vals_out[g] = sval[p];
+    }
+}
+
+// In-place exclusive prefix sum of a[0..len): chunk sums, the last workgroup scans them
+// (and may publish the grand total), then every chunk is rescanned with its base.
+__global__ void __launch_bounds__(kPgThreads)
+scan_chunk_sums(const uint32_t* __restrict__ a, int64_t len, uint32_t* __restrict__ sums, uint32_t n_chunks,
+                uint32_t* ticket, int64_t* total_out) {
+    __shared__ uint32_t lds4[kPgThreads / kWave];
+    __shared__ bool is_last;
+    for (uint32_t chunk = blockIdx.x; chunk < n_chunks; chunk += gridDim.x) {
+        const int64_t i0 = ((int64_t)chunk * kPgThreads + threadIdx.x) * kWordsPerThread;
+        uint32_t s = 0;
+#pragma unroll
+        for (int k = 0; k < kWordsPerThread; ++k)
+            if (i0 + k < len) s += a[i0 + k];
+        uint32_t total;
+        (void)block_exclusive_scan(s, lds4, total);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&sums[chunk], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (threadIdx.x == 0) {
+        __threadfence();
+        is_last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    uint32_t carry = 0;
+    for (uint32_t b0 = 0; b0 < n_chunks; b0 += kPgThreads) {
+        const uint32_t b = b0 + threadIdx.x;
+        const uint32_t x = b < n_chunks ? __hip_atomic_load(&sums[b], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        uint32_t tot;
+        const uint32_t ex = block_exclusive_scan(x, lds4, tot);
+        if (b < n_chunks) sums[b] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) {
+        *ticket = 0u;   // ready for the next scan on this stream
+        if (total_out != nullptr) *total_out = (int64_t)carry;
+    }
+}
+
+__global__ void __launch_bounds__(kPgThreads)
+scan_apply(uint32_t* __restrict__ a, int64_t len, const uint32_t* __restrict__ sums) {
+    __shared__ uint32_t lds4[kPgThreads / kWave];
+    const int64_t i0 = ((int64_t)blockIdx.x * kPgThreads + threadIdx.x) * kWordsPerThread;
+    uint32_t v[kWordsPerThread];
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kWordsPerThread; ++k) {
+        v[k] = i0 + k < len ? a[i0 + k] : 0u;
+        s += v[k];
+    }
+    uint32_t total;
+    uint32_t run = sums[blockIdx.x] + block_exclusive_scan(s, lds4, total);
+#pragma unroll
+    for (int k = 0; k < kWordsPerThread; ++k) {
+        if (i0 + k < len) a[i0 + k] = run;
+        run += v[k];
+    }
+}
+
+__global__ void __launch_bounds__(kPgThreads)
+radix_head_flags(const uint32_t* __restrict__ keys, int64_t n, uint32_t invalid_key, uint32_t* __restrict__ flags,
+                 uint32_t* ticket) {
+    const int64_t i = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
+    if (i == 0) *ticket = 0u;
+    if (i < n) {
+        const uint32_t k = keys[i];
+        flags[i] = (k < invalid_key && (i == 0 || keys[i - 1] != k)) ? 1u : 0u;
+    }
+}
+
+__global__ void __launch_bounds__(kPgThreads)
+radix_emit(const uint32_t* __restrict__ keys, const uint32_t* __restrict__ vals, const uint32_t* __restrict__ excl,
+           int64_t n, uint32_t invalid_key, int32_t* __restrict__ uniq, int32_t* __restrict__ remap) {
+    const int64_t i = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t k = keys[i];
+    if (k >= invalid_key) {
+        remap[vals[i]] = -1;
+        return;
+    }
+    const bool head = i == 0 || keys[i - 1] != k;
+    const uint32_t e = excl[i];                 // heads strictly before i
+    if (head) uniq[e] = (int32_t)k;
+    remap[vals[i]] = (int32_t)(head ? e : e - 1);
+}
+
+__global__ void set_count_zero(int64_t* n_uniq) { *n_uniq = 0; }
+
+static hopgnn_status scan_in_place(uint32_t* a, int64_t len, const RadixWs& L, int64_t* total_out, hipStream_t s) {
+    const int64_t n_chunks = ceil_div(len, kWordsPerBlock);
+    hipLaunchKernelGGL(scan_chunk_sums, dim3((unsigned)(n_chunks < 1024 ? n_chunks : 1024)), dim3(kPgThreads), 0, s,
+                       a, len, L.sums, (uint32_t)n_chunks, L.ticket, total_out);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_chunks), dim3(kPgThreads), 0, s, a, len, L.sums);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+static hopgnn_status pregather_radix(const int32_t* ids, int64_t n_ids, int64_t n_vertices, int32_t* uniq,
+                                     int64_t* n_uniq_dev, int32_t* remap, void* ws, size_t ws_bytes,
+                                     hipStream_t s) {
+    const RadixWs L = radix_layout(ws, n_ids);
+    if (ws_bytes < L.bytes) return HOPGNN_ENOMEM_WS;
+    if (n_ids == 0) {
+        hipLaunchKernelGGL(set_count_zero, dim3(1), dim3(1), 0, s, n_uniq_dev);
+        HOPGNN_LAUNCH_CHECK();
+        return HOPGNN_OK;
+    }
+    int bits = 0;
+    while (bits < 31 && ((int64_t)1 << bits) < n_vertices) ++bits;   // ids < 2^bits
+    const uint32_t invalid_key = 1u << bits;
+    const int passes = (bits + 1 + 7) / 8;
+    const uint32_t n_tiles = (uint32_t)L.n_tiles;
+    const int64_t n_blocks_1d = ceil_div(n_ids, kPgThreads);
+
+    // the ticket is zeroed by radix_head_flags' counterpart below on every call; the first scan of
+    // this call needs it zero too
+    hipLaunchKernelGGL(set_count_zero, dim3(1), dim3(1), 0, s, reinterpret_cast<int64_t*>(L.ticket));
+    HOPGNN_LAUNCH_CHECK();
+    int cur = 0;
+    for (int p = 0; p < passes; ++p) {
+        const int shift = 8 * p;
+        const uint32_t* kin = p == 0 ? reinterpret_cast<const uint32_t*>(ids) : L.keys[cur];
+        const uint32_t* vin = p == 0 ? nullptr : L.vals[cur];
+        if (p == 0)
+            hipLaunchKernelGGL(radix_histogram<true>, dim3(n_tiles), dim3(kRxThreads), 0, s, kin, n_ids, shift,
+                               invalid_key, L.hist, n_tiles);
+        else
+            hipLaunchKernelGGL(radix_histogram<false>, dim3(n_tiles), dim3(kRxThreads), 0, s, kin, n_ids, shift,
+                               invalid_key, L.hist, n_tiles);
+        HOPGNN_LAUNCH_CHECK();
+        hopgnn_status st = scan_in_place(L.hist, 256 * (int64_t)n_tiles, L, nullptr, s);
+        if (st != HOPGNN_OK) return st;
+        const int nxt = p == 0 ? 0 : cur ^ 1;
+        if (p == 0)
+            hipLaunchKernelGGL(radix_scatter<true>, dim3(n_tiles), dim3(kRxThreads), 0, s, kin, vin, n_ids, shift,
+                               invalid_key, L.hist, n_tiles, L.keys[nxt], L.vals[nxt]);
+        else
+            hipLaunchKernelGGL(radix_scatter<false>, dim3(n_tiles), dim3(kRxThreads), 0, s, kin, vin, n_ids, shift,
+                               invalid_key, L.hist, n_tiles, L.keys[nxt], L.vals[nxt]);
+        HOPGNN_LAUNCH_CHECK();
+        cur = nxt;
+    }
+    hipLaunchKernelGGL(radix_head_flags, dim3((unsigned)n_blocks_1d), dim3(kPgThreads), 0, s, L.keys[cur], n_ids,
+                       invalid_key, L.flags, L.ticket);
+    HOPGNN_LAUNCH_CHECK();
+    hopgnn_status st = scan_in_place(L.flags, n_ids, L, n_uniq_dev, s);
+    if (st != HOPGNN_OK) return st;
+    hipLaunchKernelGGL(radix_emit, dim3((unsigned)n_blocks_1d), dim3(kPgThreads), 0, s, L.keys[cur], L.vals[cur],
+                       L.flags, n_ids, invalid_key, uniq, remap);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
 }  // namespace hopgnn
 
 using namespace hopgnn;
 
+// The bitmap path costs ~1 us per million vertices (it clears, packs and ranks the whole vertex
+// range), the radix path ~100 us of launches plus ~50 us per million slots.  Measured on MI355X the
+// bitmap wins on every shape up to 176 vertices per slot (0.57 M slots over 100 M vertices: 106 vs
+// 129 us); AUTO switches to the sort beyond 256 vertices per slot.
+static int32_t pick_algo(int32_t algo, int64_t n_ids, int64_t n_vertices) {
+    if (algo != HOPGNN_PG_AUTO) return algo;
+    const int64_t slots = n_ids > (1 << 18) ? n_ids : (1 << 18);
+    return n_vertices > 256 * slots ? HOPGNN_PG_RADIX : HOPGNN_PG_BITMAP;
+}
+
 extern "C" size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo) {
     if (n_ids < 0 || n_vertices < 0) return 0;
-    (void)algo;
+    if (pick_algo(algo, n_ids, n_vertices) == HOPGNN_PG_RADIX) return radix_layout(nullptr, n_ids).bytes;
     return bitmap_layout(nullptr, n_vertices).bytes;
 }
 
@@ -257,6 +589,9 @@ extern "C" hopgnn_status hopgnn_pregather(const int32_t* ids, int64_t n_ids, int
     if (algo != HOPGNN_PG_AUTO && algo != HOPGNN_PG_BITMAP && algo != HOPGNN_PG_RADIX) return HOPGNN_EINVAL;
     if (n_ids >= ((int64_t)1 << 31) || n_vertices > ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
+    if (pick_algo(algo, n_ids, n_vertices) == HOPGNN_PG_RADIX)
+        return pregather_radix(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, ws_bytes,
+                               static_cast<hipStream_t>(stream));
     return pregather_bitmap(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
 }

@@ -124,8 +124,8 @@ def test_pregather_hub_heavy_and_repeatable(hb, orc):
     N = 1 << 22
     ids = np.minimum((N * rng.random(500000) ** 6).astype(np.int64), N - 1).astype(np.int32)
     ref_uniq, ref_remap = orc.pregather(ids)
-    for _ in range(2):
-        uniq, remap, U = _gpu_pregather(hb, ids, N)
+    for algo in (1, 1, 2, 2):
+        uniq, remap, U = _gpu_pregather(hb, ids, N, algo)
         np.testing.assert_array_equal(uniq, ref_uniq)
         np.testing.assert_array_equal(remap, ref_remap)
 
@@ -174,7 +174,8 @@ def _rand_csr(rng, n_dst, n_src, max_len, p_invalid=0.15):
 @pytest.mark.parametrize("shape", [(700, 333, 32, 32, 6), (3000, 1111, 128, 128, 12),
                                    (5000, 777, 100, 256, 16), (900, 300, 256, 256, 30),
                                    (400, 129, 20, 12, 5), (300, 65, 7, 5, 4),
-                                   (2000, 40000, 64, 128, 3)])
+                                   (2000, 40000, 64, 128, 3), (1500, 600, 512, 64, 8),
+                                   (900, 4000, 136, 520, 7)])
 def test_sage_fwd_within_tolerance(hb, orc, dtype, shape):
     n_src, n_dst, d_in, d_out, max_len = shape
     rng = np.random.default_rng(n_src + d_in)
