@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload shape 1..5")
     ap.add_argument("--group", type=int, default=0, help="batches per pre-gather (0: the shape's default)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams (each with its own buffers) that consecutive steps alternate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -110,7 +112,10 @@ def main():
     g = cfg.make_graph(device=dev)
     X = cfg.make_features(device=dev)
     W = cfg.make_weights(device=dev)
-    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group)
+    n_streams = max(1, args.streams)
+    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group) for _ in range(n_streams)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]      # default priority
+    hp = hps[0]
     sh = hp.shape
     n_total = args.warmup + args.steps
     seeds = [[synth.seeds(cfg.n_vertices, cfg.batch, i * group + b, device=dev) for b in range(group)]
@@ -119,19 +124,22 @@ def main():
     torch.cuda.synchronize()
 
     def step(i, ev=None):
+        """One whole step on stream i % n_streams (consecutive steps overlap on the GPU)."""
+        h, stream = hps[i % n_streams], streams[i % n_streams]
+        st = stream.cuda_stream
         for b in range(group):
-            hp.sample(b, seeds[i][b], keys[i][b])
-        hp.pregather()
+            h.sample(b, seeds[i][b], keys[i][b], st)
+        h.pregather(st)
         if ev is not None:
-            ev[0].record()
-        hp.gather()
+            ev[0].record(stream)
+        h.gather(st)
         if ev is not None:
-            ev[1].record()
+            ev[1].record(stream)
         for b in range(group):
-            hp.layers(b)
+            h.layers(b, st)
         if ev is not None:      # an empty pair: what two event markers cost with nothing between
-            ev[2].record()
-            ev[3].record()
+            ev[2].record(stream)
+            ev[3].record(stream)
 
     for i in range(args.warmup):
         step(i)
@@ -145,23 +153,24 @@ def main():
     gather_ms = [e[0].elapsed_time(e[1]) for e in gather_ev]
     empty_ms = [e[2].elapsed_time(e[3]) for e in gather_ev]
 
-    # untimed, instrumented replay of the same steps: U per step and a per-stage breakdown
+    # untimed, instrumented replay of the same steps on one stream: U per step and a per-stage breakdown
     stage = {"sample": 0.0, "pregather": 0.0, "gather": 0.0}
     for k in range(1, sh.n_layers + 1):
         stage["sage_l%d" % k] = 0.0
-    U_sum, valid_sum, gbytes = 0, 0, 0.0
+    U_sum, valid_sum = 0, 0
     E = lambda: torch.cuda.Event(enable_timing=True)
     n_replay = min(args.steps, 50)
+    st0 = torch.cuda.current_stream().cuda_stream
     for i in range(n_replay):
         j = args.warmup + i
         e = [E() for _ in range(4)]
         e[0].record()
         for b in range(group):
-            hp.sample(b, seeds[j][b], keys[j][b])
+            hp.sample(b, seeds[j][b], keys[j][b], st0)
         e[1].record()
-        hp.pregather()
+        hp.pregather(st0)
         e[2].record()
-        hp.gather()
+        hp.gather(st0)
         e[3].record()
         torch.cuda.synchronize()
         stage["sample"] += e[0].elapsed_time(e[1])
@@ -169,23 +178,14 @@ def main():
         stage["gather"] += e[2].elapsed_time(e[3])
         U_sum += int(hp.n_uniq.item())
         valid_sum += int((hp.ids >= 0).sum().item())
-        # layers, one event pair per layer, summed over the group's batches
-        T, B, L = sh.n_slots, sh.n_seeds, sh.n_layers
-        for b in range(group):
-            remap = hp.remap[b * T:(b + 1) * T]
-            src, n_src = hp.Xu, hp.cap
-            for k in range(1, L + 1):
-                n_dst, nnz = sh.n_dst(k), sh.nnz(k)
-                Ws, Wn, bias = W[k - 1]
-                self_idx, idx = (remap[:n_dst], remap[B:B + nnz]) if k == 1 else (None, hp.slot_idx[b][:nnz])
+        for b in range(group):      # one event pair per layer, summed over the group's batches
+            for k in range(1, sh.n_layers + 1):
                 a, c = E(), E()
                 a.record()
-                hb.hopgnn_sage_fwd(src, n_src, self_idx, hp.indptr[:n_dst + 1], idx, n_dst, Ws, Wn, bias,
-                                   k < L, hp.H[k - 1], hp.sage_ws)
+                hp.layer(b, k, st0)
                 c.record()
                 torch.cuda.synchronize()
                 stage["sage_l%d" % k] += a.elapsed_time(c)
-                src, n_src = hp.H[k - 1], n_dst
     stage = {k: v / n_replay for k, v in stage.items()}
     U_avg = U_sum / n_replay
     row_bytes = X.shape[1] * X.element_size()
@@ -227,7 +227,8 @@ def main():
         "dtype": DTYPE_NAME[str(X.dtype)], "data": "synthetic",
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges,
                    "feature_dim": cfg.d, "batch": cfg.batch, "fanouts": cfg.fanouts,
-                   "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots},
+                   "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots,
+                   "streams": n_streams},
         "gather_GBps": gather_gbps,
         "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
         "unique_rows_per_step": U_avg,

@@ -246,14 +246,15 @@ __device__ __forceinline__ void project_epilogue_staged(floatx16 (&acc)[TM][TN],
 // k values 4g..4g+3 of an 8-wide K block and the four MFMAs of the block pair A's i-th
 // value with B row 4g+i, which only permutes the order in which k is summed.
 // B is [BK][BN+4], read as 32 consecutive floats per half wave.
-template <int BM, int BN, bool VEC>
+template <int BM, int BN, int BK, bool VEC>
 __global__ void __launch_bounds__(kProjThreads)
 sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                  const float* __restrict__ Mean, const float* __restrict__ Wself,
                  const float* __restrict__ Wneigh, const float* __restrict__ bias, int64_t n_dst,
                  int32_t d_in, int32_t d_out, int relu, uint32_t n_tiles_n, const float* __restrict__ Zero,
                  float* __restrict__ out) {
-    constexpr int BK = 16, LDA = BK + 4, LDB = BN + 4;
+    constexpr int LDA = BK + 4, LDB = BN + 4;   // LDA/4 odd: conflict-free 128-bit reads
+    static_assert(BK % 8 == 0 && (LDA / 4) % 2 == 1, "K tile");
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_ITEMS = BM * BK / 4 / kProjThreads;   // float4 items per thread
     constexpr int B_ITEMS = BK * BN / 4 / kProjThreads;
@@ -637,7 +638,7 @@ static uint32_t project_grid(int64_t n_dst, int BM, uint32_t n_tiles_n) {
     return (uint32_t)(ceil_div(m_tiles, kXcds) * kXcds * n_tiles_n);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int BK>
 static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                         const void* mean, const void* Ws, const void* Wn, const void* bias,
                                         int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
@@ -652,10 +653,10 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
     auto o = static_cast<float*>(out);
     auto z = static_cast<const float*>(zero);
     if (vec)
-        hipLaunchKernelGGL((sage_project_f32<BM, BN, true>), grid, dim3(kProjThreads), 0, s, a, self_idx,
+        hipLaunchKernelGGL((sage_project_f32<BM, BN, BK, true>), grid, dim3(kProjThreads), 0, s, a, self_idx,
                            m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
     else
-        hipLaunchKernelGGL((sage_project_f32<BM, BN, false>), grid, dim3(kProjThreads), 0, s, a, self_idx,
+        hipLaunchKernelGGL((sage_project_f32<BM, BN, BK, false>), grid, dim3(kProjThreads), 0, s, a, self_idx,
                            m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
@@ -753,8 +754,8 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
                          aligned(W_self, 16) && aligned(W_neigh, 16);
         // large tiles once there is enough work to fill 256 CUs twice over
         if (d_out > 64 && work >= 512)
-            return launch_project_f32<128, 128>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
-        return launch_project_f32<64, 64>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
+            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
+        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
     }
     hipLaunchKernelGGL(sage_transpose_w, dim3(L.KP / 32, L.NP / 32), dim3(256), 0, s,
                        static_cast<const uint16_t*>(W_self), static_cast<const uint16_t*>(W_neigh), d_in, d_out,

@@ -8,6 +8,7 @@ on torch's current stream, with no host synchronisation inside a batch.
 """
 from __future__ import annotations
 
+import ctypes
 from dataclasses import dataclass
 from typing import List, Optional, Sequence
 
@@ -70,58 +71,105 @@ class HotPath:
         ws_bytes = max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0],
                                                    hidden) for k in range(1, sh.n_layers + 1))
         self.sage_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._prepare_calls()
+
+    def _prepare_calls(self) -> None:
+        """Marshal every argument that never changes once: the buffers are fixed, so a batch only
+        has to supply the seeds pointer, the key and the stream.  (At ~10 launches of a few
+        microseconds each, per-call tensor slicing and pointer extraction in Python would cost
+        more than the kernels.)"""
+        lib = hb.load_library()
+        sh = self.shape
+        T, B, L, S = sh.n_slots, sh.n_seeds, sh.n_layers, sh.n_nonleaf
+        self._csr = hb._Csr(self.n_vertices, self.indices.numel(), self.offsets.data_ptr(),
+                            1 if self.offsets.dtype == torch.int64 else 0, self.indices.data_ptr())
+        self._fan = (ctypes.c_int32 * L)(*sh.fanouts)
+        ids, remap = self.ids.data_ptr(), self.remap.data_ptr()
+        dt = hb.DTYPE_OF[self.X.dtype]
+        self._lib = lib
+        self._sample_args = [(ctypes.byref(self._csr), B, self._fan, L, ids + 4 * b * T,
+                              self.indptr.data_ptr(),
+                              self.slot_idx[b].data_ptr() if L > 1 else None) for b in range(self.group)]
+        self._pregather_args = (ids, self.group * T, self.n_vertices, self.pg_algo, self.uniq.data_ptr(),
+                                self.n_uniq.data_ptr(), remap, self.pg_ws.data_ptr(), self.pg_ws.numel())
+        self._gather_args = (self.X.data_ptr(), dt, self.X.shape[0], self.X.shape[1], self.X.stride(0),
+                             self.uniq.data_ptr(), self.cap, self.n_uniq.data_ptr(), self.Xu.data_ptr())
+        self._layer_args = []
+        for b in range(self.group):
+            rb = remap + 4 * b * T
+            src, n_src, per_batch = self.Xu.data_ptr(), self.cap, []
+            for k in range(1, L + 1):
+                n_dst, nnz = sh.n_dst(k), sh.nnz(k)
+                Ws, Wn, bias = self.weights[k - 1]
+                d_in, d_out = Ws.shape
+                self_idx, idx = (rb, rb + 4 * B) if k == 1 else (None, self.slot_idx[b].data_ptr())
+                per_batch.append((src, dt, n_src, d_in, self_idx, self.indptr.data_ptr(), idx, n_dst,
+                                  Ws.data_ptr(), Wn.data_ptr(), None if bias is None else bias.data_ptr(),
+                                  d_out, 1 if k < L else 0, self.H[k - 1].data_ptr(), self.sage_ws.data_ptr(),
+                                  self.sage_ws.numel()))
+                src, n_src = self.H[k - 1].data_ptr(), n_dst
+            self._layer_args.append(per_batch)
 
     # -- the four steps ------------------------------------------------------
+    # `stream` is a raw hipStream_t (int); None = torch's current stream.
 
-    def sample(self, b: int, seeds: torch.Tensor, key: int) -> None:
-        T = self.shape.n_slots
-        hb.hopgnn_sample(self.offsets, self.indices, seeds, self.shape.fanouts, key,
-                         self.ids[b * T:(b + 1) * T], self.indptr,
-                         self.slot_idx[b] if self.shape.n_layers > 1 else None)
+    @staticmethod
+    def _stream(stream):
+        return torch.cuda.current_stream().cuda_stream if stream is None else stream
 
-    def pregather(self) -> None:
-        hb.hopgnn_pregather(self.ids, self.n_vertices, self.uniq, self.n_uniq, self.remap,
-                            self.pg_ws, self.pg_algo)
+    def sample(self, b: int, seeds: torch.Tensor, key: int, stream=None) -> None:
+        g, B, fan, L, ids, indptr, slot_idx = self._sample_args[b]
+        if seeds.numel() != B or seeds.dtype != torch.int32 or not seeds.is_cuda:
+            raise hb.HopgnnError("seeds must be %d int32 values on the device" % B)
+        rc = self._lib.hopgnn_sample(g, seeds.data_ptr(), B, fan, L, key & 0xFFFFFFFFFFFFFFFF, ids, indptr,
+                                     slot_idx, self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_sample")
 
-    def gather(self) -> None:
-        hb.hopgnn_gather(self.X, self.uniq, self.cap, self.n_uniq, self.Xu)
+    def pregather(self, stream=None) -> None:
+        rc = self._lib.hopgnn_pregather(*self._pregather_args, self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_pregather")
 
-    def layers(self, b: int) -> torch.Tensor:
-        sh = self.shape
-        T, B, L = sh.n_slots, sh.n_seeds, sh.n_layers
-        remap = self.remap[b * T:(b + 1) * T]
-        src, n_src = self.Xu, self.cap
-        for k in range(1, L + 1):
-            n_dst, nnz = sh.n_dst(k), sh.nnz(k)
-            Ws, Wn, bias = self.weights[k - 1]
-            if k == 1:
-                self_idx, idx = remap[:n_dst], remap[B:B + nnz]
-            else:
-                self_idx, idx = None, self.slot_idx[b][:nnz]
-            hb.hopgnn_sage_fwd(src, n_src, self_idx, self.indptr[:n_dst + 1], idx, n_dst, Ws, Wn,
-                               bias, k < L, self.H[k - 1], self.sage_ws)
-            src, n_src = self.H[k - 1], n_dst
-        return self.H[L - 1]
+    def gather(self, stream=None) -> None:
+        rc = self._lib.hopgnn_gather(*self._gather_args, self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_gather")
+
+    def layer(self, b: int, k: int, stream=None) -> torch.Tensor:
+        """Layer k (1-based) of batch b; its input is Xu (k = 1) or H[k-2]."""
+        rc = self._lib.hopgnn_sage_fwd(*self._layer_args[b][k - 1], self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_sage_fwd")
+        return self.H[k - 1]
+
+    def layers(self, b: int, stream=None) -> torch.Tensor:
+        st = self._stream(stream)
+        for k in range(1, self.shape.n_layers + 1):
+            self.layer(b, k, st)
+        return self.H[-1]
 
     # -- whole steps ---------------------------------------------------------
 
-    def run_batch(self, seeds: torch.Tensor, key: int) -> torch.Tensor:
+    def run_batch(self, seeds: torch.Tensor, key: int, stream=None) -> torch.Tensor:
         """One batch (group size 1): returns the [B, hidden] output of the last layer."""
-        self.sample(0, seeds, key)
-        self.pregather()
-        self.gather()
-        return self.layers(0)
+        st = self._stream(stream)
+        self.sample(0, seeds, key, st)
+        self.pregather(st)
+        self.gather(st)
+        return self.layers(0, st)
 
     def run_group(self, seeds_list: Sequence[torch.Tensor], keys: Sequence[int],
-                  outs: Optional[List[torch.Tensor]] = None) -> None:
+                  outs: Optional[List[torch.Tensor]] = None, stream=None) -> None:
         """G batches share one pre-gather and one gather; `outs[b]` (if given)
         receives a copy of batch b's final rows."""
         assert len(seeds_list) == self.group
+        st = self._stream(stream)
         for b, (s, k) in enumerate(zip(seeds_list, keys)):
-            self.sample(b, s, k)
-        self.pregather()
-        self.gather()
+            self.sample(b, s, k, st)
+        self.pregather(st)
+        self.gather(st)
         for b in range(self.group):
-            h = self.layers(b)
+            h = self.layers(b, st)
             if outs is not None:
                 outs[b].copy_(h)
