@@ -61,6 +61,38 @@ union Pack16 {
 
 // ------------------------------------------------------------ segmented mean --
 
+// Side job of the mean kernels for 2-byte types: the projection wants the weights with k
+// contiguous, Wt[n][k] = (k < d_in ? W_self[k][n] : W_neigh[k - d_in][n]), zero outside
+// [0, 2*d_in) x [0, d_out).  The workgroups after the last mean workgroup each transpose one
+// 32 x 32 tile through LDS (coalesced reads and writes), which saves a launch per layer.
+struct TransposeJob {
+    const uint16_t* Wself;
+    const uint16_t* Wneigh;
+    uint16_t* Wt;
+    int32_t d_in, d_out, KP, NP;
+    uint32_t first_block;   // workgroups >= first_block transpose; n_tiles_k = KP / 32
+};
+
+__device__ __forceinline__ void transpose_w_tile(const TransposeJob& J, uint32_t tile_id) {
+    __shared__ uint16_t tile[32][33];
+    const uint32_t tiles_k = J.KP / 32;
+    const int k0 = (tile_id % tiles_k) * 32, n0 = (tile_id / tiles_k) * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int j = ty; j < 32; j += 8) {
+        const int k = k0 + j, n = n0 + tx;
+        uint16_t v = 0;
+        if (k < 2 * J.d_in && n < J.d_out)
+            v = k < J.d_in ? J.Wself[(int64_t)k * J.d_out + n] : J.Wneigh[(int64_t)(k - J.d_in) * J.d_out + n];
+        tile[j][tx] = v;
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        const int n = n0 + j, k = k0 + tx;
+        if (n < J.NP && k < J.KP) J.Wt[(int64_t)n * J.KP + k] = tile[tx][j];
+    }
+}
+
+
 constexpr int kMeanThreads = 256;
 constexpr int kMeanUnroll = 4;
 
@@ -74,7 +106,11 @@ template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
-              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words) {
+              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job) {
+    if (blockIdx.x >= job.first_block) {
+        transpose_w_tile(job, blockIdx.x - job.first_block);
+        return;
+    }
     if (blockIdx.x == 0)   // the projection reads absent rows and the K padding from this row
         for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
@@ -116,7 +152,12 @@ template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
                const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
-               typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words) {
+               typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words,
+               TransposeJob job) {
+    if (blockIdx.x >= job.first_block) {
+        transpose_w_tile(job, blockIdx.x - job.first_block);
+        return;
+    }
     if (blockIdx.x == 0)
         for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
@@ -259,8 +300,9 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     constexpr int A_ITEMS = BM * BK / 4 / kProjThreads;   // float4 items per thread
     constexpr int B_ITEMS = BK * BN / 4 / kProjThreads;
     static_assert(A_ITEMS >= 1 && B_ITEMS >= 1, "tile too small for 256 threads");
-    __shared__ __attribute__((aligned(16))) float As[2][BM][LDA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK][LDB];
+    extern __shared__ __attribute__((aligned(16))) float lds_f32[];
+    float (*As)[BM][LDA] = reinterpret_cast<float (*)[BM][LDA]>(lds_f32);
+    float (*Bs)[BK][LDB] = reinterpret_cast<float (*)[BK][LDB]>(lds_f32 + 2 * BM * LDA);
 
     uint32_t mt, nt;
     tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
@@ -410,7 +452,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
 // column) l%32, k-group l/32, so both operands sit in LDS with k contiguous and are read
 // as 128-bit words: A [BM][BK+8], B [BN][BK+8] (row stride 80 bytes: conflict free).
 // B comes from Wt, the transposed weights [NP][KP] (k contiguous, zero padded to whole
-// tiles) that sage_transpose_w writes into the workspace.
+// tiles) that the mean kernel's side job writes into the workspace.
 template <typename Tr>
 __device__ __forceinline__ floatx16 mfma16(const uint4& a, const uint4& b, floatx16 c);
 template <>
@@ -425,28 +467,6 @@ __device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b
 }
 
 constexpr int kKPad16 = 64;   // Wt rows are zero padded to a multiple of this many k
-
-// Wt[n][k] = (k < d_in ? W_self[k][n] : W_neigh[k - d_in][n]), zero outside [0,2*d_in) x [0,d_out).
-// 32 x 32 tiles through LDS so both the reads and the writes are coalesced.
-__global__ void __launch_bounds__(256)
-sage_transpose_w(const uint16_t* __restrict__ Wself, const uint16_t* __restrict__ Wneigh, int32_t d_in,
-                 int32_t d_out, int32_t KP, int32_t NP, uint16_t* __restrict__ Wt) {
-    __shared__ uint16_t tile[32][33];
-    const int k0 = blockIdx.x * 32, n0 = blockIdx.y * 32;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
-    for (int j = ty; j < 32; j += 8) {
-        const int k = k0 + j, n = n0 + tx;
-        uint16_t v = 0;
-        if (k < 2 * d_in && n < d_out)
-            v = k < d_in ? Wself[(int64_t)k * d_out + n] : Wneigh[(int64_t)(k - d_in) * d_out + n];
-        tile[j][tx] = v;
-    }
-    __syncthreads();
-    for (int j = ty; j < 32; j += 8) {
-        const int n = n0 + j, k = k0 + tx;
-        if (n < NP && k < KP) Wt[(int64_t)n * KP + k] = tile[tx][j];
-    }
-}
 
 template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
 __global__ void __launch_bounds__(64 * WM * WN)
@@ -615,20 +635,23 @@ static int mean_group(int units) {   // lanes per destination row: power of two,
 template <typename Tr>
 static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const int32_t* idx,
                                  int64_t n_dst, int32_t d_in, void* mean, void* zero_row,
-                                 size_t zero_bytes, hipStream_t s) {
+                                 size_t zero_bytes, TransposeJob job, uint32_t n_transpose_tiles, hipStream_t s) {
     using T = typename Tr::store_t;
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
     const int group = mean_group(units);
-    const int64_t blocks = ceil_div(n_dst * group, kMeanThreads);
+    const int64_t mean_blocks = ceil_div(n_dst * group, kMeanThreads);
+    if (mean_blocks + n_transpose_tiles >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    job.first_block = (uint32_t)mean_blocks;
+    const int64_t blocks = mean_blocks + n_transpose_tiles;
     if (vec)
         hipLaunchKernelGGL(sage_mean_vec<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
-                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4));
+                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
     else
         hipLaunchKernelGGL(sage_mean_elem<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
-                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4));
+                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -652,12 +675,14 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
     auto b = static_cast<const float*>(bias);
     auto o = static_cast<float*>(out);
     auto z = static_cast<const float*>(zero);
-    if (vec)
-        hipLaunchKernelGGL((sage_project_f32<BM, BN, BK, true>), grid, dim3(kProjThreads), 0, s, a, self_idx,
-                           m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
-    else
-        hipLaunchKernelGGL((sage_project_f32<BM, BN, BK, false>), grid, dim3(kProjThreads), 0, s, a, self_idx,
-                           m, ws, wn, b, n_dst, d_in, d_out, relu, ntn, z, o);
+    constexpr size_t lds = (size_t)2 * (BM * (BK + 4) + BK * (BN + 4)) * sizeof(float);
+    auto kern = vec ? sage_project_f32<BM, BN, BK, true> : sage_project_f32<BM, BN, BK, false>;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+        return HOPGNN_EHIP;
+    hipLaunchKernelGGL(kern, grid, dim3(kProjThreads), lds, s, a, self_idx, m, ws, wn, b, n_dst, d_in, d_out, relu,
+                       ntn, z, o);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -741,10 +766,17 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     uint16_t* Wt = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + L.mean_bytes);
     void* zero = static_cast<char*>(ws) + L.mean_bytes + L.wt_bytes;
 
+    TransposeJob job{};
+    uint32_t n_tr = 0;
+    if (dt != HOPGNN_F32) {
+        job = TransposeJob{static_cast<const uint16_t*>(W_self), static_cast<const uint16_t*>(W_neigh), Wt, d_in,
+                           d_out, L.KP, L.NP, 0u};
+        n_tr = (uint32_t)(L.KP / 32) * (uint32_t)(L.NP / 32);
+    }
     hopgnn_status st;
-    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
-    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
-    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, s);
+    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
+    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
+    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
     if (st != HOPGNN_OK) return st;
 
     const int per16 = dt == HOPGNN_F32 ? 4 : 8;
@@ -757,10 +789,6 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
             return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
         return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
     }
-    hipLaunchKernelGGL(sage_transpose_w, dim3(L.KP / 32, L.NP / 32), dim3(256), 0, s,
-                       static_cast<const uint16_t*>(W_self), static_cast<const uint16_t*>(W_neigh), d_in, d_out,
-                       L.KP, L.NP, Wt);
-    HOPGNN_LAUNCH_CHECK();
     const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16);
     const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
     const bool big = d_out > 64 && work >= 512;
