@@ -54,6 +54,11 @@ def lib() -> ctypes.CDLL:
         L.orc_gather.restype = c.c_int
         L.orc_gather.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_int64, c.c_void_p,
                                  c.c_int64, c.c_void_p]
+        L.orc_micrograph_locality.restype = c.c_int
+        L.orc_micrograph_locality.argtypes = [c.c_void_p, c.c_int32, c.c_void_p, c.c_int32, c.c_void_p,
+                                              c.c_void_p, c.c_void_p]
+        L.orc_split_by_owner.restype = c.c_int64
+        L.orc_split_by_owner.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p]
         L.orc_round_store.restype = None
         L.orc_round_store.argtypes = [c.c_void_p, c.c_int64, c.c_int, c.c_void_p]
         L.orc_load_f64.restype = None
@@ -142,6 +147,29 @@ def gather(X, uniq):
     if rc:
         raise ValueError("orc_gather failed: %d" % rc)
     return out
+
+
+def micrograph_locality(ids, n_seeds: int, fanouts, owner):
+    """-> (n_total[n_seeds], n_colocated[n_seeds]) int32: distinct vertices per micrograph and
+    distinct non-root vertices that share the root's home server."""
+    ids = _arr(ids, np.int32)
+    f = _arr(fanouts, np.int32)
+    owner = _arr(owner, np.int32)
+    n_total = np.empty(n_seeds, np.int32)
+    n_coloc = np.empty(n_seeds, np.int32)
+    rc = lib().orc_micrograph_locality(_p(ids), n_seeds, _p(f), len(f), _p(owner), _p(n_total), _p(n_coloc))
+    if rc:
+        raise ValueError("orc_micrograph_locality failed: %d" % rc)
+    return n_total, n_coloc
+
+
+def split_by_owner(uniq, owner, server: int):
+    """-> the entries of uniq that are not stored on `server` (in order)."""
+    uniq = _arr(uniq, np.int32)
+    owner = _arr(owner, np.int32)
+    remote = np.empty(max(len(uniq), 1), np.int32)
+    n = lib().orc_split_by_owner(_p(uniq), len(uniq), _p(owner), server, _p(remote))
+    return remote[:n].copy()
 
 
 def round_store(x64, dtype: int):

@@ -181,6 +181,67 @@ int64_t orc_pregather(const int32_t *ids, int64_t n_ids, int32_t *uniq, int32_t 
     return U;
 }
 
+/* -------------------------------------------------------------- locality -- */
+
+/*
+ * Data locality of micrographs (paper section 4, "data locality in micrographs"
+ * and the text under the locality table): for each micrograph, N_total = number
+ * of distinct vertices in it, N_colocated = number of distinct NON-ROOT vertices
+ * whose home server equals the root's home server; R_micro = N_colocated/N_total.
+ * (The worked example of the same section counts the root as local too - 3 of 4
+ * for micrograph 6 - which is N_colocated + 1 over N_total.)
+ * owner[v] = home server of vertex v.  A micrograph whose root is its only vertex
+ * has N_total = 1, N_colocated = 0.
+ */
+int orc_micrograph_locality(const int32_t *ids, int32_t n_seeds, const int32_t *fanouts,
+                            int32_t n_layers, const int32_t *owner, int32_t *n_total,
+                            int32_t *n_coloc)
+{
+    const int64_t t_seed = orc_slots_per_seed(fanouts, n_layers);
+    if (t_seed < 0 || n_seeds < 0) return 1;
+    int32_t *tmp = (int32_t *)malloc((size_t)t_seed * sizeof(int32_t));
+    if (!tmp) return 2;
+    for (int64_t m = 0; m < n_seeds; ++m) {
+        int64_t n = 0, base = 0, P = 1;
+        for (int32_t h = 0; h <= n_layers; ++h) {
+            for (int64_t p = 0; p < P; ++p) {
+                int32_t v = ids[base + m * P + p];
+                if (v >= 0) tmp[n++] = v;
+            }
+            base += (int64_t)n_seeds * P;
+            if (h < n_layers) P *= fanouts[h];
+        }
+        const int32_t root = ids[m];
+        qsort(tmp, (size_t)n, sizeof(int32_t), cmp_i32);
+        int32_t tot = 0, col = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            if (i > 0 && tmp[i] == tmp[i - 1]) continue;
+            ++tot;
+            if (tmp[i] != root && owner[tmp[i]] == owner[root]) ++col;
+        }
+        n_total[m] = tot;
+        n_coloc[m] = col;
+    }
+    free(tmp);
+    return 0;
+}
+
+/*
+ * Owner split of a pre-gathered ID set (paper section 5.2: only the vertices that
+ * are NOT stored on the worker's own server are fetched; section 7.3 reports the
+ * miss rate of feature gathering = non-local requests / all requests).
+ * remote = the entries of uniq whose owner differs from `server`, in order;
+ * returns their number.  miss rate = return value / n_uniq.
+ */
+int64_t orc_split_by_owner(const int32_t *uniq, int64_t n_uniq, const int32_t *owner, int32_t server,
+                           int32_t *remote)
+{
+    int64_t n = 0;
+    for (int64_t i = 0; i < n_uniq; ++i)
+        if (owner[uniq[i]] != server) remote[n++] = uniq[i];
+    return n;
+}
+
 /* ---------------------------------------------------------------- gather -- */
 
 /* Gathering (paper section 2): Xu[i,:] = X[uniq[i],:], a copy of row bytes.
