@@ -120,6 +120,38 @@ hopgnn_status hopgnn_pregather(const int32_t *ids, int64_t n_ids, int64_t n_vert
                                void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Data locality of micrographs (paper section 4, "data locality in micrographs": the
+ * ratio R_micro = N_colocated / N_total of the locality table).
+ * For every micrograph m of one batch (ids as written by hopgnn_sample):
+ *   n_total[m] = number of distinct vertices among its valid slots,
+ *   n_coloc[m] = number of distinct vertices other than the root whose home server
+ *                owner[v] equals the root's, owner[ids[m]].
+ * (The section's worked example also counts the root as local: n_coloc + 1.)
+ * ids   DEVICE [n_seeds*T_seed]; owner DEVICE [n_vertices] int32;
+ * n_total, n_coloc DEVICE out [n_seeds].
+ * Errors: EINVAL; ERANGE if T_seed > 16384 (the per-micrograph hash set lives in LDS).
+ */
+hopgnn_status hopgnn_micrograph_locality(const int32_t *ids, int32_t n_seeds, const int32_t *fanouts /*HOST*/,
+                                         int32_t n_layers, const int32_t *owner, int32_t *n_total,
+                                         int32_t *n_coloc, void *stream);
+
+/*
+ * Owner split of a pre-gathered set (paper section 5.2: only vertices that are not stored
+ * on the worker's own server are fetched; section 7.3: miss rate of feature gathering =
+ * non-local requests / all requests).
+ * remote       DEVICE out, capacity n_uniq: the entries of uniq with owner != server, in
+ *              order (so still ascending);
+ * n_remote_dev DEVICE out, one int64: their number; miss rate = n_remote / U.
+ * n_uniq / n_uniq_dev as in hopgnn_gather (capacity + device count, or the count itself).
+ * ws           DEVICE scratch, hopgnn_split_ws_bytes(n_uniq) bytes, 256-byte aligned.
+ */
+size_t hopgnn_split_ws_bytes(int64_t n_uniq);
+
+hopgnn_status hopgnn_split_by_owner(const int32_t *uniq, int64_t n_uniq, const int64_t *n_uniq_dev,
+                                    const int32_t *owner, int32_t server, int32_t *remote,
+                                    int64_t *n_remote_dev, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Gathering (paper section 2 "gathering": collect the feature vector of every
  * vertex of the sampled structure; section 3.1 names it the bottleneck).
  *

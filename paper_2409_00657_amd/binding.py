@@ -23,7 +23,8 @@ PG_AUTO, PG_BITMAP, PG_RADIX = 0, 1, 2
 
 EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_pregather_ws_bytes", "hopgnn_pregather", "hopgnn_gather",
-           "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd"]
+           "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_micrograph_locality",
+           "hopgnn_split_ws_bytes", "hopgnn_split_by_owner"]
 
 
 class HopgnnError(RuntimeError):
@@ -73,6 +74,14 @@ def load_library() -> ctypes.CDLL:
                                   c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
                                   c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
                                   c.c_size_t, c.c_void_p]
+    L.hopgnn_micrograph_locality.restype = c.c_int
+    L.hopgnn_micrograph_locality.argtypes = [c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
+                                             c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+    L.hopgnn_split_ws_bytes.restype = c.c_size_t
+    L.hopgnn_split_ws_bytes.argtypes = [c.c_int64]
+    L.hopgnn_split_by_owner.restype = c.c_int
+    L.hopgnn_split_by_owner.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32,
+                                        c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     _lib = L
     return L
 
@@ -158,3 +167,23 @@ def hopgnn_sage_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Ten
                                         1 if relu else 0, _ptr(out), _ptr(ws),
                                         ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sage_fwd")
+
+
+def hopgnn_micrograph_locality(ids: torch.Tensor, n_seeds: int, fanouts: Sequence[int], owner: torch.Tensor,
+                               n_total: torch.Tensor, n_coloc: torch.Tensor) -> None:
+    rc = load_library().hopgnn_micrograph_locality(_ptr(ids), n_seeds, _fan(fanouts), len(fanouts),
+                                                   _ptr(owner), _ptr(n_total), _ptr(n_coloc), _stream())
+    _check(rc, "hopgnn_micrograph_locality")
+
+
+def hopgnn_split_ws_bytes(n_uniq: int) -> int:
+    return int(load_library().hopgnn_split_ws_bytes(n_uniq))
+
+
+def hopgnn_split_by_owner(uniq: torch.Tensor, n_uniq: int, n_uniq_dev: Optional[torch.Tensor],
+                          owner: torch.Tensor, server: int, remote: torch.Tensor, n_remote_dev: torch.Tensor,
+                          ws: torch.Tensor) -> None:
+    rc = load_library().hopgnn_split_by_owner(_ptr(uniq), n_uniq, _ptr(n_uniq_dev), _ptr(owner), server,
+                                              _ptr(remote), _ptr(n_remote_dev), _ptr(ws),
+                                              ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_split_by_owner")

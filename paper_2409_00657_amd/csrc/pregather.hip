@@ -18,6 +18,13 @@
 
 namespace hopgnn {
 
+// level-major slot layout of a batch (see hopgnn_sample)
+struct SlotShape {
+    int32_t n_layers;
+    int32_t P[kMaxLayers + 1];      // slots per micrograph at level h
+    int32_t base[kMaxLayers + 2];   // first slot of level h
+};
+
 constexpr int kPgThreads = 256;
 constexpr int kWordsPerThread = 4;                              // one 128-bit load
 constexpr int kWordsPerBlock = kPgThreads * kWordsPerThread;    // 1024 words = 32768 vertices
@@ -561,6 +568,94 @@ static hopgnn_status pregather_radix(const int32_t* ids, int64_t n_ids, int64_t 
     return HOPGNN_OK;
 }
 
+// --------------------------------------------------------- locality statistics --
+
+constexpr int kLocThreads = 256;
+constexpr int32_t kLocEmpty = -1;
+
+// One workgroup per micrograph: its slots are inserted into an open-addressing hash set in
+// LDS (atomicCAS); the thread that claims a free cell has found a new distinct vertex.
+__global__ void __launch_bounds__(kLocThreads)
+micrograph_locality(const int32_t* __restrict__ ids, int32_t n_seeds, SlotShape sh,
+                    const int32_t* __restrict__ owner, uint32_t table_mask, int32_t* __restrict__ n_total,
+                    int32_t* __restrict__ n_coloc) {
+    extern __shared__ int32_t table[];
+    __shared__ uint32_t lds4[kLocThreads / kWave];
+    const int32_t m = blockIdx.x;
+    for (uint32_t i = threadIdx.x; i <= table_mask; i += kLocThreads) table[i] = kLocEmpty;
+    __syncthreads();
+    const int32_t root = ids[m];
+    const int32_t root_home = owner[root];
+    uint32_t tot = 0, col = 0;
+    for (int32_t h = 0; h <= sh.n_layers; ++h) {
+        const int32_t* lvl = ids + sh.base[h] + (int64_t)m * sh.P[h];
+        for (int32_t p = threadIdx.x; p < sh.P[h]; p += kLocThreads) {
+            const int32_t v = lvl[p];
+            if (v < 0) continue;
+            uint32_t cell = ((uint32_t)v * 2654435761u) & table_mask;
+            while (true) {
+                const int32_t old = atomicCAS(&table[cell], kLocEmpty, v);
+                if (old == kLocEmpty) {   // first time this vertex is seen in the micrograph
+                    ++tot;
+                    if (v != root && owner[v] == root_home) ++col;
+                    break;
+                }
+                if (old == v) break;
+                cell = (cell + 1) & table_mask;
+            }
+        }
+    }
+    uint32_t t_all, c_all;
+    (void)block_exclusive_scan(tot, lds4, t_all);
+    (void)block_exclusive_scan(col, lds4, c_all);
+    if (threadIdx.x == 0) {
+        n_total[m] = (int32_t)t_all;
+        n_coloc[m] = (int32_t)c_all;
+    }
+}
+
+__global__ void __launch_bounds__(kPgThreads)
+owner_flags(const int32_t* __restrict__ uniq, int64_t n_host, const int64_t* __restrict__ n_dev,
+            const int32_t* __restrict__ owner, int32_t server, uint32_t* __restrict__ flags, uint32_t* ticket) {
+    const int64_t i = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
+    if (i == 0) *ticket = 0u;
+    if (i >= n_host) return;
+    int64_t n = n_host;
+    if (n_dev != nullptr) n = *n_dev < n ? *n_dev : n;
+    flags[i] = (i < n && owner[uniq[i]] != server) ? 1u : 0u;
+}
+
+__global__ void __launch_bounds__(kPgThreads)
+owner_compact(const int32_t* __restrict__ uniq, int64_t n_host, const int64_t* __restrict__ n_dev,
+              const int32_t* __restrict__ owner, int32_t server, const uint32_t* __restrict__ excl,
+              int32_t* __restrict__ remote) {
+    const int64_t i = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
+    int64_t n = n_host;
+    if (n_dev != nullptr) n = *n_dev < n ? *n_dev : n;
+    if (i >= n) return;
+    const int32_t v = uniq[i];
+    if (owner[v] != server) remote[excl[i]] = v;
+}
+
+struct SplitWs {
+    uint32_t *flags, *sums, *ticket;
+    size_t bytes;
+};
+static SplitWs split_layout(void* ws, int64_t n_uniq) {
+    SplitWs L{};
+    const int64_t n = n_uniq > 0 ? n_uniq : 1;
+    char* p = static_cast<char*>(ws);
+    size_t o = 0;
+    L.flags = reinterpret_cast<uint32_t*>(p + o);
+    o += align_up((size_t)n * 4, 256);
+    L.sums = reinterpret_cast<uint32_t*>(p + o);
+    o += align_up((size_t)ceil_div(n, kWordsPerBlock) * 4, 256);
+    L.ticket = reinterpret_cast<uint32_t*>(p + o);
+    o += 256;
+    L.bytes = o;
+    return L;
+}
+
 }  // namespace hopgnn
 
 using namespace hopgnn;
@@ -594,4 +689,72 @@ extern "C" hopgnn_status hopgnn_pregather(const int32_t* ids, int64_t n_ids, int
                                static_cast<hipStream_t>(stream));
     return pregather_bitmap(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, ws_bytes,
                             static_cast<hipStream_t>(stream));
+}
+
+extern "C" hopgnn_status hopgnn_micrograph_locality(const int32_t* ids, int32_t n_seeds, const int32_t* fanouts,
+                                                    int32_t n_layers, const int32_t* owner, int32_t* n_total,
+                                                    int32_t* n_coloc, void* stream) {
+    if (fanouts == nullptr || n_seeds < 0 || n_layers < 1 || n_layers > kMaxLayers) return HOPGNN_EINVAL;
+    SlotShape sh{};
+    sh.n_layers = n_layers;
+    sh.P[0] = 1;
+    sh.base[0] = 0;
+    int64_t t_seed = 1;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        if (fanouts[h - 1] < 1) return HOPGNN_EINVAL;
+        const int64_t p = (int64_t)sh.P[h - 1] * fanouts[h - 1];
+        t_seed += p;
+        if (t_seed > 16384) return HOPGNN_ERANGE;   // hash set of 2*T_seed cells must fit 160 KB of LDS
+        sh.P[h] = (int32_t)p;
+    }
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (ids == nullptr || owner == nullptr || n_total == nullptr || n_coloc == nullptr) return HOPGNN_EINVAL;
+    if ((int64_t)n_seeds * t_seed >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    for (int32_t h = 1; h <= n_layers + 1; ++h) sh.base[h] = sh.base[h - 1] + n_seeds * sh.P[h - 1];
+    uint32_t cells = 64;
+    while (cells < 2 * (uint32_t)t_seed) cells *= 2;   // load factor <= 1/2
+    const size_t lds = (size_t)cells * 4;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(micrograph_locality),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return HOPGNN_EHIP;
+    hipLaunchKernelGGL(micrograph_locality, dim3(n_seeds), dim3(kLocThreads), lds, static_cast<hipStream_t>(stream),
+                       ids, n_seeds, sh, owner, cells - 1, n_total, n_coloc);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+extern "C" size_t hopgnn_split_ws_bytes(int64_t n_uniq) {
+    if (n_uniq < 0) return 0;
+    return split_layout(nullptr, n_uniq).bytes;
+}
+
+extern "C" hopgnn_status hopgnn_split_by_owner(const int32_t* uniq, int64_t n_uniq, const int64_t* n_uniq_dev,
+                                               const int32_t* owner, int32_t server, int32_t* remote,
+                                               int64_t* n_remote_dev, void* ws, size_t ws_bytes, void* stream) {
+    if (n_uniq < 0 || n_remote_dev == nullptr || ws == nullptr || !aligned(ws, 256)) return HOPGNN_EINVAL;
+    if (n_uniq >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (n_uniq == 0) {
+        hipLaunchKernelGGL(set_count_zero, dim3(1), dim3(1), 0, s, n_remote_dev);
+        HOPGNN_LAUNCH_CHECK();
+        return HOPGNN_OK;
+    }
+    if (uniq == nullptr || owner == nullptr || remote == nullptr) return HOPGNN_EINVAL;
+    const SplitWs L = split_layout(ws, n_uniq);
+    if (ws_bytes < L.bytes) return HOPGNN_ENOMEM_WS;
+    const unsigned blocks = (unsigned)ceil_div(n_uniq, kPgThreads);
+    hipLaunchKernelGGL(owner_flags, dim3(blocks), dim3(kPgThreads), 0, s, uniq, n_uniq, n_uniq_dev, owner, server,
+                       L.flags, L.ticket);
+    HOPGNN_LAUNCH_CHECK();
+    const int64_t n_chunks = ceil_div(n_uniq, kWordsPerBlock);
+    hipLaunchKernelGGL(scan_chunk_sums, dim3((unsigned)(n_chunks < 1024 ? n_chunks : 1024)), dim3(kPgThreads), 0, s,
+                       L.flags, n_uniq, L.sums, (uint32_t)n_chunks, L.ticket, n_remote_dev);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_chunks), dim3(kPgThreads), 0, s, L.flags, n_uniq, L.sums);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(owner_compact, dim3(blocks), dim3(kPgThreads), 0, s, uniq, n_uniq, n_uniq_dev, owner, server,
+                       L.flags, remote);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }

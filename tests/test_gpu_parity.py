@@ -227,3 +227,42 @@ def test_sage_fwd_special_cases_exact(hb):
     hb.hopgnn_sage_fwd(H, 50, None, indptr, idx, n_dst, I, Z, None, False, out, ws)
     torch.cuda.synchronize()
     assert torch.equal(out, H[:n_dst])
+
+
+@pytest.mark.parametrize("case", range(4))
+def test_micrograph_locality_and_owner_split_bit_exact(hb, orc, case):
+    rng = np.random.default_rng(300 + case)
+    N = [40, 3000, 20000, 500][case]
+    fan = [[2, 2], [10, 10], [15, 10, 5], [3]][case]
+    B = [5, 70, 33, 9][case]
+    S = [2, 4, 8, 16][case]
+    rows = [rng.integers(0, N, size=int(rng.integers(0, 9))).tolist() for _ in range(N)]
+    off, idx = _csr(rows)
+    seeds = rng.integers(0, N, size=B).astype(np.int32)
+    owner = rng.integers(0, S, size=N).astype(np.int32)
+    ids, _, _, _ = _gpu_sample(hb, off, idx, seeds, fan, 77)
+    ref_tot, ref_col = orc.micrograph_locality(ids, B, fan, owner)
+    n_total = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    n_coloc = torch.full((B,), -7, dtype=torch.int32, device=DEV)
+    d_owner = torch.from_numpy(owner).to(DEV)
+    hb.hopgnn_micrograph_locality(torch.from_numpy(ids).to(DEV), B, fan, d_owner, n_total, n_coloc)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(n_total.cpu().numpy(), ref_tot)
+    np.testing.assert_array_equal(n_coloc.cpu().numpy(), ref_col)
+    # owner split of the batch's pre-gathered set, with U on the device and on the host
+    uniq_np, _ = orc.pregather(ids)
+    U = len(uniq_np)
+    cap = U + 37
+    uniq = torch.zeros(cap, dtype=torch.int32, device=DEV)
+    uniq[:U] = torch.from_numpy(uniq_np).to(DEV)
+    ws = torch.empty(hb.hopgnn_split_ws_bytes(cap), dtype=torch.uint8, device=DEV)
+    for server in range(min(S, 3)):
+        want = orc.split_by_owner(uniq_np, owner, server)
+        for n_arg, n_dev in ((cap, torch.tensor([U], dtype=torch.int64, device=DEV)), (U, None)):
+            remote = torch.full((cap,), -7, dtype=torch.int32, device=DEV)
+            n_remote = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+            hb.hopgnn_split_by_owner(uniq, n_arg, n_dev, d_owner, server, remote, n_remote, ws)
+            torch.cuda.synchronize()
+            assert int(n_remote.item()) == len(want)
+            np.testing.assert_array_equal(remote.cpu().numpy()[:len(want)], want)
+            assert (remote[len(want):] == -7).all()
