@@ -199,6 +199,40 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               const void *bias, int32_t d_out, int32_t relu, void *out, void *ws,
                               size_t ws_bytes, void *stream);
 
+/*
+ * Micrograph merging (paper section 5.3).  HOST-only bookkeeping, no device work.
+ *
+ * counts is a HOST matrix [n_models x n_steps], row-major: root vertices model m trains at
+ * time step t of one iteration.
+ *
+ * hopgnn_merge_min_step  "which micrographs to merge": the time step with the fewest root
+ *     vertices over all models (the paper's stand-in for the number of vertex features a
+ *     step needs); ties go to the earliest step.  -1 on bad input.
+ * hopgnn_merge_apply     merges step ts away: each model's roots of step ts are dealt to that
+ *     model's other steps as evenly as possible (floor share each, the remainder one apiece to
+ *     the earliest steps), then column ts is removed in place (rows become n_steps-1 long).
+ *     Every model keeps its total.  Returns the new number of steps, -1 on bad input.
+ *     Worked example of the section: a model with 4, 2, 2 roots at t0, t1, t2 and ts = t1
+ *     ends with 5 and 3.
+ * hopgnn_merge_ctl_*     "how many to merge": the examination period.  _init starts with one
+ *     step per server.  _report is called once per epoch with that epoch's run time and
+ *     returns the number of steps to use in the next epoch: after the first epoch one step is
+ *     merged; while an epoch gets faster another is merged; the first epoch that does not get
+ *     faster undoes its merge and the pattern is kept from then on (the paper's run goes
+ *     4 -> 3 -> 2 -> 3).
+ */
+typedef struct {
+    int32_t n_steps;     /* steps per iteration to use now                */
+    int32_t settled;     /* 1 once the examination period is over         */
+    int32_t epochs_seen;
+    double prev_time;    /* run time of the last epoch that was kept      */
+} hopgnn_merge_ctl;
+
+int32_t hopgnn_merge_min_step(const int64_t *counts /*HOST*/, int32_t n_models, int32_t n_steps);
+int32_t hopgnn_merge_apply(int64_t *counts /*HOST, in/out*/, int32_t n_models, int32_t n_steps, int32_t ts);
+hopgnn_status hopgnn_merge_ctl_init(hopgnn_merge_ctl *ctl /*HOST*/, int32_t n_servers);
+int32_t hopgnn_merge_ctl_report(hopgnn_merge_ctl *ctl /*HOST*/, double epoch_time);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,11 +24,17 @@ PG_AUTO, PG_BITMAP, PG_RADIX = 0, 1, 2
 EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_pregather_ws_bytes", "hopgnn_pregather", "hopgnn_gather",
            "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_micrograph_locality",
-           "hopgnn_split_ws_bytes", "hopgnn_split_by_owner"]
+           "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
+           "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report"]
 
 
 class HopgnnError(RuntimeError):
     pass
+
+
+class MergeCtl(ctypes.Structure):
+    _fields_ = [("n_steps", ctypes.c_int32), ("settled", ctypes.c_int32), ("epochs_seen", ctypes.c_int32),
+                ("prev_time", ctypes.c_double)]
 
 
 class _Csr(ctypes.Structure):
@@ -82,6 +88,14 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_split_by_owner.restype = c.c_int
     L.hopgnn_split_by_owner.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_int32,
                                         c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_merge_min_step.restype = c.c_int32
+    L.hopgnn_merge_min_step.argtypes = [c.POINTER(c.c_int64), c.c_int32, c.c_int32]
+    L.hopgnn_merge_apply.restype = c.c_int32
+    L.hopgnn_merge_apply.argtypes = [c.POINTER(c.c_int64), c.c_int32, c.c_int32, c.c_int32]
+    L.hopgnn_merge_ctl_init.restype = c.c_int
+    L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
+    L.hopgnn_merge_ctl_report.restype = c.c_int32
+    L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
     _lib = L
     return L
 
@@ -187,3 +201,20 @@ def hopgnn_split_by_owner(uniq: torch.Tensor, n_uniq: int, n_uniq_dev: Optional[
                                               _ptr(remote), _ptr(n_remote_dev), _ptr(ws),
                                               ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_split_by_owner")
+
+
+def hopgnn_merge_min_step(counts) -> int:
+    """counts: list of rows (models) of per-step root counts (host)."""
+    n_models, n_steps = len(counts), len(counts[0])
+    flat = (ctypes.c_int64 * (n_models * n_steps))(*[int(x) for r in counts for x in r])
+    return int(load_library().hopgnn_merge_min_step(flat, n_models, n_steps))
+
+
+def hopgnn_merge_apply(counts, ts: int):
+    """-> the merged matrix (list of rows, one step fewer)."""
+    n_models, n_steps = len(counts), len(counts[0])
+    flat = (ctypes.c_int64 * (n_models * n_steps))(*[int(x) for r in counts for x in r])
+    n = int(load_library().hopgnn_merge_apply(flat, n_models, n_steps, ts))
+    if n < 0:
+        raise HopgnnError("hopgnn_merge_apply: invalid argument")
+    return [[int(flat[m * n + t]) for t in range(n)] for m in range(n_models)]
