@@ -67,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.orc_sage_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p,
                                    c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
                                    c.c_void_p, c.c_int32, c.c_int32, c.c_void_p]
+        L.orc_sage_bwd.restype = c.c_int
+        L.orc_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                   c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
+                                   c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
         _lib = L
     return _lib
 
@@ -208,6 +212,33 @@ def sage_fwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, bias, relu):
     if rc:
         raise ValueError("orc_sage_fwd failed: %d" % rc)
     return out
+
+
+def sage_bwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, out_fwd, relu, dOut, want_dH=True):
+    """Backward of one layer in float64 -> (gW_self, gW_neigh, gbias, dHsrc-or-None), fresh arrays."""
+    npdt = _NP_OF[dtype]
+    Hsrc = _arr(Hsrc, npdt)
+    W_self = _arr(W_self, npdt)
+    W_neigh = _arr(W_neigh, npdt)
+    n_src, d_in = Hsrc.shape
+    d_out = W_self.shape[1]
+    indptr = _arr(indptr, np.int32)
+    idx = _arr(idx, np.int32)
+    n_dst = len(indptr) - 1
+    self_idx = None if self_idx is None else _arr(self_idx, np.int32)
+    out_fwd = None if out_fwd is None else _arr(out_fwd, npdt)
+    dOut = _arr(dOut, np.float64)
+    assert dOut.shape == (n_dst, d_out)
+    gWs = np.zeros((d_in, d_out), np.float64)
+    gWn = np.zeros((d_in, d_out), np.float64)
+    gb = np.zeros(d_out, np.float64)
+    dH = np.zeros((n_src, d_in), np.float64) if want_dH else None
+    rc = lib().orc_sage_bwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W_self),
+                            _p(W_neigh), _p(out_fwd), int(bool(relu)), _p(dOut), d_out, _p(gWs), _p(gWn), _p(gb),
+                            _p(dH))
+    if rc:
+        raise ValueError("orc_sage_bwd failed: %d" % rc)
+    return gWs, gWn, gb, dH
 
 
 def forward(X_rows, dtype, ids, indptr, remap, n_seeds, fanouts, weights):

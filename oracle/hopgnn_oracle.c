@@ -399,3 +399,71 @@ int orc_sage_fwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in,
     free(mn);
     return rc;
 }
+
+/*
+ * Backward of one GraphSAGE-mean layer (paper section 5.1, steps 3-4: each micrograph
+ * batch runs forward and backward on the server it sits on and the gradients are
+ * accumulated until the whole subgraph is done; the discussion section says the
+ * accumulated partial gradients are updated in place).
+ *
+ * With out = act(x_self W_self + m W_neigh + b) and dOut = dL/d out:
+ *   dZ        = dOut where the activation passes (relu: where out_fwd > 0), else 0
+ *   gW_self  += x_self^T dZ        gW_neigh += m^T dZ        gbias += column sums of dZ
+ *   dHsrc[self_idx[r]] += dZ[r] W_self^T
+ *   dHsrc[idx[e]]      += (dZ[r] W_neigh^T) / c_r   for every valid entry e of row r
+ * out_fwd is the stored forward output that decides the ReLU mask (so that both sides of a
+ * comparison take that decision on the same numbers); it may be NULL when relu == 0.
+ * All accumulators are double and are ADDED to; dHsrc may be NULL.
+ */
+int orc_sage_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const int32_t *self_idx,
+                 const int32_t *indptr, const int32_t *idx, int64_t n_dst, const void *W_self,
+                 const void *W_neigh, const void *out_fwd, int32_t relu, const double *dOut,
+                 int32_t d_out, double *gW_self, double *gW_neigh, double *gbias, double *dHsrc)
+{
+    double *xs = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *mn = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *dz = (double *)malloc(sizeof(double) * (size_t)d_out);
+    if (!xs || !mn || !dz) { free(xs); free(mn); free(dz); return 2; }
+    for (int64_t r = 0; r < n_dst; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        for (int32_t k = 0; k < d_in; ++k) {
+            xs[k] = s < 0 ? 0.0 : load_elem(Hsrc, dtype, s * d_in + k);
+            mn[k] = 0.0;
+        }
+        int64_t c = 0;
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            if (idx[e] < 0) continue;
+            for (int32_t k = 0; k < d_in; ++k) mn[k] += load_elem(Hsrc, dtype, (int64_t)idx[e] * d_in + k);
+            ++c;
+        }
+        if (c > 0)
+            for (int32_t k = 0; k < d_in; ++k) mn[k] /= (double)c;
+        for (int32_t n = 0; n < d_out; ++n) {
+            int pass = !relu || load_elem(out_fwd, dtype, r * d_out + n) > 0.0;
+            dz[n] = pass ? dOut[r * d_out + n] : 0.0;
+            if (gbias) gbias[n] += dz[n];
+        }
+        for (int32_t k = 0; k < d_in; ++k)
+            for (int32_t n = 0; n < d_out; ++n) {
+                gW_self[(int64_t)k * d_out + n] += xs[k] * dz[n];
+                gW_neigh[(int64_t)k * d_out + n] += mn[k] * dz[n];
+            }
+        if (dHsrc) {
+            for (int32_t k = 0; k < d_in; ++k) {
+                double gs = 0.0, gm = 0.0;
+                for (int32_t n = 0; n < d_out; ++n) {
+                    gs += dz[n] * load_elem(W_self, dtype, (int64_t)k * d_out + n);
+                    gm += dz[n] * load_elem(W_neigh, dtype, (int64_t)k * d_out + n);
+                }
+                if (s >= 0) dHsrc[s * d_in + k] += gs;
+                if (c > 0)
+                    for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e)
+                        if (idx[e] >= 0) dHsrc[(int64_t)idx[e] * d_in + k] += gm / (double)c;
+            }
+        }
+    }
+    free(xs);
+    free(mn);
+    free(dz);
+    return 0;
+}
