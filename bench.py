@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--group", type=int, default=0, help="batches per pre-gather (0: the shape's default)")
     ap.add_argument("--streams", type=int, default=2,
                     help="HIP streams (each with its own buffers) that consecutive steps alternate over")
+    ap.add_argument("--backward", action="store_true",
+                    help="also run the layers' backward pass with in-place gradient accumulation (fp32 shapes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -115,6 +117,9 @@ def main():
     n_streams = max(1, args.streams)
     hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group) for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]      # default priority
+    if args.backward:
+        for h in hps:
+            h.enable_backward()
     hp = hps[0]
     sh = hp.shape
     n_total = args.warmup + args.steps
@@ -137,6 +142,8 @@ def main():
             ev[1].record(stream)
         for b in range(group):
             h.layers(b, st)
+            if args.backward:
+                h.backward(b, st)
         if ev is not None:      # an empty pair: what two event markers cost with nothing between
             ev[2].record(stream)
             ev[3].record(stream)
@@ -231,7 +238,7 @@ def main():
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges,
                    "feature_dim": cfg.d, "batch": cfg.batch, "fanouts": cfg.fanouts,
                    "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots,
-                   "streams": n_streams},
+                   "streams": n_streams, "backward": bool(args.backward)},
         "gather_GBps": gather_gbps,
         "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
         "unique_rows_per_step": U_avg,

@@ -200,6 +200,40 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               size_t ws_bytes, void *stream);
 
 /*
+ * GraphSAGE-mean layer backward with in-place gradient accumulation (paper section 5.1,
+ * steps 3-4: every micrograph batch runs forward and backward on the server it sits on and
+ * the gradients are accumulated until the subgraph is done; discussion section: the
+ * accumulated partial gradients are updated in place).  With the forward call's Hsrc,
+ * self_idx, indptr, idx, W_self, W_neigh and dOut = dL/d out:
+ *
+ *   dZ        = dOut where out_fwd > 0 (relu != 0), else dOut
+ *   gW_self  += x_self^T dZ      gW_neigh += mean^T dZ      gbias += column sums of dZ
+ *   dHsrc     = 0;  dHsrc[self_idx[r]] += dZ[r] W_self^T;
+ *               dHsrc[idx[e]] += (dZ[r] W_neigh^T) / c_r  for every valid entry e of row r
+ *
+ * dt       HOPGNN_F32 only in this version (EINVAL otherwise).
+ * out_fwd  DEVICE [n_dst x d_out], the stored forward output (decides the ReLU mask); may be
+ *          NULL when relu == 0.
+ * dOut     DEVICE [n_dst x d_out] fp32.
+ * gW_self, gW_neigh DEVICE [d_in x d_out] fp32 accumulators, ADDED to (the caller zeroes them
+ *          at the start of an iteration); gbias DEVICE [d_out] fp32 accumulator or NULL.
+ *          Bit-stable from run to run (partial sums are combined in a fixed order).
+ * dHsrc    DEVICE out [n_src x d_in] fp32 (overwritten), or NULL when the gradient of the
+ *          layer input is not needed (the first layer: features are not trained).  Uses float
+ *          atomic adds: bit-stable when every source row receives at most two contributions
+ *          (true for hopgnn_sample's slot trees), else the rounding depends on arrival order.
+ * ws       DEVICE scratch of hopgnn_sage_bwd_ws_bytes(dt, n_dst, d_in, d_out, dHsrc != NULL) bytes.
+ */
+size_t hopgnn_sage_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out, int32_t want_dh);
+
+hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                              const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                              int64_t n_dst, const void *W_self, const void *W_neigh, const void *out_fwd,
+                              int32_t relu, const float *dOut, int32_t d_out, float *gW_self,
+                              float *gW_neigh, float *gbias, float *dHsrc, void *ws, size_t ws_bytes,
+                              void *stream);
+
+/*
  * Micrograph merging (paper section 5.3).  HOST-only bookkeeping, no device work.
  *
  * counts is a HOST matrix [n_models x n_steps], row-major: root vertices model m trains at

@@ -23,7 +23,8 @@ PG_AUTO, PG_BITMAP, PG_RADIX = 0, 1, 2
 
 EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_pregather_ws_bytes", "hopgnn_pregather", "hopgnn_gather",
-           "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_micrograph_locality",
+           "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_sage_bwd_ws_bytes", "hopgnn_sage_bwd",
+           "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report"]
 
@@ -80,6 +81,12 @@ def load_library() -> ctypes.CDLL:
                                   c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p,
                                   c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p,
                                   c.c_size_t, c.c_void_p]
+    L.hopgnn_sage_bwd_ws_bytes.restype = c.c_size_t
+    L.hopgnn_sage_bwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
+    L.hopgnn_sage_bwd.restype = c.c_int
+    L.hopgnn_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
+                                  c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_micrograph_locality.restype = c.c_int
     L.hopgnn_micrograph_locality.argtypes = [c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
                                              c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -218,3 +225,20 @@ def hopgnn_merge_apply(counts, ts: int):
     if n < 0:
         raise HopgnnError("hopgnn_merge_apply: invalid argument")
     return [[int(flat[m * n + t]) for t in range(n)] for m in range(n_models)]
+
+
+def hopgnn_sage_bwd_ws_bytes(dtype: torch.dtype, n_dst: int, d_in: int, d_out: int, want_dh: bool) -> int:
+    return int(load_library().hopgnn_sage_bwd_ws_bytes(DTYPE_OF[dtype], n_dst, d_in, d_out, 1 if want_dh else 0))
+
+
+def hopgnn_sage_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                    idx: torch.Tensor, n_dst: int, W_self: torch.Tensor, W_neigh: torch.Tensor,
+                    out_fwd: Optional[torch.Tensor], relu: bool, dOut: torch.Tensor, gW_self: torch.Tensor,
+                    gW_neigh: torch.Tensor, gbias: Optional[torch.Tensor], dHsrc: Optional[torch.Tensor],
+                    ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_bwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                        _ptr(idx), n_dst, _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd),
+                                        1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
+                                        _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_sage_bwd")

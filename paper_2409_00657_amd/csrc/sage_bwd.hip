@@ -1,0 +1,399 @@
+// hopgnn_sage_bwd: backward of one GraphSAGE-mean layer with in-place accumulation of
+// the weight gradients (paper section 5.1, steps 3-4: every micrograph batch runs forward
+// and backward where it sits and the gradients are accumulated until the subgraph is done;
+// the discussion section: accumulated partial gradients are updated in place).
+//
+//   dZ        = dOut masked by the stored forward output (ReLU)          bwd_mask
+//   G         = [x_self | mean]^T dZ      (2*d_in x d_out)               bwd_weight_grad (MFMA)
+//   gW_self  += G[:d_in], gW_neigh += G[d_in:], gbias += colsum(dZ)      bwd_weight_reduce
+//   [dXs|dM]  = dZ [W_self ; W_neigh]^T   (n_dst x 2*d_in)               bwd_input_grad (MFMA)
+//   dHsrc[self_idx[r]] += dXs[r];  dHsrc[idx[e]] += dM[r] / c_r          bwd_scatter
+//
+// fp32 activations only in this version.  The weight gradient contracts over the destination
+// rows, which are split over workgroups; the partial tiles are summed in split order by a
+// second kernel, so gW/gbias are bit-stable from run to run.  dHsrc uses float atomic adds:
+// bit-stable when a source row receives at most two contributions (always the case for the
+// slot-tree layout of hopgnn_sample: one self term, one parent), otherwise the rounding
+// depends on arrival order.
+#include "sage_common.hpp"
+
+namespace hopgnn {
+
+constexpr int kBwdThreads = 256;
+
+// ---------------------------------------------------------------- dZ mask --
+
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_mask(const float4* __restrict__ out_fwd, const float4* __restrict__ dOut, int64_t n4, float4* __restrict__ dZ) {
+    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (i >= n4) return;
+    const float4 o = out_fwd[i];
+    float4 g = dOut[i];
+    g.x = o.x > 0.f ? g.x : 0.f;
+    g.y = o.y > 0.f ? g.y : 0.f;
+    g.z = o.z > 0.f ? g.z : 0.f;
+    g.w = o.w > 0.f ? g.w : 0.f;
+    dZ[i] = g;
+}
+
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_mask_elem(const float* __restrict__ out_fwd, const float* __restrict__ dOut, int64_t n, float* __restrict__ dZ) {
+    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (i < n) dZ[i] = out_fwd[i] > 0.f ? dOut[i] : 0.f;
+}
+
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_zero_elem(float* __restrict__ p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_zero(float4* __restrict__ p, int64_t n4) {
+    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// ---------------------------------------------------------- weight gradient --
+//
+// G[k][n] = sum_r A[r][k] dZ[r][n] with A = [x_self | mean].  The contraction index r is the
+// MFMA's K dimension: for v_mfma_f32_32x32x2_f32 lane l feeds A[r + l/32][k0 + l%32] and
+// dZ[r + l/32][n0 + l%32], i.e. both operands are plain coalesced reads of 32 consecutive
+// floats of a row - no LDS, no transposition.  A wave owns a 64 x 64 piece of G (2 x 2 MFMA
+// tiles: two A values and two dZ values feed four MFMAs), a workgroup (4 waves, 2 x 2) a
+// 128 x 128 tile, for the rows [split*rows_per_split, ...); it writes the tile to
+// partial[split].  Workgroups of the first k-tile row also produce the column sums of dZ.
+constexpr int kGradTile = 128;
+
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
+                const float* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
+                int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
+                float* __restrict__ bias_partial) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, l32 = lane & 31;
+    const int K = 2 * d_in;
+    const uint32_t tk = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    const int k0 = (int)tk * kGradTile + (wave >> 1) * 64;    // first row of G of this wave
+    const int n0 = (int)tn * kGradTile + (wave & 1) * 64;     // first column
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
+    const int64_t r1 = r0 + rows_per_split < n_dst ? r0 + rows_per_split : n_dst;
+    int k[2], n[2];
+    bool k_ok[2], n_ok[2], k_self[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        k[t] = k0 + t * 32 + l32;
+        n[t] = n0 + t * 32 + l32;
+        k_ok[t] = k[t] < K;
+        n_ok[t] = n[t] < d_out;
+        k_self[t] = k[t] < d_in;
+    }
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    float colsum[2] = {0.f, 0.f};
+    constexpr int U = 2;   // MFMA steps (2 rows each) per loop trip
+    for (int64_t rb = r0; rb < r1; rb += 2 * U) {
+        float a[U][2], b[U][2];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t r = rb + 2 * u + g;
+            const bool r_ok = r < r1;
+            int64_t s = -1;
+            if (r_ok) s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                a[u][t] = 0.f;
+                b[u][t] = 0.f;
+                if (r_ok && n_ok[t]) b[u][t] = dZ[r * d_out + n[t]];
+                if (r_ok && k_ok[t]) {
+                    if (k_self[t]) {
+                        if (s >= 0) a[u][t] = Hsrc[s * d_in + k[t]];
+                    } else {
+                        a[u][t] = Mean[r * d_in + (k[t] - d_in)];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
+            colsum[0] += b[u][0];
+            colsum[1] += b[u][1];
+        }
+    }
+    // partial[split][k][n]; accumulator register e of lane l holds G row 8*(e/4)+4*(l/32)+e%4, col l%32
+    float* P = partial + (int64_t)blockIdx.y * K * d_out;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (!n_ok[j]) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int kk = k0 + i * 32 + 8 * (e / 4) + 4 * g + (e & 3);
+                if (kk < K) P[(int64_t)kk * d_out + n[j]] = acc[i][j][e];
+            }
+        }
+    if (bias_partial != nullptr && tk == 0 && (wave >> 1) == 0) {   // one wave per 64-column block
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const float c = colsum[j] + __shfl_xor(colsum[j], 32, kWave);   // even rows + odd rows
+            if (g == 0 && n_ok[j]) bias_partial[(int64_t)blockIdx.y * d_out + n[j]] = c;
+        }
+    }
+}
+
+// gW += sum over splits (in split order) of the partial tiles; same for the bias.
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ bias_partial, int32_t n_splits,
+                  int32_t d_in, int32_t d_out, float* __restrict__ gW_self, float* __restrict__ gW_neigh,
+                  float* __restrict__ gbias) {
+    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    const int64_t per = (int64_t)2 * d_in * d_out;
+    if (i < per) {
+        float s = 0.f;
+        for (int32_t p = 0; p < n_splits; ++p) s += partial[(int64_t)p * per + i];
+        const int64_t half = (int64_t)d_in * d_out;
+        if (i < half) gW_self[i] += s;
+        else gW_neigh[i - half] += s;
+    } else if (gbias != nullptr && i < per + d_out) {
+        const int64_t nn = i - per;
+        float s = 0.f;
+        for (int32_t p = 0; p < n_splits; ++p) s += bias_partial[(int64_t)p * d_out + nn];
+        gbias[nn] += s;
+    }
+}
+
+// ----------------------------------------------------------- input gradient --
+//
+// D[r][j] = sum_n dZ[r][n] Wcat[j][n], j over the 2*d_in rows of [W_self ; W_neigh].  Both
+// operands have the contraction index contiguous, so both sit in LDS row-major [64][BK+4] and
+// are read as 128-bit words: lane group g = l/32 takes the four n values 4g..4g+3 of an 8-wide
+// block and the block's four MFMAs pair the i-th values (a permutation of the summation order).
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_input_grad(const float* __restrict__ dZ, const float* __restrict__ Wself, const float* __restrict__ Wneigh,
+               int64_t n_dst, int32_t d_in, int32_t d_out, float* __restrict__ D) {
+    constexpr int BM = 64, BN = 64, BK = 16, LD = BK + 4;
+    __shared__ __attribute__((aligned(16))) float As[BM][LD];
+    __shared__ __attribute__((aligned(16))) float Bs[BN][LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, l32 = lane & 31;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t row0 = (int64_t)blockIdx.x * BM;
+    const int col0 = blockIdx.y * BN;
+    const int N = 2 * d_in;
+    const bool vec = (d_out & 3) == 0;
+
+    // one 16-byte item of each tile per thread: row tid/4, words (tid%4)*4 .. +3
+    const int lr = tid >> 2, lk = (tid & 3) * 4;
+    const int64_t ar = row0 + lr;
+    const int bj = col0 + lr;
+    const float* arow = ar < n_dst ? dZ + ar * d_out : nullptr;
+    const float* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
+                               : nullptr;
+    auto load4 = [&](const float* row, int kq) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row != nullptr) {
+            if (vec && kq + 3 < d_out) {
+                v = *reinterpret_cast<const float4*>(row + kq);
+            } else {
+                if (kq + 0 < d_out) v.x = row[kq + 0];
+                if (kq + 1 < d_out) v.y = row[kq + 1];
+                if (kq + 2 < d_out) v.z = row[kq + 2];
+                if (kq + 3 < d_out) v.w = row[kq + 3];
+            }
+        }
+        return v;
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    const int n_tiles = (d_out + BK - 1) / BK;
+    float4 ra = load4(arow, lk), rb = load4(brow, lk);
+    for (int t = 0; t < n_tiles; ++t) {
+        __syncthreads();
+        *reinterpret_cast<float4*>(&As[lr][lk]) = ra;
+        *reinterpret_cast<float4*>(&Bs[lr][lk]) = rb;
+        __syncthreads();
+        if (t + 1 < n_tiles) {
+            ra = load4(arow, (t + 1) * BK + lk);
+            rb = load4(brow, (t + 1) * BK + lk);
+        }
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+            const float4 a = *reinterpret_cast<const float4*>(&As[wm * 32 + l32][kk + 4 * g]);
+            const float4 b = *reinterpret_cast<const float4*>(&Bs[wn * 32 + l32][kk + 4 * g]);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b.x, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+    }
+    const int col = col0 + wn * 32 + l32;
+    if (col < N) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t row = row0 + wm * 32 + 8 * (i / 4) + 4 * g + (i & 3);
+            if (row < n_dst) D[row * N + col] = acc[i];
+        }
+    }
+}
+
+// dHsrc[self_idx[r]] += D[r][:d_in];  dHsrc[idx[e]] += D[r][d_in:] / c_r for the valid entries e.
+// `group` lanes (power of two) per destination row, lane j owns columns j, j+group, ...
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_scatter(const float* __restrict__ D, const int32_t* __restrict__ self_idx, const int32_t* __restrict__ indptr,
+            const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group, float* __restrict__ dHsrc) {
+    const int64_t gid = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    const int64_t r = gid / group;
+    const int32_t j = (int32_t)(gid - r * group);
+    if (r >= n_dst) return;
+    const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    int32_t cnt = 0;
+    for (int32_t e = beg; e < end; ++e) cnt += idx[e] >= 0 ? 1 : 0;
+    const float inv = cnt > 0 ? 1.f / (float)cnt : 0.f;
+    const float* Dr = D + r * (2 * (int64_t)d_in);
+    for (int32_t c = j; c < d_in; c += group) {
+        if (s >= 0) atomicAdd(&dHsrc[s * d_in + c], Dr[c]);
+        if (cnt > 0) {
+            const float m = Dr[d_in + c] * inv;
+            for (int32_t e = beg; e < end; ++e) {
+                const int32_t u = idx[e];
+                if (u >= 0) atomicAdd(&dHsrc[(int64_t)u * d_in + c], m);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ host --
+
+struct BwdWs {
+    size_t mean_bytes, zero_bytes, dz_bytes, partial_bytes, bias_bytes, d_bytes, total;
+    int32_t rows_per_split, n_splits;
+};
+
+static BwdWs bwd_ws_layout(int64_t n_dst, int32_t d_in, int32_t d_out, int want_dh) {
+    BwdWs L{};
+    const int64_t nd = n_dst > 0 ? n_dst : 1;
+    L.mean_bytes = align_up((size_t)nd * d_in * 4, 256);
+    L.zero_bytes = align_up(((size_t)2 * d_in + 64) * 4, 256);
+    L.dz_bytes = align_up((size_t)nd * d_out * 4, 256);
+    // enough splits to fill the chip (about 2048 waves), at least 64 rows each
+    const int64_t tiles = ceil_div(2 * (int64_t)d_in, kGradTile) * ceil_div(d_out, kGradTile);
+    int64_t splits = ceil_div(512, tiles);
+    int64_t rows = ceil_div(nd, splits);
+    if (rows < 64) rows = 64;
+    rows = (rows + 7) / 8 * 8;
+    L.rows_per_split = (int32_t)rows;
+    L.n_splits = (int32_t)ceil_div(nd, rows);
+    L.partial_bytes = align_up((size_t)L.n_splits * 2 * d_in * d_out * 4, 256);
+    L.bias_bytes = align_up((size_t)L.n_splits * d_out * 4, 256);
+    L.d_bytes = want_dh ? align_up((size_t)nd * 2 * d_in * 4, 256) : 0;
+    L.total = L.mean_bytes + L.zero_bytes + L.dz_bytes + L.partial_bytes + L.bias_bytes + L.d_bytes;
+    return L;
+}
+
+}  // namespace hopgnn
+
+using namespace hopgnn;
+
+extern "C" size_t hopgnn_sage_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out,
+                                           int32_t want_dh) {
+    if (dt != HOPGNN_F32 || n_dst < 0 || d_in < 1 || d_out < 1) return 0;
+    return bwd_ws_layout(n_dst, d_in, d_out, want_dh).total;
+}
+
+extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                         const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                         int64_t n_dst, const void* W_self, const void* W_neigh,
+                                         const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out,
+                                         float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
+                                         size_t ws_bytes, void* stream) {
+    if (dt != HOPGNN_F32) return HOPGNN_EINVAL;   // 2-byte activations: not in this version
+    if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
+    if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
+    if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dHsrc != nullptr && n_src > 0) {
+        if (!aligned(dHsrc, 16) || ((int64_t)n_src * d_in) % 4 != 0) {   // a fill kernel, never a memset node
+            const int64_t n = (int64_t)n_src * d_in;
+            hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s, dHsrc, n);
+            HOPGNN_LAUNCH_CHECK();
+        } else {
+            const int64_t n4 = (int64_t)n_src * d_in / 4;
+            hipLaunchKernelGGL(bwd_zero, dim3((unsigned)ceil_div(n4, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               reinterpret_cast<float4*>(dHsrc), n4);
+            HOPGNN_LAUNCH_CHECK();
+        }
+    }
+    if (n_dst == 0) return HOPGNN_OK;
+    if (indptr == nullptr || W_self == nullptr || W_neigh == nullptr || dOut == nullptr || gW_self == nullptr ||
+        gW_neigh == nullptr || ws == nullptr || (relu && out_fwd == nullptr))
+        return HOPGNN_EINVAL;
+    if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
+    if (!aligned(ws, 256)) return HOPGNN_EINVAL;
+    const BwdWs L = bwd_ws_layout(n_dst, d_in, d_out, dHsrc != nullptr);
+    if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
+    char* p = static_cast<char*>(ws);
+    float* mean = reinterpret_cast<float*>(p);
+    void* zero = p + L.mean_bytes;
+    float* dz_buf = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes);
+    float* partial = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes + L.dz_bytes);
+    float* bias_partial = reinterpret_cast<float*>(reinterpret_cast<char*>(partial) + L.partial_bytes);
+    float* D = reinterpret_cast<float*>(reinterpret_cast<char*>(bias_partial) + L.bias_bytes);
+    if (n_src == 0) Hsrc = zero;   // nothing is read from it unmasked
+
+    // the means again (same kernel as the forward pass)
+    hopgnn_status st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s);
+    if (st != HOPGNN_OK) return st;
+
+    const float* dZ = dOut;
+    if (relu) {
+        const int64_t n = n_dst * d_out;
+        if (n % 4 == 0 && aligned(out_fwd, 16) && aligned(dOut, 16))
+            hipLaunchKernelGGL(bwd_mask, dim3((unsigned)ceil_div(n / 4, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               static_cast<const float4*>(out_fwd), reinterpret_cast<const float4*>(dOut), n / 4,
+                               reinterpret_cast<float4*>(dz_buf));
+        else
+            hipLaunchKernelGGL(bwd_mask_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               static_cast<const float*>(out_fwd), dOut, n, dz_buf);
+        HOPGNN_LAUNCH_CHECK();
+        dZ = dz_buf;
+    }
+
+    const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
+    hipLaunchKernelGGL(bwd_weight_grad, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
+                       static_cast<const float*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out, L.rows_per_split,
+                       tiles_n, partial, gbias != nullptr ? bias_partial : nullptr);
+    HOPGNN_LAUNCH_CHECK();
+    const int64_t red = (int64_t)2 * d_in * d_out + d_out;
+    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kBwdThreads)), dim3(kBwdThreads), 0, s, partial,
+                       bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias);
+    HOPGNN_LAUNCH_CHECK();
+
+    if (dHsrc != nullptr && n_src > 0) {
+        const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
+        if (gy > 65535) return HOPGNN_ERANGE;
+        hipLaunchKernelGGL(bwd_input_grad, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0, s,
+                           dZ, static_cast<const float*>(W_self), static_cast<const float*>(W_neigh), n_dst, d_in,
+                           d_out, D);
+        HOPGNN_LAUNCH_CHECK();
+        const int group = mean_group(d_in);
+        hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc);
+        HOPGNN_LAUNCH_CHECK();
+    }
+    return HOPGNN_OK;
+}

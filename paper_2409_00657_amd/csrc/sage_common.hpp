@@ -1,0 +1,201 @@
+// Pieces of the GraphSAGE-mean layer shared by the forward (sage.hip) and backward
+// (sage_bwd.hip) translation units: element types, the segmented-mean kernels and their launcher.
+#pragma once
+#include "common.hpp"
+
+namespace hopgnn {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
+// ----------------------------------------------------------- element types --
+
+struct TrF32 {
+    using store_t = float;
+    static constexpr int kPer16 = 4;
+    static constexpr hopgnn_dtype kDt = HOPGNN_F32;
+    __device__ static __forceinline__ float to_f(float x) { return x; }
+    __device__ static __forceinline__ float from_f(float x) { return x; }
+};
+
+struct TrBF16 {
+    using store_t = uint16_t;
+    static constexpr int kPer16 = 8;
+    static constexpr hopgnn_dtype kDt = HOPGNN_BF16;
+    __device__ static __forceinline__ float to_f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+    __device__ static __forceinline__ uint16_t from_f(float x) {   // round to nearest even
+        uint32_t u = __float_as_uint(x);
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);   // quiet NaN
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+};
+
+struct TrF16 {
+    using store_t = _Float16;
+    static constexpr int kPer16 = 8;
+    static constexpr hopgnn_dtype kDt = HOPGNN_F16;
+    __device__ static __forceinline__ float to_f(_Float16 h) { return (float)h; }
+    __device__ static __forceinline__ _Float16 from_f(float x) { return (_Float16)x; }
+};
+
+template <typename Tr>
+union Pack16 {
+    uint4 v;
+    typename Tr::store_t e[Tr::kPer16];
+};
+
+// ------------------------------------------------------------ segmented mean --
+
+// Side job of the mean kernels for 2-byte types: the projection wants the weights with k
+// contiguous, Wt[n][k] = (k < d_in ? W_self[k][n] : W_neigh[k - d_in][n]), zero outside
+// [0, 2*d_in) x [0, d_out).  The workgroups after the last mean workgroup each transpose one
+// 32 x 32 tile through LDS (coalesced reads and writes), which saves a launch per layer.
+struct TransposeJob {
+    const uint16_t* Wself;
+    const uint16_t* Wneigh;
+    uint16_t* Wt;
+    int32_t d_in, d_out, KP, NP;
+    uint32_t first_block;   // workgroups >= first_block transpose; n_tiles_k = KP / 32
+};
+
+__device__ __forceinline__ void transpose_w_tile(const TransposeJob& J, uint32_t tile_id) {
+    __shared__ uint16_t tile[32][33];
+    const uint32_t tiles_k = J.KP / 32;
+    const int k0 = (tile_id % tiles_k) * 32, n0 = (tile_id / tiles_k) * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+    for (int j = ty; j < 32; j += 8) {
+        const int k = k0 + j, n = n0 + tx;
+        uint16_t v = 0;
+        if (k < 2 * J.d_in && n < J.d_out)
+            v = k < J.d_in ? J.Wself[(int64_t)k * J.d_out + n] : J.Wneigh[(int64_t)(k - J.d_in) * J.d_out + n];
+        tile[j][tx] = v;
+    }
+    __syncthreads();
+    for (int j = ty; j < 32; j += 8) {
+        const int n = n0 + j, k = k0 + tx;
+        if (n < J.NP && k < J.KP) J.Wt[(int64_t)n * J.KP + k] = tile[tx][j];
+    }
+}
+
+
+constexpr int kMeanThreads = 256;
+constexpr int kMeanUnroll = 4;
+
+// Vector path: d_in * sizeof(elem) is a multiple of 16.  `group` lanes (a power of
+// two <= 64) share one destination row; lane g of the group owns 16-byte word
+// g, g+group, ... of the row.  Four neighbour rows are fetched per step; absent
+// entries (negative index) are skipped by predication, which measured faster than
+// reading a stand-in row and masking it out (whole dead micrographs are common on
+// graphs with isolated vertices).  The sum runs in entry order.
+template <typename Tr>
+__global__ void __launch_bounds__(kMeanThreads)
+sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
+              const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
+              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job) {
+    if (blockIdx.x >= job.first_block) {
+        transpose_w_tile(job, blockIdx.x - job.first_block);
+        return;
+    }
+    if (blockIdx.x == 0)   // the projection reads absent rows and the K padding from this row
+        for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
+    const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
+    const int64_t r = gid / group;
+    const int32_t g = (int32_t)(gid - r * group);
+    if (r >= n_dst) return;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    for (int32_t c = g; c < words_per_row; c += group) {
+        float acc[Tr::kPer16];
+#pragma unroll
+        for (int i = 0; i < Tr::kPer16; ++i) acc[i] = 0.f;
+        int32_t cnt = 0;
+        for (int32_t e = beg; e < end; e += kMeanUnroll) {
+            int32_t u[kMeanUnroll];
+            Pack16<Tr> v[kMeanUnroll];
+#pragma unroll
+            for (int k = 0; k < kMeanUnroll; ++k) u[k] = (e + k < end) ? idx[e + k] : -1;
+#pragma unroll
+            for (int k = 0; k < kMeanUnroll; ++k)
+                if (u[k] >= 0) v[k].v = Hsrc[(int64_t)u[k] * words_per_row + c];
+#pragma unroll
+            for (int k = 0; k < kMeanUnroll; ++k)
+                if (u[k] >= 0) {
+#pragma unroll
+                    for (int i = 0; i < Tr::kPer16; ++i) acc[i] += Tr::to_f(v[k].e[i]);
+                    ++cnt;
+                }
+        }
+        Pack16<Tr> o;
+        const float fc = (float)cnt;
+#pragma unroll
+        for (int i = 0; i < Tr::kPer16; ++i) o.e[i] = Tr::from_f(cnt > 0 ? acc[i] / fc : 0.f);
+        Mean[r * words_per_row + c] = o.v;
+    }
+}
+
+// Element path for rows that are not a whole number of 16-byte words.
+template <typename Tr>
+__global__ void __launch_bounds__(kMeanThreads)
+sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
+               const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
+               typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words,
+               TransposeJob job) {
+    if (blockIdx.x >= job.first_block) {
+        transpose_w_tile(job, blockIdx.x - job.first_block);
+        return;
+    }
+    if (blockIdx.x == 0)
+        for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
+    const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
+    const int64_t r = gid / group;
+    const int32_t g = (int32_t)(gid - r * group);
+    if (r >= n_dst) return;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    for (int32_t c = g; c < d_in; c += group) {
+        float acc = 0.f;
+        int32_t cnt = 0;
+        for (int32_t e = beg; e < end; ++e) {
+            const int32_t u = idx[e];
+            if (u >= 0) {
+                acc += Tr::to_f(Hsrc[(int64_t)u * d_in + c]);
+                ++cnt;
+            }
+        }
+        Mean[r * d_in + c] = Tr::from_f(cnt > 0 ? acc / (float)cnt : 0.f);
+    }
+}
+
+// ------------------------------------------------------------------ launch --
+
+static inline int mean_group(int units) {   // lanes per destination row: power of two, 1..64
+    int g = 1;
+    while (g < units && g < 64) g *= 2;
+    return g;
+}
+
+template <typename Tr>
+static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const int32_t* idx,
+                                 int64_t n_dst, int32_t d_in, void* mean, void* zero_row,
+                                 size_t zero_bytes, TransposeJob job, uint32_t n_transpose_tiles, hipStream_t s) {
+    using T = typename Tr::store_t;
+    const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
+    const int units = vec ? d_in / Tr::kPer16 : d_in;
+    const int group = mean_group(units);
+    const int64_t mean_blocks = ceil_div(n_dst * group, kMeanThreads);
+    if (mean_blocks + n_transpose_tiles >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    job.first_block = (uint32_t)mean_blocks;
+    const int64_t blocks = mean_blocks + n_transpose_tiles;
+    if (vec)
+        hipLaunchKernelGGL(sage_mean_vec<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
+                           static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
+                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
+    else
+        hipLaunchKernelGGL(sage_mean_elem<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
+                           static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
+                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+}  // namespace hopgnn

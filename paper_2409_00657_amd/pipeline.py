@@ -149,6 +149,45 @@ class HotPath:
             self.layer(b, k, st)
         return self.H[-1]
 
+    # -- backward (fp32 activations) ------------------------------------------
+
+    def enable_backward(self) -> None:
+        """Allocate gradient accumulators (one set per layer, fp32, zero) and the buffers of the
+        backward pass.  The loss used by the harness is L = 1/2 |H_L|^2, so dL/dH_L = H_L."""
+        if self.X.dtype != torch.float32:
+            raise hb.HopgnnError("backward is implemented for fp32 activations")
+        sh, dev = self.shape, self.X.device
+        L = sh.n_layers
+        self.gW = [(torch.zeros_like(Ws, dtype=torch.float32), torch.zeros_like(Wn, dtype=torch.float32),
+                    None if b is None else torch.zeros_like(b, dtype=torch.float32)) for Ws, Wn, b in self.weights]
+        hidden = self.weights[0][0].shape[1]
+        # dH[k] = gradient of layer k's output rows (k = 1..L-1), produced by layer k+1's backward
+        self.dH = [torch.empty((sh.n_dst(k), hidden), dtype=torch.float32, device=dev) for k in range(1, L)]
+        ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(torch.float32, sh.n_dst(k), self.weights[k - 1][0].shape[0],
+                                                   hidden, k > 1) for k in range(1, L + 1))
+        self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._bwd_args = []
+        for b in range(self.group):
+            per_batch = []
+            for k in range(L, 0, -1):
+                fwd = self._layer_args[b][k - 1]
+                (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, _bias, d_out, relu, out, _ws, _wsb) = fwd
+                d_out_grad = self.H[L - 1].data_ptr() if k == L else self.dH[k - 1].data_ptr()
+                gWs, gWn, gb = self.gW[k - 1]
+                per_batch.append((src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, out, relu, d_out_grad,
+                                  d_out, gWs.data_ptr(), gWn.data_ptr(), None if gb is None else gb.data_ptr(),
+                                  self.dH[k - 2].data_ptr() if k > 1 else None, self.bwd_ws.data_ptr(),
+                                  self.bwd_ws.numel()))
+            self._bwd_args.append(per_batch)
+
+    def backward(self, b: int, stream=None) -> None:
+        """Backward of batch b's layers, last to first; weight gradients accumulate in self.gW."""
+        st = self._stream(stream)
+        for a in self._bwd_args[b]:
+            rc = self._lib.hopgnn_sage_bwd(*a, st)
+            if rc:
+                hb._check(rc, "hopgnn_sage_bwd")
+
     # -- whole steps ---------------------------------------------------------
 
     def run_batch(self, seeds: torch.Tensor, key: int, stream=None) -> torch.Tensor:

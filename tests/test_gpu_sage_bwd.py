@@ -1,0 +1,138 @@
+"""GPU parity of the layer backward against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import rel_err, to_bits, to_f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+F32 = 0
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2409_00657_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _rand_csr(rng, n_dst, n_src, max_len, p_invalid=0.15):
+    lens = rng.integers(0, max_len + 1, size=n_dst)
+    indptr = np.zeros(n_dst + 1, np.int32)
+    indptr[1:] = np.cumsum(lens)
+    idx = rng.integers(0, n_src, size=int(indptr[-1])).astype(np.int32)
+    idx[rng.random(len(idx)) < p_invalid] = -1
+    return indptr, idx
+
+
+def _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, relu, dOut, want_dh, use_bias, acc_init=None):
+    n_src, d_in = H.shape
+    d_out = Ws.shape[1]
+    n_dst = len(indptr) - 1
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    gWs = torch.zeros((d_in, d_out), device=DEV) if acc_init is None else acc_init[0].clone()
+    gWn = torch.zeros((d_in, d_out), device=DEV) if acc_init is None else acc_init[1].clone()
+    gb = (torch.zeros(d_out, device=DEV) if acc_init is None else acc_init[2].clone()) if use_bias else None
+    dH = torch.full((n_src, d_in), 7.0, device=DEV) if want_dh else None     # must be overwritten
+    ws = torch.empty(hb.hopgnn_sage_bwd_ws_bytes(torch.float32, n_dst, d_in, d_out, want_dh), dtype=torch.uint8,
+                     device=DEV)
+    ws.fill_(0x5A)
+    hb.hopgnn_sage_bwd(t(H), n_src, t(self_idx), t(indptr), t(idx), n_dst, t(Ws), t(Wn), t(out_fwd), relu, t(dOut),
+                       gWs, gWn, gb, dH, ws)
+    torch.cuda.synchronize()
+    return gWs, gWn, gb, dH
+
+
+@pytest.mark.parametrize("shape", [(300, 200, 32, 32, 6), (1500, 1111, 128, 128, 12), (4000, 777, 100, 256, 16),
+                                   (500, 129, 20, 12, 5), (300, 65, 7, 5, 4), (3000, 9000, 64, 128, 3)])
+def test_sage_bwd_vs_oracle(hb, orc, shape):
+    n_src, n_dst, d_in, d_out, max_len = shape
+    rng = np.random.default_rng(n_src * 7 + d_in)
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    H = f(n_src, d_in)
+    Ws = f(d_in, d_out) / np.float32(np.sqrt(d_in))
+    Wn = f(d_in, d_out) / np.float32(np.sqrt(d_in))
+    dOut = f(n_dst, d_out)
+    indptr, idx = _rand_csr(rng, n_dst, n_src, max_len)
+    self_idx = rng.integers(0, n_src, size=n_dst).astype(np.int32)
+    self_idx[rng.random(n_dst) < 0.05] = -1
+    out_fwd = orc.round_store(orc.sage_fwd(H, F32, self_idx, indptr, idx, Ws, Wn, None, True), F32)
+    for relu, want_dh, use_bias in [(True, True, True), (False, False, False)]:
+        ref = orc.sage_bwd(H, F32, self_idx, indptr, idx, Ws, Wn, out_fwd if relu else None, relu,
+                           dOut.astype(np.float64), want_dH=want_dh)
+        gWs, gWn, gb, dH = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd if relu else None, relu, dOut,
+                                    want_dh, use_bias)
+        assert rel_err(to_f64(gWs), ref[0]) <= 2e-5, (shape, relu)
+        assert rel_err(to_f64(gWn), ref[1]) <= 2e-5, (shape, relu)
+        if use_bias:
+            assert rel_err(to_f64(gb), ref[2]) <= 2e-5
+        if want_dh:
+            assert rel_err(to_f64(dH), ref[3]) <= 2e-5
+    # accumulation in place: a second call adds the same amount again, bit for bit
+    g1 = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, True, dOut, False, True)
+    g2 = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, True, dOut, False, True, acc_init=g1[:3])
+    for a, b in zip(g1[:3], g2[:3]):
+        assert torch.equal(b, a + a)
+    # weight gradients are bit-stable from run to run
+    g3 = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, True, dOut, False, True)
+    for a, b in zip(g1[:3], g3[:3]):
+        assert torch.equal(a, b)
+
+
+def test_backward_chain_on_a_sampled_batch(hb, orc):
+    """Two layers of config 1: forward on the GPU, then backward from a given output gradient,
+    layer 2 then layer 1; gradients against the oracle, layer by layer from the same inputs."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    cfg = synth.CONFIGS[1]
+    g = cfg.make_graph(device=DEV)
+    X = cfg.make_features(device=DEV)
+    W = cfg.make_weights(device=DEV)
+    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts)
+    seeds = synth.seeds(cfg.n_vertices, cfg.batch, 5, device=DEV)
+    hp.run_batch(seeds, 5)
+    torch.cuda.synchronize()
+    sh = hp.shape
+    B, L = sh.n_seeds, sh.n_layers
+    U = int(hp.n_uniq.item())
+    ids = hp.ids.cpu().numpy()
+    remap = hp.remap.cpu().numpy()
+    indptr = hp.indptr.cpu().numpy()
+    slot_idx = hp.slot_idx[0].cpu().numpy()
+    rng = np.random.default_rng(0)
+    dOut2 = rng.standard_normal((B, cfg.hidden)).astype(np.float32)
+    # layer 2 (last, no ReLU): input H1 (slot rows), identity self, idx = slot_idx
+    n_dst2, nnz2 = sh.n_dst(2), sh.nnz(2)
+    H1 = hp.H[0]
+    n_src2 = sh.n_dst(1)
+    g2 = _run_gpu(hb, H1.cpu().numpy(), None, indptr[:n_dst2 + 1], slot_idx[:nnz2], W[1][0].cpu().numpy(),
+                  W[1][1].cpu().numpy(), None, False, dOut2, True, False)
+    ref2 = orc.sage_bwd(to_bits(H1), F32, None, indptr[:n_dst2 + 1], slot_idx[:nnz2], to_bits(W[1][0]),
+                        to_bits(W[1][1]), None, False, dOut2.astype(np.float64))
+    assert rel_err(to_f64(g2[0]), ref2[0]) <= 2e-5 and rel_err(to_f64(g2[1]), ref2[1]) <= 2e-5
+    assert rel_err(to_f64(g2[3]), ref2[3]) <= 2e-5
+    # every source slot has at most one parent and one self term: dH1 is bit-stable
+    g2b = _run_gpu(hb, H1.cpu().numpy(), None, indptr[:n_dst2 + 1], slot_idx[:nnz2], W[1][0].cpu().numpy(),
+                   W[1][1].cpu().numpy(), None, False, dOut2, True, False)
+    assert torch.equal(g2[3], g2b[3])
+    # layer 1 (ReLU): input Xu through remap; the feature gradient is not needed
+    n_dst1, nnz1 = sh.n_dst(1), sh.nnz(1)
+    dH1 = g2[3].cpu().numpy()
+    Xu = hp.Xu[:U]
+    g1 = _run_gpu(hb, Xu.cpu().numpy(), remap[:n_dst1], indptr[:n_dst1 + 1], remap[B:B + nnz1],
+                  W[0][0].cpu().numpy(), W[0][1].cpu().numpy(), H1.cpu().numpy(), True, dH1, False, False)
+    ref1 = orc.sage_bwd(to_bits(Xu), F32, remap[:n_dst1], indptr[:n_dst1 + 1], remap[B:B + nnz1],
+                        to_bits(W[0][0]), to_bits(W[0][1]), to_bits(H1), True, dH1.astype(np.float64), want_dH=False)
+    assert rel_err(to_f64(g1[0]), ref1[0]) <= 2e-5 and rel_err(to_f64(g1[1]), ref1[1]) <= 2e-5
+
+
+def test_sage_bwd_rejects_unsupported(hb):
+    H = torch.zeros((4, 8), dtype=torch.bfloat16, device=DEV)
+    W = torch.zeros((8, 8), dtype=torch.bfloat16, device=DEV)
+    z = torch.zeros((8, 8), device=DEV)
+    ip = torch.zeros(5, dtype=torch.int32, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    with pytest.raises(hb.HopgnnError):
+        hb.hopgnn_sage_bwd(H, 4, None, ip, ip, 4, W, W, None, False, torch.zeros((4, 8), device=DEV), z, z, None,
+                           None, ws)
