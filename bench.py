@@ -3,7 +3,10 @@
 
 A *step* is one whole batch: hopgnn_sample -> hopgnn_pregather -> hopgnn_gather ->
 L x hopgnn_sage_fwd for B fresh seeds, all on one stream, inputs resident in HBM,
-no host synchronisation inside the timed region.  The default workload is the
+no host synchronisation inside the timed region.  The forward-only step issues that
+sequence through hopgnn_batch_fwd (one library call); consecutive steps alternate over
+a few streams, each with its own buffers, so that the small kernels of one batch overlap
+the next batch's.  The default workload is the
 R-MAT 2^20-vertex shape (128 fp32 features, 1024 seeds, fanout [10,10], hidden 128).
 
 Prints ONE JSON line: batches/s, the gather kernel's effective HBM GB/s against the
@@ -128,8 +131,18 @@ def main():
     keys = [[i * group + b for b in range(group)] for i in range(n_total)]
     torch.cuda.synchronize()
 
-    def step(i, ev=None):
-        """One whole step on stream i % n_streams (consecutive steps overlap on the GPU)."""
+    seeds_cat = [torch.cat(s) for s in seeds]
+    hidden = hp.H[-1].shape[1]
+    outs = [torch.empty((group * cfg.batch, hidden), dtype=X.dtype, device=dev) for _ in range(n_streams)]
+    raw_streams = [s.cuda_stream for s in streams]
+
+    def step_fwd(i, marks=None):
+        """One whole forward step on stream i % n_streams: one call of hopgnn_batch_fwd."""
+        j = i % n_streams
+        hps[j].forward(seeds_cat[i], keys[i], outs[j], raw_streams[j], marks)
+
+    def step_calls(i, ev=None):
+        """The same step call by call (with the backward pass, if asked for)."""
         h, stream = hps[i % n_streams], streams[i % n_streams]
         st = stream.cuda_stream
         for b in range(group):
@@ -144,24 +157,29 @@ def main():
             h.layers(b, st)
             if args.backward:
                 h.backward(b, st)
-        if ev is not None:      # an empty pair: what two event markers cost with nothing between
-            ev[2].record(stream)
-            ev[3].record(stream)
 
+    step = step_calls if args.backward else step_fwd
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    gather_ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(4)) for _ in range(args.steps)]
+    # one event pair per timed step around the gather launch; recorded once here so that the
+    # handles exist, then re-recorded by the step itself
+    gather_ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(2)) for _ in range(args.steps)]
+    for i, e in enumerate(gather_ev):
+        e[0].record(streams[i % n_streams])
+        e[1].record(streams[i % n_streams])
+    torch.cuda.synchronize()
+    marks = gather_ev if args.backward else [(e[0].cuda_event, e[1].cuda_event) for e in gather_ev]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, gather_ev[i])
+        step(args.warmup + i, marks[i])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     gather_ms = [e[0].elapsed_time(e[1]) for e in gather_ev]
-    empty_ms = [e[2].elapsed_time(e[3]) for e in gather_ev]
 
     # untimed, instrumented replay of the same steps on one stream: U per step and a per-stage breakdown
     stage = {"sample": 0.0, "pregather": 0.0, "gather": 0.0}
+    empty_ms = []
     for k in range(1, sh.n_layers + 1):
         stage["sage_l%d" % k] = 0.0
     U_sum, valid_sum = 0, 0
@@ -170,7 +188,7 @@ def main():
     st0 = torch.cuda.current_stream().cuda_stream
     for i in range(n_replay):
         j = args.warmup + i
-        e = [E() for _ in range(4)]
+        e = [E() for _ in range(6)]
         e[0].record()
         for b in range(group):
             hp.sample(b, seeds[j][b], keys[j][b], st0)
@@ -179,7 +197,10 @@ def main():
         e[2].record()
         hp.gather(st0)
         e[3].record()
+        e[4].record()        # an empty pair: what two event markers cost with nothing between
+        e[5].record()
         torch.cuda.synchronize()
+        empty_ms.append(e[4].elapsed_time(e[5]))
         stage["sample"] += e[0].elapsed_time(e[1])
         stage["pregather"] += e[1].elapsed_time(e[2])
         stage["gather"] += e[2].elapsed_time(e[3])

@@ -234,6 +234,67 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               void *stream);
 
 /*
+ * One call per group of batches: the whole hot path in the order of paper sections 2, 4
+ * and 5.2 - sample the micrographs of each batch's seeds, pre-gather the group's merged slot
+ * list once, fetch every distinct row once, then run the L layers of each batch on the
+ * fetched rows.  It issues exactly the calls above (hopgnn_sample x n_batches, hopgnn_pregather,
+ * hopgnn_gather, hopgnn_sage_fwd x n_batches x L) from C on one stream; it exists because at
+ * a few microseconds per kernel the launch sequence itself is the bottleneck when it is driven
+ * call by call from an interpreter.  No host synchronisation, no allocation.
+ *
+ * The plan is a HOST struct the caller fills once; every pointer in it is DEVICE memory the
+ * caller owns (T = n_seeds * hopgnn_slots_per_seed, S = T minus the leaf level):
+ *   graph, X/dt/dim/ld_elems    as in hopgnn_sample and hopgnn_gather
+ *   n_seeds, n_layers, fanouts  shape of every batch
+ *   d_out[k], W_self[k], W_neigh[k], bias[k]   layer k+1; d_in of layer 1 is dim, of layer
+ *                               k+1 it is d_out[k-1]; ReLU after every layer but the last
+ *   group                       most batches one call may carry (buffers are sized for it)
+ *   ids, remap                  [group*T];  indptr [S+1];  slot_idx [group*max(S-n_seeds,1)]
+ *   uniq [uniq_capacity], n_uniq (1 x int64), Xu [uniq_capacity x dim]; uniq_capacity >=
+ *                               min(group*T, n_vertices)
+ *   H[k]                        [n_dst(k+1) x d_out[k]] for k < n_layers-1 (the last layer writes
+ *                               to `out`); reused by every batch of the group
+ *   pg_ws, sage_ws              scratch of hopgnn_pregather_ws_bytes(group*T, ..) and the largest
+ *                               hopgnn_sage_fwd_ws_bytes over the layers
+ *   mark_gather_begin/_end      optional hipEvent_t pair recorded on `stream` around the gather
+ *                               launch (NULL: none) so that a harness can time that kernel
+ *                               inside its timed region
+ *
+ * seeds  DEVICE [n_batches*n_seeds]; keys HOST [n_batches]; out DEVICE
+ *        [n_batches*n_seeds x d_out[n_layers-1]] in X's element type.
+ * Returns the first failing call's status (nothing later is launched); HOPGNN_EINVAL if
+ * n_batches is outside 1..group or a pointer is NULL.
+ */
+typedef struct {
+    hopgnn_csr graph;
+    const void *X;
+    hopgnn_dtype dt;
+    int32_t dim;
+    int64_t ld_elems;
+    int32_t n_seeds, n_layers;
+    int32_t fanouts[8];
+    int32_t d_out[8];
+    const void *W_self[8];
+    const void *W_neigh[8];
+    const void *bias[8];
+    int32_t pg_algo, group;
+    int32_t *ids, *indptr, *slot_idx, *uniq;
+    int64_t uniq_capacity;
+    int64_t *n_uniq;
+    int32_t *remap;
+    void *Xu;
+    void *H[8];
+    void *pg_ws;
+    size_t pg_ws_bytes;
+    void *sage_ws;
+    size_t sage_ws_bytes;
+    void *mark_gather_begin, *mark_gather_end;
+} hopgnn_batch_plan;
+
+hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,
+                               const uint64_t *keys /*HOST*/, int32_t n_batches, void *out, void *stream);
+
+/*
  * Micrograph merging (paper section 5.3).  HOST-only bookkeeping, no device work.
  *
  * counts is a HOST matrix [n_models x n_steps], row-major: root vertices model m trains at

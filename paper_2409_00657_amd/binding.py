@@ -26,7 +26,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_sage_bwd_ws_bytes", "hopgnn_sage_bwd",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
-           "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report"]
+           "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -42,6 +42,21 @@ class _Csr(ctypes.Structure):
     _fields_ = [("n_vertices", ctypes.c_int64), ("n_edges", ctypes.c_int64),
                 ("offsets", ctypes.c_void_p), ("offsets_i64", ctypes.c_int32),
                 ("indices", ctypes.c_void_p)]
+
+
+class BatchPlan(ctypes.Structure):
+    """hopgnn_batch_plan: field for field the C struct."""
+    _fields_ = [("graph", _Csr), ("X", ctypes.c_void_p), ("dt", ctypes.c_int), ("dim", ctypes.c_int32),
+                ("ld_elems", ctypes.c_int64), ("n_seeds", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+                ("fanouts", ctypes.c_int32 * 8), ("d_out", ctypes.c_int32 * 8),
+                ("W_self", ctypes.c_void_p * 8), ("W_neigh", ctypes.c_void_p * 8), ("bias", ctypes.c_void_p * 8),
+                ("pg_algo", ctypes.c_int32), ("group", ctypes.c_int32),
+                ("ids", ctypes.c_void_p), ("indptr", ctypes.c_void_p), ("slot_idx", ctypes.c_void_p),
+                ("uniq", ctypes.c_void_p), ("uniq_capacity", ctypes.c_int64), ("n_uniq", ctypes.c_void_p),
+                ("remap", ctypes.c_void_p), ("Xu", ctypes.c_void_p), ("H", ctypes.c_void_p * 8),
+                ("pg_ws", ctypes.c_void_p), ("pg_ws_bytes", ctypes.c_size_t),
+                ("sage_ws", ctypes.c_void_p), ("sage_ws_bytes", ctypes.c_size_t),
+                ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -103,6 +118,9 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_batch_fwd.restype = c.c_int
+    L.hopgnn_batch_fwd.argtypes = [c.POINTER(BatchPlan), c.c_void_p, c.POINTER(c.c_uint64), c.c_int32, c.c_void_p,
+                                   c.c_void_p]
     _lib = L
     return L
 
@@ -242,3 +260,18 @@ def hopgnn_sage_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Ten
                                         1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
                                         _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sage_bwd")
+
+
+def hopgnn_batch_fwd(plan: BatchPlan, seeds: torch.Tensor, keys, out: torch.Tensor, stream=None) -> None:
+    """hopgnn_batch_fwd: len(keys) batches of plan.n_seeds seeds each; `out` receives the last
+    layer's rows of every batch."""
+    n = len(keys)
+    if seeds.dtype != torch.int32 or not seeds.is_cuda or seeds.numel() != n * plan.n_seeds:
+        raise HopgnnError("seeds must be %d int32 values on the device" % (n * plan.n_seeds))
+    if not out.is_cuda or not out.is_contiguous() or DTYPE_OF.get(out.dtype) != plan.dt \
+            or out.numel() != n * plan.n_seeds * plan.d_out[plan.n_layers - 1]:
+        raise HopgnnError("out must be a contiguous device tensor [n_batches*n_seeds, d_out] of X's type")
+    karr = (ctypes.c_uint64 * n)(*[k & 0xFFFFFFFFFFFFFFFF for k in keys])
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _check(load_library().hopgnn_batch_fwd(ctypes.byref(plan), seeds.data_ptr(), karr, n, out.data_ptr(), st),
+           "hopgnn_batch_fwd")

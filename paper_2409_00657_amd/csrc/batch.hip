@@ -1,0 +1,67 @@
+// Whole groups of batches from one C call: the launch sequence of the hot path (paper sections
+// 2, 4 and 5.2) issued from C, because the kernels of a mid-sized batch take a few microseconds
+// each and an interpreter cannot issue them that fast.  Only sequencing: every step is one of
+// the library's own entry points.
+#include <hip/hip_runtime.h>
+
+#include "common.hpp"
+
+using namespace hopgnn;
+
+extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int32_t* seeds, const uint64_t* keys,
+                                          int32_t n_batches, void* out, void* stream) {
+    if (p == nullptr || seeds == nullptr || keys == nullptr || out == nullptr) return HOPGNN_EINVAL;
+    if (n_batches < 1 || n_batches > p->group) return HOPGNN_EINVAL;
+    const int32_t L = p->n_layers, B = p->n_seeds;
+    if (L < 1 || L > kMaxLayers || B < 1) return HOPGNN_EINVAL;
+    if ((p->mark_gather_begin == nullptr) != (p->mark_gather_end == nullptr)) return HOPGNN_EINVAL;
+    const int64_t t_seed = hopgnn_slots_per_seed(p->fanouts, L);
+    if (t_seed < 0) return HOPGNN_EINVAL;
+    int64_t level[kMaxLayers + 1];
+    level[0] = B;
+    for (int h = 1; h <= L; ++h) level[h] = level[h - 1] * p->fanouts[h - 1];
+    const int64_t T = t_seed * B, S = T - level[L];
+    const int64_t slot_idx_stride = S - B > 1 ? S - B : 1;
+    const size_t es = dtype_size(p->dt);
+    hipStream_t st = (hipStream_t)stream;
+
+    hopgnn_status rc;
+    for (int32_t b = 0; b < n_batches; ++b) {
+        rc = hopgnn_sample(&p->graph, seeds + (int64_t)b * B, B, p->fanouts, L, keys[b], p->ids + b * T, p->indptr,
+                           L > 1 ? p->slot_idx + b * slot_idx_stride : nullptr, stream);
+        if (rc != HOPGNN_OK) return rc;
+    }
+    rc = hopgnn_pregather(p->ids, n_batches * T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
+                          p->pg_ws, p->pg_ws_bytes, stream);
+    if (rc != HOPGNN_OK) return rc;
+    if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
+        return HOPGNN_EHIP;
+    rc = hopgnn_gather(p->X, p->dt, p->graph.n_vertices, p->dim, p->ld_elems, p->uniq, p->uniq_capacity, p->n_uniq,
+                       p->Xu, stream);
+    if (rc != HOPGNN_OK) return rc;
+    if (p->mark_gather_end != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_end, st) != hipSuccess)
+        return HOPGNN_EHIP;
+
+    const int32_t d_last = p->d_out[L - 1];
+    for (int32_t b = 0; b < n_batches; ++b) {
+        const int32_t* rb = p->remap + b * T;
+        const void* src = p->Xu;
+        int64_t n_src = p->uniq_capacity;
+        int32_t d_in = p->dim;
+        for (int32_t k = 1; k <= L; ++k) {
+            int64_t n_dst = 0;                      // slots of levels 0 .. L-k
+            for (int h = 0; h <= L - k; ++h) n_dst += level[h];
+            void* dst = k == L ? (void*)((char*)out + (size_t)b * B * d_last * es) : p->H[k - 1];
+            if (dst == nullptr) return HOPGNN_EINVAL;
+            rc = hopgnn_sage_fwd(src, p->dt, n_src, d_in, k == 1 ? rb : nullptr, p->indptr,
+                                 k == 1 ? rb + B : p->slot_idx + b * slot_idx_stride, n_dst, p->W_self[k - 1],
+                                 p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], k < L ? 1 : 0, dst, p->sage_ws,
+                                 p->sage_ws_bytes, stream);
+            if (rc != HOPGNN_OK) return rc;
+            src = dst;
+            n_src = n_dst;
+            d_in = p->d_out[k - 1];
+        }
+    }
+    return HOPGNN_OK;
+}

@@ -5,6 +5,9 @@
 //          with a capacity, U is passed on the device and the launch is sized for the
 //          capacity, as in a batch where the pre-gather count never visits the host
 //   cbench pregather <n_ids> <n_vertices> <iters> [algo: 0 auto, 1 bitmap, 2 radix]
+//   cbench batch <scale> <avg_degree> <dim> <f32|bf16|f16> <n_seeds> <fanouts f1,f2,..> <hidden> <iters> [streams]
+//          whole batches (sample -> pregather -> gather -> layers) on a row-conditional R-MAT
+//          graph (0.57, 0.19, 0.19, 0.05) built on the host, fresh seeds and key per batch
 //   cbench copy <bytes> <iters>      plain 128-bit copy kernel of known size, to calibrate
 //                                    the profiler's FETCH_SIZE / WRITE_SIZE counters
 //
@@ -16,6 +19,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <chrono>
 #include <string>
 #include <vector>
 
@@ -177,6 +181,119 @@ int main(int argc, char** argv) {
             hopgnn_status st = hopgnn_pregather(d_ids, n_ids, n_vertices, algo, uniq, n_uniq, remap, ws, wsb, nullptr);
             if (st != HOPGNN_OK) { fprintf(stderr, "pregather: %s\n", hopgnn_status_str(st)); exit(1); }
         });
+    } else if (mode == "batch" && argc >= 10) {
+        const int scale = atoi(argv[2]);
+        const double avg_deg = atof(argv[3]);
+        const int dim = atoi(argv[4]);
+        const hopgnn_dtype dt = parse_dt(argv[5]);
+        const int B = atoi(argv[6]);
+        std::vector<int32_t> fan;
+        for (char* tok = strtok(argv[7], ","); tok; tok = strtok(nullptr, ",")) fan.push_back(atoi(tok));
+        const int hidden = atoi(argv[8]), iters = atoi(argv[9]);
+        const int L = (int)fan.size();
+        const size_t es = dt == HOPGNN_F32 ? 4 : 2;
+        const int64_t N = (int64_t)1 << scale;
+        // row-conditional R-MAT: degree of i = round(E * 0.76^zeros(i) * 0.24^ones(i)), each target bit is 0
+        // with probability 0.75 where the source bit is 0 and 0.79 where it is 1
+        std::vector<int64_t> off(N + 1, 0);
+        for (int64_t i = 0; i < N; ++i) {
+            const int ones = __builtin_popcountll((unsigned long long)i);
+            double w = avg_deg * (double)N;
+            for (int b = 0; b < scale; ++b) w *= b < ones ? 0.24 : 0.76;
+            const double fl = (double)(int64_t)w;
+            off[i + 1] = off[i] + (int64_t)fl + (((double)(rnd() >> 11) / 9007199254740992.0) < (w - fl) ? 1 : 0);
+        }
+        const int64_t E = off[N];
+        std::vector<int32_t> ind(E);
+        for (int64_t i = 0; i < N; ++i)
+            for (int64_t e = off[i]; e < off[i + 1]; ++e) {
+                const uint64_t r = rnd();
+                int64_t dst = 0;
+                for (int b = 0; b < scale; ++b) {
+                    const unsigned u = (unsigned)((r >> (b * 3 % 61)) ^ (r >> ((b * 7 + 13) % 59))) & 1023u;
+                    const unsigned thr = ((i >> b) & 1) ? 811u : 768u;   // 0.79 and 0.75 of 1024
+                    if (u >= thr) dst |= (int64_t)1 << b;
+                }
+                ind[e] = (int32_t)dst;
+            }
+        printf("graph: %lld vertices, %lld edges\n", (long long)N, (long long)E);
+        auto d_off = upload(off);
+        auto d_ind = upload(ind);
+        void* X;
+        CK(hipMalloc(&X, (size_t)N * dim * es));
+        CK(hipMemset(X, 0x3c, (size_t)N * dim * es));     // finite, non-zero values in every type
+        const int n_streams = argc >= 11 ? atoi(argv[10]) : 1;
+        const int64_t t_seed = hopgnn_slots_per_seed(fan.data(), L);
+        const int64_t T = t_seed * B;
+        std::vector<int64_t> lv(L + 1);
+        lv[0] = B;
+        for (int h = 1; h <= L; ++h) lv[h] = lv[h - 1] * fan[h - 1];
+        const int64_t S = T - lv[L];
+        const int64_t cap = T < N ? T : N;
+        int32_t* seeds;
+        CK(hipMalloc(&seeds, (size_t)B * 4 * 64));
+        std::vector<int32_t> hseeds((size_t)B * 64);
+        for (auto& x : hseeds) x = (int32_t)(rnd() % (uint64_t)N);
+        CK(hipMemcpy(seeds, hseeds.data(), hseeds.size() * 4, hipMemcpyHostToDevice));
+        std::vector<void*> Wsv(L), Wnv(L);
+        for (int k = 1; k <= L; ++k) {
+            const int din = k == 1 ? dim : hidden;
+            Wsv[k - 1] = upload(random_table((size_t)din * hidden, dt));
+            Wnv[k - 1] = upload(random_table((size_t)din * hidden, dt));
+        }
+        // one plan (its own buffers) and one stream per concurrent batch
+        std::vector<hopgnn_batch_plan> plans(n_streams);
+        std::vector<hipStream_t> streams(n_streams);
+        std::vector<void*> outs(n_streams);
+        for (int s = 0; s < n_streams; ++s) {
+            hopgnn_batch_plan& p = plans[s];
+            memset(&p, 0, sizeof p);
+            p.graph = hopgnn_csr{N, E, d_off, 1, d_ind};
+            p.X = X; p.dt = dt; p.dim = dim; p.ld_elems = dim;
+            p.n_seeds = B; p.n_layers = L;
+            p.pg_algo = 0; p.group = 1;
+            CK(hipMalloc(&p.ids, T * 4)); CK(hipMalloc(&p.indptr, (S + 1) * 4));
+            CK(hipMalloc(&p.slot_idx, (S + 1) * 4));
+            CK(hipMalloc(&p.uniq, cap * 4)); CK(hipMalloc(&p.remap, T * 4)); CK(hipMalloc(&p.n_uniq, 8));
+            p.uniq_capacity = cap;
+            CK(hipMalloc(&p.Xu, (size_t)cap * dim * es));
+            p.pg_ws_bytes = hopgnn_pregather_ws_bytes(T, N, 0);
+            CK(hipMalloc(&p.pg_ws, p.pg_ws_bytes));
+            for (int k = 1; k <= L; ++k) {
+                int64_t nd = 0;
+                for (int h = 0; h <= L - k; ++h) nd += lv[h];
+                const int din = k == 1 ? dim : hidden;
+                p.fanouts[k - 1] = fan[k - 1];
+                p.d_out[k - 1] = hidden;
+                p.W_self[k - 1] = Wsv[k - 1];
+                p.W_neigh[k - 1] = Wnv[k - 1];
+                CK(hipMalloc(&p.H[k - 1], (size_t)nd * hidden * es));
+                const size_t bytes = hopgnn_sage_fwd_ws_bytes(dt, nd, din, hidden);
+                p.sage_ws_bytes = bytes > p.sage_ws_bytes ? bytes : p.sage_ws_bytes;
+            }
+            CK(hipMalloc(&p.sage_ws, p.sage_ws_bytes));
+            CK(hipMalloc(&outs[s], (size_t)B * hidden * es));
+            CK(hipStreamCreate(&streams[s]));
+        }
+        auto run = [&](int it) {
+            const int s = it % n_streams;
+            const uint64_t key = (uint64_t)it;
+            const hopgnn_status st = hopgnn_batch_fwd(&plans[s], seeds + (size_t)(it % 64) * B, &key, 1, outs[s], streams[s]);
+            if (st != HOPGNN_OK) { fprintf(stderr, "batch: %s\n", hopgnn_status_str(st)); exit(1); }
+        };
+        for (int it = 0; it < 8; ++it) run(it);
+        CK(hipDeviceSynchronize());
+        const auto t0 = std::chrono::steady_clock::now();
+        for (int it = 0; it < iters; ++it) run(8 + it);
+        const auto t1 = std::chrono::steady_clock::now();
+        CK(hipDeviceSynchronize());
+        const auto t2 = std::chrono::steady_clock::now();
+        printf("whole batch on %d stream(s): %.2f us per batch (%.2f us to issue), %d batches\n", n_streams,
+               std::chrono::duration<double, std::micro>(t2 - t0).count() / iters,
+               std::chrono::duration<double, std::micro>(t1 - t0).count() / iters, iters);
+        int64_t U;
+        CK(hipMemcpy(&U, plans[0].n_uniq, 8, hipMemcpyDeviceToHost));
+        printf("slots per batch %lld, unique rows in the last batch on stream 0: %lld\n", (long long)T, (long long)U);
     } else if (mode == "copy" && argc >= 4) {
         const int64_t bytes = atoll(argv[2]) / 16 * 16;
         const int iters = atoi(argv[3]);

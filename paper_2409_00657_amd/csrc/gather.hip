@@ -44,7 +44,7 @@ static hopgnn_status launch_gather(const void* X, const int32_t* uniq, int64_t n
     // on the device only a capacity is known, so a resident-sized grid strides over the
     // real count instead of launching capacity-many workgroups that mostly exit at once.
     int64_t grid = ceil_div(items, kGatherThreads);
-    const int64_t resident = 256 * 8 * 4;   // 256 CUs x 8 workgroups of 4 waves, 4 rounds
+    const int64_t resident = 256 * 8;   // 256 CUs x 8 workgroups of 4 waves: all that can be resident
     if (n_uniq_dev != nullptr && grid > resident) grid = resident;
     if (grid >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     const int64_t ld_vec = ld_bytes / (int64_t)sizeof(VecT);

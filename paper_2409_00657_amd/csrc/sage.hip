@@ -603,10 +603,10 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     const bool big = d_out > 64 && work >= 512;
     if (dt == HOPGNN_BF16) {
         if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-        if (big) return launch_project_16<TrBF16, 128, 128, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-        return launch_project_16<TrBF16, 64, 64, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
     }
     if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-    if (big) return launch_project_16<TrF16, 128, 128, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-    return launch_project_16<TrF16, 64, 64, 32, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
 }

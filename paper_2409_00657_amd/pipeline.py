@@ -57,7 +57,8 @@ class HotPath:
         i32 = dict(dtype=torch.int32, device=dev)
         self.ids = torch.empty(group * T, **i32)
         self.indptr = torch.empty(S + 1, **i32)          # the same for every batch of this shape
-        self.slot_idx = [torch.empty(max(S - B, 1), **i32) for _ in range(group)]
+        self._slot_idx_all = torch.empty(group * max(S - B, 1), **i32)
+        self.slot_idx = list(self._slot_idx_all.view(group, -1))
         self.remap = torch.empty(group * T, **i32)
         self.cap = min(group * T, self.n_vertices)
         self.uniq = torch.empty(self.cap, **i32)
@@ -109,6 +110,26 @@ class HotPath:
                                   self.sage_ws.numel()))
                 src, n_src = self.H[k - 1].data_ptr(), n_dst
             self._layer_args.append(per_batch)
+        # the same buffers as one plan for hopgnn_batch_fwd (the launch sequence issued from C)
+        pl = self.plan = hb.BatchPlan()
+        pl.graph = self._csr
+        pl.X, pl.dt, pl.dim, pl.ld_elems = self.X.data_ptr(), dt, self.X.shape[1], self.X.stride(0)
+        pl.n_seeds, pl.n_layers = B, L
+        for i, f in enumerate(sh.fanouts):
+            pl.fanouts[i] = f
+        for i, (Ws, Wn, bias) in enumerate(self.weights):
+            pl.d_out[i] = Ws.shape[1]
+            pl.W_self[i], pl.W_neigh[i] = Ws.data_ptr(), Wn.data_ptr()
+            pl.bias[i] = None if bias is None else bias.data_ptr()
+            pl.H[i] = self.H[i].data_ptr()
+        pl.pg_algo, pl.group = self.pg_algo, self.group
+        pl.ids, pl.indptr, pl.slot_idx = ids, self.indptr.data_ptr(), self._slot_idx_all.data_ptr()
+        pl.uniq, pl.uniq_capacity, pl.n_uniq = self.uniq.data_ptr(), self.cap, self.n_uniq.data_ptr()
+        pl.remap, pl.Xu = remap, self.Xu.data_ptr()
+        pl.pg_ws, pl.pg_ws_bytes = self.pg_ws.data_ptr(), self.pg_ws.numel()
+        pl.sage_ws, pl.sage_ws_bytes = self.sage_ws.data_ptr(), self.sage_ws.numel()
+        pl.mark_gather_begin = pl.mark_gather_end = None
+        self._keys = (ctypes.c_uint64 * self.group)()
 
     # -- the four steps ------------------------------------------------------
     # `stream` is a raw hipStream_t (int); None = torch's current stream.
@@ -197,6 +218,26 @@ class HotPath:
         self.pregather(st)
         self.gather(st)
         return self.layers(0, st)
+
+    def forward(self, seeds: torch.Tensor, keys: Sequence[int], out: torch.Tensor, stream=None,
+                marks=None) -> None:
+        """The whole group in ONE library call (hopgnn_batch_fwd): `seeds` holds the group's
+        seeds back to back, `out` [group*B, hidden] receives every batch's last-layer rows.
+        `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
+        n = len(keys)
+        if seeds.numel() != n * self.shape.n_seeds or seeds.dtype != torch.int32 or not seeds.is_cuda:
+            raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.shape.n_seeds))
+        if out.numel() != n * self.shape.n_seeds * self.H[-1].shape[1] or out.dtype != self.X.dtype \
+                or not out.is_cuda or not out.is_contiguous():
+            raise hb.HopgnnError("out must be a contiguous [n_batches*B, hidden] device tensor of X's type")
+        for i, k in enumerate(keys):
+            self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
+        pl = self.plan
+        pl.mark_gather_begin, pl.mark_gather_end = marks if marks is not None else (None, None)
+        rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._keys, n, out.data_ptr(),
+                                        self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_batch_fwd")
 
     def run_group(self, seeds_list: Sequence[torch.Tensor], keys: Sequence[int],
                   outs: Optional[List[torch.Tensor]] = None, stream=None) -> None:

@@ -64,6 +64,35 @@ def test_argument_errors_are_reported_before_any_launch(lib):
                                None, None, 0, None) == 0                          # n_dst = 0
 
 
+def test_batch_plan_errors_and_layout(lib):
+    from paper_2409_00657_amd import binding as hb
+    c = ctypes
+    # the ctypes mirror must have the C struct's size: compile a one-line probe with the same header
+    import subprocess
+    import tempfile
+    with tempfile.TemporaryDirectory() as d:
+        src = os.path.join(d, "p.c")
+        open(src, "w").write('#include <stdio.h>\n#include <stddef.h>\n#include "hopgnn.h"\nint main(void){printf("%zu %zu %zu",'
+                             'sizeof(hopgnn_batch_plan),offsetof(hopgnn_batch_plan,W_self),'
+                             'offsetof(hopgnn_batch_plan,mark_gather_begin));return 0;}\n')
+        exe = os.path.join(d, "p")
+        subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), src, "-o", exe], check=True)
+        size, off_w, off_m = map(int, subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split())
+    assert c.sizeof(hb.BatchPlan) == size
+    assert hb.BatchPlan.W_self.offset == off_w
+    assert hb.BatchPlan.mark_gather_begin.offset == off_m
+    plan = hb.BatchPlan()
+    keys = (c.c_uint64 * 1)(0)
+    one = c.c_void_p(8)    # any non-NULL address: the checks below fail before it is used
+    assert lib.hopgnn_batch_fwd(None, one, keys, 1, one, None) == 1
+    plan.group, plan.n_layers, plan.n_seeds = 1, 2, 4
+    assert lib.hopgnn_batch_fwd(c.byref(plan), one, keys, 0, one, None) == 1      # no batches
+    assert lib.hopgnn_batch_fwd(c.byref(plan), one, keys, 2, one, None) == 1      # more than the plan's group
+    assert lib.hopgnn_batch_fwd(c.byref(plan), one, keys, 1, one, None) == 1      # fanouts are zero
+    plan.n_layers = 9
+    assert lib.hopgnn_batch_fwd(c.byref(plan), one, keys, 1, one, None) == 1
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2409_00657_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

@@ -89,6 +89,20 @@ def _check_batch(orc, hp, cfg, graph_np, X, weights, seeds_list, keys, row_budge
                 err = rel_err(to_f64(got_all[lo:hi]), ref)
                 assert err <= TOL[dt], (cfg.name, b, k, lo, hi, err)
             prev_gpu = got_all
+
+    # the same group through the single-call entry point: the same launches issued from C, so
+    # every buffer and the last layer's rows must come out bit for bit the same
+    hidden = hp.H[L - 1].shape[1]
+    out = torch.full((G * B, hidden), float("nan"), dtype=dt, device=X.device)
+    hp.ids.fill_(-7)
+    hp.remap.fill_(-7)
+    hp.forward(torch.cat(list(seeds_list)), keys, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(hp.ids.cpu().numpy(), all_ids)
+    np.testing.assert_array_equal(hp.remap.cpu().numpy(), ref_remap)
+    assert int(hp.n_uniq.item()) == U
+    for b in range(G):
+        assert to_bits(out[b * B:(b + 1) * B]).tobytes() == to_bits(layer_out[b][L - 1]).tobytes(), (cfg.name, b)
     return stats, layer_out, ref_ids, ref_remap, Xu_ref
 
 
