@@ -291,6 +291,27 @@ int main(int argc, char** argv) {
         printf("whole batch on %d stream(s): %.2f us per batch (%.2f us to issue), %d batches\n", n_streams,
                std::chrono::duration<double, std::micro>(t2 - t0).count() / iters,
                std::chrono::duration<double, std::micro>(t1 - t0).count() / iters, iters);
+        if (getenv("CBENCH_GRAPH")) {
+            // the same sequence captured once per stream and replayed (fixed key and seeds: timing only)
+            std::vector<hipGraphExec_t> execs(n_streams);
+            for (int s = 0; s < n_streams; ++s) {
+                hipGraph_t gr;
+                CK(hipStreamBeginCapture(streams[s], hipStreamCaptureModeThreadLocal));
+                run(s);
+                CK(hipStreamEndCapture(streams[s], &gr));
+                CK(hipGraphInstantiate(&execs[s], gr, nullptr, nullptr, 0));
+            }
+            for (int it = 0; it < 8; ++it) CK(hipGraphLaunch(execs[it % n_streams], streams[it % n_streams]));
+            CK(hipDeviceSynchronize());
+            const auto g0 = std::chrono::steady_clock::now();
+            for (int it = 0; it < iters; ++it) CK(hipGraphLaunch(execs[it % n_streams], streams[it % n_streams]));
+            const auto g1 = std::chrono::steady_clock::now();
+            CK(hipDeviceSynchronize());
+            const auto g2 = std::chrono::steady_clock::now();
+            printf("graph replay on %d stream(s): %.2f us per batch (%.2f us to issue)\n", n_streams,
+                   std::chrono::duration<double, std::micro>(g2 - g0).count() / iters,
+                   std::chrono::duration<double, std::micro>(g1 - g0).count() / iters);
+        }
         int64_t U;
         CK(hipMemcpy(&U, plans[0].n_uniq, 8, hipMemcpyDeviceToHost));
         printf("slots per batch %lld, unique rows in the last batch on stream 0: %lld\n", (long long)T, (long long)U);
