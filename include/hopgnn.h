@@ -180,8 +180,8 @@ hopgnn_status hopgnn_gather(const void *X, hopgnn_dtype dt, int64_t n_rows, int3
  *   out[r] = act( x_r W_self + m_r W_neigh + bias ),  x_r = Hsrc[self_idx[r], :]
  *
  * Hsrc     DEVICE [n_src x d_in], packed rows, dtype dt.
- * self_idx DEVICE [n_dst] or NULL (= identity: x_r = Hsrc[r]); a negative entry
- *          gives a zero self row.
+ * self_idx DEVICE [n_dst] or NULL (= identity: x_r = Hsrc[r], which needs n_src >= n_dst,
+ *          else HOPGNN_EINVAL); a negative entry gives a zero self row.
  * indptr   DEVICE [n_dst+1], idx DEVICE [indptr[n_dst]]; negative idx = skip.
  * W_self, W_neigh DEVICE [d_in x d_out] row-major, dtype dt; bias DEVICE [d_out] or NULL.
  * relu     0: identity activation, else max(., 0).

@@ -35,12 +35,6 @@ namespace hopgnn {
 constexpr int kProjThreads = 256;
 constexpr int kXcds = 8;
 
-// Workgroup barrier that waits for this wave's LDS operations only.  __syncthreads()
-// would also wait for every outstanding global load and drain the prefetch queue.
-__device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Keep all N
 // tiles of one M tile on one XCD so the left operand is fetched into one L2 only.
 __device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t n_tiles, uint32_t& mt, uint32_t& nt) {
@@ -564,6 +558,7 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     if (indptr == nullptr || W_self == nullptr || W_neigh == nullptr || out == nullptr || ws == nullptr)
         return HOPGNN_EINVAL;
     if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
+    if (self_idx == nullptr && n_src < n_dst) return HOPGNN_EINVAL;   // identity self rows must exist
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;

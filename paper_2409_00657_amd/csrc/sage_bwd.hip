@@ -58,36 +58,91 @@ bwd_zero(float4* __restrict__ p, int64_t n4) {
 //
 // G[k][n] = sum_r A[r][k] dZ[r][n] with A = [x_self | mean].  The contraction index r is the
 // MFMA's K dimension: for v_mfma_f32_32x32x2_f32 lane l feeds A[r + l/32][k0 + l%32] and
-// dZ[r + l/32][n0 + l%32], i.e. both operands are plain coalesced reads of 32 consecutive
-// floats of a row - no LDS, no transposition.  A wave owns a 64 x 64 piece of G (2 x 2 MFMA
-// tiles: two A values and two dZ values feed four MFMAs), a workgroup (4 waves, 2 x 2) a
-// 128 x 128 tile, for the rows [split*rows_per_split, ...); it writes the tile to
-// partial[split].  Workgroups of the first k-tile row also produce the column sums of dZ.
+// dZ[r + l/32][n0 + l%32], i.e. both operands are 32 consecutive floats of a row - no
+// transposition anywhere.  A workgroup (4 waves, 2 x 2) owns a 128 x 128 tile of G for the rows
+// [split*rows_per_split, ...), a wave a 64 x 64 piece (2 x 2 MFMA tiles: two A values and two
+// dZ values feed four MFMAs).  Rows are staged 16 at a time through LDS, so that every element
+// leaves global memory once per workgroup in a 128-bit load; the next chunk's loads (and the
+// self indices of the chunk after it) are in flight while the current chunk is multiplied.
+// Every load is unconditional from a clamped, in-bounds address and masked when it is written
+// to LDS, which keeps the loop free of branches.  The tile goes to partial[split]; workgroups
+// of the first k-tile row also produce the column sums of dZ.
 constexpr int kGradTile = 128;
+constexpr int kGradRows = 16;               // contraction rows per LDS chunk
+constexpr int kGradLd = kGradTile + 32;     // LDS row stride: the two rows of one MFMA step sit 32 banks apart
 
+// One thread's share of a chunk: two rows (lr, lr + 8), four consecutive columns, of each operand.
+struct GradFrag {
+    float4 a[2], b[2];
+};
+
+template <bool VEC>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                 const float* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
                 int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
                 float* __restrict__ bias_partial) {
+    __shared__ __attribute__((aligned(16))) float As[2][kGradRows][kGradLd];
+    __shared__ __attribute__((aligned(16))) float Bs[2][kGradRows][kGradLd];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
+    const int wk = wave >> 1, wn = wave & 1;
     const int K = 2 * d_in;
     const uint32_t tk = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
-    const int k0 = (int)tk * kGradTile + (wave >> 1) * 64;    // first row of G of this wave
-    const int n0 = (int)tn * kGradTile + (wave & 1) * 64;     // first column
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
     const int64_t r1 = r0 + rows_per_split < n_dst ? r0 + rows_per_split : n_dst;
-    int k[2], n[2];
-    bool k_ok[2], n_ok[2], k_self[2];
+    const int n_chunks = (int)((r1 - r0 + kGradRows - 1) / kGradRows);
+
+    // this thread's part of every chunk
+    const int lr = tid >> 5, lc = (tid & 31) * 4;
+    const int ka = (int)tk * kGradTile + lc;      // column of A = row of G
+    const int nb = (int)tn * kGradTile + lc;      // column of dZ and of G
+
+    auto self_of = [&](int chunk, int i) -> int32_t {   // self index of row lr + 8 i of a chunk (clamped rows)
+        int64_t r = r0 + (int64_t)chunk * kGradRows + lr + 8 * i;
+        r = r < n_dst ? r : n_dst - 1;
+        return self_idx != nullptr ? self_idx[r] : (int32_t)r;
+    };
+    auto load = [&](int chunk, const int32_t (&sidx)[2], GradFrag& f) {
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        k[t] = k0 + t * 32 + l32;
-        n[t] = n0 + t * 32 + l32;
-        k_ok[t] = k[t] < K;
-        n_ok[t] = n[t] < d_out;
-        k_self[t] = k[t] < d_in;
-    }
+        for (int i = 0; i < 2; ++i) {
+            int64_t r = r0 + (int64_t)chunk * kGradRows + lr + 8 * i;
+            r = r < n_dst ? r : n_dst - 1;
+            const int64_t srow = sidx[i] > 0 ? sidx[i] : 0;
+            if (VEC) {
+                const float* pa = ka < d_in ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - d_in : 0);
+                f.a[i] = *reinterpret_cast<const float4*>(pa);
+                f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + (nb < d_out ? nb : 0));
+            } else {
+                float av[4], bv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int k = ka + e, n = nb + e;
+                    av[e] = k < d_in ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - d_in : 0)];
+                    bv[e] = dZ[r * d_out + (n < d_out ? n : 0)];
+                }
+                f.a[i] = make_float4(av[0], av[1], av[2], av[3]);
+                f.b[i] = make_float4(bv[0], bv[1], bv[2], bv[3]);
+            }
+        }
+    };
+    auto store = [&](int chunk, const int32_t (&sidx)[2], const GradFrag& f, int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const bool row_ok = r0 + (int64_t)chunk * kGradRows + lr + 8 * i < r1;
+            float av[4] = {f.a[i].x, f.a[i].y, f.a[i].z, f.a[i].w};
+            float bv[4] = {f.b[i].x, f.b[i].y, f.b[i].z, f.b[i].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int k = ka + e, n = nb + e;
+                const bool a_ok = row_ok && k < K && (k >= d_in || sidx[i] >= 0);
+                av[e] = a_ok ? av[e] : 0.f;
+                bv[e] = row_ok && n < d_out ? bv[e] : 0.f;
+            }
+            *reinterpret_cast<float4*>(&As[buf][lr + 8 * i][lc]) = make_float4(av[0], av[1], av[2], av[3]);
+            *reinterpret_cast<float4*>(&Bs[buf][lr + 8 * i][lc]) = make_float4(bv[0], bv[1], bv[2], bv[3]);
+        }
+    };
 
     floatx16 acc[2][2];
 #pragma unroll
@@ -97,80 +152,95 @@ bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     float colsum[2] = {0.f, 0.f};
-    constexpr int U = 2;   // MFMA steps (2 rows each) per loop trip
-    for (int64_t rb = r0; rb < r1; rb += 2 * U) {
-        float a[U][2], b[U][2];
+
+    int32_t s_cur[2] = {self_of(0, 0), self_of(0, 1)};
+    int32_t s_nxt[2] = {self_of(1, 0), self_of(1, 1)};
+    GradFrag f;
+    load(0, s_cur, f);
+    store(0, s_cur, f, 0);
+    lds_barrier();
+    for (int c = 0; c < n_chunks; ++c) {
+        const int buf = c & 1;
+        // chunk c+1 (past the end: clamped rows, masked, never multiplied) and the indices of chunk c+2
+        load(c + 1, s_nxt, f);
+        s_cur[0] = s_nxt[0];
+        s_cur[1] = s_nxt[1];
+        s_nxt[0] = self_of(c + 2, 0);
+        s_nxt[1] = self_of(c + 2, 1);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int64_t r = rb + 2 * u + g;
-            const bool r_ok = r < r1;
-            int64_t s = -1;
-            if (r_ok) s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                a[u][t] = 0.f;
-                b[u][t] = 0.f;
-                if (r_ok && n_ok[t]) b[u][t] = dZ[r * d_out + n[t]];
-                if (r_ok && k_ok[t]) {
-                    if (k_self[t]) {
-                        if (s >= 0) a[u][t] = Hsrc[s * d_in + k[t]];
-                    } else {
-                        a[u][t] = Mean[r * d_in + (k[t] - d_in)];
-                    }
-                }
-            }
+        for (int st = 0; st < kGradRows / 2; ++st) {
+            const int row = 2 * st + g;
+            const float a0 = As[buf][row][wk * 64 + l32], a1 = As[buf][row][wk * 64 + 32 + l32];
+            const float b0 = Bs[buf][row][wn * 64 + l32], b1 = Bs[buf][row][wn * 64 + 32 + l32];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            colsum[0] += b0;
+            colsum[1] += b1;
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][i], b[u][j], acc[i][j], 0, 0, 0);
-            colsum[0] += b[u][0];
-            colsum[1] += b[u][1];
-        }
+        store(c + 1, s_cur, f, buf ^ 1);
+        lds_barrier();
     }
+
     // partial[split][k][n]; accumulator register e of lane l holds G row 8*(e/4)+4*(l/32)+e%4, col l%32
+    const int k0 = (int)tk * kGradTile + wk * 64, n0 = (int)tn * kGradTile + wn * 64;
     float* P = partial + (int64_t)blockIdx.y * K * d_out;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            if (!n_ok[j]) continue;
+            const int n = n0 + j * 32 + l32;
+            if (n >= d_out) continue;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int kk = k0 + i * 32 + 8 * (e / 4) + 4 * g + (e & 3);
-                if (kk < K) P[(int64_t)kk * d_out + n[j]] = acc[i][j][e];
+                if (kk < K) P[(int64_t)kk * d_out + n] = acc[i][j][e];
             }
         }
-    if (bias_partial != nullptr && tk == 0 && (wave >> 1) == 0) {   // one wave per 64-column block
+    if (bias_partial != nullptr && tk == 0 && wk == 0) {   // one wave per 64-column block
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const float c = colsum[j] + __shfl_xor(colsum[j], 32, kWave);   // even rows + odd rows
-            if (g == 0 && n_ok[j]) bias_partial[(int64_t)blockIdx.y * d_out + n[j]] = c;
+            const float cs = colsum[j] + __shfl_xor(colsum[j], 32, kWave);   // even rows + odd rows
+            const int n = n0 + j * 32 + l32;
+            if (g == 0 && n < d_out) bias_partial[(int64_t)blockIdx.y * d_out + n] = cs;
         }
     }
 }
 
-// gW += sum over splits (in split order) of the partial tiles; same for the bias.
+// gW += sum over the splits of the partial tiles; same for the bias.  A workgroup owns 64
+// consecutive elements; wave q sums the splits q, q+4, q+8, ... in that order and the four
+// sums are combined as (s0 + s1) + (s2 + s3): a fixed order, so the result is bit-stable.
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ bias_partial, int32_t n_splits,
                   int32_t d_in, int32_t d_out, float* __restrict__ gW_self, float* __restrict__ gW_neigh,
                   float* __restrict__ gbias) {
-    const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    __shared__ float part[4][kWave];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * kWave + lane;
     const int64_t per = (int64_t)2 * d_in * d_out;
-    if (i < per) {
-        float s = 0.f;
-        for (int32_t p = 0; p < n_splits; ++p) s += partial[(int64_t)p * per + i];
+    // elements [0, per) are the weights, [per, per + d_out) the bias
+    const float* src = i < per ? partial + i : bias_partial + (i - per);
+    const int64_t stride = i < per ? per : d_out;
+    const bool live = i < per || (gbias != nullptr && i < per + d_out);
+    float s = 0.f;
+    if (live) {
+        int32_t p = q;
+        for (; p + 12 < n_splits; p += 16) {      // four independent loads in flight
+            const float v0 = src[(int64_t)p * stride], v1 = src[(int64_t)(p + 4) * stride];
+            const float v2 = src[(int64_t)(p + 8) * stride], v3 = src[(int64_t)(p + 12) * stride];
+            s = (((s + v0) + v1) + v2) + v3;
+        }
+        for (; p < n_splits; p += 4) s += src[(int64_t)p * stride];
+    }
+    part[q][lane] = s;
+    __syncthreads();
+    if (q == 0 && live) {
+        const float t = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
         const int64_t half = (int64_t)d_in * d_out;
-        if (i < half) gW_self[i] += s;
-        else gW_neigh[i - half] += s;
-    } else if (gbias != nullptr && i < per + d_out) {
-        const int64_t nn = i - per;
-        float s = 0.f;
-        for (int32_t p = 0; p < n_splits; ++p) s += bias_partial[(int64_t)p * d_out + nn];
-        gbias[nn] += s;
+        if (i < half) gW_self[i] += t;
+        else if (i < per) gW_neigh[i - half] += t;
+        else gbias[i - per] += t;
     }
 }
 
@@ -290,12 +360,13 @@ static BwdWs bwd_ws_layout(int64_t n_dst, int32_t d_in, int32_t d_out, int want_
     L.mean_bytes = align_up((size_t)nd * d_in * 4, 256);
     L.zero_bytes = align_up(((size_t)2 * d_in + 64) * 4, 256);
     L.dz_bytes = align_up((size_t)nd * d_out * 4, 256);
-    // enough splits to fill the chip (about 2048 waves), at least 64 rows each
+    // enough splits to fill the chip (about 2048 waves), at least 128 rows each so that the
+    // partial tiles stay small next to the operands
     const int64_t tiles = ceil_div(2 * (int64_t)d_in, kGradTile) * ceil_div(d_out, kGradTile);
     int64_t splits = ceil_div(512, tiles);
     int64_t rows = ceil_div(nd, splits);
-    if (rows < 64) rows = 64;
-    rows = (rows + 7) / 8 * 8;
+    if (rows < 128) rows = 128;
+    rows = (rows + kGradRows - 1) / kGradRows * kGradRows;
     L.rows_per_split = (int32_t)rows;
     L.n_splits = (int32_t)ceil_div(nd, rows);
     L.partial_bytes = align_up((size_t)L.n_splits * 2 * d_in * d_out * 4, 256);
@@ -343,6 +414,7 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
         gW_neigh == nullptr || ws == nullptr || (relu && out_fwd == nullptr))
         return HOPGNN_EINVAL;
     if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
+    if (self_idx == nullptr && n_src < n_dst) return HOPGNN_EINVAL;   // identity self rows must exist
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
     const BwdWs L = bwd_ws_layout(n_dst, d_in, d_out, dHsrc != nullptr);
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
@@ -374,12 +446,13 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
     }
 
     const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
-    hipLaunchKernelGGL(bwd_weight_grad, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
-                       static_cast<const float*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out, L.rows_per_split,
-                       tiles_n, partial, gbias != nullptr ? bias_partial : nullptr);
+    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16);
+    hipLaunchKernelGGL(vec ? bwd_weight_grad<true> : bwd_weight_grad<false>, dim3(tiles_k * tiles_n, (unsigned)L.n_splits),
+                       dim3(kBwdThreads), 0, s, static_cast<const float*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out,
+                       L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr);
     HOPGNN_LAUNCH_CHECK();
     const int64_t red = (int64_t)2 * d_in * d_out + d_out;
-    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kBwdThreads)), dim3(kBwdThreads), 0, s, partial,
+    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
                        bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias);
     HOPGNN_LAUNCH_CHECK();
 

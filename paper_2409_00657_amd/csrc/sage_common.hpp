@@ -5,6 +5,13 @@
 
 namespace hopgnn {
 
+// Workgroup barrier that waits for this wave's LDS operations only.  __syncthreads()
+// would also wait for every outstanding global load and drain the prefetch queue.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
