@@ -43,7 +43,7 @@ def parse():
     ap.add_argument("--streams", type=int, default=2,
                     help="HIP streams (each with its own buffers) that consecutive steps alternate over")
     ap.add_argument("--backward", action="store_true",
-                    help="also run the layers' backward pass with in-place gradient accumulation (fp32 shapes)")
+                    help="also run the layers' backward pass with in-place gradient accumulation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()

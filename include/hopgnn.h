@@ -211,9 +211,10 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *   dHsrc     = 0;  dHsrc[self_idx[r]] += dZ[r] W_self^T;
  *               dHsrc[idx[e]] += (dZ[r] W_neigh^T) / c_r  for every valid entry e of row r
  *
- * dt       HOPGNN_F32 only in this version (EINVAL otherwise).
- * out_fwd  DEVICE [n_dst x d_out], the stored forward output (decides the ReLU mask); may be
- *          NULL when relu == 0.
+ * dt       type of Hsrc, W_self, W_neigh and out_fwd (fp32, bf16 or fp16).  Every gradient is
+ *          fp32 whatever dt is; the neighbour mean is rounded to dt as in the forward call.
+ * out_fwd  DEVICE [n_dst x d_out] of type dt, the stored forward output (decides the ReLU
+ *          mask); may be NULL when relu == 0.
  * dOut     DEVICE [n_dst x d_out] fp32.
  * gW_self, gW_neigh DEVICE [d_in x d_out] fp32 accumulators, ADDED to (the caller zeroes them
  *          at the start of an iteration); gbias DEVICE [d_out] fp32 accumulator or NULL.

@@ -9,7 +9,9 @@
 //   [dXs|dM]  = dZ [W_self ; W_neigh]^T   (n_dst x 2*d_in)               bwd_input_grad (MFMA)
 //   dHsrc[self_idx[r]] += dXs[r];  dHsrc[idx[e]] += dM[r] / c_r          bwd_scatter
 //
-// fp32 activations only in this version.  The weight gradient contracts over the destination
+// Hsrc, the weights and the stored forward output are in the activation type (fp32, bf16 or
+// fp16); gradients (dOut, gW, gbias, dHsrc) are always fp32 and the contractions run on the fp32
+// MFMA with 2-byte operands widened on their way into LDS.  The weight gradient contracts over the destination
 // rows, which are split over workgroups; the partial tiles are summed in split order by a
 // second kernel, so gW/gbias are bit-stable from run to run.  dHsrc uses float atomic adds:
 // bit-stable when a source row receives at most two contributions (always the case for the
@@ -21,13 +23,33 @@ namespace hopgnn {
 
 constexpr int kBwdThreads = 256;
 
+// Four consecutive stored elements as they sit in memory (16 bytes of fp32, 8 bytes of a 2-byte
+// type); widened to fp32 only where the values are consumed, so that a prefetched load is not
+// waited for at its issue point.
+template <typename Tr>
+struct Raw4 {
+    using type = uint2;
+    __device__ static __forceinline__ float4 widen(uint2 v) {
+        union { uint2 v; typename Tr::store_t e[4]; } u;
+        u.v = v;
+        return make_float4(Tr::to_f(u.e[0]), Tr::to_f(u.e[1]), Tr::to_f(u.e[2]), Tr::to_f(u.e[3]));
+    }
+};
+template <>
+struct Raw4<TrF32> {
+    using type = float4;
+    __device__ static __forceinline__ float4 widen(float4 v) { return v; }
+};
+
 // ---------------------------------------------------------------- dZ mask --
 
+template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_mask(const float4* __restrict__ out_fwd, const float4* __restrict__ dOut, int64_t n4, float4* __restrict__ dZ) {
+bwd_mask4(const typename Raw4<Tr>::type* __restrict__ out_fwd, const float4* __restrict__ dOut, int64_t n4,
+          float4* __restrict__ dZ) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
     if (i >= n4) return;
-    const float4 o = out_fwd[i];
+    const float4 o = Raw4<Tr>::widen(out_fwd[i]);
     float4 g = dOut[i];
     g.x = o.x > 0.f ? g.x : 0.f;
     g.y = o.y > 0.f ? g.y : 0.f;
@@ -36,10 +58,12 @@ bwd_mask(const float4* __restrict__ out_fwd, const float4* __restrict__ dOut, in
     dZ[i] = g;
 }
 
+template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_mask_elem(const float* __restrict__ out_fwd, const float* __restrict__ dOut, int64_t n, float* __restrict__ dZ) {
+bwd_mask_elem(const typename Tr::store_t* __restrict__ out_fwd, const float* __restrict__ dOut, int64_t n,
+              float* __restrict__ dZ) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
-    if (i < n) dZ[i] = out_fwd[i] > 0.f ? dOut[i] : 0.f;
+    if (i < n) dZ[i] = Tr::to_f(out_fwd[i]) > 0.f ? dOut[i] : 0.f;
 }
 
 __global__ void __launch_bounds__(kBwdThreads)
@@ -72,14 +96,16 @@ constexpr int kGradRows = 16;               // contraction rows per LDS chunk
 constexpr int kGradLd = kGradTile + 32;     // LDS row stride: the two rows of one MFMA step sit 32 banks apart
 
 // One thread's share of a chunk: two rows (lr, lr + 8), four consecutive columns, of each operand.
+template <typename Tr>
 struct GradFrag {
-    float4 a[2], b[2];
+    typename Raw4<Tr>::type a[2];
+    float4 b[2];
 };
 
-template <bool VEC>
+template <typename Tr, bool VEC>
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
-                const float* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
+bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
+                const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
                 int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
                 float* __restrict__ bias_partial) {
     __shared__ __attribute__((aligned(16))) float As[2][kGradRows][kGradLd];
@@ -103,34 +129,38 @@ bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self
         r = r < n_dst ? r : n_dst - 1;
         return self_idx != nullptr ? self_idx[r] : (int32_t)r;
     };
-    auto load = [&](int chunk, const int32_t (&sidx)[2], GradFrag& f) {
+    using T = typename Tr::store_t;
+    using R4 = typename Raw4<Tr>::type;
+    auto load = [&](int chunk, const int32_t (&sidx)[2], GradFrag<Tr>& f) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             int64_t r = r0 + (int64_t)chunk * kGradRows + lr + 8 * i;
             r = r < n_dst ? r : n_dst - 1;
             const int64_t srow = sidx[i] > 0 ? sidx[i] : 0;
             if (VEC) {
-                const float* pa = ka < d_in ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - d_in : 0);
-                f.a[i] = *reinterpret_cast<const float4*>(pa);
+                const T* pa = ka < d_in ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - d_in : 0);
+                f.a[i] = *reinterpret_cast<const R4*>(pa);
                 f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + (nb < d_out ? nb : 0));
             } else {
-                float av[4], bv[4];
+                union { R4 v; T e[4]; } av;
+                float bv[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int k = ka + e, n = nb + e;
-                    av[e] = k < d_in ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - d_in : 0)];
+                    av.e[e] = k < d_in ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - d_in : 0)];
                     bv[e] = dZ[r * d_out + (n < d_out ? n : 0)];
                 }
-                f.a[i] = make_float4(av[0], av[1], av[2], av[3]);
+                f.a[i] = av.v;
                 f.b[i] = make_float4(bv[0], bv[1], bv[2], bv[3]);
             }
         }
     };
-    auto store = [&](int chunk, const int32_t (&sidx)[2], const GradFrag& f, int buf) {
+    auto store = [&](int chunk, const int32_t (&sidx)[2], const GradFrag<Tr>& f, int buf) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const bool row_ok = r0 + (int64_t)chunk * kGradRows + lr + 8 * i < r1;
-            float av[4] = {f.a[i].x, f.a[i].y, f.a[i].z, f.a[i].w};
+            const float4 aw = Raw4<Tr>::widen(f.a[i]);
+            float av[4] = {aw.x, aw.y, aw.z, aw.w};
             float bv[4] = {f.b[i].x, f.b[i].y, f.b[i].z, f.b[i].w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -155,7 +185,7 @@ bwd_weight_grad(const float* __restrict__ Hsrc, const int32_t* __restrict__ self
 
     int32_t s_cur[2] = {self_of(0, 0), self_of(0, 1)};
     int32_t s_nxt[2] = {self_of(1, 0), self_of(1, 1)};
-    GradFrag f;
+    GradFrag<Tr> f;
     load(0, s_cur, f);
     store(0, s_cur, f, 0);
     lds_barrier();
@@ -250,9 +280,13 @@ bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ b
 // operands have the contraction index contiguous, so both sit in LDS row-major [64][BK+4] and
 // are read as 128-bit words: lane group g = l/32 takes the four n values 4g..4g+3 of an 8-wide
 // block and the block's four MFMAs pair the i-th values (a permutation of the summation order).
+template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_input_grad(const float* __restrict__ dZ, const float* __restrict__ Wself, const float* __restrict__ Wneigh,
-               int64_t n_dst, int32_t d_in, int32_t d_out, float* __restrict__ D) {
+bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restrict__ Wself,
+               const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst, int32_t d_in, int32_t d_out,
+               float* __restrict__ D) {
+    using T = typename Tr::store_t;
+    using R4 = typename Raw4<Tr>::type;
     constexpr int BM = 64, BN = 64, BK = 16, LD = BK + 4;
     __shared__ __attribute__((aligned(16))) float As[BM][LD];
     __shared__ __attribute__((aligned(16))) float Bs[BN][LD];
@@ -269,8 +303,23 @@ bwd_input_grad(const float* __restrict__ dZ, const float* __restrict__ Wself, co
     const int64_t ar = row0 + lr;
     const int bj = col0 + lr;
     const float* arow = ar < n_dst ? dZ + ar * d_out : nullptr;
-    const float* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
-                               : nullptr;
+    const T* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
+                           : nullptr;
+    auto load4w = [&](const T* row, int kq) {      // raw weight elements, widened when they go to LDS
+        union { R4 v; T e[4]; } u;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) u.e[e] = Tr::from_f(0.f);
+        if (row != nullptr) {
+            if (vec && kq + 3 < d_out) {
+                u.v = *reinterpret_cast<const R4*>(row + kq);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (kq + e < d_out) u.e[e] = row[kq + e];
+            }
+        }
+        return u.v;
+    };
     auto load4 = [&](const float* row, int kq) {
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
         if (row != nullptr) {
@@ -290,15 +339,16 @@ bwd_input_grad(const float* __restrict__ dZ, const float* __restrict__ Wself, co
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.f;
     const int n_tiles = (d_out + BK - 1) / BK;
-    float4 ra = load4(arow, lk), rb = load4(brow, lk);
+    float4 ra = load4(arow, lk);
+    R4 rb = load4w(brow, lk);
     for (int t = 0; t < n_tiles; ++t) {
         __syncthreads();
         *reinterpret_cast<float4*>(&As[lr][lk]) = ra;
-        *reinterpret_cast<float4*>(&Bs[lr][lk]) = rb;
+        *reinterpret_cast<float4*>(&Bs[lr][lk]) = Raw4<Tr>::widen(rb);
         __syncthreads();
         if (t + 1 < n_tiles) {
             ra = load4(arow, (t + 1) * BK + lk);
-            rb = load4(brow, (t + 1) * BK + lk);
+            rb = load4w(brow, (t + 1) * BK + lk);
         }
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 8) {
@@ -382,9 +432,74 @@ using namespace hopgnn;
 
 extern "C" size_t hopgnn_sage_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out,
                                            int32_t want_dh) {
-    if (dt != HOPGNN_F32 || n_dst < 0 || d_in < 1 || d_out < 1) return 0;
+    if ((dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) || n_dst < 0 || d_in < 1 || d_out < 1) return 0;
     return bwd_ws_layout(n_dst, d_in, d_out, want_dh).total;
 }
+
+namespace hopgnn {
+
+template <typename Tr>
+static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in, const int32_t* self_idx,
+                                    const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W_self,
+                                    const void* W_neigh, const void* out_fwd, int32_t relu, const float* dOut,
+                                    int32_t d_out, float* gW_self, float* gW_neigh, float* gbias, float* dHsrc,
+                                    void* ws, const BwdWs& L, hipStream_t s) {
+    using T = typename Tr::store_t;
+    using R4 = typename Raw4<Tr>::type;
+    char* p = static_cast<char*>(ws);
+    T* mean = reinterpret_cast<T*>(p);
+    void* zero = p + L.mean_bytes;
+    float* dz_buf = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes);
+    float* partial = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes + L.dz_bytes);
+    float* bias_partial = reinterpret_cast<float*>(reinterpret_cast<char*>(partial) + L.partial_bytes);
+    float* D = reinterpret_cast<float*>(reinterpret_cast<char*>(bias_partial) + L.bias_bytes);
+    if (n_src == 0) Hsrc = zero;   // nothing is read from it unmasked
+
+    // the means again (same kernel as the forward pass, same rounding to the activation type)
+    hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s);
+    if (st != HOPGNN_OK) return st;
+
+    const float* dZ = dOut;
+    if (relu) {
+        const int64_t n = n_dst * d_out;
+        if (n % 4 == 0 && aligned(out_fwd, 16) && aligned(dOut, 16))
+            hipLaunchKernelGGL(bwd_mask4<Tr>, dim3((unsigned)ceil_div(n / 4, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               static_cast<const R4*>(out_fwd), reinterpret_cast<const float4*>(dOut), n / 4,
+                               reinterpret_cast<float4*>(dz_buf));
+        else
+            hipLaunchKernelGGL(bwd_mask_elem<Tr>, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               static_cast<const T*>(out_fwd), dOut, n, dz_buf);
+        HOPGNN_LAUNCH_CHECK();
+        dZ = dz_buf;
+    }
+
+    const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
+    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16);
+    auto grad_kernel = vec ? bwd_weight_grad<Tr, true> : bwd_weight_grad<Tr, false>;
+    hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
+                       static_cast<const T*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out, L.rows_per_split, tiles_n,
+                       partial, gbias != nullptr ? bias_partial : nullptr);
+    HOPGNN_LAUNCH_CHECK();
+    const int64_t red = (int64_t)2 * d_in * d_out + d_out;
+    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
+                       bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias);
+    HOPGNN_LAUNCH_CHECK();
+
+    if (dHsrc != nullptr && n_src > 0) {
+        const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
+        if (gy > 65535) return HOPGNN_ERANGE;
+        hipLaunchKernelGGL(bwd_input_grad<Tr>, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0,
+                           s, dZ, static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D);
+        HOPGNN_LAUNCH_CHECK();
+        const int group = mean_group(d_in);
+        hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc);
+        HOPGNN_LAUNCH_CHECK();
+    }
+    return HOPGNN_OK;
+}
+
+}  // namespace hopgnn
 
 extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
                                          const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
@@ -392,7 +507,7 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
                                          const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out,
                                          float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
                                          size_t ws_bytes, void* stream) {
-    if (dt != HOPGNN_F32) return HOPGNN_EINVAL;   // 2-byte activations: not in this version
+    if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
@@ -418,55 +533,12 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
     const BwdWs L = bwd_ws_layout(n_dst, d_in, d_out, dHsrc != nullptr);
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
-    char* p = static_cast<char*>(ws);
-    float* mean = reinterpret_cast<float*>(p);
-    void* zero = p + L.mean_bytes;
-    float* dz_buf = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes);
-    float* partial = reinterpret_cast<float*>(p + L.mean_bytes + L.zero_bytes + L.dz_bytes);
-    float* bias_partial = reinterpret_cast<float*>(reinterpret_cast<char*>(partial) + L.partial_bytes);
-    float* D = reinterpret_cast<float*>(reinterpret_cast<char*>(bias_partial) + L.bias_bytes);
-    if (n_src == 0) Hsrc = zero;   // nothing is read from it unmasked
-
-    // the means again (same kernel as the forward pass)
-    hopgnn_status st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s);
-    if (st != HOPGNN_OK) return st;
-
-    const float* dZ = dOut;
-    if (relu) {
-        const int64_t n = n_dst * d_out;
-        if (n % 4 == 0 && aligned(out_fwd, 16) && aligned(dOut, 16))
-            hipLaunchKernelGGL(bwd_mask, dim3((unsigned)ceil_div(n / 4, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                               static_cast<const float4*>(out_fwd), reinterpret_cast<const float4*>(dOut), n / 4,
-                               reinterpret_cast<float4*>(dz_buf));
-        else
-            hipLaunchKernelGGL(bwd_mask_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                               static_cast<const float*>(out_fwd), dOut, n, dz_buf);
-        HOPGNN_LAUNCH_CHECK();
-        dZ = dz_buf;
-    }
-
-    const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
-    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16);
-    hipLaunchKernelGGL(vec ? bwd_weight_grad<true> : bwd_weight_grad<false>, dim3(tiles_k * tiles_n, (unsigned)L.n_splits),
-                       dim3(kBwdThreads), 0, s, static_cast<const float*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out,
-                       L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr);
-    HOPGNN_LAUNCH_CHECK();
-    const int64_t red = (int64_t)2 * d_in * d_out + d_out;
-    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
-                       bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias);
-    HOPGNN_LAUNCH_CHECK();
-
-    if (dHsrc != nullptr && n_src > 0) {
-        const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
-        if (gy > 65535) return HOPGNN_ERANGE;
-        hipLaunchKernelGGL(bwd_input_grad, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0, s,
-                           dZ, static_cast<const float*>(W_self), static_cast<const float*>(W_neigh), n_dst, d_in,
-                           d_out, D);
-        HOPGNN_LAUNCH_CHECK();
-        const int group = mean_group(d_in);
-        hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc);
-        HOPGNN_LAUNCH_CHECK();
-    }
-    return HOPGNN_OK;
+    if (dt == HOPGNN_F32)
+        return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
+                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+    if (dt == HOPGNN_BF16)
+        return sage_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu,
+                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+    return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
+                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
 }

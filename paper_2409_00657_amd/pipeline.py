@@ -15,6 +15,7 @@ from typing import List, Optional, Sequence
 import torch
 
 from . import binding as hb
+from . import synth
 
 
 @dataclass
@@ -174,17 +175,22 @@ class HotPath:
 
     def enable_backward(self) -> None:
         """Allocate gradient accumulators (one set per layer, fp32, zero) and the buffers of the
-        backward pass.  The loss used by the harness is L = 1/2 |H_L|^2, so dL/dH_L = H_L."""
-        if self.X.dtype != torch.float32:
-            raise hb.HopgnnError("backward is implemented for fp32 activations")
+        backward pass.  Gradients are fp32 whatever the activation type.  The loss used by the
+        harness is L = 1/2 |H_L|^2 for fp32 activations (dL/dH_L = H_L, read in place) and
+        L = <G, H_L> with a fixed G for 2-byte activations (dL/dH_L = G, fp32)."""
         sh, dev = self.shape, self.X.device
         L = sh.n_layers
+        if self.X.dtype == torch.float32:
+            self.dHL = self.H[L - 1]
+        else:
+            self.dHL = synth.weight(self.H[L - 1].shape[0], self.H[L - 1].shape[1], torch.float32, stream=99,
+                                    device=dev)
         self.gW = [(torch.zeros_like(Ws, dtype=torch.float32), torch.zeros_like(Wn, dtype=torch.float32),
                     None if b is None else torch.zeros_like(b, dtype=torch.float32)) for Ws, Wn, b in self.weights]
         hidden = self.weights[0][0].shape[1]
         # dH[k] = gradient of layer k's output rows (k = 1..L-1), produced by layer k+1's backward
         self.dH = [torch.empty((sh.n_dst(k), hidden), dtype=torch.float32, device=dev) for k in range(1, L)]
-        ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(torch.float32, sh.n_dst(k), self.weights[k - 1][0].shape[0],
+        ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
                                                    hidden, k > 1) for k in range(1, L + 1))
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self._bwd_args = []
@@ -193,7 +199,7 @@ class HotPath:
             for k in range(L, 0, -1):
                 fwd = self._layer_args[b][k - 1]
                 (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, _bias, d_out, relu, out, _ws, _wsb) = fwd
-                d_out_grad = self.H[L - 1].data_ptr() if k == L else self.dH[k - 1].data_ptr()
+                d_out_grad = self.dHL.data_ptr() if k == L else self.dH[k - 1].data_ptr()
                 gWs, gWn, gb = self.gW[k - 1]
                 per_batch.append((src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, out, relu, d_out_grad,
                                   d_out, gWs.data_ptr(), gWn.data_ptr(), None if gb is None else gb.data_ptr(),

@@ -127,12 +127,53 @@ def test_backward_chain_on_a_sampled_batch(hb, orc):
     assert rel_err(to_f64(g1[0]), ref1[0]) <= 2e-5 and rel_err(to_f64(g1[1]), ref1[1]) <= 2e-5
 
 
-def test_sage_bwd_rejects_unsupported(hb):
-    H = torch.zeros((4, 8), dtype=torch.bfloat16, device=DEV)
-    W = torch.zeros((8, 8), dtype=torch.bfloat16, device=DEV)
+@pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("shape", [(1500, 1111, 128, 128, 12), (4000, 777, 100, 256, 16), (300, 65, 7, 5, 4)])
+def test_sage_bwd_two_byte_activations_vs_oracle(hb, orc, dt, shape):
+    """bf16 / fp16 rows, weights and stored forward output; fp32 gradients in and out."""
+    from helpers import ORC_DT, TOL
+    n_src, n_dst, d_in, d_out, max_len = shape
+    rng = np.random.default_rng(n_src * 11 + d_in)
+    f = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32))
+    H = f(n_src, d_in).to(dt).to(DEV)
+    Ws = (f(d_in, d_out) / np.sqrt(d_in)).to(dt).to(DEV)
+    Wn = (f(d_in, d_out) / np.sqrt(d_in)).to(dt).to(DEV)
+    dOut = rng.standard_normal((n_dst, d_out)).astype(np.float32)
+    indptr, idx = _rand_csr(rng, n_dst, n_src, max_len)
+    self_idx = rng.integers(0, n_src, size=n_dst).astype(np.int32)
+    self_idx[rng.random(n_dst) < 0.05] = -1
+    odt = ORC_DT[dt]
+    Hb, Wsb, Wnb = to_bits(H), to_bits(Ws), to_bits(Wn)
+    out_bits = orc.round_store(orc.sage_fwd(Hb, odt, self_idx, indptr, idx, Wsb, Wnb, None, True), odt)
+    out_fwd = torch.from_numpy(out_bits.view(np.int16)).view(dt).to(DEV)
+    t = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    for relu, want_dh, use_bias in [(True, True, True), (False, False, False)]:
+        ref = orc.sage_bwd(Hb, odt, self_idx, indptr, idx, Wsb, Wnb, out_bits if relu else None, relu,
+                           dOut.astype(np.float64), want_dH=want_dh)
+        gWs = torch.zeros((d_in, d_out), device=DEV)
+        gWn = torch.zeros((d_in, d_out), device=DEV)
+        gb = torch.zeros(d_out, device=DEV) if use_bias else None
+        dH = torch.full((n_src, d_in), 7.0, device=DEV) if want_dh else None
+        ws = torch.empty(hb.hopgnn_sage_bwd_ws_bytes(dt, n_dst, d_in, d_out, want_dh), dtype=torch.uint8, device=DEV)
+        ws.fill_(0x5A)
+        hb.hopgnn_sage_bwd(H, n_src, t(self_idx), t(indptr), t(idx), n_dst, Ws, Wn, out_fwd if relu else None, relu,
+                           t(dOut), gWs, gWn, gb, dH, ws)
+        torch.cuda.synchronize()
+        # only the neighbour mean is rounded to the 2-byte type; everything else is fp32 arithmetic
+        assert rel_err(to_f64(gWs), ref[0]) <= 2e-5, (shape, relu)
+        assert rel_err(to_f64(gWn), ref[1]) <= TOL[dt], (shape, relu)
+        if use_bias:
+            assert rel_err(to_f64(gb), ref[2]) <= 2e-5
+        if want_dh:
+            assert rel_err(to_f64(dH), ref[3]) <= 2e-5
+
+
+def test_sage_bwd_rejects_identity_self_without_rows(hb):
+    H = torch.zeros((4, 8), device=DEV)
+    W = torch.zeros((8, 8), device=DEV)
     z = torch.zeros((8, 8), device=DEV)
-    ip = torch.zeros(5, dtype=torch.int32, device=DEV)
+    ip = torch.zeros(7, dtype=torch.int32, device=DEV)
     ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
-    with pytest.raises(hb.HopgnnError):
-        hb.hopgnn_sage_bwd(H, 4, None, ip, ip, 4, W, W, None, False, torch.zeros((4, 8), device=DEV), z, z, None,
+    with pytest.raises(hb.HopgnnError):     # 6 destination rows with identity self, but only 4 source rows
+        hb.hopgnn_sage_bwd(H, 4, None, ip, ip, 6, W, W, None, False, torch.zeros((6, 8), device=DEV), z, z, None,
                            None, ws)
