@@ -182,7 +182,7 @@ def main():
     empty_ms = []
     for k in range(1, sh.n_layers + 1):
         stage["sage_l%d" % k] = 0.0
-    U_sum, valid_sum = 0, 0
+    U_sum, valid_sum, U_per_batch_sum = 0, 0, 0
     E = lambda: torch.cuda.Event(enable_timing=True)
     n_replay = min(args.steps, 50)
     st0 = torch.cuda.current_stream().cuda_stream
@@ -206,6 +206,10 @@ def main():
         stage["gather"] += e[2].elapsed_time(e[3])
         U_sum += int(hp.n_uniq.item())
         valid_sum += int((hp.ids >= 0).sum().item())
+        if group > 1:       # reporting only: what per-batch pre-gathering would have fetched
+            for b in range(group):
+                ib = hp.ids[b * sh.n_slots:(b + 1) * sh.n_slots]
+                U_per_batch_sum += int(torch.unique(ib[ib >= 0]).numel())
         for b in range(group):      # one event pair per layer, summed over the group's batches
             for k in range(1, sh.n_layers + 1):
                 a, c = E(), E()
@@ -225,6 +229,8 @@ def main():
     # kernel's duration, so the fraction is a lower bound.  rocprofv3's per-kernel average
     # (profiles/) is the direct figure; the pair minus the empty pair is given beside it.
     gather_ms_raw = sum(gather_ms) / len(gather_ms)
+    gs = sorted(gather_ms)
+    gather_pct = {"p10": gs[len(gs) // 10], "p50": gs[len(gs) // 2], "p90": gs[(len(gs) * 9) // 10]}
     empty_ms_avg = sum(empty_ms) / len(empty_ms)
     gather_ms_avg = gather_ms_raw
     gather_ms_net = max(gather_ms_raw - empty_ms_avg, 1e-6)
@@ -264,6 +270,7 @@ def main():
         "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
         "unique_rows_per_step": U_avg,
         "unique_over_valid_slots": U_sum / max(valid_sum, 1),
+        "unique_group_over_sum_of_per_batch_unique": (U_sum / U_per_batch_sum) if group > 1 else 1.0,
         "valid_slot_fraction": valid_sum / (n_replay * group * sh.n_slots),
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
         "stage_work": stage_work,
@@ -271,7 +278,8 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
                      "traffic": gather_bytes * GATHER_TRAFFIC_OVER_ALGORITHMIC,
                      "algorithmic_bytes_per_launch": gather_bytes,
-                     "avg_launch_ms": gather_ms_avg, "empty_event_pair_ms": empty_ms_avg,
+                     "avg_launch_ms": gather_ms_avg, "launch_ms_percentiles": gather_pct,
+                     "empty_event_pair_ms": empty_ms_avg,
                      "achieved_net_of_marker_cost": gather_bytes / (gather_ms_net * 1e-3) / 1e9},
     }
     if not args.no_cpu_baseline:

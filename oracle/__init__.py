@@ -71,6 +71,13 @@ def lib() -> ctypes.CDLL:
         L.orc_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                    c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
                                    c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.orc_gcn_fwd.restype = c.c_int
+        L.orc_gcn_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p]
+        L.orc_gat_fwd.restype = c.c_int
+        L.orc_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                  c.c_int32, c.c_void_p]
         _lib = L
     return _lib
 
@@ -211,6 +218,50 @@ def sage_fwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, bias, relu):
                             _p(out))
     if rc:
         raise ValueError("orc_sage_fwd failed: %d" % rc)
+    return out
+
+
+def gcn_fwd(Hsrc, dtype, self_idx, indptr, idx, W, bias, norm, relu):
+    """One GCN-style layer (norm 0: sum, 1: mean over the vertex and its neighbours) in float64."""
+    npdt = _NP_OF[dtype]
+    Hsrc = _arr(Hsrc, npdt)
+    W = _arr(W, npdt)
+    bias = None if bias is None else _arr(bias, npdt)
+    n_src, d_in = Hsrc.shape
+    d_out = W.shape[1]
+    assert W.shape == (d_in, d_out)
+    indptr = _arr(indptr, np.int32)
+    idx = _arr(idx, np.int32)
+    n_dst = len(indptr) - 1
+    self_idx = None if self_idx is None else _arr(self_idx, np.int32)
+    out = np.empty((n_dst, d_out), np.float64)
+    rc = lib().orc_gcn_fwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W),
+                           _p(bias), d_out, int(norm), int(bool(relu)), _p(out))
+    if rc:
+        raise ValueError("orc_gcn_fwd failed: %d" % rc)
+    return out
+
+
+def gat_fwd(Hsrc, dtype, self_idx, indptr, idx, W, a_src, a_dst, bias, n_heads, relu):
+    """One graph-attention layer (heads concatenated) in float64 -> out[n_dst, d_out]."""
+    npdt = _NP_OF[dtype]
+    Hsrc = _arr(Hsrc, npdt)
+    W = _arr(W, npdt)
+    a_src = _arr(a_src, npdt)
+    a_dst = _arr(a_dst, npdt)
+    bias = None if bias is None else _arr(bias, npdt)
+    n_src, d_in = Hsrc.shape
+    d_out = W.shape[1]
+    assert W.shape == (d_in, d_out) and a_src.size == d_out and a_dst.size == d_out
+    indptr = _arr(indptr, np.int32)
+    idx = _arr(idx, np.int32)
+    n_dst = len(indptr) - 1
+    self_idx = None if self_idx is None else _arr(self_idx, np.int32)
+    out = np.empty((n_dst, d_out), np.float64)
+    rc = lib().orc_gat_fwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W),
+                           _p(a_src), _p(a_dst), _p(bias), d_out, int(n_heads), int(bool(relu)), _p(out))
+    if rc:
+        raise ValueError("orc_gat_fwd failed: %d" % rc)
     return out
 
 

@@ -18,7 +18,9 @@
  *     where the hash is a three-round chain of the SplitMix64 output finaliser;
  *   - a micrograph is a fixed-shape tree of slots stored level-major;
  *   - the pre-gather set is the ascending, duplicate-free list of valid IDs;
- *   - the layer is GraphSAGE-mean:  act(x_self W_self + mean(nbrs) W_neigh + b).
+ *   - the layer is GraphSAGE-mean:  act(x_self W_self + mean(nbrs) W_neigh + b);
+ *     the GCN-style and attention layers the evaluation also trains are defined at
+ *     orc_gcn_fwd and orc_gat_fwd.
  *
  * All floating point is done in double; the caller decides how a result is
  * rounded for storage (orc_round_store does one round-to-nearest-even step).
@@ -397,6 +399,132 @@ int orc_sage_fwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in,
     }
     free(xs);
     free(mn);
+    return rc;
+}
+
+/*
+ * GCN-style layer (the paper's evaluation trains GCN next to GraphSAGE and GAT and
+ * describes a layer only as "aggregation (like addition or averaging) over the
+ * neighbouring features, then a neural transform", section 2).  Reading: one weight
+ * matrix applied to the aggregate of the vertex itself and its sampled neighbours,
+ *   a   = x_self + sum of Hsrc[idx[e], :] over the valid entries e     (norm 0: sum)
+ *   a   = that sum / (c + [self is valid])                              (norm 1: mean)
+ *   out = act(a W + b)
+ * i.e. (A + I) H W and D^-1 (A + I) H W on the sampled block, parallel edges counted.
+ * A negative self index contributes nothing (and is not counted); no terms -> a = 0.
+ */
+int orc_gcn_fwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in,
+                const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                int64_t n_dst, const void *W, const void *bias, int32_t d_out,
+                int32_t norm, int32_t relu, double *out)
+{
+    double *a = (double *)malloc(sizeof(double) * (size_t)d_in);
+    if (!a) return 2;
+    int rc = 0;
+    for (int64_t r = 0; r < n_dst && !rc; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        if (s >= n_src) { rc = 3; break; }
+        int64_t terms = 0;
+        for (int32_t k = 0; k < d_in; ++k) a[k] = 0.0;
+        if (s >= 0) {
+            for (int32_t k = 0; k < d_in; ++k) a[k] += load_elem(Hsrc, dtype, s * d_in + k);
+            ++terms;
+        }
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            int64_t u = idx[e];
+            if (u < 0) continue;
+            if (u >= n_src) { rc = 3; break; }
+            for (int32_t k = 0; k < d_in; ++k) a[k] += load_elem(Hsrc, dtype, u * d_in + k);
+            ++terms;
+        }
+        if (rc) break;
+        if (norm && terms > 0)
+            for (int32_t k = 0; k < d_in; ++k) a[k] /= (double)terms;
+        for (int32_t n = 0; n < d_out; ++n) {
+            double acc = bias ? load_elem(bias, dtype, n) : 0.0;
+            for (int32_t k = 0; k < d_in; ++k) acc += a[k] * load_elem(W, dtype, (int64_t)k * d_out + n);
+            if (relu && acc < 0.0) acc = 0.0;
+            out[r * d_out + n] = acc;
+        }
+    }
+    free(a);
+    return rc;
+}
+
+/*
+ * Graph-attention layer (GAT, Velickovic et al. 2018, the third model of the paper's
+ * evaluation).  n_heads heads of width d_head = d_out / n_heads, outputs concatenated:
+ *   z_u        = Hsrc[u] W                                   (d_out values, head-major)
+ *   s_src[u,h] = <z_u[h], a_src[h]>,  s_dst[u,h] = <z_u[h], a_dst[h]>
+ * For destination row r with self row s the attended entries are s itself (if s >= 0)
+ * followed by the valid idx entries of its segment, parallel edges kept:
+ *   e[u,h]     = LeakyReLU_0.2( s_dst[s,h] + s_src[u,h] )   (s_dst term 0 if s < 0)
+ *   alpha      = softmax of e over the entries, per head
+ *   out[r,h]   = act( sum alpha[u,h] z_u[h] + b[h] );  no entries -> act(b)
+ */
+int orc_gat_fwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in,
+                const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                int64_t n_dst, const void *W, const void *a_src, const void *a_dst,
+                const void *bias, int32_t d_out, int32_t n_heads, int32_t relu, double *out)
+{
+    if (n_heads < 1 || d_out % n_heads != 0) return 1;
+    const int32_t dh = d_out / n_heads;
+    double *Z = (double *)malloc(sizeof(double) * (size_t)(n_src > 0 ? n_src : 1) * (size_t)d_out);
+    double *ss = (double *)malloc(sizeof(double) * (size_t)(n_src > 0 ? n_src : 1) * (size_t)n_heads);
+    double *sd = (double *)malloc(sizeof(double) * (size_t)(n_src > 0 ? n_src : 1) * (size_t)n_heads);
+    if (!Z || !ss || !sd) { free(Z); free(ss); free(sd); return 2; }
+    for (int64_t u = 0; u < n_src; ++u) {
+        for (int32_t n = 0; n < d_out; ++n) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < d_in; ++k)
+                acc += load_elem(Hsrc, dtype, u * d_in + k) * load_elem(W, dtype, (int64_t)k * d_out + n);
+            Z[u * d_out + n] = acc;
+        }
+        for (int32_t h = 0; h < n_heads; ++h) {
+            double ps = 0.0, pd = 0.0;
+            for (int32_t j = 0; j < dh; ++j) {
+                ps += Z[u * d_out + h * dh + j] * load_elem(a_src, dtype, h * dh + j);
+                pd += Z[u * d_out + h * dh + j] * load_elem(a_dst, dtype, h * dh + j);
+            }
+            ss[u * n_heads + h] = ps;
+            sd[u * n_heads + h] = pd;
+        }
+    }
+    int rc = 0;
+    for (int64_t r = 0; r < n_dst && !rc; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        if (s >= n_src) { rc = 3; break; }
+        int64_t seg = indptr[r + 1] - indptr[r];
+        int64_t *ent = (int64_t *)malloc(sizeof(int64_t) * (size_t)(seg + 1));
+        double *w = (double *)malloc(sizeof(double) * (size_t)(seg + 1));
+        if (!ent || !w) { free(ent); free(w); rc = 2; break; }
+        int64_t m = 0;
+        if (s >= 0) ent[m++] = s;
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            if (idx[e] < 0) continue;
+            if (idx[e] >= n_src) { rc = 3; break; }
+            ent[m++] = idx[e];
+        }
+        for (int32_t h = 0; h < n_heads && !rc; ++h) {
+            double mx = -INFINITY, den = 0.0;
+            for (int64_t i = 0; i < m; ++i) {
+                double e = (s >= 0 ? sd[s * n_heads + h] : 0.0) + ss[ent[i] * n_heads + h];
+                w[i] = e > 0.0 ? e : 0.2 * e;
+                if (w[i] > mx) mx = w[i];
+            }
+            for (int64_t i = 0; i < m; ++i) { w[i] = exp(w[i] - mx); den += w[i]; }
+            for (int32_t j = 0; j < dh; ++j) {
+                double acc = 0.0;
+                for (int64_t i = 0; i < m; ++i) acc += (w[i] / den) * Z[ent[i] * d_out + h * dh + j];
+                acc += bias ? load_elem(bias, dtype, h * dh + j) : 0.0;
+                if (relu && acc < 0.0) acc = 0.0;
+                out[r * d_out + h * dh + j] = acc;
+            }
+        }
+        free(ent);
+        free(w);
+    }
+    free(Z); free(ss); free(sd);
     return rc;
 }
 
