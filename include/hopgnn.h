@@ -200,6 +200,46 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               size_t ws_bytes, void *stream);
 
 /*
+ * The other two layer types the paper's evaluation trains (experimental setup: GCN, GraphSAGE,
+ * GAT; section 2 describes a layer as an aggregation - addition or averaging - over the sampled
+ * neighbours followed by a neural transform).  Same inputs as hopgnn_sage_fwd (Hsrc, self_idx,
+ * indptr, idx: see there), one weight matrix W DEVICE [d_in x d_out] of type dt.
+ *
+ * hopgnn_gcn_fwd   out[r] = act( agg_r W + bias ),
+ *     agg_r = x_r + sum of Hsrc[idx[e]] over the valid entries e of row r     (norm = 0)
+ *     agg_r = that sum / (number of terms)                                     (norm = 1)
+ *   i.e. (A+I) H W and D^-1 (A+I) H W on the sampled block, parallel edges counted.  A negative
+ *   self index adds nothing and is not counted; no terms gives agg_r = 0.  For 2-byte types
+ *   agg_r is rounded to dt before the product.
+ *
+ * hopgnn_gat_fwd   graph attention with n_heads heads (1..16, d_out divisible by it) of width
+ *   d_head = d_out / n_heads, concatenated:  z_u = Hsrc[u] W (computed once per SOURCE row and
+ *   kept in fp32 whatever dt is);  score(r,u,h) = LeakyReLU_0.2( <z_self(r)[h], a_dst[h]> + <z_u[h], a_src[h]> );
+ *   alpha = softmax of the scores over {self(r)} + the valid entries of row r (parallel edges
+ *   kept; a negative self index is left out and its a_dst term is 0);
+ *   out[r,h] = act( sum alpha z_u[h] + bias[h] ); a row without entries gives act(bias).
+ *   a_src, a_dst DEVICE [d_out] of type dt (head-major, like the columns of W).
+ *
+ * bias DEVICE [d_out] or NULL; out DEVICE [n_dst x d_out] of type dt; ws DEVICE scratch of the
+ * matching *_ws_bytes query (note that the attention layer's is sized by n_src), 256-byte
+ * aligned.  Errors as for hopgnn_sage_fwd.
+ */
+size_t hopgnn_gcn_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out);
+
+hopgnn_status hopgnn_gcn_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                             int64_t n_dst, const void *W, const void *bias, int32_t d_out, int32_t norm,
+                             int32_t relu, void *out, void *ws, size_t ws_bytes, void *stream);
+
+size_t hopgnn_gat_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out, int32_t n_heads);
+
+hopgnn_status hopgnn_gat_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                             int64_t n_dst, const void *W, const void *a_src, const void *a_dst,
+                             const void *bias, int32_t d_out, int32_t n_heads, int32_t relu, void *out,
+                             void *ws, size_t ws_bytes, void *stream);
+
+/*
  * GraphSAGE-mean layer backward with in-place gradient accumulation (paper section 5.1,
  * steps 3-4: every micrograph batch runs forward and backward on the server it sits on and
  * the gradients are accumulated until the subgraph is done; discussion section: the

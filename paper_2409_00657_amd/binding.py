@@ -26,7 +26,8 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_sage_fwd_ws_bytes", "hopgnn_sage_fwd", "hopgnn_sage_bwd_ws_bytes", "hopgnn_sage_bwd",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
-           "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd"]
+           "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
+           "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -118,6 +119,18 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_gcn_fwd_ws_bytes.restype = c.c_size_t
+    L.hopgnn_gcn_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32]
+    L.hopgnn_gcn_fwd.restype = c.c_int
+    L.hopgnn_gcn_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                 c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p,
+                                 c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_gat_fwd_ws_bytes.restype = c.c_size_t
+    L.hopgnn_gat_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
+    L.hopgnn_gat_fwd.restype = c.c_int
+    L.hopgnn_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                 c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                 c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_batch_fwd.restype = c.c_int
     L.hopgnn_batch_fwd.argtypes = [c.POINTER(BatchPlan), c.c_void_p, c.POINTER(c.c_uint64), c.c_int32, c.c_void_p,
                                    c.c_void_p]
@@ -275,3 +288,31 @@ def hopgnn_batch_fwd(plan: BatchPlan, seeds: torch.Tensor, keys, out: torch.Tens
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
     _check(load_library().hopgnn_batch_fwd(ctypes.byref(plan), seeds.data_ptr(), karr, n, out.data_ptr(), st),
            "hopgnn_batch_fwd")
+
+
+def hopgnn_gcn_fwd_ws_bytes(dtype: torch.dtype, n_dst: int, d_in: int, d_out: int) -> int:
+    return int(load_library().hopgnn_gcn_fwd_ws_bytes(DTYPE_OF[dtype], n_dst, d_in, d_out))
+
+
+def hopgnn_gcn_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                   idx: torch.Tensor, n_dst: int, W: torch.Tensor, bias: Optional[torch.Tensor], norm: int, relu: bool,
+                   out: torch.Tensor, ws: torch.Tensor) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gcn_fwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                       _ptr(idx), n_dst, _ptr(W), _ptr(bias), d_out, norm, 1 if relu else 0, _ptr(out),
+                                       _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_gcn_fwd")
+
+
+def hopgnn_gat_fwd_ws_bytes(dtype: torch.dtype, n_src: int, d_in: int, d_out: int, n_heads: int) -> int:
+    return int(load_library().hopgnn_gat_fwd_ws_bytes(DTYPE_OF[dtype], n_src, d_in, d_out, n_heads))
+
+
+def hopgnn_gat_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                   idx: torch.Tensor, n_dst: int, W: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
+                   bias: Optional[torch.Tensor], n_heads: int, relu: bool, out: torch.Tensor, ws: torch.Tensor) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gat_fwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                       _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(bias), d_out, n_heads,
+                                       1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_gat_fwd")

@@ -69,6 +69,32 @@ __device__ __forceinline__ void project_epilogue(floatx16 (&acc)[TM][TN], int64_
     }
 }
 
+// fp32 output from a kernel whose inputs are 2-byte (the attention layer keeps its projected
+// rows unrounded): 32 consecutive floats of a row per half wave.
+template <typename Tr, int TM, int TN>
+__device__ __forceinline__ void project_epilogue_f32out(floatx16 (&acc)[TM][TN], int64_t row0, int32_t col0,
+                                                        int lane, int64_t n_dst, int32_t d_out,
+                                                        const typename Tr::store_t* bias, int relu, float* out) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int32_t col = col0 + tn * 32 + (lane & 31);
+        if (col >= d_out) continue;
+        const float b = bias != nullptr ? Tr::to_f(bias[col]) : 0.f;
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int64_t row = row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                if (row < n_dst) {
+                    float x = acc[tm][tn][i] + b;
+                    if (relu) x = fmaxf(x, 0.f);
+                    out[row * d_out + col] = x;
+                }
+            }
+        }
+    }
+}
+
 // 2-byte outputs: a lane of an MFMA tile holds single elements of 16 different rows, so
 // storing them directly issues 2-byte writes (64-byte pieces of two rows per instruction).
 // Instead each wave passes one 32-row band of its tiles through a private piece of LDS
@@ -125,8 +151,8 @@ __global__ void __launch_bounds__(kProjThreads)
 sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                  const float* __restrict__ Mean, const float* __restrict__ Wself,
                  const float* __restrict__ Wneigh, const float* __restrict__ bias, int64_t n_dst,
-                 int32_t d_in, int32_t d_out, int relu, uint32_t n_tiles_n, const float* __restrict__ Zero,
-                 float* __restrict__ out) {
+                 int32_t d_in, int32_t k_total, int32_t d_out, int relu, uint32_t n_tiles_n,
+                 const float* __restrict__ Zero, float* __restrict__ out) {
     constexpr int LDA = BK + 4, LDB = BN + 4;   // LDA/4 odd: conflict-free 128-bit reads
     static_assert(BK % 8 == 0 && (LDA / 4) % 2 == 1, "K tile");
     constexpr int TM = BM / 64, TN = BN / 64;
@@ -144,7 +170,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int K = 2 * d_in;
+    const int K = k_total;
 
     // rows this thread stages, fixed for the whole K loop
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
@@ -305,9 +331,9 @@ template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
 __global__ void __launch_bounds__(64 * WM * WN)
 sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                 const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
-                const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_in,
+                const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_in, int32_t k_total,
                 int32_t d_out, int relu, uint32_t n_tiles_n, const uint16_t* __restrict__ Zero,
-                typename Tr::store_t* __restrict__ out) {
+                typename Tr::store_t* __restrict__ out, int out_f32) {
     constexpr int LD = BK + 8;
     static_assert(kKPad16 % BK == 0, "Wt padding must cover whole K tiles");
     constexpr int NT = 64 * WM * WN;                      // threads: WM x WN waves
@@ -326,7 +352,7 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int K = 2 * d_in;
+    const int K = k_total;
 
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
 #pragma unroll
@@ -444,7 +470,10 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
         compute(1);
         lds_barrier();
     }
-    if (VEC && (d_out & 7) == 0) {
+    if (out_f32) {     // `out` is a float array: unrounded result
+        project_epilogue_f32out<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out, bias,
+                                            relu, reinterpret_cast<float*>(out));
+    } else if (VEC && (d_out & 7) == 0) {
         // every wave is past its last LDS read of the tiles: reuse that LDS, one band per wave
         constexpr int BAND = 32 * (32 * TN + 8);
         static_assert((size_t)WM * WN * BAND <= (size_t)2 * (BM + BN) * LD, "epilogue bands exceed the tile LDS");
@@ -467,8 +496,8 @@ static uint32_t project_grid(int64_t n_dst, int BM, uint32_t n_tiles_n) {
 template <int BM, int BN, int BK>
 static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                         const void* mean, const void* Ws, const void* Wn, const void* bias,
-                                        int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
-                                        void* out) {
+                                        int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
+                                        const void* zero, void* out) {
     const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
     const dim3 grid(project_grid(n_dst, BM, ntn));
     auto a = static_cast<const float*>(Hsrc);
@@ -484,8 +513,8 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
         return HOPGNN_EHIP;
-    hipLaunchKernelGGL(kern, grid, dim3(kProjThreads), lds, s, a, self_idx, m, ws, wn, b, n_dst, d_in, d_out, relu,
-                       ntn, z, o);
+    hipLaunchKernelGGL(kern, grid, dim3(kProjThreads), lds, s, a, self_idx, m, ws, wn, b, n_dst, d_in, k_total, d_out,
+                       relu, ntn, z, o);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -493,8 +522,8 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
 template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
 static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                          const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
-                                         int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
-                                         void* out) {
+                                         int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
+                                         const void* zero, void* out, int out_f32) {
     using T = typename Tr::store_t;
     constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(uint16_t);
     auto kern = sage_project_16<Tr, BM, BN, BK, WM, WN, VEC>;
@@ -506,8 +535,8 @@ static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const 
     const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
     hipLaunchKernelGGL(kern, dim3(project_grid(n_dst, BM, ntn)), dim3(64 * WM * WN), lds, s,
                        static_cast<const uint16_t*>(Hsrc), self_idx, static_cast<const uint16_t*>(mean), Wt,
-                       KP, static_cast<const T*>(bias), n_dst, d_in, d_out, relu, ntn,
-                       static_cast<const uint16_t*>(zero), static_cast<T*>(out));
+                       KP, static_cast<const T*>(bias), n_dst, d_in, k_total, d_out, relu, ntn,
+                       static_cast<const uint16_t*>(zero), static_cast<T*>(out), out_f32);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -515,26 +544,48 @@ static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const 
 template <typename Tr, int BM, int BN, int BK, int WM, int WN>
 static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                        const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
-                                       int64_t n_dst, int32_t d_in, int32_t d_out, int relu, const void* zero,
-                                       void* out) {
-    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, d_out, relu, zero, out)
-               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, d_out, relu, zero, out);
+                                       int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
+                                       const void* zero, void* out, int out_f32) {
+    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32)
+               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
 }
 
-// Workspace: [ mean : n_dst x d_in ][ Wt : NP x KP, 2-byte types only ][ zero row ]
-struct SageWs {
-    size_t mean_bytes, wt_bytes, zero_bytes, total;
-    int32_t KP, NP;
-};
-static SageWs sage_ws_layout(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out) {
-    SageWs L{};
-    L.mean_bytes = align_up((size_t)n_dst * (size_t)d_in * dtype_size(dt), 256);
-    L.KP = (int32_t)(ceil_div(2 * (int64_t)d_in, kKPad16) * kKPad16);
+ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out) {
+    ProjWs L{};
+    L.agg_bytes = align_up((size_t)n_rows * (size_t)d_in * dtype_size(dt), 256);
+    L.KP = (int32_t)(ceil_div((int64_t)k_total, kKPad16) * kKPad16);
     L.NP = (int32_t)(ceil_div(d_out, 256) * 256);
     L.wt_bytes = dt == HOPGNN_F32 ? 0 : align_up((size_t)L.KP * (size_t)L.NP * 2, 256);
     L.zero_bytes = align_up(((size_t)2 * d_in + 64) * dtype_size(dt), 256);
-    L.total = L.mean_bytes + L.wt_bytes + L.zero_bytes;
+    L.total = L.agg_bytes + L.wt_bytes + L.zero_bytes;
     return L;
+}
+
+hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                               const void* mean, const void* W_self, const void* W_neigh, const uint16_t* Wt,
+                               int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
+                               int32_t d_out, int relu, const void* zero, void* out, int out_f32) {
+    const int per16 = dt == HOPGNN_F32 ? 4 : 8;
+    const int64_t work = ceil_div(n_dst, 128) * ceil_div(d_out, 128);   // 128 x 128 output tiles
+    if (dt == HOPGNN_F32) {
+        const bool vec = d_in % per16 == 0 && d_out % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16) &&
+                         aligned(W_self, 16) && aligned(W_neigh, 16);
+        // large tiles once there is enough work to fill 256 CUs twice over
+        if (d_out > 64 && work >= 512)
+            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out);
+        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out);
+    }
+    const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16);
+    const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
+    const bool big = d_out > 64 && work >= 512;
+    if (dt == HOPGNN_BF16) {
+        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+    }
+    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
 }
 
 }  // namespace hopgnn
@@ -543,7 +594,7 @@ using namespace hopgnn;
 
 extern "C" size_t hopgnn_sage_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out) {
     if (n_dst < 0 || d_in < 1 || d_out < 1) return 0;
-    return sage_ws_layout(dt, n_dst, d_in, d_out).total;
+    return proj_ws_layout(dt, n_dst, d_in, 2 * d_in, d_out).total;
 }
 
 extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
@@ -562,19 +613,19 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
-    const SageWs L = sage_ws_layout(dt, n_dst, d_in, d_out);
+    const ProjWs L = proj_ws_layout(dt, n_dst, d_in, 2 * d_in, d_out);
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     hipStream_t s = static_cast<hipStream_t>(stream);
     void* mean = ws;
-    if (n_src == 0) Hsrc = static_cast<char*>(ws) + L.mean_bytes + L.wt_bytes;   // nothing is read from it unmasked
-    uint16_t* Wt = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + L.mean_bytes);
-    void* zero = static_cast<char*>(ws) + L.mean_bytes + L.wt_bytes;
+    if (n_src == 0) Hsrc = static_cast<char*>(ws) + L.agg_bytes + L.wt_bytes;   // nothing is read from it unmasked
+    uint16_t* Wt = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + L.agg_bytes);
+    void* zero = static_cast<char*>(ws) + L.agg_bytes + L.wt_bytes;
 
     TransposeJob job{};
     uint32_t n_tr = 0;
     if (dt != HOPGNN_F32) {
         job = TransposeJob{static_cast<const uint16_t*>(W_self), static_cast<const uint16_t*>(W_neigh), Wt, d_in,
-                           d_out, L.KP, L.NP, 0u};
+                           d_out, L.KP, L.NP, 0u, 2 * d_in};
         n_tr = (uint32_t)(L.KP / 32) * (uint32_t)(L.NP / 32);
     }
     hopgnn_status st;
@@ -583,25 +634,6 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
     if (st != HOPGNN_OK) return st;
 
-    const int per16 = dt == HOPGNN_F32 ? 4 : 8;
-    const int64_t work = ceil_div(n_dst, 128) * ceil_div(d_out, 128);   // 128 x 128 output tiles
-    if (dt == HOPGNN_F32) {
-        const bool vec = d_in % per16 == 0 && d_out % per16 == 0 && aligned(Hsrc, 16) &&
-                         aligned(W_self, 16) && aligned(W_neigh, 16);
-        // large tiles once there is enough work to fill 256 CUs twice over
-        if (d_out > 64 && work >= 512)
-            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
-        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, d_out, relu, zero, out);
-    }
-    const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16);
-    const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
-    const bool big = d_out > 64 && work >= 512;
-    if (dt == HOPGNN_BF16) {
-        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-    }
-    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
-    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, L.KP, bias, n_dst, d_in, d_out, relu, zero, out);
+    return project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,
+                            zero, out, 0);
 }

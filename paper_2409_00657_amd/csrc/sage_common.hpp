@@ -57,7 +57,8 @@ union Pack16 {
 
 // Side job of the mean kernels for 2-byte types: the projection wants the weights with k
 // contiguous, Wt[n][k] = (k < d_in ? W_self[k][n] : W_neigh[k - d_in][n]), zero outside
-// [0, 2*d_in) x [0, d_out).  The workgroups after the last mean workgroup each transpose one
+// [0, k_total) x [0, d_out); k_total is 2*d_in for the two-matrix layer and d_in for a layer
+// with one weight matrix (then W_neigh is never read).  The workgroups after the last mean workgroup each transpose one
 // 32 x 32 tile through LDS (coalesced reads and writes), which saves a launch per layer.
 struct TransposeJob {
     const uint16_t* Wself;
@@ -65,7 +66,19 @@ struct TransposeJob {
     uint16_t* Wt;
     int32_t d_in, d_out, KP, NP;
     uint32_t first_block;   // workgroups >= first_block transpose; n_tiles_k = KP / 32
+    int32_t k_total;
 };
+
+// What the segmented aggregation adds to the neighbour rows and how it is normalised:
+// GraphSAGE-mean is {nullptr, 0, 1} (neighbours only, divided by their number); with_self adds
+// the destination's own source row (self_idx, or row r when self_idx is NULL; a negative entry
+// adds nothing) and counts it; divide = 0 leaves the plain sum.
+struct AggSpec {
+    const int32_t* self_idx;
+    int32_t with_self;
+    int32_t divide;
+};
+constexpr AggSpec kAggMean{nullptr, 0, 1};
 
 __device__ __forceinline__ void transpose_w_tile(const TransposeJob& J, uint32_t tile_id) {
     __shared__ uint16_t tile[32][33];
@@ -75,7 +88,7 @@ __device__ __forceinline__ void transpose_w_tile(const TransposeJob& J, uint32_t
     for (int j = ty; j < 32; j += 8) {
         const int k = k0 + j, n = n0 + tx;
         uint16_t v = 0;
-        if (k < 2 * J.d_in && n < J.d_out)
+        if (k < J.k_total && n < J.d_out)
             v = k < J.d_in ? J.Wself[(int64_t)k * J.d_out + n] : J.Wneigh[(int64_t)(k - J.d_in) * J.d_out + n];
         tile[j][tx] = v;
     }
@@ -100,7 +113,8 @@ template <typename Tr>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
-              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job) {
+              uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job,
+              AggSpec agg) {
     if (blockIdx.x >= job.first_block) {
         transpose_w_tile(job, blockIdx.x - job.first_block);
         return;
@@ -112,11 +126,20 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
     const int32_t g = (int32_t)(gid - r * group);
     if (r >= n_dst) return;
     const int32_t beg = indptr[r], end = indptr[r + 1];
+    int64_t self_row = -1;
+    if (agg.with_self) self_row = agg.self_idx != nullptr ? (int64_t)agg.self_idx[r] : r;
     for (int32_t c = g; c < words_per_row; c += group) {
         float acc[Tr::kPer16];
 #pragma unroll
         for (int i = 0; i < Tr::kPer16; ++i) acc[i] = 0.f;
         int32_t cnt = 0;
+        if (self_row >= 0) {
+            Pack16<Tr> v;
+            v.v = Hsrc[self_row * words_per_row + c];
+#pragma unroll
+            for (int i = 0; i < Tr::kPer16; ++i) acc[i] += Tr::to_f(v.e[i]);
+            ++cnt;
+        }
         for (int32_t e = beg; e < end; e += kMeanUnroll) {
             int32_t u[kMeanUnroll];
             Pack16<Tr> v[kMeanUnroll];
@@ -134,7 +157,7 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
                 }
         }
         Pack16<Tr> o;
-        const float fc = (float)cnt;
+        const float fc = agg.divide ? (float)cnt : 1.f;
 #pragma unroll
         for (int i = 0; i < Tr::kPer16; ++i) o.e[i] = Tr::from_f(cnt > 0 ? acc[i] / fc : 0.f);
         Mean[r * words_per_row + c] = o.v;
@@ -147,7 +170,7 @@ __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
                const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
                typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words,
-               TransposeJob job) {
+               TransposeJob job, AggSpec agg) {
     if (blockIdx.x >= job.first_block) {
         transpose_w_tile(job, blockIdx.x - job.first_block);
         return;
@@ -159,9 +182,15 @@ sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __r
     const int32_t g = (int32_t)(gid - r * group);
     if (r >= n_dst) return;
     const int32_t beg = indptr[r], end = indptr[r + 1];
+    int64_t self_row = -1;
+    if (agg.with_self) self_row = agg.self_idx != nullptr ? (int64_t)agg.self_idx[r] : r;
     for (int32_t c = g; c < d_in; c += group) {
         float acc = 0.f;
         int32_t cnt = 0;
+        if (self_row >= 0) {
+            acc += Tr::to_f(Hsrc[self_row * d_in + c]);
+            ++cnt;
+        }
         for (int32_t e = beg; e < end; ++e) {
             const int32_t u = idx[e];
             if (u >= 0) {
@@ -169,7 +198,7 @@ sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __r
                 ++cnt;
             }
         }
-        Mean[r * d_in + c] = Tr::from_f(cnt > 0 ? acc / (float)cnt : 0.f);
+        Mean[r * d_in + c] = Tr::from_f(cnt > 0 ? (agg.divide ? acc / (float)cnt : acc) : 0.f);
     }
 }
 
@@ -184,7 +213,8 @@ static inline int mean_group(int units) {   // lanes per destination row: power 
 template <typename Tr>
 static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const int32_t* idx,
                                  int64_t n_dst, int32_t d_in, void* mean, void* zero_row,
-                                 size_t zero_bytes, TransposeJob job, uint32_t n_transpose_tiles, hipStream_t s) {
+                                 size_t zero_bytes, TransposeJob job, uint32_t n_transpose_tiles, hipStream_t s,
+                                 AggSpec agg = kAggMean) {
     using T = typename Tr::store_t;
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
@@ -196,13 +226,32 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
     if (vec)
         hipLaunchKernelGGL(sage_mean_vec<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
-                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
+                           static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
+                           agg);
     else
         hipLaunchKernelGGL(sage_mean_elem<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
-                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job);
+                           static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
+                           agg);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
+
+// Workspace of a projection: [ aggregate : n_rows x d_in ][ Wt : NP x KP, 2-byte types only ][ zero row ]
+struct ProjWs {
+    size_t agg_bytes, wt_bytes, zero_bytes, total;
+    int32_t KP, NP;
+};
+ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out);
+
+// out = act( [x_self | agg][:, :k_total] * [W_self ; W_neigh][:k_total] + bias ) on MFMA (defined with
+// the projection kernels).  k_total = 2*d_in is the two-matrix GraphSAGE layer, k_total = d_in a
+// plain rows-times-W product over the rows Hsrc[self_idx[r]].  For 2-byte types Wt (row stride KP)
+// must already hold the transposed weights; `zero` is a zeroed row of at least 2*d_in+64 elements.
+// out_f32 != 0: `out` is a float array and receives the unrounded result whatever dt is.
+hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                               const void* agg, const void* W_self, const void* W_neigh, const uint16_t* Wt,
+                               int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
+                               int32_t d_out, int relu, const void* zero, void* out, int out_f32);
 
 }  // namespace hopgnn
