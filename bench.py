@@ -44,6 +44,8 @@ def parse():
                     help="HIP streams (each with its own buffers) that consecutive steps alternate over")
     ap.add_argument("--backward", action="store_true",
                     help="also run the layers' backward pass with in-place gradient accumulation")
+    ap.add_argument("--model", choices=["sage", "gcn", "gat"], default="sage",
+                    help="layer type: GraphSAGE-mean (the headline workload), GCN-style mean, graph attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -118,7 +120,11 @@ def main():
     X = cfg.make_features(device=dev)
     W = cfg.make_weights(device=dev)
     n_streams = max(1, args.streams)
-    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group) for _ in range(n_streams)]
+    if args.model != "sage" and args.backward:
+        print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
+        sys.exit(2)
+    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, model=args.model)
+           for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]      # default priority
     if args.backward:
         for h in hps:
@@ -158,7 +164,8 @@ def main():
             if args.backward:
                 h.backward(b, st)
 
-    step = step_calls if args.backward else step_fwd
+    by_calls = args.backward or args.model != "sage"
+    step = step_calls if by_calls else step_fwd
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -169,7 +176,7 @@ def main():
         e[0].record(streams[i % n_streams])
         e[1].record(streams[i % n_streams])
     torch.cuda.synchronize()
-    marks = gather_ev if args.backward else [(e[0].cuda_event, e[1].cuda_event) for e in gather_ev]
+    marks = gather_ev if by_calls else [(e[0].cuda_event, e[1].cuda_event) for e in gather_ev]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, marks[i])
@@ -243,10 +250,17 @@ def main():
     din = X.shape[1]
     for k in range(1, sh.n_layers + 1):
         n_dst, nnz = sh.n_dst(k), sh.nnz(k)
-        stage_work["sage_l%d" % k] = {
-            "bound": "hbm+mfma",
-            "bytes": group * ((nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es),
-            "flops": group * 2.0 * n_dst * 2 * din * cfg.hidden}
+        if args.model == "sage":
+            flops = 2.0 * n_dst * 2 * din * cfg.hidden
+            nbytes = (nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
+        elif args.model == "gcn":      # one weight matrix over the aggregate
+            flops = 2.0 * n_dst * din * cfg.hidden
+            nbytes = (nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
+        else:                          # projection once per source row, then fp32 rows through the softmax gather
+            n_src = U_avg if k == 1 else sh.n_dst(k - 1)
+            flops = 2.0 * n_src * din * cfg.hidden
+            nbytes = n_src * din * es + (nnz + n_dst) * cfg.hidden * 4 + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
+        stage_work["sage_l%d" % k] = {"bound": "hbm+mfma", "bytes": group * nbytes, "flops": group * flops}
         din = cfg.hidden
     for name, w in stage_work.items():
         t = stage[name] * 1e-3
@@ -265,7 +279,7 @@ def main():
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges,
                    "feature_dim": cfg.d, "batch": cfg.batch, "fanouts": cfg.fanouts,
                    "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots,
-                   "streams": n_streams, "backward": bool(args.backward)},
+                   "streams": n_streams, "backward": bool(args.backward), "layer": args.model},
         "gather_GBps": gather_gbps,
         "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
         "unique_rows_per_step": U_avg,
@@ -282,7 +296,7 @@ def main():
                      "empty_event_pair_ms": empty_ms_avg,
                      "achieved_net_of_marker_cost": gather_bytes / (gather_ms_net * 1e-3) / 1e9},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.model == "sage":   # the oracle's whole-batch chain is the GraphSAGE one
         out["cpu_baseline"] = cpu_baseline(cfg, g, X, W, group, args.cpu_seconds)
     print(json.dumps(out))
 

@@ -219,6 +219,9 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *   kept; a negative self index is left out and its a_dst term is 0);
  *   out[r,h] = act( sum alpha z_u[h] + bias[h] ); a row without entries gives act(bias).
  *   a_src, a_dst DEVICE [d_out] of type dt (head-major, like the columns of W).
+ *   n_src_dev: DEVICE count of the source rows that exist (at most n_src), or NULL for n_src: when
+ *   Hsrc is a pre-gathered buffer of capacity n_src whose row count hopgnn_pregather left on the
+ *   device, only those rows are projected.
  *
  * bias DEVICE [d_out] or NULL; out DEVICE [n_dst x d_out] of type dt; ws DEVICE scratch of the
  * matching *_ws_bytes query (note that the attention layer's is sized by n_src), 256-byte
@@ -233,8 +236,8 @@ hopgnn_status hopgnn_gcn_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, i
 
 size_t hopgnn_gat_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out, int32_t n_heads);
 
-hopgnn_status hopgnn_gat_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
-                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+hopgnn_status hopgnn_gat_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t *n_src_dev,
+                             int32_t d_in, const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
                              int64_t n_dst, const void *W, const void *a_src, const void *a_dst,
                              const void *bias, int32_t d_out, int32_t n_heads, int32_t relu, void *out,
                              void *ws, size_t ws_bytes, void *stream);

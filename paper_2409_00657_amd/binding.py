@@ -128,7 +128,7 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_gat_fwd_ws_bytes.restype = c.c_size_t
     L.hopgnn_gat_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     L.hopgnn_gat_fwd.restype = c.c_int
-    L.hopgnn_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+    L.hopgnn_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_batch_fwd.restype = c.c_int
@@ -310,9 +310,11 @@ def hopgnn_gat_fwd_ws_bytes(dtype: torch.dtype, n_src: int, d_in: int, d_out: in
 
 def hopgnn_gat_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
                    idx: torch.Tensor, n_dst: int, W: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
-                   bias: Optional[torch.Tensor], n_heads: int, relu: bool, out: torch.Tensor, ws: torch.Tensor) -> None:
+                   bias: Optional[torch.Tensor], n_heads: int, relu: bool, out: torch.Tensor, ws: torch.Tensor,
+                   n_src_dev: Optional[torch.Tensor] = None) -> None:
     d_in, d_out = W.shape
-    rc = load_library().hopgnn_gat_fwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+    rc = load_library().hopgnn_gat_fwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, _ptr(n_src_dev), d_in, _ptr(self_idx),
+                                       _ptr(indptr),
                                        _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(bias), d_out, n_heads,
                                        1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_gat_fwd")

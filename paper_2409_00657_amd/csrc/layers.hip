@@ -32,12 +32,60 @@ layer_prep(uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job
     transpose_w_tile(job, blockIdx.x - 1);
 }
 
-// s_src[u][h] = <z_u[h], a_src[h]>, s_dst[u][h] = <z_u[h], a_dst[h]>: one wavefront per source row.
+// s_src[u][h] = <z_u[h], a_src[h]>, s_dst[u][h] = <z_u[h], a_dst[h]>.
+//
+// Vector form (d_head / 4 a power of two <= 64): a lane takes one 16-byte word of z, the lanes of
+// a head form an aligned power-of-two segment and reduce with xor shuffles.  `lanes_row` lanes
+// (a power of two) share a row, so narrow rows are packed several to a wavefront and wide rows
+// are walked in strides of 64 words.
+template <typename Tr>
+__global__ void __launch_bounds__(kLayerThreads)
+gat_scores_vec(const float4* __restrict__ Z, const typename Tr::store_t* __restrict__ a_src,
+               const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, const int64_t* __restrict__ n_src_dev,
+               int32_t d_out, int32_t n_heads, int32_t lanes_row, int32_t seg, float* __restrict__ s_src,
+               float* __restrict__ s_dst) {
+    if (n_src_dev != nullptr) {
+        const int64_t live = *n_src_dev;
+        n_src = live < n_src ? live : n_src;
+    }
+    const int lane = threadIdx.x & 63;
+    const int rows_per_wave = 64 / lanes_row;
+    const int64_t wave = (int64_t)blockIdx.x * (kLayerThreads / 64) + (threadIdx.x >> 6);
+    const int64_t u = wave * rows_per_wave + lane / lanes_row;
+    const int32_t lw = lane % lanes_row, wpr = d_out / 4;
+    const bool live_row = u < n_src;
+    for (int32_t w0 = 0; w0 < wpr; w0 += lanes_row) {      // the same trip count for every lane of the wave
+        const int32_t w = w0 + lw;
+        const bool ok = live_row && w < wpr;
+        float ps = 0.f, pd = 0.f;
+        if (ok) {
+            const float4 z = Z[u * wpr + w];
+            const typename Tr::store_t* as = a_src + 4 * w;
+            const typename Tr::store_t* ad = a_dst + 4 * w;
+            ps = z.x * Tr::to_f(as[0]) + z.y * Tr::to_f(as[1]) + z.z * Tr::to_f(as[2]) + z.w * Tr::to_f(as[3]);
+            pd = z.x * Tr::to_f(ad[0]) + z.y * Tr::to_f(ad[1]) + z.z * Tr::to_f(ad[2]) + z.w * Tr::to_f(ad[3]);
+        }
+        for (int o = seg >> 1; o > 0; o >>= 1) {
+            ps += __shfl_xor(ps, o, kWave);
+            pd += __shfl_xor(pd, o, kWave);
+        }
+        if (ok && (w & (seg - 1)) == 0) {
+            s_src[u * n_heads + w / seg] = ps;
+            s_dst[u * n_heads + w / seg] = pd;
+        }
+    }
+}
+
+// General form: one wavefront per source row, one head after the other.
 template <typename Tr>
 __global__ void __launch_bounds__(kLayerThreads)
 gat_scores(const float* __restrict__ Z, const typename Tr::store_t* __restrict__ a_src,
-           const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, int32_t d_out, int32_t n_heads,
-           float* __restrict__ s_src, float* __restrict__ s_dst) {
+           const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, const int64_t* __restrict__ n_src_dev,
+           int32_t d_out, int32_t n_heads, float* __restrict__ s_src, float* __restrict__ s_dst) {
+    if (n_src_dev != nullptr) {
+        const int64_t live = *n_src_dev;
+        n_src = live < n_src ? live : n_src;
+    }
     const int lane = threadIdx.x & 63;
     const int64_t u = (int64_t)blockIdx.x * (kLayerThreads / 64) + (threadIdx.x >> 6);
     if (u >= n_src) return;
@@ -166,17 +214,28 @@ static hopgnn_status launch_prep(hopgnn_dtype dt, const void* W, uint16_t* Wt, c
 
 template <typename Tr>
 static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_dst, float* s_src, float* s_dst,
-                              int64_t n_src, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
-                              const void* bias, int64_t n_dst, int32_t d_out, int32_t n_heads, int relu, void* out,
-                              hipStream_t s) {
+                              int64_t n_src, const int64_t* n_src_dev, const int32_t* self_idx, const int32_t* indptr,
+                              const int32_t* idx, const void* bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
+                              int relu, void* out, hipStream_t s) {
     using T = typename Tr::store_t;
+    const int32_t dh = d_out / n_heads;
     if (n_src > 0) {
-        hipLaunchKernelGGL(gat_scores<Tr>, dim3((unsigned)ceil_div(n_src, kLayerThreads / 64)), dim3(kLayerThreads), 0, s,
-                           static_cast<const float*>(Z), static_cast<const T*>(a_src), static_cast<const T*>(a_dst), n_src,
-                           d_out, n_heads, s_src, s_dst);
+        const int32_t seg = dh / 4;
+        if (dh % 4 == 0 && seg <= 64 && (seg & (seg - 1)) == 0) {
+            int32_t lanes_row = 1;
+            while (lanes_row < d_out / 4 && lanes_row < 64) lanes_row *= 2;
+            const int64_t waves = ceil_div(n_src, 64 / lanes_row);
+            hipLaunchKernelGGL(gat_scores_vec<Tr>, dim3((unsigned)ceil_div(waves, kLayerThreads / 64)),
+                               dim3(kLayerThreads), 0, s, static_cast<const float4*>(Z), static_cast<const T*>(a_src),
+                               static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, lanes_row, seg, s_src,
+                               s_dst);
+        } else {
+            hipLaunchKernelGGL(gat_scores<Tr>, dim3((unsigned)ceil_div(n_src, kLayerThreads / 64)), dim3(kLayerThreads),
+                               0, s, static_cast<const float*>(Z), static_cast<const T*>(a_src),
+                               static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, s_src, s_dst);
+        }
         HOPGNN_LAUNCH_CHECK();
     }
-    const int32_t dh = d_out / n_heads;
     const bool vec = dh % 4 == 0 && aligned(out, 16);
     const int units = vec ? d_out / 4 : d_out;
     const int group = mean_group(units);
@@ -246,7 +305,8 @@ extern "C" hopgnn_status hopgnn_gcn_fwd(const void* Hsrc, hopgnn_dtype dt, int64
     else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);
     if (st != HOPGNN_OK) return st;
     // rows-times-W over the aggregate (identity row map, K = d_in)
-    return project_dispatch(dt, s, agg, nullptr, agg, W, W, Wt, L.KP, bias, n_dst, d_in, d_in, d_out, relu, zero, out, 0);
+    return project_dispatch(dt, s, agg, nullptr, agg, W, W, Wt, L.KP, bias, n_dst, d_in, d_in, d_out, relu, zero, out, 0,
+                            nullptr);
 }
 
 extern "C" size_t hopgnn_gat_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out,
@@ -256,8 +316,8 @@ extern "C" size_t hopgnn_gat_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int32_
     return gat_ws_layout(dt, n_src, d_in, d_out, n_heads).total;
 }
 
-extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
-                                        const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                        int32_t d_in, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
                                         int64_t n_dst, const void* W, const void* a_src, const void* a_dst,
                                         const void* bias, int32_t d_out, int32_t n_heads, int32_t relu, void* out,
                                         void* ws, size_t ws_bytes, void* stream) {
@@ -284,15 +344,16 @@ extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64
         hopgnn_status st = launch_prep(dt, W, Wt, L.P, d_in, d_out, zero, s);
         if (st != HOPGNN_OK) return st;
         // z = Hsrc W for every source row: identity row map, K = d_in, no bias, no activation
-        st = project_dispatch(dt, s, Hsrc, nullptr, Hsrc, W, W, Wt, L.P.KP, nullptr, n_src, d_in, d_in, d_out, 0, zero, Z, 1);
+        st = project_dispatch(dt, s, Hsrc, nullptr, Hsrc, W, W, Wt, L.P.KP, nullptr, n_src, d_in, d_in, d_out, 0, zero, Z, 1,
+                              n_src_dev);
         if (st != HOPGNN_OK) return st;
     }
     if (dt == HOPGNN_F32)
-        return gat_tail<TrF32>(Z, a_src, a_dst, s_src, s_dst, n_src, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
+        return gat_tail<TrF32>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
                                relu, out, s);
     if (dt == HOPGNN_BF16)
-        return gat_tail<TrBF16>(Z, a_src, a_dst, s_src, s_dst, n_src, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
+        return gat_tail<TrBF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
                                 relu, out, s);
-    return gat_tail<TrF16>(Z, a_src, a_dst, s_src, s_dst, n_src, self_idx, indptr, idx, bias, n_dst, d_out, n_heads, relu,
+    return gat_tail<TrF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads, relu,
                            out, s);
 }

@@ -152,7 +152,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
                  const float* __restrict__ Mean, const float* __restrict__ Wself,
                  const float* __restrict__ Wneigh, const float* __restrict__ bias, int64_t n_dst,
                  int32_t d_in, int32_t k_total, int32_t d_out, int relu, uint32_t n_tiles_n,
-                 const float* __restrict__ Zero, float* __restrict__ out) {
+                 const float* __restrict__ Zero, float* __restrict__ out, const int64_t* __restrict__ n_rows_dev) {
     constexpr int LDA = BK + 4, LDB = BN + 4;   // LDA/4 odd: conflict-free 128-bit reads
     static_assert(BK % 8 == 0 && (LDA / 4) % 2 == 1, "K tile");
     constexpr int TM = BM / 64, TN = BN / 64;
@@ -166,6 +166,10 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     uint32_t mt, nt;
     tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
     const int64_t row0 = (int64_t)mt * BM;
+    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+        const int64_t live = *n_rows_dev;
+        n_dst = live < n_dst ? live : n_dst;
+    }
     if (row0 >= n_dst) return;
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -333,7 +337,7 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
                 const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
                 const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_in, int32_t k_total,
                 int32_t d_out, int relu, uint32_t n_tiles_n, const uint16_t* __restrict__ Zero,
-                typename Tr::store_t* __restrict__ out, int out_f32) {
+                typename Tr::store_t* __restrict__ out, int out_f32, const int64_t* __restrict__ n_rows_dev) {
     constexpr int LD = BK + 8;
     static_assert(kKPad16 % BK == 0, "Wt padding must cover whole K tiles");
     constexpr int NT = 64 * WM * WN;                      // threads: WM x WN waves
@@ -348,6 +352,10 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
     uint32_t mt, nt;
     tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
     const int64_t row0 = (int64_t)mt * BM;
+    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+        const int64_t live = *n_rows_dev;
+        n_dst = live < n_dst ? live : n_dst;
+    }
     if (row0 >= n_dst) return;
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -497,7 +505,7 @@ template <int BM, int BN, int BK>
 static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                         const void* mean, const void* Ws, const void* Wn, const void* bias,
                                         int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                        const void* zero, void* out) {
+                                        const void* zero, void* out, const int64_t* n_rows_dev) {
     const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
     const dim3 grid(project_grid(n_dst, BM, ntn));
     auto a = static_cast<const float*>(Hsrc);
@@ -514,7 +522,7 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
                             (int)lds) != hipSuccess)
         return HOPGNN_EHIP;
     hipLaunchKernelGGL(kern, grid, dim3(kProjThreads), lds, s, a, self_idx, m, ws, wn, b, n_dst, d_in, k_total, d_out,
-                       relu, ntn, z, o);
+                       relu, ntn, z, o, n_rows_dev);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -523,7 +531,7 @@ template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
 static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                          const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
                                          int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                         const void* zero, void* out, int out_f32) {
+                                         const void* zero, void* out, int out_f32, const int64_t* n_rows_dev) {
     using T = typename Tr::store_t;
     constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(uint16_t);
     auto kern = sage_project_16<Tr, BM, BN, BK, WM, WN, VEC>;
@@ -536,7 +544,7 @@ static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const 
     hipLaunchKernelGGL(kern, dim3(project_grid(n_dst, BM, ntn)), dim3(64 * WM * WN), lds, s,
                        static_cast<const uint16_t*>(Hsrc), self_idx, static_cast<const uint16_t*>(mean), Wt,
                        KP, static_cast<const T*>(bias), n_dst, d_in, k_total, d_out, relu, ntn,
-                       static_cast<const uint16_t*>(zero), static_cast<T*>(out), out_f32);
+                       static_cast<const uint16_t*>(zero), static_cast<T*>(out), out_f32, n_rows_dev);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -545,9 +553,9 @@ template <typename Tr, int BM, int BN, int BK, int WM, int WN>
 static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                        const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
                                        int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                       const void* zero, void* out, int out_f32) {
-    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32)
-               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+                                       const void* zero, void* out, int out_f32, const int64_t* n_rows_dev) {
+    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev)
+               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
 }
 
 ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out) {
@@ -564,7 +572,8 @@ ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_t
 hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                const void* mean, const void* W_self, const void* W_neigh, const uint16_t* Wt,
                                int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
-                               int32_t d_out, int relu, const void* zero, void* out, int out_f32) {
+                               int32_t d_out, int relu, const void* zero, void* out, int out_f32,
+                               const int64_t* n_rows_dev) {
     const int per16 = dt == HOPGNN_F32 ? 4 : 8;
     const int64_t work = ceil_div(n_dst, 128) * ceil_div(d_out, 128);   // 128 x 128 output tiles
     if (dt == HOPGNN_F32) {
@@ -572,20 +581,20 @@ hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc,
                          aligned(W_self, 16) && aligned(W_neigh, 16);
         // large tiles once there is enough work to fill 256 CUs twice over
         if (d_out > 64 && work >= 512)
-            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out);
-        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out);
+            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev);
+        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev);
     }
     const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16);
     const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
     const bool big = d_out > 64 && work >= 512;
     if (dt == HOPGNN_BF16) {
-        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
-        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
-        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
     }
-    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
-    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
-    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32);
+    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
 }
 
 }  // namespace hopgnn
@@ -635,5 +644,5 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
     if (st != HOPGNN_OK) return st;
 
     return project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,
-                            zero, out, 0);
+                            zero, out, 0, nullptr);
 }

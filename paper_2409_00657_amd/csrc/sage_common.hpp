@@ -249,9 +249,11 @@ ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_t
 // plain rows-times-W product over the rows Hsrc[self_idx[r]].  For 2-byte types Wt (row stride KP)
 // must already hold the transposed weights; `zero` is a zeroed row of at least 2*d_in+64 elements.
 // out_f32 != 0: `out` is a float array and receives the unrounded result whatever dt is.
+// n_rows_dev (DEVICE, may be NULL): when given, only the first min(n_dst, *n_rows_dev) rows exist.
 hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                const void* agg, const void* W_self, const void* W_neigh, const uint16_t* Wt,
                                int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
-                               int32_t d_out, int relu, const void* zero, void* out, int out_f32);
+                               int32_t d_out, int relu, const void* zero, void* out, int out_f32,
+                               const int64_t* n_rows_dev);
 
 }  // namespace hopgnn

@@ -47,7 +47,13 @@ class HotPath:
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor,
                  weights, n_seeds: int, fanouts: Sequence[int], group: int = 1,
-                 pg_algo: int = hb.PG_AUTO):
+                 pg_algo: int = hb.PG_AUTO, model: str = "sage", gat_heads: int = 4):
+        """`weights`: per layer (W_self, W_neigh, bias-or-None).  model "sage" uses all three;
+        "gcn" (mean over the vertex and its neighbours) and "gat" use W_self as the layer's one
+        weight matrix, "gat" with seeded attention vectors and `gat_heads` heads."""
+        if model not in ("sage", "gcn", "gat"):
+            raise hb.HopgnnError("model must be sage, gcn or gat")
+        self.model, self.gat_heads = model, gat_heads
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
@@ -72,6 +78,13 @@ class HotPath:
                   for k in range(1, sh.n_layers + 1)]
         ws_bytes = max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0],
                                                    hidden) for k in range(1, sh.n_layers + 1))
+        if model == "gat":
+            self.attn = [(synth.weight(1, hidden, X.dtype, 200 + 2 * k, device=dev).view(-1),
+                          synth.weight(1, hidden, X.dtype, 201 + 2 * k, device=dev).view(-1))
+                         for k in range(sh.n_layers)]
+            n_src = [self.cap] + [sh.n_dst(k) for k in range(1, sh.n_layers)]
+            ws_bytes = max(ws_bytes, max(hb.hopgnn_gat_fwd_ws_bytes(X.dtype, n_src[k], weights[k][0].shape[0], hidden,
+                                                                    gat_heads) for k in range(sh.n_layers)))
         self.sage_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self._prepare_calls()
 
@@ -105,12 +118,21 @@ class HotPath:
                 Ws, Wn, bias = self.weights[k - 1]
                 d_in, d_out = Ws.shape
                 self_idx, idx = (rb, rb + 4 * B) if k == 1 else (None, self.slot_idx[b].data_ptr())
-                per_batch.append((src, dt, n_src, d_in, self_idx, self.indptr.data_ptr(), idx, n_dst,
-                                  Ws.data_ptr(), Wn.data_ptr(), None if bias is None else bias.data_ptr(),
-                                  d_out, 1 if k < L else 0, self.H[k - 1].data_ptr(), self.sage_ws.data_ptr(),
-                                  self.sage_ws.numel()))
+                bp = None if bias is None else bias.data_ptr()
+                tail = (1 if k < L else 0, self.H[k - 1].data_ptr(), self.sage_ws.data_ptr(), self.sage_ws.numel())
+                head = (src, dt, n_src, d_in, self_idx, self.indptr.data_ptr(), idx, n_dst, Ws.data_ptr())
+                if self.model == "gat":     # layer 1 projects only the rows the pre-gather found
+                    head = (src, dt, n_src, self.n_uniq.data_ptr() if k == 1 else None) + head[3:]
+                if self.model == "sage":
+                    per_batch.append(head + (Wn.data_ptr(), bp, d_out) + tail)
+                elif self.model == "gcn":
+                    per_batch.append(head + (bp, d_out, 1) + tail)
+                else:
+                    a_src, a_dst = self.attn[k - 1]
+                    per_batch.append(head + (a_src.data_ptr(), a_dst.data_ptr(), bp, d_out, self.gat_heads) + tail)
                 src, n_src = self.H[k - 1].data_ptr(), n_dst
             self._layer_args.append(per_batch)
+        self._layer_fn = {"sage": lib.hopgnn_sage_fwd, "gcn": lib.hopgnn_gcn_fwd, "gat": lib.hopgnn_gat_fwd}[self.model]
         # the same buffers as one plan for hopgnn_batch_fwd (the launch sequence issued from C)
         pl = self.plan = hb.BatchPlan()
         pl.graph = self._csr
@@ -160,9 +182,9 @@ class HotPath:
 
     def layer(self, b: int, k: int, stream=None) -> torch.Tensor:
         """Layer k (1-based) of batch b; its input is Xu (k = 1) or H[k-2]."""
-        rc = self._lib.hopgnn_sage_fwd(*self._layer_args[b][k - 1], self._stream(stream))
+        rc = self._layer_fn(*self._layer_args[b][k - 1], self._stream(stream))
         if rc:
-            hb._check(rc, "hopgnn_sage_fwd")
+            hb._check(rc, "hopgnn_%s_fwd" % self.model)
         return self.H[k - 1]
 
     def layers(self, b: int, stream=None) -> torch.Tensor:
@@ -178,6 +200,8 @@ class HotPath:
         backward pass.  Gradients are fp32 whatever the activation type.  The loss used by the
         harness is L = 1/2 |H_L|^2 for fp32 activations (dL/dH_L = H_L, read in place) and
         L = <G, H_L> with a fixed G for 2-byte activations (dL/dH_L = G, fp32)."""
+        if self.model != "sage":
+            raise hb.HopgnnError("backward is built for the GraphSAGE-mean layer")
         sh, dev = self.shape, self.X.device
         L = sh.n_layers
         if self.X.dtype == torch.float32:
@@ -230,6 +254,8 @@ class HotPath:
         """The whole group in ONE library call (hopgnn_batch_fwd): `seeds` holds the group's
         seeds back to back, `out` [group*B, hidden] receives every batch's last-layer rows.
         `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
+        if self.model != "sage":
+            raise hb.HopgnnError("hopgnn_batch_fwd runs GraphSAGE-mean layers; use run_batch/run_group")
         n = len(keys)
         if seeds.numel() != n * self.shape.n_seeds or seeds.dtype != torch.int32 or not seeds.is_cuda:
             raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.shape.n_seeds))

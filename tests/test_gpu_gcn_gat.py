@@ -66,12 +66,14 @@ def test_gcn_fwd_vs_oracle(hb, orc, dt, shape):
 
 
 @pytest.mark.parametrize("dt", DTYPES)
-@pytest.mark.parametrize("shape", SHAPES + [LARGE_GAT])
+@pytest.mark.parametrize("shape", SHAPES + [(600, 300, 40, 96, 5), LARGE_GAT])
 def test_gat_fwd_vs_oracle(hb, orc, dt, shape):
     n_src, n_dst, d_in, d_out, max_len = shape
     rng = np.random.default_rng(n_src + 5 * d_in)
     head_options = [h for h in (1, 2, 4, 8) if d_out % h == 0]
     variants = [(head_options[-1], True, True, False), (head_options[0], False, False, n_src >= n_dst)]
+    if d_out == 96:     # three heads of 32: rows of 24 words, packed two to a wavefront
+        variants = [(3, True, True, False)]
     for heads, relu, use_bias, ident in variants[1:] if shape == LARGE_GAT else variants:
         H, W, b, self_idx, indptr, idx = _case(rng, n_src, n_dst, d_in, d_out, max_len, dt, identity_self=ident)
         f = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32))
@@ -115,10 +117,12 @@ def test_layers_on_a_sampled_batch(hb, orc):
     a_src = torch.from_numpy(rng.standard_normal(d_out).astype(np.float32)).to(DEV)
     a_dst = torch.from_numpy(rng.standard_normal(d_out).astype(np.float32)).to(DEV)
     out = torch.empty((n_dst, d_out), device=DEV)
-    ws = torch.empty(max(hb.hopgnn_gat_fwd_ws_bytes(torch.float32, U, d_in, d_out, 4),
+    ws = torch.empty(max(hb.hopgnn_gat_fwd_ws_bytes(torch.float32, hp.cap, d_in, d_out, 4),
                          hb.hopgnn_gcn_fwd_ws_bytes(torch.float32, n_dst, d_in, d_out)), dtype=torch.uint8, device=DEV)
-    hb.hopgnn_gat_fwd(Xu, U, hp.remap[:n_dst], hp.indptr[:n_dst + 1], hp.remap[B:B + nnz], n_dst, W1, a_src, a_dst,
-                      None, 4, True, out, ws)
+    # the whole pre-gather buffer with its row count left on the device, as the pipeline passes it
+    hp.Xu[U:].fill_(float("nan"))
+    hb.hopgnn_gat_fwd(hp.Xu, hp.cap, hp.remap[:n_dst], hp.indptr[:n_dst + 1], hp.remap[B:B + nnz], n_dst, W1, a_src,
+                      a_dst, None, 4, True, out, ws, n_src_dev=hp.n_uniq)
     torch.cuda.synchronize()
     ref = orc.gat_fwd(to_bits(Xu), 0, remap[:n_dst], indptr, remap[B:B + nnz], to_bits(W1), to_bits(a_src),
                       to_bits(a_dst), None, 4, True)
