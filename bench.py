@@ -151,8 +151,7 @@ def main():
         """The same step call by call (with the backward pass, if asked for)."""
         h, stream = hps[i % n_streams], streams[i % n_streams]
         st = stream.cuda_stream
-        for b in range(group):
-            h.sample(b, seeds[i][b], keys[i][b], st)
+        h.sample_group(seeds_cat[i], keys[i], st)
         h.pregather(st)
         if ev is not None:
             ev[0].record(stream)
@@ -197,8 +196,7 @@ def main():
         j = args.warmup + i
         e = [E() for _ in range(6)]
         e[0].record()
-        for b in range(group):
-            hp.sample(b, seeds[j][b], keys[j][b], st0)
+        hp.sample_group(seeds_cat[j], keys[j], st0)
         e[1].record()
         hp.pregather(st0)
         e[2].record()

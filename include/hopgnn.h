@@ -100,6 +100,20 @@ hopgnn_status hopgnn_sample(const hopgnn_csr *g /*HOST struct*/, const int32_t *
                             void *stream);
 
 /*
+ * The micrographs of several batches of one shape in one launch (paper section 5.2 gathers for
+ * the micrographs of several time steps at once; their sampling is independent work of the same
+ * shape).  Exactly n_batches calls of hopgnn_sample: batch b reads seeds[b*n_seeds ..], uses
+ * keys[b] (HOST array) and writes ids[b*T ..] (T = n_seeds * slots per seed) and, if slot_idx is
+ * not NULL, slot_idx[b*slot_idx_stride ..] (stride >= T - n_seeds - last level, i.e. the entries
+ * one batch writes); indptr is the same for every batch and is written once.
+ * HOPGNN_ERANGE if n_batches * T does not fit the 32-bit slot arrays.
+ */
+hopgnn_status hopgnn_sample_group(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
+                                  const int32_t *fanouts /*HOST*/, int32_t n_layers,
+                                  const uint64_t *keys /*HOST*/, int32_t n_batches, int32_t *ids,
+                                  int32_t *indptr, int32_t *slot_idx, int64_t slot_idx_stride, void *stream);
+
+/*
  * Pre-gathering (paper section 5.2: merge the fetches of all micrographs a
  * worker trains in one iteration into one, each vertex once; implementation
  * section: duplicates are removed from the stored list of micrographs).
@@ -281,7 +295,7 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  * One call per group of batches: the whole hot path in the order of paper sections 2, 4
  * and 5.2 - sample the micrographs of each batch's seeds, pre-gather the group's merged slot
  * list once, fetch every distinct row once, then run the L layers of each batch on the
- * fetched rows.  It issues exactly the calls above (hopgnn_sample x n_batches, hopgnn_pregather,
+ * fetched rows.  It issues exactly the calls above (hopgnn_sample_group, hopgnn_pregather,
  * hopgnn_gather, hopgnn_sage_fwd x n_batches x L) from C on one stream; it exists because at
  * a few microseconds per kernel the launch sequence itself is the bottleneck when it is driven
  * call by call from an interpreter.  No host synchronisation, no allocation.

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sample_group", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -119,6 +119,10 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_sample_group.restype = c.c_int
+    L.hopgnn_sample_group.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
+                                      c.POINTER(c.c_uint64), c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64,
+                                      c.c_void_p]
     L.hopgnn_gcn_fwd_ws_bytes.restype = c.c_size_t
     L.hopgnn_gcn_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32]
     L.hopgnn_gcn_fwd.restype = c.c_int
@@ -179,6 +183,24 @@ def hopgnn_sample(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Ten
                                       len(fanouts), ctypes.c_uint64(key & 0xFFFFFFFFFFFFFFFF),
                                       _ptr(ids), _ptr(indptr), _ptr(slot_idx), _stream())
     _check(rc, "hopgnn_sample")
+
+
+def hopgnn_sample_group(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor, n_seeds: int,
+                        fanouts: Sequence[int], keys: Sequence[int], ids: torch.Tensor,
+                        indptr: Optional[torch.Tensor] = None, slot_idx: Optional[torch.Tensor] = None,
+                        slot_idx_stride: int = 0) -> None:
+    """len(keys) batches of n_seeds seeds each (seeds back to back) in one launch."""
+    g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
+             1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+    if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
+        raise HopgnnError("offsets must be int32/int64 and indices int32")
+    n = len(keys)
+    if seeds.numel() != n * n_seeds or seeds.dtype != torch.int32:
+        raise HopgnnError("seeds must hold n_batches * n_seeds int32 values")
+    karr = (ctypes.c_uint64 * max(n, 1))(*[k & 0xFFFFFFFFFFFFFFFF for k in keys])
+    rc = load_library().hopgnn_sample_group(ctypes.byref(g), _ptr(seeds), n_seeds, _fan(fanouts), len(fanouts), karr, n,
+                                            _ptr(ids), _ptr(indptr), _ptr(slot_idx), slot_idx_stride, _stream())
+    _check(rc, "hopgnn_sample_group")
 
 
 def hopgnn_pregather_ws_bytes(n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> int:

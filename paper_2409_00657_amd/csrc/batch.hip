@@ -25,12 +25,9 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     const size_t es = dtype_size(p->dt);
     hipStream_t st = (hipStream_t)stream;
 
-    hopgnn_status rc;
-    for (int32_t b = 0; b < n_batches; ++b) {
-        rc = hopgnn_sample(&p->graph, seeds + (int64_t)b * B, B, p->fanouts, L, keys[b], p->ids + b * T, p->indptr,
-                           L > 1 ? p->slot_idx + b * slot_idx_stride : nullptr, stream);
-        if (rc != HOPGNN_OK) return rc;
-    }
+    hopgnn_status rc = hopgnn_sample_group(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
+                                           L > 1 ? p->slot_idx : nullptr, slot_idx_stride, stream);
+    if (rc != HOPGNN_OK) return rc;
     rc = hopgnn_pregather(p->ids, n_batches * T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
                           p->pg_ws, p->pg_ws_bytes, stream);
     if (rc != HOPGNN_OK) return rc;

@@ -30,14 +30,27 @@ __device__ __forceinline__ uint64_t mod_u64(uint64_t x, uint64_t d) {
     return x % d;
 }
 
+// Batches sampled by one launch: blockIdx.y picks the batch, i.e. its seeds, its key (first
+// hash round already applied on the host) and its slice of the outputs.
+constexpr int kMaxBatchesPerLaunch = 64;
+struct BatchKeys {
+    uint64_t keyed[kMaxBatchesPerLaunch];
+};
+
 template <typename OffT>
 __global__ void __launch_bounds__(256)
 sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
                    const int32_t* __restrict__ seeds, int32_t n_seeds, SampleShape sh,
-                   uint64_t keyed, int32_t* ids, int32_t* indptr, int32_t* slot_idx) {
+                   BatchKeys keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride) {
     const int32_t m = blockIdx.x;
-    const int32_t root = seeds[m];
     const int32_t B = n_seeds;
+    const uint32_t batch = blockIdx.y;
+    const uint64_t keyed = keys.keyed[batch];
+    seeds += (int64_t)batch * B;
+    ids += (int64_t)batch * sh.base[sh.n_layers + 1];
+    if (slot_idx != nullptr) slot_idx += (int64_t)batch * slot_idx_stride;
+    if (batch != 0) indptr = nullptr;      // the segment offsets are the same for every batch of one shape
+    const int32_t root = seeds[m];
     if (threadIdx.x == 0) {
         ids[m] = root;
         if (indptr != nullptr && m == 0) indptr[sh.base[sh.n_layers]] = sh.base[sh.n_layers + 1] - B;
@@ -97,18 +110,20 @@ extern "C" int64_t hopgnn_slots_per_seed(const int32_t* fanouts, int32_t n_layer
     return t;
 }
 
-extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
-                                       const int32_t* fanouts, int32_t n_layers, uint64_t key,
-                                       int32_t* ids, int32_t* indptr, int32_t* slot_idx,
-                                       void* stream) {
-    if (g == nullptr || fanouts == nullptr || n_seeds < 0) return HOPGNN_EINVAL;
+namespace hopgnn {
+
+static hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts,
+                                    int32_t n_layers, const uint64_t* keys, int32_t n_batches, int32_t* ids,
+                                    int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride, void* stream) {
+    if (g == nullptr || fanouts == nullptr || n_seeds < 0 || n_batches < 0) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
     if (t_seed < 0) return HOPGNN_EINVAL;
     if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
-    if (n_seeds == 0) return HOPGNN_OK;
-    if (g->offsets == nullptr || seeds == nullptr || ids == nullptr) return HOPGNN_EINVAL;
+    if (n_seeds == 0 || n_batches == 0) return HOPGNN_OK;
+    if (g->offsets == nullptr || seeds == nullptr || ids == nullptr || keys == nullptr) return HOPGNN_EINVAL;
     if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
-    if ((int64_t)n_seeds * t_seed >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    const int64_t T = (int64_t)n_seeds * t_seed;
+    if (T * n_batches >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
 
     SampleShape sh{};
     sh.n_layers = n_layers;
@@ -120,21 +135,49 @@ extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds
         sh.base[h] = sh.base[h - 1] + n_seeds * sh.P[h - 1];
     }
     sh.base[n_layers + 1] = sh.base[n_layers] + n_seeds * sh.P[n_layers];
+    if (slot_idx != nullptr && n_batches > 1 && slot_idx_stride < (int64_t)sh.base[n_layers] - n_seeds)
+        return HOPGNN_EINVAL;              // the batches' neighbour lists would overlap
 
     int threads = 64;
     while (threads < 256 && threads < sh.P[n_layers]) threads *= 2;
-    const uint64_t keyed = host_finalise64(key + 0x9E3779B97F4A7C15ull);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (g->offsets_i64)
-        hipLaunchKernelGGL(sample_micrographs<int64_t>, dim3(n_seeds), dim3(threads), 0, s,
-                           static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh,
-                           keyed, ids, indptr, slot_idx);
-    else
-        hipLaunchKernelGGL(sample_micrographs<int32_t>, dim3(n_seeds), dim3(threads), 0, s,
-                           static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh,
-                           keyed, ids, indptr, slot_idx);
-    HOPGNN_LAUNCH_CHECK();
+    for (int32_t b0 = 0; b0 < n_batches; b0 += kMaxBatchesPerLaunch) {
+        const int32_t nb = n_batches - b0 < kMaxBatchesPerLaunch ? n_batches - b0 : kMaxBatchesPerLaunch;
+        BatchKeys bk{};
+        for (int32_t i = 0; i < nb; ++i) bk.keyed[i] = host_finalise64(keys[b0 + i] + 0x9E3779B97F4A7C15ull);
+        const int32_t* sd = seeds + (int64_t)b0 * n_seeds;
+        int32_t* id = ids + (int64_t)b0 * T;
+        int32_t* ip = b0 == 0 ? indptr : nullptr;
+        int32_t* si = slot_idx != nullptr ? slot_idx + (int64_t)b0 * slot_idx_stride : nullptr;
+        const dim3 grid((unsigned)n_seeds, (unsigned)nb);
+        if (g->offsets_i64)
+            hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
+                               static_cast<const int64_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
+                               slot_idx_stride);
+        else
+            hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
+                               static_cast<const int32_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
+                               slot_idx_stride);
+        HOPGNN_LAUNCH_CHECK();
+    }
     return HOPGNN_OK;
+}
+
+}  // namespace hopgnn
+
+extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                       const int32_t* fanouts, int32_t n_layers, uint64_t key,
+                                       int32_t* ids, int32_t* indptr, int32_t* slot_idx,
+                                       void* stream) {
+    return sample_batches(g, seeds, n_seeds, fanouts, n_layers, &key, 1, ids, indptr, slot_idx, 0, stream);
+}
+
+extern "C" hopgnn_status hopgnn_sample_group(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                             const int32_t* fanouts, int32_t n_layers, const uint64_t* keys,
+                                             int32_t n_batches, int32_t* ids, int32_t* indptr, int32_t* slot_idx,
+                                             int64_t slot_idx_stride, void* stream) {
+    return sample_batches(g, seeds, n_seeds, fanouts, n_layers, keys, n_batches, ids, indptr, slot_idx, slot_idx_stride,
+                          stream);
 }
 
 extern "C" const char* hopgnn_status_str(hopgnn_status s) {

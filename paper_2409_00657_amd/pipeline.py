@@ -170,6 +170,20 @@ class HotPath:
         if rc:
             hb._check(rc, "hopgnn_sample")
 
+    def sample_group(self, seeds: torch.Tensor, keys: Sequence[int], stream=None) -> None:
+        """All of the group's batches in one launch; `seeds` holds their seeds back to back."""
+        n, B, L = len(keys), self.shape.n_seeds, self.shape.n_layers
+        if seeds.numel() != n * B or seeds.dtype != torch.int32 or not seeds.is_cuda or n > self.group:
+            raise hb.HopgnnError("seeds must be %d x %d int32 values on the device" % (n, B))
+        for i, k in enumerate(keys):
+            self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
+        rc = self._lib.hopgnn_sample_group(ctypes.byref(self._csr), seeds.data_ptr(), B, self._fan, L, self._keys, n,
+                                           self.ids.data_ptr(), self.indptr.data_ptr(),
+                                           self._slot_idx_all.data_ptr() if L > 1 else None,
+                                           self._slot_idx_all.numel() // self.group, self._stream(stream))
+        if rc:
+            hb._check(rc, "hopgnn_sample_group")
+
     def pregather(self, stream=None) -> None:
         rc = self._lib.hopgnn_pregather(*self._pregather_args, self._stream(stream))
         if rc:
@@ -277,8 +291,7 @@ class HotPath:
         receives a copy of batch b's final rows."""
         assert len(seeds_list) == self.group
         st = self._stream(stream)
-        for b, (s, k) in enumerate(zip(seeds_list, keys)):
-            self.sample(b, s, k, st)
+        self.sample_group(torch.cat(list(seeds_list)) if len(seeds_list) > 1 else seeds_list[0], keys, st)
         self.pregather(st)
         self.gather(st)
         for b in range(self.group):

@@ -63,6 +63,52 @@ def test_sample_bit_exact(hb, orc, case):
             np.testing.assert_array_equal(slot_idx, np.where(ref_ids[B:S] >= 0, B + e, -1))
 
 
+def test_sample_group_equals_separate_calls(hb, orc):
+    """Several batches in one launch: bit for bit the per-batch calls, and the oracle's."""
+    from paper_2409_00657_amd import synth
+    g = synth.rmat_graph(12, 9.0, device=DEV)
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    B, fan, G = 37, [4, 3, 5], 5
+    t_seed = hb.hopgnn_slots_per_seed(fan)
+    T = B * t_seed
+    S = T - B * 4 * 3 * 5
+    seeds = synth.seeds(g.n_vertices, B * G, 3, device=DEV)
+    keys = [11, 0, 2 ** 63 + 5, 7, 7]
+    ids = torch.full((G * T,), -9, dtype=torch.int32, device=DEV)
+    indptr = torch.full((S + 1,), -9, dtype=torch.int32, device=DEV)
+    stride = S - B + 3          # a stride with slack: the gaps stay untouched
+    slot_idx = torch.full((G * stride,), -9, dtype=torch.int32, device=DEV)
+    hb.hopgnn_sample_group(g.offsets, g.indices, seeds, B, fan, keys, ids, indptr, slot_idx, stride)
+    torch.cuda.synchronize()
+    for b in range(G):
+        ids1 = torch.empty(T, dtype=torch.int32, device=DEV)
+        ip1 = torch.empty(S + 1, dtype=torch.int32, device=DEV)
+        si1 = torch.empty(S - B, dtype=torch.int32, device=DEV)
+        hb.hopgnn_sample(g.offsets, g.indices, seeds[b * B:(b + 1) * B], fan, keys[b], ids1, ip1, si1)
+        torch.cuda.synchronize()
+        assert torch.equal(ids[b * T:(b + 1) * T], ids1)
+        assert torch.equal(indptr, ip1)
+        assert torch.equal(slot_idx[b * stride:b * stride + S - B], si1)
+        assert bool((slot_idx[b * stride + S - B:(b + 1) * stride] == -9).all())
+        ref_ids, ref_ip = orc.sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fan, keys[b])
+        np.testing.assert_array_equal(ids1.cpu().numpy(), ref_ids)
+        np.testing.assert_array_equal(ip1.cpu().numpy(), ref_ip)
+    # 70 batches: more than one launch's worth of keys
+    G2 = 70
+    seeds2 = synth.seeds(g.n_vertices, 8 * G2, 4, device=DEV)
+    keys2 = list(range(100, 100 + G2))
+    t2 = 8 * hb.hopgnn_slots_per_seed([3, 2])
+    ids2 = torch.empty(G2 * t2, dtype=torch.int32, device=DEV)
+    hb.hopgnn_sample_group(g.offsets, g.indices, seeds2, 8, [3, 2], keys2, ids2)
+    torch.cuda.synchronize()
+    for b in (0, 63, 64, 69):
+        ref_ids, _ = orc.sample(off_np, idx_np, seeds2[b * 8:(b + 1) * 8].cpu().numpy(), [3, 2], keys2[b])
+        np.testing.assert_array_equal(ids2[b * t2:(b + 1) * t2].cpu().numpy(), ref_ids)
+    # overlapping neighbour lists are refused
+    with pytest.raises(hb.HopgnnError):
+        hb.hopgnn_sample_group(g.offsets, g.indices, seeds, B, fan, keys, ids, indptr, slot_idx, S - B - 1)
+
+
 def test_sample_edge_cases(hb, orc):
     # zero seeds: no-op; all-isolated graph: every child invalid
     off, idx = _csr([[], [], []])
