@@ -183,3 +183,22 @@ def test_config5_fp16_grouped_pregather_vs_oracle(orc):
     seeds, keys = _seeds(cfg, 0, 8)
     stats, *_ = _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, row_budget=1500)
     assert stats["U"] <= stats["T_valid"]
+
+
+@pytest.mark.parametrize("fanouts,group,dt", [([7], 1, torch.float32), ([3, 2, 2, 2], 3, torch.float16),
+                                              ([6, 4], 5, torch.bfloat16)])
+def test_other_depths_and_groups_vs_oracle(orc, fanouts, group, dt):
+    """One layer, four layers, odd group sizes: the step-by-step path and the single-call path
+    against the oracle on a small R-MAT graph (zero-degree vertices included)."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    g = synth.rmat_graph(13, 10.0, device=DEV)
+    n, d, hidden, B = g.n_vertices, 24, 40, 50
+    X = synth.features(n, d, dt, device=DEV)
+    W = synth.sage_weights(d, hidden, len(fanouts), dt, device=DEV, bias=True)
+    cfg = synth.Config("small-rmat", "rmat", n, 10.0, False, d, dt, B, fanouts, hidden, scale=13)
+    hp = HotPath(g.offsets, g.indices, X, W, B, fanouts, group=group)
+    graph_np = (g.offsets.cpu().numpy(), g.indices.cpu().numpy())
+    for it in range(2):
+        seeds, keys = _seeds(cfg, it, group)
+        _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, full_forward=True)
