@@ -5,9 +5,10 @@
 // Bitmap path (default).  Vertex IDs are dense integers below n_vertices, so the
 // set is a presence map: every slot stores a 1 into its vertex's byte, the bytes
 // are packed 32:1 into bitmap words, a popcount prefix sum over the words gives
-// every word its rank, and then
+// every word its rank (kept as rank inside its 1024-word chunk + the chunk's base), and then
 //     uniq  = the set bits in word order           (ascending by construction)
-//     remap = rank[word(id)] + popcount(bits of that word below id)
+//     remap = base[chunk(id)] + rank[word(id)] + popcount(bits of that word below id)
+// Both depend only on the packing pass, so they share one launch.
 // No key ever moves: HBM traffic is ~9 bytes per slot plus ~2.4 bytes per vertex,
 // against >= 16 bytes per slot per pass for a sort of (id, slot) pairs.
 // Marking uses plain byte stores, not atomic ORs on bitmap words: on power-law
@@ -31,9 +32,8 @@ constexpr int kWordsPerBlock = kPgThreads * kWordsPerThread;    // 1024 words = 
 
 struct BitmapWs {
     uint8_t* present;      // [32 * n_words_padded] one byte per vertex
-    uint32_t* bits;        // [n_words_padded]
-    uint2* word_rank;      // [n_words_padded] (bits, rank of the word's first set bit)
-    uint32_t* block_sum;   // [n_blocks]
+    uint2* word_rank;      // [n_words_padded] (bits, rank of the word's first set bit inside its chunk)
+    uint32_t* block_sum;   // [n_blocks] set bits per 1024-word chunk, then their exclusive prefix sum
     uint32_t* ticket;      // [1] blocks finished counting
     size_t bytes;
     int64_t n_words_padded;
@@ -49,8 +49,6 @@ static BitmapWs bitmap_layout(void* ws, int64_t n_vertices) {
     size_t o = 0;
     L.present = reinterpret_cast<uint8_t*>(p + o);
     o += align_up((size_t)L.n_words_padded * 32, 256);
-    L.bits = reinterpret_cast<uint32_t*>(p + o);
-    o += align_up((size_t)L.n_words_padded * 4, 256);
     L.word_rank = reinterpret_cast<uint2*>(p + o);
     o += align_up((size_t)L.n_words_padded * 8, 256);
     L.block_sum = reinterpret_cast<uint32_t*>(p + o);
@@ -118,37 +116,64 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* l
     return base + inc - x;
 }
 
-// Pass 1: pack the presence bytes of 4 words per thread into the bitmap, count every
-// 1024-word block; the block that finishes last turns the block counts into exclusive
-// block bases and publishes U.
+// Pass 1: pack the presence bytes into bitmap words, rank every word inside its 1024-word chunk
+// and count the chunk; the workgroup that finishes last turns the chunk counts into exclusive
+// chunk bases and publishes U.  With UNMARK the marks are wiped as they are read (only the
+// 16-byte pieces that hold one) and the ticket is reset, which leaves the presence map and the
+// ticket as hopgnn_pregather_ws_init left them.
+template <bool UNMARK>
 __global__ void __launch_bounds__(kPgThreads)
-bitmap_pack_count(const uint4* __restrict__ present16, uint4* __restrict__ bits4, uint32_t* block_sum,
+bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, uint32_t* block_sum,
                   uint32_t* ticket, int64_t* n_uniq, uint32_t n_blocks) {
     __shared__ uint32_t lds4[kPgThreads / kWave];
     __shared__ bool is_last;
     // A wave covers 8 KiB of presence bytes = 256 bitmap words.  Load k of lane l is the
     // 16-byte piece k*64+l of that range (fully coalesced) = one half of word k*32 + l/2;
-    // lanes 2j and 2j+1 exchange halves and the even lane stores the word.
+    // lanes 2j and 2j+1 exchange halves and the even lane owns the word.
     // A workgroup takes chunks blockIdx.x, blockIdx.x + gridDim.x, ... and draws ONE ticket at the
     // end (one ticket per chunk serialised thousands of same-address atomics on large graphs).
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
     for (uint32_t chunk = blockIdx.x; chunk < n_blocks; chunk += gridDim.x) {
-        const int64_t wave_id = ((int64_t)chunk * kPgThreads + threadIdx.x) / kWave;
-        const uint4* src = present16 + wave_id * (kWave * 8);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(bits4) + wave_id * (kWave * kWordsPerThread);
+        const int64_t wave_id = (int64_t)chunk * (kPgThreads / kWave) + wave;
+        uint4* src = present16 + wave_id * (kWave * 8);
+        uint2* dst = word_rank + wave_id * (kWave * kWordsPerThread);
         uint4 q[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) q[k] = src[k * kWave + lane];
-        uint32_t mine = 0;
+        if (UNMARK) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if ((q[k].x | q[k].y | q[k].z | q[k].w) != 0u) src[k * kWave + lane] = make_uint4(0u, 0u, 0u, 0u);
+        }
+        // word k*32 + lane/2 of the wave, its popcount on the even lane, and its rank among the
+        // wave's 256 words in word order (row k before row k+1, lanes in order inside a row)
+        uint32_t word[8], rank[8];
+        uint32_t wave_total = 0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const uint32_t half = pack16(q[k]);
-            mine += __popc(half);
             const uint32_t other = __shfl_xor(half, 1, kWave);
-            if ((lane & 1) == 0) dst[k * 32 + (lane >> 1)] = half | (other << 16);
+            word[k] = half | (other << 16);
+            const uint32_t cnt = (lane & 1) == 0 ? __popc(word[k]) : 0u;
+            const uint32_t inc = wave_inclusive_scan(cnt);
+            rank[k] = wave_total + inc - cnt;
+            wave_total += __shfl(inc, kWave - 1, kWave);
         }
-        uint32_t total;
-        (void)block_exclusive_scan(mine, lds4, total);
+        if (lane == 0) lds4[wave] = wave_total;
+        __syncthreads();
+        uint32_t wave_base = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kPgThreads / kWave; ++w) {
+            const uint32_t t = lds4[w];
+            if (w < wave) wave_base += t;
+            total += t;
+        }
+        __syncthreads();
+        if ((lane & 1) == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) dst[k * 32 + (lane >> 1)] = make_uint2(word[k], wave_base + rank[k]);
+        }
         if (threadIdx.x == 0)
             __hip_atomic_store(&block_sum[chunk], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -171,46 +196,47 @@ bitmap_pack_count(const uint4* __restrict__ present16, uint4* __restrict__ bits4
         if (b < n_blocks) block_sum[b] = carry + ex;
         carry += tot;
     }
-    if (threadIdx.x == 0) *n_uniq = (int64_t)carry;
+    if (threadIdx.x == 0) {
+        *n_uniq = (int64_t)carry;
+        if (UNMARK) *ticket = 0u;
+    }
 }
 
-// Pass 2 over the bitmap: rank of every word, and the ascending ID list.
+// Pass 2, one launch for both outputs.  Workgroups [0, n_emit_blocks) walk one chunk of the
+// bitmap each and write its set bits to uniq in word order; the others fill remap for a strided
+// share of the slots.
 __global__ void __launch_bounds__(kPgThreads)
-bitmap_emit(const uint4* __restrict__ bits4, const uint32_t* __restrict__ block_base,
-            uint2* __restrict__ word_rank, int32_t* __restrict__ uniq) {
-    __shared__ uint32_t lds4[kPgThreads / kWave];
-    const int64_t t = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
-    const uint4 w = bits4[t];
-    const uint32_t wd[4] = {w.x, w.y, w.z, w.w};
-    uint32_t total;
-    uint32_t r = block_base[blockIdx.x] +
-                 block_exclusive_scan(__popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w), lds4, total);
-    if (total == 0) {   // nothing set in these 32768 vertices: ranks are never looked up
+bitmap_emit_remap(const uint2* __restrict__ word_rank, const uint32_t* __restrict__ block_base,
+                  uint32_t n_emit_blocks, int32_t* __restrict__ uniq, const int32_t* __restrict__ ids, int64_t n_ids,
+                  int32_t* __restrict__ remap) {
+    if (blockIdx.x < n_emit_blocks) {
+        const int64_t t = (int64_t)blockIdx.x * kPgThreads + threadIdx.x;
+        const uint4* wr = reinterpret_cast<const uint4*>(word_rank + t * kWordsPerThread);
+        const uint4 a = wr[0], b = wr[1];              // (bits, rank) of words 4t .. 4t+3
+        const uint32_t wd[4] = {a.x, a.z, b.x, b.z};
+        const uint32_t rk[4] = {a.y, a.w, b.y, b.w};
+        if ((wd[0] | wd[1] | wd[2] | wd[3]) == 0u) return;
+        const uint32_t base = block_base[blockIdx.x];
+#pragma unroll
+        for (int k = 0; k < kWordsPerThread; ++k) {
+            uint32_t bits = wd[k];
+            uint32_t r = base + rk[k];
+            const int32_t v0 = (int32_t)((t * kWordsPerThread + k) << 5);
+            while (bits) {
+                const int bit = __ffs((int)bits) - 1;
+                uniq[r++] = v0 + bit;
+                bits &= bits - 1;
+            }
+        }
         return;
     }
-#pragma unroll
-    for (int k = 0; k < kWordsPerThread; ++k) {
-        uint32_t bits = wd[k];
-        word_rank[t * kWordsPerThread + k] = make_uint2(bits, r);
-        const int32_t v0 = (int32_t)((t * kWordsPerThread + k) << 5);
-        while (bits) {
-            const int b = __ffs((int)bits) - 1;
-            uniq[r++] = v0 + b;
-            bits &= bits - 1;
-        }
-    }
-}
-
-__global__ void __launch_bounds__(kPgThreads)
-bitmap_remap(const int32_t* __restrict__ ids, int64_t n_ids, const uint2* __restrict__ word_rank,
-             int32_t* __restrict__ remap) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_ids; i += stride) {
+    const int64_t stride = (int64_t)(gridDim.x - n_emit_blocks) * blockDim.x;
+    for (int64_t i = (int64_t)(blockIdx.x - n_emit_blocks) * blockDim.x + threadIdx.x; i < n_ids; i += stride) {
         const int32_t v = ids[i];
         int32_t pos = -1;
         if (v >= 0) {
             const uint2 wr = word_rank[v >> 5];
-            pos = (int32_t)(wr.y + __popc(wr.x & ((1u << (v & 31)) - 1u)));
+            pos = (int32_t)(block_base[v >> 15] + wr.y + __popc(wr.x & ((1u << (v & 31)) - 1u)));
         }
         remap[i] = pos;
     }
@@ -220,6 +246,24 @@ static int grid_for(int64_t n, int per_block, int cap) {
     int64_t g = ceil_div(n, per_block);
     if (g < 1) g = 1;
     return (int)(g < cap ? g : cap);
+}
+
+// Packing pass + the fused second pass, from a presence map that holds the marks of `ids`.
+static hopgnn_status bitmap_from_marks(const BitmapWs& L, bool unmark, const int32_t* ids, int64_t n_ids,
+                                       int32_t* uniq, int64_t* n_uniq_dev, int32_t* remap, hipStream_t s) {
+    const dim3 pack_grid((unsigned)(L.n_blocks < 1024 ? L.n_blocks : 1024));
+    if (unmark)
+        hipLaunchKernelGGL(bitmap_pack_count<true>, pack_grid, dim3(kPgThreads), 0, s, reinterpret_cast<uint4*>(L.present),
+                           L.word_rank, L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
+    else
+        hipLaunchKernelGGL(bitmap_pack_count<false>, pack_grid, dim3(kPgThreads), 0, s, reinterpret_cast<uint4*>(L.present),
+                           L.word_rank, L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
+    HOPGNN_LAUNCH_CHECK();
+    const unsigned remap_blocks = n_ids > 0 ? (unsigned)grid_for(n_ids, kPgThreads, 256 * 32) : 0u;
+    hipLaunchKernelGGL(bitmap_emit_remap, dim3((unsigned)L.n_blocks + remap_blocks), dim3(kPgThreads), 0, s, L.word_rank,
+                       L.block_sum, (uint32_t)L.n_blocks, uniq, ids, n_ids, remap);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }
 
 static hopgnn_status pregather_bitmap(const int32_t* ids, int64_t n_ids, int64_t n_vertices,
@@ -236,19 +280,7 @@ static hopgnn_status pregather_bitmap(const int32_t* ids, int64_t n_ids, int64_t
                            ids, n_ids, L.present);
         HOPGNN_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(bitmap_pack_count, dim3((unsigned)(L.n_blocks < 1024 ? L.n_blocks : 1024)), dim3(kPgThreads), 0, s,
-                       reinterpret_cast<const uint4*>(L.present), reinterpret_cast<uint4*>(L.bits),
-                       L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
-    HOPGNN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bitmap_emit, dim3((unsigned)L.n_blocks), dim3(kPgThreads), 0, s,
-                       reinterpret_cast<const uint4*>(L.bits), L.block_sum, L.word_rank, uniq);
-    HOPGNN_LAUNCH_CHECK();
-    if (n_ids > 0) {
-        hipLaunchKernelGGL(bitmap_remap, dim3(grid_for(n_ids, kPgThreads, 256 * 32)), dim3(kPgThreads), 0, s,
-                           ids, n_ids, L.word_rank, remap);
-        HOPGNN_LAUNCH_CHECK();
-    }
-    return HOPGNN_OK;
+    return bitmap_from_marks(L, false, ids, n_ids, uniq, n_uniq_dev, remap, s);
 }
 
 // ------------------------------------------------------------------ radix path --
