@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload shape 1..5")
     ap.add_argument("--group", type=int, default=0, help="batches per pre-gather (0: the shape's default)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams (each with its own buffers) that consecutive steps alternate over")
     ap.add_argument("--backward", action="store_true",
                     help="also run the layers' backward pass with in-place gradient accumulation")

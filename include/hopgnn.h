@@ -129,6 +129,16 @@ hopgnn_status hopgnn_sample_group(const hopgnn_csr *g /*HOST struct*/, const int
  */
 size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo);
 
+/*
+ * Prepares a pre-gather workspace once (zero presence map and counters; sizes and algo as in
+ * hopgnn_pregather_ws_bytes).  hopgnn_pregather itself does not need it - it clears what it uses
+ * - but every call of it, and every hopgnn_batch_fwd, leaves the workspace as this call does, so
+ * a plan may promise a clean workspace (pg_ws_clean) and skip the clearing pass.  A call that
+ * fails part-way may leave marks behind: call this again.
+ */
+hopgnn_status hopgnn_pregather_ws_init(void *ws, size_t ws_bytes, int64_t n_ids, int64_t n_vertices,
+                                       int32_t algo, void *stream);
+
 hopgnn_status hopgnn_pregather(const int32_t *ids, int64_t n_ids, int64_t n_vertices,
                                int32_t algo, int32_t *uniq, int64_t *n_uniq_dev, int32_t *remap,
                                void *ws, size_t ws_bytes, void *stream);
@@ -317,6 +327,12 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *   mark_gather_begin/_end      optional hipEvent_t pair recorded on `stream` around the gather
  *                               launch (NULL: none) so that a harness can time that kernel
  *                               inside its timed region
+ *   pg_ws_clean                 nonzero: pg_ws was prepared by hopgnn_pregather_ws_init (sizes
+ *                               group*T, n_vertices, pg_algo) and has since only been used by
+ *                               this library's calls, all of which leave it clean.  Then the
+ *                               sampler marks the pre-gather's presence map as it writes the
+ *                               ids and the clearing and marking passes are skipped (same
+ *                               results).  Zero: no assumption about pg_ws.
  *
  * seeds  DEVICE [n_batches*n_seeds]; keys HOST [n_batches]; out DEVICE
  *        [n_batches*n_seeds x d_out[n_layers-1]] in X's element type.
@@ -347,6 +363,7 @@ typedef struct {
     void *sage_ws;
     size_t sage_ws_bytes;
     void *mark_gather_begin, *mark_gather_end;
+    int32_t pg_ws_clean;
 } hopgnn_batch_plan;
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sample_group", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sample_group", "hopgnn_pregather_ws_init", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -57,7 +57,8 @@ class BatchPlan(ctypes.Structure):
                 ("remap", ctypes.c_void_p), ("Xu", ctypes.c_void_p), ("H", ctypes.c_void_p * 8),
                 ("pg_ws", ctypes.c_void_p), ("pg_ws_bytes", ctypes.c_size_t),
                 ("sage_ws", ctypes.c_void_p), ("sage_ws_bytes", ctypes.c_size_t),
-                ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p)]
+                ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p),
+                ("pg_ws_clean", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -119,6 +120,8 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_pregather_ws_init.restype = c.c_int
+    L.hopgnn_pregather_ws_init.argtypes = [c.c_void_p, c.c_size_t, c.c_int64, c.c_int64, c.c_int32, c.c_void_p]
     L.hopgnn_sample_group.restype = c.c_int
     L.hopgnn_sample_group.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
                                       c.POINTER(c.c_uint64), c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64,
@@ -205,6 +208,11 @@ def hopgnn_sample_group(offsets: torch.Tensor, indices: torch.Tensor, seeds: tor
 
 def hopgnn_pregather_ws_bytes(n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> int:
     return int(load_library().hopgnn_pregather_ws_bytes(n_ids, n_vertices, algo))
+
+
+def hopgnn_pregather_ws_init(ws: torch.Tensor, n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> None:
+    _check(load_library().hopgnn_pregather_ws_init(_ptr(ws), ws.numel() * ws.element_size(), n_ids, n_vertices, algo,
+                                                   _stream()), "hopgnn_pregather_ws_init")
 
 
 def hopgnn_pregather(ids: torch.Tensor, n_vertices: int, uniq: torch.Tensor,

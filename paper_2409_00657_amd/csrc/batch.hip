@@ -4,7 +4,7 @@
 // the library's own entry points.
 #include <hip/hip_runtime.h>
 
-#include "common.hpp"
+#include "pregather_internal.hpp"
 
 using namespace hopgnn;
 
@@ -25,11 +25,20 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     const size_t es = dtype_size(p->dt);
     hipStream_t st = (hipStream_t)stream;
 
-    hopgnn_status rc = hopgnn_sample_group(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
-                                           L > 1 ? p->slot_idx : nullptr, slot_idx_stride, stream);
+    // With a workspace the caller keeps clean (hopgnn_pregather_ws_init once, then only calls that
+    // leave it clean) the sampler marks the presence map itself: no clearing pass, no marking pass.
+    uint8_t* marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes, (int64_t)p->group * T,
+                                                          p->graph.n_vertices, p->pg_algo)
+                                    : nullptr;
+    hopgnn_status rc = sample_batches(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
+                                      L > 1 ? p->slot_idx : nullptr, slot_idx_stride, marks, stream);
     if (rc != HOPGNN_OK) return rc;
-    rc = hopgnn_pregather(p->ids, n_batches * T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
-                          p->pg_ws, p->pg_ws_bytes, stream);
+    if (marks != nullptr)
+        rc = pregather_from_marks(p->ids, n_batches * T, p->graph.n_vertices, p->uniq, p->n_uniq, p->remap, p->pg_ws,
+                                  p->pg_ws_bytes, st);
+    else
+        rc = hopgnn_pregather(p->ids, n_batches * T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
+                              p->pg_ws, p->pg_ws_bytes, stream);
     if (rc != HOPGNN_OK) return rc;
     if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
         return HOPGNN_EHIP;

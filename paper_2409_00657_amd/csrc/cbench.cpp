@@ -259,6 +259,10 @@ int main(int argc, char** argv) {
             CK(hipMalloc(&p.Xu, (size_t)cap * dim * es));
             p.pg_ws_bytes = hopgnn_pregather_ws_bytes(T, N, 0);
             CK(hipMalloc(&p.pg_ws, p.pg_ws_bytes));
+            if (!getenv("CBENCH_NO_CLEAN_WS")) {
+                if (hopgnn_pregather_ws_init(p.pg_ws, p.pg_ws_bytes, T, N, 0, nullptr) != HOPGNN_OK) return 1;
+                p.pg_ws_clean = 1;
+            }
             for (int k = 1; k <= L; ++k) {
                 int64_t nd = 0;
                 for (int h = 0; h <= L - k; ++h) nd += lv[h];

@@ -15,7 +15,7 @@
 // graphs the hubs are hit thousands of times per batch and same-address atomics
 // serialise in L2 (measured: 0.3 ms for 0.9 M slots), while racing stores of the
 // same value just overwrite each other.  The result does not depend on any order.
-#include "common.hpp"
+#include "pregather_internal.hpp"
 
 namespace hopgnn {
 
@@ -66,7 +66,7 @@ present_clear(uint4* __restrict__ present16, int64_t n_vec, uint32_t* ticket, in
         present16[i] = make_uint4(0u, 0u, 0u, 0u);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         *ticket = 0u;
-        *n_uniq = 0;
+        if (n_uniq != nullptr) *n_uniq = 0;
     }
 }
 
@@ -280,7 +280,8 @@ static hopgnn_status pregather_bitmap(const int32_t* ids, int64_t n_ids, int64_t
                            ids, n_ids, L.present);
         HOPGNN_LAUNCH_CHECK();
     }
-    return bitmap_from_marks(L, false, ids, n_ids, uniq, n_uniq_dev, remap, s);
+    // unmark while packing: whatever state the workspace came in, it leaves clean
+    return bitmap_from_marks(L, true, ids, n_ids, uniq, n_uniq_dev, remap, s);
 }
 
 // ------------------------------------------------------------------ radix path --
@@ -700,6 +701,43 @@ static int32_t pick_algo(int32_t algo, int64_t n_ids, int64_t n_vertices) {
     if (algo != HOPGNN_PG_AUTO) return algo;
     const int64_t slots = n_ids > (1 << 18) ? n_ids : (1 << 18);
     return n_vertices > 256 * slots ? HOPGNN_PG_RADIX : HOPGNN_PG_BITMAP;
+}
+
+namespace hopgnn {
+
+uint8_t* pregather_marks_map(void* ws, size_t ws_bytes, int64_t n_ids, int64_t n_vertices, int32_t algo) {
+    if (ws == nullptr || !aligned(ws, 256) || n_ids < 0 || n_vertices < 0) return nullptr;
+    if (pick_algo(algo, n_ids, n_vertices) != HOPGNN_PG_BITMAP) return nullptr;
+    const BitmapWs L = bitmap_layout(ws, n_vertices);
+    return ws_bytes >= L.bytes ? L.present : nullptr;
+}
+
+hopgnn_status pregather_from_marks(const int32_t* ids, int64_t n_ids, int64_t n_vertices, int32_t* uniq,
+                                   int64_t* n_uniq_dev, int32_t* remap, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (n_ids < 0 || n_vertices < 0 || n_uniq_dev == nullptr || ws == nullptr) return HOPGNN_EINVAL;
+    if (n_ids > 0 && (ids == nullptr || remap == nullptr || uniq == nullptr)) return HOPGNN_EINVAL;
+    if (n_ids >= ((int64_t)1 << 31) || n_vertices > ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    const BitmapWs L = bitmap_layout(ws, n_vertices);
+    if (ws_bytes < L.bytes) return HOPGNN_ENOMEM_WS;
+    return bitmap_from_marks(L, true, ids, n_ids, uniq, n_uniq_dev, remap, s);
+}
+
+}  // namespace hopgnn
+
+extern "C" hopgnn_status hopgnn_pregather_ws_init(void* ws, size_t ws_bytes, int64_t n_ids, int64_t n_vertices,
+                                                  int32_t algo, void* stream) {
+    if (ws == nullptr || n_ids < 0 || n_vertices < 0 || !aligned(ws, 256)) return HOPGNN_EINVAL;
+    if (algo != HOPGNN_PG_AUTO && algo != HOPGNN_PG_BITMAP && algo != HOPGNN_PG_RADIX) return HOPGNN_EINVAL;
+    if (pick_algo(algo, n_ids, n_vertices) == HOPGNN_PG_RADIX)
+        return ws_bytes >= radix_layout(nullptr, n_ids).bytes ? HOPGNN_OK : HOPGNN_ENOMEM_WS;   // nothing to prepare
+    const BitmapWs L = bitmap_layout(ws, n_vertices);
+    if (ws_bytes < L.bytes) return HOPGNN_ENOMEM_WS;
+    const int64_t n_vec = L.n_words_padded * 2;
+    hipLaunchKernelGGL(present_clear, dim3(grid_for(n_vec, kPgThreads, 256 * 16)), dim3(kPgThreads), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<uint4*>(L.present), n_vec, L.ticket,
+                       static_cast<int64_t*>(nullptr));
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }
 
 extern "C" size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo) {

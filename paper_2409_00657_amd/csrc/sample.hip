@@ -7,7 +7,7 @@
 // all micrographs run in a single launch.  Work per slot is two dependent
 // random reads (row bounds, then one neighbour) - latency bound, hidden by
 // keeping every micrograph's workgroup resident at once.
-#include "common.hpp"
+#include "pregather_internal.hpp"
 
 namespace hopgnn {
 
@@ -41,7 +41,8 @@ template <typename OffT>
 __global__ void __launch_bounds__(256)
 sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
                    const int32_t* __restrict__ seeds, int32_t n_seeds, SampleShape sh,
-                   BatchKeys keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride) {
+                   BatchKeys keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride,
+                   uint8_t* __restrict__ present) {
     const int32_t m = blockIdx.x;
     const int32_t B = n_seeds;
     const uint32_t batch = blockIdx.y;
@@ -53,6 +54,7 @@ sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__
     const int32_t root = seeds[m];
     if (threadIdx.x == 0) {
         ids[m] = root;
+        if (present != nullptr && root >= 0) present[root] = 1;   // the pre-gather's presence map
         if (indptr != nullptr && m == 0) indptr[sh.base[sh.n_layers]] = sh.base[sh.n_layers + 1] - B;
     }
     for (int32_t h = 1; h <= sh.n_layers; ++h) {
@@ -76,6 +78,7 @@ sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__
                 }
             }
             children[c] = child;
+            if (present != nullptr && child >= 0) present[child] = 1;
             if (slot_idx != nullptr && h < sh.n_layers) {   // non-leaf child: its own row in later layers
                 const int32_t slot = sh.base[h] + m * P + (int32_t)c;
                 slot_idx[slot - B] = child >= 0 ? slot : -1;
@@ -112,9 +115,9 @@ extern "C" int64_t hopgnn_slots_per_seed(const int32_t* fanouts, int32_t n_layer
 
 namespace hopgnn {
 
-static hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts,
-                                    int32_t n_layers, const uint64_t* keys, int32_t n_batches, int32_t* ids,
-                                    int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride, void* stream) {
+hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, const int32_t* fanouts,
+                             int32_t n_layers, const uint64_t* keys, int32_t n_batches, int32_t* ids, int32_t* indptr,
+                             int32_t* slot_idx, int64_t slot_idx_stride, uint8_t* present, void* stream) {
     if (g == nullptr || fanouts == nullptr || n_seeds < 0 || n_batches < 0) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
     if (t_seed < 0) return HOPGNN_EINVAL;
@@ -153,11 +156,11 @@ static hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, i
         if (g->offsets_i64)
             hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
                                static_cast<const int64_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride);
+                               slot_idx_stride, present);
         else
             hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
                                static_cast<const int32_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride);
+                               slot_idx_stride, present);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
@@ -169,7 +172,7 @@ extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds
                                        const int32_t* fanouts, int32_t n_layers, uint64_t key,
                                        int32_t* ids, int32_t* indptr, int32_t* slot_idx,
                                        void* stream) {
-    return sample_batches(g, seeds, n_seeds, fanouts, n_layers, &key, 1, ids, indptr, slot_idx, 0, stream);
+    return sample_batches(g, seeds, n_seeds, fanouts, n_layers, &key, 1, ids, indptr, slot_idx, 0, nullptr, stream);
 }
 
 extern "C" hopgnn_status hopgnn_sample_group(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
@@ -177,7 +180,7 @@ extern "C" hopgnn_status hopgnn_sample_group(const hopgnn_csr* g, const int32_t*
                                              int32_t n_batches, int32_t* ids, int32_t* indptr, int32_t* slot_idx,
                                              int64_t slot_idx_stride, void* stream) {
     return sample_batches(g, seeds, n_seeds, fanouts, n_layers, keys, n_batches, ids, indptr, slot_idx, slot_idx_stride,
-                          stream);
+                          nullptr, stream);
 }
 
 extern "C" const char* hopgnn_status_str(hopgnn_status s) {

@@ -152,6 +152,9 @@ class HotPath:
         pl.pg_ws, pl.pg_ws_bytes = self.pg_ws.data_ptr(), self.pg_ws.numel()
         pl.sage_ws, pl.sage_ws_bytes = self.sage_ws.data_ptr(), self.sage_ws.numel()
         pl.mark_gather_begin = pl.mark_gather_end = None
+        # every call of the library leaves the pre-gather workspace clean, so prepare it once
+        hb.hopgnn_pregather_ws_init(self.pg_ws, self.group * T, self.n_vertices, self.pg_algo)
+        pl.pg_ws_clean = 1
         self._keys = (ctypes.c_uint64 * self.group)()
 
     # -- the four steps ------------------------------------------------------

@@ -103,6 +103,17 @@ def _check_batch(orc, hp, cfg, graph_np, X, weights, seeds_list, keys, row_budge
     assert int(hp.n_uniq.item()) == U
     for b in range(G):
         assert to_bits(out[b * B:(b + 1) * B]).tobytes() == to_bits(layer_out[b][L - 1]).tobytes(), (cfg.name, b)
+    # that call sampled straight into the pre-gather's presence map (the pipeline keeps its
+    # workspace clean); without that promise the same call takes the general path: same bits
+    assert hp.plan.pg_ws_clean == 1
+    hp.plan.pg_ws_clean = 0
+    out2 = torch.full_like(out, float("nan"))
+    hp.remap.fill_(-7)
+    hp.forward(torch.cat(list(seeds_list)), keys, out2)
+    torch.cuda.synchronize()
+    hp.plan.pg_ws_clean = 1
+    np.testing.assert_array_equal(hp.remap.cpu().numpy(), ref_remap)
+    assert to_bits(out2).tobytes() == to_bits(out).tobytes()
     return stats, layer_out, ref_ids, ref_remap, Xu_ref
 
 

@@ -164,6 +164,33 @@ def test_pregather_bit_exact(hb, orc, case, algo):
     np.testing.assert_array_equal(remap, ref_remap)
 
 
+def test_pregather_leaves_its_workspace_clean(hb, orc):
+    """Whatever the workspace held, after a bitmap pre-gather the presence map (one byte per vertex
+    at the start of the workspace) is zero again, and a prepared workspace stays prepared."""
+    rng = np.random.default_rng(77)
+    N, T = 100_000, 30_000
+    ids_np = rng.integers(0, N, size=T).astype(np.int32)
+    ids_np[rng.random(T) < 0.1] = -1
+    ids = torch.from_numpy(ids_np).to(DEV)
+    ws = torch.empty(hb.hopgnn_pregather_ws_bytes(T, N, 1), dtype=torch.uint8, device=DEV)
+    ws.fill_(0x5A)
+    uniq = torch.empty(T, dtype=torch.int32, device=DEV)
+    remap = torch.empty(T, dtype=torch.int32, device=DEV)
+    n_uniq = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ref_u, ref_r = orc.pregather(ids_np)
+    for _ in range(2):
+        hb.hopgnn_pregather(ids, N, uniq, n_uniq, remap, ws, algo=1)
+        torch.cuda.synchronize()
+        assert int(n_uniq.item()) == len(ref_u)
+        np.testing.assert_array_equal(uniq[:len(ref_u)].cpu().numpy(), ref_u)
+        np.testing.assert_array_equal(remap.cpu().numpy(), ref_r)
+        assert int(ws[:N].to(torch.int64).sum().item()) == 0
+    ws.fill_(0x33)
+    hb.hopgnn_pregather_ws_init(ws, T, N, 1)
+    torch.cuda.synchronize()
+    assert int(ws[:N].to(torch.int64).sum().item()) == 0
+
+
 def test_pregather_hub_heavy_and_repeatable(hb, orc):
     # power-law-like multiset: a few IDs repeated tens of thousands of times
     rng = np.random.default_rng(7)
