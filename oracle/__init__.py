@@ -71,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.orc_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                    c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
                                    c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.orc_sage_agg_fwd.restype = c.c_int
+        L.orc_sage_agg_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                       c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                       c.c_void_p]
         L.orc_gcn_fwd.restype = c.c_int
         L.orc_gcn_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                   c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p]
@@ -218,6 +222,28 @@ def sage_fwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, bias, relu):
                             _p(out))
     if rc:
         raise ValueError("orc_sage_fwd failed: %d" % rc)
+    return out
+
+
+def sage_agg_fwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, bias, agg, relu):
+    """GraphSAGE layer with neighbour aggregator agg (0 mean, 1 sum, 2 max) in float64."""
+    npdt = _NP_OF[dtype]
+    Hsrc = _arr(Hsrc, npdt)
+    W_self = _arr(W_self, npdt)
+    W_neigh = _arr(W_neigh, npdt)
+    bias = None if bias is None else _arr(bias, npdt)
+    n_src, d_in = Hsrc.shape
+    d_out = W_self.shape[1]
+    assert W_self.shape == (d_in, d_out) and W_neigh.shape == (d_in, d_out)
+    indptr = _arr(indptr, np.int32)
+    idx = _arr(idx, np.int32)
+    n_dst = len(indptr) - 1
+    self_idx = None if self_idx is None else _arr(self_idx, np.int32)
+    out = np.empty((n_dst, d_out), np.float64)
+    rc = lib().orc_sage_agg_fwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W_self),
+                                _p(W_neigh), _p(bias), d_out, int(agg), int(bool(relu)), _p(out))
+    if rc:
+        raise ValueError("orc_sage_agg_fwd failed: %d" % rc)
     return out
 
 

@@ -163,3 +163,39 @@ def test_gat_special_cases(orc):
     b = np.arange(6.0)
     np.testing.assert_array_equal(orc.gat_fwd(H, F64, np.array([-1], np.int32), np.array([0, 1], np.int32),
                                               np.array([-1], np.int32), W, a1, a2, b, 2, False)[0], b)
+
+
+def test_sage_aggregators_sum_and_max(orc):
+    """sum = count x mean (the pinned mean oracle); max against numpy's reduction over the listed
+    rows; closed cases."""
+    rng = np.random.default_rng(21)
+    H, W, self_idx, indptr, idx = _case(rng, 35, 24, 6, 5, 7)
+    W2 = rng.standard_normal((6, 5))
+    b = rng.standard_normal(5)
+    Z = np.zeros_like(W)
+    I = np.eye(6, 5)
+    # agg 0 is the GraphSAGE-mean layer itself
+    np.testing.assert_allclose(orc.sage_agg_fwd(H, F64, self_idx, indptr, idx, W, W2, b, 0, True),
+                               orc.sage_fwd(H, F64, self_idx, indptr, idx, W, W2, b, True), rtol=1e-14, atol=1e-15)
+    c = np.array([(idx[indptr[r]:indptr[r + 1]] >= 0).sum() for r in range(24)], float)[:, None]
+    self_part = orc.sage_fwd(H, F64, self_idx, indptr, idx, W, Z, b, False)
+    mean_part = orc.sage_fwd(H, F64, self_idx, indptr, idx, Z, W2, None, False)
+    np.testing.assert_allclose(orc.sage_agg_fwd(H, F64, self_idx, indptr, idx, W, W2, b, 1, False),
+                               self_part + c * mean_part, rtol=1e-12, atol=1e-12)
+    # max: the aggregate itself (W_self = 0, W_neigh = [I | 0]) against numpy over the listed rows
+    got = orc.sage_agg_fwd(H, F64, self_idx, indptr, idx, np.zeros((6, 5)), I, None, 2, False)
+    for r in range(24):
+        seg = idx[indptr[r]:indptr[r + 1]]
+        seg = seg[seg >= 0]
+        want = H[seg].max(axis=0)[:5] if len(seg) else np.zeros(5)
+        np.testing.assert_array_equal(got[r], want)
+    # all-negative rows: the maximum is negative, not the 0 the accumulator starts from
+    Hn = -np.abs(H) - 1.0
+    got = orc.sage_agg_fwd(Hn, F64, None, np.array([0, 3], np.int32), np.array([4, -1, 9], np.int32), np.zeros((6, 5)),
+                           I, None, 2, False)
+    np.testing.assert_array_equal(got[0], np.maximum(Hn[4], Hn[9])[:5])
+    # one neighbour: every aggregator returns that row
+    for agg in (0, 1, 2):
+        got = orc.sage_agg_fwd(H, F64, None, np.array([0, 1], np.int32), np.array([7], np.int32), np.zeros((6, 5)), I,
+                               None, agg, False)
+        np.testing.assert_array_equal(got[0], H[7][:5])
