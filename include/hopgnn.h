@@ -42,6 +42,9 @@ typedef enum {
 
 typedef enum { HOPGNN_F32 = 0, HOPGNN_BF16 = 1, HOPGNN_F16 = 2 } hopgnn_dtype;
 
+/* neighbour aggregators of hopgnn_sage_fwd_agg */
+typedef enum { HOPGNN_AGG_MEAN = 0, HOPGNN_AGG_SUM = 1, HOPGNN_AGG_MAX = 2 } hopgnn_agg;
+
 /* How hopgnn_pregather builds the set. Both give identical results. */
 typedef enum {
     HOPGNN_PG_AUTO = 0,   /* bitmap unless n_vertices > 256 * max(n_ids, 2^18)          */
@@ -222,6 +225,19 @@ hopgnn_status hopgnn_sage_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               int64_t n_dst, const void *W_self, const void *W_neigh,
                               const void *bias, int32_t d_out, int32_t relu, void *out, void *ws,
                               size_t ws_bytes, void *stream);
+
+/*
+ * hopgnn_sage_fwd with another neighbour aggregator (the paper's discussion of generality names
+ * sum and max beside the mean):  m_r = mean, sum or element-wise maximum of Hsrc[idx[e]] over the
+ * valid entries of row r (0 for an empty segment), out[r] = act(x_r W_self + m_r W_neigh + bias).
+ * agg is a hopgnn_agg; HOPGNN_AGG_MEAN is hopgnn_sage_fwd itself.  Same arguments, workspace
+ * (hopgnn_sage_fwd_ws_bytes) and errors; for 2-byte types m_r is rounded to dt before the product.
+ */
+hopgnn_status hopgnn_sage_fwd_agg(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                  const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                                  int64_t n_dst, const void *W_self, const void *W_neigh, const void *bias,
+                                  int32_t d_out, int32_t agg, int32_t relu, void *out, void *ws,
+                                  size_t ws_bytes, void *stream);
 
 /*
  * The other two layer types the paper's evaluation trains (experimental setup: GCN, GraphSAGE,

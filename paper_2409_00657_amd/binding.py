@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sample_group", "hopgnn_pregather_ws_init", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sample_group", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -120,6 +120,10 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_sage_fwd_agg.restype = c.c_int
+    L.hopgnn_sage_fwd_agg.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                      c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_pregather_ws_init.restype = c.c_int
     L.hopgnn_pregather_ws_init.argtypes = [c.c_void_p, c.c_size_t, c.c_int64, c.c_int64, c.c_int32, c.c_void_p]
     L.hopgnn_sample_group.restype = c.c_int
@@ -348,3 +352,17 @@ def hopgnn_gat_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tens
                                        _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(bias), d_out, n_heads,
                                        1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_gat_fwd")
+
+
+AGG_MEAN, AGG_SUM, AGG_MAX = 0, 1, 2
+
+
+def hopgnn_sage_fwd_agg(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                        idx: torch.Tensor, n_dst: int, W_self: torch.Tensor, W_neigh: torch.Tensor,
+                        bias: Optional[torch.Tensor], agg: int, relu: bool, out: torch.Tensor, ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_fwd_agg(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                            _ptr(idx), n_dst, _ptr(W_self), _ptr(W_neigh), _ptr(bias), d_out, agg,
+                                            1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(),
+                                            _stream())
+    _check(rc, "hopgnn_sage_fwd_agg")

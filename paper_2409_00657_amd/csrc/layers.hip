@@ -298,7 +298,7 @@ extern "C" hopgnn_status hopgnn_gcn_fwd(const void* Hsrc, hopgnn_dtype dt, int64
         n_tr = (uint32_t)(L.KP / 32) * (uint32_t)(L.NP / 32);
     }
     // with n_src == 0 every self index must be negative; identity self was rejected above
-    const AggSpec spec{self_idx, 1, norm};
+    const AggSpec spec{self_idx, 1, norm ? kAggOpMean : kAggOpSum};
     hopgnn_status st;
     if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);
     else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);

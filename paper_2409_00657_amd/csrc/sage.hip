@@ -601,6 +601,9 @@ hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc,
 
 using namespace hopgnn;
 
+static_assert(HOPGNN_AGG_MEAN == kAggOpMean && HOPGNN_AGG_SUM == kAggOpSum && HOPGNN_AGG_MAX == kAggOpMax,
+              "aggregator codes");
+
 extern "C" size_t hopgnn_sage_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out) {
     if (n_dst < 0 || d_in < 1 || d_out < 1) return 0;
     return proj_ws_layout(dt, n_dst, d_in, 2 * d_in, d_out).total;
@@ -612,6 +615,17 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
                                          const void* W_neigh, const void* bias, int32_t d_out,
                                          int32_t relu, void* out, void* ws, size_t ws_bytes,
                                          void* stream) {
+    return hopgnn_sage_fwd_agg(Hsrc, dt, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, bias, d_out,
+                               HOPGNN_AGG_MEAN, relu, out, ws, ws_bytes, stream);
+}
+
+extern "C" hopgnn_status hopgnn_sage_fwd_agg(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                             const int32_t* self_idx, const int32_t* indptr,
+                                             const int32_t* idx, int64_t n_dst, const void* W_self,
+                                             const void* W_neigh, const void* bias, int32_t d_out, int32_t agg,
+                                             int32_t relu, void* out, void* ws, size_t ws_bytes,
+                                             void* stream) {
+    if (agg != HOPGNN_AGG_MEAN && agg != HOPGNN_AGG_SUM && agg != HOPGNN_AGG_MAX) return HOPGNN_EINVAL;
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (n_dst == 0) return HOPGNN_OK;
@@ -638,9 +652,10 @@ extern "C" hopgnn_status hopgnn_sage_fwd(const void* Hsrc, hopgnn_dtype dt, int6
         n_tr = (uint32_t)(L.KP / 32) * (uint32_t)(L.NP / 32);
     }
     hopgnn_status st;
-    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
-    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
-    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s);
+    const AggSpec spec{nullptr, 0, agg};     // the C ABI's aggregator codes are the kernel's op codes
+    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
+    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
+    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
     if (st != HOPGNN_OK) return st;
 
     return project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,

@@ -69,16 +69,17 @@ struct TransposeJob {
     int32_t k_total;
 };
 
-// What the segmented aggregation adds to the neighbour rows and how it is normalised:
-// GraphSAGE-mean is {nullptr, 0, 1} (neighbours only, divided by their number); with_self adds
-// the destination's own source row (self_idx, or row r when self_idx is NULL; a negative entry
-// adds nothing) and counts it; divide = 0 leaves the plain sum.
+// What the segmented aggregation combines and how:  op 0 = sum divided by the number of terms
+// (mean), 1 = plain sum, 2 = element-wise maximum; with_self adds the destination's own source
+// row as a term (self_idx, or row r when self_idx is NULL; a negative entry is no term).
+// GraphSAGE-mean is {nullptr, 0, 0}.  No terms gives 0 for every op.
 struct AggSpec {
     const int32_t* self_idx;
     int32_t with_self;
-    int32_t divide;
+    int32_t op;
 };
-constexpr AggSpec kAggMean{nullptr, 0, 1};
+constexpr int kAggOpMean = 0, kAggOpSum = 1, kAggOpMax = 2;
+constexpr AggSpec kAggMean{nullptr, 0, kAggOpMean};
 
 __device__ __forceinline__ void transpose_w_tile(const TransposeJob& J, uint32_t tile_id) {
     __shared__ uint16_t tile[32][33];
@@ -109,7 +110,7 @@ constexpr int kMeanUnroll = 4;
 // entries (negative index) are skipped by predication, which measured faster than
 // reading a stand-in row and masking it out (whole dead micrographs are common on
 // graphs with isolated vertices).  The sum runs in entry order.
-template <typename Tr>
+template <typename Tr, int OP>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
@@ -133,11 +134,12 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
 #pragma unroll
         for (int i = 0; i < Tr::kPer16; ++i) acc[i] = 0.f;
         int32_t cnt = 0;
-        if (self_row >= 0) {
+        constexpr bool is_max = OP == kAggOpMax;
+        if (self_row >= 0) {     // first term: the sum starts from 0, the maximum from this row
             Pack16<Tr> v;
             v.v = Hsrc[self_row * words_per_row + c];
 #pragma unroll
-            for (int i = 0; i < Tr::kPer16; ++i) acc[i] += Tr::to_f(v.e[i]);
+            for (int i = 0; i < Tr::kPer16; ++i) acc[i] = Tr::to_f(v.e[i]);
             ++cnt;
         }
         for (int32_t e = beg; e < end; e += kMeanUnroll) {
@@ -152,12 +154,15 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
             for (int k = 0; k < kMeanUnroll; ++k)
                 if (u[k] >= 0) {
 #pragma unroll
-                    for (int i = 0; i < Tr::kPer16; ++i) acc[i] += Tr::to_f(v[k].e[i]);
+                    for (int i = 0; i < Tr::kPer16; ++i) {
+                        const float x = Tr::to_f(v[k].e[i]);
+                        acc[i] = is_max ? (cnt == 0 ? x : fmaxf(acc[i], x)) : acc[i] + x;
+                    }
                     ++cnt;
                 }
         }
         Pack16<Tr> o;
-        const float fc = agg.divide ? (float)cnt : 1.f;
+        const float fc = OP == kAggOpMean ? (float)cnt : 1.f;
 #pragma unroll
         for (int i = 0; i < Tr::kPer16; ++i) o.e[i] = Tr::from_f(cnt > 0 ? acc[i] / fc : 0.f);
         Mean[r * words_per_row + c] = o.v;
@@ -165,7 +170,7 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
 }
 
 // Element path for rows that are not a whole number of 16-byte words.
-template <typename Tr>
+template <typename Tr, int OP>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
                const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
@@ -187,18 +192,20 @@ sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __r
     for (int32_t c = g; c < d_in; c += group) {
         float acc = 0.f;
         int32_t cnt = 0;
+        constexpr bool is_max = OP == kAggOpMax;
         if (self_row >= 0) {
-            acc += Tr::to_f(Hsrc[self_row * d_in + c]);
+            acc = Tr::to_f(Hsrc[self_row * d_in + c]);
             ++cnt;
         }
         for (int32_t e = beg; e < end; ++e) {
             const int32_t u = idx[e];
             if (u >= 0) {
-                acc += Tr::to_f(Hsrc[(int64_t)u * d_in + c]);
+                const float x = Tr::to_f(Hsrc[(int64_t)u * d_in + c]);
+                acc = is_max ? (cnt == 0 ? x : fmaxf(acc, x)) : acc + x;
                 ++cnt;
             }
         }
-        Mean[r * d_in + c] = Tr::from_f(cnt > 0 ? (agg.divide ? acc / (float)cnt : acc) : 0.f);
+        Mean[r * d_in + c] = Tr::from_f(cnt > 0 ? (OP == kAggOpMean ? acc / (float)cnt : acc) : 0.f);
     }
 }
 
@@ -223,13 +230,17 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
     if (mean_blocks + n_transpose_tiles >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     job.first_block = (uint32_t)mean_blocks;
     const int64_t blocks = mean_blocks + n_transpose_tiles;
+    auto kv = agg.op == kAggOpMean ? sage_mean_vec<Tr, kAggOpMean>
+              : agg.op == kAggOpSum ? sage_mean_vec<Tr, kAggOpSum> : sage_mean_vec<Tr, kAggOpMax>;
+    auto ke = agg.op == kAggOpMean ? sage_mean_elem<Tr, kAggOpMean>
+              : agg.op == kAggOpSum ? sage_mean_elem<Tr, kAggOpSum> : sage_mean_elem<Tr, kAggOpMax>;
     if (vec)
-        hipLaunchKernelGGL(sage_mean_vec<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
+        hipLaunchKernelGGL(kv, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
                            static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
                            agg);
     else
-        hipLaunchKernelGGL(sage_mean_elem<Tr>, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
+        hipLaunchKernelGGL(ke, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
                            static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
                            agg);

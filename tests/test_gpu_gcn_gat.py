@@ -90,6 +90,26 @@ def test_gat_fwd_vs_oracle(hb, orc, dt, shape):
         assert rel_err(to_f64(out), ref) <= TOL[dt], (shape, heads)
 
 
+@pytest.mark.parametrize("dt", DTYPES)
+@pytest.mark.parametrize("agg", [1, 2])
+@pytest.mark.parametrize("shape", [(300, 200, 32, 32, 6), (1500, 1111, 128, 128, 12), (300, 65, 7, 5, 4)])
+def test_sage_sum_and_max_aggregators_vs_oracle(hb, orc, dt, agg, shape):
+    n_src, n_dst, d_in, d_out, max_len = shape
+    rng = np.random.default_rng(n_src + 13 * agg)
+    H, W, b, self_idx, indptr, idx = _case(rng, n_src, n_dst, d_in, d_out, max_len, dt)
+    W2 = (torch.from_numpy(rng.standard_normal((d_in, d_out)).astype(np.float32)) / np.sqrt(d_in)).to(dt)
+    if agg == 2:      # all-negative rows too: the maximum must not start from zero
+        H = (-H.float().abs() - 0.5).to(dt) if n_src == 300 else H
+    ref = orc.sage_agg_fwd(to_bits(H), ORC_DT[dt], self_idx, indptr, idx, to_bits(W), to_bits(W2), to_bits(b), agg, True)
+    out = torch.full((n_dst, d_out), float("nan"), dtype=dt, device=DEV)
+    ws = torch.empty(hb.hopgnn_sage_fwd_ws_bytes(dt, n_dst, d_in, d_out), dtype=torch.uint8, device=DEV)
+    ws.fill_(0x5A)
+    hb.hopgnn_sage_fwd_agg(_dev(H), n_src, _dev(self_idx), _dev(indptr), _dev(idx), n_dst, _dev(W), _dev(W2), _dev(b),
+                           agg, True, out, ws)
+    torch.cuda.synchronize()
+    assert rel_err(to_f64(out), ref) <= TOL[dt], (shape, agg)
+
+
 def test_layers_on_a_sampled_batch(hb, orc):
     """Config 1, first layer over the pre-gathered rows (self and neighbours through remap): the
     attention layer projects each UNIQUE row once."""
