@@ -26,9 +26,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-# HBM bytes of the gather kernel per algorithmic byte, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs scaled by a plain copy kernel (profiles/gather_traffic_pmc.txt)
-GATHER_TRAFFIC_OVER_ALGORITHMIC = 1.012
+# HBM bytes of the gather kernel per algorithmic byte, by row size in bytes, from rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy kernel: 512-byte rows (workloads 2 and 4)
+# profiles/gather_traffic_pmc.txt; 400-byte rows (workload 3; rows straddle cache lines)
+# profiles/batch_traffic_pmc.txt.  Row sizes without a counter run report no traffic figure.
+GATHER_TRAFFIC_OVER_ALGORITHMIC = {512: 1.012, 400: 1.077}
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 DTYPE_NAME = {"torch.float32": "f32", "torch.bfloat16": "bf16", "torch.float16": "f16"}
 
@@ -288,7 +290,8 @@ def main():
         "stage_work": stage_work,
         "roofline": {"kernel": "gather_rows", "bound": "hbm", "achieved": gather_gbps,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gather_gbps / HBM_PEAK_GBPS,
-                     "traffic": gather_bytes * GATHER_TRAFFIC_OVER_ALGORITHMIC,
+                     "traffic": (gather_bytes * GATHER_TRAFFIC_OVER_ALGORITHMIC[row_bytes]
+                                 if row_bytes in GATHER_TRAFFIC_OVER_ALGORITHMIC else None),
                      "algorithmic_bytes_per_launch": gather_bytes,
                      "avg_launch_ms": gather_ms_avg, "launch_ms_percentiles": gather_pct,
                      "empty_event_pair_ms": empty_ms_avg,
