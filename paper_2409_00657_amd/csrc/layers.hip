@@ -21,15 +21,41 @@ namespace hopgnn {
 constexpr int kLayerThreads = 256;
 constexpr int kMaxHeads = 16;
 
-// Workgroup 0 zeroes the projection's zero row; workgroups 1.. transpose one 32 x 32 weight tile
-// each (2-byte types).
+// Attention scores are linear in the source row: <Hsrc[u] W[:, head], a[head]> = Hsrc[u] (W[:, head] a[head]),
+// so for fp32 they are 2 * n_heads extra output columns of a rows-times-matrix product with
+// Wscore[k][h] = sum_j W[k][h*dh + j] a_src[h*dh + j] and Wscore[k][n_heads + h] likewise with a_dst.
+struct ScoreWeightJob {
+    const float* W;
+    const float* a_src;
+    const float* a_dst;
+    float* Wscore;          // [d_in x 2*n_heads]; nullptr: no job
+    int32_t d_in, d_out, n_heads;
+    uint32_t n_blocks;
+};
+
+// Workgroup 0 zeroes the projection's zero row; the next n_blocks workgroups of the score-weight
+// job compute one entry of Wscore per thread; the rest transpose one 32 x 32 weight tile each
+// (2-byte types).
 __global__ void __launch_bounds__(kLayerThreads)
-layer_prep(uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job) {
+layer_prep(uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job, ScoreWeightJob sw) {
     if (blockIdx.x == 0) {
         for (int32_t i = threadIdx.x; i < zero_words; i += kLayerThreads) zero_row[i] = 0u;
         return;
     }
-    transpose_w_tile(job, blockIdx.x - 1);
+    if (blockIdx.x - 1 < sw.n_blocks) {
+        const int32_t cols = 2 * sw.n_heads, dh = sw.d_out / sw.n_heads;
+        const int64_t i = (int64_t)(blockIdx.x - 1) * kLayerThreads + threadIdx.x;
+        if (i >= (int64_t)sw.d_in * cols) return;
+        const int32_t k = (int32_t)(i / cols), c = (int32_t)(i % cols);
+        const int32_t h = c < sw.n_heads ? c : c - sw.n_heads;
+        const float* a = (c < sw.n_heads ? sw.a_src : sw.a_dst) + h * dh;
+        const float* w = sw.W + (int64_t)k * sw.d_out + h * dh;
+        float acc = 0.f;
+        for (int32_t j = 0; j < dh; ++j) acc += w[j] * a[j];
+        sw.Wscore[i] = acc;
+        return;
+    }
+    transpose_w_tile(job, blockIdx.x - 1 - sw.n_blocks);
 }
 
 // s_src[u][h] = <z_u[h], a_src[h]>, s_dst[u][h] = <z_u[h], a_dst[h]>.
@@ -43,7 +69,7 @@ __global__ void __launch_bounds__(kLayerThreads)
 gat_scores_vec(const float4* __restrict__ Z, const typename Tr::store_t* __restrict__ a_src,
                const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, const int64_t* __restrict__ n_src_dev,
                int32_t d_out, int32_t n_heads, int32_t lanes_row, int32_t seg, float* __restrict__ s_src,
-               float* __restrict__ s_dst) {
+               float* __restrict__ s_dst, int32_t score_stride) {
     if (n_src_dev != nullptr) {
         const int64_t live = *n_src_dev;
         n_src = live < n_src ? live : n_src;
@@ -70,8 +96,8 @@ gat_scores_vec(const float4* __restrict__ Z, const typename Tr::store_t* __restr
             pd += __shfl_xor(pd, o, kWave);
         }
         if (ok && (w & (seg - 1)) == 0) {
-            s_src[u * n_heads + w / seg] = ps;
-            s_dst[u * n_heads + w / seg] = pd;
+            s_src[u * score_stride + w / seg] = ps;
+            s_dst[u * score_stride + w / seg] = pd;
         }
     }
 }
@@ -81,7 +107,8 @@ template <typename Tr>
 __global__ void __launch_bounds__(kLayerThreads)
 gat_scores(const float* __restrict__ Z, const typename Tr::store_t* __restrict__ a_src,
            const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, const int64_t* __restrict__ n_src_dev,
-           int32_t d_out, int32_t n_heads, float* __restrict__ s_src, float* __restrict__ s_dst) {
+           int32_t d_out, int32_t n_heads, float* __restrict__ s_src, float* __restrict__ s_dst,
+           int32_t score_stride) {
     if (n_src_dev != nullptr) {
         const int64_t live = *n_src_dev;
         n_src = live < n_src ? live : n_src;
@@ -103,8 +130,8 @@ gat_scores(const float* __restrict__ Z, const typename Tr::store_t* __restrict__
             pd += __shfl_xor(pd, o, kWave);
         }
         if (lane == 0) {
-            s_src[u * n_heads + h] = ps;
-            s_dst[u * n_heads + h] = pd;
+            s_src[u * score_stride + h] = ps;
+            s_dst[u * score_stride + h] = pd;
         }
     }
 }
@@ -122,7 +149,7 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
               const float* __restrict__ s_dst, const int32_t* __restrict__ self_idx,
               const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx,
               const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
-              int32_t group, int relu, typename Tr::store_t* __restrict__ out) {
+              int32_t score_stride, int32_t group, int relu, typename Tr::store_t* __restrict__ out) {
     using T = typename Tr::store_t;
     const int64_t gid = (int64_t)blockIdx.x * kLayerThreads + threadIdx.x;
     const int64_t r = gid / group;
@@ -133,19 +160,19 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
     const int32_t beg = indptr[r], end = indptr[r + 1];
     for (int32_t c = g; c < units; c += group) {
         const int32_t h = (c * W) / dh;
-        const float sd = s >= 0 ? s_dst[s * n_heads + h] : 0.f;
+        const float sd = s >= 0 ? s_dst[s * score_stride + h] : 0.f;
         float mx = -INFINITY;
-        if (s >= 0) mx = leaky(sd + s_src[s * n_heads + h]);
+        if (s >= 0) mx = leaky(sd + s_src[s * score_stride + h]);
         for (int32_t e = beg; e < end; ++e) {
             const int32_t u = idx[e];
-            if (u >= 0) mx = fmaxf(mx, leaky(sd + s_src[(int64_t)u * n_heads + h]));
+            if (u >= 0) mx = fmaxf(mx, leaky(sd + s_src[(int64_t)u * score_stride + h]));
         }
         float acc[W];
 #pragma unroll
         for (int i = 0; i < W; ++i) acc[i] = 0.f;
         float den = 0.f;
         auto add = [&](int64_t u) {
-            const float w = expf(leaky(sd + s_src[u * n_heads + h]) - mx);
+            const float w = expf(leaky(sd + s_src[u * score_stride + h]) - mx);
             den += w;
             if (W == 1) {
                 acc[0] += w * Z[u * d_out + c];
@@ -183,7 +210,7 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
 // -------------------------------------------------------------------- host --
 
 struct GatWs {
-    size_t z_bytes, score_bytes;   // then the projection's [Wt][zero row]
+    size_t z_bytes, score_bytes, wscore_bytes;   // then the projection's [Wt][zero row]
     ProjWs P;
     size_t total;
 };
@@ -191,14 +218,15 @@ static GatWs gat_ws_layout(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t
     GatWs L{};
     const int64_t ns = n_src > 0 ? n_src : 1;
     L.z_bytes = align_up((size_t)ns * d_out * 4, 256);
-    L.score_bytes = align_up((size_t)ns * n_heads * 4, 256);
+    L.score_bytes = align_up((size_t)ns * 2 * n_heads * 4, 256);     // [n_src][s_src heads | s_dst heads]
+    L.wscore_bytes = align_up((size_t)d_in * 2 * n_heads * 4, 256);
     L.P = proj_ws_layout(dt, 0, d_in, d_in, d_out);     // no aggregate buffer: the rows are Hsrc itself
-    L.total = L.z_bytes + 2 * L.score_bytes + L.P.wt_bytes + L.P.zero_bytes;
+    L.total = L.z_bytes + L.score_bytes + L.wscore_bytes + L.P.wt_bytes + L.P.zero_bytes;
     return L;
 }
 
 static hopgnn_status launch_prep(hopgnn_dtype dt, const void* W, uint16_t* Wt, const ProjWs& P, int32_t d_in,
-                                 int32_t d_out, void* zero, hipStream_t s) {
+                                 int32_t d_out, void* zero, ScoreWeightJob sw, hipStream_t s) {
     TransposeJob job{};
     uint32_t n_tr = 0;
     if (dt != HOPGNN_F32) {
@@ -206,8 +234,9 @@ static hopgnn_status launch_prep(hopgnn_dtype dt, const void* W, uint16_t* Wt, c
                            P.NP, 0u, d_in};
         n_tr = (uint32_t)(P.KP / 32) * (uint32_t)(P.NP / 32);
     }
-    hipLaunchKernelGGL(layer_prep, dim3(1 + n_tr), dim3(kLayerThreads), 0, s, static_cast<uint32_t*>(zero),
-                       (int32_t)(P.zero_bytes / 4), job);
+    sw.n_blocks = sw.Wscore != nullptr ? (uint32_t)ceil_div((int64_t)sw.d_in * 2 * sw.n_heads, kLayerThreads) : 0u;
+    hipLaunchKernelGGL(layer_prep, dim3(1 + sw.n_blocks + n_tr), dim3(kLayerThreads), 0, s, static_cast<uint32_t*>(zero),
+                       (int32_t)(P.zero_bytes / 4), job, sw);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -216,10 +245,10 @@ template <typename Tr>
 static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_dst, float* s_src, float* s_dst,
                               int64_t n_src, const int64_t* n_src_dev, const int32_t* self_idx, const int32_t* indptr,
                               const int32_t* idx, const void* bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
-                              int relu, void* out, hipStream_t s) {
+                              int relu, void* out, bool scores_done, hipStream_t s) {
     using T = typename Tr::store_t;
-    const int32_t dh = d_out / n_heads;
-    if (n_src > 0) {
+    const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
+    if (n_src > 0 && !scores_done) {
         const int32_t seg = dh / 4;
         if (dh % 4 == 0 && seg <= 64 && (seg & (seg - 1)) == 0) {
             int32_t lanes_row = 1;
@@ -228,11 +257,11 @@ static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_ds
             hipLaunchKernelGGL(gat_scores_vec<Tr>, dim3((unsigned)ceil_div(waves, kLayerThreads / 64)),
                                dim3(kLayerThreads), 0, s, static_cast<const float4*>(Z), static_cast<const T*>(a_src),
                                static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, lanes_row, seg, s_src,
-                               s_dst);
+                               s_dst, stride);
         } else {
             hipLaunchKernelGGL(gat_scores<Tr>, dim3((unsigned)ceil_div(n_src, kLayerThreads / 64)), dim3(kLayerThreads),
                                0, s, static_cast<const float*>(Z), static_cast<const T*>(a_src),
-                               static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, s_src, s_dst);
+                               static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, s_src, s_dst, stride);
         }
         HOPGNN_LAUNCH_CHECK();
     }
@@ -244,11 +273,11 @@ static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_ds
     if (vec)
         hipLaunchKernelGGL((gat_aggregate<Tr, 4>), dim3((unsigned)blocks), dim3(kLayerThreads), 0, s,
                            static_cast<const float*>(Z), s_src, s_dst, self_idx, indptr, idx, static_cast<const T*>(bias),
-                           n_dst, d_out, n_heads, group, relu, static_cast<T*>(out));
+                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out));
     else
         hipLaunchKernelGGL((gat_aggregate<Tr, 1>), dim3((unsigned)blocks), dim3(kLayerThreads), 0, s,
                            static_cast<const float*>(Z), s_src, s_dst, self_idx, indptr, idx, static_cast<const T*>(bias),
-                           n_dst, d_out, n_heads, group, relu, static_cast<T*>(out));
+                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out));
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -336,13 +365,28 @@ extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64
     char* p = static_cast<char*>(ws);
     void* Z = p;
     float* s_src = reinterpret_cast<float*>(p + L.z_bytes);
-    float* s_dst = reinterpret_cast<float*>(p + L.z_bytes + L.score_bytes);
-    uint16_t* Wt = reinterpret_cast<uint16_t*>(p + L.z_bytes + 2 * L.score_bytes);
-    void* zero = p + L.z_bytes + 2 * L.score_bytes + L.P.wt_bytes;
+    float* s_dst = s_src + n_heads;
+    float* Wscore = reinterpret_cast<float*>(p + L.z_bytes + L.score_bytes);
+    uint16_t* Wt = reinterpret_cast<uint16_t*>(p + L.z_bytes + L.score_bytes + L.wscore_bytes);
+    void* zero = p + L.z_bytes + L.score_bytes + L.wscore_bytes + L.P.wt_bytes;
 
+    // fp32 with many source rows: the scores come from a second, skinny rows-times-matrix product (it
+    // reads the source rows once more instead of the wider z: 74 against 165 us on 0.47 M rows of
+    // 100 -> 256); otherwise from z, which is kept in fp32 (a few microseconds on small inputs,
+    // where the extra product's latency costs more)
+    const bool score_gemm = dt == HOPGNN_F32 && n_src >= 131072;
     if (n_src > 0) {
-        hopgnn_status st = launch_prep(dt, W, Wt, L.P, d_in, d_out, zero, s);
+        ScoreWeightJob sw{};
+        if (score_gemm)
+            sw = ScoreWeightJob{static_cast<const float*>(W), static_cast<const float*>(a_src),
+                                static_cast<const float*>(a_dst), Wscore, d_in, d_out, n_heads, 0u};
+        hopgnn_status st = launch_prep(dt, W, Wt, L.P, d_in, d_out, zero, sw, s);
         if (st != HOPGNN_OK) return st;
+        if (score_gemm) {
+            st = project_dispatch(dt, s, Hsrc, nullptr, Hsrc, Wscore, Wscore, nullptr, 0, nullptr, n_src, d_in, d_in,
+                                  2 * n_heads, 0, zero, s_src, 0, n_src_dev);
+            if (st != HOPGNN_OK) return st;
+        }
         // z = Hsrc W for every source row: identity row map, K = d_in, no bias, no activation
         st = project_dispatch(dt, s, Hsrc, nullptr, Hsrc, W, W, Wt, L.P.KP, nullptr, n_src, d_in, d_in, d_out, 0, zero, Z, 1,
                               n_src_dev);
@@ -350,10 +394,10 @@ extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64
     }
     if (dt == HOPGNN_F32)
         return gat_tail<TrF32>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
-                               relu, out, s);
+                               relu, out, score_gemm, s);
     if (dt == HOPGNN_BF16)
         return gat_tail<TrBF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
-                                relu, out, s);
+                                relu, out, false, s);
     return gat_tail<TrF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads, relu,
-                           out, s);
+                           out, false, s);
 }

@@ -44,6 +44,8 @@ SHAPES = [(300, 200, 32, 32, 6), (1500, 1111, 128, 128, 12), (4000, 777, 100, 25
 # enough rows for the 128 x 128 (fp32) and 256 x 256 (2-byte) projection tiles
 LARGE_GCN = (3000, 66000, 64, 256, 3)
 LARGE_GAT = (66000, 2000, 64, 256, 6)
+# enough source rows for fp32 attention scores to come from the skinny product
+MANY_ROWS_GAT = (132000, 500, 16, 32, 4)
 
 
 @pytest.mark.parametrize("dt", DTYPES)
@@ -66,7 +68,7 @@ def test_gcn_fwd_vs_oracle(hb, orc, dt, shape):
 
 
 @pytest.mark.parametrize("dt", DTYPES)
-@pytest.mark.parametrize("shape", SHAPES + [(600, 300, 40, 96, 5), LARGE_GAT])
+@pytest.mark.parametrize("shape", SHAPES + [(600, 300, 40, 96, 5), LARGE_GAT, MANY_ROWS_GAT])
 def test_gat_fwd_vs_oracle(hb, orc, dt, shape):
     n_src, n_dst, d_in, d_out, max_len = shape
     rng = np.random.default_rng(n_src + 5 * d_in)
