@@ -151,6 +151,7 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
               const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
               int32_t score_stride, int32_t group, int relu, typename Tr::store_t* __restrict__ out) {
     using T = typename Tr::store_t;
+    static_assert(W == 1 || W == 4, "one element or one 16-byte word of z per unit");
     const int64_t gid = (int64_t)blockIdx.x * kLayerThreads + threadIdx.x;
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
@@ -161,33 +162,60 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
     for (int32_t c = g; c < units; c += group) {
         const int32_t h = (c * W) / dh;
         const float sd = s >= 0 ? s_dst[s * score_stride + h] : 0.f;
+        constexpr int U = 4;     // entries in flight
         float mx = -INFINITY;
         if (s >= 0) mx = leaky(sd + s_src[s * score_stride + h]);
-        for (int32_t e = beg; e < end; ++e) {
-            const int32_t u = idx[e];
-            if (u >= 0) mx = fmaxf(mx, leaky(sd + s_src[(int64_t)u * score_stride + h]));
+        for (int32_t e = beg; e < end; e += U) {
+            int32_t u[U];
+            float sc[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) u[k] = e + k < end ? idx[e + k] : -1;
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (u[k] >= 0) sc[k] = s_src[(int64_t)u[k] * score_stride + h];
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (u[k] >= 0) mx = fmaxf(mx, leaky(sd + sc[k]));
         }
         float acc[W];
 #pragma unroll
         for (int i = 0; i < W; ++i) acc[i] = 0.f;
         float den = 0.f;
-        auto add = [&](int64_t u) {
-            const float w = expf(leaky(sd + s_src[u * score_stride + h]) - mx);
+        auto fetch = [&](int64_t u, float4& v) {
+            if (W == 1) v.x = Z[u * d_out + c];
+            else v = *reinterpret_cast<const float4*>(Z + u * d_out + (int64_t)c * W);
+        };
+        auto add = [&](float score, const float4& v) {
+            const float w = expf(leaky(sd + score) - mx);
             den += w;
-            if (W == 1) {
-                acc[0] += w * Z[u * d_out + c];
-            } else {
-                const float4 v = *reinterpret_cast<const float4*>(Z + u * d_out + (int64_t)c * W);
-                acc[0] += w * v.x;
+            acc[0] += w * v.x;
+            if (W > 1) {
                 acc[1] += w * v.y;
                 acc[2] += w * v.z;
                 acc[3] += w * v.w;
             }
         };
-        if (s >= 0) add(s);
-        for (int32_t e = beg; e < end; ++e) {
-            const int32_t u = idx[e];
-            if (u >= 0) add(u);
+        if (s >= 0) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            fetch(s, v);
+            add(s_src[s * score_stride + h], v);
+        }
+        for (int32_t e = beg; e < end; e += U) {     // U rows in flight, accumulated in entry order
+            int32_t u[U];
+            float sc[U];
+            float4 v[U];
+#pragma unroll
+            for (int k = 0; k < U; ++k) u[k] = e + k < end ? idx[e + k] : -1;
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (u[k] >= 0) {
+                    sc[k] = s_src[(int64_t)u[k] * score_stride + h];
+                    v[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    fetch(u[k], v[k]);
+                }
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+                if (u[k] >= 0) add(sc[k], v[k]);
         }
         const float inv = den > 0.f ? 1.f / den : 0.f;
         T o[W];
