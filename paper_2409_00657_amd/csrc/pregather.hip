@@ -30,11 +30,21 @@ constexpr int kPgThreads = 256;
 constexpr int kWordsPerThread = 4;                              // one 128-bit load
 constexpr int kWordsPerBlock = kPgThreads * kWordsPerThread;    // 1024 words = 32768 vertices
 
+// Same-address atomics retire one every ~40 ns, so a single "who is last" counter drawn by a
+// thousand workgroups costs 40 us.  The workgroups draw from per-group counters instead (groups of
+// kTicketGroup, each counter on its own line) and only the last of each group draws from the top one.
+constexpr int kTicketGroup = 32;
+constexpr int kMaxPackGrid = 1024;
+constexpr int kTicketChunks = 64;      // up to this many chunks (2 M vertices) the packing pass scans its own counts
+constexpr int kTicketLines = 1 + kMaxPackGrid / kTicketGroup;   // 33
+constexpr int kTicketStride = 32;                                // uint32 per 128-byte line
+
 struct BitmapWs {
     uint8_t* present;      // [32 * n_words_padded] one byte per vertex
     uint2* word_rank;      // [n_words_padded] (bits, rank of the word's first set bit inside its chunk)
     uint32_t* block_sum;   // [n_blocks] set bits per 1024-word chunk, then their exclusive prefix sum
-    uint32_t* ticket;      // [1] blocks finished counting
+    uint32_t* ticket;      // two-level "workgroups finished" counters, one per 128-byte line:
+                           // line 0 counts finished groups, line 1+g the finished workgroups of group g
     size_t bytes;
     int64_t n_words_padded;
     int64_t n_blocks;
@@ -54,7 +64,7 @@ static BitmapWs bitmap_layout(void* ws, int64_t n_vertices) {
     L.block_sum = reinterpret_cast<uint32_t*>(p + o);
     o += align_up((size_t)L.n_blocks * 4, 256);
     L.ticket = reinterpret_cast<uint32_t*>(p + o);
-    o += 256;
+    o += kTicketLines * 128;
     L.bytes = o;
     return L;
 }
@@ -64,9 +74,9 @@ present_clear(uint4* __restrict__ present16, int64_t n_vec, uint32_t* ticket, in
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
         present16[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *ticket = 0u;
-        if (n_uniq != nullptr) *n_uniq = 0;
+    if (blockIdx.x == 0) {
+        for (int i = threadIdx.x; i < kTicketLines; i += blockDim.x) ticket[i * kTicketStride] = 0u;
+        if (threadIdx.x == 0 && n_uniq != nullptr) *n_uniq = 0;
     }
 }
 
@@ -121,7 +131,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* l
 // chunk bases and publishes U.  With UNMARK the marks are wiped as they are read (only the
 // 16-byte pieces that hold one) and the ticket is reset, which leaves the presence map and the
 // ticket as hopgnn_pregather_ws_init left them.
-template <bool UNMARK>
+template <bool UNMARK, bool TICKET>
 __global__ void __launch_bounds__(kPgThreads)
 bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, uint32_t* block_sum,
                   uint32_t* ticket, int64_t* n_uniq, uint32_t n_blocks) {
@@ -142,9 +152,14 @@ bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, 
 #pragma unroll
         for (int k = 0; k < 8; ++k) q[k] = src[k * kWave + lane];
         if (UNMARK) {
+            // Wipe only the pieces that hold a mark while they are few (sparse partial-line writes);
+            // once more than a quarter of a 1 KiB run is marked, rewrite the whole run (full lines).
 #pragma unroll
-            for (int k = 0; k < 8; ++k)
-                if ((q[k].x | q[k].y | q[k].z | q[k].w) != 0u) src[k * kWave + lane] = make_uint4(0u, 0u, 0u, 0u);
+            for (int k = 0; k < 8; ++k) {
+                const bool marked = (q[k].x | q[k].y | q[k].z | q[k].w) != 0u;
+                const bool dense = __popcll(__ballot(marked)) > kWave / 4;
+                if (marked || dense) src[k * kWave + lane] = make_uint4(0u, 0u, 0u, 0u);
+            }
         }
         // word k*32 + lane/2 of the wave, its popcount on the even lane, and its rank among the
         // wave's 256 words in word order (row k before row k+1, lanes in order inside a row)
@@ -177,10 +192,17 @@ bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, 
         if (threadIdx.x == 0)
             __hip_atomic_store(&block_sum[chunk], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (!TICKET) return;      // the chunk counts are scanned by a launch of their own
     if (threadIdx.x == 0) {
+        const uint32_t group = blockIdx.x / kTicketGroup, n_groups = (gridDim.x + kTicketGroup - 1) / kTicketGroup;
+        const uint32_t group_size = group + 1 < n_groups ? kTicketGroup : gridDim.x - group * kTicketGroup;
         __threadfence();
-        const uint32_t done = atomicAdd(ticket, 1u);
-        is_last = (done == gridDim.x - 1);
+        bool last = atomicAdd(&ticket[(1 + group) * kTicketStride], 1u) == group_size - 1;
+        if (last) {
+            __threadfence();
+            last = atomicAdd(&ticket[0], 1u) == n_groups - 1;
+        }
+        is_last = last;
     }
     __syncthreads();
     if (!is_last) return;
@@ -196,10 +218,31 @@ bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, 
         if (b < n_blocks) block_sum[b] = carry + ex;
         carry += tot;
     }
-    if (threadIdx.x == 0) {
-        *n_uniq = (int64_t)carry;
-        if (UNMARK) *ticket = 0u;
+    if (threadIdx.x == 0) *n_uniq = (int64_t)carry;
+    if (UNMARK)
+        for (int i = threadIdx.x; i < kTicketLines; i += kPgThreads) ticket[i * kTicketStride] = 0u;
+}
+
+// The scan of the chunk counts as a launch of its own (one workgroup): exclusive prefix in place,
+// U published.  Used when there are many chunks: the in-kernel variant needs a device-scope
+// release fence in every workgroup before it draws its ticket, and with thousands of workgroups
+// those fences cost far more than one small launch.
+__global__ void __launch_bounds__(kPgThreads)
+bitmap_scan_sums(uint32_t* __restrict__ block_sum, uint32_t n_blocks, int64_t* __restrict__ n_uniq) {
+    __shared__ uint32_t lds4[kPgThreads / kWave];
+    // thread t owns the contiguous run [t*per, (t+1)*per): sum it, scan the 256 run sums, write back
+    const uint32_t per = (n_blocks + kPgThreads - 1) / kPgThreads;
+    const uint32_t b0 = threadIdx.x * per, b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
+    uint32_t mine = 0;
+    for (uint32_t b = b0; b < b1; ++b) mine += block_sum[b];
+    uint32_t total;
+    uint32_t run = block_exclusive_scan(mine, lds4, total);
+    for (uint32_t b = b0; b < b1; ++b) {
+        const uint32_t x = block_sum[b];
+        block_sum[b] = run;
+        run += x;
     }
+    if (threadIdx.x == 0) *n_uniq = (int64_t)total;
 }
 
 // Pass 2, one launch for both outputs.  Workgroups [0, n_emit_blocks) walk one chunk of the
@@ -251,14 +294,18 @@ static int grid_for(int64_t n, int per_block, int cap) {
 // Packing pass + the fused second pass, from a presence map that holds the marks of `ids`.
 static hopgnn_status bitmap_from_marks(const BitmapWs& L, bool unmark, const int32_t* ids, int64_t n_ids,
                                        int32_t* uniq, int64_t* n_uniq_dev, int32_t* remap, hipStream_t s) {
-    const dim3 pack_grid((unsigned)(L.n_blocks < 1024 ? L.n_blocks : 1024));
-    if (unmark)
-        hipLaunchKernelGGL(bitmap_pack_count<true>, pack_grid, dim3(kPgThreads), 0, s, reinterpret_cast<uint4*>(L.present),
-                           L.word_rank, L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
-    else
-        hipLaunchKernelGGL(bitmap_pack_count<false>, pack_grid, dim3(kPgThreads), 0, s, reinterpret_cast<uint4*>(L.present),
-                           L.word_rank, L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
+    const dim3 pack_grid((unsigned)(L.n_blocks < kMaxPackGrid ? L.n_blocks : kMaxPackGrid));
+    const bool ticket = L.n_blocks <= kTicketChunks;
+    auto pack = unmark ? (ticket ? bitmap_pack_count<true, true> : bitmap_pack_count<true, false>)
+                       : (ticket ? bitmap_pack_count<false, true> : bitmap_pack_count<false, false>);
+    hipLaunchKernelGGL(pack, pack_grid, dim3(kPgThreads), 0, s, reinterpret_cast<uint4*>(L.present), L.word_rank,
+                       L.block_sum, L.ticket, n_uniq_dev, (uint32_t)L.n_blocks);
     HOPGNN_LAUNCH_CHECK();
+    if (!ticket) {
+        hipLaunchKernelGGL(bitmap_scan_sums, dim3(1), dim3(kPgThreads), 0, s, L.block_sum, (uint32_t)L.n_blocks,
+                           n_uniq_dev);
+        HOPGNN_LAUNCH_CHECK();
+    }
     const unsigned remap_blocks = n_ids > 0 ? (unsigned)grid_for(n_ids, kPgThreads, 256 * 32) : 0u;
     hipLaunchKernelGGL(bitmap_emit_remap, dim3((unsigned)L.n_blocks + remap_blocks), dim3(kPgThreads), 0, s, L.word_rank,
                        L.block_sum, (uint32_t)L.n_blocks, uniq, ids, n_ids, remap);
@@ -684,7 +731,7 @@ static SplitWs split_layout(void* ws, int64_t n_uniq) {
     L.sums = reinterpret_cast<uint32_t*>(p + o);
     o += align_up((size_t)ceil_div(n, kWordsPerBlock) * 4, 256);
     L.ticket = reinterpret_cast<uint32_t*>(p + o);
-    o += 256;
+    o += kTicketLines * 128;
     L.bytes = o;
     return L;
 }
