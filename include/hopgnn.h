@@ -47,7 +47,7 @@ typedef enum { HOPGNN_AGG_MEAN = 0, HOPGNN_AGG_SUM = 1, HOPGNN_AGG_MAX = 2 } hop
 
 /* How hopgnn_pregather builds the set. Both give identical results. */
 typedef enum {
-    HOPGNN_PG_AUTO = 0,   /* bitmap unless n_vertices > 256 * max(n_ids, 2^18)          */
+    HOPGNN_PG_AUTO = 0,   /* bitmap unless n_vertices > 133e6 + 42 * n_ids               */
     HOPGNN_PG_BITMAP = 1, /* presence bitmap over the vertex range + popcount ranks     */
     HOPGNN_PG_RADIX = 2   /* LSD radix sort of (id, slot) pairs, head flags, scan       */
 } hopgnn_pg_algo;

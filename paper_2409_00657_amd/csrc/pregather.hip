@@ -242,7 +242,7 @@ bitmap_scan_sums(uint32_t* __restrict__ block_sum, uint32_t n_blocks, int64_t* _
         block_sum[b] = run;
         run += x;
     }
-    if (threadIdx.x == 0) *n_uniq = (int64_t)total;
+    if (threadIdx.x == 0 && n_uniq != nullptr) *n_uniq = (int64_t)total;
 }
 
 // Pass 2, one launch for both outputs.  Workgroups [0, n_emit_blocks) walk one chunk of the
@@ -495,6 +495,7 @@ radix_scatter(const uint32_t* __restrict__ keys_in, const uint32_t* __restrict__
 
 // In-place exclusive prefix sum of a[0..len): chunk sums, the last workgroup scans them
 // (and may publish the grand total), then every chunk is rescanned with its base.
+template <bool TICKET>
 __global__ void __launch_bounds__(kPgThreads)
 scan_chunk_sums(const uint32_t* __restrict__ a, int64_t len, uint32_t* __restrict__ sums, uint32_t n_chunks,
                 uint32_t* ticket, int64_t* total_out) {
@@ -511,6 +512,7 @@ scan_chunk_sums(const uint32_t* __restrict__ a, int64_t len, uint32_t* __restric
         if (threadIdx.x == 0)
             __hip_atomic_store(&sums[chunk], total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+    if (!TICKET) return;      // many chunks: bitmap_scan_sums scans the sums in a launch of its own
     if (threadIdx.x == 0) {
         __threadfence();
         is_last = (atomicAdd(ticket, 1u) == gridDim.x - 1);
@@ -584,9 +586,18 @@ __global__ void set_count_zero(int64_t* n_uniq) { *n_uniq = 0; }
 
 static hopgnn_status scan_in_place(uint32_t* a, int64_t len, const RadixWs& L, int64_t* total_out, hipStream_t s) {
     const int64_t n_chunks = ceil_div(len, kWordsPerBlock);
-    hipLaunchKernelGGL(scan_chunk_sums, dim3((unsigned)(n_chunks < 1024 ? n_chunks : 1024)), dim3(kPgThreads), 0, s,
-                       a, len, L.sums, (uint32_t)n_chunks, L.ticket, total_out);
-    HOPGNN_LAUNCH_CHECK();
+    const dim3 grid((unsigned)(n_chunks < 1024 ? n_chunks : 1024));
+    if (n_chunks <= kTicketChunks) {
+        hipLaunchKernelGGL(scan_chunk_sums<true>, grid, dim3(kPgThreads), 0, s, a, len, L.sums, (uint32_t)n_chunks,
+                           L.ticket, total_out);
+        HOPGNN_LAUNCH_CHECK();
+    } else {
+        hipLaunchKernelGGL(scan_chunk_sums<false>, grid, dim3(kPgThreads), 0, s, a, len, L.sums, (uint32_t)n_chunks,
+                           L.ticket, total_out);
+        HOPGNN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(bitmap_scan_sums, dim3(1), dim3(kPgThreads), 0, s, L.sums, (uint32_t)n_chunks, total_out);
+        HOPGNN_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_chunks), dim3(kPgThreads), 0, s, a, len, L.sums);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
@@ -740,14 +751,14 @@ static SplitWs split_layout(void* ws, int64_t n_uniq) {
 
 using namespace hopgnn;
 
-// The bitmap path costs ~1 us per million vertices (it clears, packs and ranks the whole vertex
-// range), the radix path ~100 us of launches plus ~50 us per million slots.  Measured on MI355X the
-// bitmap wins on every shape up to 176 vertices per slot (0.57 M slots over 100 M vertices: 106 vs
-// 129 us); AUTO switches to the sort beyond 256 vertices per slot.
+// The bitmap path costs ~0.6 us per million vertices (it packs and ranks the whole vertex range)
+// plus ~25 us per million slots, the radix path ~90 us of launches plus ~50 us per million slots.
+// Measured on MI355X (us, bitmap vs radix): 0.11 M slots / 1 M vertices 21 vs 75; 0.94 M / 2.4 M 41 vs
+// 105; 4.55 M / 100 M 208 vs 310; 0.57 M / 100 M 67 vs 117; 0.26 M / 100 M 59 vs 103; 0.26 M / 1500 M
+// 950 vs 105.  AUTO takes the sort where that model says it is cheaper.
 static int32_t pick_algo(int32_t algo, int64_t n_ids, int64_t n_vertices) {
     if (algo != HOPGNN_PG_AUTO) return algo;
-    const int64_t slots = n_ids > (1 << 18) ? n_ids : (1 << 18);
-    return n_vertices > 256 * slots ? HOPGNN_PG_RADIX : HOPGNN_PG_BITMAP;
+    return n_vertices > 133000000 + 42 * n_ids ? HOPGNN_PG_RADIX : HOPGNN_PG_BITMAP;
 }
 
 namespace hopgnn {
@@ -865,9 +876,18 @@ extern "C" hopgnn_status hopgnn_split_by_owner(const int32_t* uniq, int64_t n_un
                        L.flags, L.ticket);
     HOPGNN_LAUNCH_CHECK();
     const int64_t n_chunks = ceil_div(n_uniq, kWordsPerBlock);
-    hipLaunchKernelGGL(scan_chunk_sums, dim3((unsigned)(n_chunks < 1024 ? n_chunks : 1024)), dim3(kPgThreads), 0, s,
-                       L.flags, n_uniq, L.sums, (uint32_t)n_chunks, L.ticket, n_remote_dev);
-    HOPGNN_LAUNCH_CHECK();
+    const dim3 scan_grid((unsigned)(n_chunks < 1024 ? n_chunks : 1024));
+    if (n_chunks <= kTicketChunks) {
+        hipLaunchKernelGGL(scan_chunk_sums<true>, scan_grid, dim3(kPgThreads), 0, s, L.flags, n_uniq, L.sums,
+                           (uint32_t)n_chunks, L.ticket, n_remote_dev);
+        HOPGNN_LAUNCH_CHECK();
+    } else {
+        hipLaunchKernelGGL(scan_chunk_sums<false>, scan_grid, dim3(kPgThreads), 0, s, L.flags, n_uniq, L.sums,
+                           (uint32_t)n_chunks, L.ticket, n_remote_dev);
+        HOPGNN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(bitmap_scan_sums, dim3(1), dim3(kPgThreads), 0, s, L.sums, (uint32_t)n_chunks, n_remote_dev);
+        HOPGNN_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(scan_apply, dim3((unsigned)n_chunks), dim3(kPgThreads), 0, s, L.flags, n_uniq, L.sums);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(owner_compact, dim3(blocks), dim3(kPgThreads), 0, s, uniq, n_uniq, n_uniq_dev, owner, server,
