@@ -48,6 +48,9 @@ def parse():
                     help="also run the layers' backward pass with in-place gradient accumulation")
     ap.add_argument("--model", choices=["sage", "gcn", "gat"], default="sage",
                     help="layer type: GraphSAGE-mean (the headline workload), GCN-style mean, graph attention")
+    ap.add_argument("--no-merge", action="store_true",
+                    help="with a group > 1: run every batch's layers separately instead of one launch per layer "
+                         "over the group's merged micrographs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -125,14 +128,17 @@ def main():
     if args.model != "sage" and args.backward:
         print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
         sys.exit(2)
-    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, model=args.model)
+    merge = group > 1 and not args.no_merge and not args.backward
+    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, model=args.model, merge=merge)
            for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]      # default priority
     if args.backward:
         for h in hps:
             h.enable_backward()
     hp = hps[0]
-    sh = hp.shape
+    sh = hp.shape                                   # the layout the layers run on (merged: the whole group)
+    from paper_2409_00657_amd.pipeline import BatchShape
+    shb = BatchShape(cfg.batch, list(cfg.fanouts))  # one batch
     n_total = args.warmup + args.steps
     seeds = [[synth.seeds(cfg.n_vertices, cfg.batch, i * group + b, device=dev) for b in range(group)]
              for i in range(n_total)]
@@ -160,7 +166,7 @@ def main():
         h.gather(st)
         if ev is not None:
             ev[1].record(stream)
-        for b in range(group):
+        for b in range(h.layer_batches):
             h.layers(b, st)
             if args.backward:
                 h.backward(b, st)
@@ -215,9 +221,13 @@ def main():
         valid_sum += int((hp.ids >= 0).sum().item())
         if group > 1:       # reporting only: what per-batch pre-gathering would have fetched
             for b in range(group):
-                ib = hp.ids[b * sh.n_slots:(b + 1) * sh.n_slots]
+                if merge:   # batch b's slots of every level of the merged level-major array
+                    ib = torch.cat([hp.ids[sum(sh.levels[:h]) + b * shb.levels[h]:
+                                           sum(sh.levels[:h]) + (b + 1) * shb.levels[h]] for h in range(len(sh.levels))])
+                else:
+                    ib = hp.ids[b * shb.n_slots:(b + 1) * shb.n_slots]
                 U_per_batch_sum += int(torch.unique(ib[ib >= 0]).numel())
-        for b in range(group):      # one event pair per layer, summed over the group's batches
+        for b in range(hp.layer_batches):      # one event pair per layer, summed over the group's batches
             for k in range(1, sh.n_layers + 1):
                 a, c = E(), E()
                 a.record()
@@ -246,10 +256,10 @@ def main():
     es = X.element_size()
     valid_avg = valid_sum / n_replay
     stage_work = {"gather": {"bound": "hbm", "bytes": gather_bytes}}
-    stage_work["pregather"] = {"bound": "hbm", "bytes": group * sh.n_slots * 8 + 4 * U_avg}
+    stage_work["pregather"] = {"bound": "hbm", "bytes": group * shb.n_slots * 8 + 4 * U_avg}
     din = X.shape[1]
     for k in range(1, sh.n_layers + 1):
-        n_dst, nnz = sh.n_dst(k), sh.nnz(k)
+        n_dst, nnz = shb.n_dst(k), shb.nnz(k)
         if args.model == "sage":
             flops = 2.0 * n_dst * 2 * din * cfg.hidden
             nbytes = (nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
@@ -257,7 +267,7 @@ def main():
             flops = 2.0 * n_dst * din * cfg.hidden
             nbytes = (nnz + n_dst) * din * es + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
         else:                          # projection once per source row, then fp32 rows through the softmax gather
-            n_src = U_avg if k == 1 else sh.n_dst(k - 1)
+            n_src = U_avg / group if k == 1 else shb.n_dst(k - 1)
             flops = 2.0 * n_src * din * cfg.hidden
             nbytes = n_src * din * es + (nnz + n_dst) * cfg.hidden * 4 + 4 * (nnz + 2 * n_dst) + n_dst * cfg.hidden * es
         stage_work["sage_l%d" % k] = {"bound": "hbm+mfma", "bytes": group * nbytes, "flops": group * flops}
@@ -278,14 +288,14 @@ def main():
         "dtype": DTYPE_NAME[str(X.dtype)], "data": "synthetic",
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges,
                    "feature_dim": cfg.d, "batch": cfg.batch, "fanouts": cfg.fanouts,
-                   "hidden": cfg.hidden, "group": group, "slots_per_batch": sh.n_slots,
+                   "hidden": cfg.hidden, "group": group, "merged_layers": merge, "slots_per_batch": shb.n_slots,
                    "streams": n_streams, "backward": bool(args.backward), "layer": args.model},
         "gather_GBps": gather_gbps,
         "gather_frac_of_hbm_peak": gather_gbps / HBM_PEAK_GBPS,
         "unique_rows_per_step": U_avg,
         "unique_over_valid_slots": U_sum / max(valid_sum, 1),
         "unique_group_over_sum_of_per_batch_unique": (U_sum / U_per_batch_sum) if group > 1 else 1.0,
-        "valid_slot_fraction": valid_sum / (n_replay * group * sh.n_slots),
+        "valid_slot_fraction": valid_sum / (n_replay * group * shb.n_slots),
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
         "stage_work": stage_work,
         "roofline": {"kernel": "gather_rows", "bound": "hbm", "achieved": gather_gbps,

@@ -111,6 +111,20 @@ hopgnn_status hopgnn_sample(const hopgnn_csr *g /*HOST struct*/, const int32_t *
  * one batch writes); indptr is the same for every batch and is written once.
  * HOPGNN_ERANGE if n_batches * T does not fit the 32-bit slot arrays.
  */
+/*
+ * The same micrographs as hopgnn_sample_group, laid out as ONE level-major batch of n_seeds
+ * micrographs in which micrograph m draws with keys[m / seeds_per_key] (HOST array of
+ * ceil(n_seeds / seeds_per_key) keys): block b of seeds_per_key consecutive seeds is exactly the
+ * batch hopgnn_sample(seeds + b*seeds_per_key, seeds_per_key, ..., keys[b]) would sample, only the
+ * slots of all blocks share one level-major array, so that a layer runs once over all of them
+ * (micrograph merging, paper section 5.3: fewer, fuller steps).  ids [n_seeds * slots per seed],
+ * indptr and slot_idx as in hopgnn_sample for n_seeds seeds.
+ */
+hopgnn_status hopgnn_sample_merged(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
+                                   int32_t seeds_per_key, const int32_t *fanouts /*HOST*/, int32_t n_layers,
+                                   const uint64_t *keys /*HOST*/, int32_t *ids, int32_t *indptr,
+                                   int32_t *slot_idx, void *stream);
+
 hopgnn_status hopgnn_sample_group(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
                                   const int32_t *fanouts /*HOST*/, int32_t n_layers,
                                   const uint64_t *keys /*HOST*/, int32_t n_batches, int32_t *ids,
@@ -343,6 +357,13 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *   mark_gather_begin/_end      optional hipEvent_t pair recorded on `stream` around the gather
  *                               launch (NULL: none) so that a harness can time that kernel
  *                               inside its timed region
+ *   merge_layers                nonzero: the group's micrographs are sampled as one level-major
+ *                               batch (hopgnn_sample_merged, seeds_per_key = n_seeds) and every
+ *                               layer is ONE hopgnn_sage_fwd over the whole group instead of one
+ *                               per batch - the same rows per seed, far fewer and fuller launches.
+ *                               Then indptr holds group*S+1 entries, H[k] group times the rows,
+ *                               sage_ws is sized for group times the rows, and ids / remap /
+ *                               slot_idx are in the merged layout.
  *   pg_ws_clean                 nonzero: pg_ws was prepared by hopgnn_pregather_ws_init (sizes
  *                               group*T, n_vertices, pg_algo) and has since only been used by
  *                               this library's calls, all of which leave it clean.  Then the
@@ -380,6 +401,7 @@ typedef struct {
     size_t sage_ws_bytes;
     void *mark_gather_begin, *mark_gather_end;
     int32_t pg_ws_clean;
+    int32_t merge_layers;
 } hopgnn_batch_plan;
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sample_group", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -58,7 +58,7 @@ class BatchPlan(ctypes.Structure):
                 ("pg_ws", ctypes.c_void_p), ("pg_ws_bytes", ctypes.c_size_t),
                 ("sage_ws", ctypes.c_void_p), ("sage_ws_bytes", ctypes.c_size_t),
                 ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p),
-                ("pg_ws_clean", ctypes.c_int32)]
+                ("pg_ws_clean", ctypes.c_int32), ("merge_layers", ctypes.c_int32)]
 
 
 def library_path() -> str:
@@ -120,6 +120,9 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_sample_merged.restype = c.c_int
+    L.hopgnn_sample_merged.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.c_int32, c.POINTER(c.c_int32),
+                                       c.c_int32, c.POINTER(c.c_uint64), c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     L.hopgnn_sage_fwd_agg.restype = c.c_int
     L.hopgnn_sage_fwd_agg.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
@@ -208,6 +211,23 @@ def hopgnn_sample_group(offsets: torch.Tensor, indices: torch.Tensor, seeds: tor
     rc = load_library().hopgnn_sample_group(ctypes.byref(g), _ptr(seeds), n_seeds, _fan(fanouts), len(fanouts), karr, n,
                                             _ptr(ids), _ptr(indptr), _ptr(slot_idx), slot_idx_stride, _stream())
     _check(rc, "hopgnn_sample_group")
+
+
+def hopgnn_sample_merged(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor, seeds_per_key: int,
+                         fanouts: Sequence[int], keys: Sequence[int], ids: torch.Tensor,
+                         indptr: Optional[torch.Tensor] = None, slot_idx: Optional[torch.Tensor] = None) -> None:
+    """One level-major batch of seeds.numel() micrographs; block b of seeds_per_key seeds uses keys[b]."""
+    g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
+             1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+    if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
+        raise HopgnnError("offsets must be int32/int64 and indices int32")
+    n = seeds.numel()
+    if seeds.dtype != torch.int32 or len(keys) != -(-n // max(seeds_per_key, 1)):
+        raise HopgnnError("seeds must be int32 and keys hold one key per block of seeds_per_key seeds")
+    karr = (ctypes.c_uint64 * max(len(keys), 1))(*[k & 0xFFFFFFFFFFFFFFFF for k in keys])
+    rc = load_library().hopgnn_sample_merged(ctypes.byref(g), _ptr(seeds), n, seeds_per_key, _fan(fanouts), len(fanouts),
+                                             karr, _ptr(ids), _ptr(indptr), _ptr(slot_idx), _stream())
+    _check(rc, "hopgnn_sample_merged")
 
 
 def hopgnn_pregather_ws_bytes(n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> int:

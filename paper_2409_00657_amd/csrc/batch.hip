@@ -24,14 +24,23 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     const int64_t slot_idx_stride = S - B > 1 ? S - B : 1;
     const size_t es = dtype_size(p->dt);
     hipStream_t st = (hipStream_t)stream;
+    // merge_layers: the group is laid out as ONE level-major batch of n_batches * B micrographs
+    // (each block of B seeds with its own key), so every layer is one launch over the whole group
+    const bool merged = p->merge_layers != 0;
+    const int32_t B_run = merged ? n_batches * B : B;          // micrographs per layer launch
+    const int32_t n_runs = merged ? 1 : n_batches;
+    if ((int64_t)n_batches * T >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
 
     // With a workspace the caller keeps clean (hopgnn_pregather_ws_init once, then only calls that
     // leave it clean) the sampler marks the presence map itself: no clearing pass, no marking pass.
     uint8_t* marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes, (int64_t)p->group * T,
                                                           p->graph.n_vertices, p->pg_algo)
                                     : nullptr;
-    hopgnn_status rc = sample_batches(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
-                                      L > 1 ? p->slot_idx : nullptr, slot_idx_stride, marks, stream);
+    hopgnn_status rc =
+        merged ? sample_merged(&p->graph, seeds, B_run, B, p->fanouts, L, keys, p->ids, p->indptr,
+                               L > 1 ? p->slot_idx : nullptr, marks, stream)
+               : sample_batches(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
+                                L > 1 ? p->slot_idx : nullptr, slot_idx_stride, marks, stream);
     if (rc != HOPGNN_OK) return rc;
     if (marks != nullptr)
         rc = pregather_from_marks(p->ids, n_batches * T, p->graph.n_vertices, p->uniq, p->n_uniq, p->remap, p->pg_ws,
@@ -49,18 +58,19 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         return HOPGNN_EHIP;
 
     const int32_t d_last = p->d_out[L - 1];
-    for (int32_t b = 0; b < n_batches; ++b) {
+    const int64_t rows_scale = merged ? n_batches : 1;         // level sizes of one run = B_run / B times a batch's
+    for (int32_t b = 0; b < n_runs; ++b) {
         const int32_t* rb = p->remap + b * T;
         const void* src = p->Xu;
         int64_t n_src = p->uniq_capacity;
         int32_t d_in = p->dim;
         for (int32_t k = 1; k <= L; ++k) {
             int64_t n_dst = 0;                      // slots of levels 0 .. L-k
-            for (int h = 0; h <= L - k; ++h) n_dst += level[h];
+            for (int h = 0; h <= L - k; ++h) n_dst += level[h] * rows_scale;
             void* dst = k == L ? (void*)((char*)out + (size_t)b * B * d_last * es) : p->H[k - 1];
             if (dst == nullptr) return HOPGNN_EINVAL;
             rc = hopgnn_sage_fwd(src, p->dt, n_src, d_in, k == 1 ? rb : nullptr, p->indptr,
-                                 k == 1 ? rb + B : p->slot_idx + b * slot_idx_stride, n_dst, p->W_self[k - 1],
+                                 k == 1 ? rb + B_run : p->slot_idx + b * slot_idx_stride, n_dst, p->W_self[k - 1],
                                  p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], k < L ? 1 : 0, dst, p->sage_ws,
                                  p->sage_ws_bytes, stream);
             if (rc != HOPGNN_OK) return rc;

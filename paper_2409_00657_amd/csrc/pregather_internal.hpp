@@ -21,4 +21,9 @@ hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t 
                              int32_t n_layers, const uint64_t* keys, int32_t n_batches, int32_t* ids, int32_t* indptr,
                              int32_t* slot_idx, int64_t slot_idx_stride, uint8_t* present, void* stream);
 
+// hopgnn_sample_merged with the same optional marking.
+hopgnn_status sample_merged(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, int32_t seeds_per_key,
+                            const int32_t* fanouts, int32_t n_layers, const uint64_t* keys, int32_t* ids,
+                            int32_t* indptr, int32_t* slot_idx, uint8_t* present, void* stream);
+
 }  // namespace hopgnn

@@ -42,11 +42,14 @@ __global__ void __launch_bounds__(256)
 sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
                    const int32_t* __restrict__ seeds, int32_t n_seeds, SampleShape sh,
                    BatchKeys keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride,
-                   uint8_t* __restrict__ present) {
-    const int32_t m = blockIdx.x;
+                   uint8_t* __restrict__ present, int32_t m_offset, int32_t seeds_per_key) {
+    // Two ways to carry several keys: blockIdx.y = one batch (own seeds, key and output slices) of
+    // n_seeds micrographs each, or ONE level-major batch whose micrographs m_offset + blockIdx.x
+    // take the key of their block of seeds_per_key consecutive seeds (then gridDim.y = 1).
+    const int32_t m = m_offset + (int32_t)blockIdx.x;
     const int32_t B = n_seeds;
     const uint32_t batch = blockIdx.y;
-    const uint64_t keyed = keys.keyed[batch];
+    const uint64_t keyed = keys.keyed[batch + blockIdx.x / (uint32_t)seeds_per_key];
     seeds += (int64_t)batch * B;
     ids += (int64_t)batch * sh.base[sh.n_layers + 1];
     if (slot_idx != nullptr) slot_idx += (int64_t)batch * slot_idx_stride;
@@ -156,17 +159,71 @@ hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t 
         if (g->offsets_i64)
             hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
                                static_cast<const int64_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride, present);
+                               slot_idx_stride, present, 0, n_seeds);
         else
             hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
                                static_cast<const int32_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride, present);
+                               slot_idx_stride, present, 0, n_seeds);
+        HOPGNN_LAUNCH_CHECK();
+    }
+    return HOPGNN_OK;
+}
+
+hopgnn_status sample_merged(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, int32_t seeds_per_key,
+                            const int32_t* fanouts, int32_t n_layers, const uint64_t* keys, int32_t* ids,
+                            int32_t* indptr, int32_t* slot_idx, uint8_t* present, void* stream) {
+    if (g == nullptr || fanouts == nullptr || n_seeds < 0 || seeds_per_key < 1) return HOPGNN_EINVAL;
+    const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
+    if (t_seed < 0) return HOPGNN_EINVAL;
+    if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (g->offsets == nullptr || seeds == nullptr || ids == nullptr || keys == nullptr) return HOPGNN_EINVAL;
+    if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
+    if ((int64_t)n_seeds * t_seed >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+
+    SampleShape sh{};
+    sh.n_layers = n_layers;
+    sh.P[0] = 1;
+    sh.base[0] = 0;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        sh.f[h] = fanouts[h - 1];
+        sh.P[h] = sh.P[h - 1] * sh.f[h];
+        sh.base[h] = sh.base[h - 1] + n_seeds * sh.P[h - 1];
+    }
+    sh.base[n_layers + 1] = sh.base[n_layers] + n_seeds * sh.P[n_layers];
+    int threads = 64;
+    while (threads < 256 && threads < sh.P[n_layers]) threads *= 2;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int32_t n_keys = (int32_t)ceil_div(n_seeds, seeds_per_key);
+    for (int32_t k0 = 0; k0 < n_keys; k0 += kMaxBatchesPerLaunch) {     // 64 keys fit one launch's arguments
+        const int32_t nk = n_keys - k0 < kMaxBatchesPerLaunch ? n_keys - k0 : kMaxBatchesPerLaunch;
+        BatchKeys bk{};
+        for (int32_t i = 0; i < nk; ++i) bk.keyed[i] = host_finalise64(keys[k0 + i] + 0x9E3779B97F4A7C15ull);
+        const int64_t m0 = (int64_t)k0 * seeds_per_key;
+        const int64_t count = (int64_t)nk * seeds_per_key < n_seeds - m0 ? (int64_t)nk * seeds_per_key : n_seeds - m0;
+        const dim3 grid((unsigned)count, 1u);
+        if (g->offsets_i64)
+            hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
+                               static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh, bk, ids, indptr,
+                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key);
+        else
+            hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
+                               static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh, bk, ids, indptr,
+                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
 }
 
 }  // namespace hopgnn
+
+extern "C" hopgnn_status hopgnn_sample_merged(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                              int32_t seeds_per_key, const int32_t* fanouts, int32_t n_layers,
+                                              const uint64_t* keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx,
+                                              void* stream) {
+    return sample_merged(g, seeds, n_seeds, seeds_per_key, fanouts, n_layers, keys, ids, indptr, slot_idx, nullptr,
+                         stream);
+}
 
 extern "C" hopgnn_status hopgnn_sample(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
                                        const int32_t* fanouts, int32_t n_layers, uint64_t key,

@@ -47,16 +47,24 @@ class HotPath:
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor,
                  weights, n_seeds: int, fanouts: Sequence[int], group: int = 1,
-                 pg_algo: int = hb.PG_AUTO, model: str = "sage", gat_heads: int = 4):
+                 pg_algo: int = hb.PG_AUTO, model: str = "sage", gat_heads: int = 4, merge: bool = False):
         """`weights`: per layer (W_self, W_neigh, bias-or-None).  model "sage" uses all three;
         "gcn" (mean over the vertex and its neighbours) and "gat" use W_self as the layer's one
-        weight matrix, "gat" with seeded attention vectors and `gat_heads` heads."""
+        weight matrix, "gat" with seeded attention vectors and `gat_heads` heads.
+        merge: the group's micrographs form ONE level-major batch of group * n_seeds micrographs
+        (block b of n_seeds seeds keeps its own key), so every layer is one launch over the group;
+        `shape`, `ids`, `remap`, `H` then describe that merged batch and `layer_batches` is 1."""
         if model not in ("sage", "gcn", "gat"):
             raise hb.HopgnnError("model must be sage, gcn or gat")
         self.model, self.gat_heads = model, gat_heads
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
+        self.merge = bool(merge) and group > 1
+        self.n_keys, self.seeds_per_key = group, n_seeds       # one key per block of n_seeds seeds
+        if self.merge:
+            n_seeds, group = n_seeds * group, 1
+        self.layer_batches = group
         self.shape = sh = BatchShape(n_seeds, list(fanouts))
         self.group = group
         self.pg_algo = pg_algo
@@ -137,7 +145,7 @@ class HotPath:
         pl = self.plan = hb.BatchPlan()
         pl.graph = self._csr
         pl.X, pl.dt, pl.dim, pl.ld_elems = self.X.data_ptr(), dt, self.X.shape[1], self.X.stride(0)
-        pl.n_seeds, pl.n_layers = B, L
+        pl.n_seeds, pl.n_layers = self.seeds_per_key, L
         for i, f in enumerate(sh.fanouts):
             pl.fanouts[i] = f
         for i, (Ws, Wn, bias) in enumerate(self.weights):
@@ -145,7 +153,8 @@ class HotPath:
             pl.W_self[i], pl.W_neigh[i] = Ws.data_ptr(), Wn.data_ptr()
             pl.bias[i] = None if bias is None else bias.data_ptr()
             pl.H[i] = self.H[i].data_ptr()
-        pl.pg_algo, pl.group = self.pg_algo, self.group
+        pl.pg_algo, pl.group = self.pg_algo, self.n_keys
+        pl.merge_layers = 1 if self.merge else 0
         pl.ids, pl.indptr, pl.slot_idx = ids, self.indptr.data_ptr(), self._slot_idx_all.data_ptr()
         pl.uniq, pl.uniq_capacity, pl.n_uniq = self.uniq.data_ptr(), self.cap, self.n_uniq.data_ptr()
         pl.remap, pl.Xu = remap, self.Xu.data_ptr()
@@ -155,7 +164,7 @@ class HotPath:
         # every call of the library leaves the pre-gather workspace clean, so prepare it once
         hb.hopgnn_pregather_ws_init(self.pg_ws, self.group * T, self.n_vertices, self.pg_algo)
         pl.pg_ws_clean = 1
-        self._keys = (ctypes.c_uint64 * self.group)()
+        self._keys = (ctypes.c_uint64 * self.n_keys)()
 
     # -- the four steps ------------------------------------------------------
     # `stream` is a raw hipStream_t (int); None = torch's current stream.
@@ -165,6 +174,8 @@ class HotPath:
         return torch.cuda.current_stream().cuda_stream if stream is None else stream
 
     def sample(self, b: int, seeds: torch.Tensor, key: int, stream=None) -> None:
+        if self.merge:
+            raise hb.HopgnnError("a merged group is sampled with sample_group")
         g, B, fan, L, ids, indptr, slot_idx = self._sample_args[b]
         if seeds.numel() != B or seeds.dtype != torch.int32 or not seeds.is_cuda:
             raise hb.HopgnnError("seeds must be %d int32 values on the device" % B)
@@ -175,11 +186,21 @@ class HotPath:
 
     def sample_group(self, seeds: torch.Tensor, keys: Sequence[int], stream=None) -> None:
         """All of the group's batches in one launch; `seeds` holds their seeds back to back."""
-        n, B, L = len(keys), self.shape.n_seeds, self.shape.n_layers
-        if seeds.numel() != n * B or seeds.dtype != torch.int32 or not seeds.is_cuda or n > self.group:
+        n, B, L = len(keys), self.seeds_per_key, self.shape.n_layers
+        if seeds.numel() != n * B or seeds.dtype != torch.int32 or not seeds.is_cuda or n > self.n_keys:
             raise hb.HopgnnError("seeds must be %d x %d int32 values on the device" % (n, B))
         for i, k in enumerate(keys):
             self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
+        if self.merge:
+            if n != self.n_keys:
+                raise hb.HopgnnError("a merged group is sampled whole: %d keys" % self.n_keys)
+            rc = self._lib.hopgnn_sample_merged(ctypes.byref(self._csr), seeds.data_ptr(), n * B, B, self._fan, L,
+                                                self._keys, self.ids.data_ptr(), self.indptr.data_ptr(),
+                                                self._slot_idx_all.data_ptr() if L > 1 else None,
+                                                self._stream(stream))
+            if rc:
+                hb._check(rc, "hopgnn_sample_merged")
+            return
         rc = self._lib.hopgnn_sample_group(ctypes.byref(self._csr), seeds.data_ptr(), B, self._fan, L, self._keys, n,
                                            self.ids.data_ptr(), self.indptr.data_ptr(),
                                            self._slot_idx_all.data_ptr() if L > 1 else None,
@@ -274,9 +295,9 @@ class HotPath:
         if self.model != "sage":
             raise hb.HopgnnError("hopgnn_batch_fwd runs GraphSAGE-mean layers; use run_batch/run_group")
         n = len(keys)
-        if seeds.numel() != n * self.shape.n_seeds or seeds.dtype != torch.int32 or not seeds.is_cuda:
-            raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.shape.n_seeds))
-        if out.numel() != n * self.shape.n_seeds * self.H[-1].shape[1] or out.dtype != self.X.dtype \
+        if seeds.numel() != n * self.seeds_per_key or seeds.dtype != torch.int32 or not seeds.is_cuda:
+            raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.seeds_per_key))
+        if out.numel() != n * self.seeds_per_key * self.H[-1].shape[1] or out.dtype != self.X.dtype \
                 or not out.is_cuda or not out.is_contiguous():
             raise hb.HopgnnError("out must be a contiguous [n_batches*B, hidden] device tensor of X's type")
         for i, k in enumerate(keys):
@@ -292,12 +313,17 @@ class HotPath:
                   outs: Optional[List[torch.Tensor]] = None, stream=None) -> None:
         """G batches share one pre-gather and one gather; `outs[b]` (if given)
         receives a copy of batch b's final rows."""
-        assert len(seeds_list) == self.group
+        assert len(seeds_list) == self.n_keys
         st = self._stream(stream)
         self.sample_group(torch.cat(list(seeds_list)) if len(seeds_list) > 1 else seeds_list[0], keys, st)
         self.pregather(st)
         self.gather(st)
-        for b in range(self.group):
+        B = self.seeds_per_key
+        for b in range(self.layer_batches):
             h = self.layers(b, st)
             if outs is not None:
-                outs[b].copy_(h)
+                if self.merge:      # one launch per layer covered every batch of the group
+                    for i in range(self.n_keys):
+                        outs[i].copy_(h[i * B:(i + 1) * B])
+                else:
+                    outs[b].copy_(h)

@@ -213,3 +213,60 @@ def test_other_depths_and_groups_vs_oracle(orc, fanouts, group, dt):
     for it in range(2):
         seeds, keys = _seeds(cfg, it, group)
         _check_batch(orc, hp, cfg, graph_np, X, W, seeds, keys, full_forward=True)
+
+
+@pytest.mark.parametrize("fanouts,group,dt", [([5, 4], 3, torch.float32), ([3, 2, 2], 70, torch.float16),
+                                              ([6], 4, torch.bfloat16)])
+def test_merged_group_vs_oracle(orc, fanouts, group, dt):
+    """A group run as ONE level-major batch (every layer one launch over the group): block b of the
+    merged arrays is exactly the batch the oracle samples with keys[b], the pre-gathered set is that
+    of the concatenated batches, and every seed's output rows match the oracle's."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import BatchShape, HotPath
+    g = synth.rmat_graph(12, 9.0, device=DEV)
+    n, d, hidden, B = g.n_vertices, 16, 24, 20
+    L = len(fanouts)
+    X = synth.features(n, d, dt, device=DEV)
+    W = synth.sage_weights(d, hidden, L, dt, device=DEV, bias=True)
+    hp = HotPath(g.offsets, g.indices, X, W, B, fanouts, group=group, merge=True)
+    assert hp.merge and hp.layer_batches == 1 and hp.shape.n_seeds == group * B
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    shb, shm = BatchShape(B, list(fanouts)), hp.shape
+    for it in range(2):
+        seeds = synth.seeds(n, B * group, 50 + it, device=DEV)
+        keys = [1000 * it + 7 * b for b in range(group)]
+        out = torch.full((group * B, hidden), float("nan"), dtype=dt, device=DEV)
+        hp.forward(seeds, keys, out)
+        torch.cuda.synchronize()
+        ids_m = hp.ids.cpu().numpy()
+        remap_m = hp.remap.cpu().numpy()
+        # slots of batch b at level h inside the merged level-major array
+        def block(arr, b, h):
+            base = sum(shm.levels[:h])
+            return arr[base + b * shb.levels[h]: base + (b + 1) * shb.levels[h]]
+        ref_ids = []
+        for b in range(group):
+            i, ip = orc.sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fanouts, keys[b])
+            ref_ids.append(i)
+            for h in range(L + 1):
+                lo = sum(shb.levels[:h])
+                np.testing.assert_array_equal(block(ids_m, b, h), i[lo:lo + shb.levels[h]])
+        ru, rr = orc.pregather(np.concatenate(ref_ids))
+        U = int(hp.n_uniq.item())
+        assert U == len(ru)
+        np.testing.assert_array_equal(hp.uniq[:U].cpu().numpy(), ru)
+        Xu_ref = orc.gather(to_bits(X), ru)
+        assert to_bits(hp.Xu[:U]).tobytes() == Xu_ref.tobytes()
+        T = shb.n_slots
+        wb = weights_bits(W)
+        for b in range(group if group < 10 else 3):
+            for h in range(L + 1):
+                lo = sum(shb.levels[:h])
+                np.testing.assert_array_equal(block(remap_m, b, h), rr[b * T + lo: b * T + lo + shb.levels[h]])
+            outs = orc.forward(Xu_ref, ORC_DT[dt], ref_ids[b], ip, rr[b * T:(b + 1) * T], B, fanouts, wb)
+            assert rel_err(to_f64(out[b * B:(b + 1) * B]), outs[-1][0]) <= TOL[dt] * L
+        # the step-by-step path on the same merged layout gives the same bits
+        outs2 = [torch.empty((B, hidden), dtype=dt, device=DEV) for _ in range(group)]
+        hp.run_group([seeds[b * B:(b + 1) * B] for b in range(group)], keys, outs2)
+        torch.cuda.synchronize()
+        assert to_bits(torch.cat(outs2)).tobytes() == to_bits(out).tobytes()
