@@ -93,6 +93,37 @@ def test_batch_plan_errors_and_layout(lib):
     assert lib.hopgnn_batch_fwd(c.byref(plan), one, keys, 1, one, None) == 1
 
 
+def test_newer_entry_points_reject_bad_arguments(lib):
+    c = ctypes
+    fan = (c.c_int32 * 2)(5, 5)
+    keys = (c.c_uint64 * 2)(1, 2)
+    one = c.c_void_p(8)
+    from paper_2409_00657_amd import binding as hb
+    g = hb._Csr(10, 20, 8, 0, 8)
+    # grouped / merged sampling
+    assert lib.hopgnn_sample_group(None, one, 4, fan, 2, keys, 2, one, None, None, 0, None) == 1
+    assert lib.hopgnn_sample_group(c.byref(g), one, 4, fan, 2, keys, -1, one, None, None, 0, None) == 1
+    assert lib.hopgnn_sample_group(c.byref(g), one, 4, fan, 2, keys, 0, one, None, None, 0, None) == 0   # no batches
+    assert lib.hopgnn_sample_group(c.byref(g), one, 4, fan, 2, None, 2, one, None, None, 0, None) == 1   # no keys
+    assert lib.hopgnn_sample_merged(c.byref(g), one, 8, 0, fan, 2, keys, one, None, None, None) == 1     # seeds_per_key < 1
+    assert lib.hopgnn_sample_merged(c.byref(g), one, 0, 4, fan, 2, keys, one, None, None, None) == 0     # no seeds
+    big = (c.c_int32 * 3)(1000, 1000, 1000)
+    assert lib.hopgnn_sample_merged(c.byref(g), one, 4, 4, big, 3, keys, one, None, None, None) == 3     # 4e9 slots
+    # workspace preparation
+    assert lib.hopgnn_pregather_ws_init(None, 1 << 20, 10, 1000, 0, None) == 1
+    assert lib.hopgnn_pregather_ws_init(one, 1 << 20, 10, 1000, 0, None) == 1          # not 256-byte aligned
+    assert lib.hopgnn_pregather_ws_init(c.c_void_p(256), 16, 10, 1000, 1, None) == 2   # too small
+    # aggregator and layer variants
+    assert lib.hopgnn_sage_fwd_agg(None, 0, 5, 4, None, None, None, 3, None, None, None, 4, 7, 0, None, None, 0,
+                                   None) == 1                                          # unknown aggregator
+    assert lib.hopgnn_gcn_fwd(None, 0, 5, 4, None, None, None, 0, None, None, 4, 1, 0, None, None, 0, None) == 0
+    assert lib.hopgnn_gcn_fwd(None, 0, 5, 4, None, None, None, 3, None, None, 4, 2, 0, None, None, 0, None) == 1
+    assert lib.hopgnn_gat_fwd(None, 0, 5, None, 4, None, None, None, 3, None, None, None, None, 6, 4, 0, None, None,
+                              0, None) == 1                                            # 4 heads do not divide 6
+    assert lib.hopgnn_gat_fwd_ws_bytes(0, 100, 8, 8, 17) == 0
+    assert lib.hopgnn_sage_bwd_ws_bytes(5, 100, 8, 8, 1) == 0
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2409_00657_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
