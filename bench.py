@@ -171,7 +171,7 @@ def main():
             if args.backward:
                 h.backward(b, st)
 
-    by_calls = args.backward or args.model != "sage"
+    by_calls = args.backward
     step = step_calls if by_calls else step_fwd
     for i in range(args.warmup):
         step(i)

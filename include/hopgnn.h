@@ -357,6 +357,12 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *   mark_gather_begin/_end      optional hipEvent_t pair recorded on `stream` around the gather
  *                               launch (NULL: none) so that a harness can time that kernel
  *                               inside its timed region
+ *   layer_kind                  0: GraphSAGE-mean layers (hopgnn_sage_fwd, W_self/W_neigh);
+ *                               1: GCN-style layers (hopgnn_gcn_fwd with W_self as the one weight
+ *                               matrix and norm = gcn_norm); 2: attention layers (hopgnn_gat_fwd
+ *                               with W_self, a_src[k], a_dst[k], gat_heads heads; the first layer
+ *                               projects only the rows the pre-gather found).  sage_ws must be
+ *                               large enough for the chosen layer type's *_ws_bytes.
  *   merge_layers                nonzero: the group's micrographs are sampled as one level-major
  *                               batch (hopgnn_sample_merged, seeds_per_key = n_seeds) and every
  *                               layer is ONE hopgnn_sage_fwd over the whole group instead of one
@@ -402,6 +408,9 @@ typedef struct {
     void *mark_gather_begin, *mark_gather_end;
     int32_t pg_ws_clean;
     int32_t merge_layers;
+    int32_t layer_kind, gcn_norm, gat_heads;
+    const void *a_src[8];
+    const void *a_dst[8];
 } hopgnn_batch_plan;
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,

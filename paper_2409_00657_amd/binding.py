@@ -58,7 +58,9 @@ class BatchPlan(ctypes.Structure):
                 ("pg_ws", ctypes.c_void_p), ("pg_ws_bytes", ctypes.c_size_t),
                 ("sage_ws", ctypes.c_void_p), ("sage_ws_bytes", ctypes.c_size_t),
                 ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p),
-                ("pg_ws_clean", ctypes.c_int32), ("merge_layers", ctypes.c_int32)]
+                ("pg_ws_clean", ctypes.c_int32), ("merge_layers", ctypes.c_int32),
+                ("layer_kind", ctypes.c_int32), ("gcn_norm", ctypes.c_int32), ("gat_heads", ctypes.c_int32),
+                ("a_src", ctypes.c_void_p * 8), ("a_dst", ctypes.c_void_p * 8)]
 
 
 def library_path() -> str:

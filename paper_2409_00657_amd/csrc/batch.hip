@@ -15,6 +15,7 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     const int32_t L = p->n_layers, B = p->n_seeds;
     if (L < 1 || L > kMaxLayers || B < 1) return HOPGNN_EINVAL;
     if ((p->mark_gather_begin == nullptr) != (p->mark_gather_end == nullptr)) return HOPGNN_EINVAL;
+    if (p->layer_kind < 0 || p->layer_kind > 2) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(p->fanouts, L);
     if (t_seed < 0) return HOPGNN_EINVAL;
     int64_t level[kMaxLayers + 1];
@@ -69,10 +70,21 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
             for (int h = 0; h <= L - k; ++h) n_dst += level[h] * rows_scale;
             void* dst = k == L ? (void*)((char*)out + (size_t)b * B * d_last * es) : p->H[k - 1];
             if (dst == nullptr) return HOPGNN_EINVAL;
-            rc = hopgnn_sage_fwd(src, p->dt, n_src, d_in, k == 1 ? rb : nullptr, p->indptr,
-                                 k == 1 ? rb + B_run : p->slot_idx + b * slot_idx_stride, n_dst, p->W_self[k - 1],
-                                 p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], k < L ? 1 : 0, dst, p->sage_ws,
-                                 p->sage_ws_bytes, stream);
+            const int32_t* self_idx = k == 1 ? rb : nullptr;
+            const int32_t* nbr = k == 1 ? rb + B_run : p->slot_idx + b * slot_idx_stride;
+            const int32_t relu = k < L ? 1 : 0;
+            if (p->layer_kind == 0)
+                rc = hopgnn_sage_fwd(src, p->dt, n_src, d_in, self_idx, p->indptr, nbr, n_dst, p->W_self[k - 1],
+                                     p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], relu, dst, p->sage_ws,
+                                     p->sage_ws_bytes, stream);
+            else if (p->layer_kind == 1)
+                rc = hopgnn_gcn_fwd(src, p->dt, n_src, d_in, self_idx, p->indptr, nbr, n_dst, p->W_self[k - 1],
+                                    p->bias[k - 1], p->d_out[k - 1], p->gcn_norm, relu, dst, p->sage_ws, p->sage_ws_bytes,
+                                    stream);
+            else
+                rc = hopgnn_gat_fwd(src, p->dt, n_src, k == 1 ? p->n_uniq : nullptr, d_in, self_idx, p->indptr, nbr,
+                                    n_dst, p->W_self[k - 1], p->a_src[k - 1], p->a_dst[k - 1], p->bias[k - 1],
+                                    p->d_out[k - 1], p->gat_heads, relu, dst, p->sage_ws, p->sage_ws_bytes, stream);
             if (rc != HOPGNN_OK) return rc;
             src = dst;
             n_src = n_dst;

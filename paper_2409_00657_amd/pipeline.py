@@ -86,6 +86,9 @@ class HotPath:
                   for k in range(1, sh.n_layers + 1)]
         ws_bytes = max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0],
                                                    hidden) for k in range(1, sh.n_layers + 1))
+        if model == "gcn":
+            ws_bytes = max(ws_bytes, max(hb.hopgnn_gcn_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0],
+                                                                    hidden) for k in range(1, sh.n_layers + 1)))
         if model == "gat":
             self.attn = [(synth.weight(1, hidden, X.dtype, 200 + 2 * k, device=dev).view(-1),
                           synth.weight(1, hidden, X.dtype, 201 + 2 * k, device=dev).view(-1))
@@ -155,6 +158,11 @@ class HotPath:
             pl.H[i] = self.H[i].data_ptr()
         pl.pg_algo, pl.group = self.pg_algo, self.n_keys
         pl.merge_layers = 1 if self.merge else 0
+        pl.layer_kind = {"sage": 0, "gcn": 1, "gat": 2}[self.model]
+        pl.gcn_norm, pl.gat_heads = 1, self.gat_heads
+        if self.model == "gat":
+            for i, (a_s, a_d) in enumerate(self.attn):
+                pl.a_src[i], pl.a_dst[i] = a_s.data_ptr(), a_d.data_ptr()
         pl.ids, pl.indptr, pl.slot_idx = ids, self.indptr.data_ptr(), self._slot_idx_all.data_ptr()
         pl.uniq, pl.uniq_capacity, pl.n_uniq = self.uniq.data_ptr(), self.cap, self.n_uniq.data_ptr()
         pl.remap, pl.Xu = remap, self.Xu.data_ptr()
@@ -292,8 +300,6 @@ class HotPath:
         """The whole group in ONE library call (hopgnn_batch_fwd): `seeds` holds the group's
         seeds back to back, `out` [group*B, hidden] receives every batch's last-layer rows.
         `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
-        if self.model != "sage":
-            raise hb.HopgnnError("hopgnn_batch_fwd runs GraphSAGE-mean layers; use run_batch/run_group")
         n = len(keys)
         if seeds.numel() != n * self.seeds_per_key or seeds.dtype != torch.int32 or not seeds.is_cuda:
             raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.seeds_per_key))

@@ -169,3 +169,55 @@ def test_layer_argument_errors(hb):
     with pytest.raises(hb.HopgnnError):          # workspace too small
         hb.hopgnn_gat_fwd(H, 4, None, ip, ip, 4, W, W[0], W[0], None, 2, False, out, ws[:256])
     assert hb.hopgnn_gat_fwd_ws_bytes(torch.float32, 4, 8, 8, 3) == 0
+
+
+@pytest.mark.parametrize("model", ["gcn", "gat"])
+@pytest.mark.parametrize("merge", [False, True])
+def test_layer_kinds_through_the_single_call_path(hb, orc, model, merge):
+    """hopgnn_batch_fwd with GCN-style / attention layers: the same bits as the step-by-step
+    sequence, and the last layer's rows against the oracle's chain of that layer type."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    cfg = synth.CONFIGS[1]
+    g = cfg.make_graph(device=DEV)
+    X = cfg.make_features(device=DEV)
+    W = cfg.make_weights(device=DEV)
+    G, B, L = 3, cfg.batch, len(cfg.fanouts)
+    hp = HotPath(g.offsets, g.indices, X, W, B, cfg.fanouts, group=G, model=model, merge=merge)
+    seeds = synth.seeds(cfg.n_vertices, B * G, 21, device=DEV)
+    keys = [5, 6, 7]
+    out = torch.full((G * B, cfg.hidden), float("nan"), device=DEV)
+    hp.forward(seeds, keys, out)
+    torch.cuda.synchronize()
+    outs2 = [torch.empty((B, cfg.hidden), device=DEV) for _ in range(G)]
+    hp.run_group([seeds[b * B:(b + 1) * B] for b in range(G)], keys, outs2)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat(outs2), out)
+    # oracle: per batch, chain the layer type over the batch's own slot arrays
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    ref_ids = [orc.sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), cfg.fanouts, keys[b]) for b in range(G)]
+    ru, rr = orc.pregather(np.concatenate([i for i, _ in ref_ids]))
+    Xu = orc.gather(to_bits(X), ru)
+    T = len(ref_ids[0][0])
+    from paper_2409_00657_amd.pipeline import BatchShape
+    shb = BatchShape(B, list(cfg.fanouts))
+    for b in range(G):
+        ids_b, ip = ref_ids[b]
+        remap_b = rr[b * T:(b + 1) * T]
+        H = Xu
+        for k in range(1, L + 1):
+            n_dst, nnz = shb.n_dst(k), shb.nnz(k)
+            if k == 1:
+                self_idx, idx = remap_b[:n_dst], remap_b[B:B + nnz]
+            else:
+                e = np.arange(nnz, dtype=np.int32)
+                self_idx, idx = None, np.where(ids_b[B:B + nnz] >= 0, B + e, -1).astype(np.int32)
+            Wk = to_bits(W[k - 1][0])
+            if model == "gcn":
+                o = orc.gcn_fwd(H, 0, self_idx, ip[:n_dst + 1], idx, Wk, None, 1, k < L)
+            else:
+                a_s, a_d = hp.attn[k - 1]
+                o = orc.gat_fwd(H, 0, self_idx, ip[:n_dst + 1], idx, Wk, to_bits(a_s), to_bits(a_d), None, hp.gat_heads,
+                                k < L)
+            H = orc.round_store(o, 0)
+        assert rel_err(to_f64(out[b * B:(b + 1) * B]), o) <= 2e-5, (model, merge, b)
