@@ -30,21 +30,16 @@ constexpr int kPgThreads = 256;
 constexpr int kWordsPerThread = 4;                              // one 128-bit load
 constexpr int kWordsPerBlock = kPgThreads * kWordsPerThread;    // 1024 words = 32768 vertices
 
-// Same-address atomics retire one every ~40 ns, so a single "who is last" counter drawn by a
-// thousand workgroups costs 40 us.  The workgroups draw from per-group counters instead (groups of
-// kTicketGroup, each counter on its own line) and only the last of each group draws from the top one.
-constexpr int kTicketGroup = 32;
 constexpr int kMaxPackGrid = 1024;
-constexpr int kTicketChunks = 64;      // up to this many chunks (2 M vertices) the packing pass scans its own counts
-constexpr int kTicketLines = 1 + kMaxPackGrid / kTicketGroup;   // 33
-constexpr int kTicketStride = 32;                                // uint32 per 128-byte line
+// Up to this many chunks (2 M vertices) the packing pass scans its own chunk counts ("last
+// workgroup to finish"); beyond it the scan is a launch of its own, see bitmap_scan_sums.
+constexpr int kTicketChunks = 64;
 
 struct BitmapWs {
     uint8_t* present;      // [32 * n_words_padded] one byte per vertex
     uint2* word_rank;      // [n_words_padded] (bits, rank of the word's first set bit inside its chunk)
     uint32_t* block_sum;   // [n_blocks] set bits per 1024-word chunk, then their exclusive prefix sum
-    uint32_t* ticket;      // two-level "workgroups finished" counters, one per 128-byte line:
-                           // line 0 counts finished groups, line 1+g the finished workgroups of group g
+    uint32_t* ticket;      // [1] workgroups that finished counting (small inputs only, see kTicketChunks)
     size_t bytes;
     int64_t n_words_padded;
     int64_t n_blocks;
@@ -64,7 +59,7 @@ static BitmapWs bitmap_layout(void* ws, int64_t n_vertices) {
     L.block_sum = reinterpret_cast<uint32_t*>(p + o);
     o += align_up((size_t)L.n_blocks * 4, 256);
     L.ticket = reinterpret_cast<uint32_t*>(p + o);
-    o += kTicketLines * 128;
+    o += 256;
     L.bytes = o;
     return L;
 }
@@ -74,9 +69,9 @@ present_clear(uint4* __restrict__ present16, int64_t n_vec, uint32_t* ticket, in
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += stride)
         present16[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (blockIdx.x == 0) {
-        for (int i = threadIdx.x; i < kTicketLines; i += blockDim.x) ticket[i * kTicketStride] = 0u;
-        if (threadIdx.x == 0 && n_uniq != nullptr) *n_uniq = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *ticket = 0u;
+        if (n_uniq != nullptr) *n_uniq = 0;
     }
 }
 
@@ -194,15 +189,8 @@ bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, 
     }
     if (!TICKET) return;      // the chunk counts are scanned by a launch of their own
     if (threadIdx.x == 0) {
-        const uint32_t group = blockIdx.x / kTicketGroup, n_groups = (gridDim.x + kTicketGroup - 1) / kTicketGroup;
-        const uint32_t group_size = group + 1 < n_groups ? kTicketGroup : gridDim.x - group * kTicketGroup;
         __threadfence();
-        bool last = atomicAdd(&ticket[(1 + group) * kTicketStride], 1u) == group_size - 1;
-        if (last) {
-            __threadfence();
-            last = atomicAdd(&ticket[0], 1u) == n_groups - 1;
-        }
-        is_last = last;
+        is_last = atomicAdd(ticket, 1u) == gridDim.x - 1;
     }
     __syncthreads();
     if (!is_last) return;
@@ -218,9 +206,10 @@ bitmap_pack_count(uint4* __restrict__ present16, uint2* __restrict__ word_rank, 
         if (b < n_blocks) block_sum[b] = carry + ex;
         carry += tot;
     }
-    if (threadIdx.x == 0) *n_uniq = (int64_t)carry;
-    if (UNMARK)
-        for (int i = threadIdx.x; i < kTicketLines; i += kPgThreads) ticket[i * kTicketStride] = 0u;
+    if (threadIdx.x == 0) {
+        *n_uniq = (int64_t)carry;
+        if (UNMARK) *ticket = 0u;
+    }
 }
 
 // The scan of the chunk counts as a launch of its own (one workgroup): exclusive prefix in place,
@@ -742,7 +731,7 @@ static SplitWs split_layout(void* ws, int64_t n_uniq) {
     L.sums = reinterpret_cast<uint32_t*>(p + o);
     o += align_up((size_t)ceil_div(n, kWordsPerBlock) * 4, 256);
     L.ticket = reinterpret_cast<uint32_t*>(p + o);
-    o += kTicketLines * 128;
+    o += 256;
     L.bytes = o;
     return L;
 }
