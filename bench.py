@@ -45,7 +45,8 @@ def parse():
     ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams (each with its own buffers) that consecutive steps alternate over")
     ap.add_argument("--backward", action="store_true",
-                    help="also run the layers' backward pass with in-place gradient accumulation")
+                    help="training steps: the layers' backward pass with in-place gradient accumulation and one "
+                         "SGD update per step")
     ap.add_argument("--model", choices=["sage", "gcn", "gat"], default="sage",
                     help="layer type: GraphSAGE-mean (the headline workload), GCN-style mean, graph attention")
     ap.add_argument("--no-merge", action="store_true",
@@ -129,8 +130,11 @@ def main():
         print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
         sys.exit(2)
     merge = group > 1 and not args.no_merge and not args.backward
-    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, model=args.model, merge=merge)
-           for _ in range(n_streams)]
+    # training steps update the weights: every stream is then a worker with its own replica
+    Ws = [W] + [[tuple(None if t is None else t.clone() for t in layer) for layer in W]
+                for _ in range(n_streams - 1)] if args.backward else [W] * n_streams
+    hps = [HotPath(g.offsets, g.indices, X, Ws[j], cfg.batch, cfg.fanouts, group=group, model=args.model, merge=merge)
+           for j in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]      # default priority
     if args.backward:
         for h in hps:
@@ -170,6 +174,8 @@ def main():
             h.layers(b, st)
             if args.backward:
                 h.backward(b, st)
+        if args.backward:       # end of the iteration: update from the accumulated gradients, clear them
+            h.apply_sgd(1e-4, st)
 
     by_calls = args.backward
     step = step_calls if by_calls else step_fwd

@@ -417,6 +417,16 @@ hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int
                                const uint64_t *keys /*HOST*/, int32_t n_batches, void *out, void *stream);
 
 /*
+ * End of an iteration (paper section 5.1, step 5, and the discussion: the accumulated partial
+ * gradients are cleared at the end of each iteration).  The optimiser is not named; reading:
+ * plain SGD.  W[i] <- W[i] - lr * grad[i], computed in fp32 and rounded once to W's type; with
+ * zero_grad != 0 the accumulator is cleared in the same pass.
+ * W DEVICE [n] of type dt (in/out), grad DEVICE [n] fp32 (in, cleared if asked).
+ */
+hopgnn_status hopgnn_sgd_update(void *W, hopgnn_dtype dt, float *grad, int64_t n, float lr, int32_t zero_grad,
+                                void *stream);
+
+/*
  * Micrograph merging (paper section 5.3).  HOST-only bookkeeping, no device work.
  *
  * counts is a HOST matrix [n_models x n_steps], row-major: root vertices model m trains at

@@ -318,6 +318,14 @@ def sage_bwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, out_fwd, relu,
     return gWs, gWn, gb, dH
 
 
+def sgd_update(W, dtype, grad, lr):
+    """End of an iteration (paper section 5.1, step 5: the model parameters are updated from the
+    accumulated, synchronised gradients; the optimiser is not named - reading: plain SGD):
+    W <- W - lr * grad in float64, rounded once to W's storage dtype.  Returns the new W bits."""
+    w = load_f64(W, dtype)
+    return round_store(w - float(lr) * np.asarray(grad, np.float64).reshape(w.shape), dtype)
+
+
 def forward(X_rows, dtype, ids, indptr, remap, n_seeds, fanouts, weights):
     """All L layers of one batch on top of its gathered rows.
 

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sgd_update", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -122,6 +122,8 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_sgd_update.restype = c.c_int
+    L.hopgnn_sgd_update.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_int64, c.c_float, c.c_int32, c.c_void_p]
     L.hopgnn_sample_merged.restype = c.c_int
     L.hopgnn_sample_merged.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.c_int32, c.POINTER(c.c_int32),
                                        c.c_int32, c.POINTER(c.c_uint64), c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -388,3 +390,11 @@ def hopgnn_sage_fwd_agg(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch
                                             1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(),
                                             _stream())
     _check(rc, "hopgnn_sage_fwd_agg")
+
+
+def hopgnn_sgd_update(W: torch.Tensor, grad: torch.Tensor, lr: float, zero_grad: bool = True, stream=None) -> None:
+    if grad.dtype != torch.float32 or grad.numel() != W.numel():
+        raise HopgnnError("grad must be fp32 with as many elements as W")
+    st = _stream() if stream is None else stream
+    _check(load_library().hopgnn_sgd_update(_ptr(W), DTYPE_OF[W.dtype], _ptr(grad), W.numel(), lr,
+                                            1 if zero_grad else 0, st), "hopgnn_sgd_update")

@@ -397,6 +397,19 @@ bwd_scatter(const float* __restrict__ D, const int32_t* __restrict__ self_idx, c
     }
 }
 
+// ---------------------------------------------------------------- update --
+
+// W <- W - lr * grad (fp32 arithmetic, one rounding to the stored type), optionally grad <- 0.
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+sgd_update(typename Tr::store_t* __restrict__ W, float* __restrict__ grad, int64_t n, float lr, int zero_grad) {
+    const int64_t stride = (int64_t)gridDim.x * kBwdThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x; i < n; i += stride) {
+        W[i] = Tr::from_f(Tr::to_f(W[i]) - lr * grad[i]);
+        if (zero_grad) grad[i] = 0.f;
+    }
+}
+
 // ------------------------------------------------------------------ host --
 
 struct BwdWs {
@@ -541,4 +554,25 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
                                       dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
     return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
                                  d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+}
+
+extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,
+                                           void* stream) {
+    if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
+    if (n < 0) return HOPGNN_EINVAL;
+    if (n == 0) return HOPGNN_OK;
+    if (W == nullptr || grad == nullptr) return HOPGNN_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t want = ceil_div(n, kBwdThreads);
+    const dim3 grid((unsigned)(want < 4096 ? want : 4096));
+    if (dt == HOPGNN_F32)
+        hipLaunchKernelGGL(sgd_update<TrF32>, grid, dim3(kBwdThreads), 0, s, static_cast<float*>(W), grad, n, lr, zero_grad);
+    else if (dt == HOPGNN_BF16)
+        hipLaunchKernelGGL(sgd_update<TrBF16>, grid, dim3(kBwdThreads), 0, s, static_cast<uint16_t*>(W), grad, n, lr,
+                           zero_grad);
+    else
+        hipLaunchKernelGGL(sgd_update<TrF16>, grid, dim3(kBwdThreads), 0, s, static_cast<_Float16*>(W), grad, n, lr,
+                           zero_grad);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }

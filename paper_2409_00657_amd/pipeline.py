@@ -285,6 +285,16 @@ class HotPath:
             if rc:
                 hb._check(rc, "hopgnn_sage_bwd")
 
+    def apply_sgd(self, lr: float, stream=None) -> None:
+        """End of an iteration: every weight matrix (and bias) takes its accumulated gradient,
+        W <- W - lr * gW, and the accumulators are cleared."""
+        st = self._stream(stream)
+        for (Ws, Wn, b), (gWs, gWn, gb) in zip(self.weights, self.gW):
+            hb.hopgnn_sgd_update(Ws, gWs, lr, True, st)
+            hb.hopgnn_sgd_update(Wn, gWn, lr, True, st)
+            if b is not None:
+                hb.hopgnn_sgd_update(b, gb, lr, True, st)
+
     # -- whole steps ---------------------------------------------------------
 
     def run_batch(self, seeds: torch.Tensor, key: int, stream=None) -> torch.Tensor:

@@ -177,3 +177,55 @@ def test_sage_bwd_rejects_identity_self_without_rows(hb):
     with pytest.raises(hb.HopgnnError):     # 6 destination rows with identity self, but only 4 source rows
         hb.hopgnn_sage_bwd(H, 4, None, ip, ip, 6, W, W, None, False, torch.zeros((6, 8), device=DEV), z, z, None,
                            None, ws)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16, torch.float16])
+def test_sgd_update_vs_oracle(hb, orc, dt):
+    from helpers import ORC_DT
+    rng = np.random.default_rng(5)
+    for n in (1, 7, 1000, 100_003):
+        W = torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(dt).to(DEV)
+        g = torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(DEV)
+        ref = orc.sgd_update(to_bits(W), ORC_DT[dt], g.cpu().numpy(), 0.05)
+        hb.hopgnn_sgd_update(W, g, 0.05, True)
+        torch.cuda.synchronize()
+        got = to_f64(W)
+        want = orc.load_f64(ref, ORC_DT[dt])
+        # fp32 arithmetic against fp64, then one rounding: within a place or so of the stored
+        # type at the size of the operands (W and lr*g are O(1); their difference may be tiny)
+        if dt == torch.float32:
+            assert np.max(np.abs(got - want)) <= 1e-6
+        else:
+            assert np.max(np.abs(got - want) / np.maximum(np.abs(want), 0.05)) <= 2.0 ** -7
+        assert float(g.abs().max().item()) == 0.0
+    W0 = torch.ones(33, dtype=dt, device=DEV)
+    hb.hopgnn_sgd_update(W0, torch.ones(33, device=DEV), 0.25, False)
+    torch.cuda.synchronize()
+    assert torch.equal(W0, torch.full((33,), 0.75, dtype=dt, device=DEV))
+
+
+def test_training_iterations_lower_the_loss(hb):
+    """Forward, backward with accumulation over two batches, one SGD update per iteration: the loss
+    1/2 |H_L|^2 of a fixed pair of batches falls from iteration to iteration."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    cfg = synth.CONFIGS[1]
+    g = cfg.make_graph(device=DEV)
+    X = cfg.make_features(device=DEV)
+    W = cfg.make_weights(device=DEV)
+    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts)
+    hp.enable_backward()
+    batches = [(synth.seeds(cfg.n_vertices, cfg.batch, s, device=DEV), s) for s in (3, 4)]
+    losses = []
+    for it in range(6):
+        loss = 0.0
+        for seeds, key in batches:            # gradients of both batches accumulate in place
+            out = hp.run_batch(seeds, key)
+            loss += 0.5 * float((out.double() ** 2).sum().item())
+            hp.backward(0)
+        losses.append(loss)
+        hp.apply_sgd(3e-4)
+        torch.cuda.synchronize()
+        assert all(float(gw.abs().max().item()) == 0.0 for gw in hp.gW[0][:2])
+    assert all(b < a for a, b in zip(losses, losses[1:])), losses
+    assert losses[-1] < 0.8 * losses[0], losses

@@ -92,3 +92,19 @@ def test_special_cases(orc):
     np.testing.assert_allclose(gb, G[0] * mask)
     np.testing.assert_allclose(gWs, np.outer(H[0], G[0] * mask))
     # accumulation: calling twice on the same accumulators doubles them (checked via the C entry)
+
+
+def test_sgd_update_closed_cases(orc):
+    """W - lr g: exact small cases in every storage type, identity for lr = 0 or g = 0."""
+    import numpy as np
+    for dt, one, three_q in ((0, np.float32(1.0), np.float32(0.75)), (1, np.uint16(0x3F80), np.uint16(0x3F40)),
+                             (2, np.uint16(0x3C00), np.uint16(0x3A00))):
+        W = np.full((2, 3), one)
+        g = np.ones((2, 3))
+        np.testing.assert_array_equal(orc.sgd_update(W, dt, g, 0.25), np.full((2, 3), three_q))
+        np.testing.assert_array_equal(orc.sgd_update(W, dt, g, 0.0), W)
+        np.testing.assert_array_equal(orc.sgd_update(W, dt, np.zeros((2, 3)), 0.3), W)
+    rng = np.random.default_rng(0)
+    W = rng.standard_normal((5, 4)).astype(np.float32)
+    g = rng.standard_normal((5, 4))
+    np.testing.assert_allclose(orc.sgd_update(W, 0, g, 0.01), W - 0.01 * g, rtol=1e-7)
