@@ -147,6 +147,43 @@ hopgnn_status hopgnn_sample_group(const hopgnn_csr *g /*HOST struct*/, const int
 size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo);
 
 /*
+ * k-hop sampling with per-micrograph deduplicated frontiers (paper section 4: a micrograph is the
+ * set of vertices its sampling reaches, counted once each).  The same draws as hopgnn_sample - the
+ * children of a vertex depend only on (key, root, vertex, hop, j), so equal vertices at one level of
+ * one micrograph carry identical subtrees in the slot tree - but every (level, vertex) pair of a
+ * micrograph is kept once, so the layers run over fewer rows and give the same rows for the roots.
+ *
+ * Nodes are numbered level-major: level 0 of every micrograph (the roots, in seed order), then level
+ * 1 of every micrograph, ...; inside one micrograph's level the vertices ascend.
+ *   node_vertex DEVICE out [T]     vertex of every node; entries past the node count are -1
+ *                                  (T = n_seeds * hopgnn_slots_per_seed: the slot tree's size is the
+ *                                  capacity), so the array can go to hopgnn_pregather as it is
+ *   level_start DEVICE out int64 [n_layers + 2]   first node of level h; [n_layers + 1] = node count.
+ *                                  Layer k (1-based) has level_start[n_layers - k + 1] destination rows
+ *                                  (the nodes of levels 0 .. n_layers - k): pass its address as
+ *                                  n_dst_dev of hopgnn_sage_fwd_dev
+ *   indptr      DEVICE out [S + 1] S = T minus the last level; segment of node i = its children in
+ *                                  draw order (fanout many, parallel edges kept); entries past the
+ *                                  non-leaf node count equal the total, i.e. empty segments
+ *   idx         DEVICE out [T - n_seeds]   child NODE index or -1 (the vertex has no neighbours);
+ *                                  entries past the total are -1
+ *   ws          DEVICE scratch, hopgnn_sample_dedup_ws_bytes, 256-byte aligned
+ * One level of one micrograph may hold at most 4096 slots (product of the fanouts), else
+ * HOPGNN_ERANGE.  Other errors as hopgnn_sample.
+ *
+ * hopgnn_compose_idx: out[e] = idx[e] >= 0 ? map[idx[e]] : -1 - the first layer reads the
+ * pre-gathered rows, so its neighbour list is the node list's remap applied to the child indices.
+ */
+size_t hopgnn_sample_dedup_ws_bytes(int32_t n_seeds, const int32_t *fanouts /*HOST*/, int32_t n_layers);
+
+hopgnn_status hopgnn_sample_dedup(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
+                                  const int32_t *fanouts /*HOST*/, int32_t n_layers, uint64_t key,
+                                  int32_t *node_vertex, int64_t *level_start, int32_t *indptr, int32_t *idx,
+                                  void *ws, size_t ws_bytes, void *stream);
+
+hopgnn_status hopgnn_compose_idx(const int32_t *idx, int64_t n, const int32_t *map, int32_t *out, void *stream);
+
+/*
  * Prepares a pre-gather workspace once (zero presence map and counters; sizes and algo as in
  * hopgnn_pregather_ws_bytes).  hopgnn_pregather itself does not need it - it clears what it uses
  * - but every call of it, and every hopgnn_batch_fwd, leaves the workspace as this call does, so
@@ -252,6 +289,18 @@ hopgnn_status hopgnn_sage_fwd_agg(const void *Hsrc, hopgnn_dtype dt, int64_t n_s
                                   int64_t n_dst, const void *W_self, const void *W_neigh, const void *bias,
                                   int32_t d_out, int32_t agg, int32_t relu, void *out, void *ws,
                                   size_t ws_bytes, void *stream);
+
+/*
+ * hopgnn_sage_fwd_agg for a row count that only the device knows: n_dst is the capacity the launch
+ * is sized for and *n_dst_dev (DEVICE, NULL = n_dst) the number of destination rows that exist;
+ * rows past it are neither read nor written.  Used with hopgnn_sample_dedup, whose level sizes
+ * depend on the data.  The identity-self check (n_src >= n_dst) applies to the capacity.
+ */
+hopgnn_status hopgnn_sage_fwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                  const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                                  int64_t n_dst, const int64_t *n_dst_dev, const void *W_self,
+                                  const void *W_neigh, const void *bias, int32_t d_out, int32_t agg,
+                                  int32_t relu, void *out, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * The other two layer types the paper's evaluation trains (experimental setup: GCN, GraphSAGE,

@@ -27,7 +27,8 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sgd_update", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
+           "hopgnn_compose_idx", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -122,6 +123,18 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_merge_ctl_init.argtypes = [c.POINTER(MergeCtl), c.c_int32]
     L.hopgnn_merge_ctl_report.restype = c.c_int32
     L.hopgnn_merge_ctl_report.argtypes = [c.POINTER(MergeCtl), c.c_double]
+    L.hopgnn_sage_fwd_dev.restype = c.c_int
+    L.hopgnn_sage_fwd_dev.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                      c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_sample_dedup_ws_bytes.restype = c.c_size_t
+    L.hopgnn_sample_dedup_ws_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int32), c.c_int32]
+    L.hopgnn_sample_dedup.restype = c.c_int
+    L.hopgnn_sample_dedup.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
+                                      c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_size_t, c.c_void_p]
+    L.hopgnn_compose_idx.restype = c.c_int
+    L.hopgnn_compose_idx.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p]
     L.hopgnn_sgd_update.restype = c.c_int
     L.hopgnn_sgd_update.argtypes = [c.c_void_p, c.c_int, c.c_void_p, c.c_int64, c.c_float, c.c_int32, c.c_void_p]
     L.hopgnn_sample_merged.restype = c.c_int
@@ -398,3 +411,40 @@ def hopgnn_sgd_update(W: torch.Tensor, grad: torch.Tensor, lr: float, zero_grad:
     st = _stream() if stream is None else stream
     _check(load_library().hopgnn_sgd_update(_ptr(W), DTYPE_OF[W.dtype], _ptr(grad), W.numel(), lr,
                                             1 if zero_grad else 0, st), "hopgnn_sgd_update")
+
+
+def hopgnn_sample_dedup_ws_bytes(n_seeds: int, fanouts: Sequence[int]) -> int:
+    return int(load_library().hopgnn_sample_dedup_ws_bytes(n_seeds, _fan(fanouts), len(fanouts)))
+
+
+def hopgnn_sample_dedup(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
+                        key: int, node_vertex: torch.Tensor, level_start: torch.Tensor, indptr: torch.Tensor,
+                        idx: torch.Tensor, ws: torch.Tensor) -> None:
+    g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
+             1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+    if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
+        raise HopgnnError("offsets must be int32/int64 and indices int32")
+    if level_start.dtype != torch.int64 or level_start.numel() < len(fanouts) + 2:
+        raise HopgnnError("level_start must hold n_layers + 2 int64 values")
+    rc = load_library().hopgnn_sample_dedup(ctypes.byref(g), _ptr(seeds), seeds.numel(), _fan(fanouts), len(fanouts),
+                                            ctypes.c_uint64(key & 0xFFFFFFFFFFFFFFFF), _ptr(node_vertex),
+                                            _ptr(level_start), _ptr(indptr), _ptr(idx), _ptr(ws),
+                                            ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_sample_dedup")
+
+
+def hopgnn_compose_idx(idx: torch.Tensor, map_: torch.Tensor, out: torch.Tensor) -> None:
+    _check(load_library().hopgnn_compose_idx(_ptr(idx), idx.numel(), _ptr(map_), _ptr(out), _stream()),
+           "hopgnn_compose_idx")
+
+
+def hopgnn_sage_fwd_dev(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                        idx: torch.Tensor, n_dst: int, n_dst_dev: Optional[torch.Tensor], W_self: torch.Tensor,
+                        W_neigh: torch.Tensor, bias: Optional[torch.Tensor], agg: int, relu: bool, out: torch.Tensor,
+                        ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_fwd_dev(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                            _ptr(idx), n_dst, _ptr(n_dst_dev), _ptr(W_self), _ptr(W_neigh), _ptr(bias),
+                                            d_out, agg, 1 if relu else 0, _ptr(out), _ptr(ws),
+                                            ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_sage_fwd_dev")

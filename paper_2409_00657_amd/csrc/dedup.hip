@@ -1,0 +1,331 @@
+// hopgnn_sample_dedup: k-hop sampling with per-micrograph deduplicated frontiers.
+//
+// A micrograph is the set of vertices its sampling reaches (paper section 4, "micrograph
+// definition", which counts distinct vertices).  The children a vertex draws depend only on
+// (key, root, vertex, hop, j), so equal vertices at one level of one micrograph carry identical
+// subtrees in the slot tree of hopgnn_sample; here every (level, vertex) pair of a micrograph is
+// kept once.  The rows computed for the roots are the same, over fewer rows below them (on
+// power-law graphs with replacement about half the valid slots of a level are repeats).
+//
+//   dedup_sample   one workgroup per micrograph: per hop it draws the children of the current
+//                  distinct vertices into LDS, sorts them (bitonic, in LDS), keeps the distinct ones
+//                  in ascending order and finds every child's position by binary search; node lists
+//                  and child positions go to per-micrograph staging slices of slot-tree capacity
+//   dedup_scan     exclusive sums of the per-micrograph node counts, level by level
+//   dedup_compact  level-major global numbering: node vertices, CSR of child node indices
+//                  (parallel edges kept, -1 where a vertex has no neighbours), unused tails filled
+#include "common.hpp"
+
+namespace hopgnn {
+
+constexpr int kDdThreads = 256;
+constexpr int kDdMaxLevel = 4096;      // most slots one micrograph may have at one level
+constexpr uint32_t kDdNone = 0xFFFFFFFFu;
+
+struct DedupShape {
+    int32_t n_layers;
+    int32_t f[kMaxLayers + 1];      // f[h], h = 1..L
+    int32_t P[kMaxLayers + 1];      // slot-tree slots per micrograph at level h
+    int32_t base[kMaxLayers + 2];   // first slot of level h in the slot-tree layout; base[L+1] = T
+};
+
+__device__ __forceinline__ uint64_t dd_finalise64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Exclusive prefix sum of one value per thread over the 256-thread workgroup; `total` = their sum.
+__device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, uint32_t& total) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    uint32_t inc = x;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t y = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += y;
+    }
+    if (lane == kWave - 1) lds4[wave] = inc;
+    __syncthreads();
+    uint32_t wave_base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kDdThreads / kWave; ++w) {
+        const uint32_t s = lds4[w];
+        if (w < wave) wave_base += s;
+        tot += s;
+    }
+    __syncthreads();
+    total = tot;
+    return wave_base + inc - x;
+}
+
+template <typename OffT>
+__global__ void __launch_bounds__(kDdThreads)
+dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices, const int32_t* __restrict__ seeds,
+             int32_t n_seeds, DedupShape sh, uint64_t keyed, int32_t* __restrict__ stage_nodes,
+             int32_t* __restrict__ stage_child, int32_t* __restrict__ cnt) {
+    __shared__ uint32_t cur[kDdMaxLevel];     // distinct vertices of the current level, ascending
+    __shared__ uint32_t ent[kDdMaxLevel];     // children in draw order (kDdNone: none)
+    __shared__ uint32_t srt[kDdMaxLevel];     // the same, sorted; then the distinct ones packed in front
+    __shared__ uint32_t lds4[kDdThreads / kWave];
+    __shared__ uint32_t n_next_s;
+    const int32_t m = blockIdx.x, B = n_seeds;
+    const int tid = threadIdx.x;
+    const int32_t root = seeds[m];
+    if (tid == 0) {
+        cur[0] = (uint32_t)root;
+        stage_nodes[m] = root;
+        cnt[m] = 1;
+    }
+    __syncthreads();
+    uint32_t n_cur = 1;
+    for (int32_t h = 1; h <= sh.n_layers; ++h) {
+        const uint32_t f = (uint32_t)sh.f[h];
+        const uint32_t n_cand = n_cur * f;
+        uint32_t n2 = 1;
+        while (n2 < n_cand) n2 <<= 1;
+        // draw: entry c = (node q, draw j)
+        for (uint32_t c = tid; c < n2; c += kDdThreads) {
+            uint32_t child = kDdNone;
+            if (c < n_cand) {
+                const uint32_t q = c / f, j = c - q * f;
+                const int32_t v = (int32_t)cur[q];
+                if (v >= 0) {
+                    const int64_t o0 = (int64_t)offsets[v];
+                    const int64_t deg = (int64_t)offsets[(int64_t)v + 1] - o0;
+                    if (deg > 0) {
+                        uint64_t x = dd_finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v)) +
+                                                   0x9E3779B97F4A7C15ull);
+                        x = dd_finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
+                        child = (uint32_t)indices[o0 + (int64_t)(x % (uint64_t)deg)];
+                    }
+                }
+                ent[c] = child;
+            }
+            srt[c] = child;
+        }
+        __syncthreads();
+        // ascending bitonic sort of srt[0, n2)  (kDdNone sorts last)
+        for (uint32_t k = 2; k <= n2; k <<= 1)
+            for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+                for (uint32_t i = tid; i < n2; i += kDdThreads) {
+                    const uint32_t p = i ^ j;
+                    if (p > i) {
+                        const uint32_t a = srt[i], b = srt[p];
+                        if ((a > b) == ((i & k) == 0)) {
+                            srt[i] = b;
+                            srt[p] = a;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        // distinct values, packed in order into cur (the next level's node list)
+        uint32_t carry = 0;
+        for (uint32_t i0 = 0; i0 < n2; i0 += kDdThreads) {
+            const uint32_t i = i0 + tid;
+            const uint32_t v = i < n2 ? srt[i] : kDdNone;
+            const uint32_t head = (v != kDdNone && (i == 0 || srt[i - 1] != v)) ? 1u : 0u;
+            uint32_t total;
+            const uint32_t pos = carry + dd_block_scan(head, lds4, total);
+            if (head) cur[pos] = v;        // cur is free: every draw of this hop has been made
+            carry += total;
+        }
+        if (tid == 0) n_next_s = carry;
+        __syncthreads();
+        const uint32_t n_next = n_next_s;
+        // this micrograph's slices of the staging arrays (slot-tree capacity)
+        int32_t* nodes_out = stage_nodes + sh.base[h] + (int64_t)m * sh.P[h];
+        int32_t* child_out = stage_child + (sh.base[h] - B) + (int64_t)m * sh.P[h];
+        for (uint32_t i = tid; i < n_next; i += kDdThreads) nodes_out[i] = (int32_t)cur[i];
+        for (uint32_t c = tid; c < n_cand; c += kDdThreads) {
+            const uint32_t child = ent[c];
+            int32_t pos = -1;
+            if (child != kDdNone) {          // lower bound in cur[0, n_next): the value is there
+                uint32_t lo = 0, hi = n_next;
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (cur[mid] < child) lo = mid + 1;
+                    else hi = mid;
+                }
+                pos = (int32_t)lo;
+            }
+            child_out[c] = pos;
+        }
+        if (tid == 0) cnt[(int64_t)h * B + m] = (int32_t)n_next;
+        __syncthreads();
+        n_cur = n_next;
+    }
+}
+
+// One workgroup: per level the exclusive sums of the micrographs' node counts, the first node of
+// every level and the first entry of every level's nodes.
+__global__ void __launch_bounds__(kDdThreads)
+dedup_scan(const int32_t* __restrict__ cnt, int32_t n_seeds, DedupShape sh, int32_t* __restrict__ mg_off,
+           int64_t* __restrict__ level_start, int64_t* __restrict__ ent_start) {
+    __shared__ uint32_t lds4[kDdThreads / kWave];
+    int64_t nodes = 0, ents = 0;
+    for (int32_t h = 0; h <= sh.n_layers; ++h) {
+        if (threadIdx.x == 0) {
+            level_start[h] = nodes;
+            ent_start[h] = ents;
+        }
+        uint32_t carry = 0;
+        for (int32_t m0 = 0; m0 < n_seeds; m0 += kDdThreads) {
+            const int32_t mm = m0 + threadIdx.x;
+            const uint32_t x = mm < n_seeds ? (uint32_t)cnt[(int64_t)h * n_seeds + mm] : 0u;
+            uint32_t total;
+            const uint32_t ex = dd_block_scan(x, lds4, total);
+            if (mm < n_seeds) mg_off[(int64_t)h * n_seeds + mm] = (int32_t)(carry + ex);
+            carry += total;
+        }
+        nodes += carry;
+        if (h < sh.n_layers) ents += (int64_t)carry * sh.f[h + 1];
+    }
+    if (threadIdx.x == 0) {
+        level_start[sh.n_layers + 1] = nodes;
+        ent_start[sh.n_layers + 1] = ents;       // total entries
+    }
+}
+
+// One thread per staging slot (level h, micrograph m, i-th node of that micrograph's level).
+__global__ void __launch_bounds__(kDdThreads)
+dedup_compact(const int32_t* __restrict__ stage_nodes, const int32_t* __restrict__ stage_child,
+              const int32_t* __restrict__ cnt, const int32_t* __restrict__ mg_off,
+              const int64_t* __restrict__ level_start, const int64_t* __restrict__ ent_start, int32_t n_seeds,
+              DedupShape sh, int32_t* __restrict__ node_vertex, int32_t* __restrict__ indptr,
+              int32_t* __restrict__ idx) {
+    const int32_t L = sh.n_layers, B = n_seeds;
+    const int64_t T = sh.base[L + 1], S = sh.base[L];
+    const int64_t t = (int64_t)blockIdx.x * kDdThreads + threadIdx.x;
+    if (t >= T) return;
+    // unused tails: no vertex, empty segments, no child
+    const int64_t n_nodes = level_start[L + 1], n_nonleaf = level_start[L], nnz = ent_start[L + 1];
+    if (t >= n_nodes) node_vertex[t] = -1;
+    if (t >= n_nonleaf && t <= S) indptr[t] = (int32_t)nnz;
+    if (t >= nnz && t < T - B) idx[t] = -1;
+    int32_t h = 0;
+    while (h < L && t >= sh.base[h + 1]) ++h;
+    const int64_t o = t - sh.base[h];
+    const int32_t mg = (int32_t)(o / sh.P[h]), i = (int32_t)(o - (int64_t)mg * sh.P[h]);
+    if (i >= cnt[(int64_t)h * B + mg]) return;
+    const int64_t local = (int64_t)mg_off[(int64_t)h * B + mg] + i;       // rank inside the level
+    const int64_t gi = level_start[h] + local;
+    node_vertex[gi] = stage_nodes[t];
+    if (h == L) return;
+    const int32_t f = sh.f[h + 1];
+    const int64_t e0 = ent_start[h] + local * f;
+    indptr[gi] = (int32_t)e0;
+    const int32_t* child = stage_child + (sh.base[h + 1] - B) + ((int64_t)mg * sh.P[h] + i) * f;
+    const int64_t next0 = level_start[h + 1] + mg_off[(int64_t)(h + 1) * B + mg];
+    for (int32_t j = 0; j < f; ++j) {
+        const int32_t c = child[j];
+        idx[e0 + j] = c >= 0 ? (int32_t)(next0 + c) : -1;
+    }
+}
+
+__global__ void __launch_bounds__(kDdThreads)
+compose_idx(const int32_t* __restrict__ idx, int64_t n, const int32_t* __restrict__ map, int32_t* __restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * kDdThreads;
+    for (int64_t e = (int64_t)blockIdx.x * kDdThreads + threadIdx.x; e < n; e += stride) {
+        const int32_t u = idx[e];
+        out[e] = u >= 0 ? map[u] : -1;
+    }
+}
+
+struct DedupWs {
+    size_t nodes_bytes, child_bytes, cnt_bytes, ent_start_bytes, total;
+};
+static DedupWs dedup_ws_layout(int64_t T, int64_t B, int32_t L) {
+    DedupWs W{};
+    W.nodes_bytes = align_up((size_t)T * 4, 256);
+    W.child_bytes = align_up((size_t)(T - B > 0 ? T - B : 1) * 4, 256);
+    W.cnt_bytes = align_up((size_t)(L + 1) * B * 4, 256);          // once for cnt, once for mg_off
+    W.ent_start_bytes = align_up((size_t)(L + 2) * 8, 256);
+    W.total = W.nodes_bytes + W.child_bytes + 2 * W.cnt_bytes + W.ent_start_bytes;
+    return W;
+}
+
+static uint64_t dd_host_finalise64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace hopgnn
+
+using namespace hopgnn;
+
+extern "C" size_t hopgnn_sample_dedup_ws_bytes(int32_t n_seeds, const int32_t* fanouts, int32_t n_layers) {
+    const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
+    if (t_seed < 0 || n_seeds < 0) return 0;
+    return dedup_ws_layout(t_seed * n_seeds, n_seeds, n_layers).total;
+}
+
+extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                             const int32_t* fanouts, int32_t n_layers, uint64_t key,
+                                             int32_t* node_vertex, int64_t* level_start, int32_t* indptr, int32_t* idx,
+                                             void* ws, size_t ws_bytes, void* stream) {
+    if (g == nullptr || fanouts == nullptr || n_seeds < 0) return HOPGNN_EINVAL;
+    const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
+    if (t_seed < 0) return HOPGNN_EINVAL;
+    if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (g->offsets == nullptr || seeds == nullptr || node_vertex == nullptr || level_start == nullptr ||
+        indptr == nullptr || idx == nullptr || ws == nullptr)
+        return HOPGNN_EINVAL;
+    if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
+    const int64_t T = (int64_t)n_seeds * t_seed;
+    if (T >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if (!aligned(ws, 256)) return HOPGNN_EINVAL;
+
+    DedupShape sh{};
+    sh.n_layers = n_layers;
+    sh.P[0] = 1;
+    sh.base[0] = 0;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        sh.f[h] = fanouts[h - 1];
+        sh.P[h] = sh.P[h - 1] * sh.f[h];
+        sh.base[h] = sh.base[h - 1] + n_seeds * sh.P[h - 1];
+    }
+    sh.base[n_layers + 1] = sh.base[n_layers] + n_seeds * sh.P[n_layers];
+    if (sh.P[n_layers] > kDdMaxLevel) return HOPGNN_ERANGE;     // a level of one micrograph must fit the LDS sort
+
+    const DedupWs W = dedup_ws_layout(T, n_seeds, n_layers);
+    if (ws_bytes < W.total) return HOPGNN_ENOMEM_WS;
+    char* p = static_cast<char*>(ws);
+    int32_t* stage_nodes = reinterpret_cast<int32_t*>(p);
+    int32_t* stage_child = reinterpret_cast<int32_t*>(p + W.nodes_bytes);
+    int32_t* cnt = reinterpret_cast<int32_t*>(p + W.nodes_bytes + W.child_bytes);
+    int32_t* mg_off = reinterpret_cast<int32_t*>(p + W.nodes_bytes + W.child_bytes + W.cnt_bytes);
+    int64_t* ent_start = reinterpret_cast<int64_t*>(p + W.nodes_bytes + W.child_bytes + 2 * W.cnt_bytes);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t keyed = dd_host_finalise64(key + 0x9E3779B97F4A7C15ull);
+    if (g->offsets_i64)
+        hipLaunchKernelGGL(dedup_sample<int64_t>, dim3(n_seeds), dim3(kDdThreads), 0, s,
+                           static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh, keyed, stage_nodes,
+                           stage_child, cnt);
+    else
+        hipLaunchKernelGGL(dedup_sample<int32_t>, dim3(n_seeds), dim3(kDdThreads), 0, s,
+                           static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh, keyed, stage_nodes,
+                           stage_child, cnt);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(dedup_compact, dim3((unsigned)ceil_div(T, kDdThreads)), dim3(kDdThreads), 0, s, stage_nodes,
+                       stage_child, cnt, mg_off, level_start, ent_start, n_seeds, sh, node_vertex, indptr, idx);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+extern "C" hopgnn_status hopgnn_compose_idx(const int32_t* idx, int64_t n, const int32_t* map, int32_t* out,
+                                            void* stream) {
+    if (n < 0) return HOPGNN_EINVAL;
+    if (n == 0) return HOPGNN_OK;
+    if (idx == nullptr || map == nullptr || out == nullptr) return HOPGNN_EINVAL;
+    const int64_t want = ceil_div(n, kDdThreads);
+    hipLaunchKernelGGL(compose_idx, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(kDdThreads), 0,
+                       static_cast<hipStream_t>(stream), idx, n, map, out);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}

@@ -625,6 +625,16 @@ extern "C" hopgnn_status hopgnn_sage_fwd_agg(const void* Hsrc, hopgnn_dtype dt, 
                                              const void* W_neigh, const void* bias, int32_t d_out, int32_t agg,
                                              int32_t relu, void* out, void* ws, size_t ws_bytes,
                                              void* stream) {
+    return hopgnn_sage_fwd_dev(Hsrc, dt, n_src, d_in, self_idx, indptr, idx, n_dst, nullptr, W_self, W_neigh, bias, d_out,
+                               agg, relu, out, ws, ws_bytes, stream);
+}
+
+extern "C" hopgnn_status hopgnn_sage_fwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                             const int32_t* self_idx, const int32_t* indptr,
+                                             const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
+                                             const void* W_self, const void* W_neigh, const void* bias,
+                                             int32_t d_out, int32_t agg, int32_t relu, void* out, void* ws,
+                                             size_t ws_bytes, void* stream) {
     if (agg != HOPGNN_AGG_MEAN && agg != HOPGNN_AGG_SUM && agg != HOPGNN_AGG_MAX) return HOPGNN_EINVAL;
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
@@ -653,11 +663,11 @@ extern "C" hopgnn_status hopgnn_sage_fwd_agg(const void* Hsrc, hopgnn_dtype dt, 
     }
     hopgnn_status st;
     const AggSpec spec{nullptr, 0, agg};     // the C ABI's aggregator codes are the kernel's op codes
-    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
-    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
-    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec);
+    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
+    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
+    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
     if (st != HOPGNN_OK) return st;
 
     return project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,
-                            zero, out, 0, nullptr);
+                            zero, out, 0, n_dst_dev);
 }

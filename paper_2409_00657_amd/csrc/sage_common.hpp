@@ -115,13 +115,17 @@ __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
               uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job,
-              AggSpec agg) {
+              AggSpec agg, const int64_t* __restrict__ n_rows_dev) {
     if (blockIdx.x >= job.first_block) {
         transpose_w_tile(job, blockIdx.x - job.first_block);
         return;
     }
     if (blockIdx.x == 0)   // the projection reads absent rows and the K padding from this row
         for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
+    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+        const int64_t live = *n_rows_dev;
+        n_dst = live < n_dst ? live : n_dst;
+    }
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
@@ -175,13 +179,17 @@ __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_elem(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
                const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group,
                typename Tr::store_t* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words,
-               TransposeJob job, AggSpec agg) {
+               TransposeJob job, AggSpec agg, const int64_t* __restrict__ n_rows_dev) {
     if (blockIdx.x >= job.first_block) {
         transpose_w_tile(job, blockIdx.x - job.first_block);
         return;
     }
     if (blockIdx.x == 0)
         for (int32_t i = threadIdx.x; i < zero_words; i += kMeanThreads) zero_row[i] = 0u;
+    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+        const int64_t live = *n_rows_dev;
+        n_dst = live < n_dst ? live : n_dst;
+    }
     const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
@@ -221,7 +229,7 @@ template <typename Tr>
 static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const int32_t* idx,
                                  int64_t n_dst, int32_t d_in, void* mean, void* zero_row,
                                  size_t zero_bytes, TransposeJob job, uint32_t n_transpose_tiles, hipStream_t s,
-                                 AggSpec agg = kAggMean) {
+                                 AggSpec agg = kAggMean, const int64_t* n_rows_dev = nullptr) {
     using T = typename Tr::store_t;
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
@@ -238,12 +246,12 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
         hipLaunchKernelGGL(kv, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
                            static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
-                           agg);
+                           agg, n_rows_dev);
     else
         hipLaunchKernelGGL(ke, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,
                            static_cast<T*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
-                           agg);
+                           agg, n_rows_dev);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }

@@ -343,3 +343,58 @@ class HotPath:
                         outs[i].copy_(h[i * B:(i + 1) * B])
                 else:
                     outs[b].copy_(h)
+
+
+class DedupPath:
+    """The forward path over per-micrograph deduplicated frontiers (hopgnn_sample_dedup): the same
+    rows for the seeds as HotPath, over fewer rows below them.  Node counts depend on the data, so
+    every buffer has the slot tree's size and the layers take their row counts from the device."""
+
+    def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor, weights, n_seeds: int,
+                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO):
+        dev = X.device
+        self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
+        self.n_vertices = offsets.numel() - 1
+        self.shape = sh = BatchShape(n_seeds, list(fanouts))
+        T, S, B, L = sh.n_slots, sh.n_nonleaf, n_seeds, sh.n_layers
+        self.capacity = T
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.node_vertex = torch.empty(T, **i32)
+        self.level_start = torch.zeros(L + 2, dtype=torch.int64, device=dev)
+        self.indptr = torch.empty(S + 1, **i32)
+        self.idx = torch.empty(max(T - B, 1), **i32)
+        self.idx_l1 = torch.empty(max(T - B, 1), **i32)      # the first layer's list: positions in Xu
+        self.remap = torch.empty(T, **i32)
+        self.cap = min(T, self.n_vertices)
+        self.uniq = torch.empty(self.cap, **i32)
+        self.n_uniq = torch.zeros(1, dtype=torch.int64, device=dev)
+        self.Xu = torch.empty((self.cap, X.shape[1]), dtype=X.dtype, device=dev)
+        self.pg_algo = pg_algo
+        self.pg_ws = torch.empty(hb.hopgnn_pregather_ws_bytes(T, self.n_vertices, pg_algo), dtype=torch.uint8, device=dev)
+        self.dd_ws = torch.empty(hb.hopgnn_sample_dedup_ws_bytes(B, list(fanouts)), dtype=torch.uint8, device=dev)
+        hidden = weights[0][0].shape[1]
+        self.H = [torch.empty((sh.n_dst(k), hidden), dtype=X.dtype, device=dev) for k in range(1, L + 1)]
+        self.sage_ws = torch.empty(max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0], hidden)
+                                       for k in range(1, L + 1)), dtype=torch.uint8, device=dev)
+        # row count of layer k = first node of level L-k+1: one-element views into level_start
+        self._n_dst_dev = [self.level_start[L - k + 1:L - k + 2] for k in range(1, L + 1)]
+
+    def run_batch(self, seeds: torch.Tensor, key: int) -> torch.Tensor:
+        """Returns the [capacity of level 0 = B, hidden] rows of the last layer (all B exist)."""
+        sh = self.shape
+        B, L = sh.n_seeds, sh.n_layers
+        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, sh.fanouts, key, self.node_vertex, self.level_start,
+                               self.indptr, self.idx, self.dd_ws)
+        hb.hopgnn_pregather(self.node_vertex, self.n_vertices, self.uniq, self.n_uniq, self.remap, self.pg_ws,
+                            self.pg_algo)
+        hb.hopgnn_gather(self.X, self.uniq, self.cap, self.n_uniq, self.Xu)
+        hb.hopgnn_compose_idx(self.idx, self.remap, self.idx_l1)
+        src, n_src = self.Xu, self.cap
+        for k in range(1, L + 1):
+            Ws, Wn, bias = self.weights[k - 1]
+            n_dst = sh.n_dst(k)
+            hb.hopgnn_sage_fwd_dev(src, n_src, self.remap[:n_dst] if k == 1 else None, self.indptr[:n_dst + 1],
+                                   self.idx_l1 if k == 1 else self.idx, n_dst, self._n_dst_dev[k - 1], Ws, Wn, bias,
+                                   hb.AGG_MEAN, k < L, self.H[k - 1], self.sage_ws)
+            src, n_src = self.H[k - 1], n_dst
+        return self.H[-1]
