@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--no-merge", action="store_true",
                     help="with a group > 1: run every batch's layers separately instead of one launch per layer "
                          "over the group's merged micrographs")
+    ap.add_argument("--dedup", action="store_true",
+                    help="sample per-micrograph deduplicated frontiers (hopgnn_sample_dedup): the same rows for the "
+                         "seeds over fewer rows below them; one batch per pre-gather, forward only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -104,12 +107,110 @@ def cpu_baseline(cfg, g, X, W, group, budget_s):
             "seconds": round(t_total, 2)}
 
 
+def main_dedup(args):
+    """The forward step over deduplicated frontiers: same JSON line, call-by-call sequence."""
+    import torch
+
+    from paper_2409_00657_amd import binding as hb
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+
+    hb.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    g = cfg.make_graph(device=dev)
+    X = cfg.make_features(device=dev)
+    W = cfg.make_weights(device=dev)
+    n_streams = max(1, args.streams)
+    dps = [DedupPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts) for _ in range(n_streams)]
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    n_total = args.warmup + args.steps
+    seeds = [synth.seeds(cfg.n_vertices, cfg.batch, i, device=dev) for i in range(n_total)]
+    torch.cuda.synchronize()
+
+    outs = [torch.empty((cfg.batch, cfg.hidden), dtype=X.dtype, device=dev) for _ in range(n_streams)]
+    raw_streams = [s.cuda_stream for s in streams]
+
+    def step(i, marks=None):
+        j = i % n_streams
+        dps[j].forward(seeds[i], i, outs[j], raw_streams[j], marks)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(2)) for _ in range(args.steps)]
+    for i, e in enumerate(ev):      # record once so that the handles exist
+        e[0].record(streams[i % n_streams])
+        e[1].record(streams[i % n_streams])
+    torch.cuda.synchronize()
+    raw_marks = [(a.cuda_event, b.cuda_event) for a, b in ev]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, raw_marks[i])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    gather_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    # instrumented replay on one stream: stage times, U, node counts
+    dp, L = dps[0], len(cfg.fanouts)
+    E = lambda: torch.cuda.Event(enable_timing=True)
+    stage = {"sample": 0.0, "pregather": 0.0, "gather": 0.0, "compose": 0.0}
+    for k in range(1, L + 1):
+        stage["sage_l%d" % k] = 0.0
+    n_replay, U_sum, nodes_sum, valid_sum = min(args.steps, 50), 0, 0, 0
+    for i in range(n_replay):
+        j = args.warmup + i
+        fns = [("sample", lambda: dp.sample(seeds[j], j)), ("pregather", dp.pregather), ("gather", dp.gather),
+               ("compose", dp.compose)] + [("sage_l%d" % k, (lambda k=k: dp.layer(k))) for k in range(1, L + 1)]
+        for name, fn in fns:
+            a, b = E(), E()
+            a.record()
+            fn()
+            b.record()
+            torch.cuda.synchronize()
+            stage[name] += a.elapsed_time(b)
+        U_sum += int(dp.n_uniq.item())
+        nodes_sum += int(dp.level_start[L + 1].item())
+    stage = {k: v / n_replay for k, v in stage.items()}
+    U_avg = U_sum / n_replay
+    row_bytes = X.shape[1] * X.element_size()
+    gather_bytes = U_avg * (2 * row_bytes + 4)
+    g_avg = sum(gather_ms) / len(gather_ms)
+    gbps = gather_bytes / (g_avg * 1e-3) / 1e9
+    out = {
+        "metric": "micrograph batches/s", "value": args.steps / elapsed, "unit": "batches/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE_NAME[str(X.dtype)],
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges, "feature_dim": cfg.d,
+                   "batch": cfg.batch, "fanouts": cfg.fanouts, "hidden": cfg.hidden, "group": 1, "streams": n_streams,
+                   "deduplicated_frontiers": True, "slots_per_batch": dp.capacity},
+        "unique_rows_per_step": U_avg, "nodes_per_step": nodes_sum / n_replay,
+        "nodes_over_slots": nodes_sum / n_replay / dp.capacity,
+        "stage_ms": {k: round(v, 5) for k, v in stage.items()},
+        "roofline": {"kernel": "gather_rows", "bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS,
+                     "traffic": (gather_bytes * GATHER_TRAFFIC_OVER_ALGORITHMIC[row_bytes]
+                                 if row_bytes in GATHER_TRAFFIC_OVER_ALGORITHMIC else None),
+                     "algorithmic_bytes_per_launch": gather_bytes, "avg_launch_ms": g_avg,
+                     "launch_ms_percentiles": {"p10": gather_ms[len(gather_ms) // 10], "p50": gather_ms[len(gather_ms) // 2],
+                                               "p90": gather_ms[(len(gather_ms) * 9) // 10]}},
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build is the single-GPU hot path (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.dedup:
+        if args.backward or args.model != "sage" or args.group > 1:
+            print("bench.py: --dedup runs the GraphSAGE forward path, one batch per pre-gather", file=sys.stderr)
+            sys.exit(2)
+        return main_dedup(args)
 
     import torch
 

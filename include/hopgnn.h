@@ -412,6 +412,15 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *                               with W_self, a_src[k], a_dst[k], gat_heads heads; the first layer
  *                               projects only the rows the pre-gather found).  sage_ws must be
  *                               large enough for the chosen layer type's *_ws_bytes.
+ *   dedup                       nonzero: per-micrograph deduplicated frontiers - hopgnn_sample_dedup
+ *                               (into node_vertex / level_start / indptr / dd_idx with dd_ws),
+ *                               hopgnn_pregather over node_vertex, hopgnn_gather, hopgnn_compose_idx
+ *                               (into dd_idx_l1) and the layers through hopgnn_sage_fwd_dev with
+ *                               their row counts read from level_start.  One batch per call
+ *                               (n_batches = 1), GraphSAGE-mean layers; ids, slot_idx and
+ *                               merge_layers are not used; remap holds the node list's positions.
+ *                               node_vertex [T], level_start int64 [n_layers+2], dd_idx and
+ *                               dd_idx_l1 [T - n_seeds], dd_ws of hopgnn_sample_dedup_ws_bytes.
  *   merge_layers                nonzero: the group's micrographs are sampled as one level-major
  *                               batch (hopgnn_sample_merged, seeds_per_key = n_seeds) and every
  *                               layer is ONE hopgnn_sage_fwd over the whole group instead of one
@@ -460,6 +469,12 @@ typedef struct {
     int32_t layer_kind, gcn_norm, gat_heads;
     const void *a_src[8];
     const void *a_dst[8];
+    int32_t dedup;
+    int32_t *node_vertex;
+    int64_t *level_start;
+    int32_t *dd_idx, *dd_idx_l1;
+    void *dd_ws;
+    size_t dd_ws_bytes;
 } hopgnn_batch_plan;
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,

@@ -61,7 +61,10 @@ class BatchPlan(ctypes.Structure):
                 ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p),
                 ("pg_ws_clean", ctypes.c_int32), ("merge_layers", ctypes.c_int32),
                 ("layer_kind", ctypes.c_int32), ("gcn_norm", ctypes.c_int32), ("gat_heads", ctypes.c_int32),
-                ("a_src", ctypes.c_void_p * 8), ("a_dst", ctypes.c_void_p * 8)]
+                ("a_src", ctypes.c_void_p * 8), ("a_dst", ctypes.c_void_p * 8),
+                ("dedup", ctypes.c_int32), ("node_vertex", ctypes.c_void_p), ("level_start", ctypes.c_void_p),
+                ("dd_idx", ctypes.c_void_p), ("dd_idx_l1", ctypes.c_void_p), ("dd_ws", ctypes.c_void_p),
+                ("dd_ws_bytes", ctypes.c_size_t)]
 
 
 def library_path() -> str:

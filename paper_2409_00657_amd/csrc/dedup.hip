@@ -35,7 +35,8 @@ __device__ __forceinline__ uint64_t dd_finalise64(uint64_t z) {
     return z ^ (z >> 31);
 }
 
-// Exclusive prefix sum of one value per thread over the 256-thread workgroup; `total` = their sum.
+// Exclusive prefix sum of one value per thread over a workgroup of THREADS; `total` = their sum.
+template <int THREADS>
 __device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, uint32_t& total) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     uint32_t inc = x;
@@ -48,7 +49,7 @@ __device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, ui
     __syncthreads();
     uint32_t wave_base = 0, tot = 0;
 #pragma unroll
-    for (int w = 0; w < kDdThreads / kWave; ++w) {
+    for (int w = 0; w < THREADS / kWave; ++w) {
         const uint32_t s = lds4[w];
         if (w < wave) wave_base += s;
         tot += s;
@@ -58,15 +59,19 @@ __device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, ui
     return wave_base + inc - x;
 }
 
-template <typename OffT>
-__global__ void __launch_bounds__(kDdThreads)
+// LDS (dynamic): three arrays of `cap` words, cap = the last level's slot count rounded up to a
+// power of two - a few KiB for the usual fanouts, so that many micrographs share a CU; THREADS
+// is chosen to match (64 .. 256).
+template <typename OffT, int THREADS>
+__global__ void __launch_bounds__(THREADS)
 dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices, const int32_t* __restrict__ seeds,
              int32_t n_seeds, DedupShape sh, uint64_t keyed, int32_t* __restrict__ stage_nodes,
-             int32_t* __restrict__ stage_child, int32_t* __restrict__ cnt) {
-    __shared__ uint32_t cur[kDdMaxLevel];     // distinct vertices of the current level, ascending
-    __shared__ uint32_t ent[kDdMaxLevel];     // children in draw order (kDdNone: none)
-    __shared__ uint32_t srt[kDdMaxLevel];     // the same, sorted; then the distinct ones packed in front
-    __shared__ uint32_t lds4[kDdThreads / kWave];
+             int32_t* __restrict__ stage_child, int32_t* __restrict__ cnt, uint32_t cap) {
+    extern __shared__ uint32_t dd_lds[];
+    uint32_t* cur = dd_lds;                   // distinct vertices of the current level, ascending
+    uint32_t* ent = dd_lds + cap;             // children in draw order (kDdNone: none)
+    uint32_t* srt = dd_lds + 2 * cap;         // the same, sorted
+    __shared__ uint32_t lds4[THREADS / kWave];
     __shared__ uint32_t n_next_s;
     const int32_t m = blockIdx.x, B = n_seeds;
     const int tid = threadIdx.x;
@@ -84,7 +89,7 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
         uint32_t n2 = 1;
         while (n2 < n_cand) n2 <<= 1;
         // draw: entry c = (node q, draw j)
-        for (uint32_t c = tid; c < n2; c += kDdThreads) {
+        for (uint32_t c = tid; c < n2; c += THREADS) {
             uint32_t child = kDdNone;
             if (c < n_cand) {
                 const uint32_t q = c / f, j = c - q * f;
@@ -107,7 +112,7 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
         // ascending bitonic sort of srt[0, n2)  (kDdNone sorts last)
         for (uint32_t k = 2; k <= n2; k <<= 1)
             for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-                for (uint32_t i = tid; i < n2; i += kDdThreads) {
+                for (uint32_t i = tid; i < n2; i += THREADS) {
                     const uint32_t p = i ^ j;
                     if (p > i) {
                         const uint32_t a = srt[i], b = srt[p];
@@ -121,12 +126,12 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
             }
         // distinct values, packed in order into cur (the next level's node list)
         uint32_t carry = 0;
-        for (uint32_t i0 = 0; i0 < n2; i0 += kDdThreads) {
+        for (uint32_t i0 = 0; i0 < n2; i0 += THREADS) {
             const uint32_t i = i0 + tid;
             const uint32_t v = i < n2 ? srt[i] : kDdNone;
             const uint32_t head = (v != kDdNone && (i == 0 || srt[i - 1] != v)) ? 1u : 0u;
             uint32_t total;
-            const uint32_t pos = carry + dd_block_scan(head, lds4, total);
+            const uint32_t pos = carry + dd_block_scan<THREADS>(head, lds4, total);
             if (head) cur[pos] = v;        // cur is free: every draw of this hop has been made
             carry += total;
         }
@@ -136,8 +141,8 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
         // this micrograph's slices of the staging arrays (slot-tree capacity)
         int32_t* nodes_out = stage_nodes + sh.base[h] + (int64_t)m * sh.P[h];
         int32_t* child_out = stage_child + (sh.base[h] - B) + (int64_t)m * sh.P[h];
-        for (uint32_t i = tid; i < n_next; i += kDdThreads) nodes_out[i] = (int32_t)cur[i];
-        for (uint32_t c = tid; c < n_cand; c += kDdThreads) {
+        for (uint32_t i = tid; i < n_next; i += THREADS) nodes_out[i] = (int32_t)cur[i];
+        for (uint32_t c = tid; c < n_cand; c += THREADS) {
             const uint32_t child = ent[c];
             int32_t pos = -1;
             if (child != kDdNone) {          // lower bound in cur[0, n_next): the value is there
@@ -164,22 +169,25 @@ dedup_scan(const int32_t* __restrict__ cnt, int32_t n_seeds, DedupShape sh, int3
            int64_t* __restrict__ level_start, int64_t* __restrict__ ent_start) {
     __shared__ uint32_t lds4[kDdThreads / kWave];
     int64_t nodes = 0, ents = 0;
+    // thread t owns the contiguous run [t*per, (t+1)*per) of micrographs: sum it, scan the run sums
+    const int32_t per = (n_seeds + kDdThreads - 1) / kDdThreads;
+    const int32_t m0 = threadIdx.x * per, m1 = m0 + per < n_seeds ? m0 + per : n_seeds;
     for (int32_t h = 0; h <= sh.n_layers; ++h) {
         if (threadIdx.x == 0) {
             level_start[h] = nodes;
             ent_start[h] = ents;
         }
-        uint32_t carry = 0;
-        for (int32_t m0 = 0; m0 < n_seeds; m0 += kDdThreads) {
-            const int32_t mm = m0 + threadIdx.x;
-            const uint32_t x = mm < n_seeds ? (uint32_t)cnt[(int64_t)h * n_seeds + mm] : 0u;
-            uint32_t total;
-            const uint32_t ex = dd_block_scan(x, lds4, total);
-            if (mm < n_seeds) mg_off[(int64_t)h * n_seeds + mm] = (int32_t)(carry + ex);
-            carry += total;
+        const int32_t* c = cnt + (int64_t)h * n_seeds;
+        uint32_t mine = 0;
+        for (int32_t mm = m0; mm < m1; ++mm) mine += (uint32_t)c[mm];
+        uint32_t total;
+        uint32_t run = dd_block_scan<kDdThreads>(mine, lds4, total);
+        for (int32_t mm = m0; mm < m1; ++mm) {
+            mg_off[(int64_t)h * n_seeds + mm] = (int32_t)run;
+            run += (uint32_t)c[mm];
         }
-        nodes += carry;
-        if (h < sh.n_layers) ents += (int64_t)carry * sh.f[h + 1];
+        nodes += total;
+        if (h < sh.n_layers) ents += (int64_t)total * sh.f[h + 1];
     }
     if (threadIdx.x == 0) {
         level_start[sh.n_layers + 1] = nodes;
@@ -301,14 +309,25 @@ extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t*
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const uint64_t keyed = dd_host_finalise64(key + 0x9E3779B97F4A7C15ull);
-    if (g->offsets_i64)
-        hipLaunchKernelGGL(dedup_sample<int64_t>, dim3(n_seeds), dim3(kDdThreads), 0, s,
-                           static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh, keyed, stage_nodes,
-                           stage_child, cnt);
-    else
-        hipLaunchKernelGGL(dedup_sample<int32_t>, dim3(n_seeds), dim3(kDdThreads), 0, s,
-                           static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh, keyed, stage_nodes,
-                           stage_child, cnt);
+    uint32_t cap = 1;
+    while (cap < (uint32_t)sh.P[n_layers]) cap <<= 1;
+    const size_t lds = (size_t)3 * cap * sizeof(uint32_t);
+    const int threads = cap >= 1024 ? 256 : (cap >= 256 ? 128 : 64);
+    const void* off = g->offsets;
+#define HOPGNN_DD_LAUNCH(OffT, THREADS)                                                                              \
+    hipLaunchKernelGGL((dedup_sample<OffT, THREADS>), dim3(n_seeds), dim3(THREADS), lds, s,                          \
+                       static_cast<const OffT*>(off), g->indices, seeds, n_seeds, sh, keyed, stage_nodes, stage_child, \
+                       cnt, cap)
+    if (g->offsets_i64) {
+        if (threads == 256) HOPGNN_DD_LAUNCH(int64_t, 256);
+        else if (threads == 128) HOPGNN_DD_LAUNCH(int64_t, 128);
+        else HOPGNN_DD_LAUNCH(int64_t, 64);
+    } else {
+        if (threads == 256) HOPGNN_DD_LAUNCH(int32_t, 256);
+        else if (threads == 128) HOPGNN_DD_LAUNCH(int32_t, 128);
+        else HOPGNN_DD_LAUNCH(int32_t, 64);
+    }
+#undef HOPGNN_DD_LAUNCH
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
     HOPGNN_LAUNCH_CHECK();

@@ -378,23 +378,84 @@ class DedupPath:
                                        for k in range(1, L + 1)), dtype=torch.uint8, device=dev)
         # row count of layer k = first node of level L-k+1: one-element views into level_start
         self._n_dst_dev = [self.level_start[L - k + 1:L - k + 2] for k in range(1, L + 1)]
+        # the same buffers as a plan for hopgnn_batch_fwd (the sequence issued from C)
+        pl = self.plan = hb.BatchPlan()
+        pl.graph = hb._Csr(self.n_vertices, indices.numel(), offsets.data_ptr(),
+                           1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+        pl.X, pl.dt, pl.dim, pl.ld_elems = X.data_ptr(), hb.DTYPE_OF[X.dtype], X.shape[1], X.stride(0)
+        pl.n_seeds, pl.n_layers = B, L
+        for i, f in enumerate(sh.fanouts):
+            pl.fanouts[i] = f
+        for i, (Ws, Wn, bias) in enumerate(weights):
+            pl.d_out[i] = Ws.shape[1]
+            pl.W_self[i], pl.W_neigh[i] = Ws.data_ptr(), Wn.data_ptr()
+            pl.bias[i] = None if bias is None else bias.data_ptr()
+            pl.H[i] = self.H[i].data_ptr()
+        pl.pg_algo, pl.group, pl.dedup = pg_algo, 1, 1
+        pl.indptr, pl.uniq, pl.uniq_capacity, pl.n_uniq = self.indptr.data_ptr(), self.uniq.data_ptr(), self.cap, \
+            self.n_uniq.data_ptr()
+        pl.remap, pl.Xu = self.remap.data_ptr(), self.Xu.data_ptr()
+        pl.pg_ws, pl.pg_ws_bytes = self.pg_ws.data_ptr(), self.pg_ws.numel()
+        pl.sage_ws, pl.sage_ws_bytes = self.sage_ws.data_ptr(), self.sage_ws.numel()
+        pl.node_vertex, pl.level_start = self.node_vertex.data_ptr(), self.level_start.data_ptr()
+        pl.dd_idx, pl.dd_idx_l1 = self.idx.data_ptr(), self.idx_l1.data_ptr()
+        pl.dd_ws, pl.dd_ws_bytes = self.dd_ws.data_ptr(), self.dd_ws.numel()
+        self._key = (ctypes.c_uint64 * 1)()
+        self._lib = hb.load_library()
 
-    def run_batch(self, seeds: torch.Tensor, key: int) -> torch.Tensor:
-        """Returns the [capacity of level 0 = B, hidden] rows of the last layer (all B exist)."""
-        sh = self.shape
-        B, L = sh.n_seeds, sh.n_layers
-        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, sh.fanouts, key, self.node_vertex, self.level_start,
-                               self.indptr, self.idx, self.dd_ws)
+    def forward(self, seeds: torch.Tensor, key: int, out: torch.Tensor, stream=None, marks=None) -> None:
+        """The whole batch in ONE library call; `out` [B, hidden] receives the last layer's rows;
+        `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
+        B = self.shape.n_seeds
+        if seeds.numel() != B or seeds.dtype != torch.int32 or not seeds.is_cuda:
+            raise hb.HopgnnError("seeds must be %d int32 values on the device" % B)
+        if out.numel() != B * self.H[-1].shape[1] or out.dtype != self.X.dtype or not out.is_cuda \
+                or not out.is_contiguous():
+            raise hb.HopgnnError("out must be a contiguous [B, hidden] device tensor of X's type")
+        self._key[0] = key & 0xFFFFFFFFFFFFFFFF
+        pl = self.plan
+        pl.mark_gather_begin, pl.mark_gather_end = marks if marks is not None else (None, None)
+        st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._key, 1, out.data_ptr(), st)
+        if rc:
+            hb._check(rc, "hopgnn_batch_fwd")
+
+    # the steps, all on torch's current stream
+    def sample(self, seeds: torch.Tensor, key: int) -> None:
+        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, self.shape.fanouts, key, self.node_vertex,
+                               self.level_start, self.indptr, self.idx, self.dd_ws)
+
+    def pregather(self) -> None:
         hb.hopgnn_pregather(self.node_vertex, self.n_vertices, self.uniq, self.n_uniq, self.remap, self.pg_ws,
                             self.pg_algo)
+
+    def gather(self) -> None:
         hb.hopgnn_gather(self.X, self.uniq, self.cap, self.n_uniq, self.Xu)
+
+    def compose(self) -> None:
         hb.hopgnn_compose_idx(self.idx, self.remap, self.idx_l1)
-        src, n_src = self.Xu, self.cap
-        for k in range(1, L + 1):
-            Ws, Wn, bias = self.weights[k - 1]
-            n_dst = sh.n_dst(k)
-            hb.hopgnn_sage_fwd_dev(src, n_src, self.remap[:n_dst] if k == 1 else None, self.indptr[:n_dst + 1],
-                                   self.idx_l1 if k == 1 else self.idx, n_dst, self._n_dst_dev[k - 1], Ws, Wn, bias,
-                                   hb.AGG_MEAN, k < L, self.H[k - 1], self.sage_ws)
-            src, n_src = self.H[k - 1], n_dst
+
+    def layer(self, k: int) -> torch.Tensor:
+        sh = self.shape
+        Ws, Wn, bias = self.weights[k - 1]
+        n_dst = sh.n_dst(k)
+        src, n_src = (self.Xu, self.cap) if k == 1 else (self.H[k - 2], sh.n_dst(k - 1))
+        hb.hopgnn_sage_fwd_dev(src, n_src, self.remap[:n_dst] if k == 1 else None, self.indptr[:n_dst + 1],
+                               self.idx_l1 if k == 1 else self.idx, n_dst, self._n_dst_dev[k - 1], Ws, Wn, bias,
+                               hb.AGG_MEAN, k < sh.n_layers, self.H[k - 1], self.sage_ws)
+        return self.H[k - 1]
+
+    def run_batch(self, seeds: torch.Tensor, key: int, marks=None) -> torch.Tensor:
+        """Returns the [B, hidden] rows of the last layer (level 0 always has all B roots).
+        `marks` = (begin, end) torch events recorded around the gather launch."""
+        self.sample(seeds, key)
+        self.pregather()
+        if marks is not None:
+            marks[0].record()
+        self.gather()
+        if marks is not None:
+            marks[1].record()
+        self.compose()
+        for k in range(1, self.shape.n_layers + 1):
+            self.layer(k)
         return self.H[-1]

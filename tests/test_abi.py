@@ -74,13 +74,13 @@ def test_batch_plan_errors_and_layout(lib):
         src = os.path.join(d, "p.c")
         open(src, "w").write('#include <stdio.h>\n#include <stddef.h>\n#include "hopgnn.h"\nint main(void){printf("%zu %zu %zu",'
                              'sizeof(hopgnn_batch_plan),offsetof(hopgnn_batch_plan,W_self),'
-                             'offsetof(hopgnn_batch_plan,a_dst));return 0;}\n')
+                             'offsetof(hopgnn_batch_plan,dd_ws_bytes));return 0;}\n')
         exe = os.path.join(d, "p")
         subprocess.run(["gcc", "-I", os.path.join(ROOT, "include"), src, "-o", exe], check=True)
         size, off_w, off_m = map(int, subprocess.run([exe], capture_output=True, text=True, check=True).stdout.split())
     assert c.sizeof(hb.BatchPlan) == size
     assert hb.BatchPlan.W_self.offset == off_w
-    assert hb.BatchPlan.a_dst.offset == off_m
+    assert hb.BatchPlan.dd_ws_bytes.offset == off_m
     plan = hb.BatchPlan()
     keys = (c.c_uint64 * 1)(0)
     one = c.c_void_p(8)    # any non-NULL address: the checks below fail before it is used

@@ -82,6 +82,12 @@ def test_layers_over_deduplicated_nodes_give_the_tree_rows(hb, orc, dt, fanouts)
         seeds = synth.seeds(n, B, 30 + it, device=DEV)
         out = dp.run_batch(seeds, 400 + it).clone()
         torch.cuda.synchronize()
+        # the same sequence from one library call: the same bits
+        out2 = torch.full_like(out, float("nan"))
+        dp.remap.fill_(-7)
+        dp.forward(seeds, 400 + it, out2)
+        torch.cuda.synchronize()
+        assert to_bits(out2).tobytes() == to_bits(out).tobytes()
         # the tree oracle's rows for the same seeds and key
         ids, ip = orc.sample(off_np, idx_np, seeds.cpu().numpy(), fanouts, 400 + it)
         uniq, remap = orc.pregather(ids)
