@@ -168,6 +168,8 @@ size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo
  *   idx         DEVICE out [T - n_seeds]   child NODE index or -1 (the vertex has no neighbours);
  *                                  entries past the total are -1
  *   ws          DEVICE scratch, hopgnn_sample_dedup_ws_bytes, 256-byte aligned
+ * Micrograph m draws with keys[m / seeds_per_key] (HOST array of ceil(n_seeds / seeds_per_key)
+ * keys), as in hopgnn_sample_merged: one key for the whole batch is seeds_per_key = n_seeds.
  * One level of one micrograph may hold at most 4096 slots (product of the fanouts), else
  * HOPGNN_ERANGE.  Other errors as hopgnn_sample.
  *
@@ -177,8 +179,8 @@ size_t hopgnn_pregather_ws_bytes(int64_t n_ids, int64_t n_vertices, int32_t algo
 size_t hopgnn_sample_dedup_ws_bytes(int32_t n_seeds, const int32_t *fanouts /*HOST*/, int32_t n_layers);
 
 hopgnn_status hopgnn_sample_dedup(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
-                                  const int32_t *fanouts /*HOST*/, int32_t n_layers, uint64_t key,
-                                  int32_t *node_vertex, int64_t *level_start, int32_t *indptr, int32_t *idx,
+                                  int32_t seeds_per_key, const int32_t *fanouts /*HOST*/, int32_t n_layers,
+                                  const uint64_t *keys /*HOST*/, int32_t *node_vertex, int64_t *level_start, int32_t *indptr, int32_t *idx,
                                   void *ws, size_t ws_bytes, void *stream);
 
 hopgnn_status hopgnn_compose_idx(const int32_t *idx, int64_t n, const int32_t *map, int32_t *out, void *stream);
@@ -416,11 +418,15 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *                               (into node_vertex / level_start / indptr / dd_idx with dd_ws),
  *                               hopgnn_pregather over node_vertex, hopgnn_gather, hopgnn_compose_idx
  *                               (into dd_idx_l1) and the layers through hopgnn_sage_fwd_dev with
- *                               their row counts read from level_start.  One batch per call
- *                               (n_batches = 1), GraphSAGE-mean layers; ids, slot_idx and
- *                               merge_layers are not used; remap holds the node list's positions.
- *                               node_vertex [T], level_start int64 [n_layers+2], dd_idx and
- *                               dd_idx_l1 [T - n_seeds], dd_ws of hopgnn_sample_dedup_ws_bytes.
+ *                               their row counts read from level_start.  The n_batches batches of
+ *                               a call form one merged batch (batch b draws with keys[b]) and
+ *                               every layer is one launch; GraphSAGE-mean layers; ids, slot_idx
+ *                               and merge_layers are not used; remap holds the node list's
+ *                               positions.  With G = group and T the slots of G*n_seeds seeds:
+ *                               node_vertex and remap [T], level_start int64 [n_layers+2], indptr
+ *                               [T - last level + 1], dd_idx and dd_idx_l1 [T - G*n_seeds], H[k] and
+ *                               sage_ws for G times the rows, dd_ws of
+ *                               hopgnn_sample_dedup_ws_bytes(G*n_seeds, ..).
  *   merge_layers                nonzero: the group's micrographs are sampled as one level-major
  *                               batch (hopgnn_sample_merged, seeds_per_key = n_seeds) and every
  *                               layer is ONE hopgnn_sage_fwd over the whole group instead of one

@@ -133,8 +133,8 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_sample_dedup_ws_bytes.restype = c.c_size_t
     L.hopgnn_sample_dedup_ws_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int32), c.c_int32]
     L.hopgnn_sample_dedup.restype = c.c_int
-    L.hopgnn_sample_dedup.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
-                                      c.c_uint64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+    L.hopgnn_sample_dedup.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
+                                      c.POINTER(c.c_uint64), c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_size_t, c.c_void_p]
     L.hopgnn_compose_idx.restype = c.c_int
     L.hopgnn_compose_idx.argtypes = [c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -421,16 +421,22 @@ def hopgnn_sample_dedup_ws_bytes(n_seeds: int, fanouts: Sequence[int]) -> int:
 
 
 def hopgnn_sample_dedup(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor, fanouts: Sequence[int],
-                        key: int, node_vertex: torch.Tensor, level_start: torch.Tensor, indptr: torch.Tensor,
-                        idx: torch.Tensor, ws: torch.Tensor) -> None:
+                        key, node_vertex: torch.Tensor, level_start: torch.Tensor, indptr: torch.Tensor,
+                        idx: torch.Tensor, ws: torch.Tensor, seeds_per_key: int = 0) -> None:
+    """`key`: one key for the whole batch, or a list with one key per block of seeds_per_key seeds."""
+    keys = list(key) if isinstance(key, (list, tuple)) else [key]
+    spk = seeds_per_key if seeds_per_key > 0 else max(seeds.numel(), 1)
+    if len(keys) != -(-seeds.numel() // spk) and seeds.numel() > 0:
+        raise HopgnnError("one key per block of seeds_per_key seeds")
+    karr = (ctypes.c_uint64 * max(len(keys), 1))(*[k & 0xFFFFFFFFFFFFFFFF for k in keys])
     g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
              1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
     if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
         raise HopgnnError("offsets must be int32/int64 and indices int32")
     if level_start.dtype != torch.int64 or level_start.numel() < len(fanouts) + 2:
         raise HopgnnError("level_start must hold n_layers + 2 int64 values")
-    rc = load_library().hopgnn_sample_dedup(ctypes.byref(g), _ptr(seeds), seeds.numel(), _fan(fanouts), len(fanouts),
-                                            ctypes.c_uint64(key & 0xFFFFFFFFFFFFFFFF), _ptr(node_vertex),
+    rc = load_library().hopgnn_sample_dedup(ctypes.byref(g), _ptr(seeds), seeds.numel(), spk, _fan(fanouts), len(fanouts),
+                                            karr, _ptr(node_vertex),
                                             _ptr(level_start), _ptr(indptr), _ptr(idx), _ptr(ws),
                                             ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sample_dedup")

@@ -28,14 +28,17 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     if (p->dedup) {
         // deduplicated frontiers: node counts depend on the data, so everything is sized for the
         // slot tree and the layers read their row counts from level_start
-        if (n_batches != 1 || p->layer_kind != 0) return HOPGNN_EINVAL;
+        if (p->layer_kind != 0) return HOPGNN_EINVAL;
         if (p->node_vertex == nullptr || p->level_start == nullptr || p->dd_idx == nullptr || p->dd_idx_l1 == nullptr)
             return HOPGNN_EINVAL;
-        hopgnn_status rc = hopgnn_sample_dedup(&p->graph, seeds, B, p->fanouts, L, keys[0], p->node_vertex,
+        const int32_t B_all = n_batches * B;          // the call's batches form one merged batch
+        const int64_t T_all = (int64_t)n_batches * T;
+        if (T_all >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+        hopgnn_status rc = hopgnn_sample_dedup(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex,
                                                p->level_start, p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, stream);
         if (rc != HOPGNN_OK) return rc;
-        rc = hopgnn_pregather(p->node_vertex, T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap, p->pg_ws,
-                              p->pg_ws_bytes, stream);
+        rc = hopgnn_pregather(p->node_vertex, T_all, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
+                              p->pg_ws, p->pg_ws_bytes, stream);
         if (rc != HOPGNN_OK) return rc;
         if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
             return HOPGNN_EHIP;
@@ -44,14 +47,14 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         if (rc != HOPGNN_OK) return rc;
         if (p->mark_gather_end != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_end, st) != hipSuccess)
             return HOPGNN_EHIP;
-        rc = hopgnn_compose_idx(p->dd_idx, T - B, p->remap, p->dd_idx_l1, stream);
+        rc = hopgnn_compose_idx(p->dd_idx, T_all - B_all, p->remap, p->dd_idx_l1, stream);
         if (rc != HOPGNN_OK) return rc;
         const void* src = p->Xu;
         int64_t n_src = p->uniq_capacity;
         int32_t d_in = p->dim;
         for (int32_t k = 1; k <= L; ++k) {
             int64_t n_dst = 0;                      // capacity: the slot tree's levels 0 .. L-k
-            for (int h = 0; h <= L - k; ++h) n_dst += level[h];
+            for (int h = 0; h <= L - k; ++h) n_dst += level[h] * n_batches;
             void* dst = k == L ? out : p->H[k - 1];
             if (dst == nullptr) return HOPGNN_EINVAL;
             rc = hopgnn_sage_fwd_dev(src, p->dt, n_src, d_in, k == 1 ? p->remap : nullptr, p->indptr,

@@ -22,6 +22,11 @@ constexpr int kDdThreads = 256;
 constexpr int kDdMaxLevel = 4096;      // most slots one micrograph may have at one level
 constexpr uint32_t kDdNone = 0xFFFFFFFFu;
 
+constexpr int kDdKeysPerLaunch = 64;
+struct DedupKeys {
+    uint64_t keyed[kDdKeysPerLaunch];      // first hash round already applied on the host
+};
+
 struct DedupShape {
     int32_t n_layers;
     int32_t f[kMaxLayers + 1];      // f[h], h = 1..L
@@ -65,15 +70,17 @@ __device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, ui
 template <typename OffT, int THREADS>
 __global__ void __launch_bounds__(THREADS)
 dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices, const int32_t* __restrict__ seeds,
-             int32_t n_seeds, DedupShape sh, uint64_t keyed, int32_t* __restrict__ stage_nodes,
-             int32_t* __restrict__ stage_child, int32_t* __restrict__ cnt, uint32_t cap) {
+             int32_t n_seeds, DedupShape sh, DedupKeys keys, int32_t m_offset, int32_t seeds_per_key,
+             int32_t* __restrict__ stage_nodes, int32_t* __restrict__ stage_child, int32_t* __restrict__ cnt,
+             uint32_t cap) {
     extern __shared__ uint32_t dd_lds[];
     uint32_t* cur = dd_lds;                   // distinct vertices of the current level, ascending
     uint32_t* ent = dd_lds + cap;             // children in draw order (kDdNone: none)
     uint32_t* srt = dd_lds + 2 * cap;         // the same, sorted
     __shared__ uint32_t lds4[THREADS / kWave];
     __shared__ uint32_t n_next_s;
-    const int32_t m = blockIdx.x, B = n_seeds;
+    const int32_t m = m_offset + (int32_t)blockIdx.x, B = n_seeds;
+    const uint64_t keyed = keys.keyed[blockIdx.x / (uint32_t)seeds_per_key];   // one key per block of seeds
     const int tid = threadIdx.x;
     const int32_t root = seeds[m];
     if (tid == 0) {
@@ -270,15 +277,15 @@ extern "C" size_t hopgnn_sample_dedup_ws_bytes(int32_t n_seeds, const int32_t* f
 }
 
 extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
-                                             const int32_t* fanouts, int32_t n_layers, uint64_t key,
-                                             int32_t* node_vertex, int64_t* level_start, int32_t* indptr, int32_t* idx,
+                                             int32_t seeds_per_key, const int32_t* fanouts, int32_t n_layers,
+                                             const uint64_t* keys, int32_t* node_vertex, int64_t* level_start, int32_t* indptr, int32_t* idx,
                                              void* ws, size_t ws_bytes, void* stream) {
-    if (g == nullptr || fanouts == nullptr || n_seeds < 0) return HOPGNN_EINVAL;
+    if (g == nullptr || fanouts == nullptr || n_seeds < 0 || seeds_per_key < 1) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
     if (t_seed < 0) return HOPGNN_EINVAL;
     if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
     if (n_seeds == 0) return HOPGNN_OK;
-    if (g->offsets == nullptr || seeds == nullptr || node_vertex == nullptr || level_start == nullptr ||
+    if (g->offsets == nullptr || seeds == nullptr || keys == nullptr || node_vertex == nullptr || level_start == nullptr ||
         indptr == nullptr || idx == nullptr || ws == nullptr)
         return HOPGNN_EINVAL;
     if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
@@ -308,27 +315,34 @@ extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t*
     int64_t* ent_start = reinterpret_cast<int64_t*>(p + W.nodes_bytes + W.child_bytes + 2 * W.cnt_bytes);
 
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t keyed = dd_host_finalise64(key + 0x9E3779B97F4A7C15ull);
     uint32_t cap = 1;
     while (cap < (uint32_t)sh.P[n_layers]) cap <<= 1;
     const size_t lds = (size_t)3 * cap * sizeof(uint32_t);
     const int threads = cap >= 1024 ? 256 : (cap >= 256 ? 128 : 64);
     const void* off = g->offsets;
+    const int32_t n_keys = (int32_t)ceil_div(n_seeds, seeds_per_key);
+    for (int32_t k0 = 0; k0 < n_keys; k0 += kDdKeysPerLaunch) {     // 64 keys fit one launch's arguments
+        const int32_t nk = n_keys - k0 < kDdKeysPerLaunch ? n_keys - k0 : kDdKeysPerLaunch;
+        DedupKeys dk{};
+        for (int32_t i = 0; i < nk; ++i) dk.keyed[i] = dd_host_finalise64(keys[k0 + i] + 0x9E3779B97F4A7C15ull);
+        const int64_t m0 = (int64_t)k0 * seeds_per_key;
+        const int64_t count = (int64_t)nk * seeds_per_key < n_seeds - m0 ? (int64_t)nk * seeds_per_key : n_seeds - m0;
 #define HOPGNN_DD_LAUNCH(OffT, THREADS)                                                                              \
-    hipLaunchKernelGGL((dedup_sample<OffT, THREADS>), dim3(n_seeds), dim3(THREADS), lds, s,                          \
-                       static_cast<const OffT*>(off), g->indices, seeds, n_seeds, sh, keyed, stage_nodes, stage_child, \
-                       cnt, cap)
-    if (g->offsets_i64) {
-        if (threads == 256) HOPGNN_DD_LAUNCH(int64_t, 256);
-        else if (threads == 128) HOPGNN_DD_LAUNCH(int64_t, 128);
-        else HOPGNN_DD_LAUNCH(int64_t, 64);
-    } else {
-        if (threads == 256) HOPGNN_DD_LAUNCH(int32_t, 256);
-        else if (threads == 128) HOPGNN_DD_LAUNCH(int32_t, 128);
-        else HOPGNN_DD_LAUNCH(int32_t, 64);
-    }
+    hipLaunchKernelGGL((dedup_sample<OffT, THREADS>), dim3((unsigned)count), dim3(THREADS), lds, s,                  \
+                       static_cast<const OffT*>(off), g->indices, seeds, n_seeds, sh, dk, (int32_t)m0, seeds_per_key, \
+                       stage_nodes, stage_child, cnt, cap)
+        if (g->offsets_i64) {
+            if (threads == 256) HOPGNN_DD_LAUNCH(int64_t, 256);
+            else if (threads == 128) HOPGNN_DD_LAUNCH(int64_t, 128);
+            else HOPGNN_DD_LAUNCH(int64_t, 64);
+        } else {
+            if (threads == 256) HOPGNN_DD_LAUNCH(int32_t, 256);
+            else if (threads == 128) HOPGNN_DD_LAUNCH(int32_t, 128);
+            else HOPGNN_DD_LAUNCH(int32_t, 64);
+        }
 #undef HOPGNN_DD_LAUNCH
-    HOPGNN_LAUNCH_CHECK();
+        HOPGNN_LAUNCH_CHECK();
+    }
     hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(dedup_compact, dim3((unsigned)ceil_div(T, kDdThreads)), dim3(kDdThreads), 0, s, stage_nodes,

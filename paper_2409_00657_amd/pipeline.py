@@ -351,10 +351,13 @@ class DedupPath:
     every buffer has the slot tree's size and the layers take their row counts from the device."""
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor, weights, n_seeds: int,
-                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO):
+                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO, group: int = 1):
+        """`group` batches of n_seeds seeds form one merged batch (block b draws with key b)."""
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
+        self.n_keys, self.seeds_per_key = group, n_seeds
+        n_seeds = n_seeds * group
         self.shape = sh = BatchShape(n_seeds, list(fanouts))
         T, S, B, L = sh.n_slots, sh.n_nonleaf, n_seeds, sh.n_layers
         self.capacity = T
@@ -383,7 +386,7 @@ class DedupPath:
         pl.graph = hb._Csr(self.n_vertices, indices.numel(), offsets.data_ptr(),
                            1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
         pl.X, pl.dt, pl.dim, pl.ld_elems = X.data_ptr(), hb.DTYPE_OF[X.dtype], X.shape[1], X.stride(0)
-        pl.n_seeds, pl.n_layers = B, L
+        pl.n_seeds, pl.n_layers = self.seeds_per_key, L
         for i, f in enumerate(sh.fanouts):
             pl.fanouts[i] = f
         for i, (Ws, Wn, bias) in enumerate(weights):
@@ -391,7 +394,7 @@ class DedupPath:
             pl.W_self[i], pl.W_neigh[i] = Ws.data_ptr(), Wn.data_ptr()
             pl.bias[i] = None if bias is None else bias.data_ptr()
             pl.H[i] = self.H[i].data_ptr()
-        pl.pg_algo, pl.group, pl.dedup = pg_algo, 1, 1
+        pl.pg_algo, pl.group, pl.dedup = pg_algo, self.n_keys, 1
         pl.indptr, pl.uniq, pl.uniq_capacity, pl.n_uniq = self.indptr.data_ptr(), self.uniq.data_ptr(), self.cap, \
             self.n_uniq.data_ptr()
         pl.remap, pl.Xu = self.remap.data_ptr(), self.Xu.data_ptr()
@@ -400,30 +403,39 @@ class DedupPath:
         pl.node_vertex, pl.level_start = self.node_vertex.data_ptr(), self.level_start.data_ptr()
         pl.dd_idx, pl.dd_idx_l1 = self.idx.data_ptr(), self.idx_l1.data_ptr()
         pl.dd_ws, pl.dd_ws_bytes = self.dd_ws.data_ptr(), self.dd_ws.numel()
-        self._key = (ctypes.c_uint64 * 1)()
+        self._keys = (ctypes.c_uint64 * self.n_keys)()
         self._lib = hb.load_library()
 
-    def forward(self, seeds: torch.Tensor, key: int, out: torch.Tensor, stream=None, marks=None) -> None:
-        """The whole batch in ONE library call; `out` [B, hidden] receives the last layer's rows;
-        `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
-        B = self.shape.n_seeds
-        if seeds.numel() != B or seeds.dtype != torch.int32 or not seeds.is_cuda:
-            raise hb.HopgnnError("seeds must be %d int32 values on the device" % B)
-        if out.numel() != B * self.H[-1].shape[1] or out.dtype != self.X.dtype or not out.is_cuda \
+    def _key_list(self, key):
+        keys = list(key) if isinstance(key, (list, tuple)) else [key]
+        if len(keys) != self.n_keys:
+            raise hb.HopgnnError("one key per batch of the group: %d" % self.n_keys)
+        return keys
+
+    def forward(self, seeds: torch.Tensor, key, out: torch.Tensor, stream=None, marks=None) -> None:
+        """The whole (merged) batch in ONE library call; `out` [group*B, hidden] receives the last
+        layer's rows; `key`: one key per batch of the group; `marks` = (begin, end) raw hipEvent_t
+        handles recorded around the gather launch."""
+        n = self.shape.n_seeds
+        if seeds.numel() != n or seeds.dtype != torch.int32 or not seeds.is_cuda:
+            raise hb.HopgnnError("seeds must be %d int32 values on the device" % n)
+        if out.numel() != n * self.H[-1].shape[1] or out.dtype != self.X.dtype or not out.is_cuda \
                 or not out.is_contiguous():
-            raise hb.HopgnnError("out must be a contiguous [B, hidden] device tensor of X's type")
-        self._key[0] = key & 0xFFFFFFFFFFFFFFFF
+            raise hb.HopgnnError("out must be a contiguous [group*B, hidden] device tensor of X's type")
+        for i, k in enumerate(self._key_list(key)):
+            self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
         pl = self.plan
         pl.mark_gather_begin, pl.mark_gather_end = marks if marks is not None else (None, None)
         st = torch.cuda.current_stream().cuda_stream if stream is None else stream
-        rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._key, 1, out.data_ptr(), st)
+        rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._keys, self.n_keys, out.data_ptr(), st)
         if rc:
             hb._check(rc, "hopgnn_batch_fwd")
 
     # the steps, all on torch's current stream
-    def sample(self, seeds: torch.Tensor, key: int) -> None:
-        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, self.shape.fanouts, key, self.node_vertex,
-                               self.level_start, self.indptr, self.idx, self.dd_ws)
+    def sample(self, seeds: torch.Tensor, key) -> None:
+        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, self.shape.fanouts, self._key_list(key),
+                               self.node_vertex, self.level_start, self.indptr, self.idx, self.dd_ws,
+                               seeds_per_key=self.seeds_per_key)
 
     def pregather(self) -> None:
         hb.hopgnn_pregather(self.node_vertex, self.n_vertices, self.uniq, self.n_uniq, self.remap, self.pg_ws,
@@ -445,8 +457,8 @@ class DedupPath:
                                hb.AGG_MEAN, k < sh.n_layers, self.H[k - 1], self.sage_ws)
         return self.H[k - 1]
 
-    def run_batch(self, seeds: torch.Tensor, key: int, marks=None) -> torch.Tensor:
-        """Returns the [B, hidden] rows of the last layer (level 0 always has all B roots).
+    def run_batch(self, seeds: torch.Tensor, key, marks=None) -> torch.Tensor:
+        """Returns the [group*B, hidden] rows of the last layer (level 0 always has every root).
         `marks` = (begin, end) torch events recorded around the gather launch."""
         self.sample(seeds, key)
         self.pregather()

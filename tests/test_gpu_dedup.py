@@ -18,7 +18,7 @@ def hb():
     return binding
 
 
-def _run_sampler(hb, g, seeds, fanouts, key):
+def _run_sampler(hb, g, seeds, fanouts, key, seeds_per_key=0):
     B = seeds.numel()
     t_seed = hb.hopgnn_slots_per_seed(fanouts)
     T = B * t_seed
@@ -33,7 +33,7 @@ def _run_sampler(hb, g, seeds, fanouts, key):
     ix = torch.full((max(T - B, 1),), -9, **i32)
     ws = torch.empty(hb.hopgnn_sample_dedup_ws_bytes(B, fanouts), dtype=torch.uint8, device=DEV)
     ws.fill_(0x5A)
-    hb.hopgnn_sample_dedup(g.offsets, g.indices, seeds, fanouts, key, nv, ls, ip, ix, ws)
+    hb.hopgnn_sample_dedup(g.offsets, g.indices, seeds, fanouts, key, nv, ls, ip, ix, ws, seeds_per_key=seeds_per_key)
     torch.cuda.synchronize()
     return nv, ls, ip, ix, T, S
 
@@ -100,6 +100,40 @@ def test_layers_over_deduplicated_nodes_give_the_tree_rows(hb, orc, dt, fanouts)
         # fewer rows than slots
         n_nodes = int(dp.level_start[L + 1].item())
         assert n_nodes < dp.capacity
+
+
+def test_grouped_dedup_equals_per_batch_oracle(hb, orc):
+    """A group as one merged batch with a key per block of seeds: block b's nodes are those of the
+    oracle's batch b, and the layer chain gives every seed the tree oracle's row."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    g = synth.rmat_graph(12, 10.0, device=DEV)
+    n, d, hidden, B, G, fan = g.n_vertices, 16, 24, 10, 70, [4, 3]
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    seeds = synth.seeds(n, B * G, 77, device=DEV)
+    keys = [900 + 3 * b for b in range(G)]
+    nv, ls, ip, ix, T, S = _run_sampler(hb, g, seeds, fan, keys, seeds_per_key=B)
+    nv_np, ls_np = nv.cpu().numpy(), ls.cpu().numpy()
+    # level 1 of the merged batch = level 1 of every batch in turn
+    pos = int(ls_np[1])
+    for b in range(G):
+        r_nv, r_ls, _, _ = orc_dedup.sample_dedup(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fan, keys[b])
+        lvl1 = r_nv[r_ls[1]:r_ls[2]]
+        np.testing.assert_array_equal(nv_np[pos:pos + len(lvl1)], lvl1)
+        pos += len(lvl1)
+    assert pos == ls_np[2]
+    X = synth.features(n, d, torch.float32, device=DEV)
+    W = synth.sage_weights(d, hidden, 2, torch.float32, device=DEV)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, fan, group=G)
+    out = torch.empty((G * B, hidden), device=DEV)
+    dp.forward(seeds, keys, out)
+    torch.cuda.synchronize()
+    for b in (0, 1, 63, 64, 69):
+        sb = seeds[b * B:(b + 1) * B].cpu().numpy()
+        ids, tip = orc.sample(off_np, idx_np, sb, fan, keys[b])
+        uniq, remap = orc.pregather(ids)
+        ref = orc.forward(orc.gather(to_bits(X), uniq), 0, ids, tip, remap, B, fan, weights_bits(W))[-1][0]
+        assert rel_err(to_f64(out[b * B:(b + 1) * B]), ref) <= 2e-5, b
 
 
 def test_sample_dedup_argument_errors(hb):
