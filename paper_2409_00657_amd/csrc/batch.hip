@@ -34,11 +34,19 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         const int32_t B_all = n_batches * B;          // the call's batches form one merged batch
         const int64_t T_all = (int64_t)n_batches * T;
         if (T_all >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
-        hopgnn_status rc = hopgnn_sample_dedup(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex,
-                                               p->level_start, p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, stream);
+        // with a workspace the caller keeps clean the compaction marks the presence map itself
+        uint8_t* dd_marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes, (int64_t)p->group * T,
+                                                                 p->graph.n_vertices, p->pg_algo)
+                                           : nullptr;
+        hopgnn_status rc = sample_dedup(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex, p->level_start,
+                                        p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, dd_marks, stream);
         if (rc != HOPGNN_OK) return rc;
-        rc = hopgnn_pregather(p->node_vertex, T_all, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
-                              p->pg_ws, p->pg_ws_bytes, stream);
+        if (dd_marks != nullptr)
+            rc = pregather_from_marks(p->node_vertex, T_all, p->graph.n_vertices, p->uniq, p->n_uniq, p->remap, p->pg_ws,
+                                      p->pg_ws_bytes, st);
+        else
+            rc = hopgnn_pregather(p->node_vertex, T_all, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
+                                  p->pg_ws, p->pg_ws_bytes, stream);
         if (rc != HOPGNN_OK) return rc;
         if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
             return HOPGNN_EHIP;

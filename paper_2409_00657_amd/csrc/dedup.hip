@@ -14,7 +14,7 @@
 //   dedup_scan     exclusive sums of the per-micrograph node counts, level by level
 //   dedup_compact  level-major global numbering: node vertices, CSR of child node indices
 //                  (parallel edges kept, -1 where a vertex has no neighbours), unused tails filled
-#include "common.hpp"
+#include "pregather_internal.hpp"
 
 namespace hopgnn {
 
@@ -208,7 +208,7 @@ dedup_compact(const int32_t* __restrict__ stage_nodes, const int32_t* __restrict
               const int32_t* __restrict__ cnt, const int32_t* __restrict__ mg_off,
               const int64_t* __restrict__ level_start, const int64_t* __restrict__ ent_start, int32_t n_seeds,
               DedupShape sh, int32_t* __restrict__ node_vertex, int32_t* __restrict__ indptr,
-              int32_t* __restrict__ idx) {
+              int32_t* __restrict__ idx, uint8_t* __restrict__ present) {
     const int32_t L = sh.n_layers, B = n_seeds;
     const int64_t T = sh.base[L + 1], S = sh.base[L];
     const int64_t t = (int64_t)blockIdx.x * kDdThreads + threadIdx.x;
@@ -225,7 +225,9 @@ dedup_compact(const int32_t* __restrict__ stage_nodes, const int32_t* __restrict
     if (i >= cnt[(int64_t)h * B + mg]) return;
     const int64_t local = (int64_t)mg_off[(int64_t)h * B + mg] + i;       // rank inside the level
     const int64_t gi = level_start[h] + local;
-    node_vertex[gi] = stage_nodes[t];
+    const int32_t vertex = stage_nodes[t];
+    node_vertex[gi] = vertex;
+    if (present != nullptr && vertex >= 0) present[vertex] = 1;     // the pre-gather's presence map
     if (h == L) return;
     const int32_t f = sh.f[h + 1];
     const int64_t e0 = ent_start[h] + local * f;
@@ -278,8 +280,16 @@ extern "C" size_t hopgnn_sample_dedup_ws_bytes(int32_t n_seeds, const int32_t* f
 
 extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
                                              int32_t seeds_per_key, const int32_t* fanouts, int32_t n_layers,
-                                             const uint64_t* keys, int32_t* node_vertex, int64_t* level_start, int32_t* indptr, int32_t* idx,
-                                             void* ws, size_t ws_bytes, void* stream) {
+                                             const uint64_t* keys, int32_t* node_vertex, int64_t* level_start,
+                                             int32_t* indptr, int32_t* idx, void* ws, size_t ws_bytes, void* stream) {
+    return sample_dedup(g, seeds, n_seeds, seeds_per_key, fanouts, n_layers, keys, node_vertex, level_start, indptr, idx,
+                        ws, ws_bytes, nullptr, stream);
+}
+
+hopgnn_status hopgnn::sample_dedup(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, int32_t seeds_per_key,
+                                   const int32_t* fanouts, int32_t n_layers, const uint64_t* keys, int32_t* node_vertex,
+                                   int64_t* level_start, int32_t* indptr, int32_t* idx, void* ws, size_t ws_bytes,
+                                   uint8_t* present, void* stream) {
     if (g == nullptr || fanouts == nullptr || n_seeds < 0 || seeds_per_key < 1) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(fanouts, n_layers);
     if (t_seed < 0) return HOPGNN_EINVAL;
@@ -346,7 +356,7 @@ extern "C" hopgnn_status hopgnn_sample_dedup(const hopgnn_csr* g, const int32_t*
     hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(dedup_compact, dim3((unsigned)ceil_div(T, kDdThreads)), dim3(kDdThreads), 0, s, stage_nodes,
-                       stage_child, cnt, mg_off, level_start, ent_start, n_seeds, sh, node_vertex, indptr, idx);
+                       stage_child, cnt, mg_off, level_start, ent_start, n_seeds, sh, node_vertex, indptr, idx, present);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }

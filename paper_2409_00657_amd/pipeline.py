@@ -403,6 +403,9 @@ class DedupPath:
         pl.node_vertex, pl.level_start = self.node_vertex.data_ptr(), self.level_start.data_ptr()
         pl.dd_idx, pl.dd_idx_l1 = self.idx.data_ptr(), self.idx_l1.data_ptr()
         pl.dd_ws, pl.dd_ws_bytes = self.dd_ws.data_ptr(), self.dd_ws.numel()
+        # every call of the library leaves the pre-gather workspace clean, so prepare it once
+        hb.hopgnn_pregather_ws_init(self.pg_ws, T, self.n_vertices, pg_algo)
+        pl.pg_ws_clean = 1
         self._keys = (ctypes.c_uint64 * self.n_keys)()
         self._lib = hb.load_library()
 
