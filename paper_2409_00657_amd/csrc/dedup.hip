@@ -328,7 +328,9 @@ hopgnn_status hopgnn::sample_dedup(const hopgnn_csr* g, const int32_t* seeds, in
     uint32_t cap = 1;
     while (cap < (uint32_t)sh.P[n_layers]) cap <<= 1;
     const size_t lds = (size_t)3 * cap * sizeof(uint32_t);
-    const int threads = cap >= 1024 ? 256 : (cap >= 256 ? 128 : 64);
+    // wide workgroups sort a long level faster, narrow ones keep more micrographs resident (a CU
+    // holds 2048 threads): 256 threads only while all micrographs still fit the chip at once
+    const int threads = cap >= 1024 && (cap >= 4096 || n_seeds <= 2048) ? 256 : (cap >= 256 ? 128 : 64);
     const void* off = g->offsets;
     const int32_t n_keys = (int32_t)ceil_div(n_seeds, seeds_per_key);
     for (int32_t k0 = 0; k0 < n_keys; k0 += kDdKeysPerLaunch) {     // 64 keys fit one launch's arguments
