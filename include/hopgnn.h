@@ -186,6 +186,39 @@ hopgnn_status hopgnn_sample_dedup(const hopgnn_csr *g /*HOST struct*/, const int
 hopgnn_status hopgnn_compose_idx(const int32_t *idx, int64_t n, const int32_t *map, int32_t *out, void *stream);
 
 /*
+ * Layer-wise sampling of micrographs (paper section 4 measures micrograph locality under node-wise
+ * and under layer-wise sampling; the paper gives no detail beyond naming the sampler, so this is the
+ * reading taken).  Per micrograph and hop h a budget of budgets[h-1] draws is made for the whole
+ * layer: position p_j = hash64(key, root, 0xFFFFFFFF, h, j) mod D in the concatenation of the
+ * neighbour lists of the previous level's nodes (node order, list order; D = its length), with
+ * replacement, so a vertex is drawn with probability proportional to the number of edges from the
+ * previous level into it.  The level's nodes are the distinct drawn vertices, ascending (none if
+ * D = 0).  Every edge between the two node sets is kept, each (node, node) pair once: the segment of
+ * a previous-level node lists, in ascending order, the level's nodes adjacent to it.
+ *
+ * Output in the layout of hopgnn_sample_dedup (level-major node numbering, level_start, CSR of node
+ * indices; the layers run through hopgnn_sage_fwd_dev in the same way), with segments of varying
+ * length and no -1 entries.  Capacities per seed come from hopgnn_layerwise_caps:
+ *   caps[0] nodes     = 1 + sum of the budgets           node_vertex [n_seeds * caps[0]], tail -1
+ *   caps[1] non-leaf  = caps[0] - the last budget        indptr [n_seeds * caps[1] + 1], tail = total
+ *   caps[2] entries   = sum of budgets[h-1] * budgets[h] (budgets[-1] = 1)
+ *                                                        idx [n_seeds * caps[2]], tail -1
+ * level_start DEVICE out int64 [n_layers + 2] as in hopgnn_sample_dedup; keys, seeds_per_key, ws
+ * (hopgnn_sample_layerwise_ws_bytes, 256-byte aligned) likewise.
+ * Limits: a budget is at most 1024 and the product of two consecutive budgets at most 65536, else
+ * HOPGNN_ERANGE (hopgnn_layerwise_caps reports it too; the ws size is then 0).  Other errors as
+ * hopgnn_sample.
+ */
+hopgnn_status hopgnn_layerwise_caps(const int32_t *budgets /*HOST*/, int32_t n_layers, int64_t *caps /*HOST out [3]*/);
+
+size_t hopgnn_sample_layerwise_ws_bytes(int32_t n_seeds, const int32_t *budgets /*HOST*/, int32_t n_layers);
+
+hopgnn_status hopgnn_sample_layerwise(const hopgnn_csr *g /*HOST struct*/, const int32_t *seeds, int32_t n_seeds,
+                                      int32_t seeds_per_key, const int32_t *budgets /*HOST*/, int32_t n_layers,
+                                      const uint64_t *keys /*HOST*/, int32_t *node_vertex, int64_t *level_start,
+                                      int32_t *indptr, int32_t *idx, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Prepares a pre-gather workspace once (zero presence map and counters; sizes and algo as in
  * hopgnn_pregather_ws_bytes).  hopgnn_pregather itself does not need it - it clears what it uses
  * - but every call of it, and every hopgnn_batch_fwd, leaves the workspace as this call does, so
@@ -427,6 +460,11 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  *                               [T - last level + 1], dd_idx and dd_idx_l1 [T - G*n_seeds], H[k] and
  *                               sage_ws for G times the rows, dd_ws of
  *                               hopgnn_sample_dedup_ws_bytes(G*n_seeds, ..).
+ *                               dedup = 2: the same sequence over layer-wise sampled micrographs
+ *                               (hopgnn_sample_layerwise, fanouts read as the budgets); with
+ *                               caps = hopgnn_layerwise_caps: node_vertex and remap [G*n_seeds*caps[0]],
+ *                               indptr [G*n_seeds*caps[1] + 1], dd_idx and dd_idx_l1
+ *                               [G*n_seeds*caps[2]], dd_ws of hopgnn_sample_layerwise_ws_bytes.
  *   merge_layers                nonzero: the group's micrographs are sampled as one level-major
  *                               batch (hopgnn_sample_merged, seeds_per_key = n_seeds) and every
  *                               layer is ONE hopgnn_sage_fwd over the whole group instead of one

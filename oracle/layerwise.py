@@ -86,5 +86,6 @@ def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights):
             ix = np.where(idx[:nnz] >= 0, remap[np.maximum(idx[:nnz], 0)], -1).astype(np.int32)
         else:
             self_idx, ix = None, idx[:nnz]
-        H = orc.sage_fwd(H, fmt, self_idx, indptr[:n_dst + 1], ix, *weights[k - 1], relu=(k < L))
-    return H
+        out = orc.sage_fwd(H, fmt, self_idx, indptr[:n_dst + 1], ix, *weights[k - 1], relu=(k < L))
+        H = orc.round_store(out, fmt)       # the next layer reads the rows as stored
+    return out

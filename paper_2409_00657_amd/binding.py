@@ -28,7 +28,8 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
            "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
-           "hopgnn_compose_idx", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_compose_idx", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
+           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
 class HopgnnError(RuntimeError):
@@ -132,6 +133,14 @@ def load_library() -> ctypes.CDLL:
                                       c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_sample_dedup_ws_bytes.restype = c.c_size_t
     L.hopgnn_sample_dedup_ws_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int32), c.c_int32]
+    L.hopgnn_layerwise_caps.restype = c.c_int
+    L.hopgnn_layerwise_caps.argtypes = [c.POINTER(c.c_int32), c.c_int32, c.POINTER(c.c_int64)]
+    L.hopgnn_sample_layerwise_ws_bytes.restype = c.c_size_t
+    L.hopgnn_sample_layerwise_ws_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int32), c.c_int32]
+    L.hopgnn_sample_layerwise.restype = c.c_int
+    L.hopgnn_sample_layerwise.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.c_int32, c.POINTER(c.c_int32),
+                                          c.c_int32, c.POINTER(c.c_uint64), c.c_void_p, c.c_void_p, c.c_void_p,
+                                          c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_sample_dedup.restype = c.c_int
     L.hopgnn_sample_dedup.argtypes = [c.POINTER(_Csr), c.c_void_p, c.c_int32, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
                                       c.POINTER(c.c_uint64), c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
@@ -440,6 +449,38 @@ def hopgnn_sample_dedup(offsets: torch.Tensor, indices: torch.Tensor, seeds: tor
                                             _ptr(level_start), _ptr(indptr), _ptr(idx), _ptr(ws),
                                             ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sample_dedup")
+
+
+def hopgnn_layerwise_caps(budgets: Sequence[int]):
+    """(nodes, non-leaf nodes, entries) one seed may need."""
+    caps = (ctypes.c_int64 * 3)()
+    _check(load_library().hopgnn_layerwise_caps(_fan(budgets), len(budgets), caps), "hopgnn_layerwise_caps")
+    return int(caps[0]), int(caps[1]), int(caps[2])
+
+
+def hopgnn_sample_layerwise_ws_bytes(n_seeds: int, budgets: Sequence[int]) -> int:
+    return int(load_library().hopgnn_sample_layerwise_ws_bytes(n_seeds, _fan(budgets), len(budgets)))
+
+
+def hopgnn_sample_layerwise(offsets: torch.Tensor, indices: torch.Tensor, seeds: torch.Tensor, budgets: Sequence[int],
+                            key, node_vertex: torch.Tensor, level_start: torch.Tensor, indptr: torch.Tensor,
+                            idx: torch.Tensor, ws: torch.Tensor, seeds_per_key: int = 0) -> None:
+    """`key`: one key for the whole batch, or a list with one key per block of seeds_per_key seeds."""
+    keys = list(key) if isinstance(key, (list, tuple)) else [key]
+    spk = seeds_per_key if seeds_per_key > 0 else max(seeds.numel(), 1)
+    if len(keys) != -(-seeds.numel() // spk) and seeds.numel() > 0:
+        raise HopgnnError("one key per block of seeds_per_key seeds")
+    karr = (ctypes.c_uint64 * max(len(keys), 1))(*[k & 0xFFFFFFFFFFFFFFFF for k in keys])
+    if offsets.dtype not in (torch.int32, torch.int64) or indices.dtype != torch.int32:
+        raise HopgnnError("offsets must be int32/int64 and indices int32")
+    if level_start.dtype != torch.int64 or level_start.numel() < len(budgets) + 2:
+        raise HopgnnError("level_start must hold n_layers + 2 int64 values")
+    g = _Csr(offsets.numel() - 1, indices.numel(), offsets.data_ptr(),
+             1 if offsets.dtype == torch.int64 else 0, indices.data_ptr())
+    rc = load_library().hopgnn_sample_layerwise(ctypes.byref(g), _ptr(seeds), seeds.numel(), spk, _fan(budgets),
+                                                len(budgets), karr, _ptr(node_vertex), _ptr(level_start), _ptr(indptr),
+                                                _ptr(idx), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_sample_layerwise")
 
 
 def hopgnn_compose_idx(idx: torch.Tensor, map_: torch.Tensor, out: torch.Tensor) -> None:

@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhopgnn.so")
-SOURCES = ["sample.hip", "pregather.hip", "gather.hip", "sage.hip", "sage_bwd.hip", "merge.hip", "batch.hip", "layers.hip", "dedup.hip"]
+SOURCES = ["sample.hip", "pregather.hip", "gather.hip", "sage.hip", "sage_bwd.hip", "merge.hip", "batch.hip", "layers.hip", "dedup.hip", "layerwise.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",

@@ -26,20 +26,41 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     const size_t es = dtype_size(p->dt);
     hipStream_t st = (hipStream_t)stream;
     if (p->dedup) {
-        // deduplicated frontiers: node counts depend on the data, so everything is sized for the
-        // slot tree and the layers read their row counts from level_start
-        if (p->layer_kind != 0) return HOPGNN_EINVAL;
+        // per-micrograph frontiers (1: node-wise draws kept once per level, 2: layer-wise sampling):
+        // node counts depend on the data, so everything is sized for the capacity and the layers
+        // read their row counts from level_start
+        if (p->layer_kind != 0 || p->dedup > 2) return HOPGNN_EINVAL;
         if (p->node_vertex == nullptr || p->level_start == nullptr || p->dd_idx == nullptr || p->dd_idx_l1 == nullptr)
             return HOPGNN_EINVAL;
+        const bool layerwise = p->dedup == 2;
         const int32_t B_all = n_batches * B;          // the call's batches form one merged batch
-        const int64_t T_all = (int64_t)n_batches * T;
-        if (T_all >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+        int64_t cap_level[kMaxLayers + 1];            // node capacity of level h, per seed
+        int64_t nodes_seed = 0, entries_seed = 0;
+        if (layerwise) {
+            int64_t caps[3];
+            const hopgnn_status rc_caps = hopgnn_layerwise_caps(p->fanouts, L, caps);
+            if (rc_caps != HOPGNN_OK) return rc_caps;
+            cap_level[0] = 1;
+            for (int h = 1; h <= L; ++h) cap_level[h] = p->fanouts[h - 1];
+            nodes_seed = caps[0];
+            entries_seed = caps[2];
+        } else {
+            for (int h = 0; h <= L; ++h) cap_level[h] = level[h] / B;
+            nodes_seed = t_seed;
+            entries_seed = t_seed - 1;
+        }
+        const int64_t T_all = nodes_seed * B_all;
+        if (T_all + (layerwise ? entries_seed * B_all : 0) >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
         // with a workspace the caller keeps clean the compaction marks the presence map itself
-        uint8_t* dd_marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes, (int64_t)p->group * T,
+        uint8_t* dd_marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes,
+                                                                 (int64_t)p->group * B * nodes_seed,
                                                                  p->graph.n_vertices, p->pg_algo)
                                            : nullptr;
-        hopgnn_status rc = sample_dedup(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex, p->level_start,
-                                        p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, dd_marks, stream);
+        hopgnn_status rc =
+            layerwise ? sample_layerwise(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex, p->level_start,
+                                         p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, dd_marks, stream)
+                      : sample_dedup(&p->graph, seeds, B_all, B, p->fanouts, L, keys, p->node_vertex, p->level_start,
+                                     p->indptr, p->dd_idx, p->dd_ws, p->dd_ws_bytes, dd_marks, stream);
         if (rc != HOPGNN_OK) return rc;
         if (dd_marks != nullptr)
             rc = pregather_from_marks(p->node_vertex, T_all, p->graph.n_vertices, p->uniq, p->n_uniq, p->remap, p->pg_ws,
@@ -55,14 +76,14 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         if (rc != HOPGNN_OK) return rc;
         if (p->mark_gather_end != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_end, st) != hipSuccess)
             return HOPGNN_EHIP;
-        rc = hopgnn_compose_idx(p->dd_idx, T_all - B_all, p->remap, p->dd_idx_l1, stream);
+        rc = hopgnn_compose_idx(p->dd_idx, entries_seed * B_all, p->remap, p->dd_idx_l1, stream);
         if (rc != HOPGNN_OK) return rc;
         const void* src = p->Xu;
         int64_t n_src = p->uniq_capacity;
         int32_t d_in = p->dim;
         for (int32_t k = 1; k <= L; ++k) {
-            int64_t n_dst = 0;                      // capacity: the slot tree's levels 0 .. L-k
-            for (int h = 0; h <= L - k; ++h) n_dst += level[h] * n_batches;
+            int64_t n_dst = 0;                      // capacity: levels 0 .. L-k
+            for (int h = 0; h <= L - k; ++h) n_dst += cap_level[h] * B_all;
             void* dst = k == L ? out : p->H[k - 1];
             if (dst == nullptr) return HOPGNN_EINVAL;
             rc = hopgnn_sage_fwd_dev(src, p->dt, n_src, d_in, k == 1 ? p->remap : nullptr, p->indptr,

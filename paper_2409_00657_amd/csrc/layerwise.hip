@@ -1,0 +1,426 @@
+// hopgnn_sample_layerwise: layer-wise sampling of micrographs (paper section 4 measures the
+// locality of micrographs under node-wise and under layer-wise sampling).  Per micrograph and hop
+// a budget of s_h draws is made for the WHOLE layer: uniformly, with replacement, over the
+// concatenated neighbour lists of the previous level's nodes, so a vertex is drawn with probability
+// proportional to the number of edges from the previous level into it.  The level's nodes are the
+// distinct drawn vertices in ascending order; every edge between the previous level's nodes and
+// them is kept, each (node, node) pair once.
+//
+//   lw_sample    one workgroup per micrograph; per hop: prefix sums of the previous level's degrees
+//                (LDS), the draws (position -> node by binary search in the prefix sums), an LDS
+//                bitonic sort + distinct, then ONE pass over the previous level's neighbour lists
+//                that looks every neighbour up in the new node list and sets a bit in an LDS
+//                (previous node x node) matrix; the rows of that matrix are the segments
+//   lw_scan      exclusive sums of the per-micrograph node and entry counts, level by level
+//   lw_compact   level-major global numbering: node vertices, CSR of node indices, tails filled
+#include "frontier_common.hpp"
+#include "pregather_internal.hpp"
+
+namespace hopgnn {
+
+constexpr int kLwThreads = 256;           // scan and compaction
+constexpr int kLwMaxLevel = 1024;         // largest budget of one level
+constexpr int kLwMaxPairs = 65536;        // largest product of two consecutive budgets
+constexpr int kLwKeysPerLaunch = 64;
+
+struct LwKeys {
+    uint64_t keyed[kLwKeysPerLaunch];     // first hash round already applied on the host
+};
+
+struct LwShape {
+    int32_t n_layers;
+    int32_t s[kMaxLayers + 1];            // node capacity of level h per micrograph; s[0] = 1
+    int32_t nbase[kMaxLayers + 2];        // first staging slot of level h's nodes; [L+1] = node capacity
+    int32_t ebase[kMaxLayers + 1];        // first staging slot of the entries of level h's nodes; [L] = entry capacity
+};
+
+struct LwLds {
+    uint32_t max_s, cap2, bit_words;
+    size_t bytes;
+};
+static LwLds lw_lds_layout(const LwShape& sh) {
+    LwLds l{};
+    for (int32_t h = 0; h <= sh.n_layers; ++h) l.max_s = (uint32_t)sh.s[h] > l.max_s ? (uint32_t)sh.s[h] : l.max_s;
+    l.cap2 = 1;
+    while (l.cap2 < l.max_s) l.cap2 <<= 1;
+    for (int32_t h = 0; h < sh.n_layers; ++h) {
+        const uint32_t w = (uint32_t)sh.s[h] * (((uint32_t)sh.s[h + 1] + 31) / 32);
+        l.bit_words = w > l.bit_words ? w : l.bit_words;
+    }
+    // pref (u64, max_s + 1) first for its alignment, then cur, nxt, rowoff (max_s + 1), srt, bits
+    l.bytes = (size_t)(l.max_s + 1) * 8 + ((size_t)3 * l.max_s + 1 + l.cap2 + l.bit_words) * 4;
+    return l;
+}
+
+template <typename OffT, int THREADS>
+__global__ void __launch_bounds__(THREADS)
+lw_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices, const int32_t* __restrict__ seeds,
+          int32_t n_seeds, LwShape sh, LwKeys keys, int32_t m_offset, int32_t seeds_per_key, uint32_t max_s, uint32_t cap2,
+          int32_t* __restrict__ stage_nodes, int32_t* __restrict__ stage_eoff, int32_t* __restrict__ stage_child,
+          int32_t* __restrict__ cnt, int32_t* __restrict__ ecnt) {
+    extern __shared__ uint64_t lw_lds[];
+    uint64_t* pref = lw_lds;                                             // exclusive degree sums, [n_cur + 1]
+    uint32_t* cur = reinterpret_cast<uint32_t*>(lw_lds + max_s + 1);     // previous level's nodes, ascending
+    uint32_t* nxt = cur + max_s;                                         // this level's nodes
+    uint32_t* rowoff = nxt + max_s;                                      // [n_cur + 1] entry offsets
+    uint32_t* srt = rowoff + max_s + 1;                                  // [cap2] drawn vertices
+    uint32_t* bits = srt + cap2;                                         // [n_cur x words] adjacency bits
+    __shared__ uint64_t lds8[THREADS / kWave];
+    __shared__ uint32_t lds4[THREADS / kWave];
+    const int32_t m = m_offset + (int32_t)blockIdx.x, B = n_seeds;
+    const uint64_t keyed = keys.keyed[blockIdx.x / (uint32_t)seeds_per_key];
+    const uint32_t tid = threadIdx.x;
+    const int32_t root = seeds[m];
+    // the micrograph's draws: hash(key, root, no vertex, hop, j)
+    const uint64_t rooted =
+        fr_finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | 0xFFFFFFFFull)) + 0x9E3779B97F4A7C15ull);
+    if (tid == 0) {
+        cur[0] = (uint32_t)root;
+        stage_nodes[m] = root;
+        cnt[m] = 1;
+    }
+    __syncthreads();
+    uint32_t n_cur = 1;
+    for (int32_t h = 1; h <= sh.n_layers; ++h) {
+        const uint32_t s_h = (uint32_t)sh.s[h];
+        // exclusive sums of the previous level's degrees
+        uint64_t carry = 0;
+        for (uint32_t i0 = 0; i0 < n_cur; i0 += THREADS) {
+            const uint32_t i = i0 + tid;
+            uint64_t deg = 0;
+            if (i < n_cur && (int32_t)cur[i] >= 0) {          // only a seed can be negative: no neighbours
+                const int64_t v = (int64_t)cur[i];
+                deg = (uint64_t)((int64_t)offsets[v + 1] - (int64_t)offsets[v]);
+            }
+            uint64_t total;
+            const uint64_t ex = carry + fr_block_scan<THREADS, uint64_t>(deg, lds8, total);
+            if (i < n_cur) pref[i] = ex;
+            carry += total;
+        }
+        const uint64_t D = carry;
+        if (tid == 0) pref[n_cur] = D;
+        __syncthreads();
+        int32_t* nodes_out = stage_nodes + sh.nbase[h] + (int64_t)m * s_h;
+        int32_t* eoff_out = stage_eoff + sh.nbase[h - 1] + (int64_t)m * sh.s[h - 1];
+        int32_t* child_out = stage_child + sh.ebase[h - 1] + (int64_t)m * sh.s[h - 1] * s_h;
+        if (D == 0) {          // no candidate (uniform over the workgroup): an empty level, empty segments
+            for (uint32_t i = tid; i < n_cur; i += THREADS) eoff_out[i] = 0;
+            if (tid == 0) {
+                cnt[(int64_t)h * B + m] = 0;
+                ecnt[(int64_t)(h - 1) * B + m] = 0;
+            }
+            __syncthreads();
+            n_cur = 0;
+            continue;
+        }
+        // the draws
+        uint32_t n2 = 1;
+        while (n2 < s_h) n2 <<= 1;
+        for (uint32_t j = tid; j < n2; j += THREADS) {
+            uint32_t v = kFrNone;
+            if (j < s_h) {
+                const uint64_t x = fr_finalise64((rooted ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
+                const uint64_t p = x % D;
+                uint32_t lo = 0, hi = n_cur;          // the last q with pref[q] <= p
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (pref[mid] <= p) lo = mid;
+                    else hi = mid;
+                }
+                v = (uint32_t)indices[(int64_t)offsets[(int64_t)cur[lo]] + (int64_t)(p - pref[lo])];
+            }
+            srt[j] = v;
+        }
+        __syncthreads();
+        fr_bitonic_sort<THREADS>(srt, n2);
+        const uint32_t n_next = fr_pack_distinct<THREADS>(srt, n2, nxt, lds4);
+        // adjacency bits between the two node lists: one pass over the previous level's lists
+        const uint32_t words = (s_h + 31) / 32;
+        for (uint32_t i = tid; i < n_cur * words; i += THREADS) bits[i] = 0;
+        __syncthreads();
+        for (uint64_t p = tid; p < D; p += THREADS) {
+            uint32_t lo = 0, hi = n_cur;
+            while (hi - lo > 1) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (pref[mid] <= p) lo = mid;
+                else hi = mid;
+            }
+            const uint32_t v = (uint32_t)indices[(int64_t)offsets[(int64_t)cur[lo]] + (int64_t)(p - pref[lo])];
+            const uint32_t pos = fr_lower_bound(nxt, n_next, v);
+            if (pos < n_next && nxt[pos] == v) atomicOr(&bits[lo * words + (pos >> 5)], 1u << (pos & 31));
+        }
+        __syncthreads();
+        // segment lengths and their exclusive sums
+        uint32_t ecarry = 0;
+        for (uint32_t i0 = 0; i0 < n_cur; i0 += THREADS) {
+            const uint32_t i = i0 + tid;
+            uint32_t c = 0;
+            if (i < n_cur)
+                for (uint32_t w = 0; w < words; ++w) c += (uint32_t)__popc(bits[i * words + w]);
+            uint32_t total;
+            const uint32_t ex = ecarry + fr_block_scan<THREADS, uint32_t>(c, lds4, total);
+            if (i < n_cur) {
+                rowoff[i] = ex;
+                eoff_out[i] = (int32_t)ex;
+            }
+            ecarry += total;
+        }
+        __syncthreads();
+        // the segments: set bits of every row in ascending position
+        for (uint32_t t = tid; t < n_cur * words; t += THREADS) {
+            const uint32_t q = t / words, w = t - q * words;
+            uint32_t word = bits[t];
+            if (word == 0) continue;
+            uint32_t at = rowoff[q];
+            for (uint32_t w2 = 0; w2 < w; ++w2) at += (uint32_t)__popc(bits[q * words + w2]);
+            while (word != 0) {
+                const uint32_t b = (uint32_t)__ffs((int)word) - 1;
+                child_out[at++] = (int32_t)(w * 32 + b);
+                word &= word - 1;
+            }
+        }
+        for (uint32_t i = tid; i < n_next; i += THREADS) nodes_out[i] = (int32_t)nxt[i];
+        if (tid == 0) {
+            cnt[(int64_t)h * B + m] = (int32_t)n_next;
+            ecnt[(int64_t)(h - 1) * B + m] = (int32_t)ecarry;
+        }
+        __syncthreads();
+        uint32_t* t = cur;
+        cur = nxt;
+        nxt = t;
+        n_cur = n_next;
+    }
+}
+
+// One workgroup: per level the exclusive sums of the micrographs' node counts and of the entry
+// counts of that level's nodes, the first node of every level and the first entry of every level.
+__global__ void __launch_bounds__(kLwThreads)
+lw_scan(const int32_t* __restrict__ cnt, const int32_t* __restrict__ ecnt, int32_t n_seeds, int32_t n_layers,
+        int32_t* __restrict__ mg_off, int32_t* __restrict__ mg_eoff, int64_t* __restrict__ level_start,
+        int64_t* __restrict__ ent_start) {
+    __shared__ uint32_t lds4[kLwThreads / kWave];
+    int64_t nodes = 0, ents = 0;
+    // thread t owns the contiguous run [t*per, (t+1)*per) of micrographs: sum it, scan the run sums
+    const int32_t per = (n_seeds + kLwThreads - 1) / kLwThreads;
+    const int32_t m0 = threadIdx.x * per, m1 = m0 + per < n_seeds ? m0 + per : n_seeds;
+    for (int32_t h = 0; h <= n_layers; ++h) {
+        if (threadIdx.x == 0) level_start[h] = nodes;
+        const int32_t* c = cnt + (int64_t)h * n_seeds;
+        uint32_t mine = 0, total;
+        for (int32_t mm = m0; mm < m1; ++mm) mine += (uint32_t)c[mm];
+        uint32_t run = fr_block_scan<kLwThreads, uint32_t>(mine, lds4, total);
+        for (int32_t mm = m0; mm < m1; ++mm) {
+            mg_off[(int64_t)h * n_seeds + mm] = (int32_t)run;
+            run += (uint32_t)c[mm];
+        }
+        nodes += total;
+        if (h == n_layers) break;
+        if (threadIdx.x == 0) ent_start[h] = ents;
+        const int32_t* e = ecnt + (int64_t)h * n_seeds;
+        mine = 0;
+        for (int32_t mm = m0; mm < m1; ++mm) mine += (uint32_t)e[mm];
+        run = fr_block_scan<kLwThreads, uint32_t>(mine, lds4, total);
+        for (int32_t mm = m0; mm < m1; ++mm) {
+            mg_eoff[(int64_t)h * n_seeds + mm] = (int32_t)run;
+            run += (uint32_t)e[mm];
+        }
+        ents += total;
+    }
+    if (threadIdx.x == 0) {
+        level_start[n_layers + 1] = nodes;
+        ent_start[n_layers] = ents;       // total entries
+    }
+}
+
+// One thread per staging slot: first the node slots (level h, micrograph, i-th node), then the
+// entry slots (level h of the source node, micrograph, i-th entry of that micrograph's level).
+__global__ void __launch_bounds__(kLwThreads)
+lw_compact(const int32_t* __restrict__ stage_nodes, const int32_t* __restrict__ stage_eoff,
+           const int32_t* __restrict__ stage_child, const int32_t* __restrict__ cnt, const int32_t* __restrict__ ecnt,
+           const int32_t* __restrict__ mg_off, const int32_t* __restrict__ mg_eoff,
+           const int64_t* __restrict__ level_start, const int64_t* __restrict__ ent_start, int32_t n_seeds, LwShape sh,
+           int32_t* __restrict__ node_vertex, int32_t* __restrict__ indptr, int32_t* __restrict__ idx,
+           uint8_t* __restrict__ present) {
+    const int32_t L = sh.n_layers, B = n_seeds;
+    const int64_t T = sh.nbase[L + 1], S = sh.nbase[L], E = sh.ebase[L];
+    const int64_t t = (int64_t)blockIdx.x * kLwThreads + threadIdx.x;
+    const int64_t n_nodes = level_start[L + 1], n_nonleaf = level_start[L], nnz = ent_start[L];
+    if (t < T) {
+        // unused tails: no vertex, empty segments
+        if (t >= n_nodes) node_vertex[t] = -1;
+        if (t >= n_nonleaf && t <= S) indptr[t] = (int32_t)nnz;
+        int32_t h = 0;
+        while (h < L && t >= sh.nbase[h + 1]) ++h;
+        const int64_t o = t - sh.nbase[h];
+        const int32_t mg = (int32_t)(o / sh.s[h]), i = (int32_t)(o - (int64_t)mg * sh.s[h]);
+        if (i >= cnt[(int64_t)h * B + mg]) return;
+        const int64_t gi = level_start[h] + mg_off[(int64_t)h * B + mg] + i;
+        const int32_t vertex = stage_nodes[t];
+        node_vertex[gi] = vertex;
+        if (present != nullptr && vertex >= 0) present[vertex] = 1;          // the pre-gather's presence map
+        if (h < L) indptr[gi] = (int32_t)(ent_start[h] + mg_eoff[(int64_t)h * B + mg] + stage_eoff[t]);
+        return;
+    }
+    const int64_t e = t - T;
+    if (e >= E) return;
+    if (e >= nnz) idx[e] = -1;                                // unused tail
+    int32_t h = 0;
+    while (h < L - 1 && e >= sh.ebase[h + 1]) ++h;
+    const int64_t o = e - sh.ebase[h];
+    const int64_t per = (int64_t)sh.s[h] * sh.s[h + 1];
+    const int32_t mg = (int32_t)(o / per), i = (int32_t)(o - (int64_t)mg * per);
+    if (i >= ecnt[(int64_t)h * B + mg]) return;
+    idx[ent_start[h] + mg_eoff[(int64_t)h * B + mg] + i] =
+        (int32_t)(level_start[h + 1] + mg_off[(int64_t)(h + 1) * B + mg] + stage_child[e]);
+}
+
+struct LwWs {
+    size_t nodes_bytes, eoff_bytes, child_bytes, cnt_bytes, ecnt_bytes, ent_start_bytes, total;
+};
+static LwWs lw_ws_layout(int64_t T, int64_t S, int64_t E, int64_t B, int32_t L) {
+    LwWs W{};
+    W.nodes_bytes = align_up((size_t)T * 4, 256);
+    W.eoff_bytes = align_up((size_t)S * 4, 256);
+    W.child_bytes = align_up((size_t)E * 4, 256);
+    W.cnt_bytes = align_up((size_t)(L + 1) * B * 4, 256);          // once for cnt, once for mg_off
+    W.ecnt_bytes = align_up((size_t)L * B * 4, 256);               // once for ecnt, once for mg_eoff
+    W.ent_start_bytes = align_up((size_t)(L + 1) * 8, 256);
+    W.total = W.nodes_bytes + W.eoff_bytes + W.child_bytes + 2 * W.cnt_bytes + 2 * W.ecnt_bytes + W.ent_start_bytes;
+    return W;
+}
+
+// Per-seed capacities; false if a budget is out of range.
+static bool lw_caps(const int32_t* budgets, int32_t n_layers, int64_t caps[3]) {
+    if (budgets == nullptr || n_layers < 1 || n_layers > kMaxLayers) return false;
+    int64_t nodes = 1, nonleaf = 0, entries = 0, prev = 1;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        const int64_t s = budgets[h - 1];
+        if (s < 1 || s > kLwMaxLevel || prev * s > kLwMaxPairs) return false;
+        nonleaf += prev;
+        entries += prev * s;
+        nodes += s;
+        prev = s;
+    }
+    caps[0] = nodes;
+    caps[1] = nonleaf;
+    caps[2] = entries;
+    return true;
+}
+
+static uint64_t lw_host_finalise64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+}  // namespace hopgnn
+
+using namespace hopgnn;
+
+extern "C" hopgnn_status hopgnn_layerwise_caps(const int32_t* budgets, int32_t n_layers, int64_t* caps) {
+    if (caps == nullptr) return HOPGNN_EINVAL;
+    if (budgets == nullptr || n_layers < 1 || n_layers > kMaxLayers) return HOPGNN_EINVAL;
+    for (int32_t h = 0; h < n_layers; ++h)
+        if (budgets[h] < 1) return HOPGNN_EINVAL;
+    return lw_caps(budgets, n_layers, caps) ? HOPGNN_OK : HOPGNN_ERANGE;
+}
+
+extern "C" size_t hopgnn_sample_layerwise_ws_bytes(int32_t n_seeds, const int32_t* budgets, int32_t n_layers) {
+    int64_t caps[3];
+    if (n_seeds < 0 || !lw_caps(budgets, n_layers, caps)) return 0;
+    return lw_ws_layout(caps[0] * n_seeds, caps[1] * n_seeds, caps[2] * n_seeds, n_seeds, n_layers).total;
+}
+
+extern "C" hopgnn_status hopgnn_sample_layerwise(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds,
+                                                 int32_t seeds_per_key, const int32_t* budgets, int32_t n_layers,
+                                                 const uint64_t* keys, int32_t* node_vertex, int64_t* level_start,
+                                                 int32_t* indptr, int32_t* idx, void* ws, size_t ws_bytes, void* stream) {
+    return sample_layerwise(g, seeds, n_seeds, seeds_per_key, budgets, n_layers, keys, node_vertex, level_start, indptr,
+                            idx, ws, ws_bytes, nullptr, stream);
+}
+
+hopgnn_status hopgnn::sample_layerwise(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, int32_t seeds_per_key,
+                                       const int32_t* budgets, int32_t n_layers, const uint64_t* keys,
+                                       int32_t* node_vertex, int64_t* level_start, int32_t* indptr, int32_t* idx, void* ws,
+                                       size_t ws_bytes, uint8_t* present, void* stream) {
+    if (g == nullptr || n_seeds < 0 || seeds_per_key < 1) return HOPGNN_EINVAL;
+    int64_t caps[3];
+    hopgnn_status rc = hopgnn_layerwise_caps(budgets, n_layers, caps);
+    if (rc != HOPGNN_OK) return rc;
+    if (g->n_vertices < 0 || g->n_edges < 0 || g->n_vertices > ((int64_t)1 << 31)) return HOPGNN_EINVAL;
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (g->offsets == nullptr || seeds == nullptr || keys == nullptr || node_vertex == nullptr || level_start == nullptr ||
+        indptr == nullptr || idx == nullptr || ws == nullptr)
+        return HOPGNN_EINVAL;
+    if (g->n_edges > 0 && g->indices == nullptr) return HOPGNN_EINVAL;
+    const int64_t T = caps[0] * n_seeds, S = caps[1] * n_seeds, E = caps[2] * n_seeds;
+    if (T + E >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if (!aligned(ws, 256)) return HOPGNN_EINVAL;
+
+    LwShape sh{};
+    sh.n_layers = n_layers;
+    sh.s[0] = 1;
+    sh.nbase[0] = 0;
+    sh.ebase[0] = 0;
+    for (int32_t h = 1; h <= n_layers; ++h) {
+        sh.s[h] = budgets[h - 1];
+        sh.nbase[h] = sh.nbase[h - 1] + n_seeds * sh.s[h - 1];
+        sh.ebase[h] = sh.ebase[h - 1] + n_seeds * sh.s[h - 1] * sh.s[h];
+    }
+    sh.nbase[n_layers + 1] = sh.nbase[n_layers] + n_seeds * sh.s[n_layers];
+
+    const LwWs W = lw_ws_layout(T, S, E, n_seeds, n_layers);
+    if (ws_bytes < W.total) return HOPGNN_ENOMEM_WS;
+    char* p = static_cast<char*>(ws);
+    int32_t* stage_nodes = reinterpret_cast<int32_t*>(p);
+    p += W.nodes_bytes;
+    int32_t* stage_eoff = reinterpret_cast<int32_t*>(p);
+    p += W.eoff_bytes;
+    int32_t* stage_child = reinterpret_cast<int32_t*>(p);
+    p += W.child_bytes;
+    int32_t* cnt = reinterpret_cast<int32_t*>(p);
+    p += W.cnt_bytes;
+    int32_t* mg_off = reinterpret_cast<int32_t*>(p);
+    p += W.cnt_bytes;
+    int32_t* ecnt = reinterpret_cast<int32_t*>(p);
+    p += W.ecnt_bytes;
+    int32_t* mg_eoff = reinterpret_cast<int32_t*>(p);
+    p += W.ecnt_bytes;
+    int64_t* ent_start = reinterpret_cast<int64_t*>(p);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const LwLds lds = lw_lds_layout(sh);
+    // most of a micrograph's work is the pass over its previous level's neighbour lists, whose
+    // length follows the degrees: wide workgroups while all micrographs still fit the chip at once
+    const int threads = n_seeds <= 2048 ? 256 : 128;
+    const void* off = g->offsets;
+    const int32_t n_keys = (int32_t)ceil_div(n_seeds, seeds_per_key);
+    for (int32_t k0 = 0; k0 < n_keys; k0 += kLwKeysPerLaunch) {     // 64 keys fit one launch's arguments
+        const int32_t nk = n_keys - k0 < kLwKeysPerLaunch ? n_keys - k0 : kLwKeysPerLaunch;
+        LwKeys lk{};
+        for (int32_t i = 0; i < nk; ++i) lk.keyed[i] = lw_host_finalise64(keys[k0 + i] + 0x9E3779B97F4A7C15ull);
+        const int64_t m0 = (int64_t)k0 * seeds_per_key;
+        const int64_t count = (int64_t)nk * seeds_per_key < n_seeds - m0 ? (int64_t)nk * seeds_per_key : n_seeds - m0;
+#define HOPGNN_LW_LAUNCH(OffT, THREADS)                                                                               \
+    hipLaunchKernelGGL((lw_sample<OffT, THREADS>), dim3((unsigned)count), dim3(THREADS), lds.bytes, s,               \
+                       static_cast<const OffT*>(off), g->indices, seeds, n_seeds, sh, lk, (int32_t)m0, seeds_per_key, \
+                       lds.max_s, lds.cap2, stage_nodes, stage_eoff, stage_child, cnt, ecnt)
+        if (g->offsets_i64) {
+            if (threads == 256) HOPGNN_LW_LAUNCH(int64_t, 256);
+            else HOPGNN_LW_LAUNCH(int64_t, 128);
+        } else {
+            if (threads == 256) HOPGNN_LW_LAUNCH(int32_t, 256);
+            else HOPGNN_LW_LAUNCH(int32_t, 128);
+        }
+#undef HOPGNN_LW_LAUNCH
+        HOPGNN_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(lw_scan, dim3(1), dim3(kLwThreads), 0, s, cnt, ecnt, n_seeds, n_layers, mg_off, mg_eoff,
+                       level_start, ent_start);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(lw_compact, dim3((unsigned)ceil_div(T + E, kLwThreads)), dim3(kLwThreads), 0, s, stage_nodes,
+                       stage_eoff, stage_child, cnt, ecnt, mg_off, mg_eoff, level_start, ent_start, n_seeds, sh,
+                       node_vertex, indptr, idx, present);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}

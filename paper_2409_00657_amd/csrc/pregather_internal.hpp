@@ -32,4 +32,10 @@ hopgnn_status sample_dedup(const hopgnn_csr* g, const int32_t* seeds, int32_t n_
                            int64_t* level_start, int32_t* indptr, int32_t* idx, void* ws, size_t ws_bytes,
                            uint8_t* present, void* stream);
 
+// hopgnn_sample_layerwise with the same optional marking.
+hopgnn_status sample_layerwise(const hopgnn_csr* g, const int32_t* seeds, int32_t n_seeds, int32_t seeds_per_key,
+                               const int32_t* budgets, int32_t n_layers, const uint64_t* keys, int32_t* node_vertex,
+                               int64_t* level_start, int32_t* indptr, int32_t* idx, void* ws, size_t ws_bytes,
+                               uint8_t* present, void* stream);
+
 }  // namespace hopgnn

@@ -41,6 +41,30 @@ class BatchShape:
     def nnz(self, layer: int) -> int:
         return sum(self.levels[1: self.n_layers - layer + 2])
 
+    @property
+    def n_entries(self) -> int:
+        """Entries of the whole tree's neighbour lists: one per slot below the roots."""
+        return self.n_slots - self.n_seeds
+
+
+@dataclass
+class LayerwiseShape:
+    """Capacities of layer-wise sampled micrographs for B seeds: `fanouts` holds the budget of
+    draws per level, so level h has at most fanouts[h-1] nodes per micrograph."""
+    n_seeds: int
+    fanouts: List[int]
+
+    def __post_init__(self):
+        self.n_layers = len(self.fanouts)
+        per = [1] + [int(s) for s in self.fanouts]
+        self.levels = [self.n_seeds * s for s in per]
+        self.n_slots = sum(self.levels)
+        self.n_nonleaf = self.n_slots - self.levels[-1]
+        self.n_entries = self.n_seeds * sum(a * b for a, b in zip(per[:-1], per[1:]))
+
+    def n_dst(self, layer: int) -> int:
+        return sum(self.levels[: self.n_layers - layer + 1])
+
 
 class HotPath:
     """Pre-allocated device buffers for groups of `group` batches of one shape."""
@@ -351,22 +375,27 @@ class DedupPath:
     every buffer has the slot tree's size and the layers take their row counts from the device."""
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor, weights, n_seeds: int,
-                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO, group: int = 1):
-        """`group` batches of n_seeds seeds form one merged batch (block b draws with key b)."""
+                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO, group: int = 1, sampler: str = "node"):
+        """`group` batches of n_seeds seeds form one merged batch (block b draws with key b).
+        sampler "node": the node-wise draws of the slot tree, every (level, vertex) kept once;
+        "layer": layer-wise sampling, `fanouts` then holds the budget of draws per level."""
+        if sampler not in ("node", "layer"):
+            raise hb.HopgnnError("sampler must be node or layer")
+        self.sampler = sampler
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
         self.n_keys, self.seeds_per_key = group, n_seeds
         n_seeds = n_seeds * group
-        self.shape = sh = BatchShape(n_seeds, list(fanouts))
-        T, S, B, L = sh.n_slots, sh.n_nonleaf, n_seeds, sh.n_layers
+        self.shape = sh = (BatchShape if sampler == "node" else LayerwiseShape)(n_seeds, list(fanouts))
+        T, S, B, L, E = sh.n_slots, sh.n_nonleaf, n_seeds, sh.n_layers, max(sh.n_entries, 1)
         self.capacity = T
         i32 = dict(dtype=torch.int32, device=dev)
         self.node_vertex = torch.empty(T, **i32)
         self.level_start = torch.zeros(L + 2, dtype=torch.int64, device=dev)
         self.indptr = torch.empty(S + 1, **i32)
-        self.idx = torch.empty(max(T - B, 1), **i32)
-        self.idx_l1 = torch.empty(max(T - B, 1), **i32)      # the first layer's list: positions in Xu
+        self.idx = torch.empty(E, **i32)
+        self.idx_l1 = torch.empty(E, **i32)      # the first layer's list: positions in Xu
         self.remap = torch.empty(T, **i32)
         self.cap = min(T, self.n_vertices)
         self.uniq = torch.empty(self.cap, **i32)
@@ -374,7 +403,8 @@ class DedupPath:
         self.Xu = torch.empty((self.cap, X.shape[1]), dtype=X.dtype, device=dev)
         self.pg_algo = pg_algo
         self.pg_ws = torch.empty(hb.hopgnn_pregather_ws_bytes(T, self.n_vertices, pg_algo), dtype=torch.uint8, device=dev)
-        self.dd_ws = torch.empty(hb.hopgnn_sample_dedup_ws_bytes(B, list(fanouts)), dtype=torch.uint8, device=dev)
+        ws_bytes = (hb.hopgnn_sample_dedup_ws_bytes if sampler == "node" else hb.hopgnn_sample_layerwise_ws_bytes)
+        self.dd_ws = torch.empty(ws_bytes(B, list(fanouts)), dtype=torch.uint8, device=dev)
         hidden = weights[0][0].shape[1]
         self.H = [torch.empty((sh.n_dst(k), hidden), dtype=X.dtype, device=dev) for k in range(1, L + 1)]
         self.sage_ws = torch.empty(max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0], hidden)
@@ -394,7 +424,7 @@ class DedupPath:
             pl.W_self[i], pl.W_neigh[i] = Ws.data_ptr(), Wn.data_ptr()
             pl.bias[i] = None if bias is None else bias.data_ptr()
             pl.H[i] = self.H[i].data_ptr()
-        pl.pg_algo, pl.group, pl.dedup = pg_algo, self.n_keys, 1
+        pl.pg_algo, pl.group, pl.dedup = pg_algo, self.n_keys, 1 if sampler == "node" else 2
         pl.indptr, pl.uniq, pl.uniq_capacity, pl.n_uniq = self.indptr.data_ptr(), self.uniq.data_ptr(), self.cap, \
             self.n_uniq.data_ptr()
         pl.remap, pl.Xu = self.remap.data_ptr(), self.Xu.data_ptr()
@@ -436,9 +466,9 @@ class DedupPath:
 
     # the steps, all on torch's current stream
     def sample(self, seeds: torch.Tensor, key) -> None:
-        hb.hopgnn_sample_dedup(self.offsets, self.indices, seeds, self.shape.fanouts, self._key_list(key),
-                               self.node_vertex, self.level_start, self.indptr, self.idx, self.dd_ws,
-                               seeds_per_key=self.seeds_per_key)
+        fn = hb.hopgnn_sample_dedup if self.sampler == "node" else hb.hopgnn_sample_layerwise
+        fn(self.offsets, self.indices, seeds, self.shape.fanouts, self._key_list(key), self.node_vertex,
+           self.level_start, self.indptr, self.idx, self.dd_ws, seeds_per_key=self.seeds_per_key)
 
     def pregather(self) -> None:
         hb.hopgnn_pregather(self.node_vertex, self.n_vertices, self.uniq, self.n_uniq, self.remap, self.pg_ws,

@@ -124,6 +124,41 @@ def test_newer_entry_points_reject_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_ws_bytes(5, 100, 8, 8, 1) == 0
 
 
+def test_layerwise_capacities_and_errors(lib):
+    c = ctypes
+    from paper_2409_00657_amd import binding as hb
+    assert hb.hopgnn_layerwise_caps([10, 25]) == (36, 11, 260)
+    assert hb.hopgnn_layerwise_caps([7]) == (8, 1, 7)
+    assert hb.hopgnn_layerwise_caps([4, 3, 2]) == (10, 8, 4 + 12 + 6)
+    caps = (c.c_int64 * 3)()
+    ok = (c.c_int32 * 2)(10, 25)
+    assert lib.hopgnn_layerwise_caps(ok, 2, None) == 1
+    assert lib.hopgnn_layerwise_caps(None, 2, caps) == 1
+    assert lib.hopgnn_layerwise_caps(ok, 0, caps) == 1
+    assert lib.hopgnn_layerwise_caps(ok, 9, caps) == 1
+    assert lib.hopgnn_layerwise_caps((c.c_int32 * 2)(10, 0), 2, caps) == 1
+    assert lib.hopgnn_layerwise_caps((c.c_int32 * 1)(1025), 1, caps) == 3            # a budget above 1024
+    assert lib.hopgnn_layerwise_caps((c.c_int32 * 2)(300, 300), 2, caps) == 3        # 90000 pairs
+    assert lib.hopgnn_layerwise_caps((c.c_int32 * 2)(256, 256), 2, caps) == 0
+    assert lib.hopgnn_sample_layerwise_ws_bytes(4, (c.c_int32 * 2)(300, 300), 2) == 0
+    assert lib.hopgnn_sample_layerwise_ws_bytes(-1, ok, 2) == 0
+    assert lib.hopgnn_sample_layerwise_ws_bytes(100, ok, 2) >= 100 * (36 + 11 + 260) * 4
+    one = c.c_void_p(256)
+    keys = (c.c_uint64 * 1)(1)
+    g = hb._Csr(10, 20, 8, 0, 8)
+    args = (keys, one, one, one, one, one, 1 << 30, None)
+    assert lib.hopgnn_sample_layerwise(None, one, 4, 4, ok, 2, *args) == 1
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 4, 0, ok, 2, *args) == 1          # seeds_per_key < 1
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, -1, 4, ok, 2, *args) == 1
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 0, 4, ok, 2, *args) == 0          # no seeds
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 4, 4, (c.c_int32 * 2)(300, 300), 2, *args) == 3
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 4, 4, ok, 2, None, one, one, one, one, one, 1 << 30, None) == 1
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 4, 4, ok, 2, keys, one, one, one, one, one, 16, None) == 2
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 4, 4, ok, 2, keys, one, one, one, one, c.c_void_p(8), 1 << 30,
+                                       None) == 1                                         # workspace not aligned
+    assert lib.hopgnn_sample_layerwise(c.byref(g), one, 8000000, 4, ok, 2, *args) == 3    # 2^31 staging slots
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     from paper_2409_00657_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

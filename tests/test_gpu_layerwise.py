@@ -1,0 +1,134 @@
+"""GPU parity of the layer-wise sampler (bit-exact against the oracle) and of the layer chain over
+its micrographs."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+from oracle import layerwise as orc_lw
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2409_00657_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _run_sampler(hb, g, seeds, budgets, key, seeds_per_key=0):
+    B = seeds.numel()
+    nodes, nonleaf, entries = hb.hopgnn_layerwise_caps(budgets)
+    T, S, E = B * nodes, B * nonleaf, B * entries
+    i32 = dict(dtype=torch.int32, device=DEV)
+    nv = torch.full((T,), -9, **i32)
+    ls = torch.full((len(budgets) + 2,), -9, dtype=torch.int64, device=DEV)
+    ip = torch.full((S + 1,), -9, **i32)
+    ix = torch.full((E,), -9, **i32)
+    ws = torch.empty(hb.hopgnn_sample_layerwise_ws_bytes(B, budgets), dtype=torch.uint8, device=DEV)
+    ws.fill_(0x5A)
+    hb.hopgnn_sample_layerwise(g.offsets, g.indices, seeds, budgets, key, nv, ls, ip, ix, ws, seeds_per_key=seeds_per_key)
+    torch.cuda.synchronize()
+    return nv, ls, ip, ix, T, S, E
+
+
+def _check_against(nv, ls, ip, ix, T, S, E, ref):
+    r_nv, r_ls, r_ip, r_ix = ref
+    np.testing.assert_array_equal(ls.cpu().numpy(), r_ls)
+    n_nodes, n_nonleaf, nnz = len(r_nv), int(r_ls[-2]), len(r_ix)
+    np.testing.assert_array_equal(nv[:n_nodes].cpu().numpy(), r_nv)
+    assert bool((nv[n_nodes:] == -1).all())
+    np.testing.assert_array_equal(ip[:n_nonleaf + 1].cpu().numpy(), r_ip)
+    assert bool((ip[n_nonleaf:] == nnz).all())
+    np.testing.assert_array_equal(ix[:nnz].cpu().numpy(), r_ix)
+    assert bool((ix[nnz:] == -1).all())
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_sample_layerwise_bit_exact(hb, case):
+    from paper_2409_00657_amd import synth
+    graphs = [lambda: synth.uniform_graph(500, 1, 6, seed=3, device=DEV),
+              lambda: synth.rmat_graph(11, 8.0, seed=4, device=DEV),
+              lambda: synth.chung_lu_graph(3000, 12.0, 2.1, seed=5, device=DEV, offsets_i64=True),
+              lambda: synth.rmat_graph(10, 3.0, seed=6, device=DEV, offsets_i64=True),
+              lambda: synth.uniform_graph(40, 1, 3, seed=7, device=DEV),
+              lambda: synth.rmat_graph(12, 16.0, seed=8, device=DEV),
+              lambda: synth.rmat_graph(11, 6.0, seed=9, device=DEV),
+              lambda: synth.rmat_graph(10, 12.0, seed=10, device=DEV)]
+    buds = [[5, 5], [10, 25], [15, 10, 5], [4, 3, 2, 2], [7], [16, 40, 100], [1, 1, 1, 1, 1], [300, 200]]
+    Bs = [64, 100, 33, 50, 300, 20, 130, 9]
+    g = graphs[case]()
+    bud, B = buds[case], Bs[case]
+    seeds = synth.seeds(g.n_vertices, B, case, device=DEV)
+    key = 2000 + case
+    out = _run_sampler(hb, g, seeds, bud, key)
+    ref = orc_lw.sample_layerwise(g.offsets.cpu().numpy(), g.indices.cpu().numpy(), seeds.cpu().numpy(), bud, key)
+    _check_against(*out, ref)
+    assert len(ref[0]) <= out[4]
+
+
+def test_keys_per_block_of_seeds(hb):
+    """More blocks than one launch carries keys for; micrograph m draws with keys[m // seeds_per_key]."""
+    from paper_2409_00657_amd import synth
+    g = synth.rmat_graph(11, 8.0, seed=12, device=DEV)
+    B, G, bud = 7, 70, [4, 6]
+    seeds = synth.seeds(g.n_vertices, B * G, 5, device=DEV)
+    keys = [500 + 7 * b for b in range(G)]
+    out = _run_sampler(hb, g, seeds, bud, keys, seeds_per_key=B)
+    per_mg = [k for k in keys for _ in range(B)]
+    ref = orc_lw.sample_layerwise(g.offsets.cpu().numpy(), g.indices.cpu().numpy(), seeds.cpu().numpy(), bud, per_mg)
+    _check_against(*out, ref)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("budgets", [[6, 12], [5, 8, 10]])
+def test_layers_over_layerwise_micrographs(hb, orc, dt, budgets):
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    g = synth.rmat_graph(12, 10.0, device=DEV)
+    n, d, hidden, B, L = g.n_vertices, 24, 40, 60, len(budgets)
+    X = synth.features(n, d, dt, device=DEV)
+    W = synth.sage_weights(d, hidden, L, dt, device=DEV, bias=True)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, budgets, sampler="layer")
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    for it in range(2):
+        seeds = synth.seeds(n, B, 40 + it, device=DEV)
+        out = dp.run_batch(seeds, 600 + it).clone()
+        torch.cuda.synchronize()
+        # the same sequence from one library call: the same bits
+        out2 = torch.full_like(out, float("nan"))
+        dp.remap.fill_(-7)
+        dp.forward(seeds, 600 + it, out2)
+        torch.cuda.synchronize()
+        assert to_bits(out2).tobytes() == to_bits(out).tobytes()
+        nv, ls, ip, ix = orc_lw.sample_layerwise(off_np, idx_np, seeds.cpu().numpy(), budgets, 600 + it)
+        ref = orc_lw.layer_chain(orc, to_bits(X), ORC_DT[dt], nv, ls, ip, ix, weights_bits(W))
+        assert rel_err(to_f64(out), ref) <= TOL[dt] * L
+        uniq, _ = orc.pregather(nv)
+        U = int(dp.n_uniq.item())
+        assert U == len(uniq)
+        np.testing.assert_array_equal(dp.uniq[:U].cpu().numpy(), uniq)
+
+
+def test_grouped_layerwise_single_call(hb, orc):
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    g = synth.rmat_graph(12, 10.0, device=DEV)
+    n, d, hidden, B, G, bud = g.n_vertices, 16, 24, 10, 5, [4, 6]
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    seeds = synth.seeds(n, B * G, 78, device=DEV)
+    keys = [700 + 3 * b for b in range(G)]
+    X = synth.features(n, d, torch.float32, device=DEV)
+    W = synth.sage_weights(d, hidden, 2, torch.float32, device=DEV)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, bud, group=G, sampler="layer")
+    out = torch.empty((G * B, hidden), device=DEV)
+    for rep in range(2):            # twice: the workspace is left clean
+        dp.forward(seeds, keys, out)
+        torch.cuda.synchronize()
+        for b in range(G):
+            sb = seeds[b * B:(b + 1) * B].cpu().numpy()
+            nv, ls, ip, ix = orc_lw.sample_layerwise(off_np, idx_np, sb, bud, keys[b])
+            ref = orc_lw.layer_chain(orc, to_bits(X), 0, nv, ls, ip, ix, weights_bits(W))
+            assert rel_err(to_f64(out[b * B:(b + 1) * B]), ref) <= 2e-5, b
