@@ -55,6 +55,8 @@ def parse():
     ap.add_argument("--dedup", action="store_true",
                     help="sample per-micrograph deduplicated frontiers (hopgnn_sample_dedup): the same rows for the "
                          "seeds over fewer rows below them; one batch per pre-gather, forward only")
+    ap.add_argument("--layerwise", action="store_true",
+                    help="layer-wise sampled micrographs (the shape's fanouts are the budgets of draws per level)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     return ap.parse_args()
@@ -124,7 +126,9 @@ def main_dedup(args):
     W = cfg.make_weights(device=dev)
     n_streams = max(1, args.streams)
     group = args.group or cfg.groups[0]
-    dps = [DedupPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group) for _ in range(n_streams)]
+    sampler = "layer" if args.layerwise else "node"
+    dps = [DedupPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, sampler=sampler)
+           for _ in range(n_streams)]
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     n_total = args.warmup + args.steps
     seeds = [torch.cat([synth.seeds(cfg.n_vertices, cfg.batch, i * group + b, device=dev) for b in range(group)])
@@ -187,7 +191,7 @@ def main_dedup(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges, "feature_dim": cfg.d,
                    "batch": cfg.batch, "fanouts": cfg.fanouts, "hidden": cfg.hidden, "group": group, "streams": n_streams,
-                   "deduplicated_frontiers": True, "slots_per_batch": dp.capacity // group},
+                   "deduplicated_frontiers": True, "sampler": sampler + "-wise", "slots_per_batch": dp.capacity // group},
         "unique_rows_per_step": U_avg, "nodes_per_step": nodes_sum / n_replay,
         "nodes_over_slots": nodes_sum / n_replay / dp.capacity,
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
@@ -209,7 +213,7 @@ def main():
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    if args.dedup:
+    if args.dedup or args.layerwise:
         if args.backward or args.model != "sage":
             print("bench.py: --dedup runs the GraphSAGE forward path", file=sys.stderr)
             sys.exit(2)

@@ -22,6 +22,7 @@ constexpr int kLwThreads = 256;           // scan and compaction
 constexpr int kLwMaxLevel = 1024;         // largest budget of one level
 constexpr int kLwMaxPairs = 65536;        // largest product of two consecutive budgets
 constexpr int kLwKeysPerLaunch = 64;
+constexpr int kLwUnroll = 4;              // neighbour loads in flight per thread in the adjacency pass
 
 struct LwKeys {
     uint64_t keyed[kLwKeysPerLaunch];     // first hash round already applied on the host
@@ -35,7 +36,7 @@ struct LwShape {
 };
 
 struct LwLds {
-    uint32_t max_s, cap2, bit_words;
+    uint32_t max_s, cap2, bit_words, filt_words;
     size_t bytes;
 };
 static LwLds lw_lds_layout(const LwShape& sh) {
@@ -47,8 +48,11 @@ static LwLds lw_lds_layout(const LwShape& sh) {
         const uint32_t w = (uint32_t)sh.s[h] * (((uint32_t)sh.s[h + 1] + 31) / 32);
         l.bit_words = w > l.bit_words ? w : l.bit_words;
     }
-    // pref (u64, max_s + 1) first for its alignment, then cur, nxt, rowoff (max_s + 1), srt, bits
-    l.bytes = (size_t)(l.max_s + 1) * 8 + ((size_t)3 * l.max_s + 1 + l.cap2 + l.bit_words) * 4;
+    // membership filter of a level's nodes: 32 bits per node of the largest level keep false hits rare
+    l.filt_words = l.cap2 < 64 ? 64 : l.cap2;
+    // pref (u64, max_s + 1) and obase (u64, max_s) first for their alignment, then cur, nxt,
+    // rowoff (max_s + 1), srt, bits, filt
+    l.bytes = (size_t)(2 * l.max_s + 1) * 8 + ((size_t)3 * l.max_s + 1 + l.cap2 + l.bit_words + l.filt_words) * 4;
     return l;
 }
 
@@ -56,15 +60,19 @@ template <typename OffT, int THREADS>
 __global__ void __launch_bounds__(THREADS)
 lw_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices, const int32_t* __restrict__ seeds,
           int32_t n_seeds, LwShape sh, LwKeys keys, int32_t m_offset, int32_t seeds_per_key, uint32_t max_s, uint32_t cap2,
+          uint32_t bit_words, uint32_t filt_words,
           int32_t* __restrict__ stage_nodes, int32_t* __restrict__ stage_eoff, int32_t* __restrict__ stage_child,
           int32_t* __restrict__ cnt, int32_t* __restrict__ ecnt) {
     extern __shared__ uint64_t lw_lds[];
     uint64_t* pref = lw_lds;                                             // exclusive degree sums, [n_cur + 1]
-    uint32_t* cur = reinterpret_cast<uint32_t*>(lw_lds + max_s + 1);     // previous level's nodes, ascending
+    uint64_t* obase = lw_lds + max_s + 1;                                // first list entry of every node
+    uint32_t* cur = reinterpret_cast<uint32_t*>(obase + max_s);          // previous level's nodes, ascending
     uint32_t* nxt = cur + max_s;                                         // this level's nodes
     uint32_t* rowoff = nxt + max_s;                                      // [n_cur + 1] entry offsets
     uint32_t* srt = rowoff + max_s + 1;                                  // [cap2] drawn vertices
     uint32_t* bits = srt + cap2;                                         // [n_cur x words] adjacency bits
+    uint32_t* filt = bits + bit_words;                                   // hashed membership bits of nxt
+    const uint32_t filt_shift = 32u - (uint32_t)__builtin_ctz(filt_words * 32u);
     __shared__ uint64_t lds8[THREADS / kWave];
     __shared__ uint32_t lds4[THREADS / kWave];
     const int32_t m = m_offset + (int32_t)blockIdx.x, B = n_seeds;
@@ -87,14 +95,18 @@ lw_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
         uint64_t carry = 0;
         for (uint32_t i0 = 0; i0 < n_cur; i0 += THREADS) {
             const uint32_t i = i0 + tid;
-            uint64_t deg = 0;
+            uint64_t deg = 0, o0 = 0;
             if (i < n_cur && (int32_t)cur[i] >= 0) {          // only a seed can be negative: no neighbours
                 const int64_t v = (int64_t)cur[i];
-                deg = (uint64_t)((int64_t)offsets[v + 1] - (int64_t)offsets[v]);
+                o0 = (uint64_t)offsets[v];
+                deg = (uint64_t)offsets[v + 1] - o0;
             }
             uint64_t total;
             const uint64_t ex = carry + fr_block_scan<THREADS, uint64_t>(deg, lds8, total);
-            if (i < n_cur) pref[i] = ex;
+            if (i < n_cur) {
+                pref[i] = ex;
+                obase[i] = o0;
+            }
             carry += total;
         }
         const uint64_t D = carry;
@@ -127,27 +139,48 @@ lw_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
                     if (pref[mid] <= p) lo = mid;
                     else hi = mid;
                 }
-                v = (uint32_t)indices[(int64_t)offsets[(int64_t)cur[lo]] + (int64_t)(p - pref[lo])];
+                v = (uint32_t)indices[obase[lo] + (p - pref[lo])];
             }
             srt[j] = v;
         }
         __syncthreads();
         fr_bitonic_sort<THREADS>(srt, n2);
         const uint32_t n_next = fr_pack_distinct<THREADS>(srt, n2, nxt, lds4);
-        // adjacency bits between the two node lists: one pass over the previous level's lists
+        // adjacency bits between the two node lists: ONE pass over the previous level's lists.
+        // Nearly every neighbour is outside the new level, so a hashed membership bit rejects it
+        // before the binary search; a thread's positions ascend, so its list pointer only advances;
+        // kLwUnroll independent loads are in flight per thread (hub lists make D large).
         const uint32_t words = (s_h + 31) / 32;
         for (uint32_t i = tid; i < n_cur * words; i += THREADS) bits[i] = 0;
+        for (uint32_t i = tid; i < filt_words; i += THREADS) filt[i] = 0;
         __syncthreads();
-        for (uint64_t p = tid; p < D; p += THREADS) {
-            uint32_t lo = 0, hi = n_cur;
-            while (hi - lo > 1) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (pref[mid] <= p) lo = mid;
-                else hi = mid;
+        for (uint32_t i = tid; i < n_next; i += THREADS) {
+            const uint32_t hsh = (nxt[i] * 0x9E3779B1u) >> filt_shift;
+            atomicOr(&filt[hsh >> 5], 1u << (hsh & 31));
+        }
+        __syncthreads();
+        uint32_t q = 0;
+        for (uint64_t p0 = tid; p0 < D; p0 += (uint64_t)kLwUnroll * THREADS) {
+            uint32_t v[kLwUnroll], qq[kLwUnroll];
+#pragma unroll
+            for (int u = 0; u < kLwUnroll; ++u) {
+                const uint64_t p = p0 + (uint64_t)u * THREADS;
+                v[u] = kFrNone;
+                qq[u] = 0;
+                if (p < D) {
+                    while (pref[q + 1] <= p) ++q;          // p < D = pref[n_cur]: q stays below n_cur
+                    qq[u] = q;
+                    v[u] = (uint32_t)indices[obase[q] + (p - pref[q])];
+                }
             }
-            const uint32_t v = (uint32_t)indices[(int64_t)offsets[(int64_t)cur[lo]] + (int64_t)(p - pref[lo])];
-            const uint32_t pos = fr_lower_bound(nxt, n_next, v);
-            if (pos < n_next && nxt[pos] == v) atomicOr(&bits[lo * words + (pos >> 5)], 1u << (pos & 31));
+#pragma unroll
+            for (int u = 0; u < kLwUnroll; ++u) {
+                if (v[u] == kFrNone) continue;
+                const uint32_t hsh = (v[u] * 0x9E3779B1u) >> filt_shift;
+                if (((filt[hsh >> 5] >> (hsh & 31)) & 1u) == 0) continue;
+                const uint32_t pos = fr_lower_bound(nxt, n_next, v[u]);
+                if (pos < n_next && nxt[pos] == v[u]) atomicOr(&bits[qq[u] * words + (pos >> 5)], 1u << (pos & 31));
+            }
         }
         __syncthreads();
         // segment lengths and their exclusive sums
@@ -404,7 +437,7 @@ hopgnn_status hopgnn::sample_layerwise(const hopgnn_csr* g, const int32_t* seeds
 #define HOPGNN_LW_LAUNCH(OffT, THREADS)                                                                               \
     hipLaunchKernelGGL((lw_sample<OffT, THREADS>), dim3((unsigned)count), dim3(THREADS), lds.bytes, s,               \
                        static_cast<const OffT*>(off), g->indices, seeds, n_seeds, sh, lk, (int32_t)m0, seeds_per_key, \
-                       lds.max_s, lds.cap2, stage_nodes, stage_eoff, stage_child, cnt, ecnt)
+                       lds.max_s, lds.cap2, lds.bit_words, lds.filt_words, stage_nodes, stage_eoff, stage_child, cnt, ecnt)
         if (g->offsets_i64) {
             if (threads == 256) HOPGNN_LW_LAUNCH(int64_t, 256);
             else HOPGNN_LW_LAUNCH(int64_t, 128);
