@@ -14,13 +14,15 @@
 //   dedup_scan     exclusive sums of the per-micrograph node counts, level by level
 //   dedup_compact  level-major global numbering: node vertices, CSR of child node indices
 //                  (parallel edges kept, -1 where a vertex has no neighbours), unused tails filled
+#include "frontier_common.hpp"
 #include "pregather_internal.hpp"
 
 namespace hopgnn {
 
 constexpr int kDdThreads = 256;
 constexpr int kDdMaxLevel = 4096;      // most slots one micrograph may have at one level
-constexpr uint32_t kDdNone = 0xFFFFFFFFu;
+constexpr uint32_t kDdNone = kFrNone;
+constexpr int kDdScanThreads = 1024;    // the one-workgroup scan of the node counts
 
 constexpr int kDdKeysPerLaunch = 64;
 struct DedupKeys {
@@ -33,36 +35,6 @@ struct DedupShape {
     int32_t P[kMaxLayers + 1];      // slot-tree slots per micrograph at level h
     int32_t base[kMaxLayers + 2];   // first slot of level h in the slot-tree layout; base[L+1] = T
 };
-
-__device__ __forceinline__ uint64_t dd_finalise64(uint64_t z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
-// Exclusive prefix sum of one value per thread over a workgroup of THREADS; `total` = their sum.
-template <int THREADS>
-__device__ __forceinline__ uint32_t dd_block_scan(uint32_t x, uint32_t* lds4, uint32_t& total) {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    uint32_t inc = x;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t y = __shfl_up(inc, d, kWave);
-        if (lane >= d) inc += y;
-    }
-    if (lane == kWave - 1) lds4[wave] = inc;
-    __syncthreads();
-    uint32_t wave_base = 0, tot = 0;
-#pragma unroll
-    for (int w = 0; w < THREADS / kWave; ++w) {
-        const uint32_t s = lds4[w];
-        if (w < wave) wave_base += s;
-        tot += s;
-    }
-    __syncthreads();
-    total = tot;
-    return wave_base + inc - x;
-}
 
 // LDS (dynamic): three arrays of `cap` words, cap = the last level's slot count rounded up to a
 // power of two - a few KiB for the usual fanouts, so that many micrographs share a CU; THREADS
@@ -78,7 +50,6 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
     uint32_t* ent = dd_lds + cap;             // children in draw order (kDdNone: none)
     uint32_t* srt = dd_lds + 2 * cap;         // the same, sorted
     __shared__ uint32_t lds4[THREADS / kWave];
-    __shared__ uint32_t n_next_s;
     const int32_t m = m_offset + (int32_t)blockIdx.x, B = n_seeds;
     const uint64_t keyed = keys.keyed[blockIdx.x / (uint32_t)seeds_per_key];   // one key per block of seeds
     const int tid = threadIdx.x;
@@ -105,9 +76,9 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
                     const int64_t o0 = (int64_t)offsets[v];
                     const int64_t deg = (int64_t)offsets[(int64_t)v + 1] - o0;
                     if (deg > 0) {
-                        uint64_t x = dd_finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v)) +
+                        uint64_t x = fr_finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v)) +
                                                    0x9E3779B97F4A7C15ull);
-                        x = dd_finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
+                        x = fr_finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
                         child = (uint32_t)indices[o0 + (int64_t)(x % (uint64_t)deg)];
                     }
                 }
@@ -116,35 +87,10 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
             srt[c] = child;
         }
         __syncthreads();
-        // ascending bitonic sort of srt[0, n2)  (kDdNone sorts last)
-        for (uint32_t k = 2; k <= n2; k <<= 1)
-            for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-                for (uint32_t i = tid; i < n2; i += THREADS) {
-                    const uint32_t p = i ^ j;
-                    if (p > i) {
-                        const uint32_t a = srt[i], b = srt[p];
-                        if ((a > b) == ((i & k) == 0)) {
-                            srt[i] = b;
-                            srt[p] = a;
-                        }
-                    }
-                }
-                __syncthreads();
-            }
-        // distinct values, packed in order into cur (the next level's node list)
-        uint32_t carry = 0;
-        for (uint32_t i0 = 0; i0 < n2; i0 += THREADS) {
-            const uint32_t i = i0 + tid;
-            const uint32_t v = i < n2 ? srt[i] : kDdNone;
-            const uint32_t head = (v != kDdNone && (i == 0 || srt[i - 1] != v)) ? 1u : 0u;
-            uint32_t total;
-            const uint32_t pos = carry + dd_block_scan<THREADS>(head, lds4, total);
-            if (head) cur[pos] = v;        // cur is free: every draw of this hop has been made
-            carry += total;
-        }
-        if (tid == 0) n_next_s = carry;
-        __syncthreads();
-        const uint32_t n_next = n_next_s;
+        // ascending sort (kDdNone sorts last), then the distinct values packed into cur, the next
+        // level's node list (cur is free: every draw of this hop has been made)
+        fr_bitonic_sort<THREADS>(srt, n2);
+        const uint32_t n_next = fr_pack_distinct<THREADS>(srt, n2, cur, lds4);
         // this micrograph's slices of the staging arrays (slot-tree capacity)
         int32_t* nodes_out = stage_nodes + sh.base[h] + (int64_t)m * sh.P[h];
         int32_t* child_out = stage_child + (sh.base[h] - B) + (int64_t)m * sh.P[h];
@@ -152,15 +98,7 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
         for (uint32_t c = tid; c < n_cand; c += THREADS) {
             const uint32_t child = ent[c];
             int32_t pos = -1;
-            if (child != kDdNone) {          // lower bound in cur[0, n_next): the value is there
-                uint32_t lo = 0, hi = n_next;
-                while (lo < hi) {
-                    const uint32_t mid = (lo + hi) >> 1;
-                    if (cur[mid] < child) lo = mid + 1;
-                    else hi = mid;
-                }
-                pos = (int32_t)lo;
-            }
+            if (child != kDdNone) pos = (int32_t)fr_lower_bound(cur, n_next, child);      // the value is there
             child_out[c] = pos;
         }
         if (tid == 0) cnt[(int64_t)h * B + m] = (int32_t)n_next;
@@ -171,13 +109,13 @@ dedup_sample(const OffT* __restrict__ offsets, const int32_t* __restrict__ indic
 
 // One workgroup: per level the exclusive sums of the micrographs' node counts, the first node of
 // every level and the first entry of every level's nodes.
-__global__ void __launch_bounds__(kDdThreads)
+__global__ void __launch_bounds__(kDdScanThreads)
 dedup_scan(const int32_t* __restrict__ cnt, int32_t n_seeds, DedupShape sh, int32_t* __restrict__ mg_off,
            int64_t* __restrict__ level_start, int64_t* __restrict__ ent_start) {
-    __shared__ uint32_t lds4[kDdThreads / kWave];
+    __shared__ uint32_t lds4[kDdScanThreads / kWave];
     int64_t nodes = 0, ents = 0;
     // thread t owns the contiguous run [t*per, (t+1)*per) of micrographs: sum it, scan the run sums
-    const int32_t per = (n_seeds + kDdThreads - 1) / kDdThreads;
+    const int32_t per = (n_seeds + kDdScanThreads - 1) / kDdScanThreads;
     const int32_t m0 = threadIdx.x * per, m1 = m0 + per < n_seeds ? m0 + per : n_seeds;
     for (int32_t h = 0; h <= sh.n_layers; ++h) {
         if (threadIdx.x == 0) {
@@ -188,7 +126,7 @@ dedup_scan(const int32_t* __restrict__ cnt, int32_t n_seeds, DedupShape sh, int3
         uint32_t mine = 0;
         for (int32_t mm = m0; mm < m1; ++mm) mine += (uint32_t)c[mm];
         uint32_t total;
-        uint32_t run = dd_block_scan<kDdThreads>(mine, lds4, total);
+        uint32_t run = fr_block_scan<kDdScanThreads, uint32_t>(mine, lds4, total);
         for (int32_t mm = m0; mm < m1; ++mm) {
             mg_off[(int64_t)h * n_seeds + mm] = (int32_t)run;
             run += (uint32_t)c[mm];
@@ -262,12 +200,6 @@ static DedupWs dedup_ws_layout(int64_t T, int64_t B, int32_t L) {
     return W;
 }
 
-static uint64_t dd_host_finalise64(uint64_t z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 }  // namespace hopgnn
 
 using namespace hopgnn;
@@ -336,7 +268,7 @@ hopgnn_status hopgnn::sample_dedup(const hopgnn_csr* g, const int32_t* seeds, in
     for (int32_t k0 = 0; k0 < n_keys; k0 += kDdKeysPerLaunch) {     // 64 keys fit one launch's arguments
         const int32_t nk = n_keys - k0 < kDdKeysPerLaunch ? n_keys - k0 : kDdKeysPerLaunch;
         DedupKeys dk{};
-        for (int32_t i = 0; i < nk; ++i) dk.keyed[i] = dd_host_finalise64(keys[k0 + i] + 0x9E3779B97F4A7C15ull);
+        for (int32_t i = 0; i < nk; ++i) dk.keyed[i] = fr_finalise64(keys[k0 + i] + 0x9E3779B97F4A7C15ull);
         const int64_t m0 = (int64_t)k0 * seeds_per_key;
         const int64_t count = (int64_t)nk * seeds_per_key < n_seeds - m0 ? (int64_t)nk * seeds_per_key : n_seeds - m0;
 #define HOPGNN_DD_LAUNCH(OffT, THREADS)                                                                              \
@@ -355,7 +287,7 @@ hopgnn_status hopgnn::sample_dedup(const hopgnn_csr* g, const int32_t* seeds, in
 #undef HOPGNN_DD_LAUNCH
         HOPGNN_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
+    hipLaunchKernelGGL(dedup_scan, dim3(1), dim3(kDdScanThreads), 0, s, cnt, n_seeds, sh, mg_off, level_start, ent_start);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(dedup_compact, dim3((unsigned)ceil_div(T, kDdThreads)), dim3(kDdThreads), 0, s, stage_nodes,
                        stage_child, cnt, mg_off, level_start, ent_start, n_seeds, sh, node_vertex, indptr, idx, present);

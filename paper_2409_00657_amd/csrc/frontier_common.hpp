@@ -7,7 +7,7 @@ namespace hopgnn {
 
 constexpr uint32_t kFrNone = 0xFFFFFFFFu;      // "no vertex": sorts after every vertex id
 
-__device__ __forceinline__ uint64_t fr_finalise64(uint64_t z) {
+__host__ __device__ __forceinline__ uint64_t fr_finalise64(uint64_t z) {
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
