@@ -1,0 +1,61 @@
+"""Oracle for GraphSAGE-mean layers over a level-major frontier structure (the output layout of
+the deduplicated-frontier and the layer-wise samplers).  TEST INFRASTRUCTURE ONLY.
+
+Nodes are numbered level by level; layer k (1-based) computes the rows of levels 0..L-k from those
+of levels 0..L-k+1 (paper section 2, "computation": one layer per hop, from the outermost inwards);
+the first layer reads the pre-gathered feature rows (section 5.2).  Every step is one of the
+oracle package's pinned functions (pre-gather, gather, the layer and its backward)."""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _layer_inputs(k, L, level_start, indptr, idx, remap):
+    n_dst = int(level_start[L - k + 1])
+    nnz = int(indptr[n_dst])
+    if k == 1:
+        self_idx = remap[:n_dst]
+        ix = np.where(idx[:nnz] >= 0, remap[np.maximum(idx[:nnz], 0)], -1).astype(np.int32)
+    else:
+        self_idx, ix = None, idx[:nnz]
+    return n_dst, self_idx, indptr[:n_dst + 1], ix
+
+
+def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights):
+    """GraphSAGE-mean layers over a level-major frontier structure: layer k computes the rows of
+    levels 0..L-k from those of levels 0..L-k+1 (the first from the pre-gathered feature rows).
+    `orc` is the oracle package (pre-gather, gather and the pinned layer).  Returns the root rows."""
+    L = len(weights)
+    uniq, remap = orc.pregather(node_vertex)
+    H = orc.gather(X, uniq)
+    for k in range(1, L + 1):
+        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        out = orc.sage_fwd(H, fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
+        H = orc.round_store(out, fmt)       # the next layer reads the rows as stored
+    return out
+
+
+def layer_chain_grads(orc, X, fmt, node_vertex, level_start, indptr, idx, weights, dOut):
+    """Forward as layer_chain, then the backward pass from dOut = dL/d(root rows) (paper section
+    5.1, steps 3-4: forward and backward per micrograph batch).  Returns
+    (root rows, [(gW_self, gW_neigh, gbias) per layer])."""
+    L = len(weights)
+    uniq, remap = orc.pregather(node_vertex)
+    H = [orc.gather(X, uniq)]
+    out = None
+    for k in range(1, L + 1):
+        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        out = orc.sage_fwd(H[-1], fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
+        H.append(orc.round_store(out, fmt))
+    grads = [None] * L
+    d = np.asarray(dOut, np.float64)
+    for k in range(L, 0, -1):
+        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        Ws, Wn, _b = weights[k - 1]
+        relu = k < L
+        gWs, gWn, gb, dH = orc.sage_bwd(H[k - 1], fmt, self_idx, ip, ix, Ws, Wn, H[k] if relu else None, relu, d,
+                                        want_dH=(k > 1))
+        grads[k - 1] = (gWs, gWn, gb)
+        if k > 1:
+            d = dH[:int(level_start[L - k + 2])]
+    return out, grads

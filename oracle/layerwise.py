@@ -71,21 +71,4 @@ def sample_layerwise(offsets, indices, seeds, budgets, key=0):
     return (node_vertex.astype(np.int32), level_start, np.asarray(indptr, np.int32), np.asarray(idx, np.int32))
 
 
-def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights):
-    """GraphSAGE-mean layers over a level-major frontier structure: layer k computes the rows of
-    levels 0..L-k from those of levels 0..L-k+1 (the first from the pre-gathered feature rows).
-    `orc` is the oracle package (pre-gather, gather and the pinned layer).  Returns the root rows."""
-    L = len(weights)
-    uniq, remap = orc.pregather(node_vertex)
-    H = orc.gather(X, uniq)
-    for k in range(1, L + 1):
-        n_dst = int(level_start[L - k + 1])
-        nnz = int(indptr[n_dst])
-        if k == 1:
-            self_idx = remap[:n_dst]
-            ix = np.where(idx[:nnz] >= 0, remap[np.maximum(idx[:nnz], 0)], -1).astype(np.int32)
-        else:
-            self_idx, ix = None, idx[:nnz]
-        out = orc.sage_fwd(H, fmt, self_idx, indptr[:n_dst + 1], ix, *weights[k - 1], relu=(k < L))
-        H = orc.round_store(out, fmt)       # the next layer reads the rows as stored
-    return out
+from .frontier import layer_chain  # noqa: E402,F401  (the layers over the structure)

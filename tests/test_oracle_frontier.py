@@ -1,0 +1,81 @@
+"""Pins of the layer chain and its gradients over a frontier structure (oracle/frontier.py):
+central differences of L = <G, root rows> in float64, and - for the deduplicated frontiers, which
+compute the same function of the weights as the slot tree - the tree chain's gradients."""
+import numpy as np
+import pytest
+
+from oracle import dedup, frontier, layerwise
+
+F64 = 3
+
+
+def _graph(rng, n, max_deg, p_isolated=0.1):
+    deg = rng.integers(1, max_deg + 1, size=n)
+    deg[rng.random(n) < p_isolated] = 0
+    off = np.zeros(n + 1, np.int64)
+    off[1:] = np.cumsum(deg)
+    idx = rng.integers(0, n, size=int(off[-1])).astype(np.int32)
+    return off, idx
+
+
+def _weights(rng, d, hid, L):
+    return [(rng.standard_normal((d if k == 0 else hid, hid)) / 3, rng.standard_normal((d if k == 0 else hid, hid)) / 3,
+             rng.standard_normal(hid) / 3) for k in range(L)]
+
+
+@pytest.mark.parametrize("sampler", ["dedup", "layerwise"])
+def test_gradients_match_central_differences(orc, sampler):
+    rng = np.random.default_rng(17)
+    n, d, hid, L = 60, 4, 5, 3
+    off, idx = _graph(rng, n, 5)
+    seeds = rng.integers(0, n, size=5).astype(np.int32)
+    X = rng.standard_normal((n, d))
+    W = _weights(rng, d, hid, L)
+    if sampler == "dedup":
+        st = dedup.sample_dedup(off, idx, seeds, [3, 3, 2], 4)
+    else:
+        st = layerwise.sample_layerwise(off, idx, seeds, [3, 4, 4], 4)
+    G = rng.standard_normal((len(seeds), hid))
+    out, grads = frontier.layer_chain_grads(orc, X, F64, *st, W, G)
+    np.testing.assert_allclose(out, frontier.layer_chain(orc, X, F64, *st, W), rtol=0, atol=0)
+    loss = lambda Wp: float((G * frontier.layer_chain(orc, X, F64, *st, Wp)).sum())
+    eps = 1e-6
+    for k in range(L):
+        for part in range(3):
+            A = W[k][part]
+            picks = [tuple(rng.integers(0, s) for s in A.shape) for _ in range(4)]
+            for at in picks:
+                Wp = [list(w) for w in W]
+                Wm = [list(w) for w in W]
+                Wp[k][part] = A.copy()
+                Wm[k][part] = A.copy()
+                Wp[k][part][at] += eps
+                Wm[k][part][at] -= eps
+                fd = (loss([tuple(w) for w in Wp]) - loss([tuple(w) for w in Wm])) / (2 * eps)
+                assert abs(fd - grads[k][part][at]) <= 1e-6 * max(1.0, abs(fd)), (k, part, at)
+
+
+def test_deduplicated_chain_has_the_tree_chains_gradients(orc):
+    rng = np.random.default_rng(23)
+    n, d, hid, fan = 80, 5, 6, [4, 3]
+    off, idx = _graph(rng, n, 4)
+    seeds = rng.integers(0, n, size=7).astype(np.int32)
+    B, L = len(seeds), 2
+    X = rng.standard_normal((n, d))
+    W = _weights(rng, d, hid, L)
+    G = rng.standard_normal((B, hid))
+    _, grads = frontier.layer_chain_grads(orc, X, F64, *dedup.sample_dedup(off, idx, seeds, fan, 6), W, G)
+    # the slot tree, layer by layer with the pinned single-layer functions
+    ids, ip = orc.sample(off, idx, seeds, fan, 6)
+    uniq, remap = orc.pregather(ids)
+    Xu = orc.gather(X, uniq)
+    lv = orc.level_sizes(B, fan)
+    n1, nnz1 = lv[0] + lv[1], lv[1] + lv[2]
+    H1 = orc.sage_fwd(Xu, F64, remap[:n1], ip[:n1 + 1], remap[B:B + nnz1], *W[0], relu=True)
+    slot_idx = np.where(ids[B:B + lv[1]] >= 0, B + np.arange(lv[1]), -1).astype(np.int32)
+    g2 = orc.sage_bwd(H1, F64, None, ip[:B + 1], slot_idx, W[1][0], W[1][1], None, False, G)
+    g1 = orc.sage_bwd(Xu, F64, remap[:n1], ip[:n1 + 1], remap[B:B + nnz1], W[0][0], W[0][1], H1, True, g2[3],
+                      want_dH=False)
+    for part in range(3):
+        np.testing.assert_allclose(grads[1][part], g2[part], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(grads[0][part], g1[part], rtol=1e-10, atol=1e-12)
