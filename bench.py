@@ -127,8 +127,14 @@ def main_dedup(args):
     n_streams = max(1, args.streams)
     group = args.group or cfg.groups[0]
     sampler = "layer" if args.layerwise else "node"
-    dps = [DedupPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, sampler=sampler)
-           for _ in range(n_streams)]
+    # training steps update the weights: every stream is then a worker with its own replica
+    Ws = [W] + [[tuple(None if t is None else t.clone() for t in layer) for layer in W]
+                for _ in range(n_streams - 1)] if args.backward else [W] * n_streams
+    dps = [DedupPath(g.offsets, g.indices, X, Ws[j], cfg.batch, cfg.fanouts, group=group, sampler=sampler)
+           for j in range(n_streams)]
+    if args.backward:
+        for d in dps:
+            d.enable_backward()
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
     n_total = args.warmup + args.steps
     seeds = [torch.cat([synth.seeds(cfg.n_vertices, cfg.batch, i * group + b, device=dev) for b in range(group)])
@@ -139,9 +145,17 @@ def main_dedup(args):
     outs = [torch.empty((group * cfg.batch, cfg.hidden), dtype=X.dtype, device=dev) for _ in range(n_streams)]
     raw_streams = [s.cuda_stream for s in streams]
 
-    def step(i, marks=None):
+    def step_fwd(i, marks=None):
         j = i % n_streams
         dps[j].forward(seeds[i], keys[i], outs[j], raw_streams[j], marks)
+
+    def step_train(i, marks=None):
+        """Forward call by call, backward with in-place accumulation, update: one iteration."""
+        j = i % n_streams
+        with torch.cuda.stream(streams[j]):         # the gather's event pair records on the current stream
+            dps[j].train_step(seeds[i], keys[i], 1e-4, raw_streams[j], marks)
+
+    step = step_train if args.backward else step_fwd
 
     for i in range(args.warmup):
         step(i)
@@ -151,7 +165,7 @@ def main_dedup(args):
         e[0].record(streams[i % n_streams])
         e[1].record(streams[i % n_streams])
     torch.cuda.synchronize()
-    raw_marks = [(a.cuda_event, b.cuda_event) for a, b in ev]
+    raw_marks = ev if args.backward else [(a.cuda_event, b.cuda_event) for a, b in ev]
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(args.warmup + i, raw_marks[i])
@@ -191,7 +205,7 @@ def main_dedup(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges, "feature_dim": cfg.d,
                    "batch": cfg.batch, "fanouts": cfg.fanouts, "hidden": cfg.hidden, "group": group, "streams": n_streams,
-                   "deduplicated_frontiers": True, "sampler": sampler + "-wise", "slots_per_batch": dp.capacity // group},
+                   "deduplicated_frontiers": True, "sampler": sampler + "-wise", "backward": bool(args.backward), "slots_per_batch": dp.capacity // group},
         "unique_rows_per_step": U_avg, "nodes_per_step": nodes_sum / n_replay,
         "nodes_over_slots": nodes_sum / n_replay / dp.capacity,
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
@@ -214,8 +228,8 @@ def main():
         sys.exit(2)
 
     if args.dedup or args.layerwise:
-        if args.backward or args.model != "sage":
-            print("bench.py: --dedup runs the GraphSAGE forward path", file=sys.stderr)
+        if args.model != "sage":
+            print("bench.py: --dedup and --layerwise run GraphSAGE-mean layers", file=sys.stderr)
             sys.exit(2)
         return main_dedup(args)
 

@@ -416,6 +416,22 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               void *stream);
 
 /*
+ * hopgnn_sage_bwd for row counts that only the device knows (the layers over hopgnn_sample_dedup's
+ * or hopgnn_sample_layerwise's micrographs, as hopgnn_sage_fwd_dev in the forward pass): n_dst and
+ * n_src are the capacities the launches and the workspace are sized for, *n_dst_dev and *n_src_dev
+ * (DEVICE, NULL = the capacity) the rows that exist.  Destination rows past *n_dst_dev contribute
+ * nothing and their out_fwd / dOut / Hsrc entries are not used; of dHsrc only the first *n_src_dev
+ * rows are written.  A source row may have many parents here, so the float atomic adds into dHsrc
+ * arrive in varying order (gradients agree to rounding, not bit for bit).
+ */
+hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t *n_src_dev,
+                                  int32_t d_in, const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                                  int64_t n_dst, const int64_t *n_dst_dev, const void *W_self, const void *W_neigh,
+                                  const void *out_fwd, int32_t relu, const float *dOut, int32_t d_out,
+                                  float *gW_self, float *gW_neigh, float *gbias, float *dHsrc, void *ws,
+                                  size_t ws_bytes, void *stream);
+
+/*
  * One call per group of batches: the whole hot path in the order of paper sections 2, 4
  * and 5.2 - sample the micrographs of each batch's seeds, pre-gather the group's merged slot
  * list once, fetch every distinct row once, then run the L layers of each batch on the

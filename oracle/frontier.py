@@ -10,7 +10,8 @@ from __future__ import annotations
 import numpy as np
 
 
-def _layer_inputs(k, L, level_start, indptr, idx, remap):
+def layer_inputs(k, L, level_start, indptr, idx, remap):
+    """(n_dst, self_idx, indptr, idx) of layer k (1-based) in the numbering of its source rows."""
     n_dst = int(level_start[L - k + 1])
     nnz = int(indptr[n_dst])
     if k == 1:
@@ -29,7 +30,7 @@ def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights):
     uniq, remap = orc.pregather(node_vertex)
     H = orc.gather(X, uniq)
     for k in range(1, L + 1):
-        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        _, self_idx, ip, ix = layer_inputs(k, L, level_start, indptr, idx, remap)
         out = orc.sage_fwd(H, fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
         H = orc.round_store(out, fmt)       # the next layer reads the rows as stored
     return out
@@ -44,13 +45,13 @@ def layer_chain_grads(orc, X, fmt, node_vertex, level_start, indptr, idx, weight
     H = [orc.gather(X, uniq)]
     out = None
     for k in range(1, L + 1):
-        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        _, self_idx, ip, ix = layer_inputs(k, L, level_start, indptr, idx, remap)
         out = orc.sage_fwd(H[-1], fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
         H.append(orc.round_store(out, fmt))
     grads = [None] * L
     d = np.asarray(dOut, np.float64)
     for k in range(L, 0, -1):
-        _, self_idx, ip, ix = _layer_inputs(k, L, level_start, indptr, idx, remap)
+        _, self_idx, ip, ix = layer_inputs(k, L, level_start, indptr, idx, remap)
         Ws, Wn, _b = weights[k - 1]
         relu = k < L
         gWs, gWn, gb, dH = orc.sage_bwd(H[k - 1], fmt, self_idx, ip, ix, Ws, Wn, H[k] if relu else None, relu, d,

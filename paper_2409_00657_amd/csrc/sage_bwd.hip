@@ -46,9 +46,9 @@ struct Raw4<TrF32> {
 template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_mask4(const typename Raw4<Tr>::type* __restrict__ out_fwd, const float4* __restrict__ dOut, int64_t n4,
-          float4* __restrict__ dZ) {
+          float4* __restrict__ dZ, const int64_t* __restrict__ n_rows_dev, int32_t row4) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
-    if (i >= n4) return;
+    if (i >= n4 || (n_rows_dev != nullptr && i >= *n_rows_dev * row4)) return;     // row4 = 16-byte items per row
     const float4 o = Raw4<Tr>::widen(out_fwd[i]);
     float4 g = dOut[i];
     g.x = o.x > 0.f ? g.x : 0.f;
@@ -61,20 +61,23 @@ bwd_mask4(const typename Raw4<Tr>::type* __restrict__ out_fwd, const float4* __r
 template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_mask_elem(const typename Tr::store_t* __restrict__ out_fwd, const float* __restrict__ dOut, int64_t n,
-              float* __restrict__ dZ) {
+              float* __restrict__ dZ, const int64_t* __restrict__ n_rows_dev, int32_t d_out) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (n_rows_dev != nullptr && i >= *n_rows_dev * d_out) return;
     if (i < n) dZ[i] = Tr::to_f(out_fwd[i]) > 0.f ? dOut[i] : 0.f;
 }
 
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_zero_elem(float* __restrict__ p, int64_t n) {
+bwd_zero_elem(float* __restrict__ p, int64_t n, const int64_t* __restrict__ n_rows_dev, int32_t row_items) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (n_rows_dev != nullptr && i >= *n_rows_dev * row_items) return;
     if (i < n) p[i] = 0.f;
 }
 
 __global__ void __launch_bounds__(kBwdThreads)
-bwd_zero(float4* __restrict__ p, int64_t n4) {
+bwd_zero(float4* __restrict__ p, int64_t n4, const int64_t* __restrict__ n_rows_dev, int32_t row_items) {
     const int64_t i = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    if (n_rows_dev != nullptr && i >= *n_rows_dev * row_items) return;
     if (i < n4) p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 }
 
@@ -107,7 +110,7 @@ __global__ void __launch_bounds__(kBwdThreads)
 bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                 const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
                 int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
-                float* __restrict__ bias_partial) {
+                float* __restrict__ bias_partial, const int64_t* __restrict__ n_rows_dev) {
     __shared__ __attribute__((aligned(16))) float As[2][kGradRows][kGradLd];
     __shared__ __attribute__((aligned(16))) float Bs[2][kGradRows][kGradLd];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -115,8 +118,11 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
     const int wk = wave >> 1, wn = wave & 1;
     const int K = 2 * d_in;
     const uint32_t tk = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
+    // rows that exist (n_dst is the capacity: addresses are clamped to it, rows past n_rows are masked)
+    const int64_t n_rows = n_rows_dev != nullptr && *n_rows_dev < n_dst ? *n_rows_dev : n_dst;
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
-    const int64_t r1 = r0 + rows_per_split < n_dst ? r0 + rows_per_split : n_dst;
+    int64_t r1 = r0 + rows_per_split < n_rows ? r0 + rows_per_split : n_rows;
+    r1 = r1 > r0 ? r1 : r0;                    // a split past the last row: no chunk, a zero tile
     const int n_chunks = (int)((r1 - r0 + kGradRows - 1) / kGradRows);
 
     // this thread's part of every chunk
@@ -283,8 +289,8 @@ bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ b
 template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restrict__ Wself,
-               const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst, int32_t d_in, int32_t d_out,
-               float* __restrict__ D) {
+               const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst_cap, int32_t d_in, int32_t d_out,
+               float* __restrict__ D, const int64_t* __restrict__ n_rows_dev) {
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     constexpr int BM = 64, BN = 64, BK = 16, LD = BK + 4;
@@ -293,7 +299,9 @@ bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restr
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
     const int wm = wave >> 1, wn = wave & 1;
+    const int64_t n_dst = n_rows_dev != nullptr && *n_rows_dev < n_dst_cap ? *n_rows_dev : n_dst_cap;
     const int64_t row0 = (int64_t)blockIdx.x * BM;
+    if (row0 >= n_dst) return;                 // uniform over the workgroup
     const int col0 = blockIdx.y * BN;
     const int N = 2 * d_in;
     const bool vec = (d_out & 3) == 0;
@@ -374,11 +382,12 @@ bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restr
 // `group` lanes (power of two) per destination row, lane j owns columns j, j+group, ...
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_scatter(const float* __restrict__ D, const int32_t* __restrict__ self_idx, const int32_t* __restrict__ indptr,
-            const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group, float* __restrict__ dHsrc) {
+            const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group, float* __restrict__ dHsrc,
+            const int64_t* __restrict__ n_rows_dev) {
     const int64_t gid = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
     const int64_t r = gid / group;
     const int32_t j = (int32_t)(gid - r * group);
-    if (r >= n_dst) return;
+    if (r >= n_dst || (n_rows_dev != nullptr && r >= *n_rows_dev)) return;
     const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
     const int32_t beg = indptr[r], end = indptr[r + 1];
     int32_t cnt = 0;
@@ -456,7 +465,7 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                                     const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W_self,
                                     const void* W_neigh, const void* out_fwd, int32_t relu, const float* dOut,
                                     int32_t d_out, float* gW_self, float* gW_neigh, float* gbias, float* dHsrc,
-                                    void* ws, const BwdWs& L, hipStream_t s) {
+                                    void* ws, const BwdWs& L, const int64_t* n_dst_dev, hipStream_t s) {
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     char* p = static_cast<char*>(ws);
@@ -469,19 +478,21 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     if (n_src == 0) Hsrc = zero;   // nothing is read from it unmasked
 
     // the means again (same kernel as the forward pass, same rounding to the activation type)
-    hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s);
+    hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s, kAggMean,
+                                       n_dst_dev);
     if (st != HOPGNN_OK) return st;
 
     const float* dZ = dOut;
     if (relu) {
         const int64_t n = n_dst * d_out;
-        if (n % 4 == 0 && aligned(out_fwd, 16) && aligned(dOut, 16))
+        // four elements per thread when the total allows it (and, with a device row count, every row does)
+        if (n % 4 == 0 && (n_dst_dev == nullptr || d_out % 4 == 0) && aligned(out_fwd, 16) && aligned(dOut, 16))
             hipLaunchKernelGGL(bwd_mask4<Tr>, dim3((unsigned)ceil_div(n / 4, kBwdThreads)), dim3(kBwdThreads), 0, s,
                                static_cast<const R4*>(out_fwd), reinterpret_cast<const float4*>(dOut), n / 4,
-                               reinterpret_cast<float4*>(dz_buf));
+                               reinterpret_cast<float4*>(dz_buf), n_dst_dev, d_out / 4);
         else
             hipLaunchKernelGGL(bwd_mask_elem<Tr>, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                               static_cast<const T*>(out_fwd), dOut, n, dz_buf);
+                               static_cast<const T*>(out_fwd), dOut, n, dz_buf, n_dst_dev, d_out);
         HOPGNN_LAUNCH_CHECK();
         dZ = dz_buf;
     }
@@ -491,7 +502,7 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     auto grad_kernel = vec ? bwd_weight_grad<Tr, true> : bwd_weight_grad<Tr, false>;
     hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
                        static_cast<const T*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out, L.rows_per_split, tiles_n,
-                       partial, gbias != nullptr ? bias_partial : nullptr);
+                       partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
     HOPGNN_LAUNCH_CHECK();
     const int64_t red = (int64_t)2 * d_in * d_out + d_out;
     hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
@@ -502,11 +513,12 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
         const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
         if (gy > 65535) return HOPGNN_ERANGE;
         hipLaunchKernelGGL(bwd_input_grad<Tr>, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0,
-                           s, dZ, static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D);
+                           s, dZ, static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D,
+                           n_dst_dev);
         HOPGNN_LAUNCH_CHECK();
         const int group = mean_group(d_in);
         hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc);
+                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc, n_dst_dev);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
@@ -520,20 +532,32 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
                                          const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out,
                                          float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
                                          size_t ws_bytes, void* stream) {
+    return hopgnn_sage_bwd_dev(Hsrc, dt, n_src, nullptr, d_in, self_idx, indptr, idx, n_dst, nullptr, W_self, W_neigh,
+                               out_fwd, relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, stream);
+}
+
+extern "C" hopgnn_status hopgnn_sage_bwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                             int32_t d_in, const int32_t* self_idx, const int32_t* indptr,
+                                             const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
+                                             const void* W_self, const void* W_neigh, const void* out_fwd, int32_t relu,
+                                             const float* dOut, int32_t d_out, float* gW_self, float* gW_neigh,
+                                             float* gbias, float* dHsrc, void* ws, size_t ws_bytes, void* stream) {
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dHsrc != nullptr && n_src > 0) {
-        if (!aligned(dHsrc, 16) || ((int64_t)n_src * d_in) % 4 != 0) {   // a fill kernel, never a memset node
+        // a fill kernel, never a memset node; with a device row count only the rows that exist
+        if (!aligned(dHsrc, 16) || ((int64_t)n_src * d_in) % 4 != 0 || (n_src_dev != nullptr && d_in % 4 != 0)) {
             const int64_t n = (int64_t)n_src * d_in;
-            hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s, dHsrc, n);
+            hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0, s, dHsrc, n,
+                               n_src_dev, d_in);
             HOPGNN_LAUNCH_CHECK();
         } else {
             const int64_t n4 = (int64_t)n_src * d_in / 4;
             hipLaunchKernelGGL(bwd_zero, dim3((unsigned)ceil_div(n4, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                               reinterpret_cast<float4*>(dHsrc), n4);
+                               reinterpret_cast<float4*>(dHsrc), n4, n_src_dev, d_in / 4);
             HOPGNN_LAUNCH_CHECK();
         }
     }
@@ -548,12 +572,12 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     if (dt == HOPGNN_F32)
         return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
     if (dt == HOPGNN_BF16)
         return sage_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu,
-                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
     return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, s);
+                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
 }
 
 extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,

@@ -490,6 +490,130 @@ class DedupPath:
                                hb.AGG_MEAN, k < sh.n_layers, self.H[k - 1], self.sage_ws)
         return self.H[k - 1]
 
+    def enable_backward(self) -> None:
+        """Gradient accumulators (fp32, zero) and the buffers of the backward pass over the frontier
+        structure, as HotPath.enable_backward: the harness's loss is L = 1/2 |H_L|^2 for fp32
+        activations (dL/dH_L = H_L, read in place) and L = <G, H_L> with a fixed G otherwise."""
+        sh, dev = self.shape, self.X.device
+        L = sh.n_layers
+        hidden = self.weights[0][0].shape[1]
+        if self.X.dtype == torch.float32:
+            self.dHL = self.H[L - 1]
+        else:
+            self.dHL = synth.weight(sh.n_seeds, hidden, torch.float32, stream=99, device=dev)
+        self.gW = [(torch.zeros_like(Ws, dtype=torch.float32), torch.zeros_like(Wn, dtype=torch.float32),
+                    None if b is None else torch.zeros_like(b, dtype=torch.float32)) for Ws, Wn, b in self.weights]
+        # dH[k-1] = gradient of layer k's output rows (k = 1..L-1), produced by layer k+1's backward
+        self.dH = [torch.empty((sh.n_dst(k), hidden), dtype=torch.float32, device=dev) for k in range(1, L)]
+        ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
+                                                   hidden, k > 1) for k in range(1, L + 1))
+        self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._raw_calls()
+
+    def _raw_calls(self):
+        """The library calls of one step with every constant argument marshalled once (a step is a
+        few dozen launches of microseconds each: per-call marshalling would dominate it)."""
+        lib, sh, pl = self._lib, self.shape, self.plan
+        L, dt = sh.n_layers, hb.DTYPE_OF[self.X.dtype]
+        fan = (ctypes.c_int32 * L)(*sh.fanouts)
+        self._fan = fan
+        p = lambda t: None if t is None else t.data_ptr()
+        sample = lib.hopgnn_sample_dedup if self.sampler == "node" else lib.hopgnn_sample_layerwise
+        self._call_sample = (sample, (ctypes.byref(pl.graph),), (sh.n_seeds, self.seeds_per_key, fan, L, self._keys,
+                             p(self.node_vertex), p(self.level_start), p(self.indptr), p(self.idx), p(self.dd_ws),
+                             self.dd_ws.numel()))
+        fwd = [(lib.hopgnn_pregather, (p(self.node_vertex), sh.n_slots, self.n_vertices, self.pg_algo, p(self.uniq),
+                                       p(self.n_uniq), p(self.remap), p(self.pg_ws), self.pg_ws.numel())),
+               (lib.hopgnn_gather, (p(self.X), dt, self.n_vertices, self.X.shape[1], self.X.stride(0), p(self.uniq),
+                                    self.cap, p(self.n_uniq), p(self.Xu))),
+               (lib.hopgnn_compose_idx, (p(self.idx), self.idx.numel(), p(self.remap), p(self.idx_l1)))]
+        for k in range(1, L + 1):
+            Ws, Wn, bias = self.weights[k - 1]
+            n_dst = sh.n_dst(k)
+            src, n_src = (self.Xu, self.cap) if k == 1 else (self.H[k - 2], sh.n_dst(k - 1))
+            fwd.append((lib.hopgnn_sage_fwd_dev,
+                        (p(src), dt, n_src, Ws.shape[0], p(self.remap) if k == 1 else None, p(self.indptr),
+                         p(self.idx_l1 if k == 1 else self.idx), n_dst, p(self._n_dst_dev[k - 1]), p(Ws), p(Wn), p(bias),
+                         Ws.shape[1], hb.AGG_MEAN, 1 if k < L else 0, p(self.H[k - 1]), p(self.sage_ws),
+                         self.sage_ws.numel())))
+        self._calls_fwd = fwd
+        bwd = []
+        if hasattr(self, "gW"):
+            for k in range(L, 0, -1):
+                Ws, Wn, _bias = self.weights[k - 1]
+                gWs, gWn, gb = self.gW[k - 1]
+                n_dst = sh.n_dst(k)
+                if k == 1:
+                    src, n_src, n_src_dev = self.Xu, self.cap, None
+                else:
+                    src, n_src, n_src_dev = self.H[k - 2], sh.n_dst(k - 1), self._n_dst_dev[k - 2]
+                bwd.append((lib.hopgnn_sage_bwd_dev,
+                            (p(src), dt, n_src, p(n_src_dev), Ws.shape[0], p(self.remap) if k == 1 else None,
+                             p(self.indptr), p(self.idx_l1 if k == 1 else self.idx), n_dst, p(self._n_dst_dev[k - 1]),
+                             p(Ws), p(Wn), p(self.H[k - 1]), 1 if k < L else 0, p(self.dHL if k == L else self.dH[k - 1]),
+                             Ws.shape[1], p(gWs), p(gWn), p(gb), p(self.dH[k - 2]) if k > 1 else None, p(self.bwd_ws),
+                             self.bwd_ws.numel())))
+        self._calls_bwd = bwd
+
+    def train_step(self, seeds: torch.Tensor, key, lr: float, stream=None, marks=None) -> None:
+        """One iteration on `stream` (a raw hipStream_t, default torch's current one): forward call
+        by call, backward with in-place accumulation, update.  `marks` as in run_batch."""
+        if not hasattr(self, "gW"):
+            raise hb.HopgnnError("enable_backward first")
+        st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+        for i, k in enumerate(self._key_list(key)):
+            self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
+        fn, head, tail = self._call_sample
+        rc = fn(*head, seeds.data_ptr(), *tail, st)
+        if rc:
+            hb._check(rc, "sampling")
+        for n, (fn, args) in enumerate(self._calls_fwd):
+            if marks is not None and n == 1:
+                marks[0].record()
+            rc = fn(*args, st)
+            if rc:
+                hb._check(rc, fn.__name__)
+            if marks is not None and n == 1:
+                marks[1].record()
+        for fn, args in self._calls_bwd:
+            rc = fn(*args, st)
+            if rc:
+                hb._check(rc, fn.__name__)
+        lib, dt = self._lib, hb.DTYPE_OF[self.X.dtype]
+        for layer, grads in zip(self.weights, self.gW):
+            for W, gW in zip(layer, grads):
+                if W is not None:
+                    rc = lib.hopgnn_sgd_update(W.data_ptr(), dt, gW.data_ptr(), W.numel(), lr, 1, st)
+                    if rc:
+                        hb._check(rc, "hopgnn_sgd_update")
+
+    def backward(self) -> None:
+        """Backward of the layers of the batch last run by run_batch, last layer first; weight
+        gradients accumulate in self.gW.  Row counts come from level_start on the device."""
+        sh = self.shape
+        L = sh.n_layers
+        for k in range(L, 0, -1):
+            Ws, Wn, _bias = self.weights[k - 1]
+            gWs, gWn, gb = self.gW[k - 1]
+            n_dst = sh.n_dst(k)
+            if k == 1:
+                src, n_src, n_src_dev = self.Xu, self.cap, None
+            else:
+                src, n_src, n_src_dev = self.H[k - 2], sh.n_dst(k - 1), self._n_dst_dev[k - 2]
+            hb.hopgnn_sage_bwd_dev(src, n_src, n_src_dev, self.remap[:n_dst] if k == 1 else None,
+                                   self.indptr[:n_dst + 1], self.idx_l1 if k == 1 else self.idx, n_dst,
+                                   self._n_dst_dev[k - 1], Ws, Wn, self.H[k - 1], k < L,
+                                   self.dHL if k == L else self.dH[k - 1], gWs, gWn, gb,
+                                   self.dH[k - 2] if k > 1 else None, self.bwd_ws)
+
+    def apply_sgd(self, lr: float) -> None:
+        """W <- W - lr * gW for every weight matrix and bias; the accumulators are cleared."""
+        for (Ws, Wn, b), (gWs, gWn, gb) in zip(self.weights, self.gW):
+            hb.hopgnn_sgd_update(Ws, gWs, lr, True)
+            hb.hopgnn_sgd_update(Wn, gWn, lr, True)
+            if b is not None:
+                hb.hopgnn_sgd_update(b, gb, lr, True)
+
     def run_batch(self, seeds: torch.Tensor, key, marks=None) -> torch.Tensor:
         """Returns the [group*B, hidden] rows of the last layer (level 0 always has every root).
         `marks` = (begin, end) torch events recorded around the gather launch."""

@@ -124,6 +124,23 @@ def test_newer_entry_points_reject_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_ws_bytes(5, 100, 8, 8, 1) == 0
 
 
+def test_sage_bwd_dev_rejects_bad_arguments(lib):
+    c = ctypes
+    one = c.c_void_p(256)
+    args = lambda dt=0, n_src=8, n_dst=4, d_in=4, d_out=4, ws=one, ws_bytes=1 << 30, self_idx=one: (
+        one, dt, n_src, None, d_in, self_idx, one, one, n_dst, None, one, one, one, 1, one, d_out, one, one, None, None,
+        ws, ws_bytes, None)
+    assert lib.hopgnn_sage_bwd_dev(*args(dt=7)) == 1
+    assert lib.hopgnn_sage_bwd_dev(*args(n_dst=-1)) == 1
+    assert lib.hopgnn_sage_bwd_dev(*args(d_in=0)) == 1
+    assert lib.hopgnn_sage_bwd_dev(*args(n_dst=0)) == 0                       # nothing to do
+    assert lib.hopgnn_sage_bwd_dev(*args(ws=None)) == 1
+    assert lib.hopgnn_sage_bwd_dev(*args(ws=c.c_void_p(8))) == 1              # not 256-byte aligned
+    assert lib.hopgnn_sage_bwd_dev(*args(ws_bytes=16)) == 2
+    assert lib.hopgnn_sage_bwd_dev(*args(n_src=2, self_idx=None)) == 1        # identity self rows must exist
+    assert lib.hopgnn_sage_bwd_dev(*args(n_dst=1 << 31)) == 3
+
+
 def test_layerwise_capacities_and_errors(lib):
     c = ctypes
     from paper_2409_00657_amd import binding as hb
