@@ -147,3 +147,82 @@ def test_random_whole_batches(seed):
                 if not (e <= TOL[dt] * L):
                     failures.append(("forward", e, tag, it, b))
     assert not failures, failures
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_frontier_batches(seed):
+    """Deduplicated and layer-wise sampled micrographs on random graphs, shapes, groups and types:
+    structure bit-exact, root rows and (fp32) weight gradients against the oracle chain."""
+    from paper_2409_00657_amd import binding as hb, synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    from oracle import dedup as orc_dedup, frontier as orc_frontier, layerwise as orc_lw
+    rng = np.random.default_rng(100 + seed)
+    dts = [torch.float32, torch.bfloat16, torch.float16]
+    failures = []
+    for case in range(10):
+        kind = rng.integers(0, 3)
+        if kind == 0: g = synth.uniform_graph(int(rng.integers(10, 3000)), 0, int(rng.integers(1, 12)), seed=case, device=DEV, offsets_i64=bool(rng.integers(0, 2)))
+        elif kind == 1: g = synth.rmat_graph(int(rng.integers(6, 13)), float(rng.uniform(0.5, 12)), seed=case, device=DEV, offsets_i64=bool(rng.integers(0, 2)))
+        else: g = synth.chung_lu_graph(int(rng.integers(50, 8000)), float(rng.uniform(1, 20)), 2.1, seed=case, device=DEV, offsets_i64=bool(rng.integers(0, 2)))
+        n = g.n_vertices
+        sampler = ["node", "layer"][rng.integers(0, 2)]
+        L = int(rng.integers(1, 4))
+        fan = [int(rng.integers(1, 9 if sampler == "node" else 20)) for _ in range(L)]
+        B = int(rng.choice([1, 3, 17, 64, 90]))
+        G = int(rng.choice([1, 1, 2, 4]))
+        dt = dts[rng.integers(0, 3)]
+        d = int(rng.choice([1, 4, 12, 32, 100]))
+        hidden = int(rng.choice([1, 4, 20, 64]))
+        algo = int(rng.integers(0, 3))
+        tag = (case, kind, n, sampler, fan, B, G, str(dt), d, hidden, algo)
+        X = synth.features(n, d, dt, seed=case, device=DEV)
+        W = synth.sage_weights(d, hidden, L, dt, seed=case, device=DEV, bias=bool(rng.integers(0, 2)))
+        dp = DedupPath(g.offsets, g.indices, X, W, B, fan, pg_algo=algo, group=G, sampler=sampler)
+        dp.enable_backward()
+        for t in dp.H + dp.dH:
+            t.fill_(float("nan"))
+        off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+        sample = orc_dedup.sample_dedup if sampler == "node" else orc_lw.sample_layerwise
+        for it in range(2):
+            seeds = synth.seeds(n, B * G, case * 10 + it, device=DEV)
+            keys = [int(rng.integers(0, 2 ** 63)) for _ in range(G)]
+            out = torch.full((G * B, hidden), float("nan"), dtype=dt, device=DEV)
+            dp.forward(seeds, keys, out)
+            torch.cuda.synchronize()
+            if sampler == "node":       # the node-wise oracle takes one key: batch by batch, then the level-major merge is checked through the rows
+                parts = [sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fan, keys[b]) for b in range(G)]
+            else:
+                parts = [sample(off_np, idx_np, seeds.cpu().numpy(), fan, [k for k in keys for _ in range(B)])]
+            if len(parts) == 1:
+                nv, ls, ip, ix = parts[0]
+                n_nodes, n_nonleaf, nnz = len(nv), int(ls[L]), len(ix)
+                ok = np.array_equal(dp.level_start.cpu().numpy(), ls) and np.array_equal(dp.node_vertex[:n_nodes].cpu().numpy(), nv) \
+                    and np.array_equal(dp.indptr[:n_nonleaf + 1].cpu().numpy(), ip) and np.array_equal(dp.idx[:nnz].cpu().numpy(), ix) \
+                    and bool((dp.node_vertex[n_nodes:] == -1).all())
+                if not ok:
+                    failures.append(("structure", tag, it))
+                    continue
+            wb = weights_bits(W)
+            for b, st in enumerate(parts):
+                ref = orc_frontier.layer_chain(orc, to_bits(X), ORC_DT[dt], *st, wb)
+                got = out if len(parts) == 1 else out[b * B:(b + 1) * B]
+                e = rel_err(to_f64(got), ref)
+                if not (e <= TOL[dt] * L):
+                    failures.append(("forward", e, tag, it, b))
+            if dt == torch.float32 and len(parts) == 1:
+                dp.run_batch(seeds, keys)
+                dp.backward()
+                torch.cuda.synchronize()
+                _, grads = orc_frontier.layer_chain_grads(orc, to_bits(X), 0, *parts[0], wb, to_f64(dp.dHL))
+                for k in range(L):
+                    for part in range(3):
+                        if W[k][part] is None:
+                            continue
+                        e = rel_err(to_f64(dp.gW[k][part]), grads[k][part])
+                        if not (e <= 5e-5 * L):
+                            failures.append(("grad", e, k, part, tag, it))
+                for layer in dp.gW:
+                    for t in layer:
+                        if t is not None:
+                            t.zero_()
+    assert not failures, failures
