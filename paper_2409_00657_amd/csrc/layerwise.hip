@@ -32,7 +32,7 @@ constexpr int kLwMaxPairs = 65536;        // largest product of two consecutive 
 constexpr int kLwKeysPerLaunch = 64;
 constexpr int kLwUnroll = 8;              // neighbour loads in flight per thread in the adjacency pass
 constexpr uint32_t kLwChunk = 8192;       // list entries per chunk
-constexpr int kLwAdjGrid = 2048;          // workgroups of the adjacency pass (8 per CU)
+constexpr int kLwAdjGrid = 8192;          // workgroups of the adjacency pass: short contiguous shares balance best
 
 struct LwKeys {
     uint64_t keyed[kLwKeysPerLaunch];     // first hash round already applied on the host
