@@ -60,3 +60,32 @@ def layer_chain_grads(orc, X, fmt, node_vertex, level_start, indptr, idx, weight
         if k > 1:
             d = dH[:int(level_start[L - k + 2])]
     return out, grads
+
+
+def locality(node_vertex, level_start, indptr, idx, n_seeds, owner):
+    """R_micro's two counts (paper section 4, "data locality in micrographs") for the micrographs of
+    a frontier structure: the micrograph of root m is every node reachable from node m through the
+    structure's entries; n_total[m] = its distinct vertices, n_coloc[m] = its distinct vertices
+    other than the root whose home server owner[v] is the root's.  Plain sets."""
+    node_vertex = np.asarray(node_vertex)
+    n_nonleaf = len(indptr) - 1
+    n_total = np.zeros(n_seeds, np.int32)
+    n_coloc = np.zeros(n_seeds, np.int32)
+    for m in range(n_seeds):
+        seen, frontier_nodes = {m}, [m]
+        while frontier_nodes:
+            nxt = []
+            for q in frontier_nodes:
+                if q >= n_nonleaf:
+                    continue
+                for u in idx[indptr[q]:indptr[q + 1]]:
+                    u = int(u)
+                    if u >= 0 and u not in seen:
+                        seen.add(u)
+                        nxt.append(u)
+            frontier_nodes = nxt
+        root = int(node_vertex[m])
+        verts = {int(node_vertex[q]) for q in seen if node_vertex[q] >= 0}
+        n_total[m] = len(verts)
+        n_coloc[m] = sum(1 for v in verts if v != root and owner[v] == owner[root]) if root >= 0 else 0
+    return n_total, n_coloc

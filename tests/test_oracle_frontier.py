@@ -79,3 +79,41 @@ def test_deduplicated_chain_has_the_tree_chains_gradients(orc):
     for part in range(3):
         np.testing.assert_allclose(grads[1][part], g2[part], rtol=1e-10, atol=1e-12)
         np.testing.assert_allclose(grads[0][part], g1[part], rtol=1e-10, atol=1e-12)
+
+
+def test_locality_of_deduplicated_micrographs_is_the_slot_trees(orc):
+    rng = np.random.default_rng(31)
+    n, fan = 90, [4, 3, 2]
+    off, idx = _graph(rng, n, 5)
+    seeds = rng.integers(0, n, size=11).astype(np.int32)
+    owner = rng.integers(0, 3, size=n).astype(np.int32)
+    ids, _ = orc.sample(off, idx, seeds, fan, 2)
+    want = orc.micrograph_locality(ids, len(seeds), fan, owner)
+    got = frontier.locality(*dedup.sample_dedup(off, idx, seeds, fan, 2), len(seeds), owner)
+    np.testing.assert_array_equal(got[0], want[0])
+    np.testing.assert_array_equal(got[1], want[1])
+
+
+def test_locality_of_layerwise_micrographs_against_one_seed_at_a_time():
+    """A micrograph's draws depend on (key, root) only, so sampling each seed alone gives its vertex
+    set directly; the worked ring: level sets r±1, r±2 and r, with two servers of half a ring."""
+    rng = np.random.default_rng(37)
+    n, bud = 70, [3, 5, 4]
+    off, idx = _graph(rng, n, 6)
+    seeds = rng.integers(0, n, size=9).astype(np.int32)
+    seeds[4] = seeds[2]
+    keys = [int(k) for k in rng.integers(0, 1000, size=9)]
+    owner = rng.integers(0, 4, size=n).astype(np.int32)
+    got = frontier.locality(*layerwise.sample_layerwise(off, idx, seeds, bud, keys), len(seeds), owner)
+    for m, (s, k) in enumerate(zip(seeds, keys)):
+        nv = layerwise.sample_layerwise(off, idx, [s], bud, k)[0]
+        verts = set(int(v) for v in nv)
+        assert got[0][m] == len(verts)
+        assert got[1][m] == sum(1 for v in verts if v != s and owner[v] == owner[s])
+    # ring of 12, root 5, budgets large enough for the full layers: {4,6}, {3,5,7} -> 5 distinct
+    # vertices; servers {0..5} and {6..11}: co-located non-root vertices are 3 and 4
+    ring_off = np.arange(13, dtype=np.int64) * 2
+    ring_idx = np.stack([(np.arange(12) - 1) % 12, (np.arange(12) + 1) % 12], 1).ravel().astype(np.int32)
+    ring_owner = (np.arange(12) >= 6).astype(np.int32)
+    t, c = frontier.locality(*layerwise.sample_layerwise(ring_off, ring_idx, [5], [64, 64], 3), 1, ring_owner)
+    assert (t[0], c[0]) == (5, 2)
