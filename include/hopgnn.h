@@ -219,6 +219,22 @@ hopgnn_status hopgnn_sample_layerwise(const hopgnn_csr *g /*HOST struct*/, const
                                       int32_t *indptr, int32_t *idx, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * hopgnn_micrograph_locality (below) for the micrographs of a frontier structure, as written by
+ * hopgnn_sample_dedup or hopgnn_sample_layerwise - the paper's locality table has rows for
+ * node-wise and for layer-wise sampling.  The micrograph of seed m is every node reachable from node
+ * m through the structure's entries:
+ *   n_total[m] = its distinct vertices, n_coloc[m] = its distinct vertices other than the root
+ *   whose home server owner[v] is the root's.
+ * nodes_per_seed: the capacity of one micrograph (hopgnn_slots_per_seed or caps[0] of
+ * hopgnn_layerwise_caps); it sizes the per-micrograph hash set in LDS, at most 16384, else ERANGE.
+ * level_start is the DEVICE array the sampler wrote; owner DEVICE [n_vertices] int32; n_total,
+ * n_coloc DEVICE out [n_seeds].
+ */
+hopgnn_status hopgnn_frontier_locality(const int32_t *node_vertex, const int64_t *level_start, const int32_t *indptr,
+                                       const int32_t *idx, int32_t n_seeds, int32_t n_layers, int64_t nodes_per_seed,
+                                       const int32_t *owner, int32_t *n_total, int32_t *n_coloc, void *stream);
+
+/*
  * Prepares a pre-gather workspace once (zero presence map and counters; sizes and algo as in
  * hopgnn_pregather_ws_bytes).  hopgnn_pregather itself does not need it - it clears what it uses
  * - but every call of it, and every hopgnn_batch_fwd, leaves the workspace as this call does, so

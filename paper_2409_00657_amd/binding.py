@@ -28,7 +28,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
            "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
-           "hopgnn_compose_idx", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
+           "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
            "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
 
 
@@ -138,6 +138,9 @@ def load_library() -> ctypes.CDLL:
                                       c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_sample_dedup_ws_bytes.restype = c.c_size_t
     L.hopgnn_sample_dedup_ws_bytes.argtypes = [c.c_int32, c.POINTER(c.c_int32), c.c_int32]
+    L.hopgnn_frontier_locality.restype = c.c_int
+    L.hopgnn_frontier_locality.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
+                                           c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     L.hopgnn_layerwise_caps.restype = c.c_int
     L.hopgnn_layerwise_caps.argtypes = [c.POINTER(c.c_int32), c.c_int32, c.POINTER(c.c_int64)]
     L.hopgnn_sample_layerwise_ws_bytes.restype = c.c_size_t
@@ -469,6 +472,20 @@ def hopgnn_sample_dedup(offsets: torch.Tensor, indices: torch.Tensor, seeds: tor
                                             _ptr(level_start), _ptr(indptr), _ptr(idx), _ptr(ws),
                                             ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sample_dedup")
+
+
+def hopgnn_frontier_locality(node_vertex: torch.Tensor, level_start: torch.Tensor, indptr: torch.Tensor,
+                             idx: torch.Tensor, n_seeds: int, n_layers: int, nodes_per_seed: int, owner: torch.Tensor,
+                             n_total: torch.Tensor, n_coloc: torch.Tensor) -> None:
+    if owner.dtype != torch.int32 or n_total.dtype != torch.int32 or n_coloc.dtype != torch.int32 \
+            or level_start.dtype != torch.int64:
+        raise HopgnnError("owner, n_total, n_coloc must be int32 and level_start int64")
+    if n_total.numel() < n_seeds or n_coloc.numel() < n_seeds:
+        raise HopgnnError("n_total and n_coloc must hold one value per seed")
+    rc = load_library().hopgnn_frontier_locality(_ptr(node_vertex), _ptr(level_start), _ptr(indptr), _ptr(idx), n_seeds,
+                                                 n_layers, nodes_per_seed, _ptr(owner), _ptr(n_total), _ptr(n_coloc),
+                                                 _stream())
+    _check(rc, "hopgnn_frontier_locality")
 
 
 def hopgnn_layerwise_caps(budgets: Sequence[int]):

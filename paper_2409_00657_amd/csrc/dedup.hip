@@ -187,6 +187,77 @@ compose_idx(const int32_t* __restrict__ idx, int64_t n, const int32_t* __restric
     }
 }
 
+// Locality counts of the micrographs of a frontier structure (paper section 4, "data locality in
+// micrographs").  One workgroup per micrograph walks its levels: the nodes of a micrograph's level
+// are contiguous and every one of them is an entry of one of its previous-level nodes, so the next
+// level's range is [smallest entry, largest entry] of the current range's segments.  Vertices go
+// into an open-addressing hash set in LDS; the thread that claims a free cell has found a new one.
+constexpr int kFlThreads = 256;
+
+__global__ void __launch_bounds__(kFlThreads)
+frontier_locality(const int32_t* __restrict__ node_vertex, const int64_t* __restrict__ level_start,
+                  const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx, int32_t n_layers,
+                  const int32_t* __restrict__ owner, uint32_t table_mask, int32_t* __restrict__ n_total,
+                  int32_t* __restrict__ n_coloc) {
+    extern __shared__ int32_t fl_table[];
+    __shared__ uint32_t lds4[kFlThreads / kWave];
+    __shared__ int32_t next_lo, next_hi;
+    const int32_t m = blockIdx.x;
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i <= table_mask; i += kFlThreads) fl_table[i] = -1;
+    const int32_t root = node_vertex[m];
+    const int32_t root_home = root >= 0 ? owner[root] : -1;
+    const int64_t n_nonleaf = level_start[n_layers];
+    uint32_t tot = 0, col = 0;
+    int32_t lo = m, hi = m + 1;               // node range of the current level
+    for (int32_t h = 0; h <= n_layers && lo < hi; ++h) {
+        __syncthreads();
+        if (tid == 0) {
+            next_lo = 0x7FFFFFFF;
+            next_hi = -1;
+        }
+        __syncthreads();
+        for (int32_t q = lo + (int32_t)tid; q < hi; q += kFlThreads) {
+            const int32_t v = node_vertex[q];
+            if (v < 0) continue;
+            uint32_t cell = ((uint32_t)v * 2654435761u) & table_mask;
+            while (true) {
+                const int32_t old = atomicCAS(&fl_table[cell], -1, v);
+                if (old == -1) {   // first time this vertex is seen in the micrograph
+                    ++tot;
+                    if (v != root && owner[v] == root_home) ++col;
+                    break;
+                }
+                if (old == v) break;
+                cell = (cell + 1) & table_mask;
+            }
+        }
+        if (h == n_layers || hi > n_nonleaf) break;        // leaves have no segments (uniform)
+        int32_t mn = 0x7FFFFFFF, mx = -1;
+        for (int32_t e = indptr[lo] + (int32_t)tid; e < indptr[hi]; e += kFlThreads) {
+            const int32_t u = idx[e];
+            if (u >= 0) {
+                mn = u < mn ? u : mn;
+                mx = u > mx ? u : mx;
+            }
+        }
+        if (mx >= 0) {
+            atomicMin(&next_lo, mn);
+            atomicMax(&next_hi, mx);
+        }
+        __syncthreads();
+        lo = next_lo;
+        hi = next_hi + 1;
+    }
+    uint32_t t_all, c_all;
+    (void)fr_block_scan<kFlThreads, uint32_t>(tot, lds4, t_all);
+    (void)fr_block_scan<kFlThreads, uint32_t>(col, lds4, c_all);
+    if (tid == 0) {
+        n_total[m] = (int32_t)t_all;
+        n_coloc[m] = (int32_t)c_all;
+    }
+}
+
 struct DedupWs {
     size_t nodes_bytes, child_bytes, cnt_bytes, ent_start_bytes, total;
 };
@@ -303,6 +374,29 @@ extern "C" hopgnn_status hopgnn_compose_idx(const int32_t* idx, int64_t n, const
     const int64_t want = ceil_div(n, kDdThreads);
     hipLaunchKernelGGL(compose_idx, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(kDdThreads), 0,
                        static_cast<hipStream_t>(stream), idx, n, map, out);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+extern "C" hopgnn_status hopgnn_frontier_locality(const int32_t* node_vertex, const int64_t* level_start,
+                                                  const int32_t* indptr, const int32_t* idx, int32_t n_seeds,
+                                                  int32_t n_layers, int64_t nodes_per_seed, const int32_t* owner,
+                                                  int32_t* n_total, int32_t* n_coloc, void* stream) {
+    if (n_seeds < 0 || n_layers < 1 || n_layers > kMaxLayers || nodes_per_seed < 1) return HOPGNN_EINVAL;
+    if (nodes_per_seed > 16384) return HOPGNN_ERANGE;   // hash set of 2 * nodes_per_seed cells must fit 160 KB of LDS
+    if (n_seeds == 0) return HOPGNN_OK;
+    if (node_vertex == nullptr || level_start == nullptr || indptr == nullptr || idx == nullptr || owner == nullptr ||
+        n_total == nullptr || n_coloc == nullptr)
+        return HOPGNN_EINVAL;
+    uint32_t cells = 64;
+    while (cells < 2 * (uint32_t)nodes_per_seed) cells *= 2;   // load factor <= 1/2
+    const size_t lds = (size_t)cells * 4;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(frontier_locality), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds) != hipSuccess)
+        return HOPGNN_EHIP;
+    hipLaunchKernelGGL(frontier_locality, dim3((unsigned)n_seeds), dim3(kFlThreads), lds, static_cast<hipStream_t>(stream),
+                       node_vertex, level_start, indptr, idx, n_layers, owner, cells - 1, n_total, n_coloc);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }

@@ -141,6 +141,21 @@ def test_sage_bwd_dev_rejects_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_dev(*args(n_dst=1 << 31)) == 3
 
 
+def test_frontier_locality_rejects_bad_arguments(lib):
+    c = ctypes
+    one = c.c_void_p(256)
+    ok = (one, one, one, one, 4, 2, 31, one, one, one, None)
+    sub = lambda i, v: ok[:i] + (v,) + ok[i + 1:]
+    assert lib.hopgnn_frontier_locality(*sub(4, -1)) == 1
+    assert lib.hopgnn_frontier_locality(*sub(5, 0)) == 1
+    assert lib.hopgnn_frontier_locality(*sub(5, 9)) == 1
+    assert lib.hopgnn_frontier_locality(*sub(6, 0)) == 1
+    assert lib.hopgnn_frontier_locality(*sub(6, 16385)) == 3           # the hash set would not fit LDS
+    assert lib.hopgnn_frontier_locality(*sub(4, 0)) == 0               # no seeds
+    for i in (0, 1, 2, 3, 7, 8, 9):
+        assert lib.hopgnn_frontier_locality(*sub(i, None)) == 1
+
+
 def test_layerwise_capacities_and_errors(lib):
     c = ctypes
     from paper_2409_00657_amd import binding as hb

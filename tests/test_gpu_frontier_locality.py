@@ -1,0 +1,68 @@
+"""GPU parity (bit-exact) of the locality counts over frontier structures."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dedup as orc_dedup
+from oracle import frontier as orc_frontier
+from oracle import layerwise as orc_lw
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def hb():
+    from paper_2409_00657_amd import binding
+    binding.load_library()
+    return binding
+
+
+@pytest.mark.parametrize("sampler,fan,B", [("node", [5, 4], 70), ("node", [6, 5, 4], 33), ("layer", [6, 12], 70),
+                                           ("layer", [8, 10, 30], 40), ("layer", [1, 1, 1], 50), ("node", [300], 9)])
+def test_frontier_locality_bit_exact(hb, sampler, fan, B):
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    g = synth.rmat_graph(12, 8.0, seed=3, device=DEV)
+    n, L = g.n_vertices, len(fan)
+    X = synth.features(n, 8, torch.float32, device=DEV)
+    W = synth.sage_weights(8, 8, L, torch.float32, device=DEV)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, fan, sampler=sampler)
+    seeds = synth.seeds(n, B, 9, device=DEV)
+    seeds[3] = seeds[1]
+    dp.sample(seeds, 21)
+    rng = np.random.default_rng(5)
+    owner = torch.from_numpy(rng.integers(0, 4, size=n).astype(np.int32)).to(DEV)
+    n_total = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    n_coloc = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    hb.hopgnn_frontier_locality(dp.node_vertex, dp.level_start, dp.indptr, dp.idx, B, L, dp.capacity // B, owner,
+                                n_total, n_coloc)
+    torch.cuda.synchronize()
+    sample = orc_dedup.sample_dedup if sampler == "node" else orc_lw.sample_layerwise
+    st = sample(g.offsets.cpu().numpy(), g.indices.cpu().numpy(), seeds.cpu().numpy(), fan, 21)
+    want = orc_frontier.locality(*st, B, owner.cpu().numpy())
+    np.testing.assert_array_equal(n_total.cpu().numpy(), want[0])
+    np.testing.assert_array_equal(n_coloc.cpu().numpy(), want[1])
+    assert int(n_total.min()) >= 1
+
+
+def test_node_wise_counts_equal_the_slot_tree_entry_point(hb):
+    """The deduplicated micrograph has the slot tree's vertex set: both entry points agree."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath, HotPath
+    g = synth.rmat_graph(11, 6.0, seed=4, device=DEV)
+    n, fan, B = g.n_vertices, [5, 5], 120
+    X = synth.features(n, 8, torch.float32, device=DEV)
+    W = synth.sage_weights(8, 8, 2, torch.float32, device=DEV)
+    seeds = synth.seeds(n, B, 2, device=DEV)
+    owner = torch.from_numpy(np.random.default_rng(1).integers(0, 8, size=n).astype(np.int32)).to(DEV)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, fan)
+    dp.sample(seeds, 77)
+    hp = HotPath(g.offsets, g.indices, X, W, B, fan)
+    hp.sample(0, seeds, 77)
+    out = [torch.empty(B, dtype=torch.int32, device=DEV) for _ in range(4)]
+    hb.hopgnn_frontier_locality(dp.node_vertex, dp.level_start, dp.indptr, dp.idx, B, 2, dp.capacity // B, owner,
+                                out[0], out[1])
+    hb.hopgnn_micrograph_locality(hp.ids, B, fan, owner, out[2], out[3])
+    torch.cuda.synchronize()
+    assert torch.equal(out[0], out[2]) and torch.equal(out[1], out[3])
