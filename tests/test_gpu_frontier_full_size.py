@@ -1,0 +1,70 @@
+"""Frontier paths (deduplicated and layer-wise sampled micrographs) at the benchmark's full sizes,
+in the launch configuration bench.py times (one hopgnn_batch_fwd call per group): sampled
+micrographs against the oracle, which computes a micrograph from its seed alone (the draws depend on
+key and root only), and properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+from oracle import dedup as orc_dedup
+from oracle import frontier as orc_frontier
+from oracle import layerwise as orc_lw
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg_id,sampler", [(3, "node"), (3, "layer"), (4, "node"), (4, "layer"), (5, "layer")])
+def test_full_size_sampled_micrographs_vs_oracle(orc, cfg_id, sampler):
+    from paper_2409_00657_amd import binding as hb, synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    cfg = synth.CONFIGS[cfg_id]
+    g = cfg.make_graph(device=DEV)
+    X = cfg.make_features(device=DEV)
+    W = cfg.make_weights(device=DEV)
+    G, B, fan, L = cfg.groups[0], cfg.batch, list(cfg.fanouts), len(cfg.fanouts)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, fan, group=G, sampler=sampler)
+    seeds = torch.cat([synth.seeds(cfg.n_vertices, B, 50 + b, device=DEV) for b in range(G)])
+    keys = [900 + b for b in range(G)]
+    out = torch.full((G * B, cfg.hidden), float("nan"), dtype=X.dtype, device=DEV)
+    dp.forward(seeds, keys, out)
+    torch.cuda.synchronize()
+    # properties at any size
+    ls = dp.level_start.cpu().numpy()
+    assert ls[0] == 0 and ls[1] == G * B and (np.diff(ls) >= 0).all() and ls[-1] <= dp.capacity
+    nv = dp.node_vertex[:ls[-1]]
+    assert int(nv.min()) >= 0 and int(nv.max()) < cfg.n_vertices
+    assert bool((dp.node_vertex[ls[-1]:] == -1).all())
+    U = int(dp.n_uniq.item())
+    assert U == int(torch.unique(nv).numel())
+    uq = dp.uniq[:U]
+    assert bool((uq[1:] > uq[:-1]).all())
+    assert bool((uq[dp.remap[:ls[-1]].long()] == nv).all())            # every node finds its row
+    ip = dp.indptr[:ls[L] + 1]
+    assert int(ip[0]) == 0 and bool((ip[1:] >= ip[:-1]).all())
+    ent = dp.idx[:int(ip[-1])]
+    assert int(ent.max()) < ls[-1]
+    assert torch.isfinite(out.float()).all()
+    # sampled micrographs, each computed by the oracle from its seed alone
+    n_total = torch.empty(G * B, dtype=torch.int32, device=DEV)
+    n_coloc = torch.empty(G * B, dtype=torch.int32, device=DEV)
+    owner = torch.zeros(cfg.n_vertices, dtype=torch.int32, device=DEV)
+    hb.hopgnn_frontier_locality(dp.node_vertex, dp.level_start, dp.indptr, dp.idx, G * B, L, dp.capacity // (G * B),
+                                owner, n_total, n_coloc)
+    torch.cuda.synchronize()
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    sample = orc_dedup.sample_dedup if sampler == "node" else orc_lw.sample_layerwise
+    wb = weights_bits(W)
+    rng = np.random.default_rng(cfg_id)
+    for m in sorted(set([0, G * B - 1] + [int(x) for x in rng.integers(0, G * B, size=6)])):
+        st = sample(off_np, idx_np, seeds[m:m + 1].cpu().numpy(), fan, keys[m // B])
+        verts = np.unique(st[0])
+        assert int(n_total[m]) == len(verts), m
+        assert int(n_coloc[m]) == len(verts) - 1, m                      # one server: everything but the root
+        # the oracle reads only this micrograph's feature rows: renumber its vertices 0..len-1
+        rows = to_bits(X[torch.from_numpy(verts).long().to(DEV)])
+        local = (np.searchsorted(verts, st[0]).astype(np.int32),) + tuple(st[1:])
+        ref = orc_frontier.layer_chain(orc, rows, ORC_DT[X.dtype], *local, wb)
+        assert rel_err(to_f64(out[m:m + 1]), ref) <= TOL[X.dtype] * L, m
