@@ -117,3 +117,28 @@ def test_locality_of_layerwise_micrographs_against_one_seed_at_a_time():
     ring_owner = (np.arange(12) >= 6).astype(np.int32)
     t, c = frontier.locality(*layerwise.sample_layerwise(ring_off, ring_idx, [5], [64, 64], 3), 1, ring_owner)
     assert (t[0], c[0]) == (5, 2)
+
+
+def test_planted_partition_locality_follows_the_papers_table():
+    """The trend of the paper's locality table on a graph with planted locality: S servers, every
+    edge stays on its server with probability p_in.  For both samplers R_micro of one-hop micrographs
+    is about p_in, it decays with depth, and it stays above R_sub = 1/S of uniformly random vertices."""
+    rng = np.random.default_rng(41)
+    S, per, deg, p_in = 4, 150, 6, 0.8
+    n = S * per
+    owner = (np.arange(n) // per).astype(np.int32)
+    off = np.arange(n + 1, dtype=np.int64) * deg
+    stay = rng.random((n, deg)) < p_in
+    inside = owner[:, None] * per + rng.integers(0, per, size=(n, deg))
+    anywhere = rng.integers(0, n, size=(n, deg))
+    idx = np.where(stay, inside, anywhere).astype(np.int32).ravel()
+    seeds = rng.integers(0, n, size=120).astype(np.int32)
+    p_same = p_in + (1 - p_in) / S                       # a random target lands at home with 1/S
+    for name, sample, shapes in (("node", dedup.sample_dedup, ([6], [4, 4], [3, 3, 3, 3])),
+                                 ("layer", layerwise.sample_layerwise, ([6], [6, 8], [6, 8, 8, 8]))):
+        r = []
+        for fan in shapes:
+            t, c = frontier.locality(*sample(off, idx, seeds, fan, 5), len(seeds), owner)
+            r.append(float(c.sum()) / float((t - 1).sum()))        # co-located share of the non-root vertices
+        assert abs(r[0] - p_same) < 0.06, (name, r)
+        assert r[0] > r[1] > r[2] > 1.0 / S + 0.05, (name, r)
