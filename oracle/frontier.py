@@ -22,16 +22,21 @@ def layer_inputs(k, L, level_start, indptr, idx, remap):
     return n_dst, self_idx, indptr[:n_dst + 1], ix
 
 
-def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights):
-    """GraphSAGE-mean layers over a level-major frontier structure: layer k computes the rows of
-    levels 0..L-k from those of levels 0..L-k+1 (the first from the pre-gathered feature rows).
-    `orc` is the oracle package (pre-gather, gather and the pinned layer).  Returns the root rows."""
+def layer_chain(orc, X, fmt, node_vertex, level_start, indptr, idx, weights, layer=None):
+    """Layers over a level-major frontier structure: layer k computes the rows of levels 0..L-k
+    from those of levels 0..L-k+1 (the first from the pre-gathered feature rows).  `orc` is the
+    oracle package (pre-gather, gather and the pinned layers).  The layer is GraphSAGE-mean with
+    weights[k-1] = (W_self, W_neigh, bias), or `layer(k, H, self_idx, indptr, idx, relu)` -> float64
+    rows (one of the other pinned layer functions).  Returns the root rows."""
     L = len(weights)
     uniq, remap = orc.pregather(node_vertex)
     H = orc.gather(X, uniq)
     for k in range(1, L + 1):
         _, self_idx, ip, ix = layer_inputs(k, L, level_start, indptr, idx, remap)
-        out = orc.sage_fwd(H, fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
+        if layer is None:
+            out = orc.sage_fwd(H, fmt, self_idx, ip, ix, *weights[k - 1], relu=(k < L))
+        else:
+            out = layer(k, H, self_idx, ip, ix, k < L)
         H = orc.round_store(out, fmt)       # the next layer reads the rows as stored
     return out
 

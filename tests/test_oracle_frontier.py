@@ -142,3 +142,36 @@ def test_planted_partition_locality_follows_the_papers_table():
             r.append(float(c.sum()) / float((t - 1).sum()))        # co-located share of the non-root vertices
         assert abs(r[0] - p_same) < 0.06, (name, r)
         assert r[0] > r[1] > r[2] > 1.0 / S + 0.05, (name, r)
+
+
+@pytest.mark.parametrize("kind", ["gcn", "gat"])
+def test_other_layers_over_deduplicated_frontiers_give_the_tree_rows(orc, kind):
+    """GCN-style and attention layers over the deduplicated structure (parallel edges kept) against
+    the same layers over the slot tree, layer by layer with the pinned single-layer functions."""
+    rng = np.random.default_rng(29)
+    n, d, hid, fan, heads = 70, 5, 6, [4, 3, 2], 2
+    off, idx = _graph(rng, n, 4)
+    seeds = rng.integers(0, n, size=6).astype(np.int32)
+    B, L = len(seeds), 3
+    X = rng.standard_normal((n, d))
+    W = _weights(rng, d, hid, L)
+    attn = [(rng.standard_normal(hid), rng.standard_normal(hid)) for _ in range(L)]
+
+    def layer(k, H, self_idx, ip, ix, relu):
+        if kind == "gcn":
+            return orc.gcn_fwd(H, F64, self_idx, ip, ix, W[k - 1][0], W[k - 1][2], 1, relu)
+        return orc.gat_fwd(H, F64, self_idx, ip, ix, W[k - 1][0], attn[k - 1][0], attn[k - 1][1], W[k - 1][2], heads, relu)
+    got = frontier.layer_chain(orc, X, F64, *dedup.sample_dedup(off, idx, seeds, fan, 8), W, layer=layer)
+    ids, ip = orc.sample(off, idx, seeds, fan, 8)
+    uniq, remap = orc.pregather(ids)
+    lv = orc.level_sizes(B, fan)
+    H = orc.gather(X, uniq)
+    for k in range(1, L + 1):
+        n_dst = sum(lv[:L - k + 1])
+        nnz = int(ip[n_dst])
+        if k == 1:
+            self_idx, ix = remap[:n_dst], remap[B:B + nnz]
+        else:
+            self_idx, ix = None, np.where(ids[B:B + nnz] >= 0, B + np.arange(nnz), -1).astype(np.int32)
+        H = layer(k, H, self_idx, ip[:n_dst + 1], ix, k < L)
+    np.testing.assert_allclose(got, H, rtol=1e-10, atol=1e-12)
