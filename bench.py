@@ -157,8 +157,8 @@ def main_dedup(args):
     # training steps update the weights: every stream is then a worker with its own replica
     Ws = [W] + [[tuple(None if t is None else t.clone() for t in layer) for layer in W]
                 for _ in range(n_streams - 1)] if args.backward else [W] * n_streams
-    dps = [DedupPath(g.offsets, g.indices, X, Ws[j], cfg.batch, cfg.fanouts, group=group, sampler=sampler)
-           for j in range(n_streams)]
+    dps = [DedupPath(g.offsets, g.indices, X, Ws[j], cfg.batch, cfg.fanouts, group=group, sampler=sampler,
+                     model=args.model) for j in range(n_streams)]
     if args.backward:
         for d in dps:
             d.enable_backward()
@@ -232,7 +232,7 @@ def main_dedup(args):
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_vertices": cfg.n_vertices, "n_edges": g.n_edges, "feature_dim": cfg.d,
                    "batch": cfg.batch, "fanouts": cfg.fanouts, "hidden": cfg.hidden, "group": group, "streams": n_streams,
-                   "deduplicated_frontiers": True, "sampler": sampler + "-wise", "backward": bool(args.backward), "slots_per_batch": dp.capacity // group},
+                   "deduplicated_frontiers": True, "sampler": sampler + "-wise", "backward": bool(args.backward), "layer": args.model, "slots_per_batch": dp.capacity // group},
         "unique_rows_per_step": U_avg, "nodes_per_step": nodes_sum / n_replay,
         "nodes_over_slots": nodes_sum / n_replay / dp.capacity,
         "stage_ms": {k: round(v, 5) for k, v in stage.items()},
@@ -255,8 +255,8 @@ def main():
         sys.exit(2)
 
     if args.dedup or args.layerwise:
-        if args.model != "sage":
-            print("bench.py: --dedup and --layerwise run GraphSAGE-mean layers", file=sys.stderr)
+        if args.model != "sage" and args.backward:
+            print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
             sys.exit(2)
         return main_dedup(args)
 

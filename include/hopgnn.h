@@ -397,6 +397,23 @@ hopgnn_status hopgnn_gat_fwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, c
                              void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * hopgnn_gcn_fwd and hopgnn_gat_fwd for a destination row count that only the device knows (the
+ * layers over hopgnn_sample_dedup's or hopgnn_sample_layerwise's micrographs): n_dst is the
+ * capacity, *n_dst_dev (DEVICE, NULL = n_dst) the rows that exist; rows past it are neither read nor
+ * written.  Everything else as in the calls without _dev.
+ */
+hopgnn_status hopgnn_gcn_fwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                 const int32_t *self_idx, const int32_t *indptr, const int32_t *idx, int64_t n_dst,
+                                 const int64_t *n_dst_dev, const void *W, const void *bias, int32_t d_out,
+                                 int32_t norm, int32_t relu, void *out, void *ws, size_t ws_bytes, void *stream);
+
+hopgnn_status hopgnn_gat_fwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t *n_src_dev,
+                                 int32_t d_in, const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                                 int64_t n_dst, const int64_t *n_dst_dev, const void *W, const void *a_src,
+                                 const void *a_dst, const void *bias, int32_t d_out, int32_t n_heads, int32_t relu,
+                                 void *out, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * GraphSAGE-mean layer backward with in-place gradient accumulation (paper section 5.1,
  * steps 3-4: every micrograph batch runs forward and backward on the server it sits on and
  * the gradients are accumulated until the subgraph is done; discussion section: the
@@ -485,8 +502,8 @@ hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_s
  *                               (into dd_idx_l1) and the layers through hopgnn_sage_fwd_dev with
  *                               their row counts read from level_start.  The n_batches batches of
  *                               a call form one merged batch (batch b draws with keys[b]) and
- *                               every layer is one launch; GraphSAGE-mean layers; ids, slot_idx
- *                               and merge_layers are not used; remap holds the node list's
+ *                               every layer is one launch (layer_kind 1 / 2: hopgnn_gcn_fwd_dev /
+ *                               hopgnn_gat_fwd_dev); ids, slot_idx and merge_layers are not used; remap holds the node list's
  *                               positions.  With G = group and T the slots of G*n_seeds seeds:
  *                               node_vertex and remap [T], level_start int64 [n_layers+2], indptr
  *                               [T - last level + 1], dd_idx and dd_idx_l1 [T - G*n_seeds], H[k] and

@@ -29,7 +29,8 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
            "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
-           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd"]
+           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
+           "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
 
 
 class HopgnnError(RuntimeError):
@@ -176,6 +177,14 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_gcn_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p,
                                  c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_gcn_fwd_dev.restype = c.c_int
+    L.hopgnn_gcn_fwd_dev.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                     c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
+                                     c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_gat_fwd_dev.restype = c.c_int
+    L.hopgnn_gat_fwd_dev.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p,
+                                     c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                     c.c_int32, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_gat_fwd_ws_bytes.restype = c.c_size_t
     L.hopgnn_gat_fwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     L.hopgnn_gat_fwd.restype = c.c_int
@@ -424,6 +433,30 @@ def hopgnn_gat_fwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tens
                                        _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(bias), d_out, n_heads,
                                        1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_gat_fwd")
+
+
+def hopgnn_gcn_fwd_dev(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                       idx: torch.Tensor, n_dst: int, n_dst_dev: Optional[torch.Tensor], W: torch.Tensor,
+                       bias: Optional[torch.Tensor], norm: int, relu: bool, out: torch.Tensor, ws: torch.Tensor) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gcn_fwd_dev(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                           _ptr(idx), n_dst, _ptr(n_dst_dev), _ptr(W), _ptr(bias), d_out, norm,
+                                           1 if relu else 0, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(),
+                                           _stream())
+    _check(rc, "hopgnn_gcn_fwd_dev")
+
+
+def hopgnn_gat_fwd_dev(Hsrc: torch.Tensor, n_src: int, n_src_dev: Optional[torch.Tensor],
+                       self_idx: Optional[torch.Tensor], indptr: torch.Tensor, idx: torch.Tensor, n_dst: int,
+                       n_dst_dev: Optional[torch.Tensor], W: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
+                       bias: Optional[torch.Tensor], n_heads: int, relu: bool, out: torch.Tensor,
+                       ws: torch.Tensor) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gat_fwd_dev(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, _ptr(n_src_dev), d_in,
+                                           _ptr(self_idx), _ptr(indptr), _ptr(idx), n_dst, _ptr(n_dst_dev), _ptr(W),
+                                           _ptr(a_src), _ptr(a_dst), _ptr(bias), d_out, n_heads, 1 if relu else 0,
+                                           _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "hopgnn_gat_fwd_dev")
 
 
 AGG_MEAN, AGG_SUM, AGG_MAX = 0, 1, 2

@@ -29,7 +29,7 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         // per-micrograph frontiers (1: node-wise draws kept once per level, 2: layer-wise sampling):
         // node counts depend on the data, so everything is sized for the capacity and the layers
         // read their row counts from level_start
-        if (p->layer_kind != 0 || p->dedup > 2) return HOPGNN_EINVAL;
+        if (p->dedup > 2) return HOPGNN_EINVAL;
         if (p->node_vertex == nullptr || p->level_start == nullptr || p->dd_idx == nullptr || p->dd_idx_l1 == nullptr)
             return HOPGNN_EINVAL;
         const bool layerwise = p->dedup == 2;
@@ -86,10 +86,22 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
             for (int h = 0; h <= L - k; ++h) n_dst += cap_level[h] * B_all;
             void* dst = k == L ? out : p->H[k - 1];
             if (dst == nullptr) return HOPGNN_EINVAL;
-            rc = hopgnn_sage_fwd_dev(src, p->dt, n_src, d_in, k == 1 ? p->remap : nullptr, p->indptr,
-                                     k == 1 ? p->dd_idx_l1 : p->dd_idx, n_dst, p->level_start + (L - k + 1),
-                                     p->W_self[k - 1], p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], HOPGNN_AGG_MEAN,
-                                     k < L ? 1 : 0, dst, p->sage_ws, p->sage_ws_bytes, stream);
+            const int32_t* self_idx = k == 1 ? p->remap : nullptr;
+            const int32_t* idx = k == 1 ? p->dd_idx_l1 : p->dd_idx;
+            const int64_t* n_dst_dev = p->level_start + (L - k + 1);
+            if (p->layer_kind == 0)
+                rc = hopgnn_sage_fwd_dev(src, p->dt, n_src, d_in, self_idx, p->indptr, idx, n_dst, n_dst_dev,
+                                         p->W_self[k - 1], p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1],
+                                         HOPGNN_AGG_MEAN, k < L ? 1 : 0, dst, p->sage_ws, p->sage_ws_bytes, stream);
+            else if (p->layer_kind == 1)
+                rc = hopgnn_gcn_fwd_dev(src, p->dt, n_src, d_in, self_idx, p->indptr, idx, n_dst, n_dst_dev,
+                                        p->W_self[k - 1], p->bias[k - 1], p->d_out[k - 1], p->gcn_norm, k < L ? 1 : 0, dst,
+                                        p->sage_ws, p->sage_ws_bytes, stream);
+            else        // the source rows that exist: the pre-gathered rows, then the previous layer's rows
+                rc = hopgnn_gat_fwd_dev(src, p->dt, n_src, k == 1 ? p->n_uniq : p->level_start + (L - k + 2), d_in,
+                                        self_idx, p->indptr, idx, n_dst, n_dst_dev, p->W_self[k - 1], p->a_src[k - 1],
+                                        p->a_dst[k - 1], p->bias[k - 1], p->d_out[k - 1], p->gat_heads, k < L ? 1 : 0, dst,
+                                        p->sage_ws, p->sage_ws_bytes, stream);
             if (rc != HOPGNN_OK) return rc;
             src = dst;
             n_src = n_dst;

@@ -149,13 +149,14 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
               const float* __restrict__ s_dst, const int32_t* __restrict__ self_idx,
               const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx,
               const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
-              int32_t score_stride, int32_t group, int relu, typename Tr::store_t* __restrict__ out) {
+              int32_t score_stride, int32_t group, int relu, typename Tr::store_t* __restrict__ out,
+              const int64_t* __restrict__ n_rows_dev) {
     using T = typename Tr::store_t;
     static_assert(W == 1 || W == 4, "one element or one 16-byte word of z per unit");
     const int64_t gid = (int64_t)blockIdx.x * kLayerThreads + threadIdx.x;
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
-    if (r >= n_dst) return;
+    if (r >= n_dst || (n_rows_dev != nullptr && r >= *n_rows_dev)) return;
     const int32_t dh = d_out / n_heads, units = d_out / W;
     const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
     const int32_t beg = indptr[r], end = indptr[r + 1];
@@ -273,7 +274,7 @@ template <typename Tr>
 static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_dst, float* s_src, float* s_dst,
                               int64_t n_src, const int64_t* n_src_dev, const int32_t* self_idx, const int32_t* indptr,
                               const int32_t* idx, const void* bias, int64_t n_dst, int32_t d_out, int32_t n_heads,
-                              int relu, void* out, bool scores_done, hipStream_t s) {
+                              int relu, void* out, bool scores_done, const int64_t* n_dst_dev, hipStream_t s) {
     using T = typename Tr::store_t;
     const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
     if (n_src > 0 && !scores_done) {
@@ -301,11 +302,11 @@ static hopgnn_status gat_tail(const void* Z, const void* a_src, const void* a_ds
     if (vec)
         hipLaunchKernelGGL((gat_aggregate<Tr, 4>), dim3((unsigned)blocks), dim3(kLayerThreads), 0, s,
                            static_cast<const float*>(Z), s_src, s_dst, self_idx, indptr, idx, static_cast<const T*>(bias),
-                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out));
+                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out), n_dst_dev);
     else
         hipLaunchKernelGGL((gat_aggregate<Tr, 1>), dim3((unsigned)blocks), dim3(kLayerThreads), 0, s,
                            static_cast<const float*>(Z), s_src, s_dst, self_idx, indptr, idx, static_cast<const T*>(bias),
-                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out));
+                           n_dst, d_out, n_heads, stride, group, relu, static_cast<T*>(out), n_dst_dev);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
@@ -331,6 +332,15 @@ extern "C" hopgnn_status hopgnn_gcn_fwd(const void* Hsrc, hopgnn_dtype dt, int64
                                         const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
                                         int64_t n_dst, const void* W, const void* bias, int32_t d_out, int32_t norm,
                                         int32_t relu, void* out, void* ws, size_t ws_bytes, void* stream) {
+    return hopgnn_gcn_fwd_dev(Hsrc, dt, n_src, d_in, self_idx, indptr, idx, n_dst, nullptr, W, bias, d_out, norm, relu, out,
+                              ws, ws_bytes, stream);
+}
+
+extern "C" hopgnn_status hopgnn_gcn_fwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                            const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                            int64_t n_dst, const int64_t* n_dst_dev, const void* W, const void* bias,
+                                            int32_t d_out, int32_t norm, int32_t relu, void* out, void* ws,
+                                            size_t ws_bytes, void* stream) {
     const hopgnn_status chk = check_common(dt, n_src, d_in, n_dst, d_out);
     if (chk != HOPGNN_OK) return chk;
     if (norm != 0 && norm != 1) return HOPGNN_EINVAL;
@@ -357,13 +367,16 @@ extern "C" hopgnn_status hopgnn_gcn_fwd(const void* Hsrc, hopgnn_dtype dt, int64
     // with n_src == 0 every self index must be negative; identity self was rejected above
     const AggSpec spec{self_idx, 1, norm ? kAggOpMean : kAggOpSum};
     hopgnn_status st;
-    if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);
-    else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);
-    else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec);
+    if (dt == HOPGNN_F32)
+        st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
+    else if (dt == HOPGNN_BF16)
+        st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
+    else
+        st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, agg, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
     if (st != HOPGNN_OK) return st;
     // rows-times-W over the aggregate (identity row map, K = d_in)
     return project_dispatch(dt, s, agg, nullptr, agg, W, W, Wt, L.KP, bias, n_dst, d_in, d_in, d_out, relu, zero, out, 0,
-                            nullptr);
+                            n_dst_dev);
 }
 
 extern "C" size_t hopgnn_gat_fwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out,
@@ -378,6 +391,16 @@ extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64
                                         int64_t n_dst, const void* W, const void* a_src, const void* a_dst,
                                         const void* bias, int32_t d_out, int32_t n_heads, int32_t relu, void* out,
                                         void* ws, size_t ws_bytes, void* stream) {
+    return hopgnn_gat_fwd_dev(Hsrc, dt, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, nullptr, W, a_src, a_dst, bias,
+                              d_out, n_heads, relu, out, ws, ws_bytes, stream);
+}
+
+extern "C" hopgnn_status hopgnn_gat_fwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                            int32_t d_in, const int32_t* self_idx, const int32_t* indptr,
+                                            const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev, const void* W,
+                                            const void* a_src, const void* a_dst, const void* bias, int32_t d_out,
+                                            int32_t n_heads, int32_t relu, void* out, void* ws, size_t ws_bytes,
+                                            void* stream) {
     const hopgnn_status chk = check_common(dt, n_src, d_in, n_dst, d_out);
     if (chk != HOPGNN_OK) return chk;
     if (n_heads < 1 || n_heads > kMaxHeads || d_out % n_heads != 0) return HOPGNN_EINVAL;
@@ -422,10 +445,10 @@ extern "C" hopgnn_status hopgnn_gat_fwd(const void* Hsrc, hopgnn_dtype dt, int64
     }
     if (dt == HOPGNN_F32)
         return gat_tail<TrF32>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
-                               relu, out, score_gemm, s);
+                               relu, out, score_gemm, n_dst_dev, s);
     if (dt == HOPGNN_BF16)
         return gat_tail<TrBF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads,
-                                relu, out, false, s);
+                                relu, out, false, n_dst_dev, s);
     return gat_tail<TrF16>(Z, a_src, a_dst, s_src, s_dst, n_src, n_src_dev, self_idx, indptr, idx, bias, n_dst, d_out, n_heads, relu,
-                           out, false, s);
+                           out, false, n_dst_dev, s);
 }

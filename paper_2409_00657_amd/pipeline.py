@@ -375,13 +375,17 @@ class DedupPath:
     every buffer has the slot tree's size and the layers take their row counts from the device."""
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor, weights, n_seeds: int,
-                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO, group: int = 1, sampler: str = "node"):
+                 fanouts: Sequence[int], pg_algo: int = hb.PG_AUTO, group: int = 1, sampler: str = "node",
+                 model: str = "sage", gat_heads: int = 4):
         """`group` batches of n_seeds seeds form one merged batch (block b draws with key b).
         sampler "node": the node-wise draws of the slot tree, every (level, vertex) kept once;
-        "layer": layer-wise sampling, `fanouts` then holds the budget of draws per level."""
+        "layer": layer-wise sampling, `fanouts` then holds the budget of draws per level.
+        model "sage" | "gcn" | "gat" as in HotPath (forward only for gcn and gat)."""
         if sampler not in ("node", "layer"):
             raise hb.HopgnnError("sampler must be node or layer")
-        self.sampler = sampler
+        if model not in ("sage", "gcn", "gat"):
+            raise hb.HopgnnError("model must be sage, gcn or gat")
+        self.sampler, self.model, self.gat_heads = sampler, model, gat_heads
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
@@ -407,8 +411,18 @@ class DedupPath:
         self.dd_ws = torch.empty(ws_bytes(B, list(fanouts)), dtype=torch.uint8, device=dev)
         hidden = weights[0][0].shape[1]
         self.H = [torch.empty((sh.n_dst(k), hidden), dtype=X.dtype, device=dev) for k in range(1, L + 1)]
-        self.sage_ws = torch.empty(max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0], hidden)
-                                       for k in range(1, L + 1)), dtype=torch.uint8, device=dev)
+        ws_layers = max(hb.hopgnn_sage_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0], hidden)
+                        for k in range(1, L + 1))
+        if model == "gcn":
+            ws_layers = max(ws_layers, max(hb.hopgnn_gcn_fwd_ws_bytes(X.dtype, sh.n_dst(k), weights[k - 1][0].shape[0],
+                                                                      hidden) for k in range(1, L + 1)))
+        if model == "gat":
+            self.attn = [(synth.weight(1, hidden, X.dtype, 200 + 2 * k, device=dev).view(-1),
+                          synth.weight(1, hidden, X.dtype, 201 + 2 * k, device=dev).view(-1)) for k in range(L)]
+            n_src = [self.cap] + [sh.n_dst(k) for k in range(1, L)]
+            ws_layers = max(ws_layers, max(hb.hopgnn_gat_fwd_ws_bytes(X.dtype, n_src[k], weights[k][0].shape[0], hidden,
+                                                                      gat_heads) for k in range(L)))
+        self.sage_ws = torch.empty(ws_layers, dtype=torch.uint8, device=dev)
         # row count of layer k = first node of level L-k+1: one-element views into level_start
         self._n_dst_dev = [self.level_start[L - k + 1:L - k + 2] for k in range(1, L + 1)]
         # the same buffers as a plan for hopgnn_batch_fwd (the sequence issued from C)
@@ -425,6 +439,11 @@ class DedupPath:
             pl.bias[i] = None if bias is None else bias.data_ptr()
             pl.H[i] = self.H[i].data_ptr()
         pl.pg_algo, pl.group, pl.dedup = pg_algo, self.n_keys, 1 if sampler == "node" else 2
+        pl.layer_kind = {"sage": 0, "gcn": 1, "gat": 2}[model]
+        pl.gcn_norm, pl.gat_heads = 1, gat_heads
+        if model == "gat":
+            for i, (a_s, a_d) in enumerate(self.attn):
+                pl.a_src[i], pl.a_dst[i] = a_s.data_ptr(), a_d.data_ptr()
         pl.indptr, pl.uniq, pl.uniq_capacity, pl.n_uniq = self.indptr.data_ptr(), self.uniq.data_ptr(), self.cap, \
             self.n_uniq.data_ptr()
         pl.remap, pl.Xu = self.remap.data_ptr(), self.Xu.data_ptr()
@@ -485,15 +504,27 @@ class DedupPath:
         Ws, Wn, bias = self.weights[k - 1]
         n_dst = sh.n_dst(k)
         src, n_src = (self.Xu, self.cap) if k == 1 else (self.H[k - 2], sh.n_dst(k - 1))
-        hb.hopgnn_sage_fwd_dev(src, n_src, self.remap[:n_dst] if k == 1 else None, self.indptr[:n_dst + 1],
-                               self.idx_l1 if k == 1 else self.idx, n_dst, self._n_dst_dev[k - 1], Ws, Wn, bias,
-                               hb.AGG_MEAN, k < sh.n_layers, self.H[k - 1], self.sage_ws)
+        self_idx, idx = (self.remap[:n_dst], self.idx_l1) if k == 1 else (None, self.idx)
+        n_dst_dev, relu = self._n_dst_dev[k - 1], k < sh.n_layers
+        if self.model == "sage":
+            hb.hopgnn_sage_fwd_dev(src, n_src, self_idx, self.indptr[:n_dst + 1], idx, n_dst, n_dst_dev, Ws, Wn, bias,
+                                   hb.AGG_MEAN, relu, self.H[k - 1], self.sage_ws)
+        elif self.model == "gcn":
+            hb.hopgnn_gcn_fwd_dev(src, n_src, self_idx, self.indptr[:n_dst + 1], idx, n_dst, n_dst_dev, Ws, bias, 1, relu,
+                                  self.H[k - 1], self.sage_ws)
+        else:       # the source rows that exist: the pre-gathered rows, then the previous layer's rows
+            a_src, a_dst = self.attn[k - 1]
+            hb.hopgnn_gat_fwd_dev(src, n_src, self.n_uniq if k == 1 else self._n_dst_dev[k - 2], self_idx,
+                                  self.indptr[:n_dst + 1], idx, n_dst, n_dst_dev, Ws, a_src, a_dst, bias, self.gat_heads,
+                                  relu, self.H[k - 1], self.sage_ws)
         return self.H[k - 1]
 
     def enable_backward(self) -> None:
         """Gradient accumulators (fp32, zero) and the buffers of the backward pass over the frontier
         structure, as HotPath.enable_backward: the harness's loss is L = 1/2 |H_L|^2 for fp32
         activations (dL/dH_L = H_L, read in place) and L = <G, H_L> with a fixed G otherwise."""
+        if self.model != "sage":
+            raise hb.HopgnnError("backward is built for the GraphSAGE-mean layer")
         sh, dev = self.shape, self.X.device
         L = sh.n_layers
         hidden = self.weights[0][0].shape[1]

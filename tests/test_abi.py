@@ -141,6 +141,24 @@ def test_sage_bwd_dev_rejects_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_dev(*args(n_dst=1 << 31)) == 3
 
 
+def test_layer_calls_with_device_counts_reject_bad_arguments(lib):
+    c = ctypes
+    one = c.c_void_p(256)
+    gcn = lambda dt=0, n_dst=4, norm=1, ws_bytes=1 << 30, self_idx=one, n_src=8: (
+        one, dt, n_src, 4, self_idx, one, one, n_dst, None, one, None, 4, norm, 0, one, one, ws_bytes, None)
+    assert lib.hopgnn_gcn_fwd_dev(*gcn(dt=9)) == 1
+    assert lib.hopgnn_gcn_fwd_dev(*gcn(norm=2)) == 1
+    assert lib.hopgnn_gcn_fwd_dev(*gcn(n_dst=0)) == 0
+    assert lib.hopgnn_gcn_fwd_dev(*gcn(ws_bytes=8)) == 2
+    assert lib.hopgnn_gcn_fwd_dev(*gcn(self_idx=None, n_src=2)) == 1
+    gat = lambda heads=2, n_dst=4, ws_bytes=1 << 30: (
+        one, 0, 8, None, 4, one, one, one, n_dst, None, one, one, one, None, 4, heads, 0, one, one, ws_bytes, None)
+    assert lib.hopgnn_gat_fwd_dev(*gat(heads=3)) == 1          # 3 heads do not divide 4
+    assert lib.hopgnn_gat_fwd_dev(*gat(heads=0)) == 1
+    assert lib.hopgnn_gat_fwd_dev(*gat(n_dst=0)) == 0
+    assert lib.hopgnn_gat_fwd_dev(*gat(ws_bytes=8)) == 2
+
+
 def test_frontier_locality_rejects_bad_arguments(lib):
     c = ctypes
     one = c.c_void_p(256)
