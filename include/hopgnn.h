@@ -449,6 +449,22 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               void *stream);
 
 /*
+ * hopgnn_sage_bwd for neighbour lists in slot order, the layers k >= 2 of hopgnn_sample's trees:
+ * self rows are the rows themselves and entry e of the segments is source row first_child_row + e
+ * (idx[e] holds that number, or -1 for an invalid slot: what hopgnn_sample writes as slot_idx, with
+ * first_child_row = n_seeds).  Every source row then has at most one parent, so dHsrc is written
+ * row by row without atomic adds and without a clearing pass: bit-stable, and about four times
+ * faster than the general scatter.  n_src must be at least first_child_row + the number of entries;
+ * source rows past that are zeroed.  0 <= first_child_row <= n_dst, else EINVAL.  Other arguments,
+ * workspace and errors as hopgnn_sage_bwd; the weight gradients are computed by the same kernels.
+ */
+hopgnn_status hopgnn_sage_bwd_slots(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                    const int32_t *indptr, const int32_t *idx, int64_t n_dst, int64_t first_child_row,
+                                    const void *W_self, const void *W_neigh, const void *out_fwd, int32_t relu,
+                                    const float *dOut, int32_t d_out, float *gW_self, float *gW_neigh, float *gbias,
+                                    float *dHsrc, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * hopgnn_sage_bwd for row counts that only the device knows (the layers over hopgnn_sample_dedup's
  * or hopgnn_sample_layerwise's micrographs, as hopgnn_sage_fwd_dev in the forward pass): n_dst and
  * n_src are the capacities the launches and the workspace are sized for, *n_dst_dev and *n_src_dev

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
+           "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
            "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
@@ -112,6 +112,11 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                   c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
                                   c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_sage_bwd_slots.restype = c.c_int
+    L.hopgnn_sage_bwd_slots.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int64,
+                                        c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
+                                        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
+                                        c.c_void_p]
     L.hopgnn_sage_bwd_dev.restype = c.c_int
     L.hopgnn_sage_bwd_dev.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p,
                                       c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
@@ -373,6 +378,20 @@ def hopgnn_sage_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Ten
                                         1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
                                         _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sage_bwd")
+
+
+def hopgnn_sage_bwd_slots(Hsrc: torch.Tensor, n_src: int, indptr: torch.Tensor, idx: torch.Tensor, n_dst: int,
+                          first_child_row: int, W_self: torch.Tensor, W_neigh: torch.Tensor,
+                          out_fwd: Optional[torch.Tensor], relu: bool, dOut: torch.Tensor, gW_self: torch.Tensor,
+                          gW_neigh: torch.Tensor, gbias: Optional[torch.Tensor], dHsrc: Optional[torch.Tensor],
+                          ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_bwd_slots(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(indptr), _ptr(idx),
+                                              n_dst, first_child_row, _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd),
+                                              1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
+                                              _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(),
+                                              _stream())
+    _check(rc, "hopgnn_sage_bwd_slots")
 
 
 def hopgnn_sage_bwd_dev(Hsrc: torch.Tensor, n_src: int, n_src_dev: Optional[torch.Tensor],

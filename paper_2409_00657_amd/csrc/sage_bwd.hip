@@ -406,6 +406,40 @@ bwd_scatter(const float* __restrict__ D, const int32_t* __restrict__ self_idx, c
     }
 }
 
+// The same sums without atomics for neighbour lists in slot order: entry e of the segments is source
+// row first + e (or -1), self rows are the rows themselves, so every source row has one parent and is
+// written exactly once - by its parent's lanes, or by its own when it has none (rows below `first`).
+// One group of lanes per source row u < n_src; the group of u < n_dst also serves u as a parent.
+// Rows past the last entry are zeroed.  Nothing is read-modified: bit-stable, no zero pass before.
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_pull_slots(const float* __restrict__ D, const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx,
+               int64_t n_dst, int64_t n_src, int64_t first, int32_t d_in, int32_t group, float* __restrict__ dHsrc) {
+    const int64_t gid = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    const int64_t r = gid / group;
+    const int32_t j = (int32_t)(gid - r * group);
+    if (r >= n_src) return;
+    const int64_t two_d = 2 * (int64_t)d_in;
+    if (r < first || r >= first + (int64_t)indptr[n_dst])      // a row without a parent: its own self term, if any
+        for (int32_t c = j; c < d_in; c += group) dHsrc[r * d_in + c] = r < n_dst ? D[r * two_d + c] : 0.f;
+    if (r >= n_dst) return;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    int32_t cnt = 0;
+    for (int32_t e = beg; e < end; ++e) cnt += idx[e] >= 0 ? 1 : 0;
+    const float inv = cnt > 0 ? 1.f / (float)cnt : 0.f;
+    const float* Dr = D + r * two_d + d_in;
+    for (int32_t e = beg; e < end; ++e) {
+        const int64_t u = first + e;
+        if (u >= n_src) break;                        // fewer source rows than entries: not this call's layout
+        const bool fed = idx[e] >= 0;                 // an invalid slot takes no part in the mean
+        const bool is_dst = u < n_dst;                // ... but a destination row still has its self term
+        for (int32_t c = j; c < d_in; c += group) {
+            float v = fed ? Dr[c] * inv : 0.f;
+            if (is_dst) v += D[u * two_d + c];
+            dHsrc[u * d_in + c] = v;
+        }
+    }
+}
+
 // ---------------------------------------------------------------- update --
 
 // W <- W - lr * grad (fp32 arithmetic, one rounding to the stored type), optionally grad <- 0.
@@ -465,7 +499,8 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                                     const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W_self,
                                     const void* W_neigh, const void* out_fwd, int32_t relu, const float* dOut,
                                     int32_t d_out, float* gW_self, float* gW_neigh, float* gbias, float* dHsrc,
-                                    void* ws, const BwdWs& L, const int64_t* n_dst_dev, hipStream_t s) {
+                                    void* ws, const BwdWs& L, const int64_t* n_dst_dev, int64_t slot_first,
+                                    hipStream_t s) {
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     char* p = static_cast<char*>(ws);
@@ -517,8 +552,12 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                            n_dst_dev);
         HOPGNN_LAUNCH_CHECK();
         const int group = mean_group(d_in);
-        hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                           D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc, n_dst_dev);
+        if (slot_first >= 0)
+            hipLaunchKernelGGL(bwd_pull_slots, dim3((unsigned)ceil_div(n_src * group, kBwdThreads)), dim3(kBwdThreads), 0,
+                               s, D, indptr, idx, n_dst, n_src, slot_first, d_in, group, dHsrc);
+        else
+            hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                               D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc, n_dst_dev);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
@@ -536,18 +575,47 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
                                out_fwd, relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, stream);
 }
 
+static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                  int32_t d_in, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                  int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
+                                  const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
+                                  float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
+                                  int64_t slot_first, void* stream);
+
 extern "C" hopgnn_status hopgnn_sage_bwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
                                              int32_t d_in, const int32_t* self_idx, const int32_t* indptr,
                                              const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
                                              const void* W_self, const void* W_neigh, const void* out_fwd, int32_t relu,
                                              const float* dOut, int32_t d_out, float* gW_self, float* gW_neigh,
                                              float* gbias, float* dHsrc, void* ws, size_t ws_bytes, void* stream) {
+    return sage_bwd_any(Hsrc, dt, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, n_dst_dev, W_self, W_neigh, out_fwd,
+                        relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, -1, stream);
+}
+
+extern "C" hopgnn_status hopgnn_sage_bwd_slots(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                               const int32_t* indptr, const int32_t* idx, int64_t n_dst,
+                                               int64_t first_child_row, const void* W_self, const void* W_neigh,
+                                               const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out,
+                                               float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
+                                               size_t ws_bytes, void* stream) {
+    if (first_child_row < 0 || first_child_row > n_dst) return HOPGNN_EINVAL;
+    if (n_dst > 0 && idx == nullptr) return HOPGNN_EINVAL;
+    return sage_bwd_any(Hsrc, dt, n_src, nullptr, d_in, nullptr, indptr, idx, n_dst, nullptr, W_self, W_neigh, out_fwd, relu,
+                        dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, first_child_row, stream);
+}
+
+static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                  int32_t d_in, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                  int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
+                                  const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
+                                  float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
+                                  int64_t slot_first, void* stream) {
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
     if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dHsrc != nullptr && n_src > 0) {
+    if (dHsrc != nullptr && n_src > 0 && (slot_first < 0 || n_dst == 0)) {    // the slot-order pull writes every row itself
         // a fill kernel, never a memset node; with a device row count only the rows that exist
         if (!aligned(dHsrc, 16) || ((int64_t)n_src * d_in) % 4 != 0 || (n_src_dev != nullptr && d_in % 4 != 0)) {
             const int64_t n = (int64_t)n_src * d_in;
@@ -572,12 +640,12 @@ extern "C" hopgnn_status hopgnn_sage_bwd_dev(const void* Hsrc, hopgnn_dtype dt, 
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     if (dt == HOPGNN_F32)
         return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
+                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
     if (dt == HOPGNN_BF16)
         return sage_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu,
-                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
+                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
     return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, s);
+                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
 }
 
 extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,

@@ -295,19 +295,24 @@ class HotPath:
                 (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, _bias, d_out, relu, out, _ws, _wsb) = fwd
                 d_out_grad = self.dHL.data_ptr() if k == L else self.dH[k - 1].data_ptr()
                 gWs, gWn, gb = self.gW[k - 1]
-                per_batch.append((src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, out, relu, d_out_grad,
-                                  d_out, gWs.data_ptr(), gWn.data_ptr(), None if gb is None else gb.data_ptr(),
-                                  self.dH[k - 2].data_ptr() if k > 1 else None, self.bwd_ws.data_ptr(),
-                                  self.bwd_ws.numel()))
+                tail = (Ws, Wn, out, relu, d_out_grad, d_out, gWs.data_ptr(), gWn.data_ptr(),
+                        None if gb is None else gb.data_ptr(), self.dH[k - 2].data_ptr() if k > 1 else None,
+                        self.bwd_ws.data_ptr(), self.bwd_ws.numel())
+                if k > 1:   # neighbour lists in slot order: the input gradient is written without atomics
+                    per_batch.append((self._lib.hopgnn_sage_bwd_slots,
+                                      (src, dt, n_src, d_in, indptr, idx, n_dst, sh.n_seeds) + tail))
+                else:
+                    per_batch.append((self._lib.hopgnn_sage_bwd,
+                                      (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst) + tail))
             self._bwd_args.append(per_batch)
 
     def backward(self, b: int, stream=None) -> None:
         """Backward of batch b's layers, last to first; weight gradients accumulate in self.gW."""
         st = self._stream(stream)
-        for a in self._bwd_args[b]:
-            rc = self._lib.hopgnn_sage_bwd(*a, st)
+        for fn, a in self._bwd_args[b]:
+            rc = fn(*a, st)
             if rc:
-                hb._check(rc, "hopgnn_sage_bwd")
+                hb._check(rc, fn.__name__)
 
     def apply_sgd(self, lr: float, stream=None) -> None:
         """End of an iteration: every weight matrix (and bias) takes its accumulated gradient,

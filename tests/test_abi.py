@@ -141,6 +141,19 @@ def test_sage_bwd_dev_rejects_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_dev(*args(n_dst=1 << 31)) == 3
 
 
+def test_slot_order_backward_rejects_bad_arguments(lib):
+    c = ctypes
+    one = c.c_void_p(256)
+    args = lambda first=2, n_dst=4, n_src=8, idx=one, dt=0: (
+        one, dt, n_src, 4, one, idx, n_dst, first, one, one, None, 0, one, 4, one, one, None, None, one, 1 << 30, None)
+    assert lib.hopgnn_sage_bwd_slots(*args(first=-1)) == 1
+    assert lib.hopgnn_sage_bwd_slots(*args(first=5)) == 1            # past the destination rows
+    assert lib.hopgnn_sage_bwd_slots(*args(idx=None)) == 1
+    assert lib.hopgnn_sage_bwd_slots(*args(dt=5)) == 1
+    assert lib.hopgnn_sage_bwd_slots(*args(n_src=2)) == 1            # self rows are the rows themselves
+    assert lib.hopgnn_sage_bwd_slots(*args(n_dst=0, first=0)) == 0
+
+
 def test_layer_calls_with_device_counts_reject_bad_arguments(lib):
     c = ctypes
     one = c.c_void_p(256)

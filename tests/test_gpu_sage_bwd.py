@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import rel_err, to_bits, to_f64
+from helpers import ORC_DT, rel_err, to_bits, to_f64
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -229,3 +229,59 @@ def test_training_iterations_lower_the_loss(hb):
         assert all(float(gw.abs().max().item()) == 0.0 for gw in hp.gW[0][:2])
     assert all(b < a for a, b in zip(losses, losses[1:])), losses
     assert losses[-1] < 0.8 * losses[0], losses
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("case", range(6))
+def test_slot_order_backward_equals_the_general_call(hb, orc, dt, case):
+    """Neighbour lists in slot order (entry e is source row first + e, or -1): the atomic-free pull
+    gives the general call's gradients bit for bit (every row has at most two contributions there,
+    so the general call is exact too), and the oracle's within tolerance."""
+    rng = np.random.default_rng(50 + case)
+    n_dst = [1, 7, 64, 300, 300, 1000][case]
+    first = [0, 3, 64, 0, 120, 1000][case]            # 0: every row can be a child; n_dst: none is
+    d_in, d_out = [(4, 4), (12, 20), (32, 32), (100, 64), (33, 7), (16, 128)][case]
+    lens = rng.integers(0, 6, size=n_dst)
+    if case == 1:
+        lens[:] = 0                                   # no entries at all
+    indptr = np.zeros(n_dst + 1, np.int32)
+    indptr[1:] = np.cumsum(lens)
+    nnz = int(indptr[-1])
+    n_src = max(first + nnz, n_dst) + [0, 5, 0, 17, 1, 0][case]     # some rows past the last entry
+    idx = (first + np.arange(nnz)).astype(np.int32)
+    idx[rng.random(nnz) < 0.2] = -1
+    f32 = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32)).to(DEV)
+    H, Ws, Wn = f32(n_src, d_in).to(dt), (f32(d_in, d_out) / 3).to(dt), (f32(d_in, d_out) / 3).to(dt)
+    out_fwd, dOut = f32(n_dst, d_out).to(dt), f32(n_dst, d_out)
+    ip, ix = torch.from_numpy(indptr).to(DEV), torch.from_numpy(idx if nnz else np.zeros(1, np.int32)).to(DEV)
+
+    def run(slots):
+        g = [torch.zeros((d_in, d_out), device=DEV), torch.zeros((d_in, d_out), device=DEV), torch.zeros(d_out, device=DEV)]
+        dH = torch.full((n_src, d_in), float("nan"), device=DEV)
+        ws = torch.empty(hb.hopgnn_sage_bwd_ws_bytes(dt, n_dst, d_in, d_out, True), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)
+        if slots:
+            hb.hopgnn_sage_bwd_slots(H, n_src, ip, ix, n_dst, first, Ws, Wn, out_fwd, True, dOut, g[0], g[1], g[2], dH, ws)
+        else:
+            hb.hopgnn_sage_bwd(H, n_src, None, ip, ix, n_dst, Ws, Wn, out_fwd, True, dOut, g[0], g[1], g[2], dH, ws)
+        torch.cuda.synchronize()
+        return g + [dH]
+    a, b, a2 = run(True), run(False), run(True)
+    for x, y, z in zip(a, b, a2):
+        assert torch.equal(x, y) and torch.equal(x, z)
+    ref = orc.sage_bwd(to_bits(H), ORC_DT[dt], None, indptr, idx, to_bits(Ws), to_bits(Wn), to_bits(out_fwd), True,
+                       dOut.cpu().numpy().astype(np.float64))
+    tol = 2e-5 if dt == torch.float32 else 2e-2
+    assert rel_err(to_f64(a[3]), ref[3]) <= tol
+    assert rel_err(to_f64(a[0]), ref[0]) <= tol and rel_err(to_f64(a[1]), ref[1]) <= tol
+
+
+def test_slot_order_backward_argument_errors(hb):
+    one = torch.zeros(64, device=DEV)
+    i32 = torch.zeros(8, dtype=torch.int32, device=DEV)
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    W = torch.zeros((4, 4), device=DEV)
+    for first in (-1, 5):
+        with pytest.raises(hb.HopgnnError):
+            hb.hopgnn_sage_bwd_slots(one.view(16, 4), 16, i32, i32, 4, first, W, W, None, False, one.view(16, 4)[:4],
+                                     W.clone(), W.clone(), None, torch.zeros((16, 4), device=DEV), ws)
