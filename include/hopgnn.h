@@ -600,6 +600,15 @@ hopgnn_status hopgnn_sgd_update(void *W, hopgnn_dtype dt, float *grad, int64_t n
                                 void *stream);
 
 /*
+ * hopgnn_sgd_update for all of a model's parameter arrays in one launch: W[t] (DEVICE, type dt,
+ * n[t] elements) takes grad[t] (DEVICE fp32), t < n_tensors <= 32.  W, grad and n are HOST arrays
+ * of n_tensors entries; arrays of length 0 are skipped.  Same arithmetic, element by element.
+ */
+hopgnn_status hopgnn_sgd_update_multi(void *const *W /*HOST*/, hopgnn_dtype dt, float *const *grad /*HOST*/,
+                                      const int64_t *n /*HOST*/, int32_t n_tensors, float lr, int32_t zero_grad,
+                                      void *stream);
+
+/*
  * Micrograph merging (paper section 5.3).  HOST-only bookkeeping, no device work.
  *
  * counts is a HOST matrix [n_models x n_steps], row-major: root vertices model m trains at

@@ -27,7 +27,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sgd_update", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
+           "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
            "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
@@ -112,6 +112,9 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_sage_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                   c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
                                   c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_sgd_update_multi.restype = c.c_int
+    L.hopgnn_sgd_update_multi.argtypes = [c.POINTER(c.c_void_p), c.c_int, c.POINTER(c.c_void_p), c.POINTER(c.c_int64),
+                                          c.c_int32, c.c_float, c.c_int32, c.c_void_p]
     L.hopgnn_sage_bwd_slots.restype = c.c_int
     L.hopgnn_sage_bwd_slots.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int64,
                                         c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
@@ -498,6 +501,32 @@ def hopgnn_sgd_update(W: torch.Tensor, grad: torch.Tensor, lr: float, zero_grad:
     st = _stream() if stream is None else stream
     _check(load_library().hopgnn_sgd_update(_ptr(W), DTYPE_OF[W.dtype], _ptr(grad), W.numel(), lr,
                                             1 if zero_grad else 0, st), "hopgnn_sgd_update")
+
+
+class SgdTensors:
+    """The parameter arrays of a model and their gradient accumulators, marshalled once for
+    hopgnn_sgd_update_multi."""
+
+    def __init__(self, pairs):
+        pairs = [(W, g) for W, g in pairs if W is not None]
+        if not pairs:
+            raise HopgnnError("no tensors")
+        dts = {W.dtype for W, _ in pairs}
+        if len(dts) != 1 or any(g.dtype != torch.float32 or g.numel() != W.numel() for W, g in pairs):
+            raise HopgnnError("one parameter type; gradients fp32 with as many elements as their parameters")
+        self.dt = DTYPE_OF[pairs[0][0].dtype]
+        self.n_tensors = len(pairs)
+        self.W = (ctypes.c_void_p * self.n_tensors)(*[W.data_ptr() for W, _ in pairs])
+        self.grad = (ctypes.c_void_p * self.n_tensors)(*[g.data_ptr() for _, g in pairs])
+        self.n = (ctypes.c_int64 * self.n_tensors)(*[W.numel() for W, _ in pairs])
+        self._keep = pairs
+
+    def update(self, lr: float, zero_grad: bool = True, stream=None) -> None:
+        st = _stream() if stream is None else stream
+        rc = load_library().hopgnn_sgd_update_multi(self.W, self.dt, self.grad, self.n, self.n_tensors, lr,
+                                                    1 if zero_grad else 0, st)
+        if rc:
+            _check(rc, "hopgnn_sgd_update_multi")
 
 
 def hopgnn_sample_dedup_ws_bytes(n_seeds: int, fanouts: Sequence[int]) -> int:

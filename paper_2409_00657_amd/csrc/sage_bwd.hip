@@ -453,6 +453,35 @@ sgd_update(typename Tr::store_t* __restrict__ W, float* __restrict__ grad, int64
     }
 }
 
+// The same update for up to kSgdMaxTensors tensors in one launch (a model's weight matrices and
+// biases are a handful of small arrays: one launch each would cost more than the arithmetic).
+constexpr int kSgdMaxTensors = 32;
+struct SgdBatch {
+    void* W[kSgdMaxTensors];
+    float* grad[kSgdMaxTensors];
+    int64_t first_block[kSgdMaxTensors + 1];     // blocks [first_block[t], first_block[t+1]) work on tensor t
+    int64_t n[kSgdMaxTensors];
+    int32_t n_tensors;
+};
+constexpr int kSgdPerBlock = 4 * kBwdThreads;    // elements per workgroup
+
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+sgd_update_multi(SgdBatch b, float lr, int zero_grad) {
+    int t = 0;
+    while (t + 1 < b.n_tensors && (int64_t)blockIdx.x >= b.first_block[t + 1]) ++t;
+    typename Tr::store_t* W = static_cast<typename Tr::store_t*>(b.W[t]);
+    float* grad = b.grad[t];
+    const int64_t i0 = ((int64_t)blockIdx.x - b.first_block[t]) * kSgdPerBlock;
+    for (int k = 0; k < 4; ++k) {
+        const int64_t i = i0 + k * kBwdThreads + threadIdx.x;
+        if (i < b.n[t]) {
+            W[i] = Tr::from_f(Tr::to_f(W[i]) - lr * grad[i]);
+            if (zero_grad) grad[i] = 0.f;
+        }
+    }
+}
+
 // ------------------------------------------------------------------ host --
 
 struct BwdWs {
@@ -665,6 +694,36 @@ extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad
     else
         hipLaunchKernelGGL(sgd_update<TrF16>, grid, dim3(kBwdThreads), 0, s, static_cast<_Float16*>(W), grad, n, lr,
                            zero_grad);
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
+}
+
+extern "C" hopgnn_status hopgnn_sgd_update_multi(void* const* W, hopgnn_dtype dt, float* const* grad, const int64_t* n,
+                                                 int32_t n_tensors, float lr, int32_t zero_grad, void* stream) {
+    if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
+    if (n_tensors < 0 || n_tensors > kSgdMaxTensors) return HOPGNN_EINVAL;
+    if (n_tensors == 0) return HOPGNN_OK;
+    if (W == nullptr || grad == nullptr || n == nullptr) return HOPGNN_EINVAL;
+    SgdBatch b{};
+    int64_t blocks = 0;
+    for (int32_t t = 0; t < n_tensors; ++t) {
+        if (n[t] < 0 || (n[t] > 0 && (W[t] == nullptr || grad[t] == nullptr))) return HOPGNN_EINVAL;
+        if (n[t] == 0) continue;                 // nothing to update: no blocks
+        b.W[b.n_tensors] = W[t];
+        b.grad[b.n_tensors] = grad[t];
+        b.n[b.n_tensors] = n[t];
+        b.first_block[b.n_tensors] = blocks;
+        blocks += ceil_div(n[t], kSgdPerBlock);
+        ++b.n_tensors;
+    }
+    b.first_block[b.n_tensors] = blocks;
+    if (blocks == 0) return HOPGNN_OK;
+    if (blocks >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const dim3 grid((unsigned)blocks);
+    if (dt == HOPGNN_F32) hipLaunchKernelGGL(sgd_update_multi<TrF32>, grid, dim3(kBwdThreads), 0, s, b, lr, zero_grad);
+    else if (dt == HOPGNN_BF16) hipLaunchKernelGGL(sgd_update_multi<TrBF16>, grid, dim3(kBwdThreads), 0, s, b, lr, zero_grad);
+    else hipLaunchKernelGGL(sgd_update_multi<TrF16>, grid, dim3(kBwdThreads), 0, s, b, lr, zero_grad);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }

@@ -287,6 +287,7 @@ class HotPath:
         ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
                                                    hidden, k > 1) for k in range(1, L + 1))
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._sgd = hb.SgdTensors([(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads)])
         self._bwd_args = []
         for b in range(self.group):
             per_batch = []
@@ -317,12 +318,7 @@ class HotPath:
     def apply_sgd(self, lr: float, stream=None) -> None:
         """End of an iteration: every weight matrix (and bias) takes its accumulated gradient,
         W <- W - lr * gW, and the accumulators are cleared."""
-        st = self._stream(stream)
-        for (Ws, Wn, b), (gWs, gWn, gb) in zip(self.weights, self.gW):
-            hb.hopgnn_sgd_update(Ws, gWs, lr, True, st)
-            hb.hopgnn_sgd_update(Wn, gWn, lr, True, st)
-            if b is not None:
-                hb.hopgnn_sgd_update(b, gb, lr, True, st)
+        self._sgd.update(lr, True, self._stream(stream))
 
     # -- whole steps ---------------------------------------------------------
 
@@ -544,6 +540,7 @@ class DedupPath:
         ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
                                                    hidden, k > 1) for k in range(1, L + 1))
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self._sgd = hb.SgdTensors([(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads)])
         self._raw_calls()
 
     def _raw_calls(self):
@@ -615,13 +612,7 @@ class DedupPath:
             rc = fn(*args, st)
             if rc:
                 hb._check(rc, fn.__name__)
-        lib, dt = self._lib, hb.DTYPE_OF[self.X.dtype]
-        for layer, grads in zip(self.weights, self.gW):
-            for W, gW in zip(layer, grads):
-                if W is not None:
-                    rc = lib.hopgnn_sgd_update(W.data_ptr(), dt, gW.data_ptr(), W.numel(), lr, 1, st)
-                    if rc:
-                        hb._check(rc, "hopgnn_sgd_update")
+        self._sgd.update(lr, True, st)
 
     def backward(self) -> None:
         """Backward of the layers of the batch last run by run_batch, last layer first; weight
@@ -644,11 +635,7 @@ class DedupPath:
 
     def apply_sgd(self, lr: float) -> None:
         """W <- W - lr * gW for every weight matrix and bias; the accumulators are cleared."""
-        for (Ws, Wn, b), (gWs, gWn, gb) in zip(self.weights, self.gW):
-            hb.hopgnn_sgd_update(Ws, gWs, lr, True)
-            hb.hopgnn_sgd_update(Wn, gWn, lr, True)
-            if b is not None:
-                hb.hopgnn_sgd_update(b, gb, lr, True)
+        self._sgd.update(lr, True)
 
     def run_batch(self, seeds: torch.Tensor, key, marks=None) -> torch.Tensor:
         """Returns the [group*B, hidden] rows of the last layer (level 0 always has every root).

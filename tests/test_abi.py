@@ -141,6 +141,21 @@ def test_sage_bwd_dev_rejects_bad_arguments(lib):
     assert lib.hopgnn_sage_bwd_dev(*args(n_dst=1 << 31)) == 3
 
 
+def test_sgd_update_multi_rejects_bad_arguments(lib):
+    c = ctypes
+    W = (c.c_void_p * 2)(256, 512)
+    g = (c.c_void_p * 2)(1024, 2048)
+    n = (c.c_int64 * 2)(4, 4)
+    assert lib.hopgnn_sgd_update_multi(W, 0, g, n, 0, 0.1, 1, None) == 0           # no tensors
+    assert lib.hopgnn_sgd_update_multi(W, 0, g, n, 33, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi(W, 0, g, n, -1, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi(W, 4, g, n, 2, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi(None, 0, g, n, 2, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi(W, 0, g, (c.c_int64 * 2)(4, -1), 2, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi((c.c_void_p * 2)(256, None), 0, g, n, 2, 0.1, 1, None) == 1
+    assert lib.hopgnn_sgd_update_multi(W, 0, g, (c.c_int64 * 2)(0, 0), 2, 0.1, 1, None) == 0     # all empty
+
+
 def test_slot_order_backward_rejects_bad_arguments(lib):
     c = ctypes
     one = c.c_void_p(256)

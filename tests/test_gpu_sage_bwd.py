@@ -285,3 +285,23 @@ def test_slot_order_backward_argument_errors(hb):
         with pytest.raises(hb.HopgnnError):
             hb.hopgnn_sage_bwd_slots(one.view(16, 4), 16, i32, i32, 4, first, W, W, None, False, one.view(16, 4)[:4],
                                      W.clone(), W.clone(), None, torch.zeros((16, 4), device=DEV), ws)
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16, torch.float16])
+def test_sgd_update_multi_equals_one_call_per_tensor(hb, dt):
+    rng = np.random.default_rng(8)
+    sizes = [1, 1023, 1024, 1025, 4096 * 3 + 5, 100 * 256, 7]
+    Ws = [torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(DEV).to(dt) for n in sizes]
+    gs = [torch.from_numpy(rng.standard_normal(n).astype(np.float32)).to(DEV) for n in sizes]
+    W1, g1 = [w.clone() for w in Ws], [g.clone() for g in gs]
+    for w, g in zip(W1, g1):
+        hb.hopgnn_sgd_update(w, g, 0.05, True)
+    W2, g2 = [w.clone() for w in Ws], [g.clone() for g in gs]
+    hb.SgdTensors(list(zip(W2, g2)) + [(None, None)]).update(0.05, True)
+    W3, g3 = [w.clone() for w in Ws], [g.clone() for g in gs]
+    hb.SgdTensors(list(zip(W3, g3))).update(0.05, False)
+    torch.cuda.synchronize()
+    for a, b, c, ga, gb, gc, g0 in zip(W1, W2, W3, g1, g2, g3, gs):
+        assert torch.equal(a, b) and torch.equal(a, c)
+        assert float(ga.abs().max()) == 0.0 and float(gb.abs().max()) == 0.0
+        assert torch.equal(gc, g0)                                    # not cleared when not asked to
