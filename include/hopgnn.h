@@ -457,10 +457,16 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
  * faster than the general scatter.  n_src must be at least first_child_row + the number of entries;
  * source rows past that are zeroed.  0 <= first_child_row <= n_dst, else EINVAL.  Other arguments,
  * workspace and errors as hopgnn_sage_bwd; the weight gradients are computed by the same kernels.
+ *
+ * mean_fwd (here and in hopgnn_sage_bwd_dev): DEVICE [n_dst x d_in] of type dt, the neighbour means of
+ * the forward call, or NULL to compute them again.  hopgnn_sage_fwd, _agg (mean) and _dev leave them
+ * in the first n_dst * d_in elements of their workspace, which stay valid until that workspace is
+ * used again: a caller that gives every layer its own forward workspace passes that pointer here.
  */
 hopgnn_status hopgnn_sage_bwd_slots(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
                                     const int32_t *indptr, const int32_t *idx, int64_t n_dst, int64_t first_child_row,
-                                    const void *W_self, const void *W_neigh, const void *out_fwd, int32_t relu,
+                                    const void *W_self, const void *W_neigh, const void *out_fwd,
+                                    const void *mean_fwd, int32_t relu,
                                     const float *dOut, int32_t d_out, float *gW_self, float *gW_neigh, float *gbias,
                                     float *dHsrc, void *ws, size_t ws_bytes, void *stream);
 
@@ -476,7 +482,8 @@ hopgnn_status hopgnn_sage_bwd_slots(const void *Hsrc, hopgnn_dtype dt, int64_t n
 hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t *n_src_dev,
                                   int32_t d_in, const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
                                   int64_t n_dst, const int64_t *n_dst_dev, const void *W_self, const void *W_neigh,
-                                  const void *out_fwd, int32_t relu, const float *dOut, int32_t d_out,
+                                  const void *out_fwd, const void *mean_fwd, int32_t relu, const float *dOut,
+                                  int32_t d_out,
                                   float *gW_self, float *gW_neigh, float *gbias, float *dHsrc, void *ws,
                                   size_t ws_bytes, void *stream);
 

@@ -117,14 +117,15 @@ def load_library() -> ctypes.CDLL:
                                           c.c_int32, c.c_float, c.c_int32, c.c_void_p]
     L.hopgnn_sage_bwd_slots.restype = c.c_int
     L.hopgnn_sage_bwd_slots.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int64,
-                                        c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p, c.c_int32,
+                                        c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
+                                        c.c_int32,
                                         c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
                                         c.c_void_p]
     L.hopgnn_sage_bwd_dev.restype = c.c_int
     L.hopgnn_sage_bwd_dev.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p,
-                                      c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
-                                      c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
-                                      c.c_size_t, c.c_void_p]
+                                      c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_int32, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_micrograph_locality.restype = c.c_int
     L.hopgnn_micrograph_locality.argtypes = [c.c_void_p, c.c_int32, c.POINTER(c.c_int32), c.c_int32,
                                              c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -387,11 +388,11 @@ def hopgnn_sage_bwd_slots(Hsrc: torch.Tensor, n_src: int, indptr: torch.Tensor, 
                           first_child_row: int, W_self: torch.Tensor, W_neigh: torch.Tensor,
                           out_fwd: Optional[torch.Tensor], relu: bool, dOut: torch.Tensor, gW_self: torch.Tensor,
                           gW_neigh: torch.Tensor, gbias: Optional[torch.Tensor], dHsrc: Optional[torch.Tensor],
-                          ws: torch.Tensor) -> None:
+                          ws: torch.Tensor, mean_fwd: Optional[torch.Tensor] = None) -> None:
     d_in, d_out = W_self.shape
     rc = load_library().hopgnn_sage_bwd_slots(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(indptr), _ptr(idx),
                                               n_dst, first_child_row, _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd),
-                                              1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
+                                              _ptr(mean_fwd), 1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
                                               _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(),
                                               _stream())
     _check(rc, "hopgnn_sage_bwd_slots")
@@ -402,11 +403,12 @@ def hopgnn_sage_bwd_dev(Hsrc: torch.Tensor, n_src: int, n_src_dev: Optional[torc
                         n_dst_dev: Optional[torch.Tensor], W_self: torch.Tensor, W_neigh: torch.Tensor,
                         out_fwd: Optional[torch.Tensor], relu: bool, dOut: torch.Tensor, gW_self: torch.Tensor,
                         gW_neigh: torch.Tensor, gbias: Optional[torch.Tensor], dHsrc: Optional[torch.Tensor],
-                        ws: torch.Tensor) -> None:
+                        ws: torch.Tensor, mean_fwd: Optional[torch.Tensor] = None) -> None:
     d_in, d_out = W_self.shape
     rc = load_library().hopgnn_sage_bwd_dev(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, _ptr(n_src_dev), d_in,
                                             _ptr(self_idx), _ptr(indptr), _ptr(idx), n_dst, _ptr(n_dst_dev),
-                                            _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd), 1 if relu else 0, _ptr(dOut),
+                                            _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd), _ptr(mean_fwd),
+                                            1 if relu else 0, _ptr(dOut),
                                             d_out, _ptr(gW_self), _ptr(gW_neigh), _ptr(gbias), _ptr(dHsrc), _ptr(ws),
                                             ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sage_bwd_dev")

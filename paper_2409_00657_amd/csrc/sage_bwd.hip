@@ -529,7 +529,7 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                                     const void* W_neigh, const void* out_fwd, int32_t relu, const float* dOut,
                                     int32_t d_out, float* gW_self, float* gW_neigh, float* gbias, float* dHsrc,
                                     void* ws, const BwdWs& L, const int64_t* n_dst_dev, int64_t slot_first,
-                                    hipStream_t s) {
+                                    const void* mean_fwd, hipStream_t s) {
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     char* p = static_cast<char*>(ws);
@@ -541,10 +541,15 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     float* D = reinterpret_cast<float*>(reinterpret_cast<char*>(bias_partial) + L.bias_bytes);
     if (n_src == 0) Hsrc = zero;   // nothing is read from it unmasked
 
-    // the means again (same kernel as the forward pass, same rounding to the activation type)
-    hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s, kAggMean,
-                                       n_dst_dev);
-    if (st != HOPGNN_OK) return st;
+    // the means: the forward call's, if the caller kept them, else computed again (same kernel as the
+    // forward pass, same rounding to the activation type)
+    if (mean_fwd != nullptr) {
+        mean = const_cast<T*>(static_cast<const T*>(mean_fwd));
+    } else {
+        hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s,
+                                           kAggMean, n_dst_dev);
+        if (st != HOPGNN_OK) return st;
+    }
 
     const float* dZ = dOut;
     if (relu) {
@@ -601,7 +606,7 @@ extern "C" hopgnn_status hopgnn_sage_bwd(const void* Hsrc, hopgnn_dtype dt, int6
                                          float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
                                          size_t ws_bytes, void* stream) {
     return hopgnn_sage_bwd_dev(Hsrc, dt, n_src, nullptr, d_in, self_idx, indptr, idx, n_dst, nullptr, W_self, W_neigh,
-                               out_fwd, relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, stream);
+                               out_fwd, nullptr, relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, stream);
 }
 
 static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
@@ -609,28 +614,30 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
                                   int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
                                   const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
                                   float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
-                                  int64_t slot_first, void* stream);
+                                  int64_t slot_first, const void* mean_fwd, void* stream);
 
 extern "C" hopgnn_status hopgnn_sage_bwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
                                              int32_t d_in, const int32_t* self_idx, const int32_t* indptr,
                                              const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
-                                             const void* W_self, const void* W_neigh, const void* out_fwd, int32_t relu,
-                                             const float* dOut, int32_t d_out, float* gW_self, float* gW_neigh,
-                                             float* gbias, float* dHsrc, void* ws, size_t ws_bytes, void* stream) {
+                                             const void* W_self, const void* W_neigh, const void* out_fwd,
+                                             const void* mean_fwd, int32_t relu, const float* dOut, int32_t d_out,
+                                             float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
+                                             size_t ws_bytes, void* stream) {
     return sage_bwd_any(Hsrc, dt, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, n_dst_dev, W_self, W_neigh, out_fwd,
-                        relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, -1, stream);
+                        relu, dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, -1, mean_fwd, stream);
 }
 
 extern "C" hopgnn_status hopgnn_sage_bwd_slots(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
                                                const int32_t* indptr, const int32_t* idx, int64_t n_dst,
                                                int64_t first_child_row, const void* W_self, const void* W_neigh,
-                                               const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out,
+                                               const void* out_fwd, const void* mean_fwd, int32_t relu,
+                                               const float* dOut, int32_t d_out,
                                                float* gW_self, float* gW_neigh, float* gbias, float* dHsrc, void* ws,
                                                size_t ws_bytes, void* stream) {
     if (first_child_row < 0 || first_child_row > n_dst) return HOPGNN_EINVAL;
     if (n_dst > 0 && idx == nullptr) return HOPGNN_EINVAL;
     return sage_bwd_any(Hsrc, dt, n_src, nullptr, d_in, nullptr, indptr, idx, n_dst, nullptr, W_self, W_neigh, out_fwd, relu,
-                        dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, first_child_row, stream);
+                        dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, first_child_row, mean_fwd, stream);
 }
 
 static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
@@ -638,7 +645,7 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
                                   int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
                                   const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
                                   float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
-                                  int64_t slot_first, void* stream) {
+                                  int64_t slot_first, const void* mean_fwd, void* stream) {
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
@@ -669,12 +676,12 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     if (dt == HOPGNN_F32)
         return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
+                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
     if (dt == HOPGNN_BF16)
         return sage_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu,
-                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
+                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
     return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, s);
+                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
 }
 
 extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,

@@ -288,6 +288,14 @@ class HotPath:
                                                    hidden, k > 1) for k in range(1, L + 1))
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self._sgd = hb.SgdTensors([(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads)])
+        # every layer gets a forward workspace of its own: the neighbour means it leaves there are
+        # then still in place when the layer's backward call wants them
+        self._fwd_ws = [torch.empty(hb.hopgnn_sage_fwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
+                                                                hidden), dtype=torch.uint8, device=dev)
+                        for k in range(1, L + 1)]
+        for per_batch in self._layer_args:
+            for k in range(L):
+                per_batch[k] = per_batch[k][:-2] + (self._fwd_ws[k].data_ptr(), self._fwd_ws[k].numel())
         self._bwd_args = []
         for b in range(self.group):
             per_batch = []
@@ -296,15 +304,15 @@ class HotPath:
                 (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, _bias, d_out, relu, out, _ws, _wsb) = fwd
                 d_out_grad = self.dHL.data_ptr() if k == L else self.dH[k - 1].data_ptr()
                 gWs, gWn, gb = self.gW[k - 1]
-                tail = (Ws, Wn, out, relu, d_out_grad, d_out, gWs.data_ptr(), gWn.data_ptr(),
-                        None if gb is None else gb.data_ptr(), self.dH[k - 2].data_ptr() if k > 1 else None,
-                        self.bwd_ws.data_ptr(), self.bwd_ws.numel())
+                tail = (Ws, Wn, out, self._fwd_ws[k - 1].data_ptr(), relu, d_out_grad, d_out, gWs.data_ptr(),
+                        gWn.data_ptr(), None if gb is None else gb.data_ptr(),
+                        self.dH[k - 2].data_ptr() if k > 1 else None, self.bwd_ws.data_ptr(), self.bwd_ws.numel())
                 if k > 1:   # neighbour lists in slot order: the input gradient is written without atomics
                     per_batch.append((self._lib.hopgnn_sage_bwd_slots,
                                       (src, dt, n_src, d_in, indptr, idx, n_dst, sh.n_seeds) + tail))
                 else:
-                    per_batch.append((self._lib.hopgnn_sage_bwd,
-                                      (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst) + tail))
+                    per_batch.append((self._lib.hopgnn_sage_bwd_dev,
+                                      (src, dt, n_src, None, d_in, self_idx, indptr, idx, n_dst, None) + tail))
             self._bwd_args.append(per_batch)
 
     def backward(self, b: int, stream=None) -> None:
@@ -500,6 +508,10 @@ class DedupPath:
     def compose(self) -> None:
         hb.hopgnn_compose_idx(self.idx, self.remap, self.idx_l1)
 
+    def _layer_ws(self, k: int) -> torch.Tensor:
+        """Layer k's forward workspace: its own once the backward pass is enabled, else the shared one."""
+        return self._fwd_ws[k - 1] if hasattr(self, "_fwd_ws") else self.sage_ws
+
     def layer(self, k: int) -> torch.Tensor:
         sh = self.shape
         Ws, Wn, bias = self.weights[k - 1]
@@ -509,7 +521,7 @@ class DedupPath:
         n_dst_dev, relu = self._n_dst_dev[k - 1], k < sh.n_layers
         if self.model == "sage":
             hb.hopgnn_sage_fwd_dev(src, n_src, self_idx, self.indptr[:n_dst + 1], idx, n_dst, n_dst_dev, Ws, Wn, bias,
-                                   hb.AGG_MEAN, relu, self.H[k - 1], self.sage_ws)
+                                   hb.AGG_MEAN, relu, self.H[k - 1], self._layer_ws(k))
         elif self.model == "gcn":
             hb.hopgnn_gcn_fwd_dev(src, n_src, self_idx, self.indptr[:n_dst + 1], idx, n_dst, n_dst_dev, Ws, bias, 1, relu,
                                   self.H[k - 1], self.sage_ws)
@@ -541,6 +553,10 @@ class DedupPath:
                                                    hidden, k > 1) for k in range(1, L + 1))
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
         self._sgd = hb.SgdTensors([(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads)])
+        # a forward workspace per layer: the means a layer leaves there serve its backward call
+        self._fwd_ws = [torch.empty(hb.hopgnn_sage_fwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
+                                                                hidden), dtype=torch.uint8, device=dev)
+                        for k in range(1, L + 1)]
         self._raw_calls()
 
     def _raw_calls(self):
@@ -567,8 +583,8 @@ class DedupPath:
             fwd.append((lib.hopgnn_sage_fwd_dev,
                         (p(src), dt, n_src, Ws.shape[0], p(self.remap) if k == 1 else None, p(self.indptr),
                          p(self.idx_l1 if k == 1 else self.idx), n_dst, p(self._n_dst_dev[k - 1]), p(Ws), p(Wn), p(bias),
-                         Ws.shape[1], hb.AGG_MEAN, 1 if k < L else 0, p(self.H[k - 1]), p(self.sage_ws),
-                         self.sage_ws.numel())))
+                         Ws.shape[1], hb.AGG_MEAN, 1 if k < L else 0, p(self.H[k - 1]), p(self._layer_ws(k)),
+                         self._layer_ws(k).numel())))
         self._calls_fwd = fwd
         bwd = []
         if hasattr(self, "gW"):
@@ -583,7 +599,8 @@ class DedupPath:
                 bwd.append((lib.hopgnn_sage_bwd_dev,
                             (p(src), dt, n_src, p(n_src_dev), Ws.shape[0], p(self.remap) if k == 1 else None,
                              p(self.indptr), p(self.idx_l1 if k == 1 else self.idx), n_dst, p(self._n_dst_dev[k - 1]),
-                             p(Ws), p(Wn), p(self.H[k - 1]), 1 if k < L else 0, p(self.dHL if k == L else self.dH[k - 1]),
+                             p(Ws), p(Wn), p(self.H[k - 1]), p(self._fwd_ws[k - 1]), 1 if k < L else 0,
+                             p(self.dHL if k == L else self.dH[k - 1]),
                              Ws.shape[1], p(gWs), p(gWn), p(gb), p(self.dH[k - 2]) if k > 1 else None, p(self.bwd_ws),
                              self.bwd_ws.numel())))
         self._calls_bwd = bwd
@@ -631,7 +648,7 @@ class DedupPath:
                                    self.indptr[:n_dst + 1], self.idx_l1 if k == 1 else self.idx, n_dst,
                                    self._n_dst_dev[k - 1], Ws, Wn, self.H[k - 1], k < L,
                                    self.dHL if k == L else self.dH[k - 1], gWs, gWn, gb,
-                                   self.dH[k - 2] if k > 1 else None, self.bwd_ws)
+                                   self.dH[k - 2] if k > 1 else None, self.bwd_ws, mean_fwd=self._fwd_ws[k - 1])
 
     def apply_sgd(self, lr: float) -> None:
         """W <- W - lr * gW for every weight matrix and bias; the accumulators are cleared."""

@@ -128,8 +128,8 @@ def test_sage_bwd_dev_rejects_bad_arguments(lib):
     c = ctypes
     one = c.c_void_p(256)
     args = lambda dt=0, n_src=8, n_dst=4, d_in=4, d_out=4, ws=one, ws_bytes=1 << 30, self_idx=one: (
-        one, dt, n_src, None, d_in, self_idx, one, one, n_dst, None, one, one, one, 1, one, d_out, one, one, None, None,
-        ws, ws_bytes, None)
+        one, dt, n_src, None, d_in, self_idx, one, one, n_dst, None, one, one, one, None, 1, one, d_out, one, one, None,
+        None, ws, ws_bytes, None)
     assert lib.hopgnn_sage_bwd_dev(*args(dt=7)) == 1
     assert lib.hopgnn_sage_bwd_dev(*args(n_dst=-1)) == 1
     assert lib.hopgnn_sage_bwd_dev(*args(d_in=0)) == 1
@@ -160,7 +160,8 @@ def test_slot_order_backward_rejects_bad_arguments(lib):
     c = ctypes
     one = c.c_void_p(256)
     args = lambda first=2, n_dst=4, n_src=8, idx=one, dt=0: (
-        one, dt, n_src, 4, one, idx, n_dst, first, one, one, None, 0, one, 4, one, one, None, None, one, 1 << 30, None)
+        one, dt, n_src, 4, one, idx, n_dst, first, one, one, None, None, 0, one, 4, one, one, None, None, one, 1 << 30,
+        None)
     assert lib.hopgnn_sage_bwd_slots(*args(first=-1)) == 1
     assert lib.hopgnn_sage_bwd_slots(*args(first=5)) == 1            # past the destination rows
     assert lib.hopgnn_sage_bwd_slots(*args(idx=None)) == 1

@@ -305,3 +305,34 @@ def test_sgd_update_multi_equals_one_call_per_tensor(hb, dt):
         assert torch.equal(a, b) and torch.equal(a, c)
         assert float(ga.abs().max()) == 0.0 and float(gb.abs().max()) == 0.0
         assert torch.equal(gc, g0)                                    # not cleared when not asked to
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.float16])
+def test_backward_with_the_forward_calls_means(hb, dt):
+    """The forward call leaves the neighbour means at the start of its workspace; handing them to
+    the backward call instead of computing them again gives the same bits."""
+    rng = np.random.default_rng(12)
+    n_src, n_dst, d_in, d_out = 400, 250, 24, 40
+    indptr, idx = _rand_csr(rng, n_dst, n_src, 6)
+    self_idx = rng.integers(-1, n_src, size=n_dst).astype(np.int32)
+    f32 = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32)).to(DEV)
+    H, Ws, Wn = f32(n_src, d_in).to(dt), (f32(d_in, d_out) / 4).to(dt), (f32(d_in, d_out) / 4).to(dt)
+    dOut = f32(n_dst, d_out)
+    ip, ix, si = (torch.from_numpy(a).to(DEV) for a in (indptr, idx, self_idx))
+    out = torch.empty((n_dst, d_out), dtype=dt, device=DEV)
+    ws_f = torch.empty(hb.hopgnn_sage_fwd_ws_bytes(dt, n_dst, d_in, d_out), dtype=torch.uint8, device=DEV)
+    hb.hopgnn_sage_fwd(H, n_src, si, ip, ix, n_dst, Ws, Wn, None, True, out, ws_f)
+
+    def run(mean):
+        g = [torch.zeros((d_in, d_out), device=DEV), torch.zeros((d_in, d_out), device=DEV), torch.zeros(d_out, device=DEV)]
+        dH = torch.empty((n_src, d_in), device=DEV)
+        ws = torch.empty(hb.hopgnn_sage_bwd_ws_bytes(dt, n_dst, d_in, d_out, True), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)
+        hb.hopgnn_sage_bwd_dev(H, n_src, None, si, ip, ix, n_dst, None, Ws, Wn, out, True, dOut, g[0], g[1], g[2], dH, ws,
+                               mean_fwd=mean)
+        torch.cuda.synchronize()
+        return g + [dH]
+    a, b = run(None), run(ws_f)
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x, y)
+    assert rel_err(to_f64(a[3]), to_f64(b[3])) <= 1e-6          # float atomics: order of arrival
