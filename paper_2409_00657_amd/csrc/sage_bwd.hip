@@ -103,12 +103,17 @@ template <typename Tr>
 struct GradFrag {
     typename Raw4<Tr>::type a[2];
     float4 b[2];
+    typename Raw4<Tr>::type o[2];      // MASK: the stored forward outputs that decide the ReLU mask
 };
 
-template <typename Tr, bool VEC>
+// MASK: dZ is the incoming gradient itself and OutFwd the stored forward output; the ReLU mask is
+// applied on the way into LDS (a layer whose input gradient is not needed has no other reader of
+// the masked gradient, so the separate masking pass and its array are saved).
+template <typename Tr, bool VEC, bool MASK>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
-                const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ, int64_t n_dst, int32_t d_in,
+                const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ,
+                const typename Tr::store_t* __restrict__ OutFwd, int64_t n_dst, int32_t d_in,
                 int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
                 float* __restrict__ bias_partial, const int64_t* __restrict__ n_rows_dev) {
     __shared__ __attribute__((aligned(16))) float As[2][kGradRows][kGradLd];
@@ -147,17 +152,20 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
                 const T* pa = ka < d_in ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - d_in : 0);
                 f.a[i] = *reinterpret_cast<const R4*>(pa);
                 f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + (nb < d_out ? nb : 0));
+                if (MASK) f.o[i] = *reinterpret_cast<const R4*>(OutFwd + r * d_out + (nb < d_out ? nb : 0));
             } else {
-                union { R4 v; T e[4]; } av;
+                union { R4 v; T e[4]; } av, ov;
                 float bv[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int k = ka + e, n = nb + e;
                     av.e[e] = k < d_in ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - d_in : 0)];
                     bv[e] = dZ[r * d_out + (n < d_out ? n : 0)];
+                    if (MASK) ov.e[e] = OutFwd[r * d_out + (n < d_out ? n : 0)];
                 }
                 f.a[i] = av.v;
                 f.b[i] = make_float4(bv[0], bv[1], bv[2], bv[3]);
+                if (MASK) f.o[i] = ov.v;
             }
         }
     };
@@ -168,12 +176,20 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
             const float4 aw = Raw4<Tr>::widen(f.a[i]);
             float av[4] = {aw.x, aw.y, aw.z, aw.w};
             float bv[4] = {f.b[i].x, f.b[i].y, f.b[i].z, f.b[i].w};
+            float ov[4] = {1.f, 1.f, 1.f, 1.f};
+            if (MASK) {
+                const float4 ow = Raw4<Tr>::widen(f.o[i]);
+                ov[0] = ow.x;
+                ov[1] = ow.y;
+                ov[2] = ow.z;
+                ov[3] = ow.w;
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int k = ka + e, n = nb + e;
                 const bool a_ok = row_ok && k < K && (k >= d_in || sidx[i] >= 0);
                 av[e] = a_ok ? av[e] : 0.f;
-                bv[e] = row_ok && n < d_out ? bv[e] : 0.f;
+                bv[e] = row_ok && n < d_out && ov[e] > 0.f ? bv[e] : 0.f;
             }
             *reinterpret_cast<float4*>(&As[buf][lr + 8 * i][lc]) = make_float4(av[0], av[1], av[2], av[3]);
             *reinterpret_cast<float4*>(&Bs[buf][lr + 8 * i][lc]) = make_float4(bv[0], bv[1], bv[2], bv[3]);
@@ -552,7 +568,9 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     }
 
     const float* dZ = dOut;
-    if (relu) {
+    // the masked gradient has a second reader only when the input gradient is wanted
+    const bool fuse_mask = relu && !(dHsrc != nullptr && n_src > 0);
+    if (relu && !fuse_mask) {
         const int64_t n = n_dst * d_out;
         // four elements per thread when the total allows it (and, with a device row count, every row does)
         if (n % 4 == 0 && (n_dst_dev == nullptr || d_out % 4 == 0) && aligned(out_fwd, 16) && aligned(dOut, 16))
@@ -567,11 +585,13 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     }
 
     const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
-    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16);
-    auto grad_kernel = vec ? bwd_weight_grad<Tr, true> : bwd_weight_grad<Tr, false>;
+    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16) && aligned(mean, 16) &&
+                     (!fuse_mask || aligned(out_fwd, 16));
+    auto grad_kernel = fuse_mask ? (vec ? bwd_weight_grad<Tr, true, true> : bwd_weight_grad<Tr, false, true>)
+                                 : (vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>);
     hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
-                       static_cast<const T*>(Hsrc), self_idx, mean, dZ, n_dst, d_in, d_out, L.rows_per_split, tiles_n,
-                       partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+                       static_cast<const T*>(Hsrc), self_idx, mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out,
+                       L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
     HOPGNN_LAUNCH_CHECK();
     const int64_t red = (int64_t)2 * d_in * d_out + d_out;
     hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,

@@ -69,8 +69,13 @@ def test_sage_bwd_vs_oracle(hb, orc, shape):
             assert rel_err(to_f64(gb), ref[2]) <= 2e-5
         if want_dh:
             assert rel_err(to_f64(dH), ref[3]) <= 2e-5
+        if relu:
+            unfused = (gWs, gWn, gb)
     # accumulation in place: a second call adds the same amount again, bit for bit
     g1 = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, True, dOut, False, True)
+    # without an input gradient the ReLU mask is applied inside the weight-gradient kernel: same bits
+    for a, b in zip(g1[:3], unfused):
+        assert torch.equal(a, b)
     g2 = _run_gpu(hb, H, self_idx, indptr, idx, Ws, Wn, out_fwd, True, dOut, False, True, acc_init=g1[:3])
     for a, b in zip(g1[:3], g2[:3]):
         assert torch.equal(b, a + a)
@@ -166,6 +171,12 @@ def test_sage_bwd_two_byte_activations_vs_oracle(hb, orc, dt, shape):
             assert rel_err(to_f64(gb), ref[2]) <= 2e-5
         if want_dh:
             assert rel_err(to_f64(dH), ref[3]) <= 2e-5
+        if relu:    # the same call without an input gradient masks inside the weight-gradient kernel: same bits
+            g2 = [torch.zeros_like(gWs), torch.zeros_like(gWn), torch.zeros(d_out, device=DEV)]
+            hb.hopgnn_sage_bwd(H, n_src, t(self_idx), t(indptr), t(idx), n_dst, Ws, Wn, out_fwd, True, t(dOut), g2[0],
+                               g2[1], g2[2], None, ws)
+            torch.cuda.synchronize()
+            assert torch.equal(g2[0], gWs) and torch.equal(g2[1], gWn) and torch.equal(g2[2], gb)
 
 
 def test_sage_bwd_rejects_identity_self_without_rows(hb):
