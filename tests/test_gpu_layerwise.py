@@ -132,3 +132,38 @@ def test_grouped_layerwise_single_call(hb, orc):
             nv, ls, ip, ix = orc_lw.sample_layerwise(off_np, idx_np, sb, bud, keys[b])
             ref = orc_lw.layer_chain(orc, to_bits(X), 0, nv, ls, ip, ix, weights_bits(W))
             assert rel_err(to_f64(out[b * B:(b + 1) * B]), ref) <= 2e-5, b
+
+
+@pytest.mark.parametrize("sampler", ["node", "layer"])
+def test_last_block_of_seeds_may_be_short(hb, sampler):
+    """n_seeds need not be a multiple of seeds_per_key: the last key serves a shorter block."""
+    from paper_2409_00657_amd import synth
+    from oracle import dedup as orc_dedup
+    g = synth.rmat_graph(11, 8.0, seed=13, device=DEV)
+    spk, n_blocks, fan = 6, 67, [4, 5]
+    n_seeds = spk * n_blocks - 4
+    seeds = synth.seeds(g.n_vertices, n_seeds, 9, device=DEV)
+    keys = [40 + 3 * b for b in range(n_blocks)]
+    off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
+    if sampler == "layer":
+        out = _run_sampler(hb, g, seeds, fan, keys, seeds_per_key=spk)
+        ref = orc_lw.sample_layerwise(off_np, idx_np, seeds.cpu().numpy(), fan, [keys[m // spk] for m in range(n_seeds)])
+        _check_against(*out, ref)
+    else:
+        T = n_seeds * hb.hopgnn_slots_per_seed(fan)
+        i32 = dict(dtype=torch.int32, device=DEV)
+        nv, ls = torch.full((T,), -9, **i32), torch.zeros(len(fan) + 2, dtype=torch.int64, device=DEV)
+        ip, ix = torch.full((T + 1,), -9, **i32), torch.full((T,), -9, **i32)
+        ws = torch.empty(hb.hopgnn_sample_dedup_ws_bytes(n_seeds, fan), dtype=torch.uint8, device=DEV)
+        hb.hopgnn_sample_dedup(g.offsets, g.indices, seeds, fan, keys, nv, ls, ip, ix, ws, seeds_per_key=spk)
+        torch.cuda.synchronize()
+        # level 1 of the merged batch = level 1 of every block in turn, the last block being shorter
+        pos, nv_np, ls_np = None, nv.cpu().numpy(), ls.cpu().numpy()
+        pos = int(ls_np[1])
+        for b in range(n_blocks):
+            sb = seeds[b * spk:(b + 1) * spk].cpu().numpy()
+            r_nv, r_ls, _, _ = orc_dedup.sample_dedup(off_np, idx_np, sb, fan, keys[b])
+            lvl1 = r_nv[r_ls[1]:r_ls[2]]
+            np.testing.assert_array_equal(nv_np[pos:pos + len(lvl1)], lvl1)
+            pos += len(lvl1)
+        assert pos == ls_np[2] and ls_np[1] == n_seeds
