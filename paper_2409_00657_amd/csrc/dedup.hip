@@ -221,7 +221,9 @@ frontier_locality(const int32_t* __restrict__ node_vertex, const int64_t* __rest
             const int32_t v = node_vertex[q];
             if (v < 0) continue;
             uint32_t cell = ((uint32_t)v * 2654435761u) & table_mask;
-            while (true) {
+            // at most one pass over the table: with the capacity the caller promised it is never more
+            // than half full; a micrograph larger than that stops counting instead of probing for ever
+            for (uint32_t probe = 0; probe <= table_mask; ++probe) {
                 const int32_t old = atomicCAS(&fl_table[cell], -1, v);
                 if (old == -1) {   // first time this vertex is seen in the micrograph
                     ++tot;
