@@ -511,9 +511,16 @@ hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_s
  *                               to `out`); reused by every batch of the group
  *   pg_ws, sage_ws              scratch of hopgnn_pregather_ws_bytes(group*T, ..) and the largest
  *                               hopgnn_sage_fwd_ws_bytes over the layers
- *   mark_gather_begin/_end      optional hipEvent_t pair recorded on `stream` around the gather
- *                               launch (NULL: none) so that a harness can time that kernel
- *                               inside its timed region
+ *   mark_begin/_end, mark_stage optional hipEvent_t pair (NULL: none) recorded on `stream` around
+ *                               one stage of the sequence, so that a harness can time a kernel
+ *                               inside its timed region.  mark_stage: HOPGNN_MARK_GATHER (0) the
+ *                               gather launch; HOPGNN_MARK_EMPTY nothing (the pair is recorded
+ *                               back to back after the gather: what two markers cost by
+ *                               themselves); HOPGNN_MARK_SAMPLE, HOPGNN_MARK_PREGATHER those calls;
+ *                               HOPGNN_MARK_AGGREGATE + k / HOPGNN_MARK_PROJECT + k the segmented
+ *                               aggregation / the projection kernel of layer k (1-based) of the
+ *                               call's first batch (layer_kind 0 without dedup only; otherwise
+ *                               HOPGNN_EINVAL).
  *   layer_kind                  0: GraphSAGE-mean layers (hopgnn_sage_fwd, W_self/W_neigh);
  *                               1: GCN-style layers (hopgnn_gcn_fwd with W_self as the one weight
  *                               matrix and norm = gcn_norm); 2: attention layers (hopgnn_gat_fwd
@@ -580,7 +587,7 @@ typedef struct {
     size_t pg_ws_bytes;
     void *sage_ws;
     size_t sage_ws_bytes;
-    void *mark_gather_begin, *mark_gather_end;
+    void *mark_begin, *mark_end;
     int32_t pg_ws_clean;
     int32_t merge_layers;
     int32_t layer_kind, gcn_norm, gat_heads;
@@ -592,7 +599,11 @@ typedef struct {
     int32_t *dd_idx, *dd_idx_l1;
     void *dd_ws;
     size_t dd_ws_bytes;
+    int32_t mark_stage;
 } hopgnn_batch_plan;
+
+enum { HOPGNN_MARK_GATHER = 0, HOPGNN_MARK_EMPTY = 1, HOPGNN_MARK_SAMPLE = 2, HOPGNN_MARK_PREGATHER = 3,
+       HOPGNN_MARK_AGGREGATE = 16, HOPGNN_MARK_PROJECT = 32 };
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,
                                const uint64_t *keys /*HOST*/, int32_t n_batches, void *out, void *stream);

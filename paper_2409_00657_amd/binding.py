@@ -20,6 +20,7 @@ _lib: Optional[ctypes.CDLL] = None
 F32, BF16, F16 = 0, 1, 2
 DTYPE_OF = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 PG_AUTO, PG_BITMAP, PG_RADIX = 0, 1, 2
+MARK_GATHER, MARK_EMPTY, MARK_SAMPLE, MARK_PREGATHER, MARK_AGGREGATE, MARK_PROJECT = 0, 1, 2, 3, 16, 32
 
 EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_pregather_ws_bytes", "hopgnn_pregather", "hopgnn_gather",
@@ -60,13 +61,13 @@ class BatchPlan(ctypes.Structure):
                 ("remap", ctypes.c_void_p), ("Xu", ctypes.c_void_p), ("H", ctypes.c_void_p * 8),
                 ("pg_ws", ctypes.c_void_p), ("pg_ws_bytes", ctypes.c_size_t),
                 ("sage_ws", ctypes.c_void_p), ("sage_ws_bytes", ctypes.c_size_t),
-                ("mark_gather_begin", ctypes.c_void_p), ("mark_gather_end", ctypes.c_void_p),
+                ("mark_begin", ctypes.c_void_p), ("mark_end", ctypes.c_void_p),
                 ("pg_ws_clean", ctypes.c_int32), ("merge_layers", ctypes.c_int32),
                 ("layer_kind", ctypes.c_int32), ("gcn_norm", ctypes.c_int32), ("gat_heads", ctypes.c_int32),
                 ("a_src", ctypes.c_void_p * 8), ("a_dst", ctypes.c_void_p * 8),
                 ("dedup", ctypes.c_int32), ("node_vertex", ctypes.c_void_p), ("level_start", ctypes.c_void_p),
                 ("dd_idx", ctypes.c_void_p), ("dd_idx_l1", ctypes.c_void_p), ("dd_ws", ctypes.c_void_p),
-                ("dd_ws_bytes", ctypes.c_size_t)]
+                ("dd_ws_bytes", ctypes.c_size_t), ("mark_stage", ctypes.c_int32)]
 
 
 def library_path() -> str:

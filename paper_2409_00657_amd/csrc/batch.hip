@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include "pregather_internal.hpp"
+#include "sage_common.hpp"
 
 using namespace hopgnn;
 
@@ -14,7 +15,24 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     if (n_batches < 1 || n_batches > p->group) return HOPGNN_EINVAL;
     const int32_t L = p->n_layers, B = p->n_seeds;
     if (L < 1 || L > kMaxLayers || B < 1) return HOPGNN_EINVAL;
-    if ((p->mark_gather_begin == nullptr) != (p->mark_gather_end == nullptr)) return HOPGNN_EINVAL;
+    if ((p->mark_begin == nullptr) != (p->mark_end == nullptr)) return HOPGNN_EINVAL;
+    const bool marked = p->mark_begin != nullptr;
+    const int32_t mstage = marked ? p->mark_stage : -1;
+    int32_t mark_layer = 0;           // layer whose aggregation (mark_agg) or projection kernel is bracketed
+    bool mark_agg = false;
+    if (marked) {
+        if (mstage >= HOPGNN_MARK_PROJECT) mark_layer = mstage - HOPGNN_MARK_PROJECT;
+        else if (mstage >= HOPGNN_MARK_AGGREGATE) mark_layer = mstage - HOPGNN_MARK_AGGREGATE, mark_agg = true;
+        else if (mstage < 0 || mstage > HOPGNN_MARK_PREGATHER) return HOPGNN_EINVAL;
+        if (mstage >= HOPGNN_MARK_AGGREGATE && (mark_layer < 1 || mark_layer > p->n_layers || p->layer_kind != 0))
+            return HOPGNN_EINVAL;
+        if (p->dedup && mstage > HOPGNN_MARK_EMPTY) return HOPGNN_EINVAL;   // only the gather is bracketed there
+    }
+    hipEvent_t ev_a = (hipEvent_t)p->mark_begin, ev_b = (hipEvent_t)p->mark_end;
+    auto rec = [&](int32_t stage, bool begin) -> bool {     // record the marker of `stage`, if it is the marked one
+        if (mstage != stage) return true;
+        return hipEventRecord(begin ? ev_a : ev_b, (hipStream_t)stream) == hipSuccess;
+    };
     if (p->layer_kind < 0 || p->layer_kind > 2) return HOPGNN_EINVAL;
     const int64_t t_seed = hopgnn_slots_per_seed(p->fanouts, L);
     if (t_seed < 0) return HOPGNN_EINVAL;
@@ -69,12 +87,11 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
             rc = hopgnn_pregather(p->node_vertex, T_all, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
                                   p->pg_ws, p->pg_ws_bytes, stream);
         if (rc != HOPGNN_OK) return rc;
-        if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
-            return HOPGNN_EHIP;
+        if (!rec(HOPGNN_MARK_GATHER, true)) return HOPGNN_EHIP;
         rc = hopgnn_gather(p->X, p->dt, p->graph.n_vertices, p->dim, p->ld_elems, p->uniq, p->uniq_capacity, p->n_uniq,
                            p->Xu, stream);
         if (rc != HOPGNN_OK) return rc;
-        if (p->mark_gather_end != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_end, st) != hipSuccess)
+        if (!rec(HOPGNN_MARK_GATHER, false) || !rec(HOPGNN_MARK_EMPTY, true) || !rec(HOPGNN_MARK_EMPTY, false))
             return HOPGNN_EHIP;
         rc = hopgnn_compose_idx(p->dd_idx, entries_seed * B_all, p->remap, p->dd_idx_l1, stream);
         if (rc != HOPGNN_OK) return rc;
@@ -121,12 +138,14 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
     uint8_t* marks = p->pg_ws_clean ? pregather_marks_map(p->pg_ws, p->pg_ws_bytes, (int64_t)p->group * T,
                                                           p->graph.n_vertices, p->pg_algo)
                                     : nullptr;
+    if (!rec(HOPGNN_MARK_SAMPLE, true)) return HOPGNN_EHIP;
     hopgnn_status rc =
         merged ? sample_merged(&p->graph, seeds, B_run, B, p->fanouts, L, keys, p->ids, p->indptr,
                                L > 1 ? p->slot_idx : nullptr, marks, stream)
                : sample_batches(&p->graph, seeds, B, p->fanouts, L, keys, n_batches, p->ids, p->indptr,
                                 L > 1 ? p->slot_idx : nullptr, slot_idx_stride, marks, stream);
     if (rc != HOPGNN_OK) return rc;
+    if (!rec(HOPGNN_MARK_SAMPLE, false) || !rec(HOPGNN_MARK_PREGATHER, true)) return HOPGNN_EHIP;
     if (marks != nullptr)
         rc = pregather_from_marks(p->ids, n_batches * T, p->graph.n_vertices, p->uniq, p->n_uniq, p->remap, p->pg_ws,
                                   p->pg_ws_bytes, st);
@@ -134,12 +153,11 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         rc = hopgnn_pregather(p->ids, n_batches * T, p->graph.n_vertices, p->pg_algo, p->uniq, p->n_uniq, p->remap,
                               p->pg_ws, p->pg_ws_bytes, stream);
     if (rc != HOPGNN_OK) return rc;
-    if (p->mark_gather_begin != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_begin, st) != hipSuccess)
-        return HOPGNN_EHIP;
+    if (!rec(HOPGNN_MARK_PREGATHER, false) || !rec(HOPGNN_MARK_GATHER, true)) return HOPGNN_EHIP;
     rc = hopgnn_gather(p->X, p->dt, p->graph.n_vertices, p->dim, p->ld_elems, p->uniq, p->uniq_capacity, p->n_uniq,
                        p->Xu, stream);
     if (rc != HOPGNN_OK) return rc;
-    if (p->mark_gather_end != nullptr && hipEventRecord((hipEvent_t)p->mark_gather_end, st) != hipSuccess)
+    if (!rec(HOPGNN_MARK_GATHER, false) || !rec(HOPGNN_MARK_EMPTY, true) || !rec(HOPGNN_MARK_EMPTY, false))
         return HOPGNN_EHIP;
 
     const int32_t d_last = p->d_out[L - 1];
@@ -157,10 +175,16 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
             const int32_t* self_idx = k == 1 ? rb : nullptr;
             const int32_t* nbr = k == 1 ? rb + B_run : p->slot_idx + b * slot_idx_stride;
             const int32_t relu = k < L ? 1 : 0;
-            if (p->layer_kind == 0)
-                rc = hopgnn_sage_fwd(src, p->dt, n_src, d_in, self_idx, p->indptr, nbr, n_dst, p->W_self[k - 1],
-                                     p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], relu, dst, p->sage_ws,
-                                     p->sage_ws_bytes, stream);
+            if (p->layer_kind == 0) {
+                LayerMarks lm{};
+                if (b == 0 && k == mark_layer) {
+                    if (mark_agg) lm.agg_begin = ev_a, lm.agg_end = ev_b;
+                    else lm.proj_begin = ev_a, lm.proj_end = ev_b;
+                }
+                rc = sage_fwd_marked(src, p->dt, n_src, d_in, self_idx, p->indptr, nbr, n_dst, nullptr, p->W_self[k - 1],
+                                     p->W_neigh[k - 1], p->bias[k - 1], p->d_out[k - 1], HOPGNN_AGG_MEAN, relu, dst,
+                                     p->sage_ws, p->sage_ws_bytes, stream, b == 0 && k == mark_layer ? &lm : nullptr);
+            }
             else if (p->layer_kind == 1)
                 rc = hopgnn_gcn_fwd(src, p->dt, n_src, d_in, self_idx, p->indptr, nbr, n_dst, p->W_self[k - 1],
                                     p->bias[k - 1], p->d_out[k - 1], p->gcn_norm, relu, dst, p->sage_ws, p->sage_ws_bytes,

@@ -34,6 +34,9 @@ namespace hopgnn {
 
 constexpr int kProjThreads = 256;
 constexpr int kXcds = 8;
+// Scheduling barrier mask of the projection loops: vector/scalar ALU work and global memory
+// operations may be moved across, MFMAs and LDS operations may not.
+constexpr int kSchedPin = 0x2 | 0x4 | 0x10;
 
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Keep all N
 // tiles of one M tile on one XCD so the left operand is fetched into one L2 only.
@@ -265,47 +268,69 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
             *reinterpret_cast<float4*>(&Bs[st][i / (BN / 4)][(i % (BN / 4)) * 4]) = r.b[it];
         }
     };
-    auto compute = [&](int st) {
-        const int g = lane >> 5, l32 = lane & 31;
+    // One 8-wide K block of a stage as this lane's MFMA operands: TM 128-bit words of A, 4 x TN
+    // single values of B.  The fragments of block kk+8 are read from LDS while block kk is
+    // multiplied (two fragment sets), and the scheduler is told not to move LDS operations or
+    // MFMAs across the marked points: left alone it sinks every read to just before its first
+    // use, and the matrix pipe then idles for an LDS round trip before every group of four MFMAs.
+    struct Frag {
+        float4 a[TM];
+        float b[4][TN];
+    };
+    const int fg = lane >> 5, fl32 = lane & 31;
+    auto load_frag = [&](Frag& f, int st, int kk) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 8) {
-            float4 a[TM];
+        for (int tm = 0; tm < TM; ++tm)
+            f.a[tm] = *reinterpret_cast<const float4*>(&As[st][wm * (BM / 2) + tm * 32 + fl32][kk + 4 * fg]);
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                a[tm] = *reinterpret_cast<const float4*>(&As[st][wm * (BM / 2) + tm * 32 + l32][kk + 4 * g]);
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float b[TN];
+            for (int tn = 0; tn < TN; ++tn) f.b[i][tn] = Bs[st][kk + 4 * fg + i][wn * (BN / 2) + tn * 32 + fl32];
+    };
+    auto mma = [&](const Frag& f) {
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) b[tn] = Bs[st][kk + 4 * g + i][wn * (BN / 2) + tn * 32 + l32];
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm) {
-                    const float av = i == 0 ? a[tm].x : i == 1 ? a[tm].y : i == 2 ? a[tm].z : a[tm].w;
+            for (int tm = 0; tm < TM; ++tm) {
+                const float av = i == 0 ? f.a[tm].x : i == 1 ? f.a[tm].y : i == 2 ? f.a[tm].z : f.a[tm].w;
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, b[tn], acc[tm][tn], 0, 0, 0);
-                }
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[i][tn], acc[tm][tn], 0, 0, 0);
             }
+    };
+    auto compute = [&](int st) {
+        Frag f0, f1;
+        load_frag(f0, st, 0);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            if (kk + 8 < BK) load_frag(f1, st, kk + 8);
+            __builtin_amdgcn_sched_barrier(kSchedPin);
+            mma(f0);
+            if (kk + 16 < BK) load_frag(f0, st, kk + 16);
+            __builtin_amdgcn_sched_barrier(kSchedPin);
+            if (kk + 8 < BK) mma(f1);
         }
+        __builtin_amdgcn_sched_barrier(kSchedPin);
     };
 
     // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
-    // an even number of tiles.  Iteration t: r holds tile t+1 -> LDS stage (t+1)&1; r is
-    // refilled with tile t+3; tile t is multiplied from stage t&1.
+    // an even number of tiles.  Iteration t: the loads of tile t+2 are issued first, tile t is
+    // multiplied from LDS stage t&1, and only then is tile t+1 (loaded one iteration ago) moved
+    // from its registers to the other stage, so a load has two iterations to arrive before
+    // anything waits for it.
     Regs r0, r1;
     load_tile(r0, 0);
     store_tile(r0, 0);
-    load_tile(r1, 1);
-    load_tile(r0, 2);
+    load_tile(r0, 1);
     lds_barrier();
     for (int t = 0; t < n_tiles; t += 2) {
-        store_tile(r1, 1);
-        load_tile(r1, t + 3);
+        load_tile(r1, t + 2);
         compute(0);
+        store_tile(r0, 1);
         lds_barrier();
-        store_tile(r0, 0);
-        load_tile(r0, t + 4);
+        load_tile(r0, t + 3);
         compute(1);
+        store_tile(r1, 0);
         lds_barrier();
     }
     project_epilogue<TrF32, TM, TN>(acc, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane, n_dst, d_out, bias, relu, out);
@@ -441,41 +466,60 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
             *reinterpret_cast<uint4*>(&Bs[st][i / (BK / 8)][(i % (BK / 8)) * 8]) = r.b[it];
         }
     };
+    // One 16-wide K block of a stage as this lane's MFMA operands (TM + TN 128-bit words); the
+    // next block's are read from LDS while this one is multiplied, and the scheduler may not move
+    // LDS operations or MFMAs across the marked points (see the fp32 kernel).
+    struct Frag {
+        uint4 a[TM], b[TN];
+    };
+    const int fg = lane >> 5, fl32 = lane & 31;
+    auto load_frag = [&](Frag& f, int st, int kk) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+            f.a[tm] = *reinterpret_cast<const uint4*>(&As[st][wm * (BM / WM) + tm * 32 + fl32][kk + fg * 8]);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+            f.b[tn] = *reinterpret_cast<const uint4*>(&Bs[st][wn * (BN / WN) + tn * 32 + fl32][kk + fg * 8]);
+    };
+    auto mma = [&](const Frag& f) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma16<Tr>(f.a[tm], f.b[tn], acc[tm][tn]);
+    };
     auto compute = [&](int st) {
-        const int g = lane >> 5, l32 = lane & 31;
+        Frag f0, f1;
+        load_frag(f0, st, 0);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            uint4 a[TM], b[TN];
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-                a[tm] = *reinterpret_cast<const uint4*>(&As[st][wm * (BM / WM) + tm * 32 + l32][kk + g * 8]);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                b[tn] = *reinterpret_cast<const uint4*>(&Bs[st][wn * (BN / WN) + tn * 32 + l32][kk + g * 8]);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma16<Tr>(a[tm], b[tn], acc[tm][tn]);
+        for (int kk = 0; kk < BK; kk += 32) {
+            if (kk + 16 < BK) load_frag(f1, st, kk + 16);
+            __builtin_amdgcn_sched_barrier(kSchedPin);
+            mma(f0);
+            if (kk + 32 < BK) load_frag(f0, st, kk + 32);
+            __builtin_amdgcn_sched_barrier(kSchedPin);
+            if (kk + 16 < BK) mma(f1);
         }
+        __builtin_amdgcn_sched_barrier(kSchedPin);
     };
 
     // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
-    // an even number of tiles.  Iteration t: r holds tile t+1 -> LDS stage (t+1)&1; r is
-    // refilled with tile t+3; tile t is multiplied from stage t&1.
+    // an even number of tiles.  Iteration t: the loads of tile t+2 are issued first, tile t is
+    // multiplied from LDS stage t&1, and only then is tile t+1 (loaded one iteration ago) moved
+    // from its registers to the other stage, so a load has two iterations to arrive before
+    // anything waits for it.
     Regs r0, r1;
     load_tile(r0, 0);
     store_tile(r0, 0);
-    load_tile(r1, 1);
-    load_tile(r0, 2);
+    load_tile(r0, 1);
     lds_barrier();
     for (int t = 0; t < n_tiles; t += 2) {
-        store_tile(r1, 1);
-        load_tile(r1, t + 3);
+        load_tile(r1, t + 2);
         compute(0);
+        store_tile(r0, 1);
         lds_barrier();
-        store_tile(r0, 0);
-        load_tile(r0, t + 4);
+        load_tile(r0, t + 3);
         compute(1);
+        store_tile(r1, 0);
         lds_barrier();
     }
     if (out_f32) {     // `out` is a float array: unrounded result
@@ -635,6 +679,19 @@ extern "C" hopgnn_status hopgnn_sage_fwd_dev(const void* Hsrc, hopgnn_dtype dt, 
                                              const void* W_self, const void* W_neigh, const void* bias,
                                              int32_t d_out, int32_t agg, int32_t relu, void* out, void* ws,
                                              size_t ws_bytes, void* stream) {
+    return sage_fwd_marked(Hsrc, dt, n_src, d_in, self_idx, indptr, idx, n_dst, n_dst_dev, W_self, W_neigh, bias, d_out,
+                           agg, relu, out, ws, ws_bytes, stream, nullptr);
+}
+
+namespace hopgnn {
+
+static inline bool mark(hipEvent_t ev, hipStream_t s) { return ev == nullptr || hipEventRecord(ev, s) == hipSuccess; }
+
+hopgnn_status sage_fwd_marked(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in, const int32_t* self_idx,
+                              const int32_t* indptr, const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
+                              const void* W_self, const void* W_neigh, const void* bias, int32_t d_out, int32_t agg,
+                              int32_t relu, void* out, void* ws, size_t ws_bytes, void* stream,
+                              const LayerMarks* marks) {
     if (agg != HOPGNN_AGG_MEAN && agg != HOPGNN_AGG_SUM && agg != HOPGNN_AGG_MAX) return HOPGNN_EINVAL;
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
@@ -663,11 +720,18 @@ extern "C" hopgnn_status hopgnn_sage_fwd_dev(const void* Hsrc, hopgnn_dtype dt, 
     }
     hopgnn_status st;
     const AggSpec spec{nullptr, 0, agg};     // the C ABI's aggregator codes are the kernel's op codes
+    if (marks != nullptr && !mark(marks->agg_begin, s)) return HOPGNN_EHIP;
     if (dt == HOPGNN_F32) st = launch_mean<TrF32>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
     else if (dt == HOPGNN_BF16) st = launch_mean<TrBF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
     else st = launch_mean<TrF16>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, job, n_tr, s, spec, n_dst_dev);
     if (st != HOPGNN_OK) return st;
+    if (marks != nullptr && (!mark(marks->agg_end, s) || !mark(marks->proj_begin, s))) return HOPGNN_EHIP;
 
-    return project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,
-                            zero, out, 0, n_dst_dev);
+    st = project_dispatch(dt, s, Hsrc, self_idx, mean, W_self, W_neigh, Wt, L.KP, bias, n_dst, d_in, 2 * d_in, d_out, relu,
+                          zero, out, 0, n_dst_dev);
+    if (st != HOPGNN_OK) return st;
+    if (marks != nullptr && !mark(marks->proj_end, s)) return HOPGNN_EHIP;
+    return HOPGNN_OK;
 }
+
+}  // namespace hopgnn

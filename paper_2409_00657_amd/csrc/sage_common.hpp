@@ -275,4 +275,17 @@ hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc,
                                int32_t d_out, int relu, const void* zero, void* out, int out_f32,
                                const int64_t* n_rows_dev);
 
+// Optional event pairs around the two kernels of a layer (a harness timing them inside its
+// timed region); any handle may be NULL.
+struct LayerMarks {
+    hipEvent_t agg_begin, agg_end, proj_begin, proj_end;
+};
+
+// hopgnn_sage_fwd_dev with optional markers (marks may be NULL).
+hopgnn_status sage_fwd_marked(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in, const int32_t* self_idx,
+                              const int32_t* indptr, const int32_t* idx, int64_t n_dst, const int64_t* n_dst_dev,
+                              const void* W_self, const void* W_neigh, const void* bias, int32_t d_out, int32_t agg,
+                              int32_t relu, void* out, void* ws, size_t ws_bytes, void* stream,
+                              const LayerMarks* marks);
+
 }  // namespace hopgnn

@@ -192,7 +192,7 @@ class HotPath:
         pl.remap, pl.Xu = remap, self.Xu.data_ptr()
         pl.pg_ws, pl.pg_ws_bytes = self.pg_ws.data_ptr(), self.pg_ws.numel()
         pl.sage_ws, pl.sage_ws_bytes = self.sage_ws.data_ptr(), self.sage_ws.numel()
-        pl.mark_gather_begin = pl.mark_gather_end = None
+        pl.mark_begin = pl.mark_end = None
         # every call of the library leaves the pre-gather workspace clean, so prepare it once
         hb.hopgnn_pregather_ws_init(self.pg_ws, self.group * T, self.n_vertices, self.pg_algo)
         pl.pg_ws_clean = 1
@@ -342,7 +342,8 @@ class HotPath:
                 marks=None) -> None:
         """The whole group in ONE library call (hopgnn_batch_fwd): `seeds` holds the group's
         seeds back to back, `out` [group*B, hidden] receives every batch's last-layer rows.
-        `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch."""
+        `marks` = (begin, end) raw hipEvent_t handles recorded around the gather launch, or
+        (begin, end, stage) for another stage of the sequence (binding.MARK_*)."""
         n = len(keys)
         if seeds.numel() != n * self.seeds_per_key or seeds.dtype != torch.int32 or not seeds.is_cuda:
             raise hb.HopgnnError("seeds must be %d int32 values on the device" % (n * self.seeds_per_key))
@@ -352,7 +353,11 @@ class HotPath:
         for i, k in enumerate(keys):
             self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
         pl = self.plan
-        pl.mark_gather_begin, pl.mark_gather_end = marks if marks is not None else (None, None)
+        if marks is None:
+            pl.mark_begin = pl.mark_end = None
+        else:
+            pl.mark_begin, pl.mark_end = marks[0], marks[1]
+            pl.mark_stage = marks[2] if len(marks) > 2 else hb.MARK_GATHER
         rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._keys, n, out.data_ptr(),
                                         self._stream(stream))
         if rc:
@@ -486,7 +491,8 @@ class DedupPath:
         for i, k in enumerate(self._key_list(key)):
             self._keys[i] = k & 0xFFFFFFFFFFFFFFFF
         pl = self.plan
-        pl.mark_gather_begin, pl.mark_gather_end = marks if marks is not None else (None, None)
+        pl.mark_begin, pl.mark_end = marks if marks is not None else (None, None)
+        pl.mark_stage = hb.MARK_GATHER
         st = torch.cuda.current_stream().cuda_stream if stream is None else stream
         rc = self._lib.hopgnn_batch_fwd(ctypes.byref(pl), seeds.data_ptr(), self._keys, self.n_keys, out.data_ptr(), st)
         if rc:

@@ -1,32 +1,2 @@
 """Shared by the GPU parity tests: tensor <-> oracle conversions and the error metric."""
-import numpy as np
-import torch
-
-ORC_DT = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
-TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2, torch.float16: 2e-2}
-
-
-def to_bits(t: torch.Tensor) -> np.ndarray:
-    """Host numpy array the oracle understands (uint16 bit patterns for 2-byte floats)."""
-    t = t.detach().cpu().contiguous()
-    if t.dtype in (torch.bfloat16, torch.float16):
-        return t.view(torch.int16).numpy().view(np.uint16)
-    return t.numpy()
-
-
-def to_f64(t: torch.Tensor) -> np.ndarray:
-    return t.detach().cpu().to(torch.float64).numpy()
-
-
-def rel_err(got64: np.ndarray, ref64: np.ndarray) -> float:
-    """max |got - ref| / max(|ref|, rms(ref)): element-wise relative error with
-    the tensor's rms as the floor (plain relative error is undefined at ReLU zeros)."""
-    if ref64.size == 0:
-        return 0.0
-    rms = float(np.sqrt(np.mean(ref64 ** 2)))
-    den = np.maximum(np.abs(ref64), max(rms, 1e-30))
-    return float(np.max(np.abs(got64 - ref64) / den))
-
-
-def weights_bits(weights):
-    return [(to_bits(a), to_bits(b), None if c is None else to_bits(c)) for a, b, c in weights]
+from oracle.checks import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits  # noqa: F401
