@@ -250,6 +250,21 @@ hopgnn_status hopgnn_pregather(const int32_t *ids, int64_t n_ids, int64_t n_vert
                                void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * hopgnn_pregather for callers that cannot allocate device memory or provide a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid allocation): the same
+ * kernels and the same results (bitmap path), with the scratch in a static device array of
+ * 24 MiB that every GPU the library runs on holds until the process ends.  Calls no allocator.
+ * Limit: n_vertices <= hopgnn_pregather_static_max_vertices() = 2^24, else HOPGNN_ERANGE;
+ * other errors as hopgnn_pregather.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (different streams) race; the contents a call leaves behind are
+ * cleared by the next call before use.  The first call on a device looks the array's address
+ * up (hipGetSymbolAddress) with that device current.
+ */
+int64_t hopgnn_pregather_static_max_vertices(void);
+hopgnn_status hopgnn_pregather_static(const int32_t *ids, int64_t n_ids, int64_t n_vertices, int32_t *uniq,
+                                      int64_t *n_uniq_dev, int32_t *remap, void *stream);
+
+/*
  * Data locality of micrographs (paper section 4, "data locality in micrographs": the
  * ratio R_micro = N_colocated / N_total of the locality table).
  * For every micrograph m of one batch (ids as written by hopgnn_sample):

@@ -30,7 +30,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
            "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
-           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
+           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_pregather_static", "hopgnn_pregather_static_max_vertices", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
 
 
@@ -175,6 +175,10 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_sage_fwd_agg.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                       c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_int32,
                                       c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_pregather_static_max_vertices.restype = c.c_int64
+    L.hopgnn_pregather_static_max_vertices.argtypes = []
+    L.hopgnn_pregather_static.restype = c.c_int
+    L.hopgnn_pregather_static.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
     L.hopgnn_pregather_ws_init.restype = c.c_int
     L.hopgnn_pregather_ws_init.argtypes = [c.c_void_p, c.c_size_t, c.c_int64, c.c_int64, c.c_int32, c.c_void_p]
     L.hopgnn_sample_group.restype = c.c_int
@@ -288,6 +292,13 @@ def hopgnn_sample_merged(offsets: torch.Tensor, indices: torch.Tensor, seeds: to
 
 def hopgnn_pregather_ws_bytes(n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> int:
     return int(load_library().hopgnn_pregather_ws_bytes(n_ids, n_vertices, algo))
+
+
+def hopgnn_pregather_static(ids: torch.Tensor, n_vertices: int, uniq: torch.Tensor, n_uniq: torch.Tensor,
+                            remap: torch.Tensor) -> None:
+    """hopgnn_pregather with the library's static scratch: no workspace, no allocation."""
+    _check(load_library().hopgnn_pregather_static(_ptr(ids), ids.numel(), n_vertices, _ptr(uniq), _ptr(n_uniq),
+                                                  _ptr(remap), _stream()), "hopgnn_pregather_static")
 
 
 def hopgnn_pregather_ws_init(ws: torch.Tensor, n_ids: int, n_vertices: int, algo: int = PG_AUTO) -> None:

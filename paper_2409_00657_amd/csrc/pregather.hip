@@ -15,6 +15,8 @@
 // graphs the hubs are hit thousands of times per batch and same-address atomics
 // serialise in L2 (measured: 0.3 ms for 0.9 M slots), while racing stores of the
 // same value just overwrite each other.  The result does not depend on any order.
+#include <mutex>
+
 #include "pregather_internal.hpp"
 
 namespace hopgnn {
@@ -805,6 +807,51 @@ extern "C" hopgnn_status hopgnn_pregather(const int32_t* ids, int64_t n_ids, int
         return pregather_radix(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, ws_bytes,
                                static_cast<hipStream_t>(stream));
     return pregather_bitmap(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, ws_bytes,
+                            static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------- no-allocation entry point --
+//
+// hopgnn_pregather for callers that cannot allocate or hand over a workspace: the bitmap path's
+// scratch lives in a file-scope device array.  In host code the array's name is only a stand-in;
+// its address on the current device comes from hipGetSymbolAddress, once per device.
+
+constexpr int64_t kStaticMaxVertices = (int64_t)1 << 24;
+constexpr size_t kStaticScratchBytes = (size_t)24 << 20;   // presence bytes + word ranks + chunk sums for 2^24 vertices
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 64;
+static void* g_scratch_ptr[kStaticMaxDevices];             // per device: where that device's copy of `scratch` lives
+static std::mutex g_scratch_mutex;
+
+static hopgnn_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) return HOPGNN_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return HOPGNN_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return HOPGNN_OK;
+}
+
+extern "C" int64_t hopgnn_pregather_static_max_vertices(void) { return kStaticMaxVertices; }
+
+extern "C" hopgnn_status hopgnn_pregather_static(const int32_t* ids, int64_t n_ids, int64_t n_vertices, int32_t* uniq,
+                                                 int64_t* n_uniq_dev, int32_t* remap, void* stream) {
+    if (n_ids < 0 || n_vertices < 0 || n_uniq_dev == nullptr) return HOPGNN_EINVAL;
+    if (n_ids > 0 && (ids == nullptr || remap == nullptr || uniq == nullptr)) return HOPGNN_EINVAL;
+    if (n_ids >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if (n_vertices > kStaticMaxVertices) return HOPGNN_ERANGE;          // beyond the static scratch
+    if (bitmap_layout(nullptr, n_vertices).bytes > kStaticScratchBytes) return HOPGNN_ERANGE;
+    void* ws = nullptr;
+    const hopgnn_status st = static_scratch(&ws);
+    if (st != HOPGNN_OK) return st;
+    // the bitmap path clears the part of the scratch it uses before marking, so whatever the last
+    // call on this device left there does not matter
+    return pregather_bitmap(ids, n_ids, n_vertices, uniq, n_uniq_dev, remap, ws, kStaticScratchBytes,
                             static_cast<hipStream_t>(stream));
 }
 
