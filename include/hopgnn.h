@@ -226,8 +226,10 @@ hopgnn_status hopgnn_sample_layerwise(const hopgnn_csr *g /*HOST struct*/, const
  *   n_total[m] = its distinct vertices, n_coloc[m] = its distinct vertices other than the root
  *   whose home server owner[v] is the root's.
  * nodes_per_seed: the capacity of one micrograph (hopgnn_slots_per_seed or caps[0] of
- * hopgnn_layerwise_caps); it sizes the per-micrograph hash set in LDS, at most 16384, else ERANGE
- * (a micrograph with more distinct vertices than that capacity allows is under-counted, not an error).
+ * hopgnn_layerwise_caps); it sizes the per-micrograph hash set in LDS (the next power of two at or
+ * above 2 * nodes_per_seed cells), at most 16384, else ERANGE.  A micrograph that has more distinct
+ * vertices than the set has cells cannot be counted: it reports n_total[m] = n_coloc[m] = -1
+ * (never a wrong count); with the sampler's own capacity that cannot happen.
  * level_start is the DEVICE array the sampler wrote; owner DEVICE [n_vertices] int32; n_total,
  * n_coloc DEVICE out [n_seeds].
  */

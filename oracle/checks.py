@@ -9,6 +9,17 @@ ORC_DT = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2, torch.float16: 2e-2}
 
 
+def chain_tol(dt, n_layers: int) -> float:
+    """Bound for the last rows of a whole chain of layers against the oracle's own chain.
+    fp32: the layer bound itself (stored activations are the fp32 results; the per-layer error of
+    about 1e-6 adds up to well under 1e-5 over the depths used).  2-byte types: both sides round
+    every layer's activations to the storage type, and where the two fp32 results straddle a
+    rounding boundary the stored values differ by one unit in the last place (2^-8 relative for
+    bf16), which the next layer carries on: one layer bound per layer.  Isolated layers (the same
+    stored inputs on both sides) always meet TOL."""
+    return TOL[dt] if dt == torch.float32 else TOL[dt] * n_layers
+
+
 def to_bits(t: torch.Tensor) -> np.ndarray:
     """Host numpy array the oracle understands (uint16 bit patterns for 2-byte floats)."""
     t = t.detach().cpu().contiguous()

@@ -202,8 +202,10 @@ frontier_locality(const int32_t* __restrict__ node_vertex, const int64_t* __rest
     extern __shared__ int32_t fl_table[];
     __shared__ uint32_t lds4[kFlThreads / kWave];
     __shared__ int32_t next_lo, next_hi;
+    __shared__ int32_t overflow;              // set when a vertex found no cell: the table was too small
     const int32_t m = blockIdx.x;
     const uint32_t tid = threadIdx.x;
+    if (tid == 0) overflow = 0;
     for (uint32_t i = tid; i <= table_mask; i += kFlThreads) fl_table[i] = -1;
     const int32_t root = node_vertex[m];
     const int32_t root_home = root >= 0 ? owner[root] : -1;
@@ -222,17 +224,21 @@ frontier_locality(const int32_t* __restrict__ node_vertex, const int64_t* __rest
             if (v < 0) continue;
             uint32_t cell = ((uint32_t)v * 2654435761u) & table_mask;
             // at most one pass over the table: with the capacity the caller promised it is never more
-            // than half full; a micrograph larger than that stops counting instead of probing for ever
-            for (uint32_t probe = 0; probe <= table_mask; ++probe) {
+            // than half full; a micrograph with more distinct vertices than cells cannot be counted -
+            // the probe ends after one pass and the micrograph reports -1 instead of a wrong count
+            bool placed = false;
+            for (uint32_t probe = 0; probe <= table_mask && !placed; ++probe) {
                 const int32_t old = atomicCAS(&fl_table[cell], -1, v);
                 if (old == -1) {   // first time this vertex is seen in the micrograph
                     ++tot;
                     if (v != root && owner[v] == root_home) ++col;
-                    break;
+                    placed = true;
+                } else if (old == v) {
+                    placed = true;
                 }
-                if (old == v) break;
                 cell = (cell + 1) & table_mask;
             }
+            if (!placed) overflow = 1;
         }
         if (h == n_layers || hi > n_nonleaf) break;        // leaves have no segments (uniform)
         int32_t mn = 0x7FFFFFFF, mx = -1;
@@ -253,10 +259,10 @@ frontier_locality(const int32_t* __restrict__ node_vertex, const int64_t* __rest
     }
     uint32_t t_all, c_all;
     (void)fr_block_scan<kFlThreads, uint32_t>(tot, lds4, t_all);
-    (void)fr_block_scan<kFlThreads, uint32_t>(col, lds4, c_all);
+    (void)fr_block_scan<kFlThreads, uint32_t>(col, lds4, c_all);     // (its barriers order `overflow` too)
     if (tid == 0) {
-        n_total[m] = (int32_t)t_all;
-        n_coloc[m] = (int32_t)c_all;
+        n_total[m] = overflow ? -1 : (int32_t)t_all;
+        n_coloc[m] = overflow ? -1 : (int32_t)c_all;
     }
 }
 

@@ -48,7 +48,8 @@ static hopgnn_status launch_gather(const void* X, const int32_t* uniq, int64_t n
     if (n_uniq_dev != nullptr && grid > resident) grid = resident;
     if (grid >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     const int64_t ld_vec = ld_bytes / (int64_t)sizeof(VecT);
-    if (items + kGatherThreads < ((int64_t)1 << 32))
+    // 32-bit item indices only where the loop's last step cannot wrap around: index + stride < 2^32
+    if (items + grid * kGatherThreads < ((int64_t)1 << 32))
         hipLaunchKernelGGL((gather_rows<VecT, uint32_t>), dim3((unsigned)grid), dim3(kGatherThreads), 0, s,
                            static_cast<const VecT*>(X), uniq, n_uniq, n_uniq_dev, vpr, ld_vec,
                            static_cast<VecT*>(Xu));

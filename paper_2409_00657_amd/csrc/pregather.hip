@@ -667,6 +667,10 @@ micrograph_locality(const int32_t* __restrict__ ids, int32_t n_seeds, SlotShape 
     for (uint32_t i = threadIdx.x; i <= table_mask; i += kLocThreads) table[i] = kLocEmpty;
     __syncthreads();
     const int32_t root = ids[m];
+    if (root < 0) {            // no root, no micrograph (uniform over the workgroup)
+        if (threadIdx.x == 0) n_total[m] = n_coloc[m] = 0;
+        return;
+    }
     const int32_t root_home = owner[root];
     uint32_t tot = 0, col = 0;
     for (int32_t h = 0; h <= sh.n_layers; ++h) {
@@ -675,7 +679,7 @@ micrograph_locality(const int32_t* __restrict__ ids, int32_t n_seeds, SlotShape 
             const int32_t v = lvl[p];
             if (v < 0) continue;
             uint32_t cell = ((uint32_t)v * 2654435761u) & table_mask;
-            while (true) {
+            while (true) {     // ends: the table has more cells than a micrograph has slots
                 const int32_t old = atomicCAS(&table[cell], kLocEmpty, v);
                 if (old == kLocEmpty) {   // first time this vertex is seen in the micrograph
                     ++tot;

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits, chain_tol
 from oracle import dedup as orc_dedup
 from oracle import frontier as orc_frontier
 from oracle import layerwise as orc_lw
@@ -67,4 +67,4 @@ def test_full_size_sampled_micrographs_vs_oracle(orc, cfg_id, sampler):
         rows = to_bits(X[torch.from_numpy(verts).long().to(DEV)])
         local = (np.searchsorted(verts, st[0]).astype(np.int32),) + tuple(st[1:])
         ref = orc_frontier.layer_chain(orc, rows, ORC_DT[X.dtype], *local, wb)
-        assert rel_err(to_f64(out[m:m + 1]), ref) <= TOL[X.dtype] * L, m
+        assert rel_err(to_f64(out[m:m + 1]), ref) <= chain_tol(X.dtype, L), m

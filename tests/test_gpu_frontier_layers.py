@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits, chain_tol
 from oracle import dedup as orc_dedup
 from oracle import frontier as orc_frontier
 from oracle import layerwise as orc_lw
@@ -48,4 +48,4 @@ def test_layer_kinds_over_frontiers(orc, dt, model, sampler, fanouts):
     for b in range(G):
         st = sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fanouts, keys[b])
         ref = orc_frontier.layer_chain(orc, to_bits(X), odt, *st, wb, layer=layer)
-        assert rel_err(to_f64(out[b * B:(b + 1) * B]), ref) <= TOL[dt] * L, b
+        assert rel_err(to_f64(out[b * B:(b + 1) * B]), ref) <= chain_tol(dt, L), b

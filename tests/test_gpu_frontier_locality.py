@@ -66,3 +66,31 @@ def test_node_wise_counts_equal_the_slot_tree_entry_point(hb):
     hb.hopgnn_micrograph_locality(hp.ids, B, fan, owner, out[2], out[3])
     torch.cuda.synchronize()
     assert torch.equal(out[0], out[2]) and torch.equal(out[1], out[3])
+
+
+def test_a_capacity_that_is_too_small_reports_minus_one_not_a_wrong_count(hb):
+    """nodes_per_seed sizes the hash set; promise far too little and every micrograph with more
+    distinct vertices than cells reports -1 for both counts, the others stay exact, and the kernel
+    ends normally."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import DedupPath
+    g = synth.rmat_graph(12, 8.0, seed=3, device=DEV)
+    n, fan, B = g.n_vertices, [12, 12], 64
+    X = synth.features(n, 8, torch.float32, device=DEV)
+    W = synth.sage_weights(8, 8, 2, torch.float32, device=DEV)
+    dp = DedupPath(g.offsets, g.indices, X, W, B, fan)
+    seeds = synth.seeds(n, B, 4, device=DEV)
+    dp.sample(seeds, 5)
+    owner = torch.from_numpy(np.random.default_rng(2).integers(0, 4, size=n).astype(np.int32)).to(DEV)
+    n_total = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    n_coloc = torch.full((B,), -5, dtype=torch.int32, device=DEV)
+    hb.hopgnn_frontier_locality(dp.node_vertex, dp.level_start, dp.indptr, dp.idx, B, 2, 8, owner, n_total, n_coloc)
+    torch.cuda.synchronize()                     # nodes_per_seed = 8 -> 64 cells
+    st = orc_dedup.sample_dedup(g.offsets.cpu().numpy(), g.indices.cpu().numpy(), seeds.cpu().numpy(), fan, 5)
+    want_t, want_c = orc_frontier.locality(*st, B, owner.cpu().numpy())
+    got_t, got_c = n_total.cpu().numpy(), n_coloc.cpu().numpy()
+    big = want_t > 64
+    assert big.any() and (~big).any()            # the case really has both kinds
+    assert (got_t[big] == -1).all() and (got_c[big] == -1).all()
+    np.testing.assert_array_equal(got_t[~big], want_t[~big])
+    np.testing.assert_array_equal(got_c[~big], want_c[~big])

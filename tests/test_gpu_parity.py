@@ -282,6 +282,54 @@ def test_sage_fwd_within_tolerance(hb, orc, dtype, shape):
         assert to_bits(out).tobytes() == to_bits(out2).tobytes()
 
 
+def _oracle_rows_parallel(orc, H_bits, odt, self_idx, indptr, idx, Ws, Wn, b, relu, chunk=4096, threads=16):
+    """orc.sage_fwd over all rows, in chunks of rows on several host threads (the oracle is a loop
+    over independent rows and its C calls release the interpreter lock)."""
+    from concurrent.futures import ThreadPoolExecutor
+    n_dst = len(indptr) - 1
+
+    def run(lo):
+        hi = min(n_dst, lo + chunk)
+        ip = indptr[lo:hi + 1].astype(np.int64)
+        e0, e1 = int(ip[0]), int(ip[-1])
+        return orc.sage_fwd(H_bits, odt, None if self_idx is None else self_idx[lo:hi], (ip - e0).astype(np.int32),
+                            idx[e0:e1], Ws, Wn, b, relu)
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        return np.concatenate(list(pool.map(run, range(0, n_dst, chunk))))
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("dtype,d_out", [(torch.float32, 256), (torch.bfloat16, 512), (torch.float16, 512),
+                                         (torch.bfloat16, 256)])
+def test_sage_fwd_every_row_through_the_large_tiles(hb, orc, dtype, d_out):
+    """The two-matrix layer (K = 2*d_in, self rows through self_idx) at a size that takes the largest
+    projection tiles - 128 x 128 for fp32, 256 x 256 for 2-byte types - with EVERY output row checked
+    against the oracle: 66,000 rows span 258 to 516 row tiles, a ragged last tile, and many rounds
+    over the 8 XCDs."""
+    n_src, n_dst, d_in, max_len = 9000, 66_000, 128, 9
+    rng = np.random.default_rng(d_out + n_dst)
+    mk = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32))
+    H = mk(n_src, d_in).to(dtype)
+    Ws = (mk(d_in, d_out) / np.sqrt(d_in)).to(dtype)
+    Wn = (mk(d_in, d_out) / np.sqrt(d_in)).to(dtype)
+    b = (mk(d_out) * 0.1).to(dtype)
+    indptr, idx = _rand_csr(rng, n_dst, n_src, max_len)
+    self_idx = rng.integers(0, n_src, size=n_dst).astype(np.int32)
+    self_idx[rng.random(n_dst) < 0.03] = -1
+    ws = torch.empty(hb.hopgnn_sage_fwd_ws_bytes(dtype, n_dst, d_in, d_out), dtype=torch.uint8, device=DEV)
+    out = torch.full((n_dst, d_out), 9.0, dtype=dtype, device=DEV)
+    hb.hopgnn_sage_fwd(H.to(DEV), n_src, torch.from_numpy(self_idx).to(DEV), torch.from_numpy(indptr).to(DEV),
+                       torch.from_numpy(idx).to(DEV), n_dst, Ws.to(DEV), Wn.to(DEV), b.to(DEV), True, out, ws)
+    torch.cuda.synchronize()
+    ref = _oracle_rows_parallel(orc, to_bits(H), ORC_DT[dtype], self_idx, indptr, idx, to_bits(Ws), to_bits(Wn),
+                                to_bits(b), True)
+    got = to_f64(out)
+    # the tolerance per block of rows as well as overall, so that one bad tile cannot hide in the rms
+    assert rel_err(got, ref) <= TOL[dtype]
+    worst = max(rel_err(got[lo:lo + 256], ref[lo:lo + 256]) for lo in range(0, n_dst, 256))
+    assert worst <= 2 * TOL[dtype], worst
+
+
 def test_sage_fwd_special_cases_exact(hb):
     # one neighbour -> mean is that row; identity weights -> output is the row (exact in fp32)
     rng = np.random.default_rng(1)

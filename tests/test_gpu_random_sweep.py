@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import oracle as orc
-from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits
+from helpers import ORC_DT, TOL, rel_err, to_bits, to_f64, weights_bits, chain_tol
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -144,7 +144,7 @@ def test_random_whole_batches(seed):
                 outs = orc.forward(Xu_ref, ORC_DT[dt], ref_ids[b], ip, rr[b * T:(b + 1) * T], B, fan, wb)
                 e = rel_err(to_f64(out[b * B:(b + 1) * B]), outs[-1][0])
                 # chained layers: the oracle chains its own rounded activations, so allow the depth
-                if not (e <= TOL[dt] * L):
+                if not (e <= chain_tol(dt, L)):
                     failures.append(("forward", e, tag, it, b))
     assert not failures, failures
 
@@ -207,7 +207,7 @@ def test_random_frontier_batches(seed):
                 ref = orc_frontier.layer_chain(orc, to_bits(X), ORC_DT[dt], *st, wb)
                 got = out if len(parts) == 1 else out[b * B:(b + 1) * B]
                 e = rel_err(to_f64(got), ref)
-                if not (e <= TOL[dt] * L):
+                if not (e <= chain_tol(dt, L)):
                     failures.append(("forward", e, tag, it, b))
             if dt == torch.float32 and len(parts) == 1:
                 dp.run_batch(seeds, keys)
