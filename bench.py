@@ -66,6 +66,9 @@ def parse():
     ap.add_argument("--no-merge", action="store_true",
                     help="with a group > 1: run every batch's layers separately instead of one launch per layer "
                          "over the group's merged micrographs")
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="two kernels per layer (segmented mean, projection) for every layer, instead of letting each "
+                         "projection also form the next layer's neighbour means from the slot tree's shape")
     ap.add_argument("--dedup", action="store_true",
                     help="sample per-micrograph deduplicated frontiers (hopgnn_sample_dedup): the same rows for the "
                          "seeds over fewer rows below them; one batch per pre-gather, forward only")
@@ -230,8 +233,8 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
     g, X, W = cache["g"], cache["X"], cache["W"]
     merge = group > 1 and not args.no_merge
     n_multi = max(1, args.streams)
-    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, merge=merge)
-           for _ in range(n_multi)]
+    hps = [HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, group=group, merge=merge,
+                   fuse_tree=not args.no_fuse) for _ in range(n_multi)]
     streams = [torch.cuda.Stream() for _ in range(n_multi)]      # default priority
     raw_streams = [s.cuda_stream for s in streams]
     hp, sh = hps[0], hps[0].shape               # sh: the layout the layers run on (merged: the whole group)
@@ -259,7 +262,9 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
     stages = [("gather", hb.MARK_GATHER), ("empty_pair", hb.MARK_EMPTY), ("sample", hb.MARK_SAMPLE),
               ("pregather", hb.MARK_PREGATHER)]
     for k in range(1, L + 1):
-        stages += [("project_l%d" % k, hb.MARK_PROJECT + k), ("aggregate_l%d" % k, hb.MARK_AGGREGATE + k)]
+        stages.append(("project_l%d" % k, hb.MARK_PROJECT + k))
+        if k == 1 or not hp.fused:      # fused slot-tree layers: the previous projection made this layer's means
+            stages.append(("aggregate_l%d" % k, hb.MARK_AGGREGATE + k))
     ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(2)) for _ in range(K)]
     for a, b in ev:                       # record once so that the handles exist
         a.record(streams[0])
@@ -370,12 +375,18 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
         n_dst, nnz = sh.n_dst(k), sh.nnz(k)
         nnz_valid = sum(valid_level[1:L - k + 2]) / runs
         flops = 2.0 * n_dst * 2 * din * hidden
-        io = n_dst * 2 * din * es + n_dst * hidden * es          # left operand once + output
+        # left operand once + output (fused slot-tree layers store the next layer's destination rows and
+        # as many rows of neighbour means instead of every row)
+        out_rows = 2 * sh.n_dst(k + 1) if (hp.fused and k < L) else n_dst
+        io = n_dst * 2 * din * es + out_rows * hidden * es
         add("project_l%d" % k, "mfma", flops, MFMA_PEAK_TFLOPS[dname] * 1.0, "TFLOP/s",
             {"kernel": "sage_project", "M": n_dst, "K": 2 * din, "N": hidden,
              "hbm_bytes_operand_once_plus_output": io})
         kernels["project_l%d" % k]["hbm_GBps"] = io / (kernels["project_l%d" % k]["avg_launch_ms"] * 1e-3) * 1e-9
         kernels["project_l%d" % k]["hbm_frac"] = kernels["project_l%d" % k]["hbm_GBps"] / HBM_PEAK_GBPS
+        if "aggregate_l%d" % k not in stage_ms:
+            din = hidden
+            continue
         agg_bytes = nnz_valid * din * es + n_dst * din * es + 4.0 * (nnz + n_dst)
         src_bytes = (U_avg if k == 1 else sh.n_dst(k - 1)) * din * es
         add("aggregate_l%d" % k, "hbm", agg_bytes, HBM_PEAK_GBPS, "GB/s",
@@ -390,7 +401,7 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
     dominant = max(share, key=share.get)
     step_ms = t_single / K * 1e3
     rec = {
-        "workload": cfg.name, "dtype": dname, "group": group, "merged_layers": merge,
+        "workload": cfg.name, "dtype": dname, "group": group, "merged_layers": merge, "fused_tree_layers": hp.fused,
         "n_vertices": cfg.n_vertices, "n_edges": g.n_edges, "feature_dim": cfg.d, "batch": cfg.batch,
         "fanouts": cfg.fanouts, "hidden": cfg.hidden, "slots_per_batch": shb.n_slots,
         "batches_per_s": K * group / t_single, "ms_per_step": step_ms, "repeats": len(plain),
@@ -465,7 +476,7 @@ def main_headline(args):
         "config": {"workload": head["workload"], "n_vertices": head["n_vertices"], "n_edges": head["n_edges"],
                    "feature_dim": head["feature_dim"], "batch": head["batch"], "fanouts": head["fanouts"],
                    "hidden": head["hidden"], "group": head["group"], "merged_layers": head["merged_layers"],
-                   "slots_per_batch": head["slots_per_batch"], "streams": 1, "backward": False, "layer": "sage",
+                   "fused_tree_layers": head["fused_tree_layers"], "slots_per_batch": head["slots_per_batch"], "streams": 1, "backward": False, "layer": "sage",
                    "repeats_of_steps": head["repeats"], "min_seconds": args.min_seconds},
         "gather_GBps": head["kernels"]["gather"]["achieved"],
         "gather_frac_of_hbm_peak": head["kernels"]["gather"]["frac"],
@@ -482,7 +493,7 @@ def main_headline(args):
     if "cpu_baseline" in head:
         out["cpu_baseline"] = head["cpu_baseline"]
     if others:
-        keep = ("workload", "dtype", "group", "merged_layers", "batch", "fanouts", "hidden", "batches_per_s",
+        keep = ("workload", "dtype", "group", "merged_layers", "fused_tree_layers", "batch", "fanouts", "hidden", "batches_per_s",
                 "ms_per_step", "repeats", "multi_stream", "unique_rows_per_step", "unique_over_valid_slots",
                 "unique_group_over_sum_of_per_batch_unique", "valid_slot_fraction", "dominant_kernel",
                 "kernel_share_of_step", "cpu_baseline")

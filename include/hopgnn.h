@@ -569,6 +569,21 @@ hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_s
  *                               Then indptr holds group*S+1 entries, H[k] group times the rows,
  *                               sage_ws is sized for group times the rows, and ids / remap /
  *                               slot_idx are in the merged layout.
+ *   fuse_tree, tree_ws          nonzero fuse_tree (GraphSAGE-mean layers over slot trees only: layer_kind 0,
+ *                               dedup 0, at least two layers, every fanout but the last at most 64,
+ *                               dim and every d_out a multiple of 8; otherwise the flag is ignored): the
+ *                               slot tree's shape is used to leave work out.  A parent's children are
+ *                               consecutive slots, so layer k's projection also averages every group
+ *                               of siblings of the rows it has just produced (stored values, child
+ *                               order, invalid slots skipped: the segmented mean's arithmetic) and
+ *                               hands layer k+1 its neighbour means; layers >= 2 then run no
+ *                               aggregation kernel, and the rows of layer k's deepest level - which
+ *                               layer k+1 reads through those means only - are never written (H[k]
+ *                               holds the rows of layer k+1's destinations).  Same last-layer bits as
+ *                               without the flag.  tree_ws: scratch of hopgnn_batch_tree_ws_bytes(plan)
+ *                               (transposed weights, a zero row, two mean buffers), 256-byte aligned,
+ *                               filled by hopgnn_batch_prepare(plan) once and again whenever the
+ *                               weights change; sage_ws is then not used.
  *   pg_ws_clean                 nonzero: pg_ws was prepared by hopgnn_pregather_ws_init (sizes
  *                               group*T, n_vertices, pg_algo) and has since only been used by
  *                               this library's calls, all of which leave it clean.  Then the
@@ -617,10 +632,16 @@ typedef struct {
     void *dd_ws;
     size_t dd_ws_bytes;
     int32_t mark_stage;
+    int32_t fuse_tree;
+    void *tree_ws;
+    size_t tree_ws_bytes;
 } hopgnn_batch_plan;
 
 enum { HOPGNN_MARK_GATHER = 0, HOPGNN_MARK_EMPTY = 1, HOPGNN_MARK_SAMPLE = 2, HOPGNN_MARK_PREGATHER = 3,
        HOPGNN_MARK_AGGREGATE = 16, HOPGNN_MARK_PROJECT = 32 };
+
+size_t hopgnn_batch_tree_ws_bytes(const hopgnn_batch_plan *plan /*HOST*/);
+hopgnn_status hopgnn_batch_prepare(const hopgnn_batch_plan *plan /*HOST*/, void *stream);
 
 hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan *plan /*HOST*/, const int32_t *seeds,
                                const uint64_t *keys /*HOST*/, int32_t n_batches, void *out, void *stream);

@@ -30,7 +30,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
            "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
-           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_pregather_static", "hopgnn_pregather_static_max_vertices", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
+           "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_pregather_static", "hopgnn_batch_tree_ws_bytes", "hopgnn_batch_prepare", "hopgnn_pregather_static_max_vertices", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
 
 
@@ -67,7 +67,8 @@ class BatchPlan(ctypes.Structure):
                 ("a_src", ctypes.c_void_p * 8), ("a_dst", ctypes.c_void_p * 8),
                 ("dedup", ctypes.c_int32), ("node_vertex", ctypes.c_void_p), ("level_start", ctypes.c_void_p),
                 ("dd_idx", ctypes.c_void_p), ("dd_idx_l1", ctypes.c_void_p), ("dd_ws", ctypes.c_void_p),
-                ("dd_ws_bytes", ctypes.c_size_t), ("mark_stage", ctypes.c_int32)]
+                ("dd_ws_bytes", ctypes.c_size_t), ("mark_stage", ctypes.c_int32), ("fuse_tree", ctypes.c_int32),
+                ("tree_ws", ctypes.c_void_p), ("tree_ws_bytes", ctypes.c_size_t)]
 
 
 def library_path() -> str:
@@ -205,6 +206,10 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
                                  c.c_int32, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_batch_tree_ws_bytes.restype = c.c_size_t
+    L.hopgnn_batch_tree_ws_bytes.argtypes = [c.POINTER(BatchPlan)]
+    L.hopgnn_batch_prepare.restype = c.c_int
+    L.hopgnn_batch_prepare.argtypes = [c.POINTER(BatchPlan), c.c_void_p]
     L.hopgnn_batch_fwd.restype = c.c_int
     L.hopgnn_batch_fwd.argtypes = [c.POINTER(BatchPlan), c.c_void_p, c.POINTER(c.c_uint64), c.c_int32, c.c_void_p,
                                    c.c_void_p]

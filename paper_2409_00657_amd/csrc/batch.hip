@@ -9,6 +9,95 @@
 
 using namespace hopgnn;
 
+namespace {
+
+// Scratch of the fused slot-tree path: per layer the transposed weights (2-byte types), one zero
+// row, and two neighbour-mean buffers that consecutive layers alternate between (layer k reads
+// mean[(k-1)&1], its projection writes layer k+1's means into mean[k&1]).
+struct TreeWs {
+    size_t wt_off[kMaxLayers], zero_off, zero_bytes, mean_off[2], total;
+    int32_t KP[kMaxLayers], NP[kMaxLayers];
+    bool ok;
+};
+
+bool tree_applies(const hopgnn_batch_plan* p) {
+    const int32_t L = p->n_layers;
+    if (!p->fuse_tree || p->layer_kind != 0 || p->dedup || L < 2 || L > kMaxLayers) return false;
+    if (p->dim % 8 != 0) return false;
+    for (int32_t k = 0; k < L; ++k)
+        if (p->d_out[k] < 1 || p->d_out[k] % 8 != 0) return false;
+    for (int32_t h = 0; h + 1 < L; ++h)           // groups of siblings on the levels that some layer averages
+        if (p->fanouts[h] < 1 || p->fanouts[h] > kTreeMaxFan) return false;
+    return true;
+}
+
+TreeWs tree_ws_layout(const hopgnn_batch_plan* p) {
+    TreeWs W{};
+    const int32_t L = p->n_layers, B = p->n_seeds;
+    W.ok = tree_applies(p) && B >= 1;
+    if (!W.ok) return W;
+    const size_t es = dtype_size(p->dt);
+    const int64_t scale = p->merge_layers ? p->group : 1;
+    int64_t level[kMaxLayers + 1];
+    level[0] = (int64_t)B * scale;
+    for (int h = 1; h <= L; ++h) level[h] = level[h - 1] * p->fanouts[h - 1];
+    size_t o = 0, mean_bytes[2] = {0, 0};
+    int32_t d_in = p->dim, d_max = p->dim;
+    for (int32_t k = 1; k <= L; ++k) {
+        const ProjWs P = proj_ws_layout(p->dt, 0, d_in, 2 * d_in, p->d_out[k - 1]);
+        W.KP[k - 1] = P.KP;
+        W.NP[k - 1] = P.NP;
+        W.wt_off[k - 1] = o;
+        o += P.wt_bytes;
+        int64_t n_dst = 0;
+        for (int h = 0; h <= L - k; ++h) n_dst += level[h];
+        const size_t mb = align_up((size_t)n_dst * (size_t)d_in * es, 256);
+        if (mb > mean_bytes[(k - 1) & 1]) mean_bytes[(k - 1) & 1] = mb;
+        d_max = d_in > d_max ? d_in : d_max;
+        d_in = p->d_out[k - 1];
+    }
+    W.zero_off = o;
+    W.zero_bytes = align_up(((size_t)2 * d_max + 64) * es, 256);
+    o += W.zero_bytes;
+    W.mean_off[0] = o;
+    o += mean_bytes[0];
+    W.mean_off[1] = o;
+    o += mean_bytes[1];
+    W.total = o;
+    return W;
+}
+
+}  // namespace
+
+extern "C" size_t hopgnn_batch_tree_ws_bytes(const hopgnn_batch_plan* p) {
+    if (p == nullptr) return 0;
+    const TreeWs W = tree_ws_layout(p);
+    return W.ok ? W.total : 0;
+}
+
+extern "C" hopgnn_status hopgnn_batch_prepare(const hopgnn_batch_plan* p, void* stream) {
+    if (p == nullptr) return HOPGNN_EINVAL;
+    const TreeWs W = tree_ws_layout(p);
+    if (!W.ok) return HOPGNN_OK;                   // the flag does not apply to this plan: nothing to prepare
+    if (p->tree_ws == nullptr || !aligned(p->tree_ws, 256)) return HOPGNN_EINVAL;
+    if (p->tree_ws_bytes < W.total) return HOPGNN_ENOMEM_WS;
+    char* ws = static_cast<char*>(p->tree_ws);
+    int32_t d_in = p->dim;
+    for (int32_t k = 1; k <= p->n_layers; ++k) {
+        if (p->W_self[k - 1] == nullptr || p->W_neigh[k - 1] == nullptr) return HOPGNN_EINVAL;
+        TransposeJob job{};
+        if (p->dt != HOPGNN_F32)
+            job = TransposeJob{static_cast<const uint16_t*>(p->W_self[k - 1]), static_cast<const uint16_t*>(p->W_neigh[k - 1]),
+                               reinterpret_cast<uint16_t*>(ws + W.wt_off[k - 1]), d_in, p->d_out[k - 1], W.KP[k - 1],
+                               W.NP[k - 1], 0u, 2 * d_in};
+        const hopgnn_status rc = launch_prep_weights(job, k == 1 ? ws + W.zero_off : nullptr, k == 1 ? W.zero_bytes : 0,
+                                                     static_cast<hipStream_t>(stream));
+        if (rc != HOPGNN_OK) return rc;
+        d_in = p->d_out[k - 1];
+    }
+    return HOPGNN_OK;
+}
+
 extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int32_t* seeds, const uint64_t* keys,
                                           int32_t n_batches, void* out, void* stream) {
     if (p == nullptr || seeds == nullptr || keys == nullptr || out == nullptr) return HOPGNN_EINVAL;
@@ -162,6 +251,58 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
 
     const int32_t d_last = p->d_out[L - 1];
     const int64_t rows_scale = merged ? n_batches : 1;         // level sizes of one run = B_run / B times a batch's
+    const TreeWs TW = tree_ws_layout(p);
+    if (TW.ok) {
+        // The slot tree's shape leaves work out: see fuse_tree in the header.  Layer 1 aggregates with the
+        // segmented-mean kernel (its neighbours are scattered rows of Xu); every projection but the last
+        // also writes the next layer's neighbour means and skips the rows only those means read.
+        if (p->tree_ws == nullptr || !aligned(p->tree_ws, 256)) return HOPGNN_EINVAL;
+        if (p->tree_ws_bytes < TW.total) return HOPGNN_ENOMEM_WS;
+        if (mstage >= HOPGNN_MARK_AGGREGATE + 2 && mstage < HOPGNN_MARK_PROJECT) return HOPGNN_EINVAL;   // no such kernel
+        char* tws = static_cast<char*>(p->tree_ws);
+        const void* zero = tws + TW.zero_off;
+        for (int32_t b = 0; b < n_runs; ++b) {
+            const int32_t* rb = p->remap + b * T;
+            const void* src = p->Xu;
+            int32_t d_in = p->dim;
+            for (int32_t k = 1; k <= L; ++k) {
+                int64_t n_dst = 0;
+                for (int h = 0; h <= L - k; ++h) n_dst += level[h] * rows_scale;
+                void* dst = k == L ? (void*)((char*)out + (size_t)b * B * d_last * es) : p->H[k - 1];
+                if (dst == nullptr) return HOPGNN_EINVAL;
+                void* mean = tws + TW.mean_off[(k - 1) & 1];
+                const uint16_t* Wt = reinterpret_cast<const uint16_t*>(tws + TW.wt_off[k - 1]);
+                const bool mk = b == 0 && k == mark_layer;
+                if (k == 1) {
+                    if (mk && mark_agg && hipEventRecord(ev_a, st) != hipSuccess) return HOPGNN_EHIP;
+                    const AggSpec spec{nullptr, 0, kAggOpMean};
+                    void* zr = const_cast<void*>(zero);
+                    if (p->dt == HOPGNN_F32) rc = launch_mean<TrF32>(src, p->indptr, rb + B_run, n_dst, d_in, mean, zr, TW.zero_bytes, TransposeJob{}, 0, st, spec, nullptr);
+                    else if (p->dt == HOPGNN_BF16) rc = launch_mean<TrBF16>(src, p->indptr, rb + B_run, n_dst, d_in, mean, zr, TW.zero_bytes, TransposeJob{}, 0, st, spec, nullptr);
+                    else rc = launch_mean<TrF16>(src, p->indptr, rb + B_run, n_dst, d_in, mean, zr, TW.zero_bytes, TransposeJob{}, 0, st, spec, nullptr);
+                    if (rc != HOPGNN_OK) return rc;
+                    if (mk && mark_agg && hipEventRecord(ev_b, st) != hipSuccess) return HOPGNN_EHIP;
+                }
+                TreeLayer tree{};
+                tree.n_levels = L - k + 1;
+                for (int h = 0; h < tree.n_levels; ++h) {
+                    tree.level_rows[h] = level[h] * rows_scale;
+                    tree.fan[h] = h ? p->fanouts[h - 1] : 1;
+                }
+                tree.ids = p->ids + (merged ? 0 : (int64_t)b * T);
+                tree.mean_next = tws + TW.mean_off[k & 1];
+                if (mk && !mark_agg && hipEventRecord(ev_a, st) != hipSuccess) return HOPGNN_EHIP;
+                rc = project_dispatch(p->dt, st, src, k == 1 ? rb : nullptr, mean, p->W_self[k - 1], p->W_neigh[k - 1], Wt,
+                                      TW.KP[k - 1], p->bias[k - 1], n_dst, d_in, 2 * d_in, p->d_out[k - 1], k < L ? 1 : 0,
+                                      zero, dst, 0, nullptr, k < L ? &tree : nullptr);
+                if (rc != HOPGNN_OK) return rc;
+                if (mk && !mark_agg && hipEventRecord(ev_b, st) != hipSuccess) return HOPGNN_EHIP;
+                src = dst;
+                d_in = p->d_out[k - 1];
+            }
+        }
+        return HOPGNN_OK;
+    }
     for (int32_t b = 0; b < n_runs; ++b) {
         const int32_t* rb = p->remap + b * T;
         const void* src = p->Xu;

@@ -144,20 +144,122 @@ __device__ __forceinline__ void project_epilogue_staged(floatx16 (&acc)[TM][TN],
     (void)sizeof(T);
 }
 
+// Slot-tree layers: which rows a row tile covers.  Returns false for a tile past the last one.
+template <int BM>
+__device__ __forceinline__ bool tree_tile_rows(const TreeTiles& tt, uint32_t mt, int& lvl, uint32_t& tile_in_level,
+                                               int64_t& row0, int64_t& row_end) {
+    if (mt >= tt.tile0[tt.n_levels]) return false;
+    lvl = 0;
+    while (mt >= tt.tile0[lvl + 1]) ++lvl;
+    tile_in_level = mt - tt.tile0[lvl];
+    const int64_t per_tile = lvl == 0 ? (int64_t)BM : (int64_t)tt.g[lvl] * tt.f[lvl];
+    row0 = tt.row0[lvl] + (int64_t)tile_in_level * per_tile;
+    const int64_t level_end = tt.row0[lvl] + tt.rows[lvl];
+    row_end = row0 + per_tile < level_end ? row0 + per_tile : level_end;
+    return true;
+}
+
+// Epilogue of a slot-tree layer, by the whole workgroup.  The tile's results (bias, activation,
+// rounding to the storage type applied) are staged in LDS PW columns at a time; from there
+//   - the rows of levels the next layer reads directly leave as 128-bit row pieces, and
+//   - every group of siblings is averaged into its parent's row of the next layer's neighbour
+//     means: fp32 running sum of the STORED values in child order over the valid children, one
+//     division, one rounding - the arithmetic of the segmented-mean kernel, so the bits are the
+//     ones that kernel would produce from the written rows.
+// LDS: [BM][PW + 16 bytes] staged values, then BM validity bytes.  Needs d_out % (16 / sizeof(T)) == 0.
+template <typename Tr, int BM, int BN, int PW, int TM, int TN, int NT>
+__device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds, int wave_row0, int wave_col0, int tid,
+                                              int lane, int64_t row0, int64_t row_end, int32_t col0, int32_t d_out,
+                                              const typename Tr::store_t* bias, int relu, typename Tr::store_t* out,
+                                              const TreeTiles& tt, int lvl, uint32_t tile_in_level) {
+    using T = typename Tr::store_t;
+    constexpr int EPW = 16 / (int)sizeof(T);      // elements per 16-byte word
+    constexpr int LDT = PW + EPW;                 // padded row of the staged tile
+    constexpr int WORDS = PW / EPW;
+    static_assert(BN % PW == 0 && PW % 32 == 0, "column passes");
+    T* tile = static_cast<T*>(lds);
+    uint8_t* vld = reinterpret_cast<uint8_t*>(tile + BM * LDT);
+    const int n_rows = (int)(row_end - row0);
+    const bool make_means = lvl >= 1 && tt.mean_next != nullptr;
+    const bool store_rows = lvl < tt.store_levels;
+    if (make_means)
+        for (int i = tid; i < BM; i += NT) vld[i] = (i < n_rows && tt.ids[row0 + i] >= 0) ? 1 : 0;
+#pragma unroll 1
+    for (int c_lo = 0; c_lo < BN; c_lo += PW) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) {
+            const int wc = wave_col0 + tn * 32;
+            if (wc < c_lo || wc >= c_lo + PW) continue;
+            const int32_t col = col0 + wc + (lane & 31);
+            const float b = (bias != nullptr && col < d_out) ? Tr::to_f(bias[col]) : 0.f;
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float x = acc[tm][tn][i] + b;
+                    if (relu) x = fmaxf(x, 0.f);
+                    const int row = wave_row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                    tile[row * LDT + (wc - c_lo) + (lane & 31)] = Tr::from_f(x);
+                }
+        }
+        __syncthreads();
+        if (store_rows)
+            for (int w = tid; w < n_rows * WORDS; w += NT) {
+                const int r = w / WORDS, c = (w % WORDS) * EPW;
+                const int32_t gc = col0 + c_lo + c;
+                if (gc < d_out)
+                    *reinterpret_cast<uint4*>(&out[(row0 + r) * d_out + gc]) =
+                        *reinterpret_cast<const uint4*>(&tile[r * LDT + c]);
+            }
+        if (make_means) {
+            const int f = tt.f[lvl];
+            const int n_groups = n_rows / f;              // a level's rows are whole groups
+            T* mean_next = static_cast<T*>(tt.mean_next);
+            const int64_t parent0 = tt.row0[lvl - 1] + (int64_t)tile_in_level * tt.g[lvl];
+            for (int w = tid; w < n_groups * WORDS; w += NT) {
+                const int j = w / WORDS, c = (w % WORDS) * EPW;
+                float a[EPW];
+#pragma unroll
+                for (int e = 0; e < EPW; ++e) a[e] = 0.f;
+                int cnt = 0;
+                for (int i = 0; i < f; ++i) {
+                    const int row = j * f + i;
+                    if (vld[row]) {
+                        Pack16<Tr> v;
+                        v.v = *reinterpret_cast<const uint4*>(&tile[row * LDT + c]);
+#pragma unroll
+                        for (int e = 0; e < EPW; ++e) a[e] = a[e] + Tr::to_f(v.e[e]);
+                        ++cnt;
+                    }
+                }
+                Pack16<Tr> o;
+                const float fc = (float)cnt;
+#pragma unroll
+                for (int e = 0; e < EPW; ++e) o.e[e] = Tr::from_f(cnt > 0 ? a[e] / fc : 0.f);
+                const int32_t gc = col0 + c_lo + c;
+                if (gc < d_out) *reinterpret_cast<uint4*>(&mean_next[(parent0 + j) * d_out + gc]) = o.v;
+            }
+        }
+        __syncthreads();      // the staged tile is rewritten by the next pass
+    }
+}
+
 // fp32: v_mfma_f32_32x32x2_f32 (lane l feeds A[row l%32][k = l/32] and B[k = l/32][col l%32]).
 // LDS: A row-major [BM][BK+4] read as 128-bit words - lane group g = l/32 takes the four
 // k values 4g..4g+3 of an 8-wide K block and the four MFMAs of the block pair A's i-th
 // value with B row 4g+i, which only permutes the order in which k is summed.
 // B is [BK][BN+4], read as 32 consecutive floats per half wave.
-template <int BM, int BN, int BK, bool VEC>
+template <int BM, int BN, int BK, int D, bool VEC, bool TREE>
 __global__ void __launch_bounds__(kProjThreads)
 sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                  const float* __restrict__ Mean, const float* __restrict__ Wself,
                  const float* __restrict__ Wneigh, const float* __restrict__ bias, int64_t n_dst,
                  int32_t d_in, int32_t k_total, int32_t d_out, int relu, uint32_t n_tiles_n,
-                 const float* __restrict__ Zero, float* __restrict__ out, const int64_t* __restrict__ n_rows_dev) {
+                 const float* __restrict__ Zero, float* __restrict__ out, const int64_t* __restrict__ n_rows_dev,
+                 TreeTiles tt) {
     constexpr int LDA = BK + 4, LDB = BN + 4;   // LDA/4 odd: conflict-free 128-bit reads
     static_assert(BK % 8 == 0 && (LDA / 4) % 2 == 1, "K tile");
+    static_assert(D >= 2 && D % 2 == 0, "ring depth");
     constexpr int TM = BM / 64, TN = BN / 64;
     constexpr int A_ITEMS = BM * BK / 4 / kProjThreads;   // float4 items per thread
     constexpr int B_ITEMS = BK * BN / 4 / kProjThreads;
@@ -168,12 +270,19 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
 
     uint32_t mt, nt;
     tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
-    const int64_t row0 = (int64_t)mt * BM;
-    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
-        const int64_t live = *n_rows_dev;
-        n_dst = live < n_dst ? live : n_dst;
+    int64_t row0 = (int64_t)mt * BM, row_end;
+    int lvl = 0;
+    uint32_t tile_in_level = 0;
+    if (TREE) {
+        if (!tree_tile_rows<BM>(tt, mt, lvl, tile_in_level, row0, row_end)) return;
+    } else {
+        if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+            const int64_t live = *n_rows_dev;
+            n_dst = live < n_dst ? live : n_dst;
+        }
+        if (row0 >= n_dst) return;
+        row_end = n_dst;
     }
-    if (row0 >= n_dst) return;
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -187,7 +296,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
         const int64_t r = row0 + i / (BK / 4);
         a_self[it] = -1;
         a_mean[it] = -1;
-        if (r < n_dst) {
+        if (r < row_end) {
             const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
             a_self[it] = s >= 0 ? s * d_in : -1;
             a_mean[it] = r * d_in;
@@ -313,27 +422,39 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
         __builtin_amdgcn_sched_barrier(kSchedPin);
     };
 
-    // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
-    // an even number of tiles.  Iteration t: the loads of tile t+2 are issued first, tile t is
-    // multiplied from LDS stage t&1, and only then is tile t+1 (loaded one iteration ago) moved
-    // from its registers to the other stage, so a load has two iterations to arrive before
-    // anything waits for it.
-    Regs r0, r1;
-    load_tile(r0, 0);
-    store_tile(r0, 0);
-    load_tile(r0, 1);
+    // A ring of D register sets and two LDS stages.  Iteration t: the loads of tile t+D are issued
+    // first (into the set tile t has left), tile t is multiplied from LDS stage t&1, and only then
+    // is tile t+1 - loaded D-1 iterations ago - moved from its registers to the other stage, so
+    // a load has D iterations to arrive before anything waits for it.  Exactly n_tiles tiles are
+    // multiplied (tiles at or beyond n_tiles load as zeros and are never multiplied); D is even
+    // so that the stage of an unrolled iteration is a constant.
+    Regs r[D];
+    load_tile(r[0], 0);
+    store_tile(r[0], 0);
+#pragma unroll
+    for (int j = 1; j < D; ++j) load_tile(r[j], j);
     lds_barrier();
-    for (int t = 0; t < n_tiles; t += 2) {
-        load_tile(r1, t + 2);
-        compute(0);
-        store_tile(r0, 1);
+    auto iter = [&](int t, int i) {     // i = t % D, a constant after unrolling
+        load_tile(r[i], t + D);
+        compute(i & 1);
+        store_tile(r[(i + 1) % D], (i + 1) & 1);
         lds_barrier();
-        load_tile(r0, t + 3);
-        compute(1);
-        store_tile(r1, 0);
-        lds_barrier();
+    };
+    int t = 0;
+    for (; t + D <= n_tiles; t += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) iter(t + i, i);
     }
-    project_epilogue<TrF32, TM, TN>(acc, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane, n_dst, d_out, bias, relu, out);
+#pragma unroll
+    for (int i = 0; i < D - 1; ++i)
+        if (t + i < n_tiles) iter(t + i, i);
+    if (TREE)
+        tree_epilogue<TrF32, BM, BN, 64, TM, TN, kProjThreads>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
+                                                               row_end, col0, d_out, bias, relu, out, tt, lvl,
+                                                               tile_in_level);
+    else
+        project_epilogue<TrF32, TM, TN>(acc, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane, row_end, d_out, bias, relu,
+                                        out);
 }
 
 // bf16 / fp16: v_mfma_f32_32x32x16_{bf16,f16}.  Lane l feeds 8 consecutive k of row (or
@@ -356,15 +477,17 @@ __device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b
 
 constexpr int kKPad16 = 64;   // Wt rows are zero padded to a multiple of this many k
 
-template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
+template <typename Tr, int BM, int BN, int BK, int WM, int WN, int D, bool VEC, bool TREE>
 __global__ void __launch_bounds__(64 * WM * WN)
 sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                 const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
                 const typename Tr::store_t* __restrict__ bias, int64_t n_dst, int32_t d_in, int32_t k_total,
                 int32_t d_out, int relu, uint32_t n_tiles_n, const uint16_t* __restrict__ Zero,
-                typename Tr::store_t* __restrict__ out, int out_f32, const int64_t* __restrict__ n_rows_dev) {
+                typename Tr::store_t* __restrict__ out, int out_f32, const int64_t* __restrict__ n_rows_dev,
+                TreeTiles tt) {
     constexpr int LD = BK + 8;
     static_assert(kKPad16 % BK == 0, "Wt padding must cover whole K tiles");
+    static_assert(D >= 2 && D % 2 == 0, "ring depth");
     constexpr int NT = 64 * WM * WN;                      // threads: WM x WN waves
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;   // 32x32 MFMA tiles per wave
     constexpr int A_ITEMS = BM * BK / 8 / NT;             // 16-byte items per thread
@@ -376,12 +499,19 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
 
     uint32_t mt, nt;
     tile_of_block(blockIdx.x, n_tiles_n, mt, nt);
-    const int64_t row0 = (int64_t)mt * BM;
-    if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
-        const int64_t live = *n_rows_dev;
-        n_dst = live < n_dst ? live : n_dst;
+    int64_t row0 = (int64_t)mt * BM, row_end;
+    int lvl = 0;
+    uint32_t tile_in_level = 0;
+    if (TREE) {
+        if (!tree_tile_rows<BM>(tt, mt, lvl, tile_in_level, row0, row_end)) return;
+    } else {
+        if (n_rows_dev != nullptr) {      // the row count lives on the device: rows past it do not exist
+            const int64_t live = *n_rows_dev;
+            n_dst = live < n_dst ? live : n_dst;
+        }
+        if (row0 >= n_dst) return;
+        row_end = n_dst;
     }
-    if (row0 >= n_dst) return;
     const int32_t col0 = nt * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -394,7 +524,7 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
         const int64_t r = row0 + i / (BK / 8);
         a_self[it] = -1;
         a_mean[it] = -1;
-        if (r < n_dst) {
+        if (r < row_end) {
             const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
             a_self[it] = s >= 0 ? s * d_in : -1;
             a_mean[it] = r * d_in;
@@ -502,56 +632,89 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
         __builtin_amdgcn_sched_barrier(kSchedPin);
     };
 
-    // Tiles at or beyond n_tiles load as zeros, so the loop is unconditional and runs over
-    // an even number of tiles.  Iteration t: the loads of tile t+2 are issued first, tile t is
-    // multiplied from LDS stage t&1, and only then is tile t+1 (loaded one iteration ago) moved
-    // from its registers to the other stage, so a load has two iterations to arrive before
-    // anything waits for it.
-    Regs r0, r1;
-    load_tile(r0, 0);
-    store_tile(r0, 0);
-    load_tile(r0, 1);
+    // A ring of D register sets and two LDS stages.  Iteration t: the loads of tile t+D are issued
+    // first (into the set tile t has left), tile t is multiplied from LDS stage t&1, and only then
+    // is tile t+1 - loaded D-1 iterations ago - moved from its registers to the other stage, so
+    // a load has D iterations to arrive before anything waits for it.  Exactly n_tiles tiles are
+    // multiplied (tiles at or beyond n_tiles load as zeros and are never multiplied); D is even
+    // so that the stage of an unrolled iteration is a constant.
+    Regs r[D];
+    load_tile(r[0], 0);
+    store_tile(r[0], 0);
+#pragma unroll
+    for (int j = 1; j < D; ++j) load_tile(r[j], j);
     lds_barrier();
-    for (int t = 0; t < n_tiles; t += 2) {
-        load_tile(r1, t + 2);
-        compute(0);
-        store_tile(r0, 1);
+    auto iter = [&](int t, int i) {     // i = t % D, a constant after unrolling
+        load_tile(r[i], t + D);
+        compute(i & 1);
+        store_tile(r[(i + 1) % D], (i + 1) & 1);
         lds_barrier();
-        load_tile(r0, t + 3);
-        compute(1);
-        store_tile(r1, 0);
-        lds_barrier();
+    };
+    int t = 0;
+    for (; t + D <= n_tiles; t += D) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) iter(t + i, i);
     }
-    if (out_f32) {     // `out` is a float array: unrounded result
-        project_epilogue_f32out<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out, bias,
+#pragma unroll
+    for (int i = 0; i < D - 1; ++i)
+        if (t + i < n_tiles) iter(t + i, i);
+    if (TREE) {
+        tree_epilogue<Tr, BM, BN, BN, TM, TN, NT>(acc, lds16, wm * (BM / WM), wn * (BN / WN), tid, lane, row0, row_end, col0,
+                                                  d_out, bias, relu, out, tt, lvl, tile_in_level);
+    } else if (out_f32) {     // `out` is a float array: unrounded result
+        project_epilogue_f32out<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out, bias,
                                             relu, reinterpret_cast<float*>(out));
     } else if (VEC && (d_out & 7) == 0) {
         // every wave is past its last LDS read of the tiles: reuse that LDS, one band per wave
         constexpr int BAND = 32 * (32 * TN + 8);
         static_assert((size_t)WM * WN * BAND <= (size_t)2 * (BM + BN) * LD, "epilogue bands exceed the tile LDS");
         typename Tr::store_t* band = reinterpret_cast<typename Tr::store_t*>(lds16) + wave * BAND;
-        project_epilogue_staged<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out,
+        project_epilogue_staged<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out,
                                             bias, relu, out, band);
     } else {
-        project_epilogue<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, n_dst, d_out, bias,
+        project_epilogue<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out, bias,
                                      relu, out);
     }
 }
 
 // ------------------------------------------------------------------ launch --
 
-static uint32_t project_grid(int64_t n_dst, int BM, uint32_t n_tiles_n) {
-    const int64_t m_tiles = ceil_div(n_dst, BM);
+static uint32_t project_grid(int64_t m_tiles, uint32_t n_tiles_n) {
     return (uint32_t)(ceil_div(m_tiles, kXcds) * kXcds * n_tiles_n);
 }
 
-template <int BM, int BN, int BK>
+// The row tiles of a slot-tree layer for tile height BM (see TreeTiles); returns their number.
+static int64_t tree_tiles(const TreeLayer& t, int BM, TreeTiles& tt) {
+    tt = TreeTiles{};
+    tt.n_levels = t.n_levels;
+    tt.store_levels = t.mean_next != nullptr ? t.n_levels - 1 : t.n_levels;
+    tt.ids = t.ids;
+    tt.mean_next = t.mean_next;
+    int64_t row = 0, tiles = 0;
+    for (int h = 0; h < t.n_levels; ++h) {
+        tt.row0[h] = row;
+        tt.rows[h] = t.level_rows[h];
+        tt.f[h] = h ? t.fan[h] : 1;
+        tt.g[h] = h ? BM / t.fan[h] : BM;
+        const int64_t per_tile = h ? (int64_t)tt.g[h] * tt.f[h] : BM;
+        tt.tile0[h] = (uint32_t)tiles;
+        tiles += ceil_div(t.level_rows[h], per_tile);
+        row += t.level_rows[h];
+    }
+    tt.tile0[t.n_levels] = (uint32_t)tiles;
+    return tiles;
+}
+
+template <int BM, int BN, int BK, int D>
 static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                         const void* mean, const void* Ws, const void* Wn, const void* bias,
                                         int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                        const void* zero, void* out, const int64_t* n_rows_dev) {
+                                        const void* zero, void* out, const int64_t* n_rows_dev, const TreeLayer* tree) {
     const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
-    const dim3 grid(project_grid(n_dst, BM, ntn));
+    TreeTiles tt{};
+    const int64_t m_tiles = tree != nullptr ? tree_tiles(*tree, BM, tt) : ceil_div(n_dst, BM);
+    if (m_tiles * ntn + kXcds * ntn >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    const dim3 grid(project_grid(m_tiles, ntn));
     auto a = static_cast<const float*>(Hsrc);
     auto m = static_cast<const float*>(mean);
     auto ws = static_cast<const float*>(Ws);
@@ -559,47 +722,49 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
     auto b = static_cast<const float*>(bias);
     auto o = static_cast<float*>(out);
     auto z = static_cast<const float*>(zero);
-    constexpr size_t lds = (size_t)2 * (BM * (BK + 4) + BK * (BN + 4)) * sizeof(float);
-    auto kern = vec ? sage_project_f32<BM, BN, BK, true> : sage_project_f32<BM, BN, BK, false>;
+    constexpr size_t lds_loop = (size_t)2 * (BM * (BK + 4) + BK * (BN + 4)) * sizeof(float);
+    constexpr size_t lds_tree = (size_t)BM * (64 + 4) * sizeof(float) + BM;     // staged tile + validity bytes
+    const size_t lds = tree != nullptr && lds_tree > lds_loop ? lds_tree : lds_loop;
+    auto kern = tree != nullptr ? sage_project_f32<BM, BN, BK, D, true, true>
+                : vec           ? sage_project_f32<BM, BN, BK, D, true, false>
+                                : sage_project_f32<BM, BN, BK, D, false, false>;
     if (lds > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)lds) != hipSuccess)
         return HOPGNN_EHIP;
     hipLaunchKernelGGL(kern, grid, dim3(kProjThreads), lds, s, a, self_idx, m, ws, wn, b, n_dst, d_in, k_total, d_out,
-                       relu, ntn, z, o, n_rows_dev);
+                       relu, ntn, z, o, n_rows_dev, tt);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
 }
 
-template <typename Tr, int BM, int BN, int BK, int WM, int WN, bool VEC>
-static hopgnn_status launch_project_16_v(hipStream_t s, const void* Hsrc, const int32_t* self_idx,
-                                         const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
-                                         int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                         const void* zero, void* out, int out_f32, const int64_t* n_rows_dev) {
+template <typename Tr, int BM, int BN, int BK, int WM, int WN, int D = 2>
+static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
+                                       const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
+                                       int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
+                                       const void* zero, void* out, int out_f32, const int64_t* n_rows_dev,
+                                       const TreeLayer* tree) {
     using T = typename Tr::store_t;
     constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(uint16_t);
-    auto kern = sage_project_16<Tr, BM, BN, BK, WM, WN, VEC>;
+    static_assert((size_t)BM * (BN + 8) * 2 + BM <= lds, "the staged tile of a slot-tree layer must fit the loop's LDS");
+    auto kern = tree != nullptr ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, true>
+                : vec           ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, false>
+                                : sage_project_16<Tr, BM, BN, BK, WM, WN, D, false, false>;
     if (lds > 64 * 1024) {   // above the default limit the size has to be opted into
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
             return HOPGNN_EHIP;
     }
     const uint32_t ntn = (uint32_t)ceil_div(d_out, BN);
-    hipLaunchKernelGGL(kern, dim3(project_grid(n_dst, BM, ntn)), dim3(64 * WM * WN), lds, s,
+    TreeTiles tt{};
+    const int64_t m_tiles = tree != nullptr ? tree_tiles(*tree, BM, tt) : ceil_div(n_dst, BM);
+    if (m_tiles * ntn + kXcds * ntn >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    hipLaunchKernelGGL(kern, dim3(project_grid(m_tiles, ntn)), dim3(64 * WM * WN), lds, s,
                        static_cast<const uint16_t*>(Hsrc), self_idx, static_cast<const uint16_t*>(mean), Wt,
                        KP, static_cast<const T*>(bias), n_dst, d_in, k_total, d_out, relu, ntn,
-                       static_cast<const uint16_t*>(zero), static_cast<T*>(out), out_f32, n_rows_dev);
+                       static_cast<const uint16_t*>(zero), static_cast<T*>(out), out_f32, n_rows_dev, tt);
     HOPGNN_LAUNCH_CHECK();
     return HOPGNN_OK;
-}
-
-template <typename Tr, int BM, int BN, int BK, int WM, int WN>
-static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
-                                       const void* mean, const uint16_t* Wt, int32_t KP, const void* bias,
-                                       int64_t n_dst, int32_t d_in, int32_t k_total, int32_t d_out, int relu,
-                                       const void* zero, void* out, int out_f32, const int64_t* n_rows_dev) {
-    return vec ? launch_project_16_v<Tr, BM, BN, BK, WM, WN, true>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev)
-               : launch_project_16_v<Tr, BM, BN, BK, WM, WN, false>(s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
 }
 
 ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out) {
@@ -617,28 +782,55 @@ hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc,
                                const void* mean, const void* W_self, const void* W_neigh, const uint16_t* Wt,
                                int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
                                int32_t d_out, int relu, const void* zero, void* out, int out_f32,
-                               const int64_t* n_rows_dev) {
+                               const int64_t* n_rows_dev, const TreeLayer* tree) {
     const int per16 = dt == HOPGNN_F32 ? 4 : 8;
     const int64_t work = ceil_div(n_dst, 128) * ceil_div(d_out, 128);   // 128 x 128 output tiles
+    bool vec = d_in % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16);
+    if (dt == HOPGNN_F32) vec = vec && d_out % per16 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
+    if (tree != nullptr) {      // the slot-tree kernels are built for the vector path only
+        if (!vec || out_f32 || n_rows_dev != nullptr || d_out % 8 != 0 || !aligned(out, 16) ||
+            (tree->mean_next != nullptr && !aligned(tree->mean_next, 16)) || tree->n_levels < 1 ||
+            tree->n_levels > kMaxLayers + 1)
+            return HOPGNN_EINVAL;
+        for (int h = 1; h < tree->n_levels; ++h)
+            if (tree->fan[h] < 1 || tree->fan[h] > kTreeMaxFan) return HOPGNN_EINVAL;
+    }
     if (dt == HOPGNN_F32) {
-        const bool vec = d_in % per16 == 0 && d_out % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16) &&
-                         aligned(W_self, 16) && aligned(W_neigh, 16);
         // large tiles once there is enough work to fill 256 CUs twice over
         if (d_out > 64 && work >= 512)
-            return launch_project_f32<128, 128, 16>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev);
-        return launch_project_f32<64, 64, 32>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev);
+            return launch_project_f32<128, 128, 16, 2>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev, tree);
+        return launch_project_f32<64, 64, 32, 2>(vec, s, Hsrc, self_idx, mean, W_self, W_neigh, bias, n_dst, d_in, k_total, d_out, relu, zero, out, n_rows_dev, tree);
     }
-    const bool vec = d_in % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16);
     const bool huge = d_out > 128 && work >= 1024;   // 256 x 256 tiles once they still fill 256 CUs
     const bool big = d_out > 64 && work >= 512;
     if (dt == HOPGNN_BF16) {
-        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
-        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
-        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+        if (huge) return launch_project_16<TrBF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
+        if (big) return launch_project_16<TrBF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
+        return launch_project_16<TrBF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
     }
-    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
-    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
-    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev);
+    if (huge) return launch_project_16<TrF16, 256, 256, 64, 2, 4>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
+    if (big) return launch_project_16<TrF16, 128, 128, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
+    return launch_project_16<TrF16, 64, 64, 64, 2, 2>(vec, s, Hsrc, self_idx, mean, Wt, KP, bias, n_dst, d_in, k_total, d_out, relu, zero, out, out_f32, n_rows_dev, tree);
+}
+
+__global__ void __launch_bounds__(kMeanThreads)
+prep_weights(TransposeJob job, uint32_t n_tiles, uint32_t* __restrict__ zero_row, int32_t zero_words) {
+    if (blockIdx.x < n_tiles) {
+        transpose_w_tile(job, blockIdx.x);
+        return;
+    }
+    for (int32_t i = (blockIdx.x - n_tiles) * kMeanThreads + threadIdx.x; i < zero_words; i += kMeanThreads * (gridDim.x - n_tiles))
+        zero_row[i] = 0u;
+}
+
+hopgnn_status launch_prep_weights(TransposeJob job, void* zero_row, size_t zero_bytes, hipStream_t s) {
+    const uint32_t n_tiles = job.Wt != nullptr ? (uint32_t)(job.KP / 32) * (uint32_t)(job.NP / 32) : 0u;
+    const uint32_t n_zero = zero_bytes > 0 ? 1u : 0u;
+    if (n_tiles + n_zero == 0) return HOPGNN_OK;
+    hipLaunchKernelGGL(prep_weights, dim3(n_tiles + n_zero), dim3(kMeanThreads), 0, s, job, n_tiles,
+                       static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4));
+    HOPGNN_LAUNCH_CHECK();
+    return HOPGNN_OK;
 }
 
 }  // namespace hopgnn

@@ -263,17 +263,54 @@ struct ProjWs {
 };
 ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out);
 
+// Row tiling of one layer over a slot tree (level-major rows: level 0 = the roots, the children
+// of a level-(h-1) slot are f[h] consecutive level-h slots).  Tiles do not cross levels, and on
+// levels >= 1 a tile holds whole groups of siblings (g[h] groups of f[h] rows), so that the
+// projection's epilogue can also form the NEXT layer's neighbour means - the mean over a
+// parent's children of the rows this layer has just produced - and rows of the deepest level,
+// which the next layer reads through those means only, need not be written at all.
+struct TreeTiles {
+    int32_t n_levels;                    // this layer's destination rows are the slots of levels 0 .. n_levels-1
+    int32_t store_levels;                // rows of levels < store_levels are written to `out`
+    uint32_t tile0[kMaxLayers + 2];      // first row tile of level h; tile0[n_levels] = number of row tiles
+    int64_t row0[kMaxLayers + 1];        // first slot of level h
+    int64_t rows[kMaxLayers + 1];        // slots on level h
+    int32_t f[kMaxLayers + 1];           // siblings per group on level h (level 0: unused)
+    int32_t g[kMaxLayers + 1];           // groups per tile on level h
+    const int32_t* ids;                  // DEVICE: vertex of every slot (negative = invalid slot, no term of a mean)
+    void* mean_next;                     // DEVICE out [slots of levels 0 .. n_levels-2][d_out]; NULL: no means
+};
+
+// Host description of the same, before a tile height is chosen.
+struct TreeLayer {
+    int32_t n_levels;
+    int64_t level_rows[kMaxLayers + 1];
+    int32_t fan[kMaxLayers + 1];         // fan[h] = children per level-(h-1) slot, h >= 1
+    const int32_t* ids;
+    void* mean_next;
+};
+constexpr int kTreeMaxFan = 64;          // a group of siblings must fit the smallest row tile
+
 // out = act( [x_self | agg][:, :k_total] * [W_self ; W_neigh][:k_total] + bias ) on MFMA (defined with
 // the projection kernels).  k_total = 2*d_in is the two-matrix GraphSAGE layer, k_total = d_in a
 // plain rows-times-W product over the rows Hsrc[self_idx[r]].  For 2-byte types Wt (row stride KP)
 // must already hold the transposed weights; `zero` is a zeroed row of at least 2*d_in+64 elements.
 // out_f32 != 0: `out` is a float array and receives the unrounded result whatever dt is.
 // n_rows_dev (DEVICE, may be NULL): when given, only the first min(n_dst, *n_rows_dev) rows exist.
+// tree (may be NULL): the rows are the slots of a slot tree; rows are tiled level by level in whole
+// groups of siblings, the deepest level's rows are not written when tree->mean_next is given, and
+// that array receives the next layer's neighbour means (same bits as the segmented-mean kernel
+// would give over the stored rows).  Needs d_out % 8 == 0, every fan <= kTreeMaxFan, no n_rows_dev.
 hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                const void* agg, const void* W_self, const void* W_neigh, const uint16_t* Wt,
                                int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,
                                int32_t d_out, int relu, const void* zero, void* out, int out_f32,
-                               const int64_t* n_rows_dev);
+                               const int64_t* n_rows_dev, const TreeLayer* tree = nullptr);
+
+// Writes the transposed, zero-padded weights of one 2-byte layer (job.Wt, see TransposeJob) and
+// clears `zero_row` (zero_bytes, may be 0): what the segmented-mean kernel does as a side job, as
+// a launch of its own for layers that run without that kernel.  job.Wt == NULL: only the clearing.
+hopgnn_status launch_prep_weights(TransposeJob job, void* zero_row, size_t zero_bytes, hipStream_t s);
 
 // Optional event pairs around the two kernels of a layer (a harness timing them inside its
 // timed region); any handle may be NULL.

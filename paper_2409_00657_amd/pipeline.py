@@ -71,16 +71,22 @@ class HotPath:
 
     def __init__(self, offsets: torch.Tensor, indices: torch.Tensor, X: torch.Tensor,
                  weights, n_seeds: int, fanouts: Sequence[int], group: int = 1,
-                 pg_algo: int = hb.PG_AUTO, model: str = "sage", gat_heads: int = 4, merge: bool = False):
+                 pg_algo: int = hb.PG_AUTO, model: str = "sage", gat_heads: int = 4, merge: bool = False,
+                 fuse_tree: bool = True):
         """`weights`: per layer (W_self, W_neigh, bias-or-None).  model "sage" uses all three;
         "gcn" (mean over the vertex and its neighbours) and "gat" use W_self as the layer's one
         weight matrix, "gat" with seeded attention vectors and `gat_heads` heads.
         merge: the group's micrographs form ONE level-major batch of group * n_seeds micrographs
         (block b of n_seeds seeds keeps its own key), so every layer is one launch over the group;
-        `shape`, `ids`, `remap`, `H` then describe that merged batch and `layer_batches` is 1."""
+        `shape`, `ids`, `remap`, `H` then describe that merged batch and `layer_batches` is 1.
+        fuse_tree: the single-call path (`forward`) lets every projection but the last also form the
+        next layer's neighbour means from the slot tree's shape (plan.fuse_tree; same last-layer bits);
+        after it H[k] holds only the rows of the next layer's destinations.  The step-by-step calls
+        (`layer`, `layers`, `run_batch`, `run_group`) always run the two-kernel layers."""
         if model not in ("sage", "gcn", "gat"):
             raise hb.HopgnnError("model must be sage, gcn or gat")
         self.model, self.gat_heads = model, gat_heads
+        self.fuse_tree = bool(fuse_tree)
         dev = X.device
         self.offsets, self.indices, self.X, self.weights = offsets, indices, X, weights
         self.n_vertices = offsets.numel() - 1
@@ -193,10 +199,29 @@ class HotPath:
         pl.pg_ws, pl.pg_ws_bytes = self.pg_ws.data_ptr(), self.pg_ws.numel()
         pl.sage_ws, pl.sage_ws_bytes = self.sage_ws.data_ptr(), self.sage_ws.numel()
         pl.mark_begin = pl.mark_end = None
+        # the fused slot-tree path: its scratch holds the transposed weights, so weights that change
+        # (training) need prepare_weights() again; 0 bytes = the flag does not apply to this plan
+        pl.fuse_tree = 1 if self.fuse_tree else 0
+        pl.tree_ws, pl.tree_ws_bytes = None, 0
+        n_tree = int(lib.hopgnn_batch_tree_ws_bytes(ctypes.byref(pl))) if self.fuse_tree else 0
+        self.fused = n_tree > 0
+        if self.fused:
+            self.tree_ws = torch.empty(n_tree, dtype=torch.uint8, device=self.X.device)
+            pl.tree_ws, pl.tree_ws_bytes = self.tree_ws.data_ptr(), n_tree
+            self.prepare_weights()
+        else:
+            pl.fuse_tree = 0
         # every call of the library leaves the pre-gather workspace clean, so prepare it once
         hb.hopgnn_pregather_ws_init(self.pg_ws, self.group * T, self.n_vertices, self.pg_algo)
         pl.pg_ws_clean = 1
         self._keys = (ctypes.c_uint64 * self.n_keys)()
+
+    def prepare_weights(self, stream=None) -> None:
+        """(Re)build what the fused slot-tree path keeps of the weights (hopgnn_batch_prepare)."""
+        if self.fused:
+            rc = self._lib.hopgnn_batch_prepare(ctypes.byref(self.plan), self._stream(stream))
+            if rc:
+                hb._check(rc, "hopgnn_batch_prepare")
 
     # -- the four steps ------------------------------------------------------
     # `stream` is a raw hipStream_t (int); None = torch's current stream.

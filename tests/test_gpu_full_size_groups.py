@@ -53,7 +53,11 @@ def test_config5_merged_group_full_size_vs_oracle(orc, cfg5, G):
     from paper_2409_00657_amd.pipeline import BatchShape, HotPath
     cfg, g, X, W, (off_np, idx_np) = cfg5
     B, fan, L = cfg.batch, list(cfg.fanouts), len(cfg.fanouts)
-    hp = HotPath(g.offsets, g.indices, X, W, B, fan, group=G, merge=True)
+    # the call the benchmark issues puts the tree's shape to use (fuse_tree); the same call without it
+    # keeps every layer's rows, which is what the layer-by-layer checks below read
+    fused = HotPath(g.offsets, g.indices, X, W, B, fan, group=G, merge=True)
+    hp = HotPath(g.offsets, g.indices, X, W, B, fan, group=G, merge=True, fuse_tree=False)
+    assert fused.fused and not hp.fused
     shb, shm = BatchShape(B, fan), hp.shape
     assert hp.merge and shm.n_seeds == G * B
     Bm, T = G * B, shb.n_slots
@@ -61,8 +65,17 @@ def test_config5_merged_group_full_size_vs_oracle(orc, cfg5, G):
     keys = [9000 + 31 * G + b for b in range(G)]
     hidden = cfg.hidden
     out = torch.full((Bm, hidden), float("nan"), dtype=X.dtype, device=DEV)
-    hp.forward(seeds, keys, out)                 # the call the benchmark issues
+    hp.forward(seeds, keys, out)
+    out_fused = torch.full((Bm, hidden), float("nan"), dtype=X.dtype, device=DEV)
+    fused.forward(seeds, keys, out_fused)        # the call the benchmark issues
     torch.cuda.synchronize()
+    assert to_bits(out_fused).tobytes() == to_bits(out).tobytes()
+    assert torch.equal(fused.ids, hp.ids) and torch.equal(fused.remap, hp.remap) and torch.equal(fused.n_uniq, hp.n_uniq)
+    for k in range(1, L):                        # the rows the fused call stores: the next layer's destinations
+        keep = shm.n_dst(k + 1)
+        assert torch.equal(fused.H[k - 1][:keep].view(torch.int16), hp.H[k - 1][:keep].view(torch.int16)), k
+    del fused, out_fused
+    torch.cuda.empty_cache()
 
     # ---- oracle: the G batches one by one (R8: a group's ids are its batches' arrays back to back)
     seeds_np = seeds.cpu().numpy()
