@@ -571,7 +571,8 @@ hopgnn_status hopgnn_sage_bwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_s
  *                               slot_idx are in the merged layout.
  *   fuse_tree, tree_ws          nonzero fuse_tree (GraphSAGE-mean layers over slot trees only: layer_kind 0,
  *                               dedup 0, at least two layers, every fanout but the last at most 64,
- *                               dim and every d_out a multiple of 8; otherwise the flag is ignored): the
+ *                               dim and every d_out whole 16-byte words (multiples of 4 for fp32, of 8 for
+ *                               2-byte types); otherwise the flag is ignored): the
  *                               slot tree's shape is used to leave work out.  A parent's children are
  *                               consecutive slots, so layer k's projection also averages every group
  *                               of siblings of the rows it has just produced (stored values, child

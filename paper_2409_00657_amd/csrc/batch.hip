@@ -23,9 +23,10 @@ struct TreeWs {
 bool tree_applies(const hopgnn_batch_plan* p) {
     const int32_t L = p->n_layers;
     if (!p->fuse_tree || p->layer_kind != 0 || p->dedup || L < 2 || L > kMaxLayers) return false;
-    if (p->dim % 8 != 0) return false;
+    const int32_t per16 = p->dt == HOPGNN_F32 ? 4 : 8;        // elements per 16-byte word: rows move as whole words
+    if (p->dim % per16 != 0) return false;
     for (int32_t k = 0; k < L; ++k)
-        if (p->d_out[k] < 1 || p->d_out[k] % 8 != 0) return false;
+        if (p->d_out[k] < 1 || p->d_out[k] % per16 != 0) return false;
     for (int32_t h = 0; h + 1 < L; ++h)           // groups of siblings on the levels that some layer averages
         if (p->fanouts[h] < 1 || p->fanouts[h] > kTreeMaxFan) return false;
     return true;

@@ -144,6 +144,84 @@ __device__ __forceinline__ void project_epilogue_staged(floatx16 (&acc)[TM][TN],
     (void)sizeof(T);
 }
 
+// With SW the 2-byte kernel multiplies with its operands exchanged (weights as the MFMA's row operand,
+// the activations as its column operand), so a lane of a 32x32 tile holds ONE output row (lane % 32)
+// and 16 of its columns in four runs of four: register i is column 8*(i/4) + 4*(lane/32) + i%4.
+// Four consecutive columns convert with two packed conversions and leave in one 8-byte store,
+// instead of sixteen conversions and sixteen 2-byte stores per tile in the other orientation.
+
+// Plain stores of one wave's TM x TN block (any d_out; OutT = the storage type or float for the
+// unrounded result).
+template <typename Tr, typename OutT, int TM, int TN>
+__device__ __forceinline__ void epilogue16_direct(floatx16 (&acc)[TM][TN], int64_t row0, int32_t col0, int lane,
+                                                  int64_t row_end, int32_t d_out, const typename Tr::store_t* bias,
+                                                  int relu, OutT* out) {
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int64_t row = row0 + tm * 32 + (lane & 31);
+        if (row >= row_end) continue;
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int32_t col = col0 + tn * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                if (col < d_out) {
+                    float x = acc[tm][tn][i] + (bias != nullptr ? Tr::to_f(bias[col]) : 0.f);
+                    if (relu) x = fmaxf(x, 0.f);
+                    if constexpr (sizeof(OutT) == 4) out[row * d_out + col] = x;
+                    else out[row * d_out + col] = Tr::from_f(x);
+                }
+            }
+    }
+}
+
+// One run of four consecutive columns of a tile: bias, activation, rounding, packed.
+template <typename Tr>
+__device__ __forceinline__ uint2 pack_run(const floatx16& a, int q, const typename Tr::store_t* bias, int32_t col,
+                                          int32_t d_out, int relu) {
+    float x[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[e] = a[4 * q + e];
+        if (bias != nullptr && col + e < d_out) x[e] += Tr::to_f(bias[col + e]);
+        if (relu) x[e] = fmaxf(x[e], 0.f);
+    }
+    return make_uint2(Tr::pack2(x[0], x[1]), Tr::pack2(x[2], x[3]));
+}
+
+// 2-byte outputs through a per-wave band of LDS ([32][32*TN + 8] elements) so that rows leave as
+// 128-bit words.  Requires d_out % 8 == 0.  Waves do not share a band, so only this wave's own
+// LDS traffic has to be waited for.
+template <typename Tr, int TM, int TN>
+__device__ __forceinline__ void epilogue16_staged(floatx16 (&acc)[TM][TN], int64_t row0, int32_t col0, int lane,
+                                                  int64_t row_end, int32_t d_out, const typename Tr::store_t* bias,
+                                                  int relu, typename Tr::store_t* out, typename Tr::store_t* band) {
+    constexpr int W = 32 * TN, LDW = W + 8;          // band width in elements, padded row
+    constexpr int WORDS = W / 8;                     // 16-byte words per band row
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int c = tn * 32 + 8 * q + 4 * (lane >> 5);
+                *reinterpret_cast<uint2*>(&band[(lane & 31) * LDW + c]) =
+                    pack_run<Tr>(acc[tm][tn], q, bias, col0 + c, d_out, relu);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < 32 * WORDS / 64; ++j) {
+            const int w = j * 64 + lane;
+            const int r = w / WORDS, c = (w % WORDS) * 8;
+            const int64_t row = row0 + tm * 32 + r;
+            const uint4 v = *reinterpret_cast<const uint4*>(&band[r * LDW + c]);
+            if (row < row_end && col0 + c < d_out)
+                *reinterpret_cast<uint4*>(&out[row * d_out + col0 + c]) = v;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // band is rewritten by the next tm
+    }
+}
+
 // Slot-tree layers: which rows a row tile covers.  Returns false for a tile past the last one.
 template <int BM>
 __device__ __forceinline__ bool tree_tile_rows(const TreeTiles& tt, uint32_t mt, int& lvl, uint32_t& tile_in_level,
@@ -167,7 +245,7 @@ __device__ __forceinline__ bool tree_tile_rows(const TreeTiles& tt, uint32_t mt,
 //     division, one rounding - the arithmetic of the segmented-mean kernel, so the bits are the
 //     ones that kernel would produce from the written rows.
 // LDS: [BM][PW + 16 bytes] staged values, then BM validity bytes.  Needs d_out % (16 / sizeof(T)) == 0.
-template <typename Tr, int BM, int BN, int PW, int TM, int TN, int NT>
+template <typename Tr, int BM, int BN, int PW, int TM, int TN, int NT, bool SW>
 __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds, int wave_row0, int wave_col0, int tid,
                                               int lane, int64_t row0, int64_t row_end, int32_t col0, int32_t d_out,
                                               const typename Tr::store_t* bias, int relu, typename Tr::store_t* out,
@@ -190,17 +268,28 @@ __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds
         for (int tn = 0; tn < TN; ++tn) {
             const int wc = wave_col0 + tn * 32;
             if (wc < c_lo || wc >= c_lo + PW) continue;
-            const int32_t col = col0 + wc + (lane & 31);
-            const float b = (bias != nullptr && col < d_out) ? Tr::to_f(bias[col]) : 0.f;
+            if constexpr (SW) {      // a lane holds runs of four columns of one row (2-byte kernel)
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+                for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float x = acc[tm][tn][i] + b;
-                    if (relu) x = fmaxf(x, 0.f);
-                    const int row = wave_row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
-                    tile[row * LDT + (wc - c_lo) + (lane & 31)] = Tr::from_f(x);
-                }
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = wc + 8 * q + 4 * (lane >> 5);
+                        *reinterpret_cast<uint2*>(&tile[(wave_row0 + tm * 32 + (lane & 31)) * LDT + (c - c_lo)]) =
+                            pack_run<Tr>(acc[tm][tn], q, bias, col0 + c, d_out, relu);
+                    }
+            } else {
+                const int32_t col = col0 + wc + (lane & 31);
+                const float b = (bias != nullptr && col < d_out) ? Tr::to_f(bias[col]) : 0.f;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float x = acc[tm][tn][i] + b;
+                        if (relu) x = fmaxf(x, 0.f);
+                        const int row = wave_row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
+                        tile[row * LDT + (wc - c_lo) + (lane & 31)] = Tr::from_f(x);
+                    }
+            }
         }
         __syncthreads();
         if (store_rows)
@@ -326,6 +415,15 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
         p_self[it] = a_self[it] >= 0 ? Hsrc + a_self[it] : Zero;
         p_mean[it] = a_mean[it] >= 0 ? Mean + a_mean[it] - d_in : Zero;   // indexed by the concatenated k
     }
+    // weight rows by the concatenated k: row k of W_self for k < d_in, row k - d_in of W_neigh after
+    const float* b_self[B_ITEMS];
+    const float* b_neigh[B_ITEMS];
+#pragma unroll
+    for (int it = 0; it < B_ITEMS; ++it) {
+        const int n = col0 + ((it * kProjThreads + tid) % (BN / 4)) * 4;
+        b_self[it] = Wself + n;
+        b_neigh[it] = Wneigh + n - (int64_t)d_in * d_out;
+    }
     auto a_elem = [&](int it, int k) -> float {   // one element of the concatenated row
         if (k < d_in) return a_self[it] >= 0 ? Hsrc[a_self[it] + k] : 0.f;
         if (k < K) return a_mean[it] >= 0 ? Mean[a_mean[it] + (k - d_in)] : 0.f;
@@ -352,8 +450,8 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
             const int k = k0 + i / (BN / 4);
             const int n = col0 + (i % (BN / 4)) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (VEC) {   // d_out % 4 == 0
-                const float* p = (k < d_in ? Wself + (int64_t)k * d_out : Wneigh + (int64_t)(k - d_in) * d_out) + n;
+            if (VEC) {   // d_out % 4 == 0; one multiply-add and selects, no control flow
+                const float* p = (k < d_in ? b_self[it] : b_neigh[it]) + (int64_t)k * d_out;
                 v = *reinterpret_cast<const float4*>((k < K && n < d_out) ? p : Zero);
             } else if (k < K) {
                 const float* p = (k < d_in ? Wself + (int64_t)k * d_out : Wneigh + (int64_t)(k - d_in) * d_out) + n;
@@ -449,7 +547,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     for (int i = 0; i < D - 1; ++i)
         if (t + i < n_tiles) iter(t + i, i);
     if (TREE)
-        tree_epilogue<TrF32, BM, BN, 64, TM, TN, kProjThreads>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
+        tree_epilogue<TrF32, BM, BN, 64, TM, TN, kProjThreads, false>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
                                                                row_end, col0, d_out, bias, relu, out, tt, lvl,
                                                                tile_in_level);
     else
@@ -477,7 +575,7 @@ __device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b
 
 constexpr int kKPad16 = 64;   // Wt rows are zero padded to a multiple of this many k
 
-template <typename Tr, int BM, int BN, int BK, int WM, int WN, int D, bool VEC, bool TREE>
+template <typename Tr, int BM, int BN, int BK, int WM, int WN, int D, bool VEC, bool TREE, bool SW>
 __global__ void __launch_bounds__(64 * WM * WN)
 sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                 const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
@@ -615,21 +713,31 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) acc[tm][tn] = mfma16<Tr>(f.a[tm], f.b[tn], acc[tm][tn]);
+            for (int tn = 0; tn < TN; ++tn)
+                acc[tm][tn] = SW ? mfma16<Tr>(f.b[tn], f.a[tm], acc[tm][tn]) : mfma16<Tr>(f.a[tm], f.b[tn], acc[tm][tn]);
     };
     auto compute = [&](int st) {
-        Frag f0, f1;
-        load_frag(f0, st, 0);
+        if constexpr (TM * TN <= 4) {
+            Frag f0, f1;
+            load_frag(f0, st, 0);
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 32) {
-            if (kk + 16 < BK) load_frag(f1, st, kk + 16);
+            for (int kk = 0; kk < BK; kk += 32) {
+                if (kk + 16 < BK) load_frag(f1, st, kk + 16);
+                __builtin_amdgcn_sched_barrier(kSchedPin);
+                mma(f0);
+                if (kk + 32 < BK) load_frag(f0, st, kk + 32);
+                __builtin_amdgcn_sched_barrier(kSchedPin);
+                if (kk + 16 < BK) mma(f1);
+            }
             __builtin_amdgcn_sched_barrier(kSchedPin);
-            mma(f0);
-            if (kk + 32 < BK) load_frag(f0, st, kk + 32);
-            __builtin_amdgcn_sched_barrier(kSchedPin);
-            if (kk + 16 < BK) mma(f1);
+        } else {      // the largest tile has no registers for a second fragment set
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 16) {
+                Frag f;
+                load_frag(f, st, kk);
+                mma(f);
+            }
         }
-        __builtin_amdgcn_sched_barrier(kSchedPin);
     };
 
     // A ring of D register sets and two LDS stages.  Iteration t: the loads of tile t+D are issued
@@ -658,22 +766,24 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
 #pragma unroll
     for (int i = 0; i < D - 1; ++i)
         if (t + i < n_tiles) iter(t + i, i);
+    const int64_t wrow0 = row0 + wm * (BM / WM);
+    const int32_t wcol0 = col0 + wn * (BN / WN);
     if (TREE) {
-        tree_epilogue<Tr, BM, BN, BN, TM, TN, NT>(acc, lds16, wm * (BM / WM), wn * (BN / WN), tid, lane, row0, row_end, col0,
-                                                  d_out, bias, relu, out, tt, lvl, tile_in_level);
+        tree_epilogue<Tr, BM, BN, BN, TM, TN, NT, SW>(acc, lds16, wm * (BM / WM), wn * (BN / WN), tid, lane, row0, row_end, col0,
+                                                      d_out, bias, relu, out, tt, lvl, tile_in_level);
     } else if (out_f32) {     // `out` is a float array: unrounded result
-        project_epilogue_f32out<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out, bias,
-                                            relu, reinterpret_cast<float*>(out));
+        if constexpr (SW) epilogue16_direct<Tr, float, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, reinterpret_cast<float*>(out));
+        else project_epilogue_f32out<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, reinterpret_cast<float*>(out));
     } else if (VEC && (d_out & 7) == 0) {
         // every wave is past its last LDS read of the tiles: reuse that LDS, one band per wave
         constexpr int BAND = 32 * (32 * TN + 8);
         static_assert((size_t)WM * WN * BAND <= (size_t)2 * (BM + BN) * LD, "epilogue bands exceed the tile LDS");
         typename Tr::store_t* band = reinterpret_cast<typename Tr::store_t*>(lds16) + wave * BAND;
-        project_epilogue_staged<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out,
-                                            bias, relu, out, band);
+        if constexpr (SW) epilogue16_staged<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out, band);
+        else project_epilogue_staged<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out, band);
     } else {
-        project_epilogue<Tr, TM, TN>(acc, row0 + wm * (BM / WM), col0 + wn * (BN / WN), lane, row_end, d_out, bias,
-                                     relu, out);
+        if constexpr (SW) epilogue16_direct<Tr, typename Tr::store_t, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out);
+        else project_epilogue<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out);
     }
 }
 
@@ -747,9 +857,13 @@ static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc
     using T = typename Tr::store_t;
     constexpr size_t lds = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(uint16_t);
     static_assert((size_t)BM * (BN + 8) * 2 + BM <= lds, "the staged tile of a slot-tree layer must fit the loop's LDS");
-    auto kern = tree != nullptr ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, true>
-                : vec           ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, false>
-                                : sage_project_16<Tr, BM, BN, BK, WM, WN, D, false, false>;
+    // Exchanged operands pay where rounding is expensive: bf16 (packed hardware conversion of two
+    // values instead of an integer rounding sequence per value; measured -11 % on the 4096-seed bf16
+    // workload's first layer).  fp16 converts in one instruction either way and measured 5 % slower.
+    const bool sw = Tr::kDt == HOPGNN_BF16;
+    auto kern = tree != nullptr ? (sw ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, true, true> : sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, true, false>)
+                : vec           ? (sw ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, false, true> : sage_project_16<Tr, BM, BN, BK, WM, WN, D, true, false, false>)
+                                : (sw ? sage_project_16<Tr, BM, BN, BK, WM, WN, D, false, false, true> : sage_project_16<Tr, BM, BN, BK, WM, WN, D, false, false, false>);
     if (lds > 64 * 1024) {   // above the default limit the size has to be opted into
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
@@ -788,7 +902,7 @@ hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc,
     bool vec = d_in % per16 == 0 && aligned(Hsrc, 16) && aligned(mean, 16);
     if (dt == HOPGNN_F32) vec = vec && d_out % per16 == 0 && aligned(W_self, 16) && aligned(W_neigh, 16);
     if (tree != nullptr) {      // the slot-tree kernels are built for the vector path only
-        if (!vec || out_f32 || n_rows_dev != nullptr || d_out % 8 != 0 || !aligned(out, 16) ||
+        if (!vec || out_f32 || n_rows_dev != nullptr || d_out % per16 != 0 || !aligned(out, 16) ||
             (tree->mean_next != nullptr && !aligned(tree->mean_next, 16)) || tree->n_levels < 1 ||
             tree->n_levels > kMaxLayers + 1)
             return HOPGNN_EINVAL;

@@ -13,6 +13,9 @@ __device__ __forceinline__ void lds_barrier() {
 
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 halfx2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
@@ -37,6 +40,16 @@ struct TrBF16 {
         u += 0x7FFFu + ((u >> 16) & 1u);
         return (uint16_t)(u >> 16);
     }
+    // two values rounded to nearest even and packed (a in the low half): the hardware's packed
+    // conversion, same bits as from_f for every finite value and infinity
+    __device__ static __forceinline__ uint32_t pack2(float a, float b) {
+        union {
+            bf16x2 v;
+            uint32_t u;
+        } r;
+        r.v = __builtin_convertvector(floatx2{a, b}, bf16x2);
+        return r.u;
+    }
 };
 
 struct TrF16 {
@@ -45,6 +58,14 @@ struct TrF16 {
     static constexpr hopgnn_dtype kDt = HOPGNN_F16;
     __device__ static __forceinline__ float to_f(_Float16 h) { return (float)h; }
     __device__ static __forceinline__ _Float16 from_f(float x) { return (_Float16)x; }
+    __device__ static __forceinline__ uint32_t pack2(float a, float b) {
+        union {
+            halfx2 v;
+            uint32_t u;
+        } r;
+        r.v = __builtin_convertvector(floatx2{a, b}, halfx2);
+        return r.u;
+    }
 };
 
 template <typename Tr>
@@ -300,7 +321,7 @@ constexpr int kTreeMaxFan = 64;          // a group of siblings must fit the sma
 // tree (may be NULL): the rows are the slots of a slot tree; rows are tiled level by level in whole
 // groups of siblings, the deepest level's rows are not written when tree->mean_next is given, and
 // that array receives the next layer's neighbour means (same bits as the segmented-mean kernel
-// would give over the stored rows).  Needs d_out % 8 == 0, every fan <= kTreeMaxFan, no n_rows_dev.
+// would give over the stored rows).  Needs rows of whole 16-byte words, every fan <= kTreeMaxFan, no n_rows_dev.
 hopgnn_status project_dispatch(hopgnn_dtype dt, hipStream_t s, const void* Hsrc, const int32_t* self_idx,
                                const void* agg, const void* W_self, const void* W_neigh, const uint16_t* Wt,
                                int32_t KP, const void* bias, int64_t n_dst, int32_t d_in, int32_t k_total,

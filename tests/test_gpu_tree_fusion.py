@@ -16,7 +16,7 @@ DEV = "cuda:0"
 CASES = [
     # fanouts, seeds per batch, group, merge, dtype, feature dim, hidden
     ([10, 10], 300, 1, False, torch.float32, 128, 128),       # 64-row tiles, 6 groups of 10 per tile
-    ([15, 10, 5], 120, 1, False, torch.float32, 104, 256),    # three layers; 128-row tiles on layer 1
+    ([15, 10, 5], 120, 1, False, torch.float32, 100, 256),    # three layers; 128-row tiles on layer 1; 400-byte rows
     ([25, 10], 500, 1, False, torch.bfloat16, 256, 256),      # 256-row tiles: 10 groups of 25
     ([10, 10, 10], 64, 4, True, torch.float16, 128, 512),     # a merged group, N = 512
     ([10, 10, 10], 40, 3, False, torch.float16, 64, 64),      # batches of a group run one after the other
@@ -74,7 +74,7 @@ def test_the_flag_is_ignored_where_the_tree_path_does_not_apply():
     from paper_2409_00657_amd.pipeline import HotPath
     g = synth.rmat_graph(11, 8.0, seed=2, device=DEV)
     n = g.n_vertices
-    for fan, d, hidden in (([70, 2], 16, 16), ([5], 16, 16), ([5, 5], 16, 20), ([5, 5], 12, 16)):
+    for fan, d, hidden in (([70, 2], 16, 16), ([5], 16, 16), ([5, 5], 16, 18), ([5, 5], 10, 16)):
         X = synth.features(n, d, torch.float32, device=DEV)
         W = synth.sage_weights(d, hidden, len(fan), torch.float32, device=DEV)
         a = HotPath(g.offsets, g.indices, X, W, 30, fan, fuse_tree=True)
