@@ -9,7 +9,11 @@
 //          whole batches (sample -> pregather -> gather -> layers) on a row-conditional R-MAT
 //          graph (0.57, 0.19, 0.19, 0.05) built on the host, fresh seeds and key per batch
 //   cbench copy <bytes> <iters>      plain 128-bit copy kernel of known size, to calibrate
-//                                    the profiler's FETCH_SIZE / WRITE_SIZE counters
+//                                    the profiler's FETCH_SIZE / WRITE_SIZE counters; also the
+//                                    copy rate this machine reaches (bytes read + written per second)
+//   cbench mfma <f32|bf16|f16> <iters>   register-resident MFMA loop (no memory traffic): the
+//                                    matrix rate this machine reaches with the instruction the
+//                                    projection kernels use, against the published peak
 //
 // Inputs are pseudo-random with the right shapes; results are not checked here (the
 // parity tests do that).  Prints the mean time per call measured with HIP events.
@@ -33,6 +37,42 @@
             exit(1);                                                               \
         }                                                                          \
     } while (0)
+
+typedef float cb_floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 cb_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 cb_halfx8 __attribute__((ext_vector_type(8)));
+
+// Four independent accumulators per wave, operands in registers: nothing but MFMA issue.
+// kind 0: v_mfma_f32_32x32x2_f32, 1: v_mfma_f32_32x32x16_bf16, 2: v_mfma_f32_32x32x16_f16.
+template <int KIND>
+__global__ void __launch_bounds__(256) mfma_loop(float* __restrict__ sink, int n_rounds) {
+    cb_floatx16 acc[4];
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    const float a32 = 1.0f + threadIdx.x * 1e-6f, b32 = 0.5f;
+    cb_bf16x8 a16b, b16b;
+    cb_halfx8 a16h, b16h;
+    for (int i = 0; i < 8; ++i) {
+        a16b[i] = (__bf16)(1.0f + i * 0.001f);
+        b16b[i] = (__bf16)0.5f;
+        a16h[i] = (_Float16)(1.0f + i * 0.001f);
+        b16h[i] = (_Float16)0.5f;
+    }
+    for (int r = 0; r < n_rounds; ++r) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (KIND == 0) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a32, b32, acc[j], 0, 0, 0);
+                else if (KIND == 1) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a16b, b16b, acc[j], 0, 0, 0);
+                else acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a16h, b16h, acc[j], 0, 0, 0);
+            }
+    }
+    float s = 0.f;
+    for (int j = 0; j < 4; ++j)
+        for (int i = 0; i < 16; ++i) s += acc[j][i];
+    if (s == 123.456f) sink[threadIdx.x] = s;      // keeps the loop alive; never true for these operands
+}
 
 __global__ void __launch_bounds__(256) plain_copy(const uint4* __restrict__ a, uint4* __restrict__ b, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -83,7 +123,7 @@ static std::vector<uint8_t> random_table(size_t n, hopgnn_dtype dt) {
 }
 
 template <typename F>
-static void time_it(const char* what, int iters, F&& f) {
+static double time_it(const char* what, int iters, F&& f) {
     hipEvent_t e0, e1;
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
@@ -96,6 +136,7 @@ static void time_it(const char* what, int iters, F&& f) {
     float ms;
     CK(hipEventElapsedTime(&ms, e0, e1));
     printf("%s: %.2f us per call (%d calls)\n", what, ms * 1e3f / iters, iters);
+    return (double)ms * 1e3 / iters;
 }
 
 int main(int argc, char** argv) {
@@ -327,11 +368,28 @@ int main(int argc, char** argv) {
         CK(hipMalloc(&b, bytes));
         CK(hipMemset(a, 1, bytes));
         const int64_t n = bytes / 16;
-        time_it("plain_copy", iters, [&] {
+        const double us = time_it("plain_copy", iters, [&] {
             hipLaunchKernelGGL(plain_copy, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, 0,
                                static_cast<const uint4*>(a), static_cast<uint4*>(b), n);
         });
+        printf("copy rate: %.1f GB/s read + written\n", 2.0 * bytes / us * 1e-3);
         printf("bytes read = bytes written = %lld\n", (long long)bytes);
+    } else if (mode == "mfma" && argc >= 4) {
+        const std::string dt = argv[2];
+        const int iters = atoi(argv[3]);
+        const int kind = dt == "f32" ? 0 : dt == "bf16" ? 1 : 2;
+        const int n_rounds = 2048, blocks = 256 * 8;            // 8 workgroups of 4 waves per CU
+        float* sink;
+        CK(hipMalloc(&sink, 1024));
+        auto launch = [&] {
+            if (kind == 0) hipLaunchKernelGGL(mfma_loop<0>, dim3(blocks), dim3(256), 0, 0, sink, n_rounds);
+            else if (kind == 1) hipLaunchKernelGGL(mfma_loop<1>, dim3(blocks), dim3(256), 0, 0, sink, n_rounds);
+            else hipLaunchKernelGGL(mfma_loop<2>, dim3(blocks), dim3(256), 0, 0, sink, n_rounds);
+        };
+        const double us = time_it("mfma_loop", iters, launch);
+        const double flops_per_mfma = kind == 0 ? 32.0 * 32 * 2 * 2 : 32.0 * 32 * 16 * 2;
+        const double flops = (double)blocks * 4 /*waves*/ * n_rounds * 16 /*MFMAs per round*/ * flops_per_mfma;
+        printf("%s MFMA loop: %.1f TFLOP/s (%.3g flop in %.1f us)\n", dt.c_str(), flops / us * 1e-6, flops, us);
     } else {
         fprintf(stderr, "see the header of cbench.cpp for usage\n");
         return 1;

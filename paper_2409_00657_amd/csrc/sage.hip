@@ -268,14 +268,26 @@ __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds
         for (int tn = 0; tn < TN; ++tn) {
             const int wc = wave_col0 + tn * 32;
             if (wc < c_lo || wc >= c_lo + PW) continue;
-            if constexpr (SW) {      // a lane holds runs of four columns of one row (2-byte kernel)
+            if constexpr (SW) {      // a lane holds runs of four columns of one row (operands exchanged)
 #pragma unroll
                 for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int c = wc + 8 * q + 4 * (lane >> 5);
-                        *reinterpret_cast<uint2*>(&tile[(wave_row0 + tm * 32 + (lane & 31)) * LDT + (c - c_lo)]) =
-                            pack_run<Tr>(acc[tm][tn], q, bias, col0 + c, d_out, relu);
+                        T* dst = &tile[(wave_row0 + tm * 32 + (lane & 31)) * LDT + (c - c_lo)];
+                        if constexpr (sizeof(T) == 4) {
+                            float4 v;
+                            float* x = &v.x;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                x[e] = acc[tm][tn][4 * q + e];
+                                if (bias != nullptr && col0 + c + e < d_out) x[e] += Tr::to_f(bias[col0 + c + e]);
+                                if (relu) x[e] = fmaxf(x[e], 0.f);
+                            }
+                            *reinterpret_cast<float4*>(dst) = v;
+                        } else {
+                            *reinterpret_cast<uint2*>(dst) = pack_run<Tr>(acc[tm][tn], q, bias, col0 + c, d_out, relu);
+                        }
                     }
             } else {
                 const int32_t col = col0 + wc + (lane & 31);
@@ -501,8 +513,9 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
             for (int tm = 0; tm < TM; ++tm) {
                 const float av = i == 0 ? f.a[tm].x : i == 1 ? f.a[tm].y : i == 2 ? f.a[tm].z : f.a[tm].w;
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[i][tn], acc[tm][tn], 0, 0, 0);
+                for (int tn = 0; tn < TN; ++tn)   // slot-tree layers: operands exchanged, a lane then holds runs of one row
+                    acc[tm][tn] = TREE ? __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[i][tn], av, acc[tm][tn], 0, 0, 0)
+                                       : __builtin_amdgcn_mfma_f32_32x32x2f32(av, f.b[i][tn], acc[tm][tn], 0, 0, 0);
             }
     };
     auto compute = [&](int st) {
@@ -547,7 +560,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     for (int i = 0; i < D - 1; ++i)
         if (t + i < n_tiles) iter(t + i, i);
     if (TREE)
-        tree_epilogue<TrF32, BM, BN, 64, TM, TN, kProjThreads, false>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
+        tree_epilogue<TrF32, BM, BN, BN, TM, TN, kProjThreads, true>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
                                                                row_end, col0, d_out, bias, relu, out, tt, lvl,
                                                                tile_in_level);
     else
@@ -833,7 +846,7 @@ static hopgnn_status launch_project_f32(bool vec, hipStream_t s, const void* Hsr
     auto o = static_cast<float*>(out);
     auto z = static_cast<const float*>(zero);
     constexpr size_t lds_loop = (size_t)2 * (BM * (BK + 4) + BK * (BN + 4)) * sizeof(float);
-    constexpr size_t lds_tree = (size_t)BM * (64 + 4) * sizeof(float) + BM;     // staged tile + validity bytes
+    constexpr size_t lds_tree = (size_t)BM * (BN + 4) * sizeof(float) + BM;     // staged tile + validity bytes
     const size_t lds = tree != nullptr && lds_tree > lds_loop ? lds_tree : lds_loop;
     auto kern = tree != nullptr ? sage_project_f32<BM, BN, BK, D, true, true>
                 : vec           ? sage_project_f32<BM, BN, BK, D, true, false>
