@@ -444,7 +444,11 @@ hopgnn_status hopgnn_gat_fwd_dev(const void *Hsrc, hopgnn_dtype dt, int64_t n_sr
  *               dHsrc[idx[e]] += (dZ[r] W_neigh^T) / c_r  for every valid entry e of row r
  *
  * dt       type of Hsrc, W_self, W_neigh and out_fwd (fp32, bf16 or fp16).  Every gradient is
- *          fp32 whatever dt is; the neighbour mean is rounded to dt as in the forward call.
+ *          fp32 in memory whatever dt is; the neighbour mean is rounded to dt as in the forward
+ *          call.  With a 2-byte dt the two matrix products (weight gradient, input gradient) take
+ *          the masked incoming gradient rounded to dt and accumulate in fp32 (2-byte matrix
+ *          instructions; feature widths that are not multiples of 8 use fp32 products of the
+ *          widened values instead); the bias gradient sums the fp32 values.
  * out_fwd  DEVICE [n_dst x d_out] of type dt, the stored forward output (decides the ReLU
  *          mask); may be NULL when relu == 0.
  * dOut     DEVICE [n_dst x d_out] fp32.

@@ -573,19 +573,6 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
 // as 128-bit words: A [BM][BK+8], B [BN][BK+8] (row stride 80 bytes: conflict free).
 // B comes from Wt, the transposed weights [NP][KP] (k contiguous, zero padded to whole
 // tiles) that the mean kernel's side job writes into the workspace.
-template <typename Tr>
-__device__ __forceinline__ floatx16 mfma16(const uint4& a, const uint4& b, floatx16 c);
-template <>
-__device__ __forceinline__ floatx16 mfma16<TrBF16>(const uint4& a, const uint4& b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a),
-                                                   *reinterpret_cast<const bf16x8*>(&b), c, 0, 0, 0);
-}
-template <>
-__device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const halfx8*>(&a),
-                                                  *reinterpret_cast<const halfx8*>(&b), c, 0, 0, 0);
-}
-
 constexpr int kKPad16 = 64;   // Wt rows are zero padded to a multiple of this many k
 
 template <typename Tr, int BM, int BN, int BK, int WM, int WN, int D, bool VEC, bool TREE, bool SW>

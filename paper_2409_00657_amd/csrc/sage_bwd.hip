@@ -10,8 +10,11 @@
 //   dHsrc[self_idx[r]] += dXs[r];  dHsrc[idx[e]] += dM[r] / c_r          bwd_scatter
 //
 // Hsrc, the weights and the stored forward output are in the activation type (fp32, bf16 or
-// fp16); gradients (dOut, gW, gbias, dHsrc) are always fp32 and the contractions run on the fp32
-// MFMA with 2-byte operands widened on their way into LDS.  The weight gradient contracts over the destination
+// fp16); gradients (dOut, gW, gbias, dHsrc) are always fp32 in memory.  For fp32 activations the
+// contractions run on the fp32 MFMA.  For 2-byte activations they run on the 2-byte MFMA with fp32
+// accumulators, dZ rounded to the activation type on its way into LDS (shapes whose rows are not
+// whole 16-byte runs take the fp32 MFMA with the 2-byte operands widened instead); the bias gradient
+// always sums fp32 values.  The weight gradient contracts over the destination
 // rows, which are split over workgroups; the partial tiles are summed in split order by a
 // second kernel, so gW/gbias are bit-stable from run to run.  dHsrc uses float atomic adds:
 // bit-stable when a source row receives at most two contributions (always the case for the
@@ -260,6 +263,198 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
     }
 }
 
+// The same tile for 2-byte activations on v_mfma_f32_32x32x16_{bf16,f16} (fp32 accumulators).  Both
+// operands of that instruction hold 8 consecutive values of the contraction index per lane, and
+// the contraction index here is the row: the operands are columns of the staged chunk.  The chunk
+// (32 rows: two MFMA steps) sits in LDS row-major as 2-byte values - A as stored, dZ rounded to the
+// activation type on its way in (the mixed-precision convention: products of two 2-byte values,
+// fp32 sums) - and a lane assembles its operand from 8 two-byte reads down a column; lanes of a
+// half-wave read 32 consecutive columns of one row, the two halves rows 8 apart, whose banks the
+// row stride of 128 + 4 elements keeps apart.  The column sums of dZ (the bias gradient) are taken
+// from the fp32 values before rounding.  Workgroups are numbered so that the tiles of one row
+// split run on one XCD at about the same time (workgroup b goes to XCD b % 8): the split's rows
+// then come out of that XCD's L2 for every tile but the first.
+// Requires d_in % 8 == 0 and d_out % 4 == 0 and 16-byte aligned operands (the caller checks).
+constexpr int kG16Rows = 32;
+constexpr int kG16Ld = kGradTile + 4;       // in 2-byte elements
+
+template <typename Tr, bool MASK>
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
+                  const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ,
+                  const typename Tr::store_t* __restrict__ OutFwd, int64_t n_dst, int32_t d_in, int32_t d_out,
+                  int32_t rows_per_split, uint32_t tiles_n, uint32_t n_tiles, int32_t n_splits,
+                  float* __restrict__ partial, float* __restrict__ bias_partial,
+                  const int64_t* __restrict__ n_rows_dev) {
+    using T = typename Tr::store_t;
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][kG16Rows][kG16Ld];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kG16Rows][kG16Ld];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, l32 = lane & 31;
+    const int wk = wave >> 1, wn = wave & 1;
+    const int K = 2 * d_in;
+    // workgroup -> (tile, split): XCD x takes the splits x, x + 8, ... and runs each split's tiles back to back
+    const uint32_t xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
+    const uint32_t tile = seq % n_tiles;
+    const int32_t split = (int32_t)((seq / n_tiles) * 8u + xcd);
+    if (split >= n_splits) return;             // uniform over the workgroup
+    const uint32_t tk = tile / tiles_n, tn = tile % tiles_n;
+    const int64_t n_rows = n_rows_dev != nullptr && *n_rows_dev < n_dst ? *n_rows_dev : n_dst;
+    const int64_t r0 = (int64_t)split * rows_per_split;
+    int64_t r1 = r0 + rows_per_split < n_rows ? r0 + rows_per_split : n_rows;
+    r1 = r1 > r0 ? r1 : r0;
+    const int n_chunks = (int)((r1 - r0 + kG16Rows - 1) / kG16Rows);
+
+    // this thread's part of every chunk: A rows ar, ar + 16 (8 elements each), dZ rows br + 8 i (4 each)
+    const int ar = tid >> 4, ac = (tid & 15) * 8;
+    const int br = tid >> 5, bc = (tid & 31) * 4;
+    const int ka = (int)tk * kGradTile + ac;
+    const int nb = (int)tn * kGradTile + bc;
+    const bool ka_ok = ka < K, nb_ok = nb < d_out;
+    const int nbc = nb_ok ? nb : 0;
+    // this thread's A columns come from the self rows or from the means, the same for every chunk
+    const bool a_self = ka < d_in;
+    const T* a_base = a_self ? Hsrc + ka : Mean + (ka_ok ? ka - d_in : 0);
+
+    auto self_of = [&](int chunk, int i) -> int32_t {
+        int64_t r = r0 + (int64_t)chunk * kG16Rows + ar + 16 * i;
+        r = r < n_dst ? r : n_dst - 1;
+        return self_idx != nullptr ? self_idx[r] : (int32_t)r;
+    };
+    // One chunk's loads in flight.  Every load is unconditional from a clamped, in-bounds address;
+    // what must not count is zeroed when the chunk goes to LDS.
+    struct Frag {
+        uint4 a[2];
+        float4 b[4];
+        uint2 o[4];
+        bool a_ok[2];
+    };
+    auto load = [&](int chunk, const int32_t (&sidx)[2], Frag& f) {
+        const int64_t base = r0 + (int64_t)chunk * kG16Rows;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            int64_t r = base + ar + 16 * i;
+            f.a_ok[i] = r < r1 && ka_ok && (!a_self || sidx[i] >= 0);
+            r = r < n_dst ? r : n_dst - 1;
+            const int64_t srow = sidx[i] > 0 ? sidx[i] : 0;
+            f.a[i] = *reinterpret_cast<const uint4*>(a_base + (a_self ? srow : r) * d_in);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int64_t r = base + br + 8 * i;
+            r = r < n_dst ? r : n_dst - 1;
+            f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + nbc);
+            if (MASK) f.o[i] = *reinterpret_cast<const uint2*>(OutFwd + r * d_out + nbc);
+        }
+    };
+    float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+    auto store = [&](int chunk, const Frag& f, int buf) {
+        const int64_t base = r0 + (int64_t)chunk * kG16Rows;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint4 v = f.a_ok[i] ? f.a[i] : make_uint4(0u, 0u, 0u, 0u);
+            uint2* dst = reinterpret_cast<uint2*>(&As[buf][ar + 16 * i][ac]);
+            dst[0] = make_uint2(v.x, v.y);
+            dst[1] = make_uint2(v.z, v.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = base + br + 8 * i < r1 && nb_ok;
+            float bv[4] = {f.b[i].x, f.b[i].y, f.b[i].z, f.b[i].w};
+            if (MASK) {
+                union { uint2 v; T e[4]; } o;
+                o.v = f.o[i];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bv[e] = Tr::to_f(o.e[e]) > 0.f ? bv[e] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                bv[e] = ok ? bv[e] : 0.f;
+                colsum[e] += bv[e];
+            }
+            *reinterpret_cast<uint2*>(&Bs[buf][br + 8 * i][bc]) = make_uint2(Tr::pack2(bv[0], bv[1]), Tr::pack2(bv[2], bv[3]));
+        }
+    };
+    // 8 values down a column, rows row0 .. row0 + 7, as one MFMA operand
+    auto column8 = [&](const uint16_t (&S)[kG16Rows][kG16Ld], int row0, int col) -> uint4 {
+        union { uint4 v; uint16_t e[8]; } u;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) u.e[e] = S[row0 + e][col];
+        return u.v;
+    };
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // The next chunk's loads are in flight while one is multiplied, into the registers the current chunk
+    // left when it went to LDS (chunks past the end: clamped rows, masked, never multiplied); the self
+    // indices run one chunk ahead of the loads.  (Two chunks in flight cost a resident workgroup per
+    // CU in registers and measured slower.)
+    Frag f;
+    int32_t s_nxt[2];
+    {
+        const int32_t s_cur[2] = {self_of(0, 0), self_of(0, 1)};
+        load(0, s_cur, f);
+        s_nxt[0] = self_of(1, 0);
+        s_nxt[1] = self_of(1, 1);
+    }
+    store(0, f, 0);
+    lds_barrier();
+    for (int c = 0; c < n_chunks; ++c) {
+        const int buf = c & 1;
+        const int32_t s_cur[2] = {s_nxt[0], s_nxt[1]};
+        load(c + 1, s_cur, f);
+        s_nxt[0] = self_of(c + 2, 0);
+        s_nxt[1] = self_of(c + 2, 1);
+#pragma unroll
+        for (int kk = 0; kk < kG16Rows; kk += 16) {
+            const uint4 a0 = column8(As[buf], kk + 8 * g, wk * 64 + l32), a1 = column8(As[buf], kk + 8 * g, wk * 64 + 32 + l32);
+            const uint4 b0 = column8(Bs[buf], kk + 8 * g, wn * 64 + l32), b1 = column8(Bs[buf], kk + 8 * g, wn * 64 + 32 + l32);
+            acc[0][0] = mfma16<Tr>(a0, b0, acc[0][0]);
+            acc[0][1] = mfma16<Tr>(a0, b1, acc[0][1]);
+            acc[1][0] = mfma16<Tr>(a1, b0, acc[1][0]);
+            acc[1][1] = mfma16<Tr>(a1, b1, acc[1][1]);
+        }
+        store(c + 1, f, buf ^ 1);
+        lds_barrier();
+    }
+
+    const int k0 = (int)tk * kGradTile + wk * 64, n0 = (int)tn * kGradTile + wn * 64;
+    float* P = partial + (int64_t)split * K * d_out;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + j * 32 + l32;
+            if (n >= d_out) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int kk = k0 + i * 32 + 8 * (e / 4) + 4 * g + (e & 3);
+                if (kk < K) P[(int64_t)kk * d_out + n] = acc[i][j][e];
+            }
+        }
+    if (bias_partial != nullptr && tk == 0) {
+        // the eight row groups' sums of every column, added in a fixed order (the staging tiles are free:
+        // the loop's last barrier is behind every read of them)
+        float* cs = reinterpret_cast<float*>(&As[0][0][0]);      // [8][128]
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[br * kGradTile + bc + e] = colsum[e];
+        lds_barrier();
+        if (tid < kGradTile) {
+            float t = 0.f;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) t += cs[q * kGradTile + tid];
+            const int n = (int)tn * kGradTile + tid;
+            if (n < d_out) bias_partial[(int64_t)split * d_out + n] = t;
+        }
+    }
+}
+
 // gW += sum over the splits of the partial tiles; same for the bias.  A workgroup owns 64
 // consecutive elements; wave q sums the splits q, q+4, q+8, ... in that order and the four
 // sums are combined as (s0 + s1) + (s2 + s3): a fixed order, so the result is bit-stable.
@@ -382,6 +577,93 @@ bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restr
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b.y, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b.z, acc, 0, 0, 0);
             acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b.w, acc, 0, 0, 0);
+        }
+    }
+    const int col = col0 + wn * 32 + l32;
+    if (col < N) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t row = row0 + wm * 32 + 8 * (i / 4) + 4 * g + (i & 3);
+            if (row < n_dst) D[row * N + col] = acc[i];
+        }
+    }
+}
+
+// The same product for 2-byte activations on v_mfma_f32_32x32x16_{bf16,f16}: the weights as stored,
+// dZ rounded to the activation type on its way into LDS; both tiles [64][32 + 8] 2-byte values with
+// the contraction index contiguous, read as 128-bit words.
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_input_grad16(const float* __restrict__ dZ, const typename Tr::store_t* __restrict__ Wself,
+                 const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst_cap, int32_t d_in, int32_t d_out,
+                 float* __restrict__ D, const int64_t* __restrict__ n_rows_dev) {
+    using T = typename Tr::store_t;
+    constexpr int BM = 64, BN = 64, BK = 32, LD = BK + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM][LD];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[BN][LD];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = lane >> 5, l32 = lane & 31;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t n_dst = n_rows_dev != nullptr && *n_rows_dev < n_dst_cap ? *n_rows_dev : n_dst_cap;
+    const int64_t row0 = (int64_t)blockIdx.x * BM;
+    if (row0 >= n_dst) return;                 // uniform over the workgroup
+    const int col0 = blockIdx.y * BN;
+    const int N = 2 * d_in;
+    const bool vec = (d_out & 7) == 0;
+
+    // one 8-element item of each tile per thread: row tid/4, k (tid%4)*8 .. +7
+    const int lr = tid >> 2, lk = (tid & 3) * 8;
+    const int64_t ar = row0 + lr;
+    const int bj = col0 + lr;
+    const float* arow = ar < n_dst ? dZ + ar * d_out : nullptr;
+    const T* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
+                           : nullptr;
+    struct Item {
+        float4 a[2];
+        uint4 b;
+    };
+    auto load = [&](int kq, Item& it) {
+        it.a[0] = it.a[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+        it.b = make_uint4(0u, 0u, 0u, 0u);
+        if (vec && kq + 7 < d_out) {
+            if (arow != nullptr) {
+                it.a[0] = *reinterpret_cast<const float4*>(arow + kq);
+                it.a[1] = *reinterpret_cast<const float4*>(arow + kq + 4);
+            }
+            if (brow != nullptr) it.b = *reinterpret_cast<const uint4*>(brow + kq);
+        } else {
+            float av[8];
+            union { uint4 v; T e[8]; } u;
+            u.v = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                av[e] = arow != nullptr && kq + e < d_out ? arow[kq + e] : 0.f;
+                if (brow != nullptr && kq + e < d_out) u.e[e] = brow[kq + e];
+            }
+            it.a[0] = make_float4(av[0], av[1], av[2], av[3]);
+            it.a[1] = make_float4(av[4], av[5], av[6], av[7]);
+            it.b = u.v;
+        }
+    };
+
+    floatx16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    const int n_tiles = (d_out + BK - 1) / BK;
+    Item it;
+    load(lk, it);
+    for (int t = 0; t < n_tiles; ++t) {
+        __syncthreads();
+        *reinterpret_cast<uint4*>(&As[lr][lk]) = make_uint4(Tr::pack2(it.a[0].x, it.a[0].y), Tr::pack2(it.a[0].z, it.a[0].w),
+                                                            Tr::pack2(it.a[1].x, it.a[1].y), Tr::pack2(it.a[1].z, it.a[1].w));
+        *reinterpret_cast<uint4*>(&Bs[lr][lk]) = it.b;
+        __syncthreads();
+        if (t + 1 < n_tiles) load((t + 1) * BK + lk, it);
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            const uint4 a = *reinterpret_cast<const uint4*>(&As[wm * 32 + l32][kk + 8 * g]);
+            const uint4 b = *reinterpret_cast<const uint4*>(&Bs[wn * 32 + l32][kk + 8 * g]);
+            acc = mfma16<Tr>(a, b, acc);
         }
     }
     const int col = col0 + wn * 32 + l32;
@@ -587,11 +869,26 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
     const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16) && aligned(mean, 16) &&
                      (!fuse_mask || aligned(out_fwd, 16));
-    auto grad_kernel = fuse_mask ? (vec ? bwd_weight_grad<Tr, true, true> : bwd_weight_grad<Tr, false, true>)
-                                 : (vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>);
-    hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
-                       static_cast<const T*>(Hsrc), self_idx, mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out,
-                       L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+    bool on16 = false;
+    if constexpr (sizeof(T) == 2) {
+        // the 2-byte matrix instructions, when every 8-element run of A and 4-element run of dZ is whole
+        on16 = vec && d_in % 8 == 0;
+        if (on16) {
+            auto k16 = fuse_mask ? bwd_weight_grad16<Tr, true> : bwd_weight_grad16<Tr, false>;
+            const uint32_t n_tiles = tiles_k * tiles_n;
+            const uint32_t splits8 = (uint32_t)ceil_div(L.n_splits, 8) * 8u;
+            hipLaunchKernelGGL(k16, dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s, static_cast<const T*>(Hsrc), self_idx,
+                               mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out, L.rows_per_split, tiles_n,
+                               n_tiles, L.n_splits, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+        }
+    }
+    if (!on16) {
+        auto grad_kernel = fuse_mask ? (vec ? bwd_weight_grad<Tr, true, true> : bwd_weight_grad<Tr, false, true>)
+                                     : (vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>);
+        hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
+                           static_cast<const T*>(Hsrc), self_idx, mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out,
+                           L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+    }
     HOPGNN_LAUNCH_CHECK();
     const int64_t red = (int64_t)2 * d_in * d_out + d_out;
     hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
@@ -601,9 +898,12 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     if (dHsrc != nullptr && n_src > 0) {
         const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
         if (gy > 65535) return HOPGNN_ERANGE;
-        hipLaunchKernelGGL(bwd_input_grad<Tr>, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0,
-                           s, dZ, static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D,
-                           n_dst_dev);
+        auto in_kernel = bwd_input_grad<Tr>;
+        if constexpr (sizeof(T) == 2) {
+            if (aligned(dZ, 16) && aligned(W_self, 16) && aligned(W_neigh, 16)) in_kernel = bwd_input_grad16<Tr>;
+        }
+        hipLaunchKernelGGL(in_kernel, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0, s, dZ,
+                           static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D, n_dst_dev);
         HOPGNN_LAUNCH_CHECK();
         const int group = mean_group(d_in);
         if (slot_first >= 0)

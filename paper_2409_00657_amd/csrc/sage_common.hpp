@@ -74,6 +74,21 @@ union Pack16 {
     typename Tr::store_t e[Tr::kPer16];
 };
 
+// One v_mfma_f32_32x32x16_{bf16,f16}: lane l holds 8 consecutive contraction values of row (A) or
+// column (B) l%32, group l/32; the accumulators are fp32.
+template <typename Tr>
+__device__ __forceinline__ floatx16 mfma16(const uint4& a, const uint4& b, floatx16 c);
+template <>
+__device__ __forceinline__ floatx16 mfma16<TrBF16>(const uint4& a, const uint4& b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(&a),
+                                                   *reinterpret_cast<const bf16x8*>(&b), c, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ floatx16 mfma16<TrF16>(const uint4& a, const uint4& b, floatx16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(*reinterpret_cast<const halfx8*>(&a),
+                                                  *reinterpret_cast<const halfx8*>(&b), c, 0, 0, 0);
+}
+
 // ------------------------------------------------------------ segmented mean --
 
 // Side job of the mean kernels for 2-byte types: the projection wants the weights with k

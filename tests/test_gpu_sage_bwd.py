@@ -133,9 +133,13 @@ def test_backward_chain_on_a_sampled_batch(hb, orc):
 
 
 @pytest.mark.parametrize("dt", [torch.bfloat16, torch.float16])
-@pytest.mark.parametrize("shape", [(1500, 1111, 128, 128, 12), (4000, 777, 100, 256, 16), (300, 65, 7, 5, 4)])
+@pytest.mark.parametrize("shape", [(1500, 1111, 128, 128, 12), (4000, 777, 100, 256, 16), (300, 65, 7, 5, 4),
+                                   (6000, 5000, 136, 132, 9), (700, 2100, 512, 64, 5), (900, 300, 8, 260, 3)])
 def test_sage_bwd_two_byte_activations_vs_oracle(hb, orc, dt, shape):
-    """bf16 / fp16 rows, weights and stored forward output; fp32 gradients in and out."""
+    """bf16 / fp16 rows, weights and stored forward output; fp32 gradients in and out.  The shapes
+    cover both routes of the contractions: the 2-byte matrix instructions (feature widths that are
+    multiples of 8: several tiles each way with ragged last ones, row splits that do not fill the
+    last group of eight, a ragged last chunk) and the fp32 ones (any width)."""
     from helpers import ORC_DT, TOL
     n_src, n_dst, d_in, d_out, max_len = shape
     rng = np.random.default_rng(n_src * 11 + d_in)
@@ -164,13 +168,14 @@ def test_sage_bwd_two_byte_activations_vs_oracle(hb, orc, dt, shape):
         hb.hopgnn_sage_bwd(H, n_src, t(self_idx), t(indptr), t(idx), n_dst, Ws, Wn, out_fwd if relu else None, relu,
                            t(dOut), gWs, gWn, gb, dH, ws)
         torch.cuda.synchronize()
-        # only the neighbour mean is rounded to the 2-byte type; everything else is fp32 arithmetic
-        assert rel_err(to_f64(gWs), ref[0]) <= 2e-5, (shape, relu)
+        # the contractions take the incoming gradient rounded to the activation type (products of two
+        # 2-byte values, fp32 sums): the layer bound of that type; the bias gradient sums fp32 values
+        assert rel_err(to_f64(gWs), ref[0]) <= TOL[dt], (shape, relu)
         assert rel_err(to_f64(gWn), ref[1]) <= TOL[dt], (shape, relu)
         if use_bias:
             assert rel_err(to_f64(gb), ref[2]) <= 2e-5
         if want_dh:
-            assert rel_err(to_f64(dH), ref[3]) <= 2e-5
+            assert rel_err(to_f64(dH), ref[3]) <= TOL[dt]
         if relu:    # the same call without an input gradient masks inside the weight-gradient kernel: same bits
             g2 = [torch.zeros_like(gWs), torch.zeros_like(gWn), torch.zeros(d_out, device=DEV)]
             hb.hopgnn_sage_bwd(H, n_src, t(self_idx), t(indptr), t(idx), n_dst, Ws, Wn, out_fwd, True, t(dOut), g2[0],
