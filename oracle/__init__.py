@@ -82,6 +82,18 @@ def lib() -> ctypes.CDLL:
         L.orc_gat_fwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                   c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32,
                                   c.c_int32, c.c_void_p]
+        L.orc_sage_agg_bwd.restype = c.c_int
+        L.orc_sage_agg_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                       c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p,
+                                       c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        L.orc_gcn_bwd.restype = c.c_int
+        L.orc_gcn_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_int32,
+                                  c.c_void_p, c.c_void_p, c.c_void_p]
+        L.orc_gat_bwd.restype = c.c_int
+        L.orc_gat_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
+                                  c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
         _lib = L
     return _lib
 
@@ -316,6 +328,79 @@ def sage_bwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, out_fwd, relu,
     if rc:
         raise ValueError("orc_sage_bwd failed: %d" % rc)
     return gWs, gWn, gb, dH
+
+
+def _bwd_common(Hsrc, dtype, self_idx, indptr, idx, out_fwd, dOut, d_out):
+    npdt = _NP_OF[dtype]
+    Hsrc = _arr(Hsrc, npdt)
+    indptr = _arr(indptr, np.int32)
+    idx = _arr(idx, np.int32)
+    n_dst = len(indptr) - 1
+    self_idx = None if self_idx is None else _arr(self_idx, np.int32)
+    out_fwd = None if out_fwd is None else _arr(out_fwd, npdt)
+    dOut = _arr(dOut, np.float64)
+    assert dOut.shape == (n_dst, d_out)
+    return npdt, Hsrc, self_idx, indptr, idx, n_dst, out_fwd, dOut
+
+
+def sage_agg_bwd(Hsrc, dtype, self_idx, indptr, idx, W_self, W_neigh, out_fwd, agg, relu, dOut, want_dH=True):
+    """Backward of the GraphSAGE layer with aggregator agg (0 mean, 1 sum, 2 max) in float64
+    -> (gW_self, gW_neigh, gbias, dHsrc-or-None), fresh arrays."""
+    d_in, d_out = np.shape(W_self)
+    npdt, Hsrc, self_idx, indptr, idx, n_dst, out_fwd, dOut = _bwd_common(Hsrc, dtype, self_idx, indptr, idx, out_fwd,
+                                                                         dOut, d_out)
+    W_self = _arr(W_self, npdt)
+    W_neigh = _arr(W_neigh, npdt)
+    n_src = Hsrc.shape[0]
+    gWs = np.zeros((d_in, d_out), np.float64)
+    gWn = np.zeros((d_in, d_out), np.float64)
+    gb = np.zeros(d_out, np.float64)
+    dH = np.zeros((n_src, d_in), np.float64) if want_dH else None
+    rc = lib().orc_sage_agg_bwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W_self),
+                                _p(W_neigh), _p(out_fwd), int(agg), int(bool(relu)), _p(dOut), d_out, _p(gWs), _p(gWn),
+                                _p(gb), _p(dH))
+    if rc:
+        raise ValueError("orc_sage_agg_bwd failed: %d" % rc)
+    return gWs, gWn, gb, dH
+
+
+def gcn_bwd(Hsrc, dtype, self_idx, indptr, idx, W, out_fwd, norm, relu, dOut, want_dH=True):
+    """Backward of the GCN-style layer in float64 -> (gW, gbias, dHsrc-or-None), fresh arrays."""
+    d_in, d_out = np.shape(W)
+    npdt, Hsrc, self_idx, indptr, idx, n_dst, out_fwd, dOut = _bwd_common(Hsrc, dtype, self_idx, indptr, idx, out_fwd,
+                                                                         dOut, d_out)
+    W = _arr(W, npdt)
+    n_src = Hsrc.shape[0]
+    gW = np.zeros((d_in, d_out), np.float64)
+    gb = np.zeros(d_out, np.float64)
+    dH = np.zeros((n_src, d_in), np.float64) if want_dH else None
+    rc = lib().orc_gcn_bwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W), _p(out_fwd),
+                           int(norm), int(bool(relu)), _p(dOut), d_out, _p(gW), _p(gb), _p(dH))
+    if rc:
+        raise ValueError("orc_gcn_bwd failed: %d" % rc)
+    return gW, gb, dH
+
+
+def gat_bwd(Hsrc, dtype, self_idx, indptr, idx, W, a_src, a_dst, out_fwd, n_heads, relu, dOut, want_dH=True):
+    """Backward of the graph-attention layer in float64 -> (gW, ga_src, ga_dst, gbias, dHsrc-or-None)."""
+    d_in, d_out = np.shape(W)
+    npdt, Hsrc, self_idx, indptr, idx, n_dst, out_fwd, dOut = _bwd_common(Hsrc, dtype, self_idx, indptr, idx, out_fwd,
+                                                                         dOut, d_out)
+    W = _arr(W, npdt)
+    a_src = _arr(a_src, npdt)
+    a_dst = _arr(a_dst, npdt)
+    n_src = Hsrc.shape[0]
+    gW = np.zeros((d_in, d_out), np.float64)
+    gas = np.zeros(d_out, np.float64)
+    gad = np.zeros(d_out, np.float64)
+    gb = np.zeros(d_out, np.float64)
+    dH = np.zeros((n_src, d_in), np.float64) if want_dH else None
+    rc = lib().orc_gat_bwd(_p(Hsrc), dtype, n_src, d_in, _p(self_idx), _p(indptr), _p(idx), n_dst, _p(W), _p(a_src),
+                           _p(a_dst), _p(out_fwd), int(bool(relu)), _p(dOut), d_out, int(n_heads), _p(gW), _p(gas),
+                           _p(gad), _p(gb), _p(dH))
+    if rc:
+        raise ValueError("orc_gat_bwd failed: %d" % rc)
+    return gW, gas, gad, gb, dH
 
 
 def sgd_update(W, dtype, grad, lr):

@@ -650,3 +650,258 @@ int orc_sage_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const
     free(dz);
     return 0;
 }
+
+/*
+ * Backward of the GraphSAGE layer with the sum or max aggregator (the aggregators the paper's
+ * discussion of generality names next to the mean), same conventions as orc_sage_bwd:
+ *   out = act(x_self W_self + a W_neigh + b),   a = aggregate of the valid neighbour rows
+ *   dZ  = dOut where the activation passes;  gW_self += x_self^T dZ, gW_neigh += a^T dZ,
+ *   gbias += column sums of dZ;  dHsrc[self] += dZ W_self^T;  with g = dZ[r] W_neigh^T:
+ *   agg 0 (mean): dHsrc[u] += g / c_r for every valid entry u of row r
+ *   agg 1 (sum):  dHsrc[u] += g
+ *   agg 2 (max):  per column k only the entry that supplied the maximum receives g[k]: the first
+ *                 one in entry order among equals (the forward pass replaces the running maximum
+ *                 only by a strictly larger value, so that entry is the one it kept).
+ */
+int orc_sage_agg_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const int32_t *self_idx,
+                     const int32_t *indptr, const int32_t *idx, int64_t n_dst, const void *W_self,
+                     const void *W_neigh, const void *out_fwd, int32_t agg, int32_t relu,
+                     const double *dOut, int32_t d_out, double *gW_self, double *gW_neigh,
+                     double *gbias, double *dHsrc)
+{
+    if (agg < 0 || agg > 2) return 1;
+    double *xs = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *a = (double *)malloc(sizeof(double) * (size_t)d_in);
+    int64_t *arg = (int64_t *)malloc(sizeof(int64_t) * (size_t)d_in);
+    double *dz = (double *)malloc(sizeof(double) * (size_t)d_out);
+    if (!xs || !a || !arg || !dz) { free(xs); free(a); free(arg); free(dz); return 2; }
+    for (int64_t r = 0; r < n_dst; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        for (int32_t k = 0; k < d_in; ++k) {
+            xs[k] = s < 0 ? 0.0 : load_elem(Hsrc, dtype, s * d_in + k);
+            a[k] = 0.0;
+            arg[k] = -1;
+        }
+        int64_t c = 0;
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            int64_t u = idx[e];
+            if (u < 0) continue;
+            for (int32_t k = 0; k < d_in; ++k) {
+                double v = load_elem(Hsrc, dtype, u * d_in + k);
+                if (agg == 2) {
+                    if (c == 0 || v > a[k]) { a[k] = v; arg[k] = u; }
+                } else {
+                    a[k] += v;
+                }
+            }
+            ++c;
+        }
+        if (agg == 0 && c > 0)
+            for (int32_t k = 0; k < d_in; ++k) a[k] /= (double)c;
+        for (int32_t n = 0; n < d_out; ++n) {
+            int pass = !relu || load_elem(out_fwd, dtype, r * d_out + n) > 0.0;
+            dz[n] = pass ? dOut[r * d_out + n] : 0.0;
+            if (gbias) gbias[n] += dz[n];
+        }
+        for (int32_t k = 0; k < d_in; ++k)
+            for (int32_t n = 0; n < d_out; ++n) {
+                gW_self[(int64_t)k * d_out + n] += xs[k] * dz[n];
+                gW_neigh[(int64_t)k * d_out + n] += a[k] * dz[n];
+            }
+        if (dHsrc) {
+            for (int32_t k = 0; k < d_in; ++k) {
+                double gs = 0.0, ga = 0.0;
+                for (int32_t n = 0; n < d_out; ++n) {
+                    gs += dz[n] * load_elem(W_self, dtype, (int64_t)k * d_out + n);
+                    ga += dz[n] * load_elem(W_neigh, dtype, (int64_t)k * d_out + n);
+                }
+                if (s >= 0) dHsrc[s * d_in + k] += gs;
+                if (c == 0) continue;
+                if (agg == 2) {
+                    dHsrc[arg[k] * d_in + k] += ga;
+                } else {
+                    const double share = agg == 0 ? ga / (double)c : ga;
+                    for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e)
+                        if (idx[e] >= 0) dHsrc[(int64_t)idx[e] * d_in + k] += share;
+                }
+            }
+        }
+    }
+    free(xs); free(a); free(arg); free(dz);
+    return 0;
+}
+
+/*
+ * Backward of the GCN-style layer of orc_gcn_fwd:
+ *   a = (x_self + sum of the valid neighbour rows) / t,  t = number of terms (norm 1) or 1 (norm 0)
+ *   out = act(a W + b);  dZ = dOut where the activation passes
+ *   gW += a^T dZ;  gbias += column sums of dZ;  every term's source row receives (dZ[r] W^T) / t
+ * (a row that occurs several times among the terms receives it once per occurrence).
+ */
+int orc_gcn_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const int32_t *self_idx,
+                const int32_t *indptr, const int32_t *idx, int64_t n_dst, const void *W,
+                const void *out_fwd, int32_t norm, int32_t relu, const double *dOut, int32_t d_out,
+                double *gW, double *gbias, double *dHsrc)
+{
+    double *a = (double *)malloc(sizeof(double) * (size_t)d_in);
+    double *dz = (double *)malloc(sizeof(double) * (size_t)d_out);
+    if (!a || !dz) { free(a); free(dz); return 2; }
+    for (int64_t r = 0; r < n_dst; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        int64_t terms = 0;
+        for (int32_t k = 0; k < d_in; ++k) a[k] = 0.0;
+        if (s >= 0) {
+            for (int32_t k = 0; k < d_in; ++k) a[k] += load_elem(Hsrc, dtype, s * d_in + k);
+            ++terms;
+        }
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e) {
+            if (idx[e] < 0) continue;
+            for (int32_t k = 0; k < d_in; ++k) a[k] += load_elem(Hsrc, dtype, (int64_t)idx[e] * d_in + k);
+            ++terms;
+        }
+        const double t = norm && terms > 0 ? (double)terms : 1.0;
+        for (int32_t k = 0; k < d_in; ++k) a[k] /= t;
+        for (int32_t n = 0; n < d_out; ++n) {
+            int pass = !relu || load_elem(out_fwd, dtype, r * d_out + n) > 0.0;
+            dz[n] = pass ? dOut[r * d_out + n] : 0.0;
+            if (gbias) gbias[n] += dz[n];
+        }
+        for (int32_t k = 0; k < d_in; ++k)
+            for (int32_t n = 0; n < d_out; ++n) gW[(int64_t)k * d_out + n] += a[k] * dz[n];
+        if (dHsrc) {
+            for (int32_t k = 0; k < d_in; ++k) {
+                double ga = 0.0;
+                for (int32_t n = 0; n < d_out; ++n) ga += dz[n] * load_elem(W, dtype, (int64_t)k * d_out + n);
+                ga /= t;
+                if (s >= 0) dHsrc[s * d_in + k] += ga;
+                for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e)
+                    if (idx[e] >= 0) dHsrc[(int64_t)idx[e] * d_in + k] += ga;
+            }
+        }
+    }
+    free(a); free(dz);
+    (void)n_src;
+    return 0;
+}
+
+/*
+ * Backward of the graph-attention layer of orc_gat_fwd (the chain rule written out; the layer is
+ * Velickovic et al. 2018).  With y[r,h] = sum_i alpha_i z_{u_i}[h] + b[h], out = act(y) and
+ * dY = dOut where the activation passes, per destination row r and head h over its entries
+ * u_0..u_{m-1} (self first, then the valid neighbours):
+ *   gbias[h]    += dY[r,h]
+ *   dalpha_i     = <dY[r,h], z_{u_i}[h]>              dz_{u_i}[h] += alpha_i dY[r,h]
+ *   dl_i         = alpha_i (dalpha_i - sum_j alpha_j dalpha_j)            (softmax)
+ *   de_i         = dl_i * (e_i > 0 ? 1 : 0.2)                             (LeakyReLU_0.2)
+ *   ds_src[u_i,h] += de_i;   ds_dst[s,h] += sum_i de_i   (only if the self row exists)
+ * and then per source row u:
+ *   dz_u[h]     += ds_src[u,h] a_src[h] + ds_dst[u,h] a_dst[h]
+ *   ga_src[h]   += ds_src[u,h] z_u[h];   ga_dst[h] += ds_dst[u,h] z_u[h]
+ *   gW          += Hsrc[u]^T dz_u;       dHsrc[u] += dz_u W^T
+ * Accumulators are double and ADDED to; gbias and dHsrc may be NULL.
+ */
+int orc_gat_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const int32_t *self_idx,
+                const int32_t *indptr, const int32_t *idx, int64_t n_dst, const void *W,
+                const void *a_src, const void *a_dst, const void *out_fwd, int32_t relu,
+                const double *dOut, int32_t d_out, int32_t n_heads, double *gW, double *ga_src,
+                double *ga_dst, double *gbias, double *dHsrc)
+{
+    if (n_heads < 1 || d_out % n_heads != 0) return 1;
+    const int32_t dh = d_out / n_heads;
+    const size_t ns = (size_t)(n_src > 0 ? n_src : 1);
+    double *Z = (double *)malloc(sizeof(double) * ns * (size_t)d_out);
+    double *dZ = (double *)calloc(ns * (size_t)d_out, sizeof(double));
+    double *ss = (double *)malloc(sizeof(double) * ns * (size_t)n_heads);
+    double *sd = (double *)malloc(sizeof(double) * ns * (size_t)n_heads);
+    double *dss = (double *)calloc(ns * (size_t)n_heads, sizeof(double));
+    double *dsd = (double *)calloc(ns * (size_t)n_heads, sizeof(double));
+    if (!Z || !dZ || !ss || !sd || !dss || !dsd) { free(Z); free(dZ); free(ss); free(sd); free(dss); free(dsd); return 2; }
+    for (int64_t u = 0; u < n_src; ++u) {
+        for (int32_t n = 0; n < d_out; ++n) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < d_in; ++k)
+                acc += load_elem(Hsrc, dtype, u * d_in + k) * load_elem(W, dtype, (int64_t)k * d_out + n);
+            Z[u * d_out + n] = acc;
+        }
+        for (int32_t h = 0; h < n_heads; ++h) {
+            double ps = 0.0, pd = 0.0;
+            for (int32_t j = 0; j < dh; ++j) {
+                ps += Z[u * d_out + h * dh + j] * load_elem(a_src, dtype, h * dh + j);
+                pd += Z[u * d_out + h * dh + j] * load_elem(a_dst, dtype, h * dh + j);
+            }
+            ss[u * n_heads + h] = ps;
+            sd[u * n_heads + h] = pd;
+        }
+    }
+    int rc = 0;
+    for (int64_t r = 0; r < n_dst && !rc; ++r) {
+        int64_t s = self_idx ? self_idx[r] : r;
+        int64_t seg = indptr[r + 1] - indptr[r];
+        int64_t *ent = (int64_t *)malloc(sizeof(int64_t) * (size_t)(seg + 1));
+        double *al = (double *)malloc(sizeof(double) * (size_t)(seg + 1));
+        double *ev = (double *)malloc(sizeof(double) * (size_t)(seg + 1));
+        double *da = (double *)malloc(sizeof(double) * (size_t)(seg + 1));
+        if (!ent || !al || !ev || !da) { free(ent); free(al); free(ev); free(da); rc = 2; break; }
+        int64_t m = 0;
+        if (s >= 0) ent[m++] = s;
+        for (int64_t e = indptr[r]; e < indptr[r + 1]; ++e)
+            if (idx[e] >= 0) ent[m++] = idx[e];
+        for (int32_t h = 0; h < n_heads; ++h) {
+            /* dY of this row and head */
+            for (int32_t j = 0; j < dh; ++j) {
+                int64_t o = r * d_out + h * dh + j;
+                int pass = !relu || load_elem(out_fwd, dtype, o) > 0.0;
+                double g = pass ? dOut[o] : 0.0;
+                if (gbias) gbias[h * dh + j] += g;
+            }
+            if (m == 0) continue;
+            double mx = -INFINITY, den = 0.0;
+            for (int64_t i = 0; i < m; ++i) {
+                ev[i] = (s >= 0 ? sd[s * n_heads + h] : 0.0) + ss[ent[i] * n_heads + h];
+                al[i] = ev[i] > 0.0 ? ev[i] : 0.2 * ev[i];
+                if (al[i] > mx) mx = al[i];
+            }
+            for (int64_t i = 0; i < m; ++i) { al[i] = exp(al[i] - mx); den += al[i]; }
+            double dot = 0.0;
+            for (int64_t i = 0; i < m; ++i) {
+                al[i] /= den;
+                double d = 0.0;
+                for (int32_t j = 0; j < dh; ++j) {
+                    int64_t o = r * d_out + h * dh + j;
+                    int pass = !relu || load_elem(out_fwd, dtype, o) > 0.0;
+                    double g = pass ? dOut[o] : 0.0;
+                    d += g * Z[ent[i] * d_out + h * dh + j];
+                    dZ[ent[i] * d_out + h * dh + j] += al[i] * g;
+                }
+                da[i] = d;
+                dot += al[i] * d;
+            }
+            for (int64_t i = 0; i < m; ++i) {
+                double de = al[i] * (da[i] - dot) * (ev[i] > 0.0 ? 1.0 : 0.2);
+                dss[ent[i] * n_heads + h] += de;
+                if (s >= 0) dsd[s * n_heads + h] += de;
+            }
+        }
+        free(ent); free(al); free(ev); free(da);
+    }
+    for (int64_t u = 0; u < n_src && !rc; ++u) {
+        for (int32_t h = 0; h < n_heads; ++h)
+            for (int32_t j = 0; j < dh; ++j) {
+                int64_t o = u * d_out + h * dh + j;
+                ga_src[h * dh + j] += dss[u * n_heads + h] * Z[o];
+                ga_dst[h * dh + j] += dsd[u * n_heads + h] * Z[o];
+                dZ[o] += dss[u * n_heads + h] * load_elem(a_src, dtype, h * dh + j) +
+                         dsd[u * n_heads + h] * load_elem(a_dst, dtype, h * dh + j);
+            }
+        for (int32_t k = 0; k < d_in; ++k) {
+            double x = load_elem(Hsrc, dtype, u * d_in + k), g = 0.0;
+            for (int32_t n = 0; n < d_out; ++n) {
+                gW[(int64_t)k * d_out + n] += x * dZ[u * d_out + n];
+                g += dZ[u * d_out + n] * load_elem(W, dtype, (int64_t)k * d_out + n);
+            }
+            if (dHsrc) dHsrc[u * d_in + k] += g;
+        }
+    }
+    free(Z); free(dZ); free(ss); free(sd); free(dss); free(dsd);
+    return rc;
+}
