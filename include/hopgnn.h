@@ -471,6 +471,37 @@ hopgnn_status hopgnn_sage_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, 
                               void *stream);
 
 /*
+ * Backward of the other layer kinds the forward path offers (the aggregators the paper's
+ * discussion of generality names next to the mean; the GCN-style layer of its evaluation), for
+ * the same training loop (section 5.1, steps 3-4).  Gradient types, the rounding of the aggregate
+ * and of the products, accumulation into gW / gbias, the meaning of dHsrc (overwritten, or NULL),
+ * the workspace (hopgnn_sage_bwd_ws_bytes of the same sizes) and the errors are those of
+ * hopgnn_sage_bwd.
+ *
+ * hopgnn_sage_bwd_agg   the layer of hopgnn_sage_fwd_agg; agg is a hopgnn_agg (MEAN is
+ *     hopgnn_sage_bwd itself).  SUM hands every valid entry the whole of dZ[r] W_neigh^T; MAX
+ *     hands each column of it to the entry that supplied the maximum, the first one in entry
+ *     order among equal values (the one the forward pass keeps).  Other agg values: EINVAL.
+ * hopgnn_gcn_bwd        the layer of hopgnn_gcn_fwd: gW += agg^T dZ, and the self row and every
+ *     valid entry receive (dZ[r] W^T) / t with t the number of terms (norm = 1) or 1 (norm = 0);
+ *     gW DEVICE [d_in x d_out] fp32 accumulator.  norm other than 0 or 1: EINVAL.
+ * dHsrc is accumulated with float atomic adds after a clearing pass: bit-stable when a source row
+ * receives at most two contributions, otherwise the rounding depends on arrival order.
+ */
+hopgnn_status hopgnn_sage_bwd_agg(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                  const int32_t *self_idx, const int32_t *indptr, const int32_t *idx,
+                                  int64_t n_dst, const void *W_self, const void *W_neigh, const void *out_fwd,
+                                  int32_t agg, int32_t relu, const float *dOut, int32_t d_out, float *gW_self,
+                                  float *gW_neigh, float *gbias, float *dHsrc, void *ws, size_t ws_bytes,
+                                  void *stream);
+
+hopgnn_status hopgnn_gcn_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx, int64_t n_dst,
+                             const void *W, const void *out_fwd, int32_t norm, int32_t relu, const float *dOut,
+                             int32_t d_out, float *gW, float *gbias, float *dHsrc, void *ws, size_t ws_bytes,
+                             void *stream);
+
+/*
  * hopgnn_sage_bwd for neighbour lists in slot order, the layers k >= 2 of hopgnn_sample's trees:
  * self rows are the rows themselves and entry e of the segments is source row first_child_row + e
  * (idx[e] holds that number, or -1 for an invalid slot: what hopgnn_sample writes as slot_idx, with

@@ -8,6 +8,25 @@ ORC_DT = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
 # relative tolerance of layer outputs against the fp64 oracle, per activation type
 TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2, torch.float16: 2e-2}
 
+# Gradients of a layer with 2-byte activations against the fp64 oracle fed the unrounded incoming
+# gradient: the device rounds the masked gradient to the activation type before the two matrix
+# products (relative error up to 2^-9 per element for bf16, 2^-11 for fp16, independent from element
+# to element; a sum of n products carries about 2^-9 / sqrt(3) of the root sum of squares of its
+# terms, the largest of some 10^5 outputs about 5 times that, and rel_err's rms floor adds the spread
+# of the rows' magnitudes, e.g. the 1/terms scaling of a normalised aggregate: about 2.5e-2 observed
+# for bf16 at 256 output columns, reproduced on the CPU by feeding the oracle the rounded gradient).
+# The sharp comparison is against the oracle fed the gradient rounded the same way: GRAD_TOL_SAME.
+GRAD_TOL = {torch.float32: 2e-5, torch.bfloat16: 4e-2, torch.float16: 5e-3}
+GRAD_TOL_SAME = 3e-5
+
+
+def round_like(x: np.ndarray, dt) -> np.ndarray:
+    """x rounded to dt (round to nearest even) and widened to float64: the incoming gradient as a
+    2-byte layer's matrix products take it."""
+    if dt == torch.float32:
+        return np.asarray(x, np.float64)
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(dt).to(torch.float64).numpy()
+
 
 def chain_tol(dt, n_layers: int) -> float:
     """Bound for the last rows of a whole chain of layers against the oracle's own chain.

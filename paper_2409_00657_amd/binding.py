@@ -28,7 +28,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
+           "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sage_bwd_agg", "hopgnn_gcn_bwd", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
            "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_pregather_static", "hopgnn_batch_tree_ws_bytes", "hopgnn_batch_prepare", "hopgnn_pregather_static_max_vertices", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
@@ -117,6 +117,15 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_sgd_update_multi.restype = c.c_int
     L.hopgnn_sgd_update_multi.argtypes = [c.POINTER(c.c_void_p), c.c_int, c.POINTER(c.c_void_p), c.POINTER(c.c_int64),
                                           c.c_int32, c.c_float, c.c_int32, c.c_void_p]
+    L.hopgnn_sage_bwd_agg.restype = c.c_int
+    L.hopgnn_sage_bwd_agg.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                      c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p,
+                                      c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t,
+                                      c.c_void_p]
+    L.hopgnn_gcn_bwd.restype = c.c_int
+    L.hopgnn_gcn_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                 c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_int32,
+                                 c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_sage_bwd_slots.restype = c.c_int
     L.hopgnn_sage_bwd_slots.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int64,
                                         c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
@@ -399,6 +408,32 @@ def hopgnn_sage_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Ten
                                         1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
                                         _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "hopgnn_sage_bwd")
+
+
+def hopgnn_sage_bwd_agg(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                        idx: torch.Tensor, n_dst: int, W_self: torch.Tensor, W_neigh: torch.Tensor,
+                        out_fwd: Optional[torch.Tensor], agg: int, relu: bool, dOut: torch.Tensor,
+                        gW_self: torch.Tensor, gW_neigh: torch.Tensor, gbias: Optional[torch.Tensor],
+                        dHsrc: Optional[torch.Tensor], ws: torch.Tensor) -> None:
+    d_in, d_out = W_self.shape
+    rc = load_library().hopgnn_sage_bwd_agg(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                            _ptr(idx), n_dst, _ptr(W_self), _ptr(W_neigh), _ptr(out_fwd), int(agg),
+                                            1 if relu else 0, _ptr(dOut), d_out, _ptr(gW_self), _ptr(gW_neigh),
+                                            _ptr(gbias), _ptr(dHsrc), _ptr(ws), ws.numel() * ws.element_size(),
+                                            _stream())
+    _check(rc, "hopgnn_sage_bwd_agg")
+
+
+def hopgnn_gcn_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                   idx: torch.Tensor, n_dst: int, W: torch.Tensor, out_fwd: Optional[torch.Tensor], norm: int,
+                   relu: bool, dOut: torch.Tensor, gW: torch.Tensor, gbias: Optional[torch.Tensor],
+                   dHsrc: Optional[torch.Tensor], ws: torch.Tensor, stream=None) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gcn_bwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                       _ptr(idx), n_dst, _ptr(W), _ptr(out_fwd), int(norm), 1 if relu else 0, _ptr(dOut),
+                                       d_out, _ptr(gW), _ptr(gbias), _ptr(dHsrc), _ptr(ws),
+                                       ws.numel() * ws.element_size(), _stream() if stream is None else stream)
+    _check(rc, "hopgnn_gcn_bwd")
 
 
 def hopgnn_sage_bwd_slots(Hsrc: torch.Tensor, n_src: int, indptr: torch.Tensor, idx: torch.Tensor, n_dst: int,

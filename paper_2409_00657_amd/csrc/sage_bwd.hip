@@ -118,13 +118,13 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
                 const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ,
                 const typename Tr::store_t* __restrict__ OutFwd, int64_t n_dst, int32_t d_in,
                 int32_t d_out, int32_t rows_per_split, uint32_t tiles_n, float* __restrict__ partial,
-                float* __restrict__ bias_partial, const int64_t* __restrict__ n_rows_dev) {
+                float* __restrict__ bias_partial, const int64_t* __restrict__ n_rows_dev, int32_t k_self) {
     __shared__ __attribute__((aligned(16))) float As[2][kGradRows][kGradLd];
     __shared__ __attribute__((aligned(16))) float Bs[2][kGradRows][kGradLd];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
     const int wk = wave >> 1, wn = wave & 1;
-    const int K = 2 * d_in;
+    const int K = k_self + d_in;      // k_self = d_in: A = [x_self | aggregate]; 0: the aggregate alone
     const uint32_t tk = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
     // rows that exist (n_dst is the capacity: addresses are clamped to it, rows past n_rows are masked)
     const int64_t n_rows = n_rows_dev != nullptr && *n_rows_dev < n_dst ? *n_rows_dev : n_dst;
@@ -152,7 +152,7 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
             r = r < n_dst ? r : n_dst - 1;
             const int64_t srow = sidx[i] > 0 ? sidx[i] : 0;
             if (VEC) {
-                const T* pa = ka < d_in ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - d_in : 0);
+                const T* pa = ka < k_self ? Hsrc + srow * d_in + ka : Mean + r * d_in + (ka < K ? ka - k_self : 0);
                 f.a[i] = *reinterpret_cast<const R4*>(pa);
                 f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + (nb < d_out ? nb : 0));
                 if (MASK) f.o[i] = *reinterpret_cast<const R4*>(OutFwd + r * d_out + (nb < d_out ? nb : 0));
@@ -162,7 +162,7 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int k = ka + e, n = nb + e;
-                    av.e[e] = k < d_in ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - d_in : 0)];
+                    av.e[e] = k < k_self ? Hsrc[srow * d_in + k] : Mean[r * d_in + (k < K ? k - k_self : 0)];
                     bv[e] = dZ[r * d_out + (n < d_out ? n : 0)];
                     if (MASK) ov.e[e] = OutFwd[r * d_out + (n < d_out ? n : 0)];
                 }
@@ -190,7 +190,7 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int k = ka + e, n = nb + e;
-                const bool a_ok = row_ok && k < K && (k >= d_in || sidx[i] >= 0);
+                const bool a_ok = row_ok && k < K && (k >= k_self || sidx[i] >= 0);
                 av[e] = a_ok ? av[e] : 0.f;
                 bv[e] = row_ok && n < d_out && ov[e] > 0.f ? bv[e] : 0.f;
             }
@@ -285,14 +285,14 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
                   const typename Tr::store_t* __restrict__ OutFwd, int64_t n_dst, int32_t d_in, int32_t d_out,
                   int32_t rows_per_split, uint32_t tiles_n, uint32_t n_tiles, int32_t n_splits,
                   float* __restrict__ partial, float* __restrict__ bias_partial,
-                  const int64_t* __restrict__ n_rows_dev) {
+                  const int64_t* __restrict__ n_rows_dev, int32_t k_self) {
     using T = typename Tr::store_t;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][kG16Rows][kG16Ld];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kG16Rows][kG16Ld];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
     const int wk = wave >> 1, wn = wave & 1;
-    const int K = 2 * d_in;
+    const int K = k_self + d_in;
     // workgroup -> (tile, split): XCD x takes the splits x, x + 8, ... and runs each split's tiles back to back
     const uint32_t xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
     const uint32_t tile = seq % n_tiles;
@@ -313,8 +313,8 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     const bool ka_ok = ka < K, nb_ok = nb < d_out;
     const int nbc = nb_ok ? nb : 0;
     // this thread's A columns come from the self rows or from the means, the same for every chunk
-    const bool a_self = ka < d_in;
-    const T* a_base = a_self ? Hsrc + ka : Mean + (ka_ok ? ka - d_in : 0);
+    const bool a_self = ka < k_self;
+    const T* a_base = a_self ? Hsrc + ka : Mean + (ka_ok ? ka - k_self : 0);
 
     auto self_of = [&](int chunk, int i) -> int32_t {
         int64_t r = r0 + (int64_t)chunk * kG16Rows + ar + 16 * i;
@@ -461,11 +461,11 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ bias_partial, int32_t n_splits,
                   int32_t d_in, int32_t d_out, float* __restrict__ gW_self, float* __restrict__ gW_neigh,
-                  float* __restrict__ gbias) {
+                  float* __restrict__ gbias, int32_t k_self) {
     __shared__ float part[4][kWave];
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int64_t i = (int64_t)blockIdx.x * kWave + lane;
-    const int64_t per = (int64_t)2 * d_in * d_out;
+    const int64_t per = ((int64_t)k_self + d_in) * d_out;     // rows of G: k_self for gW_self, then d_in for gW_neigh
     // elements [0, per) are the weights, [per, per + d_out) the bias
     const float* src = i < per ? partial + i : bias_partial + (i - per);
     const int64_t stride = i < per ? per : d_out;
@@ -484,7 +484,7 @@ bwd_weight_reduce(const float* __restrict__ partial, const float* __restrict__ b
     __syncthreads();
     if (q == 0 && live) {
         const float t = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
-        const int64_t half = (int64_t)d_in * d_out;
+        const int64_t half = (int64_t)k_self * d_out;
         if (i < half) gW_self[i] += t;
         else if (i < per) gW_neigh[i - half] += t;
         else gbias[i - per] += t;
@@ -501,7 +501,7 @@ template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restrict__ Wself,
                const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst_cap, int32_t d_in, int32_t d_out,
-               float* __restrict__ D, const int64_t* __restrict__ n_rows_dev) {
+               float* __restrict__ D, const int64_t* __restrict__ n_rows_dev, int32_t k_self) {
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     constexpr int BM = 64, BN = 64, BK = 16, LD = BK + 4;
@@ -514,7 +514,7 @@ bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restr
     const int64_t row0 = (int64_t)blockIdx.x * BM;
     if (row0 >= n_dst) return;                 // uniform over the workgroup
     const int col0 = blockIdx.y * BN;
-    const int N = 2 * d_in;
+    const int N = k_self + d_in;        // rows of [W_self ; W_neigh], or of the one matrix (k_self = 0)
     const bool vec = (d_out & 3) == 0;
 
     // one 16-byte item of each tile per thread: row tid/4, words (tid%4)*4 .. +3
@@ -522,7 +522,7 @@ bwd_input_grad(const float* __restrict__ dZ, const typename Tr::store_t* __restr
     const int64_t ar = row0 + lr;
     const int bj = col0 + lr;
     const float* arow = ar < n_dst ? dZ + ar * d_out : nullptr;
-    const T* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
+    const T* brow = bj < N ? (bj < k_self ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - k_self) * d_out)
                            : nullptr;
     auto load4w = [&](const T* row, int kq) {      // raw weight elements, widened when they go to LDS
         union { R4 v; T e[4]; } u;
@@ -596,7 +596,7 @@ template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_input_grad16(const float* __restrict__ dZ, const typename Tr::store_t* __restrict__ Wself,
                  const typename Tr::store_t* __restrict__ Wneigh, int64_t n_dst_cap, int32_t d_in, int32_t d_out,
-                 float* __restrict__ D, const int64_t* __restrict__ n_rows_dev) {
+                 float* __restrict__ D, const int64_t* __restrict__ n_rows_dev, int32_t k_self) {
     using T = typename Tr::store_t;
     constexpr int BM = 64, BN = 64, BK = 32, LD = BK + 8;
     __shared__ __attribute__((aligned(16))) uint16_t As[BM][LD];
@@ -608,7 +608,7 @@ bwd_input_grad16(const float* __restrict__ dZ, const typename Tr::store_t* __res
     const int64_t row0 = (int64_t)blockIdx.x * BM;
     if (row0 >= n_dst) return;                 // uniform over the workgroup
     const int col0 = blockIdx.y * BN;
-    const int N = 2 * d_in;
+    const int N = k_self + d_in;        // rows of [W_self ; W_neigh], or of the one matrix (k_self = 0)
     const bool vec = (d_out & 7) == 0;
 
     // one 8-element item of each tile per thread: row tid/4, k (tid%4)*8 .. +7
@@ -616,7 +616,7 @@ bwd_input_grad16(const float* __restrict__ dZ, const typename Tr::store_t* __res
     const int64_t ar = row0 + lr;
     const int bj = col0 + lr;
     const float* arow = ar < n_dst ? dZ + ar * d_out : nullptr;
-    const T* brow = bj < N ? (bj < d_in ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - d_in) * d_out)
+    const T* brow = bj < N ? (bj < k_self ? Wself + (int64_t)bj * d_out : Wneigh + (int64_t)(bj - k_self) * d_out)
                            : nullptr;
     struct Item {
         float4 a[2];
@@ -700,6 +700,68 @@ bwd_scatter(const float* __restrict__ D, const int32_t* __restrict__ self_idx, c
                 const int32_t u = idx[e];
                 if (u >= 0) atomicAdd(&dHsrc[(int64_t)u * d_in + c], m);
             }
+        }
+    }
+}
+
+// The input gradient of the other layer kinds, from D = dZ [W_self ; W_neigh]^T (or dZ W^T):
+//   kScatterSum   GraphSAGE, sum aggregator:  self term as above; every valid entry receives D[r][d_in:]
+//   kScatterMax   GraphSAGE, max aggregator:  per column the entry that supplied the maximum receives it -
+//                 the first one in entry order among equals, as the forward pass keeps it (a larger
+//                 value replaces the running maximum, an equal one does not)
+//   kScatterGcn   GCN-style: the self row and every valid entry receive D[r] / t, t = number of
+//                 terms (norm = 1) or 1 (norm = 0)
+constexpr int kScatterMean = 0, kScatterSum = 1, kScatterMax = 2, kScatterGcn = 3;
+
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+bwd_scatter_kind(const float* __restrict__ D, const typename Tr::store_t* __restrict__ Hsrc,
+                 const int32_t* __restrict__ self_idx, const int32_t* __restrict__ indptr,
+                 const int32_t* __restrict__ idx, int64_t n_dst, int32_t d_in, int32_t group, int32_t mode,
+                 int32_t norm, float* __restrict__ dHsrc, const int64_t* __restrict__ n_rows_dev) {
+    const int64_t gid = (int64_t)blockIdx.x * kBwdThreads + threadIdx.x;
+    const int64_t r = gid / group;
+    const int32_t j = (int32_t)(gid - r * group);
+    if (r >= n_dst || (n_rows_dev != nullptr && r >= *n_rows_dev)) return;
+    const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    if (mode == kScatterGcn) {
+        int32_t terms = s >= 0 ? 1 : 0;
+        for (int32_t e = beg; e < end; ++e) terms += idx[e] >= 0 ? 1 : 0;
+        const float scale = norm && terms > 0 ? 1.f / (float)terms : 1.f;
+        const float* Dr = D + r * (int64_t)d_in;
+        for (int32_t c = j; c < d_in; c += group) {
+            const float g = Dr[c] * scale;
+            if (s >= 0) atomicAdd(&dHsrc[s * d_in + c], g);
+            for (int32_t e = beg; e < end; ++e) {
+                const int32_t u = idx[e];
+                if (u >= 0) atomicAdd(&dHsrc[(int64_t)u * d_in + c], g);
+            }
+        }
+        return;
+    }
+    const float* Dr = D + r * (2 * (int64_t)d_in);
+    for (int32_t c = j; c < d_in; c += group) {
+        if (s >= 0) atomicAdd(&dHsrc[s * d_in + c], Dr[c]);
+        const float g = Dr[d_in + c];
+        if (mode == kScatterSum) {
+            for (int32_t e = beg; e < end; ++e) {
+                const int32_t u = idx[e];
+                if (u >= 0) atomicAdd(&dHsrc[(int64_t)u * d_in + c], g);
+            }
+        } else {
+            int32_t best = -1;
+            float bv = 0.f;
+            for (int32_t e = beg; e < end; ++e) {
+                const int32_t u = idx[e];
+                if (u < 0) continue;
+                const float v = Tr::to_f(Hsrc[(int64_t)u * d_in + c]);
+                if (best < 0 || v > bv) {
+                    bv = v;
+                    best = u;
+                }
+            }
+            if (best >= 0) atomicAdd(&dHsrc[(int64_t)best * d_in + c], g);
         }
     }
 }
@@ -821,13 +883,23 @@ extern "C" size_t hopgnn_sage_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32
 
 namespace hopgnn {
 
+// Which layer the backward pass is for: the GraphSAGE layer with one of its aggregators (two weight
+// matrices, A = [x_self | aggregate]) or the GCN-style layer (one matrix on the aggregate that
+// includes the self row).
+struct BwdKind {
+    int32_t k_self;      // d_in (two matrices) or 0 (one)
+    int32_t scatter;     // kScatter*
+    int32_t norm;        // GCN-style: divide by the number of terms
+};
+
 template <typename Tr>
 static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in, const int32_t* self_idx,
                                     const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W_self,
                                     const void* W_neigh, const void* out_fwd, int32_t relu, const float* dOut,
                                     int32_t d_out, float* gW_self, float* gW_neigh, float* gbias, float* dHsrc,
                                     void* ws, const BwdWs& L, const int64_t* n_dst_dev, int64_t slot_first,
-                                    const void* mean_fwd, hipStream_t s) {
+                                    const void* mean_fwd, hipStream_t s, const BwdKind& kind) {
+    const int32_t k_self = kind.k_self;
     using T = typename Tr::store_t;
     using R4 = typename Raw4<Tr>::type;
     char* p = static_cast<char*>(ws);
@@ -844,8 +916,11 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
     if (mean_fwd != nullptr) {
         mean = const_cast<T*>(static_cast<const T*>(mean_fwd));
     } else {
+        const AggSpec spec = kind.scatter == kScatterGcn ? AggSpec{self_idx, 1, kind.norm ? kAggOpMean : kAggOpSum}
+                             : kind.scatter == kScatterSum ? AggSpec{nullptr, 0, kAggOpSum}
+                             : kind.scatter == kScatterMax ? AggSpec{nullptr, 0, kAggOpMax} : kAggMean;
         hopgnn_status st = launch_mean<Tr>(Hsrc, indptr, idx, n_dst, d_in, mean, zero, L.zero_bytes, TransposeJob{}, 0, s,
-                                           kAggMean, n_dst_dev);
+                                           spec, n_dst_dev);
         if (st != HOPGNN_OK) return st;
     }
 
@@ -866,7 +941,7 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
         dZ = dz_buf;
     }
 
-    const uint32_t tiles_k = (uint32_t)ceil_div(2 * (int64_t)d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
+    const uint32_t tiles_k = (uint32_t)ceil_div((int64_t)k_self + d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
     const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16) && aligned(dZ, 16) && aligned(mean, 16) &&
                      (!fuse_mask || aligned(out_fwd, 16));
     bool on16 = false;
@@ -879,7 +954,7 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
             const uint32_t splits8 = (uint32_t)ceil_div(L.n_splits, 8) * 8u;
             hipLaunchKernelGGL(k16, dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s, static_cast<const T*>(Hsrc), self_idx,
                                mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out, L.rows_per_split, tiles_n,
-                               n_tiles, L.n_splits, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+                               n_tiles, L.n_splits, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev, k_self);
         }
     }
     if (!on16) {
@@ -887,26 +962,31 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                                      : (vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>);
         hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.n_splits), dim3(kBwdThreads), 0, s,
                            static_cast<const T*>(Hsrc), self_idx, mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out,
-                           L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev);
+                           L.rows_per_split, tiles_n, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev, k_self);
     }
     HOPGNN_LAUNCH_CHECK();
-    const int64_t red = (int64_t)2 * d_in * d_out + d_out;
+    const int64_t red = ((int64_t)k_self + d_in) * d_out + d_out;
     hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
-                       bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias);
+                       bias_partial, L.n_splits, d_in, d_out, gW_self, gW_neigh, gbias, k_self);
     HOPGNN_LAUNCH_CHECK();
 
     if (dHsrc != nullptr && n_src > 0) {
-        const int64_t gy = ceil_div(2 * (int64_t)d_in, 64);
+        const int64_t gy = ceil_div((int64_t)k_self + d_in, 64);
         if (gy > 65535) return HOPGNN_ERANGE;
         auto in_kernel = bwd_input_grad<Tr>;
         if constexpr (sizeof(T) == 2) {
             if (aligned(dZ, 16) && aligned(W_self, 16) && aligned(W_neigh, 16)) in_kernel = bwd_input_grad16<Tr>;
         }
         hipLaunchKernelGGL(in_kernel, dim3((unsigned)ceil_div(n_dst, 64), (unsigned)gy), dim3(kBwdThreads), 0, s, dZ,
-                           static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D, n_dst_dev);
+                           static_cast<const T*>(W_self), static_cast<const T*>(W_neigh), n_dst, d_in, d_out, D, n_dst_dev,
+                           k_self);
         HOPGNN_LAUNCH_CHECK();
         const int group = mean_group(d_in);
-        if (slot_first >= 0)
+        if (kind.scatter != kScatterMean)
+            hipLaunchKernelGGL(bwd_scatter_kind<Tr>, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads),
+                               0, s, D, static_cast<const T*>(Hsrc), self_idx, indptr, idx, n_dst, d_in, group, kind.scatter,
+                               kind.norm, dHsrc, n_dst_dev);
+        else if (slot_first >= 0)
             hipLaunchKernelGGL(bwd_pull_slots, dim3((unsigned)ceil_div(n_src * group, kBwdThreads)), dim3(kBwdThreads), 0,
                                s, D, indptr, idx, n_dst, n_src, slot_first, d_in, group, dHsrc);
         else
@@ -934,7 +1014,8 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
                                   int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
                                   const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
                                   float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
-                                  int64_t slot_first, const void* mean_fwd, void* stream);
+                                  int64_t slot_first, const void* mean_fwd, void* stream,
+                                  const hopgnn::BwdKind& kind = hopgnn::BwdKind{-1, hopgnn::kScatterMean, 0});
 
 extern "C" hopgnn_status hopgnn_sage_bwd_dev(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
                                              int32_t d_in, const int32_t* self_idx, const int32_t* indptr,
@@ -960,12 +1041,37 @@ extern "C" hopgnn_status hopgnn_sage_bwd_slots(const void* Hsrc, hopgnn_dtype dt
                         dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, first_child_row, mean_fwd, stream);
 }
 
+extern "C" hopgnn_status hopgnn_sage_bwd_agg(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                             const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                             int64_t n_dst, const void* W_self, const void* W_neigh,
+                                             const void* out_fwd, int32_t agg, int32_t relu, const float* dOut,
+                                             int32_t d_out, float* gW_self, float* gW_neigh, float* gbias,
+                                             float* dHsrc, void* ws, size_t ws_bytes, void* stream) {
+    if (agg != HOPGNN_AGG_MEAN && agg != HOPGNN_AGG_SUM && agg != HOPGNN_AGG_MAX) return HOPGNN_EINVAL;
+    const BwdKind kind{d_in, agg == HOPGNN_AGG_MEAN ? kScatterMean : agg == HOPGNN_AGG_SUM ? kScatterSum : kScatterMax, 0};
+    return sage_bwd_any(Hsrc, dt, n_src, nullptr, d_in, self_idx, indptr, idx, n_dst, nullptr, W_self, W_neigh, out_fwd, relu,
+                        dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, ws_bytes, -1, nullptr, stream, kind);
+}
+
+extern "C" hopgnn_status hopgnn_gcn_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                        const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                        int64_t n_dst, const void* W, const void* out_fwd, int32_t norm, int32_t relu,
+                                        const float* dOut, int32_t d_out, float* gW, float* gbias, float* dHsrc,
+                                        void* ws, size_t ws_bytes, void* stream) {
+    if (norm != 0 && norm != 1) return HOPGNN_EINVAL;
+    const BwdKind kind{0, kScatterGcn, norm};
+    return sage_bwd_any(Hsrc, dt, n_src, nullptr, d_in, self_idx, indptr, idx, n_dst, nullptr, W, W, out_fwd, relu, dOut,
+                        d_out, gW, gW, gbias, dHsrc, ws, ws_bytes, -1, nullptr, stream, kind);
+}
+
 static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
                                   int32_t d_in, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
                                   int64_t n_dst, const int64_t* n_dst_dev, const void* W_self, const void* W_neigh,
                                   const void* out_fwd, int32_t relu, const float* dOut, int32_t d_out, float* gW_self,
                                   float* gW_neigh, float* gbias, float* dHsrc, void* ws, size_t ws_bytes,
-                                  int64_t slot_first, const void* mean_fwd, void* stream) {
+                                  int64_t slot_first, const void* mean_fwd, void* stream, const hopgnn::BwdKind& kind_in) {
+    BwdKind kind = kind_in;
+    if (kind.k_self < 0) kind.k_self = d_in;      // the default: the GraphSAGE-mean layer
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
     if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
     if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
@@ -996,12 +1102,12 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     if (dt == HOPGNN_F32)
         return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
+                                     d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s, kind);
     if (dt == HOPGNN_BF16)
         return sage_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu,
-                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
+                                      dOut, d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s, kind);
     return sage_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
-                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s);
+                                 d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s, kind);
 }
 
 extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,

@@ -1,5 +1,6 @@
 """Shared by the GPU parity tests: tensor <-> oracle conversions and the error metric."""
-from oracle.checks import ORC_DT, TOL, chain_tol, rel_err, to_bits, to_f64, weights_bits  # noqa: F401
+from oracle.checks import (GRAD_TOL, GRAD_TOL_SAME, ORC_DT, TOL, chain_tol, rel_err, round_like, to_bits, to_f64,  # noqa: F401
+                           weights_bits)
 
 import numpy as np
 
