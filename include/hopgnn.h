@@ -502,6 +502,35 @@ hopgnn_status hopgnn_gcn_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, i
                              void *stream);
 
 /*
+ * hopgnn_gat_bwd   backward of the layer of hopgnn_gat_fwd (the attention model of the paper's
+ * evaluation, in the training loop of section 5.1, steps 3-4): the chain rule through the weighted
+ * sum, the softmax over each destination row's entries, LeakyReLU_0.2, the two score products
+ * and z = Hsrc W.
+ * fwd_ws   DEVICE: the workspace of the hopgnn_gat_fwd call of this layer on the same inputs,
+ *          untouched since (z and the attention scores are read from its first
+ *          hopgnn_gat_fwd_ws_bytes(...) bytes); 256-byte aligned.
+ * out_fwd  the stored forward output (ReLU mask; may be NULL when relu == 0); dOut fp32.
+ * gW [d_in x d_out], ga_src [d_out], ga_dst [d_out], gbias [d_out] (or NULL): DEVICE fp32
+ *          accumulators, ADDED to.  dHsrc DEVICE out [n_src x d_in] fp32, overwritten, or NULL.
+ * ws       DEVICE scratch of hopgnn_gat_bwd_ws_bytes(dt, n_src, n_dst, d_in, d_out, n_heads)
+ *          bytes (0 for invalid arguments), 256-byte aligned.
+ * Arithmetic is fp32; with a 2-byte dt the gradient with respect to z is rounded to dt before the
+ * two matrix products (gW, dHsrc) as in hopgnn_sage_bwd.  The sums over destination rows into a
+ * source row (dz, score gradients) are float atomic adds: their rounding depends on arrival order.
+ * gbias, ga_src and ga_dst are summed in a fixed order.  Errors as hopgnn_gat_fwd, plus EINVAL for
+ * a NULL fwd_ws or a ReLU without out_fwd, ENOMEM_WS for a short workspace.
+ */
+size_t hopgnn_gat_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int64_t n_dst, int32_t d_in, int32_t d_out,
+                               int32_t n_heads);
+
+hopgnn_status hopgnn_gat_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx, int64_t n_dst,
+                             const void *W, const void *a_src, const void *a_dst, const void *out_fwd,
+                             const void *fwd_ws, int32_t relu, const float *dOut, int32_t d_out, int32_t n_heads,
+                             float *gW, float *ga_src, float *ga_dst, float *gbias, float *dHsrc, void *ws,
+                             size_t ws_bytes, void *stream);
+
+/*
  * hopgnn_sage_bwd for neighbour lists in slot order, the layers k >= 2 of hopgnn_sample's trees:
  * self rows are the rows themselves and entry e of the segments is source row first_child_row + e
  * (idx[e] holds that number, or -1 for an invalid slot: what hopgnn_sample writes as slot_idx, with

@@ -28,7 +28,7 @@ EXPORTS = ["hopgnn_status_str", "hopgnn_slots_per_seed", "hopgnn_sample",
            "hopgnn_micrograph_locality",
            "hopgnn_split_ws_bytes", "hopgnn_split_by_owner", "hopgnn_merge_min_step", "hopgnn_merge_apply",
            "hopgnn_merge_ctl_init", "hopgnn_merge_ctl_report", "hopgnn_batch_fwd",
-           "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sage_bwd_agg", "hopgnn_gcn_bwd", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
+           "hopgnn_sgd_update", "hopgnn_sgd_update_multi", "hopgnn_sage_fwd_dev", "hopgnn_sage_bwd_dev", "hopgnn_sage_bwd_slots", "hopgnn_sage_bwd_agg", "hopgnn_gcn_bwd", "hopgnn_gat_bwd_ws_bytes", "hopgnn_gat_bwd", "hopgnn_sample_dedup_ws_bytes", "hopgnn_sample_dedup",
            "hopgnn_compose_idx", "hopgnn_frontier_locality", "hopgnn_layerwise_caps", "hopgnn_sample_layerwise_ws_bytes",
            "hopgnn_sample_layerwise", "hopgnn_sample_group", "hopgnn_sample_merged", "hopgnn_pregather_ws_init", "hopgnn_pregather_static", "hopgnn_batch_tree_ws_bytes", "hopgnn_batch_prepare", "hopgnn_pregather_static_max_vertices", "hopgnn_sage_fwd_agg", "hopgnn_gcn_fwd_ws_bytes", "hopgnn_gcn_fwd", "hopgnn_gat_fwd_ws_bytes", "hopgnn_gat_fwd",
            "hopgnn_gcn_fwd_dev", "hopgnn_gat_fwd_dev"]
@@ -126,6 +126,13 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_gcn_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_int32,
                                  c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
+    L.hopgnn_gat_bwd_ws_bytes.restype = c.c_size_t
+    L.hopgnn_gat_bwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
+    L.hopgnn_gat_bwd.restype = c.c_int
+    L.hopgnn_gat_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+                                 c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
+                                 c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
+                                 c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
     L.hopgnn_sage_bwd_slots.restype = c.c_int
     L.hopgnn_sage_bwd_slots.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_int64,
                                         c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32, c.c_void_p,
@@ -434,6 +441,24 @@ def hopgnn_gcn_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tens
                                        d_out, _ptr(gW), _ptr(gbias), _ptr(dHsrc), _ptr(ws),
                                        ws.numel() * ws.element_size(), _stream() if stream is None else stream)
     _check(rc, "hopgnn_gcn_bwd")
+
+
+def hopgnn_gat_bwd_ws_bytes(dtype: torch.dtype, n_src: int, n_dst: int, d_in: int, d_out: int, n_heads: int) -> int:
+    return int(load_library().hopgnn_gat_bwd_ws_bytes(DTYPE_OF[dtype], n_src, n_dst, d_in, d_out, n_heads))
+
+
+def hopgnn_gat_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tensor], indptr: torch.Tensor,
+                   idx: torch.Tensor, n_dst: int, W: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
+                   out_fwd: Optional[torch.Tensor], fwd_ws: torch.Tensor, relu: bool, dOut: torch.Tensor, n_heads: int,
+                   gW: torch.Tensor, ga_src: torch.Tensor, ga_dst: torch.Tensor, gbias: Optional[torch.Tensor],
+                   dHsrc: Optional[torch.Tensor], ws: torch.Tensor, stream=None) -> None:
+    d_in, d_out = W.shape
+    rc = load_library().hopgnn_gat_bwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+                                       _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(out_fwd), _ptr(fwd_ws),
+                                       1 if relu else 0, _ptr(dOut), d_out, int(n_heads), _ptr(gW), _ptr(ga_src),
+                                       _ptr(ga_dst), _ptr(gbias), _ptr(dHsrc), _ptr(ws),
+                                       ws.numel() * ws.element_size(), _stream() if stream is None else stream)
+    _check(rc, "hopgnn_gat_bwd")
 
 
 def hopgnn_sage_bwd_slots(Hsrc: torch.Tensor, n_src: int, indptr: torch.Tensor, idx: torch.Tensor, n_dst: int,

@@ -238,22 +238,6 @@ gat_aggregate(const float* __restrict__ Z, const float* __restrict__ s_src,
 
 // -------------------------------------------------------------------- host --
 
-struct GatWs {
-    size_t z_bytes, score_bytes, wscore_bytes;   // then the projection's [Wt][zero row]
-    ProjWs P;
-    size_t total;
-};
-static GatWs gat_ws_layout(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out, int32_t n_heads) {
-    GatWs L{};
-    const int64_t ns = n_src > 0 ? n_src : 1;
-    L.z_bytes = align_up((size_t)ns * d_out * 4, 256);
-    L.score_bytes = align_up((size_t)ns * 2 * n_heads * 4, 256);     // [n_src][s_src heads | s_dst heads]
-    L.wscore_bytes = align_up((size_t)d_in * 2 * n_heads * 4, 256);
-    L.P = proj_ws_layout(dt, 0, d_in, d_in, d_out);     // no aggregate buffer: the rows are Hsrc itself
-    L.total = L.z_bytes + L.score_bytes + L.wscore_bytes + L.P.wt_bytes + L.P.zero_bytes;
-    return L;
-}
-
 static hopgnn_status launch_prep(hopgnn_dtype dt, const void* W, uint16_t* Wt, const ProjWs& P, int32_t d_in,
                                  int32_t d_out, void* zero, ScoreWeightJob sw, hipStream_t s) {
     TransposeJob job{};

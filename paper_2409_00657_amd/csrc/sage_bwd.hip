@@ -1110,6 +1110,332 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
                                  d_out, gW_self, gW_neigh, gbias, dHsrc, ws, L, n_dst_dev, slot_first, mean_fwd, s, kind);
 }
 
+// ------------------------------------------------------- attention layer --
+//
+// Backward of the graph-attention layer (the third model of the paper's evaluation; the chain rule
+// through softmax and LeakyReLU_0.2 written out).  z = Hsrc W (fp32) and the scores s_src, s_dst are
+// read from the forward call's workspace.  With dY = dOut masked by the stored forward output:
+//
+//   gbias += column sums of dY                                            col_sum_rows + reduce_parts_add
+//   per destination row and head over its entries u_i (self first):       gat_bwd_rows
+//     alpha_i as in the forward pass;  dalpha_i = <dY[r,h], z_{u_i}[h]>;  dz[u_i,h] += alpha_i dY[r,h]
+//     de_i = alpha_i (dalpha_i - sum_j alpha_j dalpha_j) * (e_i > 0 ? 1 : 0.2)
+//     ds_src[u_i,h] += de_i;  ds_dst[self,h] += sum_i de_i
+//   per source row:  dz[u,h] += ds_src[u,h] a_src[h] + ds_dst[u,h] a_dst[h]   gat_bwd_src
+//     ga_src[h] += ds_src[u,h] z_u[h];  ga_dst[h] += ds_dst[u,h] z_u[h]       (+ reduce_parts_add)
+//   gW += Hsrc^T dz  (the weight-gradient kernels, one matrix, rows = source rows)
+//   dHsrc = dz W^T   (the input-gradient kernels, written in place)
+
+namespace hopgnn {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float leaky02(float x) { return x > 0.f ? x : 0.2f * x; }
+
+constexpr int kColRows = 128;    // rows per workgroup of the column-sum kernels
+
+// partial[b][n] = sum over the rows of block b of dOut[r][n] where the activation passes
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+col_sum_rows(const float* __restrict__ dOut, const typename Tr::store_t* __restrict__ out_fwd, int relu,
+             int64_t n_rows, int32_t d_out, float* __restrict__ partial) {
+    const int64_t r0 = (int64_t)blockIdx.x * kColRows;
+    const int64_t r1 = r0 + kColRows < n_rows ? r0 + kColRows : n_rows;
+    for (int32_t n = threadIdx.x; n < d_out; n += kBwdThreads) {
+        float acc = 0.f;
+        for (int64_t r = r0; r < r1; ++r) {
+            const float g = dOut[r * d_out + n];
+            acc += !relu || Tr::to_f(out_fwd[r * d_out + n]) > 0.f ? g : 0.f;
+        }
+        partial[(int64_t)blockIdx.x * d_out + n] = acc;
+    }
+}
+
+// out[i] += sum over p < n_parts of partial[p * part_stride + i], i < width, in a fixed order (wave q
+// takes the parts q, q + 4, ...; the four sums are combined as (s0 + s1) + (s2 + s3)): bit-stable.
+__global__ void __launch_bounds__(kBwdThreads)
+reduce_parts_add(const float* __restrict__ partial, int64_t part_stride, int32_t n_parts, int32_t width,
+                 float* __restrict__ out) {
+    __shared__ float part[4][kWave];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int32_t i = blockIdx.x * kWave + lane;
+    float s = 0.f;
+    if (i < width)
+        for (int32_t p = q; p < n_parts; p += 4) s += partial[(int64_t)p * part_stride + i];
+    part[q][lane] = s;
+    __syncthreads();
+    if (q == 0 && i < width) out[i] += (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+}
+
+// One wavefront per destination row, one head after the other; the lanes share the head's columns.
+// The dot products dalpha_i of the first 64 entries stay in registers (lane i keeps entry i's); a
+// longer segment computes the later ones a second time.
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+gat_bwd_rows(const float* __restrict__ Z, const float* __restrict__ scores, const int32_t* __restrict__ self_idx,
+             const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx,
+             const typename Tr::store_t* __restrict__ out_fwd, int relu, const float* __restrict__ dOut,
+             int64_t n_dst, int32_t d_out, int32_t n_heads, float* __restrict__ dZ, float* __restrict__ ds) {
+    const int lane = threadIdx.x & 63;
+    const int64_t r = (int64_t)blockIdx.x * (kBwdThreads / kWave) + (threadIdx.x >> 6);
+    if (r >= n_dst) return;                       // the whole wavefront
+    const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
+    const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
+    const int32_t beg = indptr[r], end = indptr[r + 1];
+    for (int32_t h = 0; h < n_heads; ++h) {
+        const float sd = s >= 0 ? scores[s * stride + n_heads + h] : 0.f;
+        float mx = -INFINITY;
+        if (s >= 0) mx = leaky02(sd + scores[s * stride + h]);
+        for (int32_t e = beg; e < end; ++e) {
+            const int32_t u = idx[e];
+            if (u >= 0) mx = fmaxf(mx, leaky02(sd + scores[(int64_t)u * stride + h]));
+        }
+        if (mx == -INFINITY) continue;            // no entries: the row's output is act(bias)
+        float den = 0.f;
+        if (s >= 0) den += expf(leaky02(sd + scores[s * stride + h]) - mx);
+        for (int32_t e = beg; e < end; ++e) {
+            const int32_t u = idx[e];
+            if (u >= 0) den += expf(leaky02(sd + scores[(int64_t)u * stride + h]) - mx);
+        }
+        const float inv = 1.f / den;
+        const float* gy = dOut + r * d_out + (int64_t)h * dh;
+        const typename Tr::store_t* of = out_fwd != nullptr ? out_fwd + r * d_out + (int64_t)h * dh : nullptr;
+        auto g_at = [&](int32_t j) -> float {
+            const float g = gy[j];
+            return !relu || Tr::to_f(of[j]) > 0.f ? g : 0.f;
+        };
+        auto dot_with = [&](int64_t u) -> float {
+            const float* zu = Z + u * d_out + (int64_t)h * dh;
+            float d = 0.f;
+            for (int32_t j = lane; j < dh; j += kWave) d += g_at(j) * zu[j];
+            return wave_sum(d);
+        };
+        // first pass: dz, the dot products, and S = sum alpha_i dalpha_i
+        float S = 0.f, mine = 0.f;
+        int32_t i = 0;
+        auto first = [&](int64_t u) {
+            const float al = expf(leaky02(sd + scores[u * stride + h]) - mx) * inv;
+            const float* zu = Z + u * d_out + (int64_t)h * dh;
+            float* dzu = dZ + u * d_out + (int64_t)h * dh;
+            float d = 0.f;
+            for (int32_t j = lane; j < dh; j += kWave) {
+                const float g = g_at(j);
+                d += g * zu[j];
+                atomicAdd(&dzu[j], al * g);
+            }
+            d = wave_sum(d);
+            S += al * d;
+            if (lane == i) mine = d;              // entries past 63 match no lane
+            ++i;
+        };
+        if (s >= 0) first(s);
+        for (int32_t e = beg; e < end; ++e)
+            if (idx[e] >= 0) first(idx[e]);
+        // second pass: the score gradients
+        i = 0;
+        float sum_de = 0.f;
+        auto second = [&](int64_t u) {
+            const float ev = sd + scores[u * stride + h];
+            const float al = expf(leaky02(ev) - mx) * inv;
+            const float d = i < kWave ? __shfl(mine, i, kWave) : dot_with(u);
+            const float de = al * (d - S) * (ev > 0.f ? 1.f : 0.2f);
+            if (lane == 0) atomicAdd(&ds[u * stride + h], de);
+            sum_de += de;
+            ++i;
+        };
+        if (s >= 0) second(s);
+        for (int32_t e = beg; e < end; ++e)
+            if (idx[e] >= 0) second(idx[e]);
+        if (s >= 0 && lane == 0) atomicAdd(&ds[s * stride + n_heads + h], sum_de);
+    }
+}
+
+constexpr int kSrcRows = 64;     // source rows per workgroup of gat_bwd_src
+
+// dz[u] += ds_src[u,h] a_src[h] + ds_dst[u,h] a_dst[h] in place (one thread owns a column of the
+// block's rows), and the block's part of ga_src / ga_dst: partial[b][0][n], partial[b][1][n].
+template <typename Tr>
+__global__ void __launch_bounds__(kBwdThreads)
+gat_bwd_src(const float* __restrict__ Z, const float* __restrict__ ds, const typename Tr::store_t* __restrict__ a_src,
+            const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, int32_t d_out, int32_t n_heads,
+            float* __restrict__ dZ, float* __restrict__ partial) {
+    const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
+    const int64_t u0 = (int64_t)blockIdx.x * kSrcRows;
+    const int64_t u1 = u0 + kSrcRows < n_src ? u0 + kSrcRows : n_src;
+    for (int32_t n = threadIdx.x; n < d_out; n += kBwdThreads) {
+        const int32_t h = n / dh;
+        const float as = Tr::to_f(a_src[n]), ad = Tr::to_f(a_dst[n]);
+        float acc_s = 0.f, acc_d = 0.f;
+        for (int64_t u = u0; u < u1; ++u) {
+            const float dss = ds[u * stride + h], dsd = ds[u * stride + n_heads + h];
+            const float z = Z[u * d_out + n];
+            acc_s += dss * z;
+            acc_d += dsd * z;
+            dZ[u * d_out + n] += dss * as + dsd * ad;
+        }
+        partial[((int64_t)blockIdx.x * 2 + 0) * d_out + n] = acc_s;
+        partial[((int64_t)blockIdx.x * 2 + 1) * d_out + n] = acc_d;
+    }
+}
+
+struct GatBwdWs {
+    size_t dz_bytes, ds_bytes, col_bytes, zero_bytes;
+    BwdWs G;          // the weight gradient's partial tiles (rows = source rows)
+    size_t total;
+};
+static GatBwdWs gat_bwd_ws_layout(int64_t n_src, int64_t n_dst, int32_t d_in, int32_t d_out, int32_t n_heads) {
+    GatBwdWs L{};
+    const int64_t ns = n_src > 0 ? n_src : 1, nd = n_dst > 0 ? n_dst : 1;
+    L.dz_bytes = align_up((size_t)ns * d_out * 4, 256);
+    L.ds_bytes = align_up((size_t)ns * 2 * n_heads * 4, 256);
+    const int64_t parts = ceil_div(nd, kColRows) > 2 * ceil_div(ns, kSrcRows) ? ceil_div(nd, kColRows) : 2 * ceil_div(ns, kSrcRows);
+    L.col_bytes = align_up((size_t)parts * d_out * 4, 256);
+    L.G = bwd_ws_layout(ns, d_in, d_out, 0);
+    L.total = L.dz_bytes + L.ds_bytes + L.col_bytes + L.G.partial_bytes + L.G.bias_bytes;
+    return L;
+}
+
+template <typename Tr>
+static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in, const int32_t* self_idx,
+                                   const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W,
+                                   const void* a_src, const void* a_dst, const void* out_fwd, const void* fwd_ws,
+                                   int32_t relu, const float* dOut, int32_t d_out, int32_t n_heads, float* gW,
+                                   float* ga_src, float* ga_dst, float* gbias, float* dHsrc, void* ws,
+                                   const GatBwdWs& L, hipStream_t s) {
+    using T = typename Tr::store_t;
+    char* p = static_cast<char*>(ws);
+    float* dZ = reinterpret_cast<float*>(p);
+    float* ds = reinterpret_cast<float*>(p + L.dz_bytes);
+    float* col = reinterpret_cast<float*>(p + L.dz_bytes + L.ds_bytes);
+    float* partial = reinterpret_cast<float*>(p + L.dz_bytes + L.ds_bytes + L.col_bytes);
+    float* bias_partial = reinterpret_cast<float*>(reinterpret_cast<char*>(partial) + L.G.partial_bytes);
+    const GatWs F = gat_ws_layout(Tr::kDt, n_src, d_in, d_out, n_heads);
+    const float* Z = static_cast<const float*>(fwd_ws);
+    const float* scores = reinterpret_cast<const float*>(static_cast<const char*>(fwd_ws) + F.z_bytes);
+
+    if (gbias != nullptr) {
+        const int32_t parts = (int32_t)ceil_div(n_dst, kColRows);
+        hipLaunchKernelGGL(col_sum_rows<Tr>, dim3((unsigned)parts), dim3(kBwdThreads), 0, s, dOut,
+                           static_cast<const T*>(out_fwd), relu, n_dst, d_out, col);
+        HOPGNN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col,
+                           (int64_t)d_out, parts, d_out, gbias);
+        HOPGNN_LAUNCH_CHECK();
+    }
+    if (n_src == 0) return HOPGNN_OK;              // no entries anywhere: only the bias has a gradient
+
+    // dz and ds start at zero (a fill kernel, never a memset node); the two arrays are adjacent
+    const int64_t n4 = (int64_t)(L.dz_bytes + L.ds_bytes) / 16;
+    hipLaunchKernelGGL(bwd_zero, dim3((unsigned)ceil_div(n4, kBwdThreads)), dim3(kBwdThreads), 0, s,
+                       reinterpret_cast<float4*>(dZ), n4, nullptr, 0);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(gat_bwd_rows<Tr>, dim3((unsigned)ceil_div(n_dst, kBwdThreads / kWave)), dim3(kBwdThreads), 0, s, Z,
+                       scores, self_idx, indptr, idx, static_cast<const T*>(out_fwd), relu, dOut, n_dst, d_out, n_heads, dZ,
+                       ds);
+    HOPGNN_LAUNCH_CHECK();
+    const int32_t src_blocks = (int32_t)ceil_div(n_src, kSrcRows);
+    hipLaunchKernelGGL(gat_bwd_src<Tr>, dim3((unsigned)src_blocks), dim3(kBwdThreads), 0, s, Z, ds,
+                       static_cast<const T*>(a_src), static_cast<const T*>(a_dst), n_src, d_out, n_heads, dZ, col);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col,
+                       (int64_t)2 * d_out, src_blocks, d_out, ga_src);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col + d_out,
+                       (int64_t)2 * d_out, src_blocks, d_out, ga_dst);
+    HOPGNN_LAUNCH_CHECK();
+
+    // gW += Hsrc^T dz: one matrix (k_self = 0), the "aggregate" operand is Hsrc itself, rows = source rows
+    const uint32_t tiles_k = (uint32_t)ceil_div(d_in, kGradTile), tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
+    const bool vec = d_in % 4 == 0 && d_out % 4 == 0 && aligned(Hsrc, 16);
+    bool on16 = false;
+    if constexpr (sizeof(T) == 2) {
+        on16 = vec && d_in % 8 == 0;
+        if (on16) {
+            const uint32_t n_tiles = tiles_k * tiles_n;
+            const uint32_t splits8 = (uint32_t)ceil_div(L.G.n_splits, 8) * 8u;
+            hipLaunchKernelGGL((bwd_weight_grad16<Tr, false>), dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s,
+                               static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr, n_src, d_in,
+                               d_out, L.G.rows_per_split, tiles_n, n_tiles, L.G.n_splits, partial, nullptr, nullptr, 0);
+        }
+    }
+    if (!on16) {
+        auto grad_kernel = vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>;
+        hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.G.n_splits), dim3(kBwdThreads), 0, s,
+                           static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr, n_src, d_in, d_out,
+                           L.G.rows_per_split, tiles_n, partial, nullptr, nullptr, 0);
+    }
+    HOPGNN_LAUNCH_CHECK();
+    const int64_t red = (int64_t)d_in * d_out;
+    hipLaunchKernelGGL(bwd_weight_reduce, dim3((unsigned)ceil_div(red, kWave)), dim3(kBwdThreads), 0, s, partial,
+                       bias_partial, L.G.n_splits, d_in, d_out, gW, gW, nullptr, 0);
+    HOPGNN_LAUNCH_CHECK();
+
+    if (dHsrc != nullptr) {      // dHsrc = dz W^T, every element written
+        const int64_t gy = ceil_div(d_in, 64);
+        if (gy > 65535) return HOPGNN_ERANGE;
+        auto in_kernel = bwd_input_grad<Tr>;
+        if constexpr (sizeof(T) == 2) {
+            if (aligned(W, 16)) in_kernel = bwd_input_grad16<Tr>;
+        }
+        hipLaunchKernelGGL(in_kernel, dim3((unsigned)ceil_div(n_src, 64), (unsigned)gy), dim3(kBwdThreads), 0, s, dZ,
+                           static_cast<const T*>(W), static_cast<const T*>(W), n_src, d_in, d_out, dHsrc, nullptr, 0);
+        HOPGNN_LAUNCH_CHECK();
+    }
+    return HOPGNN_OK;
+}
+
+}  // namespace hopgnn
+
+extern "C" size_t hopgnn_gat_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int64_t n_dst, int32_t d_in, int32_t d_out,
+                                          int32_t n_heads) {
+    if ((dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) || n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1 ||
+        n_heads < 1 || n_heads > 16 || d_out % n_heads != 0)
+        return 0;
+    return gat_bwd_ws_layout(n_src, n_dst, d_in, d_out, n_heads).total;
+}
+
+extern "C" hopgnn_status hopgnn_gat_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
+                                        const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+                                        int64_t n_dst, const void* W, const void* a_src, const void* a_dst,
+                                        const void* out_fwd, const void* fwd_ws, int32_t relu, const float* dOut,
+                                        int32_t d_out, int32_t n_heads, float* gW, float* ga_src, float* ga_dst,
+                                        float* gbias, float* dHsrc, void* ws, size_t ws_bytes, void* stream) {
+    if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;
+    if (n_src < 0 || n_dst < 0 || d_in < 1 || d_out < 1) return HOPGNN_EINVAL;
+    if (n_heads < 1 || n_heads > 16 || d_out % n_heads != 0) return HOPGNN_EINVAL;
+    if (d_in > (1 << 20) || d_out > (1 << 20)) return HOPGNN_ERANGE;
+    if (n_dst >= ((int64_t)1 << 31) || n_src >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if (n_dst == 0) {
+        if (dHsrc != nullptr && n_src > 0) {       // no destination rows: the input gradient is zero
+            const int64_t n = (int64_t)n_src * d_in;
+            hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n, kBwdThreads)), dim3(kBwdThreads), 0,
+                               static_cast<hipStream_t>(stream), dHsrc, n, nullptr, 0);
+            HOPGNN_LAUNCH_CHECK();
+        }
+        return HOPGNN_OK;
+    }
+    if (indptr == nullptr || W == nullptr || a_src == nullptr || a_dst == nullptr || dOut == nullptr || gW == nullptr ||
+        ga_src == nullptr || ga_dst == nullptr || ws == nullptr || fwd_ws == nullptr || (relu && out_fwd == nullptr))
+        return HOPGNN_EINVAL;
+    if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
+    if (self_idx == nullptr && n_src < n_dst) return HOPGNN_EINVAL;
+    if (!aligned(ws, 256) || !aligned(fwd_ws, 256)) return HOPGNN_EINVAL;
+    const GatBwdWs L = gat_bwd_ws_layout(n_src, n_dst, d_in, d_out, n_heads);
+    if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dt == HOPGNN_F32)
+        return gat_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
+                                    d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
+    if (dt == HOPGNN_BF16)
+        return gat_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu,
+                                     dOut, d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
+    return gat_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
+                                d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
+}
+
 extern "C" hopgnn_status hopgnn_sgd_update(void* W, hopgnn_dtype dt, float* grad, int64_t n, float lr, int32_t zero_grad,
                                            void* stream) {
     if (dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) return HOPGNN_EINVAL;

@@ -299,6 +299,26 @@ struct ProjWs {
 };
 ProjWs proj_ws_layout(hopgnn_dtype dt, int64_t n_rows, int32_t d_in, int32_t k_total, int32_t d_out);
 
+// Workspace of the attention layer's forward call: [ z : n_src x d_out fp32 ][ scores : n_src x 2*n_heads
+// fp32, s_src heads then s_dst heads per row ][ score weights ][ the projection's Wt and zero row ].
+// The backward call reads z and the scores from it.
+struct GatWs {
+    size_t z_bytes, score_bytes, wscore_bytes;   // then the projection's [Wt][zero row]
+    ProjWs P;
+    size_t total;
+};
+static inline GatWs gat_ws_layout(hopgnn_dtype dt, int64_t n_src, int32_t d_in, int32_t d_out, int32_t n_heads) {
+    GatWs L{};
+    const int64_t ns = n_src > 0 ? n_src : 1;
+    L.z_bytes = align_up((size_t)ns * d_out * 4, 256);
+    L.score_bytes = align_up((size_t)ns * 2 * n_heads * 4, 256);     // [n_src][s_src heads | s_dst heads]
+    L.wscore_bytes = align_up((size_t)d_in * 2 * n_heads * 4, 256);
+    L.P = proj_ws_layout(dt, 0, d_in, d_in, d_out);     // no aggregate buffer: the rows are Hsrc itself
+    L.total = L.z_bytes + L.score_bytes + L.wscore_bytes + L.P.wt_bytes + L.P.zero_bytes;
+    return L;
+}
+
+
 // Row tiling of one layer over a slot tree (level-major rows: level 0 = the roots, the children
 // of a level-(h-1) slot are f[h] consecutive level-h slots).  Tiles do not cross levels, and on
 // levels >= 1 a tile holds whole groups of siblings (g[h] groups of f[h] rows), so that the

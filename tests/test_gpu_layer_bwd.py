@@ -182,3 +182,67 @@ def test_layer_backward_argument_errors(hb):
     with pytest.raises(HopgnnError):     # workspace too small
         hb.hopgnn_gcn_bwd(H, n_src, _t(self_idx), _t(indptr), _t(idx), n_dst, W, None, 1, False, _t(dOut), g(), None, None,
                           ws[:256])
+
+
+GAT_SHAPES = [  # n_src, n_dst, d_in, d_out, longest segment, heads
+    (1500, 1111, 128, 128, 12, 4), (4000, 777, 100, 256, 16, 2), (300, 65, 7, 6, 4, 3), (2500, 900, 136, 132, 6, 1),
+    (600, 40, 32, 64, 150, 8)]      # the last: segments longer than a wavefront
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("shape", GAT_SHAPES)
+def test_attention_backward_vs_oracle(hb, orc, dt, shape):
+    """The forward call runs first on the device (its workspace holds z and the scores the backward
+    call reads; its stored output decides the ReLU mask on both sides)."""
+    n_src, n_dst, d_in, d_out, max_len, heads = shape
+    rng = np.random.default_rng(n_src * 3 + d_in + heads)
+    H, W, _, dOut, indptr, idx, self_idx = _inputs(rng, dt, (n_src, n_dst, d_in, d_out, max_len))
+    f = lambda *s: torch.from_numpy(rng.standard_normal(s).astype(np.float32))
+    a_s, a_d, b = (f(d_out) * 0.3).to(dt).to(DEV), (f(d_out) * 0.3).to(dt).to(DEV), (f(d_out) * 0.1).to(dt).to(DEV)
+    odt = ORC_DT[dt]
+    for relu, want_dh, use_bias in [(True, True, True), (False, False, False)]:
+        fwd_ws = torch.empty(hb.hopgnn_gat_fwd_ws_bytes(dt, n_src, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+        out = torch.empty((n_dst, d_out), dtype=dt, device=DEV)
+        hb.hopgnn_gat_fwd(H, n_src, _t(self_idx), _t(indptr), _t(idx), n_dst, W, a_s, a_d, b if use_bias else None, heads,
+                          relu, out, fwd_ws)
+        gW = torch.zeros((d_in, d_out), device=DEV)
+        gas, gad = torch.zeros(d_out, device=DEV), torch.zeros(d_out, device=DEV)
+        gb = torch.zeros(d_out, device=DEV) if use_bias else None
+        dH = torch.full((n_src, d_in), 7.0, device=DEV) if want_dh else None
+        ws = torch.empty(hb.hopgnn_gat_bwd_ws_bytes(dt, n_src, n_dst, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+        ws.fill_(0x5A)
+        hb.hopgnn_gat_bwd(H, n_src, _t(self_idx), _t(indptr), _t(idx), n_dst, W, a_s, a_d, out if relu else None, fwd_ws,
+                          relu, _t(dOut), heads, gW, gas, gad, gb, dH, ws)
+        torch.cuda.synchronize()
+        ref = orc.gat_bwd(to_bits(H), odt, self_idx, indptr, idx, to_bits(W), to_bits(a_s), to_bits(a_d),
+                          to_bits(out) if relu else None, heads, relu, dOut.astype(np.float64), want_dH=want_dh)
+        # fp32: everything is fp32 arithmetic (exp, sums in another order); 2-byte: the gradient with
+        # respect to z is rounded to the activation type before the two matrix products
+        tol = 1e-4 if dt == torch.float32 else GRAD_TOL[dt]
+        assert rel_err(to_f64(gW), ref[0]) <= tol, (shape, relu)
+        assert rel_err(to_f64(gas), ref[1]) <= 1e-4 and rel_err(to_f64(gad), ref[2]) <= 1e-4, (shape, relu)
+        if use_bias:
+            assert rel_err(to_f64(gb), ref[3]) <= 2e-5
+        if want_dh:
+            assert rel_err(to_f64(dH), ref[4]) <= tol, (shape, relu)
+
+
+def test_attention_backward_argument_errors(hb):
+    from paper_2409_00657_amd.binding import HopgnnError
+    rng = np.random.default_rng(0)
+    n_src, n_dst, d_in, d_out, heads = 40, 30, 8, 8, 2
+    H, W, _, dOut, indptr, idx, self_idx = _inputs(rng, torch.float32, (n_src, n_dst, d_in, d_out, 3))
+    a = torch.zeros(d_out, device=DEV)
+    fwd_ws = torch.zeros(hb.hopgnn_gat_fwd_ws_bytes(torch.float32, n_src, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(hb.hopgnn_gat_bwd_ws_bytes(torch.float32, n_src, n_dst, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+    g = lambda: torch.zeros((d_in, d_out), device=DEV)
+    v = lambda: torch.zeros(d_out, device=DEV)
+    call = lambda **k: hb.hopgnn_gat_bwd(H, n_src, _t(self_idx), _t(indptr), _t(idx), n_dst, W, a, a, k.get("out"),
+                                         k.get("fwd_ws", fwd_ws), k.get("relu", False), _t(dOut), k.get("heads", heads), g(),
+                                         v(), v(), None, None, k.get("ws", ws))
+    call()                                        # the valid call
+    torch.cuda.synchronize()
+    for bad in (dict(heads=3), dict(heads=0), dict(relu=True), dict(ws=ws[:256])):
+        with pytest.raises(HopgnnError):
+            call(**bad)
+    assert hb.hopgnn_gat_bwd_ws_bytes(torch.float32, n_src, n_dst, d_in, d_out, 3) == 0
