@@ -640,9 +640,6 @@ def main_variant(args):
     X = cfg.make_features(device=dev)
     W = cfg.make_weights(device=dev)
     n_streams = max(1, args.streams)
-    if args.model != "sage" and args.backward:
-        print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
-        sys.exit(2)
     merge = group > 1 and not args.no_merge and not args.backward
     # training steps update the weights: every stream is then a worker with its own replica
     Ws = [W] + [[tuple(None if t is None else t.clone() for t in layer) for layer in W]
@@ -839,8 +836,9 @@ def main():
         print("bench.py: this build is the single-GPU hot path (no collectives, no sharding); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.model != "sage" and args.backward:
-        print("bench.py: --backward is built for the GraphSAGE-mean layer", file=sys.stderr)
+    if args.model != "sage" and args.backward and (args.dedup or args.layerwise):
+        print("bench.py: --backward over deduplicated frontiers is built for the GraphSAGE-mean layer "
+              "(slot-tree batches train all three layer kinds)", file=sys.stderr)
         sys.exit(2)
     if args.dedup or args.layerwise:
         return main_dedup(args)

@@ -509,6 +509,9 @@ hopgnn_status hopgnn_gcn_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, i
  * fwd_ws   DEVICE: the workspace of the hopgnn_gat_fwd call of this layer on the same inputs,
  *          untouched since (z and the attention scores are read from its first
  *          hopgnn_gat_fwd_ws_bytes(...) bytes); 256-byte aligned.
+ * n_src_dev DEVICE, or NULL = n_src: the number of source rows that exist when only the device
+ *          knows it (layer 1 reads the pre-gathered rows; n_src is then their capacity), as in
+ *          hopgnn_gat_fwd; rows past it are neither read nor written.
  * out_fwd  the stored forward output (ReLU mask; may be NULL when relu == 0); dOut fp32.
  * gW [d_in x d_out], ga_src [d_out], ga_dst [d_out], gbias [d_out] (or NULL): DEVICE fp32
  *          accumulators, ADDED to.  dHsrc DEVICE out [n_src x d_in] fp32, overwritten, or NULL.
@@ -523,8 +526,8 @@ hopgnn_status hopgnn_gcn_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, i
 size_t hopgnn_gat_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int64_t n_dst, int32_t d_in, int32_t d_out,
                                int32_t n_heads);
 
-hopgnn_status hopgnn_gat_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
-                             const int32_t *self_idx, const int32_t *indptr, const int32_t *idx, int64_t n_dst,
+hopgnn_status hopgnn_gat_bwd(const void *Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t *n_src_dev,
+                             int32_t d_in, const int32_t *self_idx, const int32_t *indptr, const int32_t *idx, int64_t n_dst,
                              const void *W, const void *a_src, const void *a_dst, const void *out_fwd,
                              const void *fwd_ws, int32_t relu, const float *dOut, int32_t d_out, int32_t n_heads,
                              float *gW, float *ga_src, float *ga_dst, float *gbias, float *dHsrc, void *ws,

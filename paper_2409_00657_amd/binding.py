@@ -129,7 +129,7 @@ def load_library() -> ctypes.CDLL:
     L.hopgnn_gat_bwd_ws_bytes.restype = c.c_size_t
     L.hopgnn_gat_bwd_ws_bytes.argtypes = [c.c_int, c.c_int64, c.c_int64, c.c_int32, c.c_int32, c.c_int32]
     L.hopgnn_gat_bwd.restype = c.c_int
-    L.hopgnn_gat_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
+    L.hopgnn_gat_bwd.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_void_p, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_int64, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32,
                                  c.c_void_p, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p,
                                  c.c_void_p, c.c_void_p, c.c_size_t, c.c_void_p]
@@ -451,9 +451,10 @@ def hopgnn_gat_bwd(Hsrc: torch.Tensor, n_src: int, self_idx: Optional[torch.Tens
                    idx: torch.Tensor, n_dst: int, W: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
                    out_fwd: Optional[torch.Tensor], fwd_ws: torch.Tensor, relu: bool, dOut: torch.Tensor, n_heads: int,
                    gW: torch.Tensor, ga_src: torch.Tensor, ga_dst: torch.Tensor, gbias: Optional[torch.Tensor],
-                   dHsrc: Optional[torch.Tensor], ws: torch.Tensor, stream=None) -> None:
+                   dHsrc: Optional[torch.Tensor], ws: torch.Tensor, stream=None,
+                   n_src_dev: Optional[torch.Tensor] = None) -> None:
     d_in, d_out = W.shape
-    rc = load_library().hopgnn_gat_bwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, d_in, _ptr(self_idx), _ptr(indptr),
+    rc = load_library().hopgnn_gat_bwd(_ptr(Hsrc), DTYPE_OF[Hsrc.dtype], n_src, _ptr(n_src_dev), d_in, _ptr(self_idx), _ptr(indptr),
                                        _ptr(idx), n_dst, _ptr(W), _ptr(a_src), _ptr(a_dst), _ptr(out_fwd), _ptr(fwd_ws),
                                        1 if relu else 0, _ptr(dOut), d_out, int(n_heads), _ptr(gW), _ptr(ga_src),
                                        _ptr(ga_dst), _ptr(gbias), _ptr(dHsrc), _ptr(ws),

@@ -1260,10 +1260,11 @@ constexpr int kSrcRows = 64;     // source rows per workgroup of gat_bwd_src
 template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 gat_bwd_src(const float* __restrict__ Z, const float* __restrict__ ds, const typename Tr::store_t* __restrict__ a_src,
-            const typename Tr::store_t* __restrict__ a_dst, int64_t n_src, int32_t d_out, int32_t n_heads,
-            float* __restrict__ dZ, float* __restrict__ partial) {
+            const typename Tr::store_t* __restrict__ a_dst, int64_t n_src_cap, const int64_t* __restrict__ n_rows_dev,
+            int32_t d_out, int32_t n_heads, float* __restrict__ dZ, float* __restrict__ partial) {
     const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
-    const int64_t u0 = (int64_t)blockIdx.x * kSrcRows;
+    const int64_t n_src = n_rows_dev != nullptr && *n_rows_dev < n_src_cap ? *n_rows_dev : n_src_cap;
+    const int64_t u0 = (int64_t)blockIdx.x * kSrcRows;       // a block past the last row writes zero parts
     const int64_t u1 = u0 + kSrcRows < n_src ? u0 + kSrcRows : n_src;
     for (int32_t n = threadIdx.x; n < d_out; n += kBwdThreads) {
         const int32_t h = n / dh;
@@ -1299,7 +1300,8 @@ static GatBwdWs gat_bwd_ws_layout(int64_t n_src, int64_t n_dst, int32_t d_in, in
 }
 
 template <typename Tr>
-static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in, const int32_t* self_idx,
+static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, const int64_t* n_src_dev, int32_t d_in,
+                                   const int32_t* self_idx,
                                    const int32_t* indptr, const int32_t* idx, int64_t n_dst, const void* W,
                                    const void* a_src, const void* a_dst, const void* out_fwd, const void* fwd_ws,
                                    int32_t relu, const float* dOut, int32_t d_out, int32_t n_heads, float* gW,
@@ -1327,10 +1329,16 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in
     }
     if (n_src == 0) return HOPGNN_OK;              // no entries anywhere: only the bias has a gradient
 
-    // dz and ds start at zero (a fill kernel, never a memset node); the two arrays are adjacent
-    const int64_t n4 = (int64_t)(L.dz_bytes + L.ds_bytes) / 16;
-    hipLaunchKernelGGL(bwd_zero, dim3((unsigned)ceil_div(n4, kBwdThreads)), dim3(kBwdThreads), 0, s,
-                       reinterpret_cast<float4*>(dZ), n4, nullptr, 0);
+    // dz and ds start at zero (fill kernels, never a memset node): the source rows that exist
+    if (d_out % 4 == 0)
+        hipLaunchKernelGGL(bwd_zero, dim3((unsigned)ceil_div(n_src * (d_out / 4), kBwdThreads)), dim3(kBwdThreads), 0, s,
+                           reinterpret_cast<float4*>(dZ), n_src * (d_out / 4), n_src_dev, d_out / 4);
+    else
+        hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n_src * d_out, kBwdThreads)), dim3(kBwdThreads), 0, s, dZ,
+                           n_src * d_out, n_src_dev, d_out);
+    HOPGNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bwd_zero_elem, dim3((unsigned)ceil_div(n_src * 2 * n_heads, kBwdThreads)), dim3(kBwdThreads), 0, s, ds,
+                       n_src * 2 * n_heads, n_src_dev, 2 * n_heads);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(gat_bwd_rows<Tr>, dim3((unsigned)ceil_div(n_dst, kBwdThreads / kWave)), dim3(kBwdThreads), 0, s, Z,
                        scores, self_idx, indptr, idx, static_cast<const T*>(out_fwd), relu, dOut, n_dst, d_out, n_heads, dZ,
@@ -1338,7 +1346,7 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in
     HOPGNN_LAUNCH_CHECK();
     const int32_t src_blocks = (int32_t)ceil_div(n_src, kSrcRows);
     hipLaunchKernelGGL(gat_bwd_src<Tr>, dim3((unsigned)src_blocks), dim3(kBwdThreads), 0, s, Z, ds,
-                       static_cast<const T*>(a_src), static_cast<const T*>(a_dst), n_src, d_out, n_heads, dZ, col);
+                       static_cast<const T*>(a_src), static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, dZ, col);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col,
                        (int64_t)2 * d_out, src_blocks, d_out, ga_src);
@@ -1358,14 +1366,14 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in
             const uint32_t splits8 = (uint32_t)ceil_div(L.G.n_splits, 8) * 8u;
             hipLaunchKernelGGL((bwd_weight_grad16<Tr, false>), dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s,
                                static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr, n_src, d_in,
-                               d_out, L.G.rows_per_split, tiles_n, n_tiles, L.G.n_splits, partial, nullptr, nullptr, 0);
+                               d_out, L.G.rows_per_split, tiles_n, n_tiles, L.G.n_splits, partial, nullptr, n_src_dev, 0);
         }
     }
     if (!on16) {
         auto grad_kernel = vec ? bwd_weight_grad<Tr, true, false> : bwd_weight_grad<Tr, false, false>;
         hipLaunchKernelGGL(grad_kernel, dim3(tiles_k * tiles_n, (unsigned)L.G.n_splits), dim3(kBwdThreads), 0, s,
                            static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr, n_src, d_in, d_out,
-                           L.G.rows_per_split, tiles_n, partial, nullptr, nullptr, 0);
+                           L.G.rows_per_split, tiles_n, partial, nullptr, n_src_dev, 0);
     }
     HOPGNN_LAUNCH_CHECK();
     const int64_t red = (int64_t)d_in * d_out;
@@ -1381,7 +1389,7 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in
             if (aligned(W, 16)) in_kernel = bwd_input_grad16<Tr>;
         }
         hipLaunchKernelGGL(in_kernel, dim3((unsigned)ceil_div(n_src, 64), (unsigned)gy), dim3(kBwdThreads), 0, s, dZ,
-                           static_cast<const T*>(W), static_cast<const T*>(W), n_src, d_in, d_out, dHsrc, nullptr, 0);
+                           static_cast<const T*>(W), static_cast<const T*>(W), n_src, d_in, d_out, dHsrc, n_src_dev, 0);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
@@ -1397,8 +1405,8 @@ extern "C" size_t hopgnn_gat_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_src, int64_
     return gat_bwd_ws_layout(n_src, n_dst, d_in, d_out, n_heads).total;
 }
 
-extern "C" hopgnn_status hopgnn_gat_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, int32_t d_in,
-                                        const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
+extern "C" hopgnn_status hopgnn_gat_bwd(const void* Hsrc, hopgnn_dtype dt, int64_t n_src, const int64_t* n_src_dev,
+                                        int32_t d_in, const int32_t* self_idx, const int32_t* indptr, const int32_t* idx,
                                         int64_t n_dst, const void* W, const void* a_src, const void* a_dst,
                                         const void* out_fwd, const void* fwd_ws, int32_t relu, const float* dOut,
                                         int32_t d_out, int32_t n_heads, float* gW, float* ga_src, float* ga_dst,
@@ -1427,12 +1435,12 @@ extern "C" hopgnn_status hopgnn_gat_bwd(const void* Hsrc, hopgnn_dtype dt, int64
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (dt == HOPGNN_F32)
-        return gat_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
+        return gat_bwd_typed<TrF32>(Hsrc, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
                                     d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
     if (dt == HOPGNN_BF16)
-        return gat_bwd_typed<TrBF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu,
+        return gat_bwd_typed<TrBF16>(Hsrc, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu,
                                      dOut, d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
-    return gat_bwd_typed<TrF16>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
+    return gat_bwd_typed<TrF16>(Hsrc, n_src, n_src_dev, d_in, self_idx, indptr, idx, n_dst, W, a_src, a_dst, out_fwd, fwd_ws, relu, dOut,
                                 d_out, n_heads, gW, ga_src, ga_dst, gbias, dHsrc, ws, L, s);
 }
 

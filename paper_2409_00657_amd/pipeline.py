@@ -294,50 +294,86 @@ class HotPath:
         """Allocate gradient accumulators (one set per layer, fp32, zero) and the buffers of the
         backward pass.  Gradients are fp32 whatever the activation type.  The loss used by the
         harness is L = 1/2 |H_L|^2 for fp32 activations (dL/dH_L = H_L, read in place) and
-        L = <G, H_L> with a fixed G for 2-byte activations (dL/dH_L = G, fp32)."""
-        if self.model != "sage":
-            raise hb.HopgnnError("backward is built for the GraphSAGE-mean layer")
-        sh, dev = self.shape, self.X.device
+        L = <G, H_L> with a fixed G for 2-byte activations (dL/dH_L = G, fp32).
+        self.gW[k]: (gW_self, gW_neigh, gbias) for "sage"; (gW, None, gbias) for "gcn";
+        (gW, None, gbias) plus self.g_attn[k] = (ga_src, ga_dst) for "gat"."""
+        sh, dev, dt = self.shape, self.X.device, self.X.dtype
         L = sh.n_layers
-        if self.X.dtype == torch.float32:
+        if dt == torch.float32:
             self.dHL = self.H[L - 1]
         else:
             self.dHL = synth.weight(self.H[L - 1].shape[0], self.H[L - 1].shape[1], torch.float32, stream=99,
                                     device=dev)
-        self.gW = [(torch.zeros_like(Ws, dtype=torch.float32), torch.zeros_like(Wn, dtype=torch.float32),
-                    None if b is None else torch.zeros_like(b, dtype=torch.float32)) for Ws, Wn, b in self.weights]
+        z = lambda t: None if t is None else torch.zeros_like(t, dtype=torch.float32)
+        if self.model == "sage":
+            self.gW = [(z(Ws), z(Wn), z(b)) for Ws, Wn, b in self.weights]
+        else:
+            self.gW = [(z(Ws), None, z(b)) for Ws, Wn, b in self.weights]
+        params = [(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads) if g is not None]
+        if self.model == "gat":
+            self.g_attn = [(z(a_s), z(a_d)) for a_s, a_d in self.attn]
+            params += [(a, g) for pair, grads in zip(self.attn, self.g_attn) for a, g in zip(pair, grads)]
         hidden = self.weights[0][0].shape[1]
+        d_in_of = lambda k: self.weights[k - 1][0].shape[0]
+        n_src_of = lambda k: self.cap if k == 1 else sh.n_dst(k - 1)
         # dH[k] = gradient of layer k's output rows (k = 1..L-1), produced by layer k+1's backward
         self.dH = [torch.empty((sh.n_dst(k), hidden), dtype=torch.float32, device=dev) for k in range(1, L)]
-        ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
-                                                   hidden, k > 1) for k in range(1, L + 1))
+        if self.model == "gat":
+            ws_bytes = max(hb.hopgnn_gat_bwd_ws_bytes(dt, n_src_of(k), sh.n_dst(k), d_in_of(k), hidden, self.gat_heads)
+                           for k in range(1, L + 1))
+            fwd_bytes = [hb.hopgnn_gat_fwd_ws_bytes(dt, n_src_of(k), d_in_of(k), hidden, self.gat_heads)
+                         for k in range(1, L + 1)]
+        else:
+            ws_bytes = max(hb.hopgnn_sage_bwd_ws_bytes(dt, sh.n_dst(k), d_in_of(k), hidden, k > 1) for k in range(1, L + 1))
+            fwd = hb.hopgnn_sage_fwd_ws_bytes if self.model == "sage" else hb.hopgnn_gcn_fwd_ws_bytes
+            fwd_bytes = [fwd(dt, sh.n_dst(k), d_in_of(k), hidden) for k in range(1, L + 1)]
         self.bwd_ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-        self._sgd = hb.SgdTensors([(W, g) for layer, grads in zip(self.weights, self.gW) for W, g in zip(layer, grads)])
-        # every layer gets a forward workspace of its own: the neighbour means it leaves there are
-        # then still in place when the layer's backward call wants them
-        self._fwd_ws = [torch.empty(hb.hopgnn_sage_fwd_ws_bytes(self.X.dtype, sh.n_dst(k), self.weights[k - 1][0].shape[0],
-                                                                hidden), dtype=torch.uint8, device=dev)
-                        for k in range(1, L + 1)]
+        self._sgd = hb.SgdTensors(params)
+        # every layer gets a forward workspace of its own: what the forward call leaves there (the
+        # neighbour means; z and the attention scores) is then still in place for the layer's backward call
+        self._fwd_ws = [torch.empty(n, dtype=torch.uint8, device=dev) for n in fwd_bytes]
         for per_batch in self._layer_args:
             for k in range(L):
                 per_batch[k] = per_batch[k][:-2] + (self._fwd_ws[k].data_ptr(), self._fwd_ws[k].numel())
         self._bwd_args = []
+        hdt = hb.DTYPE_OF[dt]
         for b in range(self.group):
+            rb = self.remap.data_ptr() + 4 * b * sh.n_slots
             per_batch = []
             for k in range(L, 0, -1):
-                fwd = self._layer_args[b][k - 1]
-                (src, dt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws, Wn, _bias, d_out, relu, out, _ws, _wsb) = fwd
+                Ws, Wn, _bias = self.weights[k - 1]
+                d_in, d_out = Ws.shape
+                n_dst, n_src = sh.n_dst(k), n_src_of(k)
+                src = self.Xu.data_ptr() if k == 1 else self.H[k - 2].data_ptr()
+                self_idx, idx = (rb, rb + 4 * sh.n_seeds) if k == 1 else (None, self.slot_idx[b].data_ptr())
+                indptr = self.indptr.data_ptr()
+                out, relu = self.H[k - 1].data_ptr(), 1 if k < L else 0
                 d_out_grad = self.dHL.data_ptr() if k == L else self.dH[k - 1].data_ptr()
                 gWs, gWn, gb = self.gW[k - 1]
-                tail = (Ws, Wn, out, self._fwd_ws[k - 1].data_ptr(), relu, d_out_grad, d_out, gWs.data_ptr(),
-                        gWn.data_ptr(), None if gb is None else gb.data_ptr(),
-                        self.dH[k - 2].data_ptr() if k > 1 else None, self.bwd_ws.data_ptr(), self.bwd_ws.numel())
-                if k > 1:   # neighbour lists in slot order: the input gradient is written without atomics
-                    per_batch.append((self._lib.hopgnn_sage_bwd_slots,
-                                      (src, dt, n_src, d_in, indptr, idx, n_dst, sh.n_seeds) + tail))
+                gbp = None if gb is None else gb.data_ptr()
+                dHsrc = self.dH[k - 2].data_ptr() if k > 1 else None
+                ws = (self.bwd_ws.data_ptr(), self.bwd_ws.numel())
+                if self.model == "sage":
+                    tail = (Ws.data_ptr(), Wn.data_ptr(), out, self._fwd_ws[k - 1].data_ptr(), relu, d_out_grad, d_out,
+                            gWs.data_ptr(), gWn.data_ptr(), gbp, dHsrc) + ws
+                    if k > 1:   # neighbour lists in slot order: the input gradient is written without atomics
+                        per_batch.append((self._lib.hopgnn_sage_bwd_slots,
+                                          (src, hdt, n_src, d_in, indptr, idx, n_dst, sh.n_seeds) + tail))
+                    else:
+                        per_batch.append((self._lib.hopgnn_sage_bwd_dev,
+                                          (src, hdt, n_src, None, d_in, self_idx, indptr, idx, n_dst, None) + tail))
+                elif self.model == "gcn":
+                    per_batch.append((self._lib.hopgnn_gcn_bwd,
+                                      (src, hdt, n_src, d_in, self_idx, indptr, idx, n_dst, Ws.data_ptr(), out, 1, relu,
+                                       d_out_grad, d_out, gWs.data_ptr(), gbp, dHsrc) + ws))
                 else:
-                    per_batch.append((self._lib.hopgnn_sage_bwd_dev,
-                                      (src, dt, n_src, None, d_in, self_idx, indptr, idx, n_dst, None) + tail))
+                    a_s, a_d = self.attn[k - 1]
+                    ga_s, ga_d = self.g_attn[k - 1]
+                    per_batch.append((self._lib.hopgnn_gat_bwd,
+                                      (src, hdt, n_src, self.n_uniq.data_ptr() if k == 1 else None, d_in, self_idx, indptr,
+                                       idx, n_dst, Ws.data_ptr(), a_s.data_ptr(), a_d.data_ptr(), out,
+                                       self._fwd_ws[k - 1].data_ptr(), relu, d_out_grad, d_out, self.gat_heads,
+                                       gWs.data_ptr(), ga_s.data_ptr(), ga_d.data_ptr(), gbp, dHsrc) + ws))
             self._bwd_args.append(per_batch)
 
     def backward(self, b: int, stream=None) -> None:

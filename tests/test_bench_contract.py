@@ -14,7 +14,7 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert r.stdout.strip() == ""                      # no JSON line
 
 
-def test_backward_of_other_layer_kinds_is_refused():
+def test_backward_of_other_layer_kinds_over_deduplicated_frontiers_is_refused():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--model", "gat", "--backward", "--dedup"],
                        capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "backward" in r.stderr

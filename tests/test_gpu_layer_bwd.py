@@ -246,3 +246,104 @@ def test_attention_backward_argument_errors(hb):
         with pytest.raises(HopgnnError):
             call(**bad)
     assert hb.hopgnn_gat_bwd_ws_bytes(torch.float32, n_src, n_dst, d_in, d_out, 3) == 0
+
+
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_attention_backward_with_a_device_row_count(hb, dt):
+    """Source rows past the device-side count (here NaN, as unwritten memory may be) are neither read
+    nor written: same gradients as the call on exactly the rows that exist."""
+    n_src, n_dst, d_in, d_out, max_len, heads = 1500, 1111, 128, 128, 12, 4
+    extra = 77
+    rng = np.random.default_rng(17)
+    H, W, _, dOut, indptr, idx, self_idx = _inputs(rng, dt, (n_src, n_dst, d_in, d_out, max_len))
+    a_s = torch.from_numpy(rng.standard_normal(d_out).astype(np.float32) * 0.3).to(dt).to(DEV)
+    a_d = torch.from_numpy(rng.standard_normal(d_out).astype(np.float32) * 0.3).to(dt).to(DEV)
+    Hcap = torch.cat([H, torch.full((extra, d_in), float("nan"), dtype=dt, device=DEV)])
+    n_dev = torch.tensor([n_src], dtype=torch.int64, device=DEV)
+    res = []
+    for Hin, cap, cnt in ((H, n_src, None), (Hcap, n_src + extra, n_dev)):
+        fwd_ws = torch.empty(hb.hopgnn_gat_fwd_ws_bytes(dt, cap, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+        fwd_ws.fill_(0xFF)          # NaN patterns where nothing is written
+        out = torch.empty((n_dst, d_out), dtype=dt, device=DEV)
+        hb.hopgnn_gat_fwd(Hin, cap, _t(self_idx), _t(indptr), _t(idx), n_dst, W, a_s, a_d, None, heads, True, out, fwd_ws,
+                          n_src_dev=cnt)
+        gW, gas, gad = torch.zeros((d_in, d_out), device=DEV), torch.zeros(d_out, device=DEV), torch.zeros(d_out, device=DEV)
+        dH = torch.full((cap, d_in), 7.0, device=DEV)
+        ws = torch.empty(hb.hopgnn_gat_bwd_ws_bytes(dt, cap, n_dst, d_in, d_out, heads), dtype=torch.uint8, device=DEV)
+        ws.fill_(0xFF)
+        hb.hopgnn_gat_bwd(Hin, cap, _t(self_idx), _t(indptr), _t(idx), n_dst, W, a_s, a_d, out, fwd_ws, True, _t(dOut), heads,
+                          gW, gas, gad, None, dH, ws, n_src_dev=cnt)
+        torch.cuda.synchronize()
+        res.append((gW, gas, gad, dH))
+    (gW0, gas0, gad0, dH0), (gW1, gas1, gad1, dH1) = res
+    assert torch.isfinite(gW1).all() and torch.isfinite(gas1).all() and torch.isfinite(gad1).all()
+    # float atomics inside: equal up to summation order
+    assert rel_err(to_f64(gW1), to_f64(gW0)) <= 1e-4 and rel_err(to_f64(gas1), to_f64(gas0)) <= 1e-4
+    assert rel_err(to_f64(gad1), to_f64(gad0)) <= 1e-4 and rel_err(to_f64(dH1[:n_src]), to_f64(dH0)) <= 1e-4
+    assert bool((dH1[n_src:] == 7.0).all())        # rows that do not exist stay untouched
+
+
+@pytest.mark.parametrize("model", ["gcn", "gat"])
+def test_pipeline_backward_chain_vs_oracle_and_training(hb, orc, model):
+    """A sampled batch of the small workload through HotPath: forward, then the pipeline's own backward
+    calls (last layer first).  Every layer's gradients against the oracle from the device's stored
+    activations and incoming gradient; then SGD iterations on a fixed pair of batches lower
+    1/2 |H_L|^2."""
+    from paper_2409_00657_amd import synth
+    from paper_2409_00657_amd.pipeline import HotPath
+    cfg = synth.CONFIGS[1]
+    g = cfg.make_graph(device=DEV)
+    X = cfg.make_features(device=DEV)
+    W = cfg.make_weights(device=DEV)
+    hp = HotPath(g.offsets, g.indices, X, W, cfg.batch, cfg.fanouts, model=model)
+    hp.enable_backward()
+    seeds = synth.seeds(cfg.n_vertices, cfg.batch, 5, device=DEV)
+    out = hp.run_batch(seeds, 5)
+    hp.backward(0)
+    torch.cuda.synchronize()
+    sh = hp.shape
+    B, L = sh.n_seeds, sh.n_layers
+    assert L == 2
+    U = int(hp.n_uniq.item())
+    remap, indptr, slot_idx = hp.remap.cpu().numpy(), hp.indptr.cpu().numpy(), hp.slot_idx[0].cpu().numpy()
+    n2, n1 = sh.n_dst(2), sh.n_dst(1)
+    H1, Xu = to_bits(hp.H[0]), to_bits(hp.Xu[:U])
+    dOut2 = to_f64(out)                               # dL/dH_L = H_L for fp32 activations
+    w = lambda k: to_bits(W[k][0])
+    if model == "gcn":
+        ref2 = orc.gcn_bwd(H1, 0, None, indptr[:n2 + 1], slot_idx[:sh.nnz(2)], w(1), None, 1, False, dOut2)
+        dH1 = to_f64(hp.dH[0])
+        ref1 = orc.gcn_bwd(Xu, 0, remap[:n1], indptr[:n1 + 1], remap[B:B + sh.nnz(1)], w(0), H1, 1, True, dH1, want_dH=False)
+        got2, got1 = (hp.gW[1][0], hp.gW[1][2]), (hp.gW[0][0], hp.gW[0][2])
+        ref2_dH, names = ref2[2], ("gW", "gbias")
+    else:
+        a = lambda k, j: to_bits(hp.attn[k][j])
+        ref2 = orc.gat_bwd(H1, 0, None, indptr[:n2 + 1], slot_idx[:sh.nnz(2)], w(1), a(1, 0), a(1, 1), None, hp.gat_heads,
+                           False, dOut2)
+        dH1 = to_f64(hp.dH[0])
+        ref1 = orc.gat_bwd(Xu, 0, remap[:n1], indptr[:n1 + 1], remap[B:B + sh.nnz(1)], w(0), a(0, 0), a(0, 1), H1,
+                           hp.gat_heads, True, dH1, want_dH=False)
+        got2 = (hp.gW[1][0], hp.g_attn[1][0], hp.g_attn[1][1], hp.gW[1][2])
+        got1 = (hp.gW[0][0], hp.g_attn[0][0], hp.g_attn[0][1], hp.gW[0][2])
+        ref2_dH, names = ref2[4], ("gW", "ga_src", "ga_dst", "gbias")
+    tol = 1e-4
+    for k, (got, ref) in ((2, (got2, ref2)), (1, (got1, ref1))):
+        for name, gt, rf in zip(names, got, ref):
+            if gt is not None:
+                assert rel_err(to_f64(gt), rf.reshape(gt.shape)) <= tol, (model, k, name)
+    assert rel_err(dH1, ref2_dH) <= tol
+
+    # training: gradients of two batches accumulate, one update per iteration
+    hp.apply_sgd(0.0)                                  # clears the accumulators
+    batches = [(synth.seeds(cfg.n_vertices, cfg.batch, s, device=DEV), s) for s in (3, 4)]
+    losses = []
+    for it in range(6):
+        loss = 0.0
+        for sd, key in batches:
+            o = hp.run_batch(sd, key)
+            loss += 0.5 * float((o.double() ** 2).sum().item())
+            hp.backward(0)
+        losses.append(loss)
+        hp.apply_sgd(3e-4)
+    torch.cuda.synchronize()
+    assert all(b < a for a, b in zip(losses, losses[1:])), losses
