@@ -97,6 +97,18 @@ bwd_zero(float4* __restrict__ p, int64_t n4, const int64_t* __restrict__ n_rows_
 // Every load is unconditional from a clamped, in-bounds address and masked when it is written
 // to LDS, which keeps the loop free of branches.  The tile goes to partial[split]; workgroups
 // of the first k-tile row also produce the column sums of dZ.
+// The host sizes the row splits for the capacity; when only the device knows how many rows exist,
+// the rows that do are dealt out evenly over the same number of splits (multiples of 32 rows, never
+// more than the host's figure), so that no split idles while another works through the whole input.
+__device__ __forceinline__ int32_t balanced_split(int32_t rows_per_split, int64_t n_rows, bool device_count,
+                                                  int32_t n_splits) {
+    if (!device_count) return rows_per_split;
+    int64_t need = (n_rows + n_splits - 1) / n_splits;
+    need = (need + 31) / 32 * 32;
+    need = need > 32 ? need : 32;
+    return need < rows_per_split ? (int32_t)need : rows_per_split;
+}
+
 constexpr int kGradTile = 128;
 constexpr int kGradRows = 16;               // contraction rows per LDS chunk
 constexpr int kGradLd = kGradTile + 32;     // LDS row stride: the two rows of one MFMA step sit 32 banks apart
@@ -128,6 +140,7 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
     const uint32_t tk = blockIdx.x / tiles_n, tn = blockIdx.x % tiles_n;
     // rows that exist (n_dst is the capacity: addresses are clamped to it, rows past n_rows are masked)
     const int64_t n_rows = n_rows_dev != nullptr && *n_rows_dev < n_dst ? *n_rows_dev : n_dst;
+    rows_per_split = balanced_split(rows_per_split, n_rows, n_rows_dev != nullptr, (int32_t)gridDim.y);
     const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
     int64_t r1 = r0 + rows_per_split < n_rows ? r0 + rows_per_split : n_rows;
     r1 = r1 > r0 ? r1 : r0;                    // a split past the last row: no chunk, a zero tile
@@ -300,6 +313,7 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     if (split >= n_splits) return;             // uniform over the workgroup
     const uint32_t tk = tile / tiles_n, tn = tile % tiles_n;
     const int64_t n_rows = n_rows_dev != nullptr && *n_rows_dev < n_dst ? *n_rows_dev : n_dst;
+    rows_per_split = balanced_split(rows_per_split, n_rows, n_rows_dev != nullptr, n_splits);
     const int64_t r0 = (int64_t)split * rows_per_split;
     int64_t r1 = r0 + rows_per_split < n_rows ? r0 + rows_per_split : n_rows;
     r1 = r1 > r0 ? r1 : r0;
@@ -1156,12 +1170,17 @@ col_sum_rows(const float* __restrict__ dOut, const typename Tr::store_t* __restr
 
 // out[i] += sum over p < n_parts of partial[p * part_stride + i], i < width, in a fixed order (wave q
 // takes the parts q, q + 4, ...; the four sums are combined as (s0 + s1) + (s2 + s3)): bit-stable.
+// With a device row count only the parts of the rows that exist are summed (rows_per_part rows each).
 __global__ void __launch_bounds__(kBwdThreads)
 reduce_parts_add(const float* __restrict__ partial, int64_t part_stride, int32_t n_parts, int32_t width,
-                 float* __restrict__ out) {
+                 float* __restrict__ out, const int64_t* __restrict__ n_rows_dev, int32_t rows_per_part) {
     __shared__ float part[4][kWave];
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int32_t i = blockIdx.x * kWave + lane;
+    if (n_rows_dev != nullptr) {
+        const int64_t live = (*n_rows_dev + rows_per_part - 1) / rows_per_part;
+        n_parts = live < n_parts ? (int32_t)live : n_parts;
+    }
     float s = 0.f;
     if (i < width)
         for (int32_t p = q; p < n_parts; p += 4) s += partial[(int64_t)p * part_stride + i];
@@ -1253,7 +1272,7 @@ gat_bwd_rows(const float* __restrict__ Z, const float* __restrict__ scores, cons
     }
 }
 
-constexpr int kSrcRows = 64;     // source rows per workgroup of gat_bwd_src
+constexpr int kSrcRows = 256;    // source rows per workgroup of gat_bwd_src
 
 // dz[u] += ds_src[u,h] a_src[h] + ds_dst[u,h] a_dst[h] in place (one thread owns a column of the
 // block's rows), and the block's part of ga_src / ga_dst: partial[b][0][n], partial[b][1][n].
@@ -1324,7 +1343,7 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, const int64_
                            static_cast<const T*>(out_fwd), relu, n_dst, d_out, col);
         HOPGNN_LAUNCH_CHECK();
         hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col,
-                           (int64_t)d_out, parts, d_out, gbias);
+                           (int64_t)d_out, parts, d_out, gbias, nullptr, 0);
         HOPGNN_LAUNCH_CHECK();
     }
     if (n_src == 0) return HOPGNN_OK;              // no entries anywhere: only the bias has a gradient
@@ -1349,10 +1368,10 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, const int64_
                        static_cast<const T*>(a_src), static_cast<const T*>(a_dst), n_src, n_src_dev, d_out, n_heads, dZ, col);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col,
-                       (int64_t)2 * d_out, src_blocks, d_out, ga_src);
+                       (int64_t)2 * d_out, src_blocks, d_out, ga_src, n_src_dev, kSrcRows);
     HOPGNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(reduce_parts_add, dim3((unsigned)ceil_div(d_out, kWave)), dim3(kBwdThreads), 0, s, col + d_out,
-                       (int64_t)2 * d_out, src_blocks, d_out, ga_dst);
+                       (int64_t)2 * d_out, src_blocks, d_out, ga_dst, n_src_dev, kSrcRows);
     HOPGNN_LAUNCH_CHECK();
 
     // gW += Hsrc^T dz: one matrix (k_self = 0), the "aggregate" operand is Hsrc itself, rows = source rows
