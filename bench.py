@@ -36,7 +36,14 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes of the gather kernel per algorithmic byte, by row size in bytes, from rocprofv3 --pmc
 # FETCH_SIZE and WRITE_SIZE runs scaled by a plain copy kernel (profiles/gather_traffic_pmc.txt,
 # profiles/batch_traffic_pmc.txt).  Row sizes without a counter run report no traffic figure.
-GATHER_TRAFFIC_OVER_ALGORITHMIC = {512: 1.012, 400: 1.077}
+# HBM bytes by the profiler's counters (FETCH_SIZE x 2 + WRITE_SIZE, scaled by a plain copy of known
+# size) over algorithmic bytes, per row size, measured on this command's own inputs
+# (profiles/batch_traffic_pmc.txt: workloads 5, 3 and 4)
+GATHER_TRAFFIC_OVER_ALGORITHMIC = {256: 1.008, 400: 1.127, 512: 1.012}
+# the same for the first projection of the fused path: counter bytes per launch over "left operand once +
+# output" (the self half of the operand is read from the gathered rows, which partly stay in cache)
+PROJECT_L1_TRAFFIC_OVER_IO = {3: (116153.2 + 32768.0) * 1024 / (169984 * 200 * 4 + 2 * 16384 * 256 * 4),
+                              4: (68137.1 + 4096.0) * 1024 / (106496 * 512 * 2 + 2 * 4096 * 256 * 2)}
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0, "f16": 2500.0}
 DTYPE_NAME = {"torch.float32": "f32", "torch.bfloat16": "bf16", "torch.float16": "f16"}
 HEADLINE_CONFIG = 3
@@ -384,16 +391,18 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
              "hbm_bytes_operand_once_plus_output": io})
         kernels["project_l%d" % k]["hbm_GBps"] = io / (kernels["project_l%d" % k]["avg_launch_ms"] * 1e-3) * 1e-9
         kernels["project_l%d" % k]["hbm_frac"] = kernels["project_l%d" % k]["hbm_GBps"] / HBM_PEAK_GBPS
+        if k == 1 and hp.fused and group == 1 and cfg_id in PROJECT_L1_TRAFFIC_OVER_IO:
+            kernels["project_l1"]["traffic"] = io * PROJECT_L1_TRAFFIC_OVER_IO[cfg_id]
         if "aggregate_l%d" % k not in stage_ms:
             din = hidden
             continue
         agg_bytes = nnz_valid * din * es + n_dst * din * es + 4.0 * (nnz + n_dst)
         src_bytes = (U_avg if k == 1 else sh.n_dst(k - 1)) * din * es
-        add("aggregate_l%d" % k, "hbm", agg_bytes, HBM_PEAK_GBPS, "GB/s",
+        cached = src_bytes < 256e6 and agg_bytes > 1.5 * src_bytes
+        add("aggregate_l%d" % k, "cache (peak shown is HBM's, for scale)" if cached else "hbm", agg_bytes, HBM_PEAK_GBPS, "GB/s",
             {"kernel": "sage_mean", "rows": n_dst, "valid_entries": nnz_valid, "source_table_bytes": src_bytes,
              "note": ("rows are re-read several times each from a table that fits the 256 MB Infinity Cache: "
-                      "the rate is cache bandwidth, not HBM" if src_bytes < 256e6 and agg_bytes > 1.5 * src_bytes
-                      else "")})
+                      "the rate is cache bandwidth, not HBM" if cached else "")})
         din = hidden
     # the kernel that takes the largest share of a step
     share = {n: r["avg_launch_ms"] * (runs if n.startswith(("project", "aggregate")) else 1)

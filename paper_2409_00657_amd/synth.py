@@ -16,6 +16,7 @@ All generators return torch tensors on ``device``.
 from __future__ import annotations
 
 import math
+import os
 from dataclasses import dataclass, field
 from typing import List, Optional
 
@@ -237,17 +238,40 @@ class Config:
     scale: int = 0
     groups: List[int] = field(default_factory=lambda: [1])
 
+    def _cache_file(self, what: str, seed: int, device) -> Optional[str]:
+        """Where HOPGNN_SYNTH_CACHE=<dir> keeps a generated input (None: no cache).  The generators are
+        deterministic, so a cached tensor is the generated one; the cache exists so that a run under a
+        counter-collecting profiler need not execute the generators' kernels."""
+        d = os.environ.get("HOPGNN_SYNTH_CACHE")
+        if not d:
+            return None
+        os.makedirs(d, exist_ok=True)
+        kind = torch.device(device).type
+        return os.path.join(d, "%s-%s-%x-%s.pt" % (self.name, what, seed, kind))
+
     def make_graph(self, seed=DEFAULT_SEED, device="cpu") -> Graph:
+        path = self._cache_file("graph", seed, device)
+        if path and os.path.exists(path):
+            t = torch.load(path, map_location="cpu", weights_only=True)
+            return Graph(self.n_vertices, t["offsets"].to(device), t["indices"].to(device), self.graph)
         if self.graph == "uniform":
-            return uniform_graph(self.n_vertices, 8, 16, seed, device, self.offsets_i64)
-        if self.graph == "rmat":
-            return rmat_graph(self.scale, self.avg_degree, seed=seed, device=device,
-                              offsets_i64=self.offsets_i64)
-        return chung_lu_graph(self.n_vertices, self.avg_degree, self.gamma, seed, device,
-                              self.offsets_i64)
+            g = uniform_graph(self.n_vertices, 8, 16, seed, device, self.offsets_i64)
+        elif self.graph == "rmat":
+            g = rmat_graph(self.scale, self.avg_degree, seed=seed, device=device, offsets_i64=self.offsets_i64)
+        else:
+            g = chung_lu_graph(self.n_vertices, self.avg_degree, self.gamma, seed, device, self.offsets_i64)
+        if path:
+            torch.save({"offsets": g.offsets.cpu(), "indices": g.indices.cpu()}, path)
+        return g
 
     def make_features(self, seed=DEFAULT_SEED, device="cpu") -> torch.Tensor:
-        return features(self.n_vertices, self.d, self.dtype, seed, device)
+        path = self._cache_file("features", seed, device)
+        if path and os.path.exists(path):
+            return torch.load(path, map_location="cpu", weights_only=True).to(device)
+        X = features(self.n_vertices, self.d, self.dtype, seed, device)
+        if path:
+            torch.save(X.cpu(), path)
+        return X
 
     def make_weights(self, seed=DEFAULT_SEED, device="cpu"):
         return sage_weights(self.d, self.hidden, len(self.fanouts), self.dtype, seed, device)
