@@ -288,11 +288,18 @@ bwd_weight_grad(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __
 // split run on one XCD at about the same time (workgroup b goes to XCD b % 8): the split's rows
 // then come out of that XCD's L2 for every tile but the first.
 // Requires d_in % 8 == 0 and d_out % 4 == 0 and 16-byte aligned operands (the caller checks).
+//
+// The workgroup's shape is a template parameter: WK x WN waves, each a (32 TM) x (32 TN) piece of G,
+// so a tile of KT = 32 WK TM rows of G (feature columns of A) by NTL = 32 WN TN columns.  Every
+// operand an MFMA consumes costs the same LDS reads and packing whatever it is multiplied with,
+// and every staged element the same loads, masks and conversions, so the instruction count per
+// MFMA falls with the piece a wave owns; and dZ (fp32, plus the 2-byte mask source: 6 of every 8
+// operand bytes) is re-read once per tile row of G.  Wide layers therefore take all of K in one
+// workgroup (4 x 2 waves of 128 x 64: dZ is read once), narrower ones 256 or 128 rows of G.
 constexpr int kG16Rows = 32;
-constexpr int kG16Ld = kGradTile + 4;       // in 2-byte elements
 
-template <typename Tr, bool MASK>
-__global__ void __launch_bounds__(kBwdThreads)
+template <typename Tr, bool MASK, int WK, int WN, int TM, int TN>
+__global__ void __launch_bounds__(64 * WK * WN)
 bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
                   const typename Tr::store_t* __restrict__ Mean, const float* __restrict__ dZ,
                   const typename Tr::store_t* __restrict__ OutFwd, int64_t n_dst, int32_t d_in, int32_t d_out,
@@ -300,11 +307,20 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
                   float* __restrict__ partial, float* __restrict__ bias_partial,
                   const int64_t* __restrict__ n_rows_dev, int32_t k_self) {
     using T = typename Tr::store_t;
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][kG16Rows][kG16Ld];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kG16Rows][kG16Ld];
+    constexpr int NT = 64 * WK * WN;                 // threads
+    constexpr int KT = 32 * WK * TM, NTL = 32 * WN * TN;
+    constexpr int LDA = KT + 4, LDB = NTL + 4;       // 2-byte elements; rows 8 apart sit 64 bytes apart in the banks
+    constexpr int A_PER_ROW = KT / 8, B_PER_ROW = NTL / 4;
+    constexpr int A_ITEMS = kG16Rows * A_PER_ROW / NT, B_ITEMS = kG16Rows * B_PER_ROW / NT;
+    constexpr int A_ROWS = NT / A_PER_ROW, B_ROWS = NT / B_PER_ROW;     // rows one round of the threads covers
+    static_assert(NT % A_PER_ROW == 0 && NT % B_PER_ROW == 0 && A_ITEMS >= 1 && B_ITEMS >= 1, "chunk shares");
+    static_assert(A_ITEMS * A_ROWS == kG16Rows && B_ITEMS * B_ROWS == kG16Rows, "chunk shares");
+    static_assert(B_ROWS * NTL * 4 <= 2 * kG16Rows * LDA * 2, "column sums fit the A stage");
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][kG16Rows][LDA];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kG16Rows][LDB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = lane >> 5, l32 = lane & 31;
-    const int wk = wave >> 1, wn = wave & 1;
+    const int wk = wave / WN, wn = wave % WN;
     const int K = k_self + d_in;
     // workgroup -> (tile, split): XCD x takes the splits x, x + 8, ... and runs each split's tiles back to back
     const uint32_t xcd = blockIdx.x & 7u, seq = blockIdx.x >> 3;
@@ -319,11 +335,11 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     r1 = r1 > r0 ? r1 : r0;
     const int n_chunks = (int)((r1 - r0 + kG16Rows - 1) / kG16Rows);
 
-    // this thread's part of every chunk: A rows ar, ar + 16 (8 elements each), dZ rows br + 8 i (4 each)
-    const int ar = tid >> 4, ac = (tid & 15) * 8;
-    const int br = tid >> 5, bc = (tid & 31) * 4;
-    const int ka = (int)tk * kGradTile + ac;
-    const int nb = (int)tn * kGradTile + bc;
+    // this thread's part of every chunk: A rows ar + A_ROWS i (8 elements each), dZ rows br + B_ROWS i (4 each)
+    const int ar = tid / A_PER_ROW, ac = (tid % A_PER_ROW) * 8;
+    const int br = tid / B_PER_ROW, bc = (tid % B_PER_ROW) * 4;
+    const int ka = (int)tk * KT + ac;
+    const int nb = (int)tn * NTL + bc;
     const bool ka_ok = ka < K, nb_ok = nb < d_out;
     const int nbc = nb_ok ? nb : 0;
     // this thread's A columns come from the self rows or from the means, the same for every chunk
@@ -331,31 +347,31 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     const T* a_base = a_self ? Hsrc + ka : Mean + (ka_ok ? ka - k_self : 0);
 
     auto self_of = [&](int chunk, int i) -> int32_t {
-        int64_t r = r0 + (int64_t)chunk * kG16Rows + ar + 16 * i;
+        int64_t r = r0 + (int64_t)chunk * kG16Rows + ar + A_ROWS * i;
         r = r < n_dst ? r : n_dst - 1;
-        return self_idx != nullptr ? self_idx[r] : (int32_t)r;
+        return self_idx != nullptr && a_self ? self_idx[r] : (int32_t)r;
     };
     // One chunk's loads in flight.  Every load is unconditional from a clamped, in-bounds address;
     // what must not count is zeroed when the chunk goes to LDS.
     struct Frag {
-        uint4 a[2];
-        float4 b[4];
-        uint2 o[4];
-        bool a_ok[2];
+        uint4 a[A_ITEMS];
+        float4 b[B_ITEMS];
+        uint2 o[B_ITEMS];
+        bool a_ok[A_ITEMS];
     };
-    auto load = [&](int chunk, const int32_t (&sidx)[2], Frag& f) {
+    auto load = [&](int chunk, const int32_t (&sidx)[A_ITEMS], Frag& f) {
         const int64_t base = r0 + (int64_t)chunk * kG16Rows;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            int64_t r = base + ar + 16 * i;
+        for (int i = 0; i < A_ITEMS; ++i) {
+            int64_t r = base + ar + A_ROWS * i;
             f.a_ok[i] = r < r1 && ka_ok && (!a_self || sidx[i] >= 0);
             r = r < n_dst ? r : n_dst - 1;
             const int64_t srow = sidx[i] > 0 ? sidx[i] : 0;
             f.a[i] = *reinterpret_cast<const uint4*>(a_base + (a_self ? srow : r) * d_in);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int64_t r = base + br + 8 * i;
+        for (int i = 0; i < B_ITEMS; ++i) {
+            int64_t r = base + br + B_ROWS * i;
             r = r < n_dst ? r : n_dst - 1;
             f.b[i] = *reinterpret_cast<const float4*>(dZ + r * d_out + nbc);
             if (MASK) f.o[i] = *reinterpret_cast<const uint2*>(OutFwd + r * d_out + nbc);
@@ -365,15 +381,15 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     auto store = [&](int chunk, const Frag& f, int buf) {
         const int64_t base = r0 + (int64_t)chunk * kG16Rows;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < A_ITEMS; ++i) {
             const uint4 v = f.a_ok[i] ? f.a[i] : make_uint4(0u, 0u, 0u, 0u);
-            uint2* dst = reinterpret_cast<uint2*>(&As[buf][ar + 16 * i][ac]);
+            uint2* dst = reinterpret_cast<uint2*>(&As[buf][ar + A_ROWS * i][ac]);
             dst[0] = make_uint2(v.x, v.y);
             dst[1] = make_uint2(v.z, v.w);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const bool ok = base + br + 8 * i < r1 && nb_ok;
+        for (int i = 0; i < B_ITEMS; ++i) {
+            const bool ok = base + br + B_ROWS * i < r1 && nb_ok;
             float bv[4] = {f.b[i].x, f.b[i].y, f.b[i].z, f.b[i].w};
             if (MASK) {
                 union { uint2 v; T e[4]; } o;
@@ -386,22 +402,22 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
                 bv[e] = ok ? bv[e] : 0.f;
                 colsum[e] += bv[e];
             }
-            *reinterpret_cast<uint2*>(&Bs[buf][br + 8 * i][bc]) = make_uint2(Tr::pack2(bv[0], bv[1]), Tr::pack2(bv[2], bv[3]));
+            *reinterpret_cast<uint2*>(&Bs[buf][br + B_ROWS * i][bc]) = make_uint2(Tr::pack2(bv[0], bv[1]), Tr::pack2(bv[2], bv[3]));
         }
     };
     // 8 values down a column, rows row0 .. row0 + 7, as one MFMA operand
-    auto column8 = [&](const uint16_t (&S)[kG16Rows][kG16Ld], int row0, int col) -> uint4 {
+    auto column8 = [&](const uint16_t* S, int ld, int row0, int col) -> uint4 {
         union { uint4 v; uint16_t e[8]; } u;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) u.e[e] = S[row0 + e][col];
+        for (int e = 0; e < 8; ++e) u.e[e] = S[(row0 + e) * ld + col];
         return u.v;
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[TM][TN];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
@@ -410,40 +426,47 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     // indices run one chunk ahead of the loads.  (Two chunks in flight cost a resident workgroup per
     // CU in registers and measured slower.)
     Frag f;
-    int32_t s_nxt[2];
+    int32_t s_nxt[A_ITEMS];
     {
-        const int32_t s_cur[2] = {self_of(0, 0), self_of(0, 1)};
+        int32_t s_cur[A_ITEMS];
+#pragma unroll
+        for (int i = 0; i < A_ITEMS; ++i) s_cur[i] = self_of(0, i);
         load(0, s_cur, f);
-        s_nxt[0] = self_of(1, 0);
-        s_nxt[1] = self_of(1, 1);
+#pragma unroll
+        for (int i = 0; i < A_ITEMS; ++i) s_nxt[i] = self_of(1, i);
     }
     store(0, f, 0);
     lds_barrier();
     for (int c = 0; c < n_chunks; ++c) {
         const int buf = c & 1;
-        const int32_t s_cur[2] = {s_nxt[0], s_nxt[1]};
+        int32_t s_cur[A_ITEMS];
+#pragma unroll
+        for (int i = 0; i < A_ITEMS; ++i) s_cur[i] = s_nxt[i];
         load(c + 1, s_cur, f);
-        s_nxt[0] = self_of(c + 2, 0);
-        s_nxt[1] = self_of(c + 2, 1);
+#pragma unroll
+        for (int i = 0; i < A_ITEMS; ++i) s_nxt[i] = self_of(c + 2, i);
 #pragma unroll
         for (int kk = 0; kk < kG16Rows; kk += 16) {
-            const uint4 a0 = column8(As[buf], kk + 8 * g, wk * 64 + l32), a1 = column8(As[buf], kk + 8 * g, wk * 64 + 32 + l32);
-            const uint4 b0 = column8(Bs[buf], kk + 8 * g, wn * 64 + l32), b1 = column8(Bs[buf], kk + 8 * g, wn * 64 + 32 + l32);
-            acc[0][0] = mfma16<Tr>(a0, b0, acc[0][0]);
-            acc[0][1] = mfma16<Tr>(a0, b1, acc[0][1]);
-            acc[1][0] = mfma16<Tr>(a1, b0, acc[1][0]);
-            acc[1][1] = mfma16<Tr>(a1, b1, acc[1][1]);
+            uint4 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = column8(&As[buf][0][0], LDA, kk + 8 * g, (wk * TM + i) * 32 + l32);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = column8(&Bs[buf][0][0], LDB, kk + 8 * g, (wn * TN + j) * 32 + l32);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = mfma16<Tr>(a[i], b[j], acc[i][j]);
         }
         store(c + 1, f, buf ^ 1);
         lds_barrier();
     }
 
-    const int k0 = (int)tk * kGradTile + wk * 64, n0 = (int)tn * kGradTile + wn * 64;
+    const int k0 = (int)tk * KT + wk * TM * 32, n0 = (int)tn * NTL + wn * TN * 32;
     float* P = partial + (int64_t)split * K * d_out;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < TN; ++j) {
             const int n = n0 + j * 32 + l32;
             if (n >= d_out) continue;
 #pragma unroll
@@ -453,21 +476,24 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
             }
         }
     if (bias_partial != nullptr && tk == 0) {
-        // the eight row groups' sums of every column, added in a fixed order (the staging tiles are free:
+        // the row groups' sums of every column, added in a fixed order (the staging tiles are free:
         // the loop's last barrier is behind every read of them)
-        float* cs = reinterpret_cast<float*>(&As[0][0][0]);      // [8][128]
+        float* cs = reinterpret_cast<float*>(&As[0][0][0]);      // [B_ROWS][NTL]
 #pragma unroll
-        for (int e = 0; e < 4; ++e) cs[br * kGradTile + bc + e] = colsum[e];
+        for (int e = 0; e < 4; ++e) cs[br * NTL + bc + e] = colsum[e];
         lds_barrier();
-        if (tid < kGradTile) {
+        if (tid < NTL) {
             float t = 0.f;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) t += cs[q * kGradTile + tid];
-            const int n = (int)tn * kGradTile + tid;
+            for (int q = 0; q < B_ROWS; ++q) t += cs[q * NTL + tid];
+            const int n = (int)tn * NTL + tid;
             if (n < d_out) bias_partial[(int64_t)split * d_out + n] = t;
         }
     }
 }
+
+// Shape of the 2-byte weight-gradient workgroup for K rows of G: rows of G per tile.
+static inline int grad16_tile_k(int64_t K) { return K > 256 ? 512 : K > 128 ? 256 : 128; }
 
 // gW += sum over the splits of the partial tiles; same for the bias.  A workgroup owns 64
 // consecutive elements; wave q sums the splits q, q+4, q+8, ... in that order and the four
@@ -863,7 +889,7 @@ struct BwdWs {
     int32_t rows_per_split, n_splits;
 };
 
-static BwdWs bwd_ws_layout(int64_t n_dst, int32_t d_in, int32_t d_out, int want_dh) {
+static BwdWs bwd_ws_layout(int64_t n_dst, int32_t d_in, int32_t d_out, int want_dh, bool two_byte = false) {
     BwdWs L{};
     const int64_t nd = n_dst > 0 ? n_dst : 1;
     L.mean_bytes = align_up((size_t)nd * d_in * 4, 256);
@@ -871,8 +897,15 @@ static BwdWs bwd_ws_layout(int64_t n_dst, int32_t d_in, int32_t d_out, int want_
     L.dz_bytes = align_up((size_t)nd * d_out * 4, 256);
     // enough splits to fill the chip (about 2048 waves), at least 128 rows each so that the
     // partial tiles stay small next to the operands
-    const int64_t tiles = ceil_div(2 * (int64_t)d_in, kGradTile) * ceil_div(d_out, kGradTile);
+    int64_t tiles = ceil_div(2 * (int64_t)d_in, kGradTile) * ceil_div(d_out, kGradTile);
     int64_t splits = ceil_div(512, tiles);
+    if (two_byte && d_in % 8 == 0 && d_out % 4 == 0) {
+        // the 2-byte kernel's tiles are taller; its 8-wave workgroups fill a CU alone (256 of them), the
+        // 4-wave ones two to a CU
+        const int kt = grad16_tile_k(2 * (int64_t)d_in);
+        tiles = ceil_div(2 * (int64_t)d_in, kt) * ceil_div(d_out, kGradTile);
+        splits = ceil_div(kt == 512 ? 256 : 512, tiles);
+    }
     int64_t rows = ceil_div(nd, splits);
     if (rows < 128) rows = 128;
     rows = (rows + kGradRows - 1) / kGradRows * kGradRows;
@@ -892,7 +925,7 @@ using namespace hopgnn;
 extern "C" size_t hopgnn_sage_bwd_ws_bytes(hopgnn_dtype dt, int64_t n_dst, int32_t d_in, int32_t d_out,
                                            int32_t want_dh) {
     if ((dt != HOPGNN_F32 && dt != HOPGNN_BF16 && dt != HOPGNN_F16) || n_dst < 0 || d_in < 1 || d_out < 1) return 0;
-    return bwd_ws_layout(n_dst, d_in, d_out, want_dh).total;
+    return bwd_ws_layout(n_dst, d_in, d_out, want_dh, dt != HOPGNN_F32).total;
 }
 
 namespace hopgnn {
@@ -905,6 +938,32 @@ struct BwdKind {
     int32_t scatter;     // kScatter*
     int32_t norm;        // GCN-style: divide by the number of terms
 };
+
+// Launch of the 2-byte weight-gradient kernel in the shape that fits K rows of G.
+template <typename Tr, bool MASK>
+static void launch_weight_grad16(hipStream_t s, const typename Tr::store_t* Hsrc, const int32_t* self_idx,
+                                 const typename Tr::store_t* mean, const float* dZ, const typename Tr::store_t* out_fwd,
+                                 int64_t n_rows, int32_t d_in, int32_t d_out, const BwdWs& L, float* partial,
+                                 float* bias_partial, const int64_t* n_rows_dev, int32_t k_self) {
+    const int64_t K = (int64_t)k_self + d_in;
+    const int kt = grad16_tile_k(K);
+    const uint32_t tiles_n = (uint32_t)ceil_div(d_out, kGradTile);
+    const uint32_t n_tiles = (uint32_t)ceil_div(K, kt) * tiles_n;
+    const uint32_t splits8 = (uint32_t)ceil_div(L.n_splits, 8) * 8u;
+    const dim3 grid(n_tiles * splits8);
+    if (kt == 512)
+        hipLaunchKernelGGL((bwd_weight_grad16<Tr, MASK, 4, 2, 4, 2>), grid, dim3(512), 0, s, Hsrc, self_idx, mean, dZ, out_fwd,
+                           n_rows, d_in, d_out, L.rows_per_split, tiles_n, n_tiles, L.n_splits, partial, bias_partial,
+                           n_rows_dev, k_self);
+    else if (kt == 256)
+        hipLaunchKernelGGL((bwd_weight_grad16<Tr, MASK, 2, 2, 4, 2>), grid, dim3(256), 0, s, Hsrc, self_idx, mean, dZ, out_fwd,
+                           n_rows, d_in, d_out, L.rows_per_split, tiles_n, n_tiles, L.n_splits, partial, bias_partial,
+                           n_rows_dev, k_self);
+    else
+        hipLaunchKernelGGL((bwd_weight_grad16<Tr, MASK, 2, 2, 2, 2>), grid, dim3(256), 0, s, Hsrc, self_idx, mean, dZ, out_fwd,
+                           n_rows, d_in, d_out, L.rows_per_split, tiles_n, n_tiles, L.n_splits, partial, bias_partial,
+                           n_rows_dev, k_self);
+}
 
 template <typename Tr>
 static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_in, const int32_t* self_idx,
@@ -963,12 +1022,14 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
         // the 2-byte matrix instructions, when every 8-element run of A and 4-element run of dZ is whole
         on16 = vec && d_in % 8 == 0;
         if (on16) {
-            auto k16 = fuse_mask ? bwd_weight_grad16<Tr, true> : bwd_weight_grad16<Tr, false>;
-            const uint32_t n_tiles = tiles_k * tiles_n;
-            const uint32_t splits8 = (uint32_t)ceil_div(L.n_splits, 8) * 8u;
-            hipLaunchKernelGGL(k16, dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s, static_cast<const T*>(Hsrc), self_idx,
-                               mean, dZ, static_cast<const T*>(out_fwd), n_dst, d_in, d_out, L.rows_per_split, tiles_n,
-                               n_tiles, L.n_splits, partial, gbias != nullptr ? bias_partial : nullptr, n_dst_dev, k_self);
+            float* bp = gbias != nullptr ? bias_partial : nullptr;
+            if (fuse_mask)
+                launch_weight_grad16<Tr, true>(s, static_cast<const T*>(Hsrc), self_idx, mean, dZ,
+                                               static_cast<const T*>(out_fwd), n_dst, d_in, d_out, L, partial, bp, n_dst_dev,
+                                               k_self);
+            else
+                launch_weight_grad16<Tr, false>(s, static_cast<const T*>(Hsrc), self_idx, mean, dZ, nullptr, n_dst, d_in,
+                                                d_out, L, partial, bp, n_dst_dev, k_self);
         }
     }
     if (!on16) {
@@ -1112,7 +1173,7 @@ static hopgnn_status sage_bwd_any(const void* Hsrc, hopgnn_dtype dt, int64_t n_s
     if (n_src > 0 && Hsrc == nullptr) return HOPGNN_EINVAL;
     if (self_idx == nullptr && n_src < n_dst) return HOPGNN_EINVAL;   // identity self rows must exist
     if (!aligned(ws, 256)) return HOPGNN_EINVAL;
-    const BwdWs L = bwd_ws_layout(n_dst, d_in, d_out, dHsrc != nullptr);
+    const BwdWs L = bwd_ws_layout(n_dst, d_in, d_out, dHsrc != nullptr, dt != HOPGNN_F32);
     if (ws_bytes < L.total) return HOPGNN_ENOMEM_WS;
     if (dt == HOPGNN_F32)
         return sage_bwd_typed<TrF32>(Hsrc, n_src, d_in, self_idx, indptr, idx, n_dst, W_self, W_neigh, out_fwd, relu, dOut,
@@ -1313,7 +1374,7 @@ static GatBwdWs gat_bwd_ws_layout(int64_t n_src, int64_t n_dst, int32_t d_in, in
     L.ds_bytes = align_up((size_t)ns * 2 * n_heads * 4, 256);
     const int64_t parts = ceil_div(nd, kColRows) > 2 * ceil_div(ns, kSrcRows) ? ceil_div(nd, kColRows) : 2 * ceil_div(ns, kSrcRows);
     L.col_bytes = align_up((size_t)parts * d_out * 4, 256);
-    L.G = bwd_ws_layout(ns, d_in, d_out, 0);
+    L.G = bwd_ws_layout(ns, d_in, d_out, 0);      // (row splits as for fp32 operands: any count is valid)
     L.total = L.dz_bytes + L.ds_bytes + L.col_bytes + L.G.partial_bytes + L.G.bias_bytes;
     return L;
 }
@@ -1381,11 +1442,8 @@ static hopgnn_status gat_bwd_typed(const void* Hsrc, int64_t n_src, const int64_
     if constexpr (sizeof(T) == 2) {
         on16 = vec && d_in % 8 == 0;
         if (on16) {
-            const uint32_t n_tiles = tiles_k * tiles_n;
-            const uint32_t splits8 = (uint32_t)ceil_div(L.G.n_splits, 8) * 8u;
-            hipLaunchKernelGGL((bwd_weight_grad16<Tr, false>), dim3(n_tiles * splits8), dim3(kBwdThreads), 0, s,
-                               static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr, n_src, d_in,
-                               d_out, L.G.rows_per_split, tiles_n, n_tiles, L.G.n_splits, partial, nullptr, n_src_dev, 0);
+            launch_weight_grad16<Tr, false>(s, static_cast<const T*>(Hsrc), nullptr, static_cast<const T*>(Hsrc), dZ, nullptr,
+                                            n_src, d_in, d_out, L.G, partial, nullptr, n_src_dev, 0);
         }
     }
     if (!on16) {
