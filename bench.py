@@ -78,7 +78,7 @@ def parse():
                          "projection also form the next layer's neighbour means from the slot tree's shape")
     ap.add_argument("--dedup", action="store_true",
                     help="sample per-micrograph deduplicated frontiers (hopgnn_sample_dedup): the same rows for the "
-                         "seeds over fewer rows below them; one batch per pre-gather, forward only")
+                         "seeds over fewer rows below them (with --backward: GraphSAGE-mean training steps)")
     ap.add_argument("--layerwise", action="store_true",
                     help="layer-wise sampled micrographs (the shape's fanouts are the budgets of draws per level)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -603,6 +603,7 @@ int orc_sage_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, const
                  const void *W_neigh, const void *out_fwd, int32_t relu, const double *dOut,
                  int32_t d_out, double *gW_self, double *gW_neigh, double *gbias, double *dHsrc)
 {
+    (void)n_src;
     double *xs = (double *)malloc(sizeof(double) * (size_t)d_in);
     double *mn = (double *)malloc(sizeof(double) * (size_t)d_in);
     double *dz = (double *)malloc(sizeof(double) * (size_t)d_out);
@@ -669,6 +670,7 @@ int orc_sage_agg_bwd(const void *Hsrc, int dtype, int64_t n_src, int32_t d_in, c
                      const double *dOut, int32_t d_out, double *gW_self, double *gW_neigh,
                      double *gbias, double *dHsrc)
 {
+    (void)n_src;
     if (agg < 0 || agg > 2) return 1;
     double *xs = (double *)malloc(sizeof(double) * (size_t)d_in);
     double *a = (double *)malloc(sizeof(double) * (size_t)d_in);
