@@ -146,12 +146,18 @@ constexpr int kMeanUnroll = 4;
 // entries (negative index) are skipped by predication, which measured faster than
 // reading a stand-in row and masking it out (whole dead micrographs are common on
 // graphs with isolated vertices).  The sum runs in entry order.
+// Consecutive workgroups' rows that one XCD takes in a row.  Aggregation of the first layer, one
+// stream, 1 (plain round robin) / 4 / 16 / 64 / 256: 56.3 / 52.1 / 46.8 / 46.9 / 46.6 us on 170 k rows of
+// 400 bytes with fanouts 15, 10, 5; 43.4 / 41.9 / 41.4 / 41.5 / 48.9 us on 106 k rows of 512 bytes (fanouts
+// 25, 10: long runs leave the XCDs with unequal levels); 149 / 147 / 145 / 146 / 146 us on 455 k rows of 256 bytes.
+constexpr int kMeanXcdRun = 16;
+
 template <typename Tr, int OP>
 __global__ void __launch_bounds__(kMeanThreads)
 sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr,
               const int32_t* __restrict__ idx, int64_t n_dst, int32_t words_per_row, int32_t group,
               uint4* __restrict__ Mean, uint32_t* __restrict__ zero_row, int32_t zero_words, TransposeJob job,
-              AggSpec agg, const int64_t* __restrict__ n_rows_dev) {
+              AggSpec agg, const int64_t* __restrict__ n_rows_dev, uint32_t xcd_run) {
     if (blockIdx.x >= job.first_block) {
         transpose_w_tile(job, blockIdx.x - job.first_block);
         return;
@@ -162,7 +168,14 @@ sage_mean_vec(const uint4* __restrict__ Hsrc, const int32_t* __restrict__ indptr
         const int64_t live = *n_rows_dev;
         n_dst = live < n_dst ? live : n_dst;
     }
-    const int64_t gid = ((int64_t)blockIdx.x * kMeanThreads + threadIdx.x);
+    // Workgroup b runs on XCD b % 8, each with an L2 of its own.  Rows that are near each other in slot
+    // order (one micrograph's) read many of the same source rows, so the XCDs take turns at runs of
+    // kMeanXcdRun consecutive workgroups' worth of rows instead of single ones: a source row a
+    // micrograph reads several times is then fetched into one L2 instead of eight, while every XCD
+    // still sees every level of the tree.  (first_block is a multiple of 8 * kMeanXcdRun.)
+    const uint32_t seq = blockIdx.x >> 3;
+    const int64_t lb = ((int64_t)(seq / xcd_run) * 8 + (blockIdx.x & 7u)) * xcd_run + seq % xcd_run;
+    const int64_t gid = (lb * kMeanThreads + threadIdx.x);
     const int64_t r = gid / group;
     const int32_t g = (int32_t)(gid - r * group);
     if (r >= n_dst) return;
@@ -270,7 +283,8 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
     const int group = mean_group(units);
-    const int64_t mean_blocks = ceil_div(n_dst * group, kMeanThreads);
+    constexpr int xcd_run = kMeanXcdRun;
+    const int64_t mean_blocks = ceil_div(ceil_div(n_dst * group, kMeanThreads), 8 * xcd_run) * (8 * xcd_run);
     if (mean_blocks + n_transpose_tiles >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
     job.first_block = (uint32_t)mean_blocks;
     const int64_t blocks = mean_blocks + n_transpose_tiles;
@@ -282,7 +296,7 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
         hipLaunchKernelGGL(kv, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const uint4*>(Hsrc), indptr, idx, n_dst, units, group,
                            static_cast<uint4*>(mean), static_cast<uint32_t*>(zero_row), (int32_t)(zero_bytes / 4), job,
-                           agg, n_rows_dev);
+                           agg, n_rows_dev, (uint32_t)xcd_run);
     else
         hipLaunchKernelGGL(ke, dim3((unsigned)blocks), dim3(kMeanThreads), 0, s,
                            static_cast<const T*>(Hsrc), indptr, idx, n_dst, d_in, group,

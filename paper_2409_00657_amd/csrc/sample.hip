@@ -7,6 +7,8 @@
 // all micrographs run in a single launch.  Work per slot is two dependent
 // random reads (row bounds, then one neighbour) - latency bound, hidden by
 // keeping every micrograph's workgroup resident at once.
+#include <type_traits>
+
 #include "pregather_internal.hpp"
 
 namespace hopgnn {
@@ -37,12 +39,14 @@ struct BatchKeys {
     uint64_t keyed[kMaxBatchesPerLaunch];
 };
 
+constexpr int kSampleUnroll = 4;
+
 template <typename OffT>
 __global__ void __launch_bounds__(256)
 sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__ indices,
                    const int32_t* __restrict__ seeds, int32_t n_seeds, SampleShape sh,
                    BatchKeys keys, int32_t* ids, int32_t* indptr, int32_t* slot_idx, int64_t slot_idx_stride,
-                   uint8_t* __restrict__ present, int32_t m_offset, int32_t seeds_per_key) {
+                   uint8_t* __restrict__ present, int32_t m_offset, int32_t seeds_per_key, int32_t has_edges) {
     // Two ways to carry several keys: blockIdx.y = one batch (own seeds, key and output slices) of
     // n_seeds micrographs each, or ONE level-major batch whose micrographs m_offset + blockIdx.x
     // take the key of their block of seeds_per_key consecutive seeds (then gridDim.y = 1).
@@ -65,31 +69,61 @@ sample_micrographs(const OffT* __restrict__ offsets, const int32_t* __restrict__
         const int32_t P = sh.P[h];
         const int32_t* parents = ids + sh.base[h - 1] + (int64_t)m * sh.P[h - 1];
         int32_t* children = ids + sh.base[h] + (int64_t)m * P;
-        for (uint32_t c = threadIdx.x; c < (uint32_t)P; c += blockDim.x) {
-            const uint32_t q = c / f;
-            const uint32_t j = c - q * f;
-            const int32_t v = (h == 1) ? root : parents[q];
-            int32_t child = -1;
-            if (v >= 0) {
-                const int64_t o0 = (int64_t)offsets[v];
-                const int64_t deg = (int64_t)offsets[(int64_t)v + 1] - o0;
-                if (deg > 0) {
-                    uint64_t x = finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v)) +
-                                            0x9E3779B97F4A7C15ull);
-                    x = finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j)) + 0x9E3779B97F4A7C15ull);
-                    child = indices[o0 + (int64_t)mod_u64(x, (uint64_t)deg)];
+        // Several slots per thread and round: every slot is a chain of dependent random reads
+        // (parent, its two row bounds, one neighbour), so the chains of a round are issued side by
+        // side - all bounds, then all neighbours - instead of one after the other.  Loads are
+        // unconditional from clamped, in-bounds addresses; what must not count is masked afterwards.
+        auto level = [&](auto unroll) {
+        constexpr int U = decltype(unroll)::value;
+        for (uint32_t c0 = threadIdx.x; c0 < (uint32_t)P; c0 += blockDim.x * U) {
+            uint32_t q[U], j[U];
+            int32_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t c = c0 + u * blockDim.x;
+                const uint32_t cc = c < (uint32_t)P ? c : 0u;
+                q[u] = cc / f;
+                j[u] = cc - q[u] * f;
+                v[u] = (h == 1) ? root : parents[q[u]];
+                if (c >= (uint32_t)P) v[u] = -1;
+            }
+            int64_t o0[U], deg[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t vv = v[u] >= 0 ? v[u] : 0;
+                o0[u] = has_edges ? (int64_t)offsets[vv] : 0;             // no edges: no vertex has a row to read
+                deg[u] = has_edges ? (int64_t)offsets[vv + 1] - o0[u] : 0;
+                if (v[u] < 0) deg[u] = 0;
+            }
+            int32_t child[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint64_t x = finalise64((keyed ^ (((uint64_t)(uint32_t)root << 32) | (uint32_t)v[u])) +
+                                        0x9E3779B97F4A7C15ull);
+                x = finalise64((x ^ (((uint64_t)(uint32_t)h << 32) | j[u])) + 0x9E3779B97F4A7C15ull);
+                const int64_t e = deg[u] > 0 ? o0[u] + (int64_t)mod_u64(x, (uint64_t)deg[u]) : 0;
+                child[u] = has_edges ? indices[e] : -1;
+                if (deg[u] <= 0) child[u] = -1;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint32_t c = c0 + u * blockDim.x;
+                if (c >= (uint32_t)P) continue;
+                children[c] = child[u];
+                if (present != nullptr && child[u] >= 0) present[child[u]] = 1;
+                if (slot_idx != nullptr && h < sh.n_layers) {   // non-leaf child: its own row in later layers
+                    const int32_t slot = sh.base[h] + m * P + (int32_t)c;
+                    slot_idx[slot - B] = child[u] >= 0 ? slot : -1;
                 }
+                if (indptr != nullptr && j[u] == 0)
+                    indptr[sh.base[h - 1] + m * sh.P[h - 1] + (int32_t)q[u]] =
+                        sh.base[h] + (m * sh.P[h - 1] + (int32_t)q[u]) * (int32_t)f - B;
             }
-            children[c] = child;
-            if (present != nullptr && child >= 0) present[child] = 1;
-            if (slot_idx != nullptr && h < sh.n_layers) {   // non-leaf child: its own row in later layers
-                const int32_t slot = sh.base[h] + m * P + (int32_t)c;
-                slot_idx[slot - B] = child >= 0 ? slot : -1;
-            }
-            if (indptr != nullptr && j == 0)
-                indptr[sh.base[h - 1] + m * sh.P[h - 1] + (int32_t)q] =
-                    sh.base[h] + (m * sh.P[h - 1] + (int32_t)q) * (int32_t)f - B;
         }
+        };
+        // a level no wider than the workgroup has one slot per thread: nothing to batch
+        if ((uint32_t)P > blockDim.x) level(std::integral_constant<int, kSampleUnroll>{});
+        else level(std::integral_constant<int, 1>{});
         __syncthreads();   // this level is visible to the whole workgroup before the next hop
     }
 }
@@ -159,11 +193,11 @@ hopgnn_status sample_batches(const hopgnn_csr* g, const int32_t* seeds, int32_t 
         if (g->offsets_i64)
             hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
                                static_cast<const int64_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride, present, 0, n_seeds);
+                               slot_idx_stride, present, 0, n_seeds, g->n_edges > 0 ? 1 : 0);
         else
             hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
                                static_cast<const int32_t*>(g->offsets), g->indices, sd, n_seeds, sh, bk, id, ip, si,
-                               slot_idx_stride, present, 0, n_seeds);
+                               slot_idx_stride, present, 0, n_seeds, g->n_edges > 0 ? 1 : 0);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
@@ -205,11 +239,11 @@ hopgnn_status sample_merged(const hopgnn_csr* g, const int32_t* seeds, int32_t n
         if (g->offsets_i64)
             hipLaunchKernelGGL(sample_micrographs<int64_t>, grid, dim3(threads), 0, s,
                                static_cast<const int64_t*>(g->offsets), g->indices, seeds, n_seeds, sh, bk, ids, indptr,
-                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key);
+                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key, g->n_edges > 0 ? 1 : 0);
         else
             hipLaunchKernelGGL(sample_micrographs<int32_t>, grid, dim3(threads), 0, s,
                                static_cast<const int32_t*>(g->offsets), g->indices, seeds, n_seeds, sh, bk, ids, indptr,
-                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key);
+                               slot_idx, (int64_t)0, present, (int32_t)m0, seeds_per_key, g->n_edges > 0 ? 1 : 0);
         HOPGNN_LAUNCH_CHECK();
     }
     return HOPGNN_OK;
