@@ -415,6 +415,8 @@ def run_workload(cfg_id, group, args, cache, cpu_budget, stats_steps=6):
         "fanouts": cfg.fanouts, "hidden": cfg.hidden, "slots_per_batch": shb.n_slots,
         "batches_per_s": K * group / t_single, "ms_per_step": step_ms, "repeats": len(plain),
         "ms_per_step_min_max": [min(plain) / K * 1e3, max(plain) / K * 1e3],
+        "ms_per_step_p10_p90": [sorted(plain)[len(plain) // 10] / K * 1e3, sorted(plain)[(len(plain) * 9) // 10] / K * 1e3],
+        "timed_steps": K * len(plain),
         "ms_per_step_with_markers": _median(marked) / K * 1e3,
         "multi_stream": ({"streams": n_multi, "batches_per_s": K * group / _median(multi),
                           "ms_per_step": _median(multi) / K * 1e3, "repeats": len(multi)} if multi else None),
