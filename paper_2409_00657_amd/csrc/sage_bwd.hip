@@ -1250,9 +1250,14 @@ reduce_parts_add(const float* __restrict__ partial, int64_t part_stride, int32_t
     if (q == 0 && i < width) out[i] += (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
 }
 
-// One wavefront per destination row, one head after the other; the lanes share the head's columns.
-// The dot products dalpha_i of the first 64 entries stay in registers (lane i keeps entry i's); a
-// longer segment computes the later ones a second time.
+// One wavefront per destination row; heads are taken kHeadBatch at a time, side by side: per entry
+// the scores, the z rows, the dot products (their wavefront sums interleave) and the atomic adds of
+// the batch's heads are independent chains, where one head after the other leaves the wavefront
+// waiting on one chain at a time (170 k rows x 4 heads x 6 entries: 2.5 ms one by one).
+// The lanes share a head's columns.  The dot products dalpha_i of the first 64 entries stay in
+// registers (lane i keeps entry i's); a longer segment computes the later ones a second time.
+constexpr int kHeadBatch = 4;
+
 template <typename Tr>
 __global__ void __launch_bounds__(kBwdThreads)
 gat_bwd_rows(const float* __restrict__ Z, const float* __restrict__ scores, const int32_t* __restrict__ self_idx,
@@ -1265,50 +1270,80 @@ gat_bwd_rows(const float* __restrict__ Z, const float* __restrict__ scores, cons
     const int32_t dh = d_out / n_heads, stride = 2 * n_heads;
     const int64_t s = self_idx != nullptr ? (int64_t)self_idx[r] : r;
     const int32_t beg = indptr[r], end = indptr[r + 1];
-    for (int32_t h = 0; h < n_heads; ++h) {
-        const float sd = s >= 0 ? scores[s * stride + n_heads + h] : 0.f;
-        float mx = -INFINITY;
-        if (s >= 0) mx = leaky02(sd + scores[s * stride + h]);
+    const float* gy_row = dOut + r * d_out;
+    const typename Tr::store_t* of_row = out_fwd != nullptr ? out_fwd + r * d_out : nullptr;
+    auto g_at = [&](int32_t col) -> float {       // dY of this row: dOut where the activation passes
+        const float g = gy_row[col];
+        return !relu || Tr::to_f(of_row[col]) > 0.f ? g : 0.f;
+    };
+    for (int32_t h0 = 0; h0 < n_heads; h0 += kHeadBatch) {
+        const int nh = n_heads - h0 < kHeadBatch ? n_heads - h0 : kHeadBatch;      // heads of this batch
+        float sd[kHeadBatch], mx[kHeadBatch], den[kHeadBatch], inv[kHeadBatch];
+#pragma unroll
+        for (int b = 0; b < kHeadBatch; ++b) {
+            sd[b] = (b < nh && s >= 0) ? scores[s * stride + n_heads + h0 + b] : 0.f;
+            mx[b] = -INFINITY;
+            den[b] = 0.f;
+        }
+        auto e_of = [&](int64_t u, int b) -> float {      // pre-activation score of entry u for head h0 + b
+            return sd[b] + scores[u * stride + h0 + (b < nh ? b : 0)];
+        };
+        // the softmax's maximum and denominator, as the forward pass takes them
+        if (s >= 0) {
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) mx[b] = leaky02(e_of(s, b));
+        }
         for (int32_t e = beg; e < end; ++e) {
             const int32_t u = idx[e];
-            if (u >= 0) mx = fmaxf(mx, leaky02(sd + scores[(int64_t)u * stride + h]));
+            if (u < 0) continue;
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) mx[b] = fmaxf(mx[b], leaky02(e_of(u, b)));
         }
-        if (mx == -INFINITY) continue;            // no entries: the row's output is act(bias)
-        float den = 0.f;
-        if (s >= 0) den += expf(leaky02(sd + scores[s * stride + h]) - mx);
+        if (mx[0] == -INFINITY) continue;         // no entries: the row's output is act(bias)
+        if (s >= 0) {
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) den[b] += expf(leaky02(e_of(s, b)) - mx[b]);
+        }
         for (int32_t e = beg; e < end; ++e) {
             const int32_t u = idx[e];
-            if (u >= 0) den += expf(leaky02(sd + scores[(int64_t)u * stride + h]) - mx);
+            if (u < 0) continue;
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) den[b] += expf(leaky02(e_of(u, b)) - mx[b]);
         }
-        const float inv = 1.f / den;
-        const float* gy = dOut + r * d_out + (int64_t)h * dh;
-        const typename Tr::store_t* of = out_fwd != nullptr ? out_fwd + r * d_out + (int64_t)h * dh : nullptr;
-        auto g_at = [&](int32_t j) -> float {
-            const float g = gy[j];
-            return !relu || Tr::to_f(of[j]) > 0.f ? g : 0.f;
-        };
-        auto dot_with = [&](int64_t u) -> float {
-            const float* zu = Z + u * d_out + (int64_t)h * dh;
-            float d = 0.f;
-            for (int32_t j = lane; j < dh; j += kWave) d += g_at(j) * zu[j];
-            return wave_sum(d);
-        };
+#pragma unroll
+        for (int b = 0; b < kHeadBatch; ++b) inv[b] = 1.f / den[b];
+
         // first pass: dz, the dot products, and S = sum alpha_i dalpha_i
-        float S = 0.f, mine = 0.f;
+        float S[kHeadBatch], mine[kHeadBatch];
+#pragma unroll
+        for (int b = 0; b < kHeadBatch; ++b) S[b] = mine[b] = 0.f;
+        auto dots = [&](int64_t u, float (&d)[kHeadBatch], const float (&al)[kHeadBatch], bool add) {
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) {
+                d[b] = 0.f;
+                if (b < nh) {
+                    const int32_t c0 = (h0 + b) * dh;
+                    for (int32_t j = lane; j < dh; j += kWave) {
+                        const float g = g_at(c0 + j);
+                        d[b] += g * Z[u * d_out + c0 + j];
+                        if (add) atomicAdd(&dZ[u * d_out + c0 + j], al[b] * g);
+                    }
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) d[b] = wave_sum(d[b]);
+        };
         int32_t i = 0;
         auto first = [&](int64_t u) {
-            const float al = expf(leaky02(sd + scores[u * stride + h]) - mx) * inv;
-            const float* zu = Z + u * d_out + (int64_t)h * dh;
-            float* dzu = dZ + u * d_out + (int64_t)h * dh;
-            float d = 0.f;
-            for (int32_t j = lane; j < dh; j += kWave) {
-                const float g = g_at(j);
-                d += g * zu[j];
-                atomicAdd(&dzu[j], al * g);
+            float al[kHeadBatch], d[kHeadBatch];
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) al[b] = expf(leaky02(e_of(u, b)) - mx[b]) * inv[b];
+            dots(u, d, al, true);
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) {
+                S[b] += al[b] * d[b];
+                if (lane == i) mine[b] = d[b];    // entries past 63 match no lane
             }
-            d = wave_sum(d);
-            S += al * d;
-            if (lane == i) mine = d;              // entries past 63 match no lane
             ++i;
         };
         if (s >= 0) first(s);
@@ -1316,20 +1351,38 @@ gat_bwd_rows(const float* __restrict__ Z, const float* __restrict__ scores, cons
             if (idx[e] >= 0) first(idx[e]);
         // second pass: the score gradients
         i = 0;
-        float sum_de = 0.f;
+        float sum_de[kHeadBatch];
+#pragma unroll
+        for (int b = 0; b < kHeadBatch; ++b) sum_de[b] = 0.f;
         auto second = [&](int64_t u) {
-            const float ev = sd + scores[u * stride + h];
-            const float al = expf(leaky02(ev) - mx) * inv;
-            const float d = i < kWave ? __shfl(mine, i, kWave) : dot_with(u);
-            const float de = al * (d - S) * (ev > 0.f ? 1.f : 0.2f);
-            if (lane == 0) atomicAdd(&ds[u * stride + h], de);
-            sum_de += de;
+            float al[kHeadBatch], d[kHeadBatch], ev[kHeadBatch];
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) {
+                ev[b] = e_of(u, b);
+                al[b] = expf(leaky02(ev[b]) - mx[b]) * inv[b];
+            }
+            if (i < kWave) {
+#pragma unroll
+                for (int b = 0; b < kHeadBatch; ++b) d[b] = __shfl(mine[b], i, kWave);
+            } else {
+                dots(u, d, al, false);
+            }
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b) {
+                const float de = al[b] * (d[b] - S[b]) * (ev[b] > 0.f ? 1.f : 0.2f);
+                if (lane == b && b < nh) atomicAdd(&ds[u * stride + h0 + b], de);
+                sum_de[b] += de;
+            }
             ++i;
         };
         if (s >= 0) second(s);
         for (int32_t e = beg; e < end; ++e)
             if (idx[e] >= 0) second(idx[e]);
-        if (s >= 0 && lane == 0) atomicAdd(&ds[s * stride + n_heads + h], sum_de);
+        if (s >= 0) {
+#pragma unroll
+            for (int b = 0; b < kHeadBatch; ++b)
+                if (lane == b && b < nh) atomicAdd(&ds[s * stride + n_heads + h0 + b], sum_de[b]);
+        }
     }
 }
 
