@@ -20,6 +20,8 @@
 // bit-stable when a source row receives at most two contributions (always the case for the
 // slot-tree layout of hopgnn_sample: one self term, one parent), otherwise the rounding
 // depends on arrival order.
+#include <type_traits>
+
 #include "sage_common.hpp"
 
 namespace hopgnn {
@@ -811,6 +813,7 @@ bwd_scatter_kind(const float* __restrict__ D, const typename Tr::store_t* __rest
 // written exactly once - by its parent's lanes, or by its own when it has none (rows below `first`).
 // One group of lanes per source row u < n_src; the group of u < n_dst also serves u as a parent.
 // Rows past the last entry are zeroed.  Nothing is read-modified: bit-stable, no zero pass before.
+template <int W>      // W = 4: 16-byte pieces (d_in % 4 == 0, 16-byte aligned arrays), else single floats
 __global__ void __launch_bounds__(kBwdThreads)
 bwd_pull_slots(const float* __restrict__ D, const int32_t* __restrict__ indptr, const int32_t* __restrict__ idx,
                int64_t n_dst, int64_t n_src, int64_t first, int32_t d_in, int32_t group, float* __restrict__ dHsrc) {
@@ -819,8 +822,22 @@ bwd_pull_slots(const float* __restrict__ D, const int32_t* __restrict__ indptr, 
     const int32_t j = (int32_t)(gid - r * group);
     if (r >= n_src) return;
     const int64_t two_d = 2 * (int64_t)d_in;
+    using V = typename std::conditional<W == 4, float4, float>::type;
+    auto ld = [](const float* p) -> V { return *reinterpret_cast<const V*>(p); };
+    auto st = [](float* p, V v) { *reinterpret_cast<V*>(p) = v; };
+    auto scaled = [](V v, float a) -> V {
+        if constexpr (W == 4) return make_float4(v.x * a, v.y * a, v.z * a, v.w * a);
+        else return v * a;
+    };
+    auto sum = [](V a, V b) -> V {
+        if constexpr (W == 4) return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+        else return a + b;
+    };
+    V zero_v;
+    if constexpr (W == 4) zero_v = make_float4(0.f, 0.f, 0.f, 0.f);
+    else zero_v = 0.f;
     if (r < first || r >= first + (int64_t)indptr[n_dst])      // a row without a parent: its own self term, if any
-        for (int32_t c = j; c < d_in; c += group) dHsrc[r * d_in + c] = r < n_dst ? D[r * two_d + c] : 0.f;
+        for (int32_t c = j * W; c < d_in; c += group * W) st(dHsrc + r * d_in + c, r < n_dst ? ld(D + r * two_d + c) : zero_v);
     if (r >= n_dst) return;
     const int32_t beg = indptr[r], end = indptr[r + 1];
     int32_t cnt = 0;
@@ -832,10 +849,10 @@ bwd_pull_slots(const float* __restrict__ D, const int32_t* __restrict__ indptr, 
         if (u >= n_src) break;                        // fewer source rows than entries: not this call's layout
         const bool fed = idx[e] >= 0;                 // an invalid slot takes no part in the mean
         const bool is_dst = u < n_dst;                // ... but a destination row still has its self term
-        for (int32_t c = j; c < d_in; c += group) {
-            float v = fed ? Dr[c] * inv : 0.f;
-            if (is_dst) v += D[u * two_d + c];
-            dHsrc[u * d_in + c] = v;
+        for (int32_t c = j * W; c < d_in; c += group * W) {
+            V v = fed ? scaled(ld(Dr + c), inv) : zero_v;
+            if (is_dst) v = sum(v, ld(D + u * two_d + c));
+            st(dHsrc + u * d_in + c, v);
         }
     }
 }
@@ -1062,8 +1079,13 @@ static hopgnn_status sage_bwd_typed(const void* Hsrc, int64_t n_src, int32_t d_i
                                0, s, D, static_cast<const T*>(Hsrc), self_idx, indptr, idx, n_dst, d_in, group, kind.scatter,
                                kind.norm, dHsrc, n_dst_dev);
         else if (slot_first >= 0)
-            hipLaunchKernelGGL(bwd_pull_slots, dim3((unsigned)ceil_div(n_src * group, kBwdThreads)), dim3(kBwdThreads), 0,
-                               s, D, indptr, idx, n_dst, n_src, slot_first, d_in, group, dHsrc);
+        {
+            const bool v4 = d_in % 4 == 0 && aligned(D, 16) && aligned(dHsrc, 16);
+            const int pull_group = mean_group(v4 ? d_in / 4 : d_in);
+            auto pull = v4 ? bwd_pull_slots<4> : bwd_pull_slots<1>;
+            hipLaunchKernelGGL(pull, dim3((unsigned)ceil_div(n_src * pull_group, kBwdThreads)), dim3(kBwdThreads), 0, s, D,
+                               indptr, idx, n_dst, n_src, slot_first, d_in, pull_group, dHsrc);
+        }
         else
             hipLaunchKernelGGL(bwd_scatter, dim3((unsigned)ceil_div(n_dst * group, kBwdThreads)), dim3(kBwdThreads), 0, s,
                                D, self_idx, indptr, idx, n_dst, d_in, group, dHsrc, n_dst_dev);
