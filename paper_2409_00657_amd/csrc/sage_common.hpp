@@ -291,7 +291,9 @@ static hopgnn_status launch_mean(const void* Hsrc, const int32_t* indptr, const 
     using T = typename Tr::store_t;
     const bool vec = (d_in % Tr::kPer16 == 0) && aligned(Hsrc, 16) && aligned(mean, 16);
     const int units = vec ? d_in / Tr::kPer16 : d_in;
-    const int group = mean_group(units);
+    // lanes per destination row: one per 16-byte word (no lane idles on rows that are not a power of two
+    // words long: 25 words of a 400-byte row on 32 lanes left 7 of them without work), at most a wavefront
+    const int group = vec ? (units < 64 ? units : 64) : mean_group(units);
     constexpr int xcd_run = kMeanXcdRun;
     const int64_t mean_blocks = ceil_div(ceil_div(n_dst * group, kMeanThreads), 8 * xcd_run) * (8 * xcd_run);
     if (mean_blocks + n_transpose_tiles >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
