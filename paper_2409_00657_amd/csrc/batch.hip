@@ -265,6 +265,7 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
         for (int32_t b = 0; b < n_runs; ++b) {
             const int32_t* rb = p->remap + b * T;
             const void* src = p->Xu;
+            int64_t n_src = p->uniq_capacity;
             int32_t d_in = p->dim;
             for (int32_t k = 1; k <= L; ++k) {
                 int64_t n_dst = 0;
@@ -292,6 +293,7 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
                 }
                 tree.ids = p->ids + (merged ? 0 : (int64_t)b * T);
                 tree.mean_next = tws + TW.mean_off[k & 1];
+                tree.n_src = n_src;
                 if (mk && !mark_agg && hipEventRecord(ev_a, st) != hipSuccess) return HOPGNN_EHIP;
                 rc = project_dispatch(p->dt, st, src, k == 1 ? rb : nullptr, mean, p->W_self[k - 1], p->W_neigh[k - 1], Wt,
                                       TW.KP[k - 1], p->bias[k - 1], n_dst, d_in, 2 * d_in, p->d_out[k - 1], k < L ? 1 : 0,
@@ -299,6 +301,7 @@ extern "C" hopgnn_status hopgnn_batch_fwd(const hopgnn_batch_plan* p, const int3
                 if (rc != HOPGNN_OK) return rc;
                 if (mk && !mark_agg && hipEventRecord(ev_b, st) != hipSuccess) return HOPGNN_EHIP;
                 src = dst;
+                n_src = n_dst;
                 d_in = p->d_out[k - 1];
             }
         }

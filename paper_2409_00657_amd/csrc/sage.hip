@@ -249,8 +249,9 @@ template <typename Tr, int BM, int BN, int PW, int TM, int TN, int NT, bool SW>
 __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds, int wave_row0, int wave_col0, int tid,
                                               int lane, int64_t row0, int64_t row_end, int32_t col0, int32_t d_out,
                                               const typename Tr::store_t* bias, int relu, typename Tr::store_t* out,
-                                              const TreeTiles& tt, int lvl, uint32_t tile_in_level) {
+                                              const TreeTiles& tt, int lvl, uint32_t tile_in_level, int32_t my_id) {
     using T = typename Tr::store_t;
+    static_assert(BM <= NT, "one validity flag per thread");
     constexpr int EPW = 16 / (int)sizeof(T);      // elements per 16-byte word
     constexpr int LDT = PW + EPW;                 // padded row of the staged tile
     constexpr int WORDS = PW / EPW;
@@ -260,17 +261,21 @@ __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds
     const int n_rows = (int)(row_end - row0);
     const bool make_means = lvl >= 1 && tt.mean_next != nullptr;
     const bool store_rows = lvl < tt.store_levels;
-    if (make_means)
-        for (int i = tid; i < BM; i += NT) vld[i] = (i < n_rows && tt.ids[row0 + i] >= 0) ? 1 : 0;
+    if (make_means && tid < BM) vld[tid] = my_id >= 0 ? 1 : 0;
 #pragma unroll 1
     for (int c_lo = 0; c_lo < BN; c_lo += PW) {
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int wc = wave_col0 + tn * 32;
             if (wc < c_lo || wc >= c_lo + PW) continue;
+            // One 32 x 32 tile at a time, fetched into ordinary registers where it is used (the
+            // accumulators may live in the accumulation registers, which no vector instruction reads)
+            // and finished before the next: a few results in flight, not the whole block's.
             if constexpr (SW) {      // a lane holds runs of four columns of one row (operands exchanged)
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
+                for (int tm = 0; tm < TM; ++tm) {
+                    floatx16 av = acc[tm][tn];
+                    asm volatile("" : "+v"(av));
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int c = wc + 8 * q + 4 * (lane >> 5);
@@ -280,30 +285,36 @@ __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds
                             float* x = &v.x;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
-                                x[e] = acc[tm][tn][4 * q + e];
+                                x[e] = av[4 * q + e];
                                 if (bias != nullptr && col0 + c + e < d_out) x[e] += Tr::to_f(bias[col0 + c + e]);
                                 if (relu) x[e] = fmaxf(x[e], 0.f);
                             }
                             *reinterpret_cast<float4*>(dst) = v;
                         } else {
-                            *reinterpret_cast<uint2*>(dst) = pack_run<Tr>(acc[tm][tn], q, bias, col0 + c, d_out, relu);
+                            *reinterpret_cast<uint2*>(dst) = pack_run<Tr>(av, q, bias, col0 + c, d_out, relu);
                         }
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             } else {
                 const int32_t col = col0 + wc + (lane & 31);
                 const float b = (bias != nullptr && col < d_out) ? Tr::to_f(bias[col]) : 0.f;
 #pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
+                for (int tm = 0; tm < TM; ++tm) {
+                    floatx16 av = acc[tm][tn];
+                    asm volatile("" : "+v"(av));
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
-                        float x = acc[tm][tn][i] + b;
+                        float x = av[i] + b;
                         if (relu) x = fmaxf(x, 0.f);
                         const int row = wave_row0 + tm * 32 + 8 * (i / 4) + 4 * (lane >> 5) + (i & 3);
                         tile[row * LDT + (wc - c_lo) + (lane & 31)] = Tr::from_f(x);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (store_rows)
             for (int w = tid; w < n_rows * WORDS; w += NT) {
                 const int r = w / WORDS, c = (w % WORDS) * EPW;
@@ -341,7 +352,7 @@ __device__ __forceinline__ void tree_epilogue(floatx16 (&acc)[TM][TN], void* lds
                 if (gc < d_out) *reinterpret_cast<uint4*>(&mean_next[(parent0 + j) * d_out + gc]) = o.v;
             }
         }
-        __syncthreads();      // the staged tile is rewritten by the next pass
+        lds_barrier();        // the staged tile is rewritten by the next pass (its words are in registers by now)
     }
 }
 
@@ -388,6 +399,10 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int K = k_total;
+    // the slot id behind this thread's row of the tile (which siblings count in a mean): read here,
+    // used after the K loop
+    int32_t my_id = -1;
+    if (TREE && lvl >= 1 && tt.mean_next != nullptr && row0 + tid < row_end) my_id = tt.ids[row0 + tid];
 
     // rows this thread stages, fixed for the whole K loop
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
@@ -562,7 +577,7 @@ sage_project_f32(const float* __restrict__ Hsrc, const int32_t* __restrict__ sel
     if (TREE)
         tree_epilogue<TrF32, BM, BN, BN, TM, TN, kProjThreads, true>(acc, lds_f32, wm * (BM / 2), wn * (BN / 2), tid, lane, row0,
                                                                row_end, col0, d_out, bias, relu, out, tt, lvl,
-                                                               tile_in_level);
+                                                               tile_in_level, my_id);
     else
         project_epilogue<TrF32, TM, TN>(acc, row0 + wm * (BM / 2), col0 + wn * (BN / 2), lane, row_end, d_out, bias, relu,
                                         out);
@@ -614,6 +629,8 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int K = k_total;
+    int32_t my_id = -1;      // see the fp32 kernel
+    if (TREE && lvl >= 1 && tt.mean_next != nullptr && row0 + tid < row_end) my_id = tt.ids[row0 + tid];
 
     int64_t a_self[A_ITEMS], a_mean[A_ITEMS];
 #pragma unroll
@@ -770,7 +787,7 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
     const int32_t wcol0 = col0 + wn * (BN / WN);
     if (TREE) {
         tree_epilogue<Tr, BM, BN, BN, TM, TN, NT, SW>(acc, lds16, wm * (BM / WM), wn * (BN / WN), tid, lane, row0, row_end, col0,
-                                                      d_out, bias, relu, out, tt, lvl, tile_in_level);
+                                                      d_out, bias, relu, out, tt, lvl, tile_in_level, my_id);
     } else if (out_f32) {     // `out` is a float array: unrounded result
         if constexpr (SW) epilogue16_direct<Tr, float, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, reinterpret_cast<float*>(out));
         else project_epilogue_f32out<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, reinterpret_cast<float*>(out));
@@ -784,6 +801,223 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
     } else {
         if constexpr (SW) epilogue16_direct<Tr, typename Tr::store_t, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out);
         else project_epilogue<Tr, TM, TN>(acc, wrow0, wcol0, lane, row_end, d_out, bias, relu, out);
+    }
+}
+
+// Slot-tree layers on the largest 2-byte tile (256 x 256 x 64, 8 waves) by workgroups that WALK over
+// their tiles (b, b + gridDim.x, ...; one workgroup per CU) instead of one workgroup per tile.
+// With K as short as 4 tiles, a tile of the one-tile kernel spends as long waiting as multiplying: for
+// the next workgroup to be started (2 us), then for its row indices, then for the rows behind them
+// (3.8 us until the first K tile is in LDS, against 7.7 us of K loop and 6.1 us of epilogue).  Here
+//   - the next tile's row indices are requested a whole K loop ahead,
+//   - its first K tile is requested during the last two K steps of the current tile and waits in the
+//     registers through the epilogue, so the next tile multiplies as soon as the epilogue's LDS is free,
+//   - the weights (L2 resident) are requested one K tile ahead, the left operand two.
+// LDS layout, summation order and the epilogue are those of sage_project_16: the same bits.
+// Needs d_in % 64 == 0 and k_total = 2 * d_in or d_in with an even number of K tiles (a K tile lies in the
+// self half or in the mean half as a whole; the ring's parity is the same for every tile), byte
+// offsets within 32 bits (the host checks), and n_blocks >= 1 blocks of project_grid's numbering.
+template <typename Tr, bool SW>
+__global__ void __launch_bounds__(512)
+sage_project_16_walk(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ self_idx,
+                     const uint16_t* __restrict__ Mean, const uint16_t* __restrict__ Wt, int32_t KP,
+                     const typename Tr::store_t* __restrict__ bias, int32_t d_in, int32_t k_total, int32_t d_out,
+                     int relu, uint32_t n_tiles_n, uint32_t n_blocks, typename Tr::store_t* __restrict__ out,
+                     TreeTiles tt) {
+    constexpr int BM = 256, BN = 256, BK = 64, WM = 2, WN = 4, LD = BK + 8, NT = 64 * WM * WN;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int ITEMS = BM * BK / 8 / NT;          // 16-byte items per thread and operand (BM == BN)
+    constexpr int SLICE = NT / (BK / 8);             // rows one item of every thread covers together
+    static_assert(BM == BN && ITEMS * SLICE == BM, "items");
+    // LDS: stage 0 (left operand's K tile [BM][LD], then the weights' [BN][LD]), then stage 1 the same
+    constexpr int STAGE = (BM + BN) * LD;            // elements per stage
+    static_assert((size_t)BM * (BN + 8) * 2 + BM <= (size_t)2 * STAGE * 2, "the staged tile must fit the K tiles' LDS");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds16[];
+    auto As = [&](int st) { return reinterpret_cast<uint16_t (*)[LD]>(lds16 + st * STAGE); };
+    auto Bs = [&](int st) { return reinterpret_cast<uint16_t (*)[LD]>(lds16 + st * STAGE + BM * LD); };
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int nk = (k_total + BK - 1) / BK;
+    const int trow = tid / (BK / 8), tk = (tid % (BK / 8)) * 8;   // this thread's row of a slice, its k within a K tile
+
+    struct Tile {
+        int64_t row0, row_end;
+        int32_t col0;
+        int lvl;
+        uint32_t til;
+    };
+    auto tile_at = [&](uint32_t bid, Tile& T) -> bool {
+        uint32_t mt, nt;
+        tile_of_block(bid, n_tiles_n, mt, nt);
+        T.col0 = (int32_t)(nt * BN);
+        return tree_tile_rows<BM>(tt, mt, T.lvl, T.til, T.row0, T.row_end);
+    };
+    // Addresses are a uniform base plus a 32-bit BYTE offset of the thread's.  Per tile a thread keeps,
+    // for each of its ITEMS rows, the offset of the self row (row index * row bytes) and of the mean
+    // row; rows past the tile's last one repeat that row (their results are never used); an absent
+    // self row (negative index) reads row 0 and is zeroed on its way to LDS.
+    const uint32_t row_bytes = (uint32_t)d_in * 2u, tk_bytes = (uint32_t)tk * 2u;
+    struct Rows {
+        uint32_t so[ITEMS];
+        uint32_t absent;         // bit it: self row absent
+        int32_t id;              // slot id behind row `tid` of the tile (see tree_epilogue)
+    };
+    // the indices are requested here and not touched: whoever turns them into offsets waits for them
+    auto load_idx = [&](const Tile& T, int32_t (&sidx)[ITEMS], int32_t& id) {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int64_t r = T.row0 + it * SLICE + trow;
+            const bool in = r < T.row_end;
+            const int32_t v = self_idx != nullptr ? self_idx[in ? r : T.row0] : (int32_t)r;    // loads are unconditional
+            sidx[it] = in ? v : -1;
+        }
+        const bool in = T.row0 + tid < T.row_end;
+        const int32_t v = tt.ids[in ? T.row0 + tid : T.row0];
+        id = (in && T.lvl >= 1 && tt.mean_next != nullptr) ? v : -1;
+    };
+    auto rows_of = [&](const Tile& T, const int32_t (&sidx)[ITEMS], int32_t id, Rows& R) {
+        R.absent = 0u;
+        R.id = id;
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            R.so[it] = (uint32_t)(sidx[it] >= 0 ? sidx[it] : 0) * row_bytes + tk_bytes;
+            if (sidx[it] < 0) R.absent |= 1u << it;
+        }
+    };
+    auto load_a = [&](uint4 (&ra)[ITEMS], const Tile& T, const Rows& R, int kt) {
+        // one instruction stream for both halves (a branch here makes the waits for earlier loads conservative)
+        const int k0 = kt * BK;
+        const bool self_half = k0 < d_in;
+        const char* base = self_half ? reinterpret_cast<const char*>(Hsrc + k0)
+                                     : reinterpret_cast<const char*>(Mean + T.row0 * d_in + (k0 - d_in));
+        const uint32_t last = (uint32_t)(T.row_end - T.row0 - 1);
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const uint32_t rr = (uint32_t)(it * SLICE + trow);
+            const uint32_t mo = (rr <= last ? rr : last) * row_bytes + tk_bytes;
+            ra[it] = *reinterpret_cast<const uint4*>(base + (self_half ? R.so[it] : mo));
+        }
+    };
+    const uint32_t b_off = ((uint32_t)trow * (uint32_t)KP + (uint32_t)tk) * 2u;
+    auto load_b = [&](uint4 (&rb)[ITEMS], int32_t col0, int kt) {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const char* base = reinterpret_cast<const char*>(Wt + (int64_t)(col0 + it * SLICE) * KP + kt * BK);
+            rb[it] = *reinterpret_cast<const uint4*>(base + b_off);
+        }
+    };
+    // kt: the K tile the words belong to, R: the rows of the tile they belong to
+    auto store_tile = [&](const uint4 (&ra)[ITEMS], const uint4 (&rb)[ITEMS], int st, int kt, const Rows& R) {
+        const uint32_t absent = kt * BK < d_in ? R.absent : 0u;
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            *reinterpret_cast<uint4*>(&As(st)[it * SLICE + trow][tk]) = (absent >> it) & 1u ? make_uint4(0u, 0u, 0u, 0u) : ra[it];
+            *reinterpret_cast<uint4*>(&Bs(st)[it * SLICE + trow][tk]) = rb[it];
+        }
+    };
+    floatx16 acc[TM][TN];
+    const int fg = lane >> 5, fl32 = lane & 31;
+    // one 16-wide K block at a time (see sage_project_16: the largest tile has registers for one set of
+    // operand words; the SIMD's other wave covers the wait for them)
+    auto compute = [&](int st) {
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            uint4 fa[TM], fb[TN];
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+                fa[tm] = *reinterpret_cast<const uint4*>(&As(st)[wm * (BM / WM) + tm * 32 + fl32][kk + fg * 8]);
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+                fb[tn] = *reinterpret_cast<const uint4*>(&Bs(st)[wn * (BN / WN) + tn * 32 + fl32][kk + fg * 8]);
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+                    acc[tm][tn] = SW ? mfma16<Tr>(fb[tn], fa[tm], acc[tm][tn]) : mfma16<Tr>(fa[tm], fb[tn], acc[tm][tn]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    uint32_t bid = blockIdx.x;
+    Tile cur;
+    if (bid >= n_blocks || !tile_at(bid, cur)) return;
+    Rows R;
+    {
+        int32_t sidx[ITEMS], id;
+        load_idx(cur, sidx, id);
+        rows_of(cur, sidx, id, R);
+    }
+    // (one struct for everything under way: a weights array of its own ended up in scratch memory)
+    struct Ring {
+        uint4 a[2][ITEMS], b[ITEMS];
+    };
+    Ring rg;
+    load_a(rg.a[0], cur, R, 0);
+    load_b(rg.b, cur.col0, 0);
+    store_tile(rg.a[0], rg.b, 0, 0, R);
+    lds_barrier();
+    for (;;) {
+        // Stage 0 holds this tile's first K tile.  The tile after this one (the last tile stands in for
+        // its own successor: its first K tile is then re-read at the end and nothing uses it):
+        uint32_t nbid = bid + gridDim.x;
+        Tile nxt = cur;
+        bool has_next = false;
+        while (nbid < n_blocks && !(has_next = tile_at(nbid, nxt))) nbid += gridDim.x;
+        if (!has_next) nxt = cur;
+        int32_t nidx[ITEMS], nid;
+        load_idx(nxt, nidx, nid);
+        load_a(rg.a[1], cur, R, 1);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.f;
+        // Step t multiplies K tile t from LDS stage t & 1 while the left operand's K tile t + 2 and the
+        // weights' K tile t + 1 are on their way.
+        int t = 0;
+        for (; t + 2 < nk; t += 2) {
+            load_b(rg.b, cur.col0, t + 1);      // wanted first: the younger load may stay under way past the hand-over
+            load_a(rg.a[0], cur, R, t + 2);
+            compute(0);
+            store_tile(rg.a[1], rg.b, 1, t + 1, R);
+            lds_barrier();
+            load_b(rg.b, cur.col0, t + 2);
+            load_a(rg.a[1], cur, R, t + 3);
+            compute(1);
+            store_tile(rg.a[0], rg.b, 0, t + 2, R);
+            lds_barrier();
+        }
+        // The last two K tiles: what is requested now is the NEXT tile's first K tile (first use of its
+        // row indices: requested at the top of this tile, waited for here).  It waits in the registers
+        // until the epilogue has released the LDS.
+        Rows N;
+        rows_of(nxt, nidx, nid, N);
+        load_b(rg.b, cur.col0, t + 1);
+        load_a(rg.a[0], nxt, N, 0);
+        compute(0);
+        store_tile(rg.a[1], rg.b, 1, t + 1, R);
+        lds_barrier();
+        load_b(rg.b, nxt.col0, 0);
+        compute(1);
+        // The next tile's words are waited for HERE, before the epilogue issues its stores: the counter of
+        // outstanding memory operations is in order, so a wait for these loads placed after the epilogue
+        // would also wait for every store of it.
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            asm volatile("" : "+v"(rg.a[0][it].x), "+v"(rg.a[0][it].y), "+v"(rg.a[0][it].z), "+v"(rg.a[0][it].w));
+            asm volatile("" : "+v"(rg.b[it].x), "+v"(rg.b[it].y), "+v"(rg.b[it].z), "+v"(rg.b[it].w));
+        }
+        lds_barrier();     // every wave is past its last read of the K tiles: the epilogue reuses their LDS
+        tree_epilogue<Tr, BM, BN, BN, TM, TN, NT, SW>(acc, lds16, wm * (BM / WM), wn * (BN / WN), tid, lane, cur.row0,
+                                                      cur.row_end, cur.col0, d_out, bias, relu, out, tt, cur.lvl, cur.til,
+                                                      R.id);
+        store_tile(rg.a[0], rg.b, 0, 0, N);      // the next tile's first K tile, which waited in the registers
+        lds_barrier();
+        if (!has_next) break;
+        cur = nxt;
+        bid = nbid;
+        R = N;
     }
 }
 
@@ -873,6 +1107,39 @@ static hopgnn_status launch_project_16(bool vec, hipStream_t s, const void* Hsrc
     TreeTiles tt{};
     const int64_t m_tiles = tree != nullptr ? tree_tiles(*tree, BM, tt) : ceil_div(n_dst, BM);
     if (m_tiles * ntn + kXcds * ntn >= ((int64_t)1 << 31)) return HOPGNN_ERANGE;
+    if constexpr (BM == 256 && BN == 256 && BK == 64 && WM == 2 && WN == 4) {
+        const int nk = (k_total + BK - 1) / BK;
+        // the walking kernel's requirements: whole K tiles in each half, 32-bit byte offsets; it is for
+        // short K (at 16 K tiles the fixed waits of a tile are a small share and the one-tile kernel's
+        // deeper ring for the weights wins: 224 us against 235 us on the 100 M-vertex workload's second layer)
+        const bool fits = tree != nullptr && vec && d_in % BK == 0 && (k_total == d_in || k_total == 2 * d_in) &&
+                          nk % 2 == 0 && nk <= 8 && n_dst * (int64_t)d_in * 2 < ((int64_t)1 << 32) &&
+                          tree->n_src * (int64_t)d_in * 2 < ((int64_t)1 << 32) && (int64_t)KP * 2 * BN < ((int64_t)1 << 32);
+        if (fits) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+                return HOPGNN_EHIP;
+            const uint32_t n_blocks = project_grid(m_tiles, ntn);
+            uint32_t grid = (uint32_t)(cus / kXcds) * kXcds;      // a multiple of the XCD count: a walk stays on its XCD
+            if (grid < kXcds) grid = kXcds;
+            // Walking pays once a workgroup has several tiles to hide waits between; with one or two tiles
+            // per CU the hardware's own placement of single-tile workgroups is as good or better
+            // (measured on one machine: 426 tiles 48 us against 44 us; 3638 tiles of K = 256: 254-257 us
+            // against 271 us, 7276 tiles 487-493 against 521 us, 14.5 k and 29 k tiles within 1 %).
+            if (n_blocks >= 4 * grid) {
+                auto walk = sw ? sage_project_16_walk<Tr, true> : sage_project_16_walk<Tr, false>;
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(walk), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        (int)lds) != hipSuccess)
+                    return HOPGNN_EHIP;
+                hipLaunchKernelGGL(walk, dim3(grid), dim3(512), lds, s, static_cast<const uint16_t*>(Hsrc), self_idx,
+                                   static_cast<const uint16_t*>(mean), Wt, KP, static_cast<const T*>(bias), d_in, k_total,
+                                   d_out, relu, ntn, n_blocks, static_cast<T*>(out), tt);
+                HOPGNN_LAUNCH_CHECK();
+                return HOPGNN_OK;
+            }
+        }
+    }
     hipLaunchKernelGGL(kern, dim3(project_grid(m_tiles, ntn)), dim3(64 * WM * WN), lds, s,
                        static_cast<const uint16_t*>(Hsrc), self_idx, static_cast<const uint16_t*>(mean), Wt,
                        KP, static_cast<const T*>(bias), n_dst, d_in, k_total, d_out, relu, ntn,

@@ -369,6 +369,7 @@ struct TreeLayer {
     int32_t fan[kMaxLayers + 1];         // fan[h] = children per level-(h-1) slot, h >= 1
     const int32_t* ids;
     void* mean_next;
+    int64_t n_src;                       // rows of the layer's source array (bounds what self_idx may name)
 };
 constexpr int kTreeMaxFan = 64;          // a group of siblings must fit the smallest row tile
 

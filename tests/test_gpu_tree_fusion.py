@@ -23,6 +23,14 @@ CASES = [
     ([64, 3], 50, 1, False, torch.float32, 32, 40),           # the widest group a tile can hold
     ([1, 1, 7], 90, 2, True, torch.bfloat16, 16, 24),         # groups of one
     ([7, 33, 2], 17, 1, False, torch.float32, 24, 8),         # ragged everything
+    ([10, 10, 10], 300, 1, False, torch.float16, 128, 512),   # 256 x 256 tiles, two column tiles, four K tiles
+    ([25, 10], 2600, 1, False, torch.bfloat16, 256, 256),     # 256 x 256 tiles, one column tile, eight K tiles
+    ([10, 10], 1500, 2, True, torch.float16, 64, 256),        # 256 x 256 tiles, two K tiles, a merged group
+    # enough 256 x 256 tiles (four and more per CU) for the workgroups that walk over their tiles; the
+    # oracle's chain is left to the full-size tests at these sizes
+    ([10, 10, 10], 1200, 1, False, torch.float16, 128, 512),  # four K tiles, two column tiles
+    ([25, 10], 5400, 2, True, torch.bfloat16, 256, 256),      # eight K tiles, one column tile, a merged group
+    ([10, 10], 13000, 1, False, torch.float16, 64, 512),      # two K tiles: the K loop is its last step only
 ]
 
 
@@ -57,6 +65,8 @@ def test_fused_tree_layers_give_the_unfused_bits(orc, fan, B, G, merge, dt, d, h
             keep = sh.n_dst(k + 1)
             assert to_bits(fused.H[k - 1][:keep]).tobytes() == to_bits(plain.H[k - 1][:keep]).tobytes(), k
             assert torch.isnan(fused.H[k - 1][keep:].float()).all()      # and nothing else is written
+    if B * G * int(np.prod(fan)) > 1_000_000:
+        return
     # against the oracle's own chain (first batch of the last group run)
     off_np, idx_np = g.offsets.cpu().numpy(), g.indices.cpu().numpy()
     ref_ids = [orc.sample(off_np, idx_np, seeds[b * B:(b + 1) * B].cpu().numpy(), fan, keys[b]) for b in range(G)]
