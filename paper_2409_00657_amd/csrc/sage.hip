@@ -955,6 +955,7 @@ sage_project_16_walk(const uint16_t* __restrict__ Hsrc, const int32_t* __restric
     load_a(rg.a[0], cur, R, 0);
     load_b(rg.b, cur.col0, 0);
     store_tile(rg.a[0], rg.b, 0, 0, R);
+    load_a(rg.a[1], cur, R, 1);
     lds_barrier();
     for (;;) {
         // Stage 0 holds this tile's first K tile.  The tile after this one (the last tile stands in for
@@ -966,7 +967,6 @@ sage_project_16_walk(const uint16_t* __restrict__ Hsrc, const int32_t* __restric
         if (!has_next) nxt = cur;
         int32_t nidx[ITEMS], nid;
         load_idx(nxt, nidx, nid);
-        load_a(rg.a[1], cur, R, 1);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -999,6 +999,7 @@ sage_project_16_walk(const uint16_t* __restrict__ Hsrc, const int32_t* __restric
         store_tile(rg.a[1], rg.b, 1, t + 1, R);
         lds_barrier();
         load_b(rg.b, nxt.col0, 0);
+        load_a(rg.a[1], nxt, N, 1);      // and its second one, wanted at the end of the next tile's first step
         compute(1);
         // The next tile's words are waited for HERE, before the epilogue issues its stores: the counter of
         // outstanding memory operations is in order, so a wait for these loads placed after the epilogue
