@@ -810,8 +810,8 @@ sage_project_16(const uint16_t* __restrict__ Hsrc, const int32_t* __restrict__ s
 // the next workgroup to be started (2 us), then for its row indices, then for the rows behind them
 // (3.8 us until the first K tile is in LDS, against 7.7 us of K loop and 6.1 us of epilogue).  Here
 //   - the next tile's row indices are requested a whole K loop ahead,
-//   - its first K tile is requested during the last two K steps of the current tile and waits in the
-//     registers through the epilogue, so the next tile multiplies as soon as the epilogue's LDS is free,
+//   - its first two K tiles are requested during the last two K steps of the current tile and wait in
+//     the registers through the epilogue, so the next tile multiplies as soon as the epilogue's LDS is free,
 //   - the weights (L2 resident) are requested one K tile ahead, the left operand two.
 // LDS layout, summation order and the epilogue are those of sage_project_16: the same bits.
 // Needs d_in % 64 == 0 and k_total = 2 * d_in or d_in with an even number of K tiles (a K tile lies in the
