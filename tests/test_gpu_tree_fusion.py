@@ -31,6 +31,7 @@ CASES = [
     ([10, 10, 10], 1200, 1, False, torch.float16, 128, 512),  # four K tiles, two column tiles
     ([25, 10], 5400, 2, True, torch.bfloat16, 256, 256),      # eight K tiles, one column tile, a merged group
     ([10, 10], 13000, 1, False, torch.float16, 64, 512),      # two K tiles: the K loop is its last step only
+    ([10, 10, 10], 1200, 1, False, torch.bfloat16, 192, 512), # six K tiles, exchanged operands
 ]
 
 
