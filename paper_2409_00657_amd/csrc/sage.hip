@@ -911,7 +911,9 @@ sage_project_16_walk(const uint16_t* __restrict__ Hsrc, const int32_t* __restric
         const uint32_t absent = kt * BK < d_in ? R.absent : 0u;
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
-            *reinterpret_cast<uint4*>(&As(st)[it * SLICE + trow][tk]) = (absent >> it) & 1u ? make_uint4(0u, 0u, 0u, 0u) : ra[it];
+            const uint32_t keep = ((absent >> it) & 1u) - 1u;      // all ones, or zero for an absent row: four ANDs, no branch
+            *reinterpret_cast<uint4*>(&As(st)[it * SLICE + trow][tk]) =
+                make_uint4(ra[it].x & keep, ra[it].y & keep, ra[it].z & keep, ra[it].w & keep);
             *reinterpret_cast<uint4*>(&Bs(st)[it * SLICE + trow][tk]) = rb[it];
         }
     };
