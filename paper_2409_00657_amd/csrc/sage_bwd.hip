@@ -311,7 +311,10 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
     using T = typename Tr::store_t;
     constexpr int NT = 64 * WK * WN;                 // threads
     constexpr int KT = 32 * WK * TM, NTL = 32 * WN * TN;
-    constexpr int LDA = KT + 4, LDB = NTL + 4;       // 2-byte elements; rows 8 apart sit 64 bytes apart in the banks
+    // 2-byte elements; a row pitch of 16 banks past a multiple of 64 keeps the four rows and two column
+    // halves that one transposing read touches on different banks
+    constexpr int LDA = KT + 32, LDB = NTL + 32;
+    static_assert(KT % 128 == 0 && NTL % 128 == 0, "row pitch");
     constexpr int A_PER_ROW = KT / 8, B_PER_ROW = NTL / 4;
     constexpr int A_ITEMS = kG16Rows * A_PER_ROW / NT, B_ITEMS = kG16Rows * B_PER_ROW / NT;
     constexpr int A_ROWS = NT / A_PER_ROW, B_ROWS = NT / B_PER_ROW;     // rows one round of the threads covers
@@ -407,11 +410,18 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
             *reinterpret_cast<uint2*>(&Bs[buf][br + B_ROWS * i][bc]) = make_uint2(Tr::pack2(bv[0], bv[1]), Tr::pack2(bv[2], bv[3]));
         }
     };
-    // 8 values down a column, rows row0 .. row0 + 7, as one MFMA operand
-    auto column8 = [&](const uint16_t* S, int ld, int row0, int col) -> uint4 {
-        union { uint4 v; uint16_t e[8]; } u;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) u.e[e] = S[(row0 + e) * ld + col];
+    // 8 values down a column, rows row0 .. row0 + 7 of column col0 + lane % 32, as one MFMA operand: two
+    // transposing LDS reads (ds_read_b64_tr_b16).  Within 16 lanes, lanes 4j .. 4j+3 name the four 8-byte
+    // words of a 16-element piece of row j (j = 0..3), and lane i receives element i of each of the four
+    // rows: four consecutive rows of ONE column, with no vector instruction spent on it.
+    typedef short v4i16 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+    const int tr_row = (lane & 15) >> 2, tr_col = ((lane >> 4) & 1) * 16 + 4 * (lane & 3);
+    auto column8 = [&](const uint16_t* S, int ld, int row0, int col0) -> uint4 {
+        const uint16_t* p = S + (row0 + tr_row) * ld + col0 + tr_col;
+        union { uint4 v; v4i16 h[2]; } u;
+        u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)p);
+        u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16*)(p + 4 * ld));
         return u.v;
     };
 
@@ -451,9 +461,9 @@ bwd_weight_grad16(const typename Tr::store_t* __restrict__ Hsrc, const int32_t* 
         for (int kk = 0; kk < kG16Rows; kk += 16) {
             uint4 a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = column8(&As[buf][0][0], LDA, kk + 8 * g, (wk * TM + i) * 32 + l32);
+            for (int i = 0; i < TM; ++i) a[i] = column8(&As[buf][0][0], LDA, kk + 8 * g, (wk * TM + i) * 32);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = column8(&Bs[buf][0][0], LDB, kk + 8 * g, (wn * TN + j) * 32 + l32);
+            for (int j = 0; j < TN; ++j) b[j] = column8(&Bs[buf][0][0], LDB, kk + 8 * g, (wn * TN + j) * 32);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
